@@ -1,0 +1,225 @@
+/*
+ * CPU oracle for the per-worker gradient-compression path of GraVAC
+ * (arxiv 2305.12201).  TEST INFRASTRUCTURE ONLY: this file is the plain, slow,
+ * single-threaded definition that the GPU library is checked against.  Only the
+ * tests, the smoke check and the bench's cpu_baseline leg may call it; the
+ * product path never does.  It shares no code with the HIP library.
+ *
+ * What it computes, with the passage each step follows:
+ *   1. error feedback   acc = residual + grad            (Sec. III-B, g_ef; Alg. 1 error-feedback line)
+ *   2. Top-k at factor CF: keep the k = ceil(n/CF) entries of largest |acc|,
+ *      everything else is dropped from the message       (Sec. II-C: CF definition, Top-k)
+ *   3. residual = acc - compressed                       (Alg. 1 "update residual")
+ *   4. compression gain ||g_c||^2 / ||g_ef||^2           (Sec. III-B, compression-gain equation;
+ *                                                         Alg. 1 gain lines) for every candidate CF
+ *   5. the same per tensor ("layerwise", Sec. III-A)     with global indices
+ *   6. decompression: rebuild to the dense dimension     (Sec. III-A, t_decompress) and sum the
+ *      workers' contributions
+ *
+ * The selection is the plain definition: a full sort of all entries by
+ * (|acc| descending, index ascending) and a cut after k entries.  No histogram,
+ * no threshold search, no blocking.
+ *
+ * Readings taken where the paper is silent (each also listed in the design notes):
+ *   - k = ceil(n / CF), clamped to [1, n]; integral CF uses exact integer arithmetic.
+ *   - magnitude order is the order of the IEEE-754 bit pattern with the sign bit
+ *     cleared, so +0 and -0 tie, and NaN patterns rank above infinity.
+ *   - ties in magnitude go to the lower index.
+ *   - the message lists pairs in ascending index order; values keep their sign bits.
+ *   - a selected slot's residual is +0.0f (x - x under round-to-nearest).
+ *   - the gain is the ratio of squared L2 norms (no mean subtracted), accumulated
+ *     in double; if ||acc||^2 == 0 the gain is 1.
+ *   - one CF of the list (position `commit`) is the one whose selection is emitted
+ *     and removed from the residual; every CF gets its statistics.
+ *   - the add of step 1 is one binary32 round-to-nearest-even add (gradients and
+ *     residuals are single-precision tensors, Sec. IV-B), no flush to zero.
+ *
+ * Build: gcc -O2 -ffp-contract=off -fPIC -shared (no -ffast-math).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_OK 0
+#define ORACLE_BAD_ARG (-1)
+#define ORACLE_CAPACITY (-2)
+#define ORACLE_NOMEM (-3)
+
+/* k = ceil(n / cf) clamped to [1, n]  (Sec. II-C: 10 % kept <-> CF 10x, 1 % <-> 100x). */
+int64_t oracle_k(int64_t n, double cf)
+{
+    int64_t k;
+    if (n <= 0 || !(cf >= 1.0) || isinf(cf)) return -1;
+    if (cf == floor(cf) && cf < 9.0e18) {
+        int64_t c = (int64_t)cf;
+        k = n / c + (n % c != 0);
+    } else {
+        k = (int64_t)ceil((double)n / cf);
+    }
+    if (k < 1) k = 1;
+    if (k > n) k = n;
+    return k;
+}
+
+static uint32_t f32_bits(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    return u;
+}
+
+/* One entry of the full sort: magnitude bit pattern and position. */
+typedef struct {
+    uint32_t mag;
+    uint32_t pos;
+} entry_t;
+
+/* larger magnitude first; equal magnitudes: lower position first */
+static int cmp_entry(const void* a, const void* b)
+{
+    const entry_t* x = (const entry_t*)a;
+    const entry_t* y = (const entry_t*)b;
+    if (x->mag != y->mag) return x->mag > y->mag ? -1 : 1;
+    if (x->pos != y->pos) return x->pos < y->pos ? -1 : 1;
+    return 0;
+}
+
+static int cmp_u32(const void* a, const void* b)
+{
+    uint32_t x = *(const uint32_t*)a, y = *(const uint32_t*)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * One tensor (a flat gradient, or one segment of it).  `base` is the offset of
+ * this tensor in the flat buffer: emitted indices are base + local position.
+ * acc is written into residual first (step 1), then selected slots are zeroed.
+ */
+static int compress_one(const float* grad, float* residual, int64_t base, int64_t n,
+                        const double* cf_list, int n_cf, int commit,
+                        int32_t* out_idx, float* out_val, int64_t* n_out, double* stats)
+{
+    entry_t* order = (entry_t*)malloc((size_t)n * sizeof(entry_t));
+    if (!order) return ORACLE_NOMEM;
+
+    /* step 1: acc = residual + grad, one binary32 add per element */
+    double ss_dense = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float a = residual[base + i] + grad[base + i];
+        residual[base + i] = a;
+        ss_dense += (double)a * (double)a;
+        order[i].mag = f32_bits(a) & 0x7FFFFFFFu;
+        order[i].pos = (uint32_t)i;
+    }
+
+    /* step 2: the full sort that defines "largest by magnitude" */
+    qsort(order, (size_t)n, sizeof(entry_t), cmp_entry);
+
+    /* step 4: statistics for every candidate CF from its prefix of the order */
+    for (int j = 0; j < n_cf; ++j) {
+        int64_t k = oracle_k(n, cf_list[j]);
+        double ss_sel = 0.0;
+        for (int64_t r = 0; r < k; ++r) {
+            double v = (double)residual[base + order[r].pos];
+            ss_sel += v * v;
+        }
+        float last = residual[base + order[k - 1].pos];
+        stats[4 * j + 0] = ss_sel;
+        stats[4 * j + 1] = ss_dense;
+        stats[4 * j + 2] = (ss_dense == 0.0) ? 1.0 : ss_sel / ss_dense;
+        stats[4 * j + 3] = fabs((double)last);
+    }
+
+    /* steps 2-3 for the committed CF: message in ascending index order, residual update */
+    int64_t kc = oracle_k(n, cf_list[commit]);
+    uint32_t* chosen = (uint32_t*)malloc((size_t)kc * sizeof(uint32_t));
+    if (!chosen) {
+        free(order);
+        return ORACLE_NOMEM;
+    }
+    for (int64_t r = 0; r < kc; ++r) chosen[r] = order[r].pos;
+    qsort(chosen, (size_t)kc, sizeof(uint32_t), cmp_u32);
+    for (int64_t r = 0; r < kc; ++r) {
+        int64_t g = base + (int64_t)chosen[r];
+        out_idx[r] = (int32_t)g;
+        out_val[r] = residual[g]; /* still acc here */
+    }
+    for (int64_t r = 0; r < kc; ++r) residual[base + (int64_t)chosen[r]] = 0.0f;
+    *n_out = kc;
+
+    free(chosen);
+    free(order);
+    return ORACLE_OK;
+}
+
+/*
+ * Host pointers throughout.  residual is updated in place.  seg_offsets == NULL
+ * (n_seg 0) means one flat tensor; otherwise n_seg + 1 offsets, strictly
+ * increasing from 0 to n, and each segment is compressed on its own with
+ * k_t = ceil(n_t / CF) (layerwise compression, Sec. III-A); the message is
+ * segment-major.  out_stats is [max(n_seg,1)][n_cf][4] doubles:
+ * { ||g_c||^2, ||g_ef||^2, gain, |acc| of the smallest selected entry }.
+ */
+int oracle_compress(const float* grad, float* residual, int64_t n,
+                    const double* cf_list, int n_cf, int commit,
+                    const int64_t* seg_offsets, int n_seg,
+                    int32_t* out_idx, float* out_val, int64_t out_capacity,
+                    int64_t* out_count, double* out_stats)
+{
+    if (!grad || !residual || !cf_list || !out_idx || !out_val || !out_stats) return ORACLE_BAD_ARG;
+    if (n <= 0 || n > 2147483647LL || n_cf < 1 || commit < 0 || commit >= n_cf) return ORACLE_BAD_ARG;
+    for (int j = 0; j < n_cf; ++j)
+        if (!(cf_list[j] >= 1.0) || isinf(cf_list[j])) return ORACLE_BAD_ARG;
+
+    int64_t flat[2] = {0, n};
+    const int64_t* off = seg_offsets;
+    int ns = n_seg;
+    if (!off || ns <= 0) {
+        off = flat;
+        ns = 1;
+    }
+    if (off[0] != 0 || off[ns] != n) return ORACLE_BAD_ARG;
+    int64_t total = 0;
+    for (int t = 0; t < ns; ++t) {
+        if (off[t + 1] <= off[t]) return ORACLE_BAD_ARG;
+        total += oracle_k(off[t + 1] - off[t], cf_list[commit]);
+    }
+    if (total > out_capacity) return ORACLE_CAPACITY;
+
+    int64_t written = 0;
+    for (int t = 0; t < ns; ++t) {
+        int64_t got = 0;
+        int rc = compress_one(grad, residual, off[t], off[t + 1] - off[t], cf_list, n_cf, commit,
+                              out_idx + written, out_val + written, &got,
+                              out_stats + (size_t)t * (size_t)n_cf * 4);
+        if (rc != ORACLE_OK) return rc;
+        written += got;
+    }
+    if (out_count) *out_count = written;
+    return ORACLE_OK;
+}
+
+/*
+ * Decompression (Sec. III-A: rebuild the compressed gradient to the original
+ * dimension) with aggregation of W workers' messages: worker w's pairs start at
+ * sum(counts[0..w)); contributions are added into dense_out in worker order,
+ * pairs in stored order, each add one binary32 add.  dense_out is not cleared.
+ */
+int oracle_decompress_accumulate(const int32_t* idx, const float* val,
+                                 const int64_t* counts, int W, int64_t n, float* dense_out)
+{
+    if (!counts || !dense_out || W < 1 || n <= 0) return ORACLE_BAD_ARG;
+    int64_t at = 0;
+    for (int w = 0; w < W; ++w) {
+        if (counts[w] < 0) return ORACLE_BAD_ARG;
+        for (int64_t r = 0; r < counts[w]; ++r) {
+            int64_t i = idx[at + r];
+            if (i < 0 || i >= n) return ORACLE_BAD_ARG;
+            volatile float s = dense_out[i] + val[at + r];
+            dense_out[i] = s;
+        }
+        at += counts[w];
+    }
+    return ORACLE_OK;
+}

@@ -1,0 +1,108 @@
+"""ctypes front end of the CPU oracle (``gravac_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY.  The oracle is the plain single-threaded definition of
+the GraVAC compression path (Sec. II-C Top-k, Sec. III-B error feedback and
+compression gain, Alg. 1 residual update, Sec. III-A layerwise mode and
+decompression).  Only the tests, the smoke check and the bench's ``cpu_baseline``
+leg may import this module; the product package never does, and this module
+imports nothing from the product package.
+
+All arrays are host numpy arrays.  ``build()`` compiles the C file with gcc.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gravac_oracle.c")
+_LIB = os.path.join(_HERE, "libgravac_oracle.so")
+
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle (gcc, no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c99", "-fPIC", "-shared",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            build()
+        lib = ctypes.CDLL(_LIB)
+        i64, dbl, i32 = ctypes.c_int64, ctypes.c_double, ctypes.c_int
+        p = ctypes.c_void_p
+        lib.oracle_k.restype = i64
+        lib.oracle_k.argtypes = [i64, dbl]
+        lib.oracle_compress.restype = i32
+        lib.oracle_compress.argtypes = [p, p, i64, p, i32, i32, p, i32, p, p, i64, p, p]
+        lib.oracle_decompress_accumulate.restype = i32
+        lib.oracle_decompress_accumulate.argtypes = [p, p, p, i32, i64, p]
+        _lib = lib
+    return _lib
+
+
+def topk_count(n: int, cf: float) -> int:
+    """k = ceil(n / CF) clamped to [1, n] (Sec. II-C)."""
+    return int(_load().oracle_k(int(n), float(cf)))
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def compress(grad: np.ndarray, residual: np.ndarray, cf_list, commit: int = 0, seg_offsets=None):
+    """Run the oracle on host arrays.
+
+    ``residual`` (float32, C-contiguous) is updated IN PLACE.  Returns
+    ``(idx int32[k], val float32[k], stats float64[n_seg][n_cf][4])`` where a
+    stats row is ``(||g_c||^2, ||g_ef||^2, gain, |acc| of the smallest selected)``.
+    """
+    lib = _load()
+    assert grad.dtype == np.float32 and residual.dtype == np.float32
+    assert grad.flags.c_contiguous and residual.flags.c_contiguous
+    n = grad.size
+    assert residual.size == n
+    cfs = np.ascontiguousarray(np.asarray(cf_list, dtype=np.float64))
+    n_cf = cfs.size
+    if seg_offsets is None:
+        off = None
+        n_seg = 0
+        rows = 1
+        cap = topk_count(n, cfs[commit])
+    else:
+        off = np.ascontiguousarray(np.asarray(seg_offsets, dtype=np.int64))
+        n_seg = off.size - 1
+        rows = n_seg
+        cap = sum(topk_count(int(off[t + 1] - off[t]), cfs[commit]) for t in range(n_seg))
+    idx = np.empty(cap, dtype=np.int32)
+    val = np.empty(cap, dtype=np.float32)
+    stats = np.zeros((rows, n_cf, 4), dtype=np.float64)
+    count = ctypes.c_int64(0)
+    rc = lib.oracle_compress(_ptr(grad), _ptr(residual), n, _ptr(cfs), n_cf, int(commit),
+                             _ptr(off) if off is not None else None, n_seg,
+                             _ptr(idx), _ptr(val), cap, ctypes.byref(count), _ptr(stats))
+    if rc != 0:
+        raise RuntimeError(f"oracle_compress failed with code {rc}")
+    assert count.value == cap
+    return idx, val, stats
+
+
+def decompress_accumulate(idx: np.ndarray, val: np.ndarray, counts, dense_out: np.ndarray) -> None:
+    """dense_out[idx] += val, workers in order (Sec. III-A decompression), in place."""
+    lib = _load()
+    assert idx.dtype == np.int32 and val.dtype == np.float32 and dense_out.dtype == np.float32
+    cnt = np.ascontiguousarray(np.asarray(counts, dtype=np.int64))
+    rc = lib.oracle_decompress_accumulate(_ptr(np.ascontiguousarray(idx)), _ptr(np.ascontiguousarray(val)),
+                                          _ptr(cnt), cnt.size, dense_out.size, _ptr(dense_out))
+    if rc != 0:
+        raise RuntimeError(f"oracle_decompress_accumulate failed with code {rc}")

@@ -1,0 +1,135 @@
+/*
+ * gravac.h - C ABI of the MI355X (gfx950) gradient-compression library.
+ *
+ * The library implements the per-worker compression path that GraVAC
+ * (arxiv 2305.12201) runs on every training iteration:
+ *
+ *   error feedback      acc = residual + grad                   Sec. III-B (g_ef), Alg. 1 error-feedback step
+ *   Top-k at factor CF  keep the k = ceil(n/CF) largest |acc|,  Sec. II-C (CF definition, Top-k: values
+ *                       send (index, value) pairs                 and indices are sent, the rest is zero)
+ *   residual update     residual = acc - compressed             Alg. 1 residual-update step, Sec. III-B
+ *   compression gain    ||g_c||^2 / ||g_ef||^2 for one or       Sec. III-B compression-gain equation,
+ *                       several candidate CFs on the same acc     Alg. 1 gain steps (theta_min and theta_s*theta_min)
+ *   layerwise mode      the same, independently per tensor      Sec. III-A (layerwise compression)
+ *   decompression       rebuild to the dense dimension and      Sec. III-A (t_decompress), Alg. 1 Aggregate
+ *                       sum W workers' messages
+ *
+ * Conventions
+ *   - "device pointer": memory of the current HIP device (any allocator).  "host pointer":
+ *     ordinary host memory, read before the call returns.
+ *   - Every call is asynchronous on `stream` (a hipStream_t passed as void*; NULL = the null
+ *     stream).  Outputs are valid once the stream has been synchronised.
+ *   - The library never allocates device memory: scratch space comes from the caller's
+ *     `workspace`.  Calls that overlap in time must use different workspaces.
+ *   - Return value: GRAVAC_OK (0) or a negative GRAVAC_ERR_* code.  On an error return no
+ *     kernel has been launched and no buffer has been touched.
+ */
+#ifndef GRAVAC_H
+#define GRAVAC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GRAVAC_OK 0
+#define GRAVAC_ERR_INVALID_ARG (-1) /* null pointer, size or CF out of range, bad segment table, misaligned buffer */
+#define GRAVAC_ERR_CAPACITY (-2)    /* out_capacity smaller than the number of pairs the call will emit */
+#define GRAVAC_ERR_WORKSPACE (-3)   /* workspace missing or smaller than gravac_workspace_bytes() */
+#define GRAVAC_ERR_HIP (-4)         /* a HIP runtime call failed (launch, copy) */
+
+#define GRAVAC_MAX_CF 8             /* candidate CFs per call */
+#define GRAVAC_STATS_PER_CF 4       /* doubles per (segment, CF) in out_stats */
+
+/* flags of gravac_compress (testing and measurement aids; 0 in production) */
+#define GRAVAC_FLAG_FORCE_FALLBACK 1u /* skip the sampled threshold estimate: every segment takes the exact
+                                         histogram route (same results, more passes over memory) */
+#define GRAVAC_FLAG_PROFILE 2u        /* record HIP events around the streaming kernel, see gravac_profile_read */
+
+/*
+ * Number of pairs a call will emit for a tensor of n elements at compression factor cf:
+ * k = ceil(n / cf) clamped to [1, n]  (Sec. II-C: keeping 10 % is CF 10x, 1 % is CF 100x).
+ * Integral cf uses exact integer arithmetic.  Returns -1 for n <= 0 or cf < 1 or non-finite cf.
+ */
+int64_t gravac_topk_count(int64_t n, double cf);
+
+/*
+ * Workspace size in bytes for a gravac_compress call on n elements with n_cf candidate CFs
+ * and n_seg segments (0 or 1 = one flat tensor).  The size depends only on these three
+ * numbers (it covers any segment table with n_seg entries).  Roughly 8 bytes per element.
+ */
+int gravac_workspace_bytes(int64_t n, int n_cf, int n_seg, size_t* bytes_out);
+
+/*
+ * One compression step of Alg. 1 for one worker.
+ *
+ *   grad        device, float[n], read only.  16-byte aligned.
+ *   residual    device, float[n], 16-byte aligned.  In: the leftover of earlier iterations.
+ *               Out: acc with the committed selection's slots set to +0.0f.
+ *   n           1 <= n <= 2^31 - 1 (indices are int32).
+ *   cf_list     host, double[n_cf], every entry finite and >= 1.  1 <= n_cf <= GRAVAC_MAX_CF.
+ *   commit      position in cf_list of the CF whose selection is emitted into out_idx/out_val
+ *               and removed from the residual.  Every CF of the list gets its statistics.
+ *   seg_offsets host, int64[n_seg + 1], strictly increasing from 0 to n: tensor boundaries for
+ *               layerwise mode (independent Top-k per tensor with k_t = ceil(n_t / CF)).
+ *               NULL with n_seg == 0 means one flat tensor.
+ *   out_idx     device, int32[out_capacity]; out_val device, float[out_capacity].
+ *               The message: pairs (global index, acc value) in ascending index order
+ *               (segment-major in layerwise mode).  Ties in |acc| go to the lower index.
+ *   out_capacity  must be >= sum over segments of gravac_topk_count(n_t, cf_list[commit]).
+ *   out_count   device, int64 scalar or NULL: number of pairs written.
+ *   out_stats   device, double[max(n_seg,1)][n_cf][4]:
+ *               { ||g_c||^2, ||g_ef||^2, gain = ratio (1 if ||g_ef||^2 == 0),
+ *                 |acc| of the smallest selected entry }.
+ *   workspace   device, 256-byte aligned, at least gravac_workspace_bytes(n, n_cf, n_seg) bytes.
+ *               Contents on entry are irrelevant; contents on exit are unspecified.
+ *   flags       0, or GRAVAC_FLAG_* bits.
+ */
+int gravac_compress(const float* grad, float* residual, int64_t n,
+                    const double* cf_list, int n_cf, int commit,
+                    const int64_t* seg_offsets, int n_seg,
+                    int32_t* out_idx, float* out_val, int64_t out_capacity,
+                    int64_t* out_count, double* out_stats,
+                    void* workspace, size_t workspace_bytes,
+                    unsigned flags, void* stream);
+
+/*
+ * Decompression with aggregation (Sec. III-A t_decompress; what a worker does with the
+ * messages it received): dense_out[idx] += val for workers w = 0 .. W-1 in that order.
+ *
+ *   idx, val    device, the W messages back to back; worker w's pairs start at
+ *               counts[0] + ... + counts[w-1].  Within one worker the indices must be
+ *               strictly ascending (as gravac_compress emits them).  Indices outside
+ *               [0, n) are ignored.
+ *   counts      host, int64[W], pairs per worker (>= 0).  W >= 1.
+ *   dense_out   device, float[n]; it is added to, not cleared.
+ * Adds are binary32, one per pair, in worker order, so the result does not depend on
+ * scheduling.  Needs no workspace.
+ */
+int gravac_decompress_accumulate(const int32_t* idx, const float* val,
+                                 const int64_t* counts, int W,
+                                 int64_t n, float* dense_out, void* stream);
+
+/*
+ * Diagnostics of the last gravac_compress call that used `workspace`: synchronises `stream`
+ * and copies 8 int32 to the host pointer out8:
+ *   [0] 1 if any segment took the exact-histogram fallback, [1] number of such segments,
+ *   [2] internal-error flag (must be 0), [3] number of segments, [4..7] reserved.
+ */
+int gravac_read_status(const void* workspace, void* stream, int32_t* out8);
+
+/*
+ * With GRAVAC_FLAG_PROFILE: synchronises and returns the duration in milliseconds of the
+ * streaming kernel (error feedback + candidate collection) of the most recent profiled call
+ * of this process, and of the whole call (first to last kernel) in total_ms.  Either pointer may be NULL.
+ */
+int gravac_profile_read(float* stream_kernel_ms, float* total_ms);
+
+const char* gravac_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRAVAC_H */

@@ -1,0 +1,177 @@
+"""Thin Python binding of the C ABI in ``include/gravac.h``.
+
+Argument marshalling only: every step of the compression path runs in the HIP
+kernels of ``libgravac.so``.  PyTorch supplies device memory and the stream.
+There is no CPU fallback: if the library cannot be loaded the import of the
+first entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+from . import _build
+
+OK = 0
+ERR_INVALID_ARG = -1
+ERR_CAPACITY = -2
+ERR_WORKSPACE = -3
+ERR_HIP = -4
+MAX_CF = 8
+FLAG_FORCE_FALLBACK = 1
+FLAG_PROFILE = 2
+
+EXPORTS = (
+    "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_decompress_accumulate",
+    "gravac_read_status", "gravac_profile_read", "gravac_strerror",
+)
+
+_lib = None
+
+
+class GravacError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+
+
+def library_path() -> str:
+    return _build.LIBRARY
+
+
+def lib() -> ctypes.CDLL:
+    """Load ``libgravac.so`` (building it first only if no built library exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIBRARY):
+            _build.build_library()
+        L = ctypes.CDLL(_build.LIBRARY)
+        vp, i64, i32, u32, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint, ctypes.c_double
+        L.gravac_topk_count.restype = i64
+        L.gravac_topk_count.argtypes = [i64, dbl]
+        L.gravac_workspace_bytes.restype = i32
+        L.gravac_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
+        L.gravac_compress.restype = i32
+        L.gravac_compress.argtypes = [vp, vp, i64, vp, i32, i32, vp, i32, vp, vp, i64, vp, vp, vp,
+                                      ctypes.c_size_t, u32, vp]
+        L.gravac_decompress_accumulate.restype = i32
+        L.gravac_decompress_accumulate.argtypes = [vp, vp, vp, i32, i64, vp, vp]
+        L.gravac_read_status.restype = i32
+        L.gravac_read_status.argtypes = [vp, vp, vp]
+        L.gravac_profile_read.restype = i32
+        L.gravac_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
+        L.gravac_strerror.restype = ctypes.c_char_p
+        L.gravac_strerror.argtypes = [i32]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().gravac_strerror(int(code)).decode()
+
+
+def gravac_topk_count(n: int, cf: float) -> int:
+    return int(lib().gravac_topk_count(int(n), float(cf)))
+
+
+def gravac_workspace_bytes(n: int, n_cf: int, n_seg: int = 0) -> int:
+    out = ctypes.c_size_t(0)
+    rc = lib().gravac_workspace_bytes(int(n), int(n_cf), int(n_seg), ctypes.byref(out))
+    if rc != OK:
+        raise GravacError(rc, "gravac_workspace_bytes")
+    return int(out.value)
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dev_ptr(t, dtype) -> int:
+    if t is None:
+        return 0
+    assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), "expected a contiguous device tensor"
+    return t.data_ptr()
+
+
+def gravac_compress(grad, residual, cf_list, commit=0, seg_offsets=None, *, out_idx, out_val,
+                    out_count=None, out_stats, workspace, flags=0, stream=None) -> None:
+    """``gravac_compress`` of the C ABI on torch device tensors (asynchronous on ``stream``)."""
+    cfs = np.ascontiguousarray(np.asarray(cf_list, dtype=np.float64))
+    if seg_offsets is None:
+        seg_ptr, n_seg = None, 0
+    else:
+        seg = np.ascontiguousarray(np.asarray(seg_offsets, dtype=np.int64))
+        seg_ptr, n_seg = seg.ctypes.data_as(ctypes.c_void_p), seg.size - 1
+    rc = lib().gravac_compress(
+        _dev_ptr(grad, torch.float32), _dev_ptr(residual, torch.float32), grad.numel(),
+        cfs.ctypes.data_as(ctypes.c_void_p), cfs.size, int(commit), seg_ptr, n_seg,
+        _dev_ptr(out_idx, torch.int32), _dev_ptr(out_val, torch.float32), out_idx.numel(),
+        _dev_ptr(out_count, torch.int64), _dev_ptr(out_stats, torch.float64),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), int(flags), _stream_handle(stream))
+    if rc != OK:
+        raise GravacError(rc, "gravac_compress")
+
+
+def gravac_decompress_accumulate(idx, val, counts, dense_out, *, stream=None) -> None:
+    """``gravac_decompress_accumulate`` of the C ABI on torch device tensors."""
+    cnt = np.ascontiguousarray(np.asarray(counts, dtype=np.int64))
+    rc = lib().gravac_decompress_accumulate(
+        _dev_ptr(idx, torch.int32), _dev_ptr(val, torch.float32), cnt.ctypes.data_as(ctypes.c_void_p),
+        cnt.size, dense_out.numel(), _dev_ptr(dense_out, torch.float32), _stream_handle(stream))
+    if rc != OK:
+        raise GravacError(rc, "gravac_decompress_accumulate")
+
+
+def gravac_read_status(workspace, stream=None) -> dict:
+    out = (ctypes.c_int32 * 8)()
+    rc = lib().gravac_read_status(workspace.data_ptr(), _stream_handle(stream), out)
+    if rc != OK:
+        raise GravacError(rc, "gravac_read_status")
+    return {"any_fallback": int(out[0]), "fallback_segments": int(out[1]), "internal_error": int(out[2]),
+            "segments": int(out[3])}
+
+
+def gravac_profile_read() -> tuple[float, float]:
+    a, b = ctypes.c_float(0), ctypes.c_float(0)
+    rc = lib().gravac_profile_read(ctypes.byref(a), ctypes.byref(b))
+    if rc != OK:
+        raise GravacError(rc, "gravac_profile_read")
+    return float(a.value), float(b.value)
+
+
+# --------------------------------------------------------------------------
+# convenience: allocate outputs and workspace with torch, call, return tensors
+# --------------------------------------------------------------------------
+
+class Compressor:
+    """Owns the workspace and output buffers for repeated calls on one gradient shape."""
+
+    def __init__(self, n: int, cf_list, commit: int = 0, seg_offsets=None, device="cuda"):
+        self.n = int(n)
+        self.cfs = [float(c) for c in cf_list]
+        self.commit = int(commit)
+        self.seg = None if seg_offsets is None else np.asarray(seg_offsets, dtype=np.int64)
+        n_seg = 0 if self.seg is None else self.seg.size - 1
+        sizes = [self.n] if self.seg is None else np.diff(self.seg).tolist()
+        self.k_total = sum(gravac_topk_count(int(s), self.cfs[self.commit]) for s in sizes)
+        self.rows = max(n_seg, 1)
+        self.workspace = torch.empty(gravac_workspace_bytes(self.n, len(self.cfs), n_seg), dtype=torch.uint8,
+                                     device=device)
+        self.out_idx = torch.empty(self.k_total, dtype=torch.int32, device=device)
+        self.out_val = torch.empty(self.k_total, dtype=torch.float32, device=device)
+        self.out_count = torch.zeros(1, dtype=torch.int64, device=device)
+        self.out_stats = torch.zeros(self.rows, len(self.cfs), 4, dtype=torch.float64, device=device)
+
+    def __call__(self, grad, residual, flags=0, stream=None):
+        gravac_compress(grad, residual, self.cfs, self.commit, self.seg, out_idx=self.out_idx,
+                        out_val=self.out_val, out_count=self.out_count, out_stats=self.out_stats,
+                        workspace=self.workspace, flags=flags, stream=stream)
+        return self.out_idx, self.out_val, self.out_stats
+
+    def status(self) -> dict:
+        return gravac_read_status(self.workspace)

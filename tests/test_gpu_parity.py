@@ -1,0 +1,295 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
+
+Bit-exact on indices, values and residuals; statistics within 1e-5 relative (fp64 sums in a
+different order); the threshold magnitude exactly.  Sizes are chosen so the full-sort oracle
+finishes in seconds while the GPU path still spans many wave tiles and a ragged tail.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2305_12201_amd import binding, workloads
+from tests.gpu_util import assert_same, check, gpu_compress, oracle_compress
+
+pytestmark = pytest.mark.gpu
+
+FB = binding.FLAG_FORCE_FALLBACK
+
+
+def test_library_is_loaded_from_the_tree():
+    import os
+    assert os.path.exists(binding.library_path())
+    assert binding.lib() is not None
+
+
+# --------------------------------------------------------------------------
+# configuration 1: N = 2^20, Normal(0, 1e-3), CF 100, two iterations carrying the residual
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("flags", [0, FB])
+def test_config1_two_iterations(flags):
+    n = 1 << 20
+    res_gpu = np.zeros(n, np.float32)
+    res_ref = np.zeros(n, np.float32)
+    for it in range(2):
+        g = workloads.config1(it)
+        gpu = gpu_compress(g, res_gpu, [100.0], flags=flags)
+        ref = oracle_compress(g, res_ref, [100.0])
+        assert gpu[0].size == 10486
+        assert_same(gpu, ref, f"config1 it{it}")
+        assert gpu[4]["internal_error"] == 0
+        assert bool(gpu[4]["any_fallback"]) == bool(flags)
+        res_gpu, res_ref = gpu[3], ref[3]
+
+
+# --------------------------------------------------------------------------
+# ragged sizes, tiny inputs, every CF regime
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 63, 64, 65, 255, 257, 1023, 4095, 4096, 4097, 8193, 100_003, 131_072,
+                               131_073, 300_001])
+def test_ragged_sizes(n):
+    g = workloads.normal_gradient(n, 1e-3, seed=n)
+    r = workloads.normal_gradient(n, 1e-4, seed=n + 1)
+    for cf in (1.0, 1.5, 10.0, 1000.0):
+        check(g, r, [cf], what=f"n={n} cf={cf}")
+    check(g, r, [3.0], flags=FB, what=f"n={n} forced", expect_fallback=True)
+
+
+def test_heavy_ties_and_signed_zeros():
+    rng = np.random.default_rng(7)
+    for n in (1000, 70_000, 500_000):
+        g = (rng.integers(-6, 7, n) * 0.125).astype(np.float32)
+        r = (rng.integers(-2, 3, n) * 0.125).astype(np.float32)
+        g[rng.random(n) < 0.1] = -0.0
+        for cf in (2.0, 7.0, 100.0):
+            check(g, r, [cf], what=f"ties n={n} cf={cf}")
+            check(g, r, [cf], flags=FB, what=f"ties forced n={n} cf={cf}")
+
+
+def test_all_zero_and_all_equal():
+    n = 50_000
+    z = np.zeros(n, np.float32)
+    gpu, ref = check(z, z, [10.0], what="all zero")
+    assert gpu[2][0, 0].tolist() == [0.0, 0.0, 1.0, 0.0]
+    one = np.full(n, -0.5, np.float32)
+    check(one, z, [100.0], what="all equal")
+    check(one, z, [100.0], flags=FB, what="all equal forced")
+
+
+def test_k_exceeds_nonzeros():
+    n = 200_000
+    g = np.zeros(n, np.float32)
+    rng = np.random.default_rng(3)
+    pos = rng.choice(n, 500, replace=False)
+    g[pos] = rng.standard_normal(500).astype(np.float32)
+    check(g, np.zeros(n, np.float32), [100.0], what="k=2000 > 500 nonzeros")
+
+
+def test_nan_inf_and_denormals():
+    n = 10_000
+    g = workloads.normal_gradient(n, 1e-3, seed=5)
+    g[17] = np.inf
+    g[99] = -np.inf
+    g[5000] = np.nan
+    g[6000:6100] = 1e-40
+    check(g, np.zeros(n, np.float32), [100.0], what="nan/inf")
+    d = np.full(n, 1e-40, np.float32)
+    d[::7] = -3e-41
+    gpu, ref = check(d, d.copy(), [10.0], what="denormals")
+    assert np.all(gpu[1] != 0)          # denormal sums are not flushed
+
+
+def test_extreme_dynamic_range_and_outliers():
+    n = 400_000
+    rng = np.random.default_rng(11)
+    g = (rng.standard_normal(n) * np.exp(rng.uniform(-30, 30, n))).astype(np.float32)
+    check(g, np.zeros(n, np.float32), [10.0, 100.0, 1000.0], commit=1, what="wide range")
+    # a sample cannot see a handful of huge entries: the bound is too low, never too high
+    g = workloads.normal_gradient(n, 1e-6, seed=2)
+    g[rng.choice(n, 37, replace=False)] = 5.0
+    check(g, np.zeros(n, np.float32), [1000.0, 10000.0], commit=0, what="rare outliers")
+
+
+def test_clustered_top_entries_hidden_from_the_sample():
+    # all large entries sit in one short run: a strided sample underestimates the tail and the
+    # library must notice (fewer candidates than k) and take the exact route
+    n = 1_000_000
+    g = workloads.normal_gradient(n, 1e-6, seed=9)
+    g[123_456:123_456 + 3000] = workloads.normal_gradient(3000, 1.0, seed=10)
+    gpu, ref = check(g, np.zeros(n, np.float32), [100.0], what="clustered")
+    assert gpu[4]["internal_error"] == 0
+
+
+# --------------------------------------------------------------------------
+# several CFs in one call, every commit position
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("flags", [0, FB])
+def test_multi_cf_every_commit(flags):
+    n = 700_001
+    g = workloads.resnet_like_gradient(n, seed=21)
+    r = workloads.normal_gradient(n, 1e-5, seed=22)
+    cfs = [10.0, 100.0, 1000.0]
+    for commit in range(3):
+        check(g, r, cfs, commit=commit, flags=flags, what=f"commit={commit}")
+    check(g, r, [1.5, 2.0, 3.0, 10.0, 50.0, 100.0, 1000.0, 5000.0], commit=5, flags=flags, what="8 CFs")
+
+
+# --------------------------------------------------------------------------
+# reduced twins of configurations 2-4, residual carried over iterations
+# --------------------------------------------------------------------------
+
+def test_config2_reduced_five_iterations():
+    n = 2_000_003
+    res_gpu = workloads.config2_residual0(n)
+    res_ref = res_gpu.copy()
+    comp = binding.Compressor(n, [10.0, 100.0, 1000.0], 1)
+    for it in range(5):
+        g = workloads.config2_grad(it, n)
+        gpu = gpu_compress(g, res_gpu, [10.0, 100.0, 1000.0], 1, comp=comp)
+        ref = oracle_compress(g, res_ref, [10.0, 100.0, 1000.0], 1)
+        assert_same(gpu, ref, f"config2 it{it}")
+        assert gpu[4] == {"any_fallback": 0, "fallback_segments": 0, "internal_error": 0, "segments": 1}
+        res_gpu, res_ref = gpu[3], ref[3]
+
+
+def test_config3_reduced_five_iterations():
+    n_conv, n_fc = 300_000, 2_500_007
+    n = n_conv + n_fc
+    res_gpu = np.zeros(n, np.float32)
+    res_ref = np.zeros(n, np.float32)
+    comp = binding.Compressor(n, [1000.0])
+    for it in range(5):
+        g = workloads.config3_grad(it, n_conv, n_fc)
+        gpu = gpu_compress(g, res_gpu, [1000.0], comp=comp)
+        ref = oracle_compress(g, res_ref, [1000.0])
+        assert_same(gpu, ref, f"config3 it{it}")
+        assert gpu[4]["internal_error"] == 0
+        res_gpu, res_ref = gpu[3], ref[3]
+
+
+def test_config4_reduced():
+    g = workloads.config4_grad(0, vocab=3000, hidden=130)   # 95 % of embedding rows exactly zero
+    z = np.zeros(g.size, np.float32)
+    for commit in (0, 1):
+        check(g, z, [100.0, 1000.0], commit=commit, what=f"config4 commit={commit}")
+
+
+# --------------------------------------------------------------------------
+# layerwise (segmented) mode
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("flags", [0, FB])
+def test_segmented_ragged(flags):
+    sizes = [64, 1, 4096, 37, 100_003, 2, 9408, 64, 64, 1000, 4097, 8191, 3, 250_001, 5]
+    off = workloads.offsets_of(sizes)
+    n = int(off[-1])
+    g = workloads.resnet_like_gradient(n, seed=61)
+    r = workloads.normal_gradient(n, 1e-5, seed=62)
+    check(g, r, [100.0], seg=off, flags=flags, what="segmented cf100")
+    check(g, r, [10.0, 100.0, 1000.0], commit=0, seg=off, flags=flags, what="segmented 3 CFs")
+
+
+def test_config5_reduced_resnet_tensor_list():
+    sizes = workloads.scaled_sizes(workloads.resnet101_tensor_sizes(), 16)
+    off = workloads.offsets_of(sizes)
+    n = int(off[-1])
+    assert len(sizes) == 314
+    g = workloads.config5_worker_grad(0, n)
+    gpu, ref = check(g, np.zeros(n, np.float32), [100.0], seg=off, what="config5 reduced")
+    assert gpu[2].shape == (314, 1, 4)
+    assert gpu[0].size == sum(-(-s // 100) for s in sizes)
+
+
+# --------------------------------------------------------------------------
+# determinism, workspace reuse, buffers left alone
+# --------------------------------------------------------------------------
+
+def test_repeat_runs_are_bit_identical_and_grad_is_untouched():
+    n = 1_500_000
+    g = workloads.resnet_like_gradient(n, seed=71)
+    r = workloads.normal_gradient(n, 1e-5, seed=72)
+    comp = binding.Compressor(n, [10.0, 100.0], 1)
+    gt = torch.from_numpy(g).cuda()
+    first = None
+    for rep in range(5):
+        rt = torch.from_numpy(r.copy()).cuda()
+        idx, val, stats = comp(gt, rt)
+        torch.cuda.synchronize()
+        out = (idx.cpu().numpy().copy(), val.cpu().numpy().copy(), stats.cpu().numpy().copy(), rt.cpu().numpy())
+        if first is None:
+            first = out
+        else:
+            for a, b in zip(first, out):
+                assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+    assert np.array_equal(gt.cpu().numpy(), g)
+
+
+# --------------------------------------------------------------------------
+# decompression
+# --------------------------------------------------------------------------
+
+def _decompress_case(n, ks, seed, offset_elems=0):
+    from oracle import oracle
+    rng = np.random.default_rng(seed)
+    idxs, vals = [], []
+    for k in ks:
+        idxs.append(np.sort(rng.choice(n, size=k, replace=False)).astype(np.int32))
+        vals.append(rng.standard_normal(k).astype(np.float32))
+    idx = np.concatenate(idxs) if ks else np.zeros(0, np.int32)
+    val = np.concatenate(vals) if ks else np.zeros(0, np.float32)
+    dense = rng.standard_normal(n).astype(np.float32)
+    want = dense.copy()
+    oracle.decompress_accumulate(idx, val, ks, want)
+    buf = torch.zeros(n + offset_elems, dtype=torch.float32, device="cuda")
+    d = buf[offset_elems:]
+    d.copy_(torch.from_numpy(dense))
+    binding.gravac_decompress_accumulate(torch.from_numpy(idx).cuda(), torch.from_numpy(val).cuda(), ks, d)
+    torch.cuda.synchronize()
+    got = d.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    if offset_elems:
+        assert float(buf[:offset_elems].abs().sum()) == 0.0
+
+
+def test_decompress_accumulate_small_and_ragged():
+    _decompress_case(1000, [100, 0, 250, 1000, 7], seed=1)
+    _decompress_case(8192, [8192], seed=2)
+    _decompress_case(8193, [1, 8193], seed=3)
+    _decompress_case(100_003, [5000] * 8, seed=4)
+    _decompress_case(100_003, [5000] * 8, seed=5, offset_elems=1)     # dense buffer not 16-byte aligned
+    _decompress_case(50_000, [100] * 70, seed=6)                       # more than 64 workers: two launches
+
+
+def test_decompress_sparse_and_dense_regimes():
+    _decompress_case(3_000_000, [3000] * 8, seed=7)                    # most tiles untouched
+    _decompress_case(1_000_000, [100_000] * 8, seed=8)                 # every tile touched by every worker
+
+
+def test_compress_then_decompress_eight_workers():
+    """Reduced twin of configuration 5: eight workers' layerwise messages summed into one dense buffer."""
+    from oracle import oracle
+    sizes = workloads.scaled_sizes(workloads.resnet101_tensor_sizes(), 32)
+    off = workloads.offsets_of(sizes)
+    n = int(off[-1])
+    comp = binding.Compressor(n, [100.0], 0, off)
+    k = comp.k_total
+    all_idx = torch.empty(8 * k, dtype=torch.int32, device="cuda")
+    all_val = torch.empty(8 * k, dtype=torch.float32, device="cuda")
+    ref_idx, ref_val = [], []
+    for w in range(8):
+        g = workloads.config5_worker_grad(w, n)
+        z = np.zeros(n, np.float32)
+        gpu = gpu_compress(g, z, [100.0], 0, off, comp=comp)
+        ref = oracle_compress(g, z, [100.0], 0, off)
+        assert_same(gpu, ref, f"worker {w}")
+        all_idx[w * k:(w + 1) * k] = comp.out_idx
+        all_val[w * k:(w + 1) * k] = comp.out_val
+        ref_idx.append(ref[0]), ref_val.append(ref[1])
+    dense = torch.zeros(n, dtype=torch.float32, device="cuda")
+    binding.gravac_decompress_accumulate(all_idx, all_val, [k] * 8, dense)
+    torch.cuda.synchronize()
+    want = np.zeros(n, np.float32)
+    oracle.decompress_accumulate(np.concatenate(ref_idx), np.concatenate(ref_val), [k] * 8, want)
+    assert np.array_equal(dense.cpu().numpy().view(np.uint32), want.view(np.uint32))

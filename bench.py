@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the GraVAC compression hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one gradient:
+  gravac_compress   error feedback + Top-k at CF 1000 + residual update + compression gain
+  gravac_decompress_accumulate   the worker's fresh message plus seven other workers' messages
+                                 (W = 8) scatter-added into one dense buffer
+Workload: the VGG16-shaped gradient (138,357,544 fp32 elements, conv part Normal(0,1e-3), fc part
+Normal(0,1e-5)), residual carried from step to step, all inputs resident in HBM before the timed
+region.  Prints ONE JSON line (see the keys below); everything else goes to stderr.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--small]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+ALGO_BYTES_PER_ELEMENT = 12.0  # read grad, read residual, write residual
+N_GRADS = 3                    # distinct gradients cycled through the steps
+N_WORKERS = 8
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(n_conv, n_fc):
+    """The oracle, as it stands, timed on a half-size twin of the workload (single thread)."""
+    from oracle import oracle
+    from paper_2305_12201_amd import workloads
+    g = workloads.config3_grad(0, n_conv // 2, n_fc // 2)
+    r = np.zeros(g.size, np.float32)
+    t0 = time.perf_counter()
+    oracle.compress(g, r, [1000.0])
+    dt = time.perf_counter() - t0
+    return {"value": 4.0 * g.size / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"one compress call (CF 1000) on a half-size VGG16-shaped gradient, {g.size} elements, "
+                      f"{dt:.1f} s on one host core of {os.cpu_count()}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--small", action="store_true", help="1/16-size workload (for a quick functional check)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build measures the one-GPU share of the path only (no collectives, no sharding); "
+            "run it with --gpus 1.")
+        sys.exit(2)
+
+    import torch
+    from paper_2305_12201_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    n_conv, n_fc = workloads.VGG16_N_CONV, workloads.VGG16_N_FC
+    if args.small:
+        n_conv, n_fc = n_conv // 16, n_fc // 16
+    n = n_conv + n_fc
+    cf = 1000.0
+    k = binding.gravac_topk_count(n, cf)
+
+    log(f"generating {N_GRADS} gradients of {n} elements and {N_WORKERS - 1} peer messages ...")
+    comp = binding.Compressor(n, [cf], 0)
+    # messages of all workers back to back; slot 0 is rewritten by every step
+    msg_idx = torch.empty(N_WORKERS * k, dtype=torch.int32, device=dev)
+    msg_val = torch.empty(N_WORKERS * k, dtype=torch.float32, device=dev)
+    out_count = torch.zeros(1, dtype=torch.int64, device=dev)
+    out_stats = torch.zeros(1, 1, 4, dtype=torch.float64, device=dev)
+    residual = torch.zeros(n, dtype=torch.float32, device=dev)
+    dense = torch.zeros(n, dtype=torch.float32, device=dev)
+
+    def compress(grad, res, slot, flags=0):
+        binding.gravac_compress(grad, res, [cf], 0, None, out_idx=msg_idx[slot * k:(slot + 1) * k],
+                                out_val=msg_val[slot * k:(slot + 1) * k], out_count=out_count,
+                                out_stats=out_stats, workspace=comp.workspace, flags=flags)
+
+    for w in range(1, N_WORKERS):                       # peers: their own gradients, residual zero
+        g = torch.from_numpy(workloads.config3_grad(100 + w, n_conv, n_fc)).to(dev)
+        scratch = torch.zeros(n, dtype=torch.float32, device=dev)
+        compress(g, scratch, w)
+        torch.cuda.synchronize()
+        del g, scratch
+    grads = [torch.from_numpy(workloads.config3_grad(i, n_conv, n_fc)).to(dev) for i in range(N_GRADS)]
+    counts = [k] * N_WORKERS
+
+    def step(i, flags=0):
+        compress(grads[i % N_GRADS], residual, 0, flags)
+        binding.gravac_decompress_accumulate(msg_idx, msg_val, counts, dense)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    status = binding.gravac_read_status(comp.workspace)
+    assert status["internal_error"] == 0, status
+
+    # ---- the timed region: exactly K steps
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    status = binding.gravac_read_status(comp.workspace)
+
+    # ---- per-kernel timing with HIP events on the launch stream (same steps, events around the
+    #      streaming kernel and around the whole compress call)
+    k_ms, c_ms = [], []
+    for i in range(min(args.steps, 50)):
+        step(args.warmup + args.steps + i, binding.FLAG_PROFILE)
+        a, b = binding.gravac_profile_read()
+        k_ms.append(a)
+        c_ms.append(b)
+    stream_ms = float(np.mean(k_ms))
+    compress_ms = float(np.mean(c_ms))
+    gain = float(out_stats.cpu()[0, 0, 2])
+
+    achieved = ALGO_BYTES_PER_ELEMENT * n / (stream_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "stream_kernel_vgg16_traffic.json")
+    if os.path.exists(tpath) and not args.small:
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "dense-gradient GB/s through Top-k+EF compress at CF=100/1000; % of HBM peak",
+        "value": 4.0 * n / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "VGG16-shaped flat gradient, 138,357,544 fp32 elements, CF 1000 (k=138,358), "
+                               "residual carried; step = compress + decompress_accumulate of W=8 messages",
+                   "n": n, "cf": cf, "k": k, "workers_decompressed": N_WORKERS},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "stream_kernel<true> (error feedback + candidate collection)",
+                     "kernel_ms": stream_ms, "algorithmic_bytes_per_launch": ALGO_BYTES_PER_ELEMENT * n},
+        "compress_only": {"ms": compress_ms, "dense_gradient_GBps": 4.0 * n / (compress_ms * 1e-3) / 1e9,
+                          "elements_per_s": n / (compress_ms * 1e-3),
+                          "algorithmic_frac_of_hbm_peak": (ALGO_BYTES_PER_ELEMENT * n + 8.0 * k)
+                          / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "decompress_ms": ms_per_step - compress_ms,
+        "compression_gain": gain,
+        "fallback_taken": bool(status["any_fallback"]),
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a half-size twin ...")
+        out["cpu_baseline"] = cpu_baseline(n_conv, n_fc)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -12,15 +12,19 @@
 // diverts every element with key >= lo (a few k of them) into an index-ordered per-tile
 // candidate list, histogramming those candidates by (key - lo) >> s.  Everything after that
 // works on the candidate lists only: locate the histogram bin that holds the k-th largest,
-// resolve it to the exact key, count per tile, scan, emit the message in ascending index order
-// and zero the selected residual slots.  If the sampled bound turns out wrong (fewer than k
-// candidates, or a bin too coarse to resolve) the segment is redone by an exact route: a full
+// resolve it to the exact key, count per tile, and emit the message in ascending index order
+// while zeroing the selected residual slots.  If the sampled bound turns out wrong (fewer than
+// k candidates, or a bin too coarse to resolve) the segment is redone by an exact route: a full
 // 2048-bin histogram of the top key bits gives a bound that cannot fail.  Results are identical
 // on both routes; only the number of passes over memory differs.
 //
-// Unit of work: a "wave tile" of TW consecutive elements handled by one 64-lane wavefront, which
-// owns the slots [tile*TW, (tile+1)*TW) of the candidate arrays, so ordered compaction needs no
-// communication between wavefronts and no tile can overflow.
+// Units of work.  A "wave tile" is TW consecutive elements handled by one 64-lane wavefront,
+// which owns the slots [tile*TW, (tile+1)*TW) of the candidate arrays, so ordered compaction
+// needs no communication between wavefronts and no tile can overflow.  No kernel waits on another
+// workgroup: cross-tile results (histograms, output offsets) are combined at kernel boundaries.
+// Global atomics complete at a rate of roughly one per cache line per 10 ns on this part, so the
+// candidate histogram and the gather lists exist in REP copies (picked by blockIdx, which the
+// dispatcher deals round-robin over the eight XCDs) and nothing else uses global atomics.
 
 #include <hip/hip_runtime.h>
 
@@ -38,6 +42,7 @@ constexpr int TW = 4096;            // elements per wave tile
 constexpr int WG = 256;             // threads per workgroup of the tile kernels
 constexpr int WAVES = WG / 64;
 constexpr int ROW = 256;            // elements one wavefront touches per load (64 lanes x float4)
+constexpr int REP = 8;              // copies of the candidate histogram and of the gather lists
 constexpr int NBIN = 2048;          // bins of the candidate / refine / coarse histograms
 constexpr uint32_t OVF = NBIN - 1;  // last bin of the candidate histogram: everything above the bracket
 constexpr int SBIN = 4096;          // bins of the sample histogram (key >> 19)
@@ -46,6 +51,7 @@ constexpr int SAMPLE_MAX = 65536;   // samples per segment at most (unless the s
 constexpr int LCAP = 4096;          // keys a gather list can hold
 constexpr int MAXCF = GRAVAC_MAX_CF;
 constexpr double ZMARGIN = 5.0;     // safety margin of the sampled rank, in standard deviations
+constexpr uint32_t NONE = 0xFFFFFFFFu;
 
 enum : uint32_t { MODE_RESOLVED = 0, MODE_GATHER = 1, MODE_HIST = 2, MODE_FAIL = 3 };
 
@@ -62,8 +68,7 @@ struct CfState {
     uint32_t tau;       // key of the k-th largest (valid once resolved)
     uint32_t need;      // how many keys equal to tau are selected (lowest indices first)
     uint32_t cnt_gt;    // number of keys greater than tau
-    uint32_t list_cnt;  // fill count of the gather list
-    uint32_t pad[4];
+    uint32_t pad[5];
 };
 static_assert(sizeof(CfState) == 64, "CfState layout");
 
@@ -94,29 +99,30 @@ struct Params {
     uint32_t n_tiles;
     uint32_t n_sample_blocks;
     // layerwise tables in the workspace (unused when n_seg == 1)
-    const int64_t* seg_off;       // [n_seg + 1]
-    const int64_t* koff;          // [n_seg + 1] output offset of each segment's message
-    const uint32_t* tile_prefix;  // [n_seg + 1] first tile of each segment
-    const uint32_t* samp_prefix;  // [n_seg + 1] first sample block of each segment
-    const uint32_t* samp_cnt;     // [n_seg] samples of each segment
-    const uint32_t* ktab;         // [n_seg][n_cf]
+    const int64_t* seg_off;        // [n_seg + 1]
+    const int64_t* koff;           // [n_seg + 1] output offset of each segment's message
+    const uint32_t* tile_prefix;   // [n_seg + 1] first tile of each segment
+    const uint32_t* samp_prefix;   // [n_seg + 1] first sample block of each segment
+    const uint32_t* samp_cnt;      // [n_seg] samples of each segment
+    const uint32_t* ktab;          // [n_seg][n_cf]
     // the same for one flat tensor
     uint32_t flat_k[MAXCF];
     uint32_t flat_samples;
     // workspace
     Status* status;
-    CfState* st;     // [n_seg][n_cf]
-    SegState* seg;   // [n_seg]
-    uint32_t* hist1;     // [n_seg][n_cf][NBIN] candidate histogram
+    CfState* st;         // [n_seg][n_cf]
+    SegState* seg;       // [n_seg]
+    uint32_t* hist1;     // [n_seg][n_cf][REP][NBIN] candidate histogram, REP copies
     uint32_t* hist2;     // [n_seg][n_cf][NBIN] refine histogram
     uint32_t* coarse;    // [n_seg][NBIN] histogram of key >> 20 (exact route)
-    uint32_t* list;      // [n_seg][n_cf][LCAP] gather lists
-    uint32_t* samp_key;  // [n_sample_blocks][SAMPLE_BLOCK]
+    uint32_t* list;      // [n_seg][n_cf][REP][LCAP] gather lists, REP copies
+    uint32_t* list_cnt;  // [n_seg][n_cf][REP][32] fill counts of the gather lists, one cache line each
+    uint32_t* samp_hist; // [n_sample_blocks][SBIN / 2] sample histograms, two 16-bit counts per word
     uint32_t* cand_cnt;  // [n_tiles]
-    uint32_t* tg;        // [n_tiles] candidates with key > tau(commit)
-    uint32_t* te;        // [n_tiles] candidates with key == tau(commit)
+    uint32_t* tg;        // [n_tiles] candidates above tau(commit) in this tile
+    uint32_t* te;        // [n_tiles] candidates equal to tau(commit) in this tile
     uint32_t* toff;      // [n_tiles] offset of the tile's output inside its segment's message
-    uint32_t* ttake;     // [n_tiles] how many of the tile's ties are selected
+    uint32_t* ttake;     // [n_tiles] how many of the tile's candidates equal to tau(commit) are selected
     double* ssd;         // [n_tiles] sum of acc^2
     double* sss;         // [n_tiles][n_cf] sum of acc^2 over keys > tau_j
     int32_t* cand_idx;   // [n_tiles][TW]
@@ -140,12 +146,12 @@ __device__ __forceinline__ uint32_t seg_tile1(const Params& p, int t) { return i
 __device__ __forceinline__ uint32_t seg_k(const Params& p, int t, int j) { return is_flat(p) ? p.flat_k[j] : p.ktab[t * p.n_cf + j]; }
 __device__ __forceinline__ int64_t seg_koff(const Params& p, int t) { return is_flat(p) ? 0 : p.koff[t]; }
 
-// largest t with prefix[t] <= x, prefix ascending with prefix[0] == 0, n entries (excluding the end marker)
+// largest t with prefix[t] <= x; prefix ascending with prefix[0] == 0, n entries before the end marker
 __device__ __forceinline__ int find_seg(const uint32_t* prefix, int n, uint32_t x)
 {
     int lo = 0, hi = n - 1;
     while (lo < hi) {
-        int mid = (lo + hi + 1) >> 1;
+        const int mid = (lo + hi + 1) >> 1;
         if (prefix[mid] <= x) lo = mid; else hi = mid - 1;
     }
     return lo;
@@ -174,62 +180,88 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
+// inclusive prefix sum over the lanes of a wavefront
+__device__ __forceinline__ uint32_t wave_scan(uint32_t v)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t x = __shfl_up(v, o, 64);
+        if (lane >= o) v += x;
+    }
+    return v;
+}
+
 __device__ __forceinline__ uint32_t hash32(uint32_t x)
 {
     x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
     return x;
 }
 
-// Inclusive suffix scan over the threads of a block (v of thread i becomes sum over i' >= i).
-// tmp must hold blockDim.x entries.
-__device__ __forceinline__ uint32_t block_suffix_scan(uint32_t v, uint32_t* tmp)
+// One wavefront finds the bin of a 2048-bin histogram (given as `copies` arrays of NBIN counts that
+// are added up) that holds the k-th largest entry: scanning from the top bin down,
+// above < k <= above + count.  Every lane gets the result; bin == NONE if the histogram holds
+// fewer than k entries.  hist must be 16-byte aligned.
+__device__ __forceinline__ void wave_locate_bin(const uint32_t* hist, int copies, uint32_t k, uint32_t& bin,
+                                                uint32_t& above, uint32_t& count)
 {
-    const int tid = threadIdx.x, nt = blockDim.x;
-    tmp[tid] = v;
-    __syncthreads();
-    for (int o = 1; o < nt; o <<= 1) {
-        uint32_t x = (tid + o < nt) ? tmp[tid + o] : 0u;
-        __syncthreads();
-        tmp[tid] += x;
-        __syncthreads();
+    const int lane = threadIdx.x & 63;
+    uint32_t h[32];
+#pragma unroll
+    for (int q = 0; q < 32; ++q) h[q] = 0;
+    for (int r = 0; r < copies; ++r) {
+        const uint4* hv = (const uint4*)(hist + (size_t)r * NBIN + 32 * lane);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint4 v = hv[q];
+            h[4 * q] += v.x; h[4 * q + 1] += v.y; h[4 * q + 2] += v.z; h[4 * q + 3] += v.w;
+        }
     }
-    uint32_t r = tmp[tid];
-    __syncthreads();
-    return r;
-}
-
-// Inclusive prefix scan over the threads of a block.
-__device__ __forceinline__ uint32_t block_prefix_scan(uint32_t v, uint32_t* tmp)
-{
-    const int tid = threadIdx.x, nt = blockDim.x;
-    tmp[tid] = v;
-    __syncthreads();
-    for (int o = 1; o < nt; o <<= 1) {
-        uint32_t x = (tid >= o) ? tmp[tid - o] : 0u;
-        __syncthreads();
-        tmp[tid] += x;
-        __syncthreads();
+    uint32_t mine = 0;
+#pragma unroll
+    for (int q = 0; q < 32; ++q) mine += h[q];
+    const uint32_t incl = wave_scan(mine);
+    const uint32_t total = __shfl(incl, 63, 64);
+    uint32_t ab = total - incl;  // entries in the bins of higher lanes
+    uint32_t fb = NONE, fa = 0, fc = 0;
+#pragma unroll
+    for (int q = 31; q >= 0; --q) {
+        if (ab < k && ab + h[q] >= k) { fb = 32 * lane + q; fa = ab; fc = h[q]; }
+        ab += h[q];
     }
-    uint32_t r = tmp[tid];
-    __syncthreads();
-    return r;
+    const uint64_t m = __ballot(fb != NONE);
+    if (m) {
+        const int src = __ffsll((unsigned long long)m) - 1;
+        bin = __shfl(fb, src, 64); above = __shfl(fa, src, 64); count = __shfl(fc, src, 64);
+    } else {
+        bin = NONE; above = 0; count = 0;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
-// K0a: sample acc = residual + grad at stratified positions, store the keys
+// K0a: sample acc = residual + grad at stratified positions; each workgroup histograms the top
+// 12 key bits of its SAMPLE_BLOCK samples in LDS and stores the counts as 16-bit numbers
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void sample_kernel(Params p)
 {
-    const uint32_t b = blockIdx.x;
+    __shared__ uint32_t h[SBIN];
+    const uint32_t b = blockIdx.x, tid = threadIdx.x;
     const int t = is_flat(p) ? 0 : find_seg(p.samp_prefix, p.n_seg, b);
     const uint32_t lb = b - (is_flat(p) ? 0u : p.samp_prefix[t]);
     const uint32_t S = is_flat(p) ? p.flat_samples : p.samp_cnt[t];
     const int64_t s0 = seg_begin(p, t);
     const uint64_t nt = (uint64_t)(seg_end(p, t) - s0);
 #pragma unroll
+    for (int q = 0; q < SBIN / 256; ++q) h[q * 256 + tid] = 0;
+    __syncthreads();
+    float acc[SAMPLE_BLOCK / 256];
+    bool live[SAMPLE_BLOCK / 256];
+#pragma unroll
     for (int q = 0; q < SAMPLE_BLOCK / 256; ++q) {
-        const uint32_t i = lb * SAMPLE_BLOCK + q * 256 + threadIdx.x;
-        if (i < S) {
+        const uint32_t i = lb * SAMPLE_BLOCK + q * 256 + tid;
+        live[q] = i < S;
+        acc[q] = 0.0f;
+        if (live[q]) {
             uint64_t pos;
             if ((uint64_t)S == nt) {
                 pos = i;  // the whole segment is read
@@ -237,83 +269,117 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
                 const uint64_t a = ((uint64_t)i * nt) / S, e = ((uint64_t)(i + 1) * nt) / S;
                 pos = a + hash32(i * 0x9E3779B9u + 0x85EBCA6Bu) % (uint32_t)(e - a);
             }
-            const float acc = p.res[s0 + (int64_t)pos] + p.grad[s0 + (int64_t)pos];
-            p.samp_key[(size_t)b * SAMPLE_BLOCK + q * 256 + threadIdx.x] = key_of(acc);
+            acc[q] = p.res[s0 + (int64_t)pos] + p.grad[s0 + (int64_t)pos];
         }
     }
+#pragma unroll
+    for (int q = 0; q < SAMPLE_BLOCK / 256; ++q)
+        if (live[q]) atomicAdd(&h[key_of(acc[q]) >> 19], 1u);
+    __syncthreads();
+    // thread i stores bins 16i .. 16i+15, two counts per word (a count is at most SAMPLE_BLOCK)
+    uint4 w[2];
+    uint32_t* wp = (uint32_t*)w;
+#pragma unroll
+    for (int m = 0; m < 8; ++m) wp[m] = h[16 * tid + 2 * m] | (h[16 * tid + 2 * m + 1] << 16);
+    uint4* dst = (uint4*)(p.samp_hist + (size_t)b * (SBIN / 2) + 8 * tid);
+    dst[0] = w[0];
+    dst[1] = w[1];
 }
 
 // ---------------------------------------------------------------------------------------------
-// K0b: per segment, turn the sampled keys into (lo, s) per CF; clear the segment's histograms
+// K0b: per segment, add up the sample histograms and turn them into (lo, s) per CF; clear the
+// segment's histograms and gather-list counts
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
 {
-    __shared__ uint32_t hist[SBIN];
-    __shared__ uint32_t tmp[1024];
-    __shared__ uint32_t found[2];
-    const int t = blockIdx.x, tid = threadIdx.x;
+    __shared__ uint32_t wtot[16];
+    __shared__ uint32_t rank_lo[MAXCF], rank_hi[MAXCF], bin_lo[MAXCF], bin_hi[MAXCF];
+    const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
     const uint32_t S = is_flat(p) ? p.flat_samples : p.samp_cnt[t];
     const uint32_t sb0 = is_flat(p) ? 0u : p.samp_prefix[t];
+    const uint32_t nb = (S + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
     const uint64_t nt = (uint64_t)(seg_end(p, t) - seg_begin(p, t));
     const bool whole = ((uint64_t)S == nt);
+    const bool forced = (p.flags & GRAVAC_FLAG_FORCE_FALLBACK) != 0;
 
-    for (int i = tid; i < SBIN; i += 1024) hist[i] = 0;
-    for (int i = tid; i < p.n_cf * NBIN; i += 1024) p.hist1[(size_t)t * p.n_cf * NBIN + i] = 0;
+    for (int i = tid; i < p.n_cf * REP * NBIN; i += 1024) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
     for (int i = tid; i < NBIN; i += 1024) p.coarse[(size_t)t * NBIN + i] = 0;
+    for (int i = tid; i < p.n_cf * REP * 32; i += 1024) p.list_cnt[(size_t)t * p.n_cf * REP * 32 + i] = 0;
     if (t == 0 && tid == 0) {
         p.status->any_fail = 0; p.status->n_fail = 0; p.status->error = 0; p.status->n_seg = p.n_seg;
     }
-    __syncthreads();
-    const bool forced = (p.flags & GRAVAC_FLAG_FORCE_FALLBACK) != 0;
-    if (!forced)
-        for (uint32_t i = tid; i < S; i += 1024) atomicAdd(&hist[p.samp_key[(size_t)sb0 * SAMPLE_BLOCK + i] >> 19], 1u);
-    __syncthreads();
-    // thread i owns bins 4i .. 4i+3
-    const uint32_t h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
-    const uint32_t mine = h0 + h1 + h2 + h3;
-    const uint32_t suf = block_suffix_scan(mine, tmp);  // samples in bins >= 4*tid
-
-    uint32_t lo_min = 0xFFFFFFFFu;
-    for (int j = 0; j < p.n_cf; ++j) {
-        const uint32_t k = seg_k(p, t, j);
+    if (tid < p.n_cf) {
+        const uint32_t k = seg_k(p, t, tid);
         uint32_t r_lo, r_hi;
         if (whole) {
             r_lo = r_hi = k;
         } else {
+            // expected number of sampled keys among the k largest, widened by ZMARGIN standard deviations
             const double m = (double)k * (double)S / (double)nt, sd = sqrt(m);
             const double a = ceil(m + ZMARGIN * sd + 2.0), b = floor(m - ZMARGIN * sd - 2.0);
-            r_lo = (a >= 4.0e9) ? 0xFFFFFFFFu : (uint32_t)a;
+            r_lo = (a >= 4.0e9) ? NONE : (uint32_t)a;
             r_hi = (b < 1.0) ? 1u : (uint32_t)b;
         }
-        if (tid == 0) { found[0] = 0; found[1] = SBIN - 1; }
-        __syncthreads();
-        // bin of the r-th largest sample: above < r <= above + count
-        uint32_t above = suf - mine;
-        const uint32_t hh[4] = {h0, h1, h2, h3};
+        rank_lo[tid] = r_lo; rank_hi[tid] = r_hi;
+        bin_lo[tid] = 0;            // fewer than r_lo samples (or none at all): every key is a candidate
+        bin_hi[tid] = SBIN - 1;
+    }
+
+    // thread i owns bins 4i .. 4i+3: two words of every block's histogram
+    uint32_t h0 = 0, h1 = 0, h2 = 0, h3 = 0;
+    if (!forced) {
+        const uint2* src = (const uint2*)(p.samp_hist + (size_t)sb0 * (SBIN / 2)) + tid;
+        for (uint32_t b0 = 0; b0 < nb; b0 += 8) {
+            uint2 w[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) w[q] = (b0 + q < nb) ? src[(size_t)(b0 + q) * (SBIN / 4)] : make_uint2(0u, 0u);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                h0 += w[q].x & 0xFFFFu; h1 += w[q].x >> 16;
+                h2 += w[q].y & 0xFFFFu; h3 += w[q].y >> 16;
+            }
+        }
+    }
+    const uint32_t mine = h0 + h1 + h2 + h3;
+    const uint32_t incl = wave_scan(mine);
+    if (lane == 63) wtot[wib] = incl;
+    __syncthreads();
+    uint32_t total = 0, before = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const uint32_t x = wtot[w];
+        total += x;
+        if (w < wib) before += x;
+    }
+    const uint32_t above0 = total - (before + incl);  // samples in bins above this thread's four
+    const uint32_t hh[4] = {h0, h1, h2, h3};
+    for (int j = 0; j < p.n_cf; ++j) {
+        const uint32_t r_lo = rank_lo[j], r_hi = rank_hi[j];
+        uint32_t above = above0;
 #pragma unroll
         for (int q = 3; q >= 0; --q) {
             const uint32_t c = hh[q];
-            if (above < r_lo && above + c >= r_lo) found[0] = 4 * tid + q;
-            if (above < r_hi && above + c >= r_hi) found[1] = 4 * tid + q;
+            if (above < r_lo && above + c >= r_lo) bin_lo[j] = 4 * tid + q;
+            if (above < r_hi && above + c >= r_hi) bin_hi[j] = 4 * tid + q;
             above += c;
         }
-        __syncthreads();
-        if (tid == 0) {
-            uint32_t lo = found[0] << 19;                 // lower edge; bin 0 if the sample has < r_lo keys
-            const uint64_t hi = ((uint64_t)found[1] + 1) << 19;  // upper edge of the bin of the r_hi-th
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t lo_min = NONE;
+        for (int j = 0; j < p.n_cf; ++j) {
+            uint32_t lo = bin_lo[j] << 19;                          // lower edge of the bin of the r_lo-th sample
+            const uint64_t hi = ((uint64_t)bin_hi[j] + 1) << 19;    // upper edge of the bin of the r_hi-th sample
             uint32_t s = 0;
-            while ((((hi > lo ? hi - lo : 0)) >> s) > (uint64_t)OVF) ++s;
-            if (forced) { lo = 0xFFFFFFFFu; s = 0; }
+            while (((hi > lo ? hi - lo : 0) >> s) > (uint64_t)OVF) ++s;
+            if (forced) { lo = NONE; s = 0; }
             CfState st;
-            st.k = k; st.lo = lo; st.s = s; st.mode = MODE_FAIL; st.base = 0; st.open = 0; st.above = 0; st.c = 0;
-            st.tau = 0; st.need = 0; st.cnt_gt = 0; st.list_cnt = 0;
-            st.pad[0] = st.pad[1] = st.pad[2] = st.pad[3] = 0;
+            st.k = seg_k(p, t, j); st.lo = lo; st.s = s; st.mode = MODE_FAIL; st.base = 0; st.open = 0; st.above = 0;
+            st.c = 0; st.tau = 0; st.need = 0; st.cnt_gt = 0;
+            st.pad[0] = st.pad[1] = st.pad[2] = st.pad[3] = st.pad[4] = 0;
             p.st[(size_t)t * p.n_cf + j] = st;
             lo_min = lo < lo_min ? lo : lo_min;
         }
-        __syncthreads();
-    }
-    if (tid == 0) {
         SegState ss;
         ss.lo_min = lo_min; ss.fail = 0; ss.pad[0] = ss.pad[1] = 0;
         p.seg[t] = ss;
@@ -321,18 +387,20 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
 }
 
 // ---------------------------------------------------------------------------------------------
-// K1: the streaming pass.  EF = true: read grad and residual, write acc back, sum acc^2.
-//     EF = false (exact route): read acc from residual only.  Both collect candidates.
+// K1: the streaming pass, one wave tile per wavefront.
+//     EF = true: read grad and residual, write acc back, sum acc^2.
+//     EF = false (exact route, failed segments only): read acc from residual; lo comes from the
+//     coarse histogram.  Both collect the candidates of the tile in index order.
 // ---------------------------------------------------------------------------------------------
 struct TileCtx {
     uint32_t lo_min;
     uint32_t lo[MAXCF];
     uint32_t sh[MAXCF];
     uint32_t ovf[MAXCF];
-    uint32_t* h1;       // candidate histograms of this tile's segment
-    int32_t* cidx;      // candidate slots of this tile
+    uint32_t* h1;   // this workgroup's copy of the candidate histograms of the tile's segment (CF stride REP*NBIN)
+    int32_t* cidx;  // candidate slots of this tile
     float* cval;
-    uint32_t run;       // candidates written so far
+    uint32_t run;   // candidates written so far
     double ssd;
     int ncf;
 };
@@ -344,12 +412,12 @@ __device__ __forceinline__ void cand_hist(TileCtx& c, uint32_t key)
         if (j < c.ncf && key >= c.lo[j]) {
             const uint32_t b = (key - c.lo[j]) >> c.sh[j];
             if (b >= OVF) c.ovf[j]++;
-            else atomicAdd(&c.h1[j * NBIN + b], 1u);
+            else atomicAdd(&c.h1[j * REP * NBIN + b], 1u);
         }
     }
 }
 
-// One lane's four consecutive elements a[0..3] at global index g, vm = validity bits.
+// One lane's four consecutive elements a[0..3] at global index g; vm = validity bits.
 template <bool EF>
 __device__ __forceinline__ void consume(TileCtx& c, const float a[4], int64_t g, unsigned vm)
 {
@@ -367,13 +435,12 @@ __device__ __forceinline__ void consume(TileCtx& c, const float a[4], int64_t g,
     }
     const bool any = f[0] | f[1] | f[2] | f[3];
     if (__ballot(any) != 0ull) {
-        uint64_t m[4];
         uint32_t pre = 0, tot = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            m[e] = __ballot(f[e]);
-            pre += lanes_below(m[e]);
-            tot += (uint32_t)__popcll(m[e]);
+            const uint64_t m = __ballot(f[e]);
+            pre += lanes_below(m);
+            tot += (uint32_t)__popcll(m);
         }
         uint32_t w = c.run + pre;
 #pragma unroll
@@ -393,280 +460,287 @@ template <bool EF>
 __global__ __launch_bounds__(WG) void stream_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
-    const uint32_t nwaves = gridDim.x * WAVES;
+    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
+    if (u >= p.n_tiles) return;
     if (!EF && p.status->any_fail == 0) return;
+    const int t = tile_seg(p, u);
+    if (!EF && p.seg[t].fail == 0) return;
+    const int64_t sb = seg_begin(p, t), se = seg_end(p, t);
+    const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW;
+    const int64_t e0 = (s0 + TW < se) ? s0 + TW : se;
 
-    for (uint32_t u = wave; u < p.n_tiles; u += nwaves) {
-        const int t = tile_seg(p, u);
-        if (!EF && p.seg[t].fail == 0) continue;
-        const int64_t sb = seg_begin(p, t), se = seg_end(p, t);
-        const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW;
-        const int64_t e0 = (s0 + TW < se) ? s0 + TW : se;
-
-        TileCtx c;
-        c.ncf = p.n_cf;
+    TileCtx c;
+    c.ncf = p.n_cf;
+    c.lo_min = NONE;
+#pragma unroll
+    for (int j = 0; j < MAXCF; ++j) {
+        c.ovf[j] = 0;
+        c.lo[j] = NONE;
+        c.sh[j] = 0;
+    }
+    if (EF) {
         c.lo_min = p.seg[t].lo_min;
 #pragma unroll
         for (int j = 0; j < MAXCF; ++j) {
-            c.ovf[j] = 0;
             if (j < p.n_cf) {
                 c.lo[j] = p.st[(size_t)t * p.n_cf + j].lo;
                 c.sh[j] = p.st[(size_t)t * p.n_cf + j].s;
-            } else {
-                c.lo[j] = 0xFFFFFFFFu;
-                c.sh[j] = 0;
             }
         }
-        c.h1 = p.hist1 + (size_t)t * p.n_cf * NBIN;
-        c.cidx = p.cand_idx + (size_t)u * TW;
-        c.cval = p.cand_val + (size_t)u * TW;
-        c.run = 0;
-        c.ssd = 0.0;
-
-        int64_t rb = s0 & ~(int64_t)3;  // rows start at a multiple of 4 elements (16-byte aligned vectors)
-        // head row(s) until the row lies fully inside the tile
-        for (; rb < e0; rb += ROW) {
-            const bool full = (rb >= s0) && (rb + ROW <= e0);
-            if (full) {
-                // four full rows at a time: all loads first, then the arithmetic
-                if (rb + 4 * ROW <= e0) {
-                    v4f gv[4], rv[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int64_t g = rb + q * ROW + 4 * lane;
-                        rv[q] = __builtin_nontemporal_load((const v4f*)(p.res + g));
-                        if (EF) gv[q] = __builtin_nontemporal_load((const v4f*)(p.grad + g));
-                    }
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int64_t g = rb + q * ROW + 4 * lane;
-                        float a[4];
-                        if (EF) {
-                            const v4f av = rv[q] + gv[q];
-                            __builtin_nontemporal_store(av, (v4f*)(p.res + g));
-                            a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
-                        } else {
-                            a[0] = rv[q].x; a[1] = rv[q].y; a[2] = rv[q].z; a[3] = rv[q].w;
-                        }
-                        consume<EF>(c, a, g, 0xFu);
-                    }
-                    rb += 3 * ROW;
-                    continue;
-                }
-                const int64_t g = rb + 4 * lane;
-                v4f rv = __builtin_nontemporal_load((const v4f*)(p.res + g));
-                float a[4];
-                if (EF) {
-                    const v4f gv = __builtin_nontemporal_load((const v4f*)(p.grad + g));
-                    const v4f av = rv + gv;
-                    __builtin_nontemporal_store(av, (v4f*)(p.res + g));
-                    a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
-                } else {
-                    a[0] = rv.x; a[1] = rv.y; a[2] = rv.z; a[3] = rv.w;
-                }
-                consume<EF>(c, a, g, 0xFu);
-            } else {
-                // ragged row: element-wise, guarded
-                const int64_t g = rb + 4 * lane;
-                float a[4];
-                unsigned vm = 0;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int64_t q = g + e;
-                    a[e] = 0.0f;
-                    if (q >= s0 && q < e0) {
-                        vm |= 1u << e;
-                        if (EF) {
-                            a[e] = p.res[q] + p.grad[q];
-                            p.res[q] = a[e];
-                        } else {
-                            a[e] = p.res[q];
-                        }
-                    }
-                }
-                consume<EF>(c, a, g, vm);
-            }
-        }
-
-        // tile epilogue
+    } else {
+        // exact route: lo_j = base of the coarse (key >> 20) bin that holds the k_j-th largest; 1024 bins of
+        // 2^10 keys cover that coarse bin, keys above it land in the open last bin
+        const bool first = (u == seg_tile0(p, t));
 #pragma unroll
         for (int j = 0; j < MAXCF; ++j) {
             if (j < p.n_cf) {
-                const uint32_t o = wave_sum(c.ovf[j]);
-                if (lane == 0 && o) atomicAdd(&c.h1[j * NBIN + OVF], o);
+                uint32_t b, ab, cn;
+                wave_locate_bin(p.coarse + (size_t)t * NBIN, 1, seg_k(p, t, j), b, ab, cn);
+                if (b == NONE) { b = 0; if (lane == 0) p.status->error = 1; }
+                c.lo[j] = b << 20;
+                c.sh[j] = 10;
+                c.lo_min = c.lo[j] < c.lo_min ? c.lo[j] : c.lo_min;
+                if (first) {
+                    // record the new bound; clear what the refine pass may add to
+                    CfState* st = &p.st[(size_t)t * p.n_cf + j];
+                    if (lane == 0) { st->lo = c.lo[j]; st->s = 10; st->mode = MODE_FAIL; }
+                    for (int i = lane; i < NBIN; i += 64) p.hist2[((size_t)t * p.n_cf + j) * NBIN + i] = 0;
+                    if (lane < REP) p.list_cnt[(((size_t)t * p.n_cf + j) * REP + lane) * 32] = 0;
+                }
             }
         }
-        if (EF) {
-            const double s = wave_sum(c.ssd);
-            if (lane == 0) p.ssd[u] = s;
-        }
-        if (lane == 0) p.cand_cnt[u] = c.run;
+        if (first && lane == 0) p.seg[t].lo_min = c.lo_min;
     }
+    c.h1 = p.hist1 + ((size_t)t * p.n_cf * REP + (blockIdx.x & (REP - 1))) * NBIN;
+    c.cidx = p.cand_idx + (size_t)u * TW;
+    c.cval = p.cand_val + (size_t)u * TW;
+    c.run = 0;
+    c.ssd = 0.0;
+
+    // rows start at a multiple of 4 elements so that vector accesses are 16-byte aligned
+    for (int64_t rb = s0 & ~(int64_t)3; rb < e0; rb += ROW) {
+        const bool full = (rb >= s0) && (rb + ROW <= e0);
+        if (full && rb + 4 * ROW <= e0) {
+            // four full rows: all loads first, then the arithmetic
+            v4f gv[4], rv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t g = rb + q * ROW + 4 * lane;
+                rv[q] = __builtin_nontemporal_load((const v4f*)(p.res + g));
+                if (EF) gv[q] = __builtin_nontemporal_load((const v4f*)(p.grad + g));
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t g = rb + q * ROW + 4 * lane;
+                float a[4];
+                if (EF) {
+                    const v4f av = rv[q] + gv[q];
+                    __builtin_nontemporal_store(av, (v4f*)(p.res + g));
+                    a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
+                } else {
+                    a[0] = rv[q].x; a[1] = rv[q].y; a[2] = rv[q].z; a[3] = rv[q].w;
+                }
+                consume<EF>(c, a, g, 0xFu);
+            }
+            rb += 3 * ROW;
+        } else if (full) {
+            const int64_t g = rb + 4 * lane;
+            const v4f rv = __builtin_nontemporal_load((const v4f*)(p.res + g));
+            float a[4];
+            if (EF) {
+                const v4f gv = __builtin_nontemporal_load((const v4f*)(p.grad + g));
+                const v4f av = rv + gv;
+                __builtin_nontemporal_store(av, (v4f*)(p.res + g));
+                a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
+            } else {
+                a[0] = rv.x; a[1] = rv.y; a[2] = rv.z; a[3] = rv.w;
+            }
+            consume<EF>(c, a, g, 0xFu);
+        } else {
+            // ragged row: element-wise, guarded
+            const int64_t g = rb + 4 * lane;
+            float a[4];
+            unsigned vm = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int64_t q = g + e;
+                a[e] = 0.0f;
+                if (q >= s0 && q < e0) {
+                    vm |= 1u << e;
+                    if (EF) {
+                        a[e] = p.res[q] + p.grad[q];
+                        p.res[q] = a[e];
+                    } else {
+                        a[e] = p.res[q];
+                    }
+                }
+            }
+            consume<EF>(c, a, g, vm);
+        }
+    }
+
+#pragma unroll
+    for (int j = 0; j < MAXCF; ++j) {
+        if (j < p.n_cf) {
+            const uint32_t o = wave_sum(c.ovf[j]);
+            if (lane == 0 && o) atomicAdd(&c.h1[j * REP * NBIN + OVF], o);
+        }
+    }
+    if (EF) {
+        const double s = wave_sum(c.ssd);
+        if (lane == 0) p.ssd[u] = s;
+    }
+    if (lane == 0) p.cand_cnt[u] = c.run;
 }
 
 // ---------------------------------------------------------------------------------------------
-// F1 (exact route): histogram of key >> 20 over the tiles of failed segments
+// F1 (exact route): histogram of key >> 20 over the tiles of failed segments; the wavefront of a
+// failed segment's first tile also clears that segment's candidate histograms
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
 {
     __shared__ uint32_t lh[WAVES][NBIN];
     if (p.status->any_fail == 0) return;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + wib);
-    const uint32_t nwaves = gridDim.x * WAVES;
-    uint32_t* h = lh[wib];
-    for (uint32_t u = wave; u < p.n_tiles; u += nwaves) {
-        const int t = tile_seg(p, u);
-        if (p.seg[t].fail == 0) continue;
-        const int64_t sb = seg_begin(p, t), se = seg_end(p, t);
-        const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW;
-        const int64_t e0 = (s0 + TW < se) ? s0 + TW : se;
-        for (int i = lane; i < NBIN; i += 64) h[i] = 0;
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-        for (int64_t q = s0 + lane; q < e0; q += 64) atomicAdd(&h[key_of(p.res[q]) >> 20], 1u);
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-        uint32_t* gh = p.coarse + (size_t)t * NBIN;
-        for (int i = lane; i < NBIN; i += 64) {
-            const uint32_t v = h[i];
-            if (v) atomicAdd(&gh[i], v);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-    }
-}
-
-// Find the bin that holds the k-th largest: scanning from the top bin down,
-// above < k <= above + count.  One block of 256 threads, thread i owns bins 8i .. 8i+7.
-// Returns through out[0..2] = {bin, above, count}; out[3] = total.  Call with all threads.
-__device__ __forceinline__ void locate_bin(const uint32_t* hist, uint32_t k, uint32_t* tmp, uint32_t* out)
-{
-    const int tid = threadIdx.x;
-    uint32_t h[8], mine = 0;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) { h[q] = hist[8 * tid + q]; mine += h[q]; }
-    const uint32_t suf = block_suffix_scan(mine, tmp);
-    if (tid == 0) { out[0] = 0xFFFFFFFFu; out[1] = 0; out[2] = 0; out[3] = suf; }
-    __syncthreads();
-    uint32_t above = suf - mine;
-#pragma unroll
-    for (int q = 7; q >= 0; --q) {
-        if (above < k && above + h[q] >= k) { out[0] = 8 * tid + q; out[1] = above; out[2] = h[q]; }
-        above += h[q];
-    }
-    __syncthreads();
-}
-
-// ---------------------------------------------------------------------------------------------
-// LC (exact route): per (failed segment, CF) set lo to the base of the coarse bin of the k-th largest
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void locate_coarse_kernel(Params p)
-{
-    __shared__ uint32_t tmp[256];
-    __shared__ uint32_t out[4];
-    if (p.status->any_fail == 0) return;
-    const int t = blockIdx.x, j = blockIdx.y, tid = threadIdx.x;
+    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + wib);
+    if (u >= p.n_tiles) return;
+    const int t = tile_seg(p, u);
     if (p.seg[t].fail == 0) return;
-    CfState* st = &p.st[(size_t)t * p.n_cf + j];
-    const uint32_t k = st->k;
-    locate_bin(p.coarse + (size_t)t * NBIN, k, tmp, out);
-    for (int i = tid; i < NBIN; i += 256) p.hist1[((size_t)t * p.n_cf + j) * NBIN + i] = 0;
-    if (tid == 0) {
-        if (out[0] == 0xFFFFFFFFu) { p.status->error = 1; out[0] = 0; }
-        const uint32_t lo = out[0] << 20;
-        st->lo = lo;
-        st->s = 10;  // 1024 bins of 2^10 keys cover the coarse bin; keys above it land in the open last bin
-        st->mode = MODE_FAIL; st->list_cnt = 0;
-        atomicMin(&p.seg[t].lo_min, lo);
+    uint32_t* h = lh[wib];
+    const int64_t sb = seg_begin(p, t), se = seg_end(p, t);
+    const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW;
+    const int64_t e0 = (s0 + TW < se) ? s0 + TW : se;
+    if (u == seg_tile0(p, t))
+        for (int i = lane; i < p.n_cf * REP * NBIN; i += 64) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
+    for (int i = lane; i < NBIN; i += 64) h[i] = 0;
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    for (int64_t q = s0 + lane; q < e0; q += 64) atomicAdd(&h[key_of(p.res[q]) >> 20], 1u);
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    uint32_t* gh = p.coarse + (size_t)t * NBIN;
+    for (int i = lane; i < NBIN; i += 64) {
+        const uint32_t v = h[i];
+        if (v) atomicAdd(&gh[i], v);
+    }
+}
+
+// How the bin that holds the k-th largest gets resolved to one key.
+struct BinPlan {
+    uint32_t mode, base, open, above, c;
+};
+
+// Decide from the located bin (b, above, c) of the candidate histogram with bins (key - lo) >> s.
+__device__ __forceinline__ BinPlan plan_bin(uint32_t lo, uint32_t s, uint32_t b, uint32_t above, uint32_t c)
+{
+    BinPlan q;
+    if (b == NONE) q.mode = MODE_FAIL;  // fewer than k candidates: the bound was too high
+    else if (b == OVF) q.mode = (c <= LCAP) ? MODE_GATHER : MODE_FAIL;
+    else if (s == 0) q.mode = MODE_RESOLVED;
+    else if (c <= LCAP) q.mode = MODE_GATHER;
+    else if (s <= 11) q.mode = MODE_HIST;
+    else q.mode = MODE_FAIL;
+    q.base = (b == NONE) ? 0u : lo + (b << s);
+    q.open = (b == OVF) ? 1u : 0u;
+    q.above = above;
+    q.c = c;
+    return q;
+}
+
+__device__ __forceinline__ void store_plan(CfState* st, const BinPlan& q)
+{
+    st->mode = q.mode;
+    if (q.mode != MODE_FAIL) {
+        st->base = q.base; st->open = q.open; st->above = q.above; st->c = q.c;
+        if (q.mode == MODE_RESOLVED) { st->tau = q.base; st->cnt_gt = q.above; st->need = st->k - q.above; }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// L1: per (segment, CF) find the candidate-histogram bin of the k-th largest and decide how to resolve it
+// L1: one wavefront per (segment, CF): find the candidate-histogram bin of the k-th largest and
+// decide how to resolve it; a segment whose bound failed is marked for the exact route
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void locate_kernel(Params p, int second)
+__global__ __launch_bounds__(WG) void locate_kernel(Params p)
 {
-    __shared__ uint32_t tmp[256];
-    __shared__ uint32_t out[4];
-    const int t = blockIdx.x, j = blockIdx.y, tid = threadIdx.x;
-    if (second) {
-        if (p.status->any_fail == 0) return;
-        if (p.seg[t].fail == 0) return;
-    }
-    CfState* st = &p.st[(size_t)t * p.n_cf + j];
-    const uint32_t k = st->k, lo = st->lo, s = st->s;
-    locate_bin(p.hist1 + ((size_t)t * p.n_cf + j) * NBIN, k, tmp, out);
-    const uint32_t b = out[0], above = out[1], c = out[2];
-    uint32_t mode;
-    if (b == 0xFFFFFFFFu) {
-        mode = MODE_FAIL;  // fewer than k candidates: the bound was too high
-    } else if (b == OVF) {
-        mode = (c <= LCAP) ? MODE_GATHER : MODE_FAIL;
-    } else if (s == 0) {
-        mode = MODE_RESOLVED;
-    } else if (c <= LCAP) {
-        mode = MODE_GATHER;
-    } else if (s <= 11) {
-        mode = MODE_HIST;
-    } else {
-        mode = MODE_FAIL;
-    }
-    if (mode == MODE_HIST)
-        for (int i = tid; i < NBIN; i += 256) p.hist2[((size_t)t * p.n_cf + j) * NBIN + i] = 0;
-    if (tid == 0) {
-        st->mode = mode;
-        st->list_cnt = 0;
-        if (mode != MODE_FAIL) {
-            st->base = lo + (b << s);
-            st->open = (b == OVF) ? 1u : 0u;
-            st->above = above;
-            st->c = c;
-            if (mode == MODE_RESOLVED) { st->tau = st->base; st->cnt_gt = above; st->need = k - above; }
-        } else if (second) {
-            p.status->error = 1;
-        } else {
+    const int lane = threadIdx.x & 63;
+    const uint32_t id = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
+    if (id >= (uint32_t)(p.n_seg * p.n_cf)) return;
+    const int t = id / p.n_cf;
+    CfState* st = &p.st[id];
+    uint32_t b, above, c;
+    wave_locate_bin(p.hist1 + (size_t)id * REP * NBIN, REP, st->k, b, above, c);
+    const BinPlan q = plan_bin(st->lo, st->s, b, above, c);
+    if (q.mode == MODE_HIST)
+        for (int i = lane; i < NBIN; i += 64) p.hist2[(size_t)id * NBIN + i] = 0;
+    if (lane == 0) {
+        store_plan(st, q);
+        if (q.mode == MODE_FAIL) {
             p.status->any_fail = 1;
             if (atomicExch(&p.seg[t].fail, 1u) == 0u) atomicAdd(&p.status->n_fail, 1);
-            p.seg[t].lo_min = 0xFFFFFFFFu;  // the exact route lowers it again with atomicMin
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// R1: one pass over the candidates: gather (or histogram) the keys of the bin that holds the k-th largest
+// R1: one pass over the candidates: gather (or histogram) the keys of the bin that holds the
+// k-th largest.  For a segment that took the exact route the plan is derived here, by every
+// wavefront for itself, from the rebuilt candidate histogram (its first tile's wavefront records it).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(WG) void refine_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
-    const uint32_t nwaves = gridDim.x * WAVES;
-    for (uint32_t u = wave; u < p.n_tiles; u += nwaves) {
-        const uint32_t cnt = p.cand_cnt[u];
-        if (cnt == 0) continue;
-        const int t = tile_seg(p, u);
-        uint32_t mode[MAXCF], base[MAXCF], span[MAXCF];
-        bool work = false;
+    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
+    if (u >= p.n_tiles) return;
+    const uint32_t cnt = p.cand_cnt[u];
+    const int t = tile_seg(p, u);
+    const bool redo = p.status->any_fail != 0 && p.seg[t].fail != 0;
+    const bool first = redo && (u == seg_tile0(p, t));
+    if (cnt == 0 && !first) return;
+    uint32_t mode[MAXCF], base[MAXCF], span[MAXCF];
+    bool work = false;
 #pragma unroll
-        for (int j = 0; j < MAXCF; ++j) {
-            mode[j] = MODE_RESOLVED; base[j] = 0; span[j] = 0;
-            if (j < p.n_cf) {
-                const CfState* st = &p.st[(size_t)t * p.n_cf + j];
-                mode[j] = st->mode;
-                base[j] = st->base;
-                span[j] = st->open ? 0xFFFFFFFFu : ((1u << st->s) - 1u);  // key - base <= span
-                work |= (mode[j] == MODE_GATHER || mode[j] == MODE_HIST);
+    for (int j = 0; j < MAXCF; ++j) {
+        mode[j] = MODE_RESOLVED; base[j] = 0; span[j] = 0;
+        if (j < p.n_cf) {
+            CfState* st = &p.st[(size_t)t * p.n_cf + j];
+            BinPlan q;
+            uint32_t s = st->s;
+            if (redo) {
+                uint32_t b, above, c;
+                wave_locate_bin(p.hist1 + ((size_t)t * p.n_cf + j) * REP * NBIN, REP, st->k, b, above, c);
+                q = plan_bin(st->lo, s, b, above, c);
+                if (first && lane == 0) {
+                    store_plan(st, q);
+                    if (q.mode == MODE_FAIL) p.status->error = 1;  // the exact route cannot fail
+                }
+            } else {
+                q.mode = st->mode; q.base = st->base; q.open = st->open;
             }
+            mode[j] = q.mode;
+            base[j] = q.base;
+            span[j] = q.open ? NONE : ((1u << s) - 1u);  // in the bin <=> key - base <= span
+            work |= (mode[j] == MODE_GATHER || mode[j] == MODE_HIST);
         }
-        if (!work) continue;
-        const float* cv = p.cand_val + (size_t)u * TW;
-        for (uint32_t i = lane; i < cnt; i += 64) {
-            const uint32_t key = key_of(cv[i]);
+    }
+    if (!work || cnt == 0) return;
+    const float* cv = p.cand_val + (size_t)u * TW;
+    for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
+        // eight loads in flight per lane; an absent slot gets a key that lies in no bin (base > key)
+        uint32_t kq[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t i = i0 + q * 64 + lane;
+            kq[q] = (i < cnt) ? key_of(cv[i]) : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t key = kq[q];
+            const bool live = i0 + q * 64 + lane < cnt;
 #pragma unroll
             for (int j = 0; j < MAXCF; ++j) {
-                if (j < p.n_cf && key >= base[j] && key - base[j] <= span[j]) {
-                    CfState* st = &p.st[(size_t)t * p.n_cf + j];
+                if (j < p.n_cf && live && key >= base[j] && key - base[j] <= span[j]) {
                     if (mode[j] == MODE_GATHER) {
-                        const uint32_t pos = atomicAdd(&st->list_cnt, 1u);
-                        if (pos < LCAP) p.list[((size_t)t * p.n_cf + j) * LCAP + pos] = key;
+                        const size_t lst = ((size_t)t * p.n_cf + j) * REP + (blockIdx.x & (REP - 1));
+                        const uint32_t pos = atomicAdd(&p.list_cnt[lst * 32], 1u);
+                        if (pos < LCAP) p.list[lst * LCAP + pos] = key;
                     } else if (mode[j] == MODE_HIST) {
                         atomicAdd(&p.hist2[((size_t)t * p.n_cf + j) * NBIN + (key - base[j])], 1u);
                     }
@@ -681,207 +755,301 @@ __global__ __launch_bounds__(WG) void refine_kernel(Params p)
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void resolve_kernel(Params p)
 {
-    __shared__ uint32_t tmp[256];
-    __shared__ uint32_t out[4];
-    __shared__ uint32_t keys[LCAP];
-    __shared__ uint32_t wsum[WAVES];
-    const int t = blockIdx.x, j = blockIdx.y, tid = threadIdx.x;
-    CfState* st = &p.st[(size_t)t * p.n_cf + j];
+    __shared__ uint32_t wsum[2][WAVES];
+    const int id = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+    CfState* st = &p.st[id];
     const uint32_t mode = st->mode;
     if (mode == MODE_RESOLVED) return;
     if (mode == MODE_FAIL) { if (tid == 0) p.status->error = 1; return; }
     const uint32_t k = st->k, above = st->above, want = k - above;  // want-th largest inside the bin
+    const uint32_t base = st->base;
     if (mode == MODE_HIST) {
-        // bins are single keys: base + b
-        locate_bin(p.hist2 + ((size_t)t * p.n_cf + j) * NBIN, want, tmp, out);
-        if (tid == 0) {
-            if (out[0] == 0xFFFFFFFFu) { p.status->error = 1; out[0] = 0; }
-            st->tau = st->base + out[0];
-            st->cnt_gt = above + out[1];
+        if (wib != 0) return;
+        uint32_t b, ab, cn;  // bins are single keys: base + b
+        wave_locate_bin(p.hist2 + (size_t)id * NBIN, 1, want, b, ab, cn);
+        if (lane == 0) {
+            if (b == NONE) { p.status->error = 1; b = 0; }
+            st->tau = base + b;
+            st->cnt_gt = above + ab;
             st->need = k - st->cnt_gt;
             st->mode = MODE_RESOLVED;
         }
         return;
     }
-    // gather: the want-th largest of the listed keys by a bitwise search on the key value
+    // gather: the want-th largest of the listed keys, by a bitwise search on d = key - base.
+    // The keys sit in REP lists; list r holds positions [off_r, off_r + n_r) of the concatenation.
     const uint32_t c = st->c;
-    if (st->list_cnt != c || c > LCAP || want == 0 || want > c) { if (tid == 0) p.status->error = 1; return; }
-    const uint32_t* lst = p.list + ((size_t)t * p.n_cf + j) * LCAP;
-    for (uint32_t i = tid; i < c; i += 256) keys[i] = lst[i];
-    __syncthreads();
+    uint32_t off[REP + 1];
+    off[0] = 0;
+#pragma unroll
+    for (int r = 0; r < REP; ++r) off[r + 1] = off[r] + p.list_cnt[((size_t)id * REP + r) * 32];
+    if (off[REP] != c || c > LCAP || want == 0 || want > c) { if (tid == 0) p.status->error = 1; return; }
+    uint32_t d[LCAP / 256];
+#pragma unroll
+    for (int q = 0; q < LCAP / 256; ++q) {
+        const uint32_t i = q * 256 + tid;
+        d[q] = 0u;                               // padding never counts: trial values are >= 1
+        if (i < c) {
+            int r = 0;
+#pragma unroll
+            for (int x = 1; x < REP; ++x) r += (i >= off[x]);
+            uint32_t o = 0;
+#pragma unroll
+            for (int x = 0; x < REP; ++x) if (x == r) o = off[x];
+            d[q] = p.list[((size_t)id * REP + r) * LCAP + (i - o)] - base;
+        }
+    }
+    const int nbits = st->open ? 31 : (int)st->s;
     uint32_t prefix = 0;
-    for (int bit = 30; bit >= 0; --bit) {
+    int buf = 0;
+    for (int bit = nbits - 1; bit >= 0; --bit) {
         const uint32_t trial = prefix | (1u << bit);
         uint32_t cnt = 0;
-        for (uint32_t i = tid; i < c; i += 256) cnt += (keys[i] >= trial);
+#pragma unroll
+        for (int q = 0; q < LCAP / 256; ++q) cnt += (d[q] >= trial);
         cnt = wave_sum(cnt);
-        if ((tid & 63) == 0) wsum[tid >> 6] = cnt;
+        if (lane == 0) wsum[buf][wib] = cnt;
         __syncthreads();
-        const uint32_t total = wsum[0] + wsum[1] + wsum[2] + wsum[3];
-        __syncthreads();
+        const uint32_t total = wsum[buf][0] + wsum[buf][1] + wsum[buf][2] + wsum[buf][3];
+        buf ^= 1;
         if (total >= want) prefix = trial;
     }
     uint32_t gt = 0;
-    for (uint32_t i = tid; i < c; i += 256) gt += (keys[i] > prefix);
+#pragma unroll
+    for (int q = 0; q < LCAP / 256; ++q) gt += (q * 256 + tid < c) && (d[q] > prefix);
     gt = wave_sum(gt);
-    if ((tid & 63) == 0) wsum[tid >> 6] = gt;
+    __syncthreads();
+    if (lane == 0) wsum[0][wib] = gt;
     __syncthreads();
     if (tid == 0) {
-        st->tau = prefix;
-        st->cnt_gt = above + wsum[0] + wsum[1] + wsum[2] + wsum[3];
+        st->tau = base + prefix;
+        st->cnt_gt = above + wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
         st->need = k - st->cnt_gt;
         st->mode = MODE_RESOLVED;
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// K3: per tile, count candidates above / at the committed threshold; energy above each CF's threshold
+// K3: one wavefront per tile: candidates above / at the committed threshold, energy above each
+// CF's threshold.  Written for every tile, so that the scan needs no second look at cand_cnt.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(WG) void tile_count_kernel(Params p)
+__global__ __launch_bounds__(WG) void count_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
-    const uint32_t nwaves = gridDim.x * WAVES;
-    for (uint32_t u = wave; u < p.n_tiles; u += nwaves) {
-        const uint32_t cnt = p.cand_cnt[u];
-        uint32_t g = 0, e = 0;
-        double ss[MAXCF];
+    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
+    if (u >= p.n_tiles) return;
+    const uint32_t cnt = p.cand_cnt[u];
+    if (cnt == 0) {
+        if (lane == 0) { p.tg[u] = 0; p.te[u] = 0; }
+        if (lane < p.n_cf) p.sss[(size_t)u * p.n_cf + lane] = 0.0;
+        return;
+    }
+    const int t = tile_seg(p, u);
+    uint32_t tau[MAXCF];
+    uint32_t tc = 0;
 #pragma unroll
-        for (int j = 0; j < MAXCF; ++j) ss[j] = 0.0;
-        if (cnt) {
-            const int t = tile_seg(p, u);
-            uint32_t tau[MAXCF];
+    for (int j = 0; j < MAXCF; ++j) {
+        tau[j] = (j < p.n_cf) ? p.st[(size_t)t * p.n_cf + j].tau : NONE;
+        if (j == p.commit) tc = tau[j];
+    }
+    double ss[MAXCF];
 #pragma unroll
-            for (int j = 0; j < MAXCF; ++j) tau[j] = (j < p.n_cf) ? p.st[(size_t)t * p.n_cf + j].tau : 0xFFFFFFFFu;
-            uint32_t tc = 0;
+    for (int j = 0; j < MAXCF; ++j) ss[j] = 0.0;
+    uint32_t g = 0, e = 0;
+    const float* cv = p.cand_val + (size_t)u * TW;
+    for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
+        float vq[8];
 #pragma unroll
-            for (int j = 0; j < MAXCF; ++j) if (j == p.commit) tc = tau[j];
-            const float* cv = p.cand_val + (size_t)u * TW;
-            for (uint32_t i = lane; i < cnt; i += 64) {
-                const float v = cv[i];
-                const uint32_t key = key_of(v);
-                const double d = (double)v;
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t i = i0 + q * 64 + lane;
+            vq[q] = (i < cnt) ? cv[i] : 0.0f;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            if (i0 + q * 64 + lane < cnt) {
+                const uint32_t key = key_of(vq[q]);
+                const double dv = (double)vq[q];
                 g += (key > tc);
                 e += (key == tc);
 #pragma unroll
-                for (int j = 0; j < MAXCF; ++j) if (j < p.n_cf && key > tau[j]) ss[j] += d * d;
+                for (int j = 0; j < MAXCF; ++j) if (j < p.n_cf && key > tau[j]) ss[j] += dv * dv;
             }
-            g = wave_sum(g);
-            e = wave_sum(e);
-#pragma unroll
-            for (int j = 0; j < MAXCF; ++j) if (j < p.n_cf) ss[j] = wave_sum(ss[j]);
-        }
-        if (lane == 0) {
-            p.tg[u] = g;
-            p.te[u] = e;
-#pragma unroll
-            for (int j = 0; j < MAXCF; ++j) if (j < p.n_cf) p.sss[(size_t)u * p.n_cf + j] = ss[j];
         }
     }
+    g = wave_sum(g);
+    e = wave_sum(e);
+#pragma unroll
+    for (int j = 0; j < MAXCF; ++j) {
+        if (j < p.n_cf) {
+            const double x = wave_sum(ss[j]);
+            if (lane == 0) p.sss[(size_t)u * p.n_cf + j] = x;
+        }
+    }
+    if (lane == 0) { p.tg[u] = g; p.te[u] = e; }
 }
 
 // ---------------------------------------------------------------------------------------------
-// SCAN: blockIdx.y == 0: per segment exclusive scan of the tile counts -> output offsets and tie quotas.
-//       blockIdx.y == 1 + j: statistics of CF j (fixed summation order).
+// SCAN: blocks [0, n_seg): exclusive scan of one segment's tile counts -> every tile's output
+//       offset and tie quota.  Blocks [n_seg, n_seg + n_seg*n_cf): statistics of one (segment, CF),
+//       summed over the tiles in a fixed order.  Every thread issues its loads in batches so
+//       that the kernel is a few memory round trips long, whatever the tile count.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void scan_kernel(Params p)
+constexpr int SCAN_T = 1024;                 // threads
+constexpr int SCAN_PER = 4;                  // tiles per thread and sweep
+constexpr int SCAN_SWEEP = SCAN_T * SCAN_PER;
+
+__global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p)
 {
-    __shared__ uint32_t tmp[1024];
-    __shared__ double dsum[2][1024];
-    const int t = blockIdx.x, role = blockIdx.y, tid = threadIdx.x, nt = blockDim.x;
-    const uint32_t u0 = seg_tile0(p, t), u1 = seg_tile1(p, t), ntile = u1 - u0;
-    if (role == 0) {
+    __shared__ uint32_t sg[SCAN_SWEEP], se[SCAN_SWEEP];
+    __shared__ uint32_t wt[2][16];
+    __shared__ double dred[2][SCAN_T];
+    const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+    if (blockIdx.x < (uint32_t)p.n_seg) {
+        const int t = blockIdx.x;
+        const uint32_t u0 = seg_tile0(p, t), u1 = seg_tile1(p, t);
         const uint32_t need = p.st[(size_t)t * p.n_cf + p.commit].need;
-        const uint32_t chunk = (ntile + nt - 1) / nt;
-        const uint32_t a = u0 + tid * chunk < u1 ? u0 + tid * chunk : u1;
-        const uint32_t b = a + chunk < u1 ? a + chunk : u1;
-        uint32_t G = 0, E = 0;
-        for (uint32_t u = a; u < b; ++u) { G += p.tg[u]; E += p.te[u]; }
-        uint32_t Gx = block_prefix_scan(G, tmp) - G;
-        uint32_t Ex = block_prefix_scan(E, tmp) - E;
-        for (uint32_t u = a; u < b; ++u) {
-            const uint32_t g = p.tg[u], e = p.te[u];
-            const uint32_t ties_before = Ex < need ? Ex : need;
-            const uint32_t left = need - ties_before;
-            p.toff[u] = Gx + ties_before;
-            p.ttake[u] = left < e ? left : e;
-            Gx += g;
-            Ex += e;
+        uint32_t carry_g = 0, carry_e = 0;
+        // coalesced loads of the next sweep are in flight while the current one is scanned
+        uint32_t ng[SCAN_PER], ne[SCAN_PER];
+#pragma unroll
+        for (int q = 0; q < SCAN_PER; ++q) {
+            const uint32_t u = u0 + q * SCAN_T + tid;
+            ng[q] = (u < u1) ? p.tg[u] : 0u;
+            ne[q] = (u < u1) ? p.te[u] : 0u;
         }
-        if (t == 0 && tid == 0 && p.out_count) {
-            int64_t total = 0;
-            if (is_flat(p)) total = p.flat_k[p.commit]; else total = p.koff[p.n_seg];
-            *p.out_count = total;
+        for (uint32_t base = u0; base < u1; base += SCAN_SWEEP) {
+#pragma unroll
+            for (int q = 0; q < SCAN_PER; ++q) { sg[q * SCAN_T + tid] = ng[q]; se[q * SCAN_T + tid] = ne[q]; }
+#pragma unroll
+            for (int q = 0; q < SCAN_PER; ++q) {
+                const uint32_t u = base + SCAN_SWEEP + q * SCAN_T + tid;
+                ng[q] = (u < u1) ? p.tg[u] : 0u;
+                ne[q] = (u < u1) ? p.te[u] : 0u;
+            }
+            __syncthreads();
+            // this thread's SCAN_PER consecutive tiles
+            uint32_t g[SCAN_PER], e[SCAN_PER], sum_g = 0, sum_e = 0;
+#pragma unroll
+            for (int i = 0; i < SCAN_PER; ++i) {
+                g[i] = sg[tid * SCAN_PER + i]; e[i] = se[tid * SCAN_PER + i];
+                sum_g += g[i]; sum_e += e[i];
+            }
+            const uint32_t ig = wave_scan(sum_g), ie = wave_scan(sum_e);
+            if (lane == 63) { wt[0][wib] = ig; wt[1][wib] = ie; }
+            __syncthreads();
+            uint32_t bg = 0, be = 0, tg = 0, te = 0;
+#pragma unroll
+            for (int w = 0; w < 16; ++w) {
+                const uint32_t xg = wt[0][w], xe = wt[1][w];
+                tg += xg; te += xe;
+                if (w < wib) { bg += xg; be += xe; }
+            }
+            uint32_t run_g = carry_g + bg + ig - sum_g;   // candidates above the threshold before this thread's tiles
+            uint32_t run_e = carry_e + be + ie - sum_e;   // candidates at the threshold before this thread's tiles
+#pragma unroll
+            for (int i = 0; i < SCAN_PER; ++i) {
+                const uint32_t ties_before = run_e < need ? run_e : need;  // ties selected in earlier tiles
+                const uint32_t left = need - ties_before;
+                sg[tid * SCAN_PER + i] = run_g + ties_before;               // output offset of the tile
+                se[tid * SCAN_PER + i] = left < e[i] ? left : e[i];         // its tie quota
+                run_g += g[i];
+                run_e += e[i];
+            }
+            carry_g += tg;
+            carry_e += te;
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < SCAN_PER; ++q) {
+                const uint32_t u = base + q * SCAN_T + tid;
+                if (u < u1) { p.toff[u] = sg[q * SCAN_T + tid]; p.ttake[u] = se[q * SCAN_T + tid]; }
+            }
+            __syncthreads();
         }
         return;
     }
-    const int j = role - 1;
-    double sd = 0.0, sj = 0.0;
-    for (uint32_t u = u0 + tid; u < u1; u += nt) {
-        sd += p.ssd[u];
-        sj += p.sss[(size_t)u * p.n_cf + j];
+    const uint32_t id = blockIdx.x - p.n_seg;
+    const int t = id / p.n_cf, j = id % p.n_cf;
+    const uint32_t ua = seg_tile0(p, t), ub = seg_tile1(p, t);
+    double pd[16], pj[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) { pd[q] = 0.0; pj[q] = 0.0; }
+    for (uint32_t u0 = ua + tid; u0 < ub; u0 += 16 * SCAN_T) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const uint32_t u = u0 + q * SCAN_T;
+            if (u < ub) {
+                pd[q] += p.ssd[u];
+                pj[q] += p.sss[(size_t)u * p.n_cf + j];
+            }
+        }
     }
-    dsum[0][tid] = sd;
-    dsum[1][tid] = sj;
+    double sd = 0.0, sj = 0.0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) { sd += pd[q]; sj += pj[q]; }
+    dred[0][tid] = sd; dred[1][tid] = sj;
     __syncthreads();
-    for (int o = nt >> 1; o > 0; o >>= 1) {
-        if (tid < o) { dsum[0][tid] += dsum[0][tid + o]; dsum[1][tid] += dsum[1][tid + o]; }
+    for (int o = SCAN_T >> 1; o > 0; o >>= 1) {
+        if (tid < o) { dred[0][tid] += dred[0][tid + o]; dred[1][tid] += dred[1][tid + o]; }
         __syncthreads();
     }
     if (tid == 0) {
-        const CfState* st = &p.st[(size_t)t * p.n_cf + j];
+        const CfState* st = &p.st[id];
         const double tau = (double)__uint_as_float(st->tau);
-        const double ss_dense = dsum[0][0];
-        const double ss_sel = dsum[1][0] + (double)st->need * tau * tau;
-        double* o = p.out_stats + ((size_t)t * p.n_cf + j) * GRAVAC_STATS_PER_CF;
+        const double ss_dense = dred[0][0];
+        const double ss_sel = dred[1][0] + (double)st->need * tau * tau;  // ties all have magnitude tau
+        double* o = p.out_stats + (size_t)id * GRAVAC_STATS_PER_CF;
         o[0] = ss_sel;
         o[1] = ss_dense;
         o[2] = (ss_dense == 0.0) ? 1.0 : ss_sel / ss_dense;
         o[3] = tau;
+        if (id == 0 && p.out_count) *p.out_count = is_flat(p) ? (int64_t)p.flat_k[p.commit] : p.koff[p.n_seg];
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// K4: emit the committed selection in ascending index order and zero its residual slots
+// K4: one wavefront per tile emits the tile's share of the committed selection in ascending index
+//     order and zeroes its residual slots
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(WG) void emit_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
-    const uint32_t nwaves = gridDim.x * WAVES;
-    for (uint32_t u = wave; u < p.n_tiles; u += nwaves) {
-        const uint32_t cnt = p.cand_cnt[u];
-        if (cnt == 0) continue;
-        const uint32_t take = p.ttake[u];
-        if (p.tg[u] == 0 && take == 0) continue;
-        const int t = tile_seg(p, u);
-        const uint32_t tau = p.st[(size_t)t * p.n_cf + p.commit].tau;
-        int64_t pos = seg_koff(p, t) + (int64_t)p.toff[u];
-        const int64_t lim = seg_koff(p, t) + (int64_t)seg_k(p, t, p.commit);  // end of this segment's message
-        uint32_t erun = 0;
-        const float* cv = p.cand_val + (size_t)u * TW;
-        const int32_t* ci = p.cand_idx + (size_t)u * TW;
-        for (uint32_t i0 = 0; i0 < cnt; i0 += 64) {
-            const uint32_t i = i0 + lane;
-            float v = 0.0f;
-            int32_t ix = 0;
-            bool gt = false, eq = false;
-            if (i < cnt) {
-                v = cv[i];
-                ix = ci[i];
-                const uint32_t key = key_of(v);
-                gt = key > tau;
-                eq = key == tau;
-            }
+    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
+    if (u >= p.n_tiles) return;
+    const uint32_t cnt = p.cand_cnt[u];
+    if (cnt == 0) return;
+    const uint32_t take = p.ttake[u];
+    if (p.tg[u] == 0 && take == 0) return;
+    const int t = tile_seg(p, u);
+    const uint32_t tau = p.st[(size_t)t * p.n_cf + p.commit].tau;
+    const int64_t seg_out = seg_koff(p, t);
+    const int64_t lim = seg_out + (int64_t)seg_k(p, t, p.commit);  // end of this segment's message
+    int64_t pos = seg_out + (int64_t)p.toff[u];
+    uint32_t erun = 0;
+    const float* cv = p.cand_val + (size_t)u * TW;
+    const int32_t* ci = p.cand_idx + (size_t)u * TW;
+    for (uint32_t b0 = 0; b0 < cnt; b0 += 64 * 4) {
+        float vq[4];
+        int32_t iq[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t q = b0 + r * 64 + lane;
+            vq[r] = (q < cnt) ? cv[q] : 0.0f;
+            iq[r] = (q < cnt) ? ci[q] : 0;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const bool live = b0 + r * 64 + lane < cnt;
+            const uint32_t key = key_of(vq[r]);
+            const bool gt = live && key > tau, eq = live && key == tau;
             const uint64_t me = __ballot(eq);
             const bool sel = gt || (eq && (erun + lanes_below(me)) < take);
             const uint64_t ms = __ballot(sel);
             if (sel) {
                 const int64_t o = pos + lanes_below(ms);
                 if (o < lim) {
-                    p.out_idx[o] = ix;
-                    p.out_val[o] = v;
-                    p.res[ix] = 0.0f;
+                    p.out_idx[o] = iq[r];
+                    p.out_val[o] = vq[r];
+                    p.res[iq[r]] = 0.0f;
                 } else {
                     p.status->error = 1;  // cannot happen if the counts are consistent; never write out of range
                 }
@@ -972,11 +1140,11 @@ __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restri
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-    size_t status, seg_off, koff, tile_prefix, samp_prefix, samp_cnt, ktab, st, seg, hist1, hist2, coarse, list,
-        samp_key, cand_cnt, tg, te, toff, ttake, ssd, sss, cand_idx, cand_val, total;
+    size_t status, seg_off, koff, tile_prefix, samp_prefix, samp_cnt, ktab, st, seg, hist1, hist2, coarse, list, list_cnt,
+        samp_hist, cand_cnt, tg, te, toff, ttake, ssd, sss, cand_idx, cand_val, total;
 };
 
-// Upper bounds that depend only on (n, n_cf, n_seg).
+// Upper bounds that depend only on (n, n_seg).
 uint64_t max_tiles(int64_t n, int n_seg) { return (uint64_t)((n + TW - 1) / TW) + (uint64_t)n_seg; }
 
 uint64_t max_sample_blocks(int64_t n, int n_seg)
@@ -1002,11 +1170,12 @@ Layout make_layout(int64_t n, int n_cf, int n_seg)
     L.ktab = take(sizeof(uint32_t) * sc);
     L.st = take(sizeof(CfState) * sc);
     L.seg = take(sizeof(SegState) * n_seg);
-    L.hist1 = take(sizeof(uint32_t) * sc * NBIN);
+    L.hist1 = take(sizeof(uint32_t) * sc * REP * NBIN);
     L.hist2 = take(sizeof(uint32_t) * sc * NBIN);
     L.coarse = take(sizeof(uint32_t) * (size_t)n_seg * NBIN);
-    L.list = take(sizeof(uint32_t) * sc * LCAP);
-    L.samp_key = take(sizeof(uint32_t) * nsb * SAMPLE_BLOCK);
+    L.list = take(sizeof(uint32_t) * sc * REP * LCAP);
+    L.list_cnt = take(sizeof(uint32_t) * sc * REP * 32);
+    L.samp_hist = take(sizeof(uint32_t) * nsb * (SBIN / 2));
     L.cand_cnt = take(sizeof(uint32_t) * nt);
     L.tg = take(sizeof(uint32_t) * nt);
     L.te = take(sizeof(uint32_t) * nt);
@@ -1027,6 +1196,7 @@ uint32_t sample_count(uint64_t nt, double cf_max, bool flat)
     if (target < 4096) target = 4096;
     if (target > (uint64_t)SAMPLE_MAX) target = SAMPLE_MAX;
     target = (target + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK * SAMPLE_BLOCK;
+    if (nt <= (uint64_t)LCAP) return 0;  // every element becomes a candidate; the gather list resolves it
     return (nt <= 2 * target) ? (uint32_t)nt : (uint32_t)target;
 }
 
@@ -1117,7 +1287,8 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
     p.hist2 = (uint32_t*)(ws + L.hist2);
     p.coarse = (uint32_t*)(ws + L.coarse);
     p.list = (uint32_t*)(ws + L.list);
-    p.samp_key = (uint32_t*)(ws + L.samp_key);
+    p.list_cnt = (uint32_t*)(ws + L.list_cnt);
+    p.samp_hist = (uint32_t*)(ws + L.samp_hist);
     p.cand_cnt = (uint32_t*)(ws + L.cand_cnt);
     p.tg = (uint32_t*)(ws + L.tg);
     p.te = (uint32_t*)(ws + L.te);
@@ -1138,7 +1309,7 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
         total_out = p.flat_k[commit];
         if (total_out > out_capacity) return GRAVAC_ERR_CAPACITY;
     } else {
-        // layerwise tables, built on the host and copied into the workspace in one piece
+        // layerwise tables, built on the host and copied into the workspace
         std::vector<int64_t> koff(ns + 1);
         std::vector<uint32_t> tile_prefix(ns + 1), samp_prefix(ns + 1), samp_cnt(ns), ktab((size_t)ns * n_cf);
         uint64_t tiles = 0, sblocks = 0;
@@ -1176,11 +1347,8 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
         if (hipStreamSynchronize(stream) != hipSuccess) return GRAVAC_ERR_HIP;
     }
 
-    const int cus = device_cus();
-    const uint32_t tile_wgs = (p.n_tiles + WAVES - 1) / WAVES;
-    const uint32_t stream_grid = tile_wgs < (uint32_t)cus * 8 ? tile_wgs : (uint32_t)cus * 8;
-    const uint32_t light_grid = tile_wgs < (uint32_t)cus * 4 ? tile_wgs : (uint32_t)cus * 4;
-    const dim3 per_cf(ns, n_cf);
+    const uint32_t tile_grid = (p.n_tiles + WAVES - 1) / WAVES;
+    const uint32_t cf_grid = ((uint32_t)(ns * n_cf) + WAVES - 1) / WAVES;
 
     const bool prof = (flags & GRAVAC_FLAG_PROFILE) != 0;
     if (prof) {
@@ -1192,23 +1360,22 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
         }
         (void)hipEventRecord(g_ev[0], stream);
     }
-    hipLaunchKernelGGL(sample_kernel, dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
+    if (p.n_sample_blocks)  // tensors of at most LCAP elements are not sampled
+        hipLaunchKernelGGL(sample_kernel, dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
     hipLaunchKernelGGL(threshold_kernel, dim3(ns), dim3(1024), 0, stream, p);
     if (prof) (void)hipEventRecord(g_ev[1], stream);
-    hipLaunchKernelGGL(stream_kernel<true>, dim3(stream_grid), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(stream_kernel<true>, dim3(tile_grid), dim3(WG), 0, stream, p);
     if (prof) (void)hipEventRecord(g_ev[2], stream);
-    hipLaunchKernelGGL(locate_kernel, per_cf, dim3(256), 0, stream, p, 0);
-    // exact route, taken only by segments whose sampled bound failed
-    hipLaunchKernelGGL(coarse_kernel, dim3(stream_grid), dim3(WG), 0, stream, p);
-    hipLaunchKernelGGL(locate_coarse_kernel, per_cf, dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(stream_kernel<false>, dim3(stream_grid), dim3(WG), 0, stream, p);
-    hipLaunchKernelGGL(locate_kernel, per_cf, dim3(256), 0, stream, p, 1);
-    // exact resolution on the candidates
-    hipLaunchKernelGGL(refine_kernel, dim3(light_grid), dim3(WG), 0, stream, p);
-    hipLaunchKernelGGL(resolve_kernel, per_cf, dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(tile_count_kernel, dim3(light_grid), dim3(WG), 0, stream, p);
-    hipLaunchKernelGGL(scan_kernel, dim3(ns, 1 + n_cf), dim3(ns == 1 ? 1024 : 256), 0, stream, p);
-    hipLaunchKernelGGL(emit_kernel, dim3(light_grid), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(locate_kernel, dim3(cf_grid), dim3(WG), 0, stream, p);
+    // exact route, taken only by segments whose sampled bound failed (the kernels return at once otherwise)
+    hipLaunchKernelGGL(coarse_kernel, dim3(tile_grid), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(stream_kernel<false>, dim3(tile_grid), dim3(WG), 0, stream, p);
+    // exact resolution on the candidates, then count and emit
+    hipLaunchKernelGGL(refine_kernel, dim3(tile_grid), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(resolve_kernel, dim3(ns * n_cf), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(count_kernel, dim3(tile_grid), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(scan_kernel, dim3(ns + ns * n_cf), dim3(SCAN_T), 0, stream, p);
+    hipLaunchKernelGGL(emit_kernel, dim3(tile_grid), dim3(WG), 0, stream, p);
     if (prof) {
         (void)hipEventRecord(g_ev[3], stream);
         g_ev_recorded = true;

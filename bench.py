@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="1/16-size workload (for a quick functional check)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run 10 plain device copies of the gradient's size (known traffic: 4N read + 4N "
+                         "written per copy) so that profiler byte counters can be scaled, then exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build measures the one-GPU share of the path only (no collectives, no sharding); "
@@ -70,6 +73,14 @@ def main():
         n_conv, n_fc = n_conv // 16, n_fc // 16
     n = n_conv + n_fc
     cf = 1000.0
+    if args.copy_calibration:
+        a = torch.zeros(n, dtype=torch.float32, device=dev)
+        b = torch.ones(n, dtype=torch.float32, device=dev)
+        for _ in range(10):
+            a.copy_(b)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": 4 * n, "bytes_written_per_copy": 4 * n}))
+        return
     k = binding.gravac_topk_count(n, cf)
 
     log(f"generating {N_GRADS} gradients of {n} elements and {N_WORKERS - 1} peer messages ...")

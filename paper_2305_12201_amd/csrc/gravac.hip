@@ -27,6 +27,7 @@
 // dispatcher deals round-robin over the eight XCDs) and nothing else uses global atomics.
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cmath>
 #include <cstdint>
@@ -1363,9 +1364,10 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
     if (p.n_sample_blocks)  // tensors of at most LCAP elements are not sampled
         hipLaunchKernelGGL(sample_kernel, dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
     hipLaunchKernelGGL(threshold_kernel, dim3(ns), dim3(1024), 0, stream, p);
-    if (prof) (void)hipEventRecord(g_ev[1], stream);
-    hipLaunchKernelGGL(stream_kernel<true>, dim3(tile_grid), dim3(WG), 0, stream, p);
-    if (prof) (void)hipEventRecord(g_ev[2], stream);
+    if (prof)  // events 1 and 2 take the kernel's own begin and end time stamps
+        hipExtLaunchKernelGGL(stream_kernel<true>, dim3(tile_grid), dim3(WG), 0, stream, g_ev[1], g_ev[2], 0, p);
+    else
+        hipLaunchKernelGGL(stream_kernel<true>, dim3(tile_grid), dim3(WG), 0, stream, p);
     hipLaunchKernelGGL(locate_kernel, dim3(cf_grid), dim3(WG), 0, stream, p);
     // exact route, taken only by segments whose sampled bound failed (the kernels return at once otherwise)
     hipLaunchKernelGGL(coarse_kernel, dim3(tile_grid), dim3(WG), 0, stream, p);

@@ -39,10 +39,29 @@
 
 namespace {
 
-constexpr int TW = 4096;            // elements per wave tile
+#ifndef GV_TW
+#define GV_TW 4096
+#endif
+constexpr int TW = GV_TW;           // elements per tile (unit of the candidate-list kernels)
+#ifndef GV_SUB
+#define GV_SUB 4
+#endif
+constexpr int SUB = GV_SUB;         // sub-tiles per tile: the streaming pass gives one wavefront a sub-tile
+constexpr int TS = TW / SUB;        // elements per sub-tile
 constexpr int WG = 256;             // threads per workgroup of the tile kernels
 constexpr int WAVES = WG / 64;
+#ifndef GV_LWG
+#define GV_LWG 256
+#endif
+constexpr int LWG = GV_LWG;         // threads per workgroup of the candidate-list kernels (refine, count, emit)
+constexpr int LWAVES = LWG / 64;
 constexpr int ROW = 256;            // elements one wavefront touches per load (64 lanes x float4)
+#ifndef GV_ROWS
+#define GV_ROWS 4                   // rows a wavefront keeps in flight
+#endif
+#ifndef GV_NT
+#define GV_NT 1                     // non-temporal hints on the streaming loads and stores
+#endif
 constexpr int REP = 8;              // copies of the candidate histogram and of the gather lists
 constexpr int NBIN = 2048;          // bins of the candidate / refine / coarse histograms
 constexpr uint32_t OVF = NBIN - 1;  // last bin of the candidate histogram: everything above the bracket
@@ -114,20 +133,23 @@ struct Params {
     CfState* st;         // [n_seg][n_cf]
     SegState* seg;       // [n_seg]
     uint32_t* hist1;     // [n_seg][n_cf][REP][NBIN] candidate histogram, REP copies
+    uint32_t* ovfc;      // [n_seg][n_cf][64][32] counts above the bracket (the histogram's last bin), spread over
+                         // 64 cache lines; word 0 of each line is used
     uint32_t* hist2;     // [n_seg][n_cf][NBIN] refine histogram
     uint32_t* coarse;    // [n_seg][NBIN] histogram of key >> 20 (exact route)
     uint32_t* list;      // [n_seg][n_cf][REP][LCAP] gather lists, REP copies
     uint32_t* list_cnt;  // [n_seg][n_cf][REP][32] fill counts of the gather lists, one cache line each
     uint32_t* samp_hist; // [n_sample_blocks][SBIN / 2] sample histograms, two 16-bit counts per word
-    uint32_t* cand_cnt;  // [n_tiles]
+    uint32_t* cand_cnt;  // [n_tiles][SUB] candidates of every sub-tile
     uint32_t* tg;        // [n_tiles] candidates above tau(commit) in this tile
     uint32_t* te;        // [n_tiles] candidates equal to tau(commit) in this tile
     uint32_t* toff;      // [n_tiles] offset of the tile's output inside its segment's message
     uint32_t* ttake;     // [n_tiles] how many of the tile's candidates equal to tau(commit) are selected
-    double* ssd;         // [n_tiles] sum of acc^2
+    double* ssd;         // [n_tiles][SUB] sum of acc^2 of every sub-tile
+    double* ssd_t;       // [n_tiles] sum of acc^2 of the tile
     double* sss;         // [n_tiles][n_cf] sum of acc^2 over keys > tau_j
-    int32_t* cand_idx;   // [n_tiles][TW]
-    float* cand_val;     // [n_tiles][TW]
+    int32_t* cand_idx;   // [n_tiles][SUB][TS] sub-tile j of tile u owns the slots from (u*SUB + j)*TS
+    float* cand_val;     // [n_tiles][SUB][TS]
     // outputs
     int32_t* out_idx;
     float* out_val;
@@ -199,14 +221,42 @@ __device__ __forceinline__ uint32_t hash32(uint32_t x)
     return x;
 }
 
+// The candidates of a tile are the concatenation of its SUB sub-tile lists.
+struct TileCands {
+    uint32_t start[SUB + 1];  // start[j] = candidates in sub-tiles before j; start[SUB] = all
+    __device__ __forceinline__ uint32_t total() const { return start[SUB]; }
+    // slot (relative to the tile's first slot) of the tile's i-th candidate
+    __device__ __forceinline__ uint32_t slot(uint32_t i) const
+    {
+        uint32_t j = 0;
+#pragma unroll
+        for (int x = 1; x < SUB; ++x) j += (i >= start[x]);
+        uint32_t s = 0;
+#pragma unroll
+        for (int x = 1; x < SUB; ++x) if ((uint32_t)x == j) s = start[x];
+        return j * TS + (i - s);
+    }
+};
+
+__device__ __forceinline__ TileCands tile_cands(const Params& p, uint32_t u)
+{
+    TileCands c;
+    c.start[0] = 0;
+#pragma unroll
+    for (int j = 0; j < SUB; ++j) c.start[j + 1] = c.start[j] + p.cand_cnt[(size_t)u * SUB + j];
+    return c;
+}
+
 // One wavefront finds the bin of a 2048-bin histogram (given as `copies` arrays of NBIN counts that
 // are added up) that holds the k-th largest entry: scanning from the top bin down,
 // above < k <= above + count.  Every lane gets the result; bin == NONE if the histogram holds
 // fewer than k entries.  hist must be 16-byte aligned.
-__device__ __forceinline__ void wave_locate_bin(const uint32_t* hist, int copies, uint32_t k, uint32_t& bin,
-                                                uint32_t& above, uint32_t& count)
+__device__ __forceinline__ void wave_locate_bin(const uint32_t* hist, int copies, const uint32_t* top_extra, uint32_t k,
+                                                uint32_t& bin, uint32_t& above, uint32_t& count)
 {
     const int lane = threadIdx.x & 63;
+    // top_extra: 64 more counts for the last bin, one per cache line (stride 32 words), or null
+    uint32_t extra = top_extra ? top_extra[lane * 32] : 0u;
     uint32_t h[32];
 #pragma unroll
     for (int q = 0; q < 32; ++q) h[q] = 0;
@@ -218,6 +268,8 @@ __device__ __forceinline__ void wave_locate_bin(const uint32_t* hist, int copies
             h[4 * q] += v.x; h[4 * q + 1] += v.y; h[4 * q + 2] += v.z; h[4 * q + 3] += v.w;
         }
     }
+    extra = wave_sum(extra);
+    if (lane == 63) h[31] += extra;
     uint32_t mine = 0;
 #pragma unroll
     for (int q = 0; q < 32; ++q) mine += h[q];
@@ -305,6 +357,7 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
 
     for (int i = tid; i < p.n_cf * REP * NBIN; i += 1024) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
     for (int i = tid; i < NBIN; i += 1024) p.coarse[(size_t)t * NBIN + i] = 0;
+    for (int i = tid; i < p.n_cf * 64; i += 1024) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
     for (int i = tid; i < p.n_cf * REP * 32; i += 1024) p.list_cnt[(size_t)t * p.n_cf * REP * 32 + i] = 0;
     if (t == 0 && tid == 0) {
         p.status->any_fail = 0; p.status->n_fail = 0; p.status->error = 0; p.status->n_seg = p.n_seg;
@@ -330,12 +383,12 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
     uint32_t h0 = 0, h1 = 0, h2 = 0, h3 = 0;
     if (!forced) {
         const uint2* src = (const uint2*)(p.samp_hist + (size_t)sb0 * (SBIN / 2)) + tid;
-        for (uint32_t b0 = 0; b0 < nb; b0 += 8) {
-            uint2 w[8];
+        for (uint32_t b0 = 0; b0 < nb; b0 += 32) {
+            uint2 w[32];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) w[q] = (b0 + q < nb) ? src[(size_t)(b0 + q) * (SBIN / 4)] : make_uint2(0u, 0u);
+            for (int q = 0; q < 32; ++q) w[q] = (b0 + q < nb) ? src[(size_t)(b0 + q) * (SBIN / 4)] : make_uint2(0u, 0u);
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
+            for (int q = 0; q < 32; ++q) {
                 h0 += w[q].x & 0xFFFFu; h1 += w[q].x >> 16;
                 h2 += w[q].y & 0xFFFFu; h3 += w[q].y >> 16;
             }
@@ -418,6 +471,24 @@ __device__ __forceinline__ void cand_hist(TileCtx& c, uint32_t key)
     }
 }
 
+__device__ __forceinline__ v4f ld_stream(const v4f* q)
+{
+#if GV_NT
+    return __builtin_nontemporal_load(q);
+#else
+    return *q;
+#endif
+}
+
+__device__ __forceinline__ void st_stream(v4f v, v4f* q)
+{
+#if GV_NT
+    __builtin_nontemporal_store(v, q);
+#else
+    *q = v;
+#endif
+}
+
 // One lane's four consecutive elements a[0..3] at global index g; vm = validity bits.
 template <bool EF>
 __device__ __forceinline__ void consume(TileCtx& c, const float a[4], int64_t g, unsigned vm)
@@ -457,18 +528,21 @@ __device__ __forceinline__ void consume(TileCtx& c, const float a[4], int64_t g,
     }
 }
 
+// One sub-tile v, by one wavefront.
 template <bool EF>
-__global__ __launch_bounds__(WG) void stream_kernel(Params p)
+__device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int lane)
 {
-    const int lane = threadIdx.x & 63;
-    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
+    const uint32_t u = v / SUB;  // tile
     if (u >= p.n_tiles) return;
-    if (!EF && p.status->any_fail == 0) return;
     const int t = tile_seg(p, u);
     if (!EF && p.seg[t].fail == 0) return;
     const int64_t sb = seg_begin(p, t), se = seg_end(p, t);
-    const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW;
-    const int64_t e0 = (s0 + TW < se) ? s0 + TW : se;
+    const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW + (int64_t)(v % SUB) * TS;
+    const int64_t e0 = (s0 + TS < se) ? s0 + TS : se;
+    if (s0 >= se) {  // sub-tile past the end of the segment
+        if (lane == 0) { p.cand_cnt[v] = 0; if (EF) p.ssd[v] = 0.0; }
+        return;
+    }
 
     TileCtx c;
     c.ncf = p.n_cf;
@@ -491,12 +565,12 @@ __global__ __launch_bounds__(WG) void stream_kernel(Params p)
     } else {
         // exact route: lo_j = base of the coarse (key >> 20) bin that holds the k_j-th largest; 1024 bins of
         // 2^10 keys cover that coarse bin, keys above it land in the open last bin
-        const bool first = (u == seg_tile0(p, t));
+        const bool first = (v == seg_tile0(p, t) * SUB);
 #pragma unroll
         for (int j = 0; j < MAXCF; ++j) {
             if (j < p.n_cf) {
                 uint32_t b, ab, cn;
-                wave_locate_bin(p.coarse + (size_t)t * NBIN, 1, seg_k(p, t, j), b, ab, cn);
+                wave_locate_bin(p.coarse + (size_t)t * NBIN, 1, nullptr, seg_k(p, t, j), b, ab, cn);
                 if (b == NONE) { b = 0; if (lane == 0) p.status->error = 1; }
                 c.lo[j] = b << 20;
                 c.sh[j] = 10;
@@ -512,46 +586,46 @@ __global__ __launch_bounds__(WG) void stream_kernel(Params p)
         }
         if (first && lane == 0) p.seg[t].lo_min = c.lo_min;
     }
-    c.h1 = p.hist1 + ((size_t)t * p.n_cf * REP + (blockIdx.x & (REP - 1))) * NBIN;
-    c.cidx = p.cand_idx + (size_t)u * TW;
-    c.cval = p.cand_val + (size_t)u * TW;
+    c.h1 = p.hist1 + ((size_t)t * p.n_cf * REP + (v & (REP - 1))) * NBIN;
+    c.cidx = p.cand_idx + (size_t)v * TS;
+    c.cval = p.cand_val + (size_t)v * TS;
     c.run = 0;
     c.ssd = 0.0;
 
     // rows start at a multiple of 4 elements so that vector accesses are 16-byte aligned
     for (int64_t rb = s0 & ~(int64_t)3; rb < e0; rb += ROW) {
         const bool full = (rb >= s0) && (rb + ROW <= e0);
-        if (full && rb + 4 * ROW <= e0) {
-            // four full rows: all loads first, then the arithmetic
-            v4f gv[4], rv[4];
+        if (full && rb + GV_ROWS * ROW <= e0) {
+            // GV_ROWS full rows: all loads first, then the arithmetic
+            v4f gv[GV_ROWS], rv[GV_ROWS];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < GV_ROWS; ++q) {
                 const int64_t g = rb + q * ROW + 4 * lane;
-                rv[q] = __builtin_nontemporal_load((const v4f*)(p.res + g));
-                if (EF) gv[q] = __builtin_nontemporal_load((const v4f*)(p.grad + g));
+                rv[q] = ld_stream((const v4f*)(p.res + g));
+                if (EF) gv[q] = ld_stream((const v4f*)(p.grad + g));
             }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < GV_ROWS; ++q) {
                 const int64_t g = rb + q * ROW + 4 * lane;
                 float a[4];
                 if (EF) {
                     const v4f av = rv[q] + gv[q];
-                    __builtin_nontemporal_store(av, (v4f*)(p.res + g));
+                    st_stream(av, (v4f*)(p.res + g));
                     a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
                 } else {
                     a[0] = rv[q].x; a[1] = rv[q].y; a[2] = rv[q].z; a[3] = rv[q].w;
                 }
                 consume<EF>(c, a, g, 0xFu);
             }
-            rb += 3 * ROW;
+            rb += (GV_ROWS - 1) * ROW;
         } else if (full) {
             const int64_t g = rb + 4 * lane;
-            const v4f rv = __builtin_nontemporal_load((const v4f*)(p.res + g));
+            const v4f rv = ld_stream((const v4f*)(p.res + g));
             float a[4];
             if (EF) {
-                const v4f gv = __builtin_nontemporal_load((const v4f*)(p.grad + g));
+                const v4f gv = ld_stream((const v4f*)(p.grad + g));
                 const v4f av = rv + gv;
-                __builtin_nontemporal_store(av, (v4f*)(p.res + g));
+                st_stream(av, (v4f*)(p.res + g));
                 a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
             } else {
                 a[0] = rv.x; a[1] = rv.y; a[2] = rv.z; a[3] = rv.w;
@@ -584,14 +658,31 @@ __global__ __launch_bounds__(WG) void stream_kernel(Params p)
     for (int j = 0; j < MAXCF; ++j) {
         if (j < p.n_cf) {
             const uint32_t o = wave_sum(c.ovf[j]);
-            if (lane == 0 && o) atomicAdd(&c.h1[j * REP * NBIN + OVF], o);
+            if (lane == 0 && o) atomicAdd(&p.ovfc[(((size_t)t * p.n_cf + j) * 64 + (v & 63)) * 32], o);
         }
     }
     if (EF) {
         const double s = wave_sum(c.ssd);
-        if (lane == 0) p.ssd[u] = s;
+        if (lane == 0) p.ssd[v] = s;
     }
-    if (lane == 0) p.cand_cnt[u] = c.run;
+    if (lane == 0) p.cand_cnt[v] = c.run;
+}
+
+// EF = true: one sub-tile per wavefront, one launch covers the whole gradient.
+// EF = false: a fixed number of wavefronts walks over all sub-tiles (only those of failed segments do
+// any work), so that the launch costs next to nothing when no segment failed.
+template <bool EF>
+__global__ __launch_bounds__(WG) void stream_kernel(Params p)
+{
+    const int lane = threadIdx.x & 63;
+    const uint32_t w = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
+    if (EF) {
+        stream_subtile<true>(p, w, lane);
+    } else {
+        if (p.status->any_fail == 0) return;
+        const uint32_t nw = gridDim.x * WAVES, nsub = p.n_tiles * SUB;
+        for (uint32_t v = w; v < nsub; v += nw) stream_subtile<false>(p, v, lane);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -611,8 +702,10 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
     const int64_t sb = seg_begin(p, t), se = seg_end(p, t);
     const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW;
     const int64_t e0 = (s0 + TW < se) ? s0 + TW : se;
-    if (u == seg_tile0(p, t))
+    if (u == seg_tile0(p, t)) {
         for (int i = lane; i < p.n_cf * REP * NBIN; i += 64) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
+        for (int i = lane; i < p.n_cf * 64; i += 64) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
+    }
     for (int i = lane; i < NBIN; i += 64) h[i] = 0;
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     for (int64_t q = s0 + lane; q < e0; q += 64) atomicAdd(&h[key_of(p.res[q]) >> 20], 1u);
@@ -667,7 +760,7 @@ __global__ __launch_bounds__(WG) void locate_kernel(Params p)
     const int t = id / p.n_cf;
     CfState* st = &p.st[id];
     uint32_t b, above, c;
-    wave_locate_bin(p.hist1 + (size_t)id * REP * NBIN, REP, st->k, b, above, c);
+    wave_locate_bin(p.hist1 + (size_t)id * REP * NBIN, REP, p.ovfc + (size_t)id * 64 * 32, st->k, b, above, c);
     const BinPlan q = plan_bin(st->lo, st->s, b, above, c);
     if (q.mode == MODE_HIST)
         for (int i = lane; i < NBIN; i += 64) p.hist2[(size_t)id * NBIN + i] = 0;
@@ -685,12 +778,13 @@ __global__ __launch_bounds__(WG) void locate_kernel(Params p)
 // k-th largest.  For a segment that took the exact route the plan is derived here, by every
 // wavefront for itself, from the rebuilt candidate histogram (its first tile's wavefront records it).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(WG) void refine_kernel(Params p)
+__global__ __launch_bounds__(LWG) void refine_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
-    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
+    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * LWAVES + (threadIdx.x >> 6));
     if (u >= p.n_tiles) return;
-    const uint32_t cnt = p.cand_cnt[u];
+    const TileCands tc = tile_cands(p, u);
+    const uint32_t cnt = tc.total();
     const int t = tile_seg(p, u);
     const bool redo = p.status->any_fail != 0 && p.seg[t].fail != 0;
     const bool first = redo && (u == seg_tile0(p, t));
@@ -706,7 +800,8 @@ __global__ __launch_bounds__(WG) void refine_kernel(Params p)
             uint32_t s = st->s;
             if (redo) {
                 uint32_t b, above, c;
-                wave_locate_bin(p.hist1 + ((size_t)t * p.n_cf + j) * REP * NBIN, REP, st->k, b, above, c);
+                wave_locate_bin(p.hist1 + ((size_t)t * p.n_cf + j) * REP * NBIN, REP, p.ovfc + ((size_t)t * p.n_cf + j) * 64 * 32,
+                                st->k, b, above, c);
                 q = plan_bin(st->lo, s, b, above, c);
                 if (first && lane == 0) {
                     store_plan(st, q);
@@ -729,7 +824,7 @@ __global__ __launch_bounds__(WG) void refine_kernel(Params p)
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const uint32_t i = i0 + q * 64 + lane;
-            kq[q] = (i < cnt) ? key_of(cv[i]) : 0u;
+            kq[q] = (i < cnt) ? key_of(cv[tc.slot(i)]) : 0u;
         }
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
@@ -767,7 +862,7 @@ __global__ __launch_bounds__(256) void resolve_kernel(Params p)
     if (mode == MODE_HIST) {
         if (wib != 0) return;
         uint32_t b, ab, cn;  // bins are single keys: base + b
-        wave_locate_bin(p.hist2 + (size_t)id * NBIN, 1, want, b, ab, cn);
+        wave_locate_bin(p.hist2 + (size_t)id * NBIN, 1, nullptr, want, b, ab, cn);
         if (lane == 0) {
             if (b == NONE) { p.status->error = 1; b = 0; }
             st->tau = base + b;
@@ -834,12 +929,17 @@ __global__ __launch_bounds__(256) void resolve_kernel(Params p)
 // K3: one wavefront per tile: candidates above / at the committed threshold, energy above each
 // CF's threshold.  Written for every tile, so that the scan needs no second look at cand_cnt.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(WG) void count_kernel(Params p)
+__global__ __launch_bounds__(LWG) void count_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
-    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
+    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * LWAVES + (threadIdx.x >> 6));
     if (u >= p.n_tiles) return;
-    const uint32_t cnt = p.cand_cnt[u];
+    const TileCands tcs = tile_cands(p, u);
+    const uint32_t cnt = tcs.total();
+    {   // energy of the tile = sum over its sub-tiles, in a fixed order
+        const double x = wave_sum(lane < SUB ? p.ssd[(size_t)u * SUB + lane] : 0.0);
+        if (lane == 0) p.ssd_t[u] = x;
+    }
     if (cnt == 0) {
         if (lane == 0) { p.tg[u] = 0; p.te[u] = 0; }
         if (lane < p.n_cf) p.sss[(size_t)u * p.n_cf + lane] = 0.0;
@@ -863,7 +963,7 @@ __global__ __launch_bounds__(WG) void count_kernel(Params p)
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const uint32_t i = i0 + q * 64 + lane;
-            vq[q] = (i < cnt) ? cv[i] : 0.0f;
+            vq[q] = (i < cnt) ? cv[tcs.slot(i)] : 0.0f;
         }
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
@@ -890,103 +990,105 @@ __global__ __launch_bounds__(WG) void count_kernel(Params p)
 }
 
 // ---------------------------------------------------------------------------------------------
-// SCAN: blocks [0, n_seg): exclusive scan of one segment's tile counts -> every tile's output
-//       offset and tie quota.  Blocks [n_seg, n_seg + n_seg*n_cf): statistics of one (segment, CF),
-//       summed over the tiles in a fixed order.  Every thread issues its loads in batches so
-//       that the kernel is a few memory round trips long, whatever the tile count.
+// SCAN: grid (n_seg, slices + n_cf).  Block (t, y < slices): exclusive scan of the counts of the
+//       y-th slice of SCAN_SLICE tiles of segment t -> every tile's output offset and tie quota.
+//       The totals of the earlier slices are re-added by every block (a few batched loads), so no
+//       block waits on another.  Block (t, slices + j): statistics of (segment t, CF j), summed
+//       over the tiles in a fixed order.
 // ---------------------------------------------------------------------------------------------
 constexpr int SCAN_T = 1024;                 // threads
-constexpr int SCAN_PER = 4;                  // tiles per thread and sweep
-constexpr int SCAN_SWEEP = SCAN_T * SCAN_PER;
+constexpr int SCAN_PER = 4;                  // tiles per thread
+constexpr int SCAN_SLICE = SCAN_T * SCAN_PER;
 
-__global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p)
+__global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
 {
-    __shared__ uint32_t sg[SCAN_SWEEP], se[SCAN_SWEEP];
-    __shared__ uint32_t wt[2][16];
+    __shared__ uint32_t sg[SCAN_SLICE], se[SCAN_SLICE];
+    __shared__ uint32_t wt[4][16];
     __shared__ double dred[2][SCAN_T];
     const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
-    if (blockIdx.x < (uint32_t)p.n_seg) {
-        const int t = blockIdx.x;
+    const int t = blockIdx.x;
+    if (blockIdx.y < slices) {
         const uint32_t u0 = seg_tile0(p, t), u1 = seg_tile1(p, t);
+        const uint32_t base = u0 + blockIdx.y * SCAN_SLICE;
+        if (base >= u1) return;
         const uint32_t need = p.st[(size_t)t * p.n_cf + p.commit].need;
-        uint32_t carry_g = 0, carry_e = 0;
-        // coalesced loads of the next sweep are in flight while the current one is scanned
-        uint32_t ng[SCAN_PER], ne[SCAN_PER];
+        // this slice, coalesced
+        uint32_t og[SCAN_PER], oe[SCAN_PER];
 #pragma unroll
         for (int q = 0; q < SCAN_PER; ++q) {
-            const uint32_t u = u0 + q * SCAN_T + tid;
-            ng[q] = (u < u1) ? p.tg[u] : 0u;
-            ne[q] = (u < u1) ? p.te[u] : 0u;
+            const uint32_t u = base + q * SCAN_T + tid;
+            og[q] = (u < u1) ? p.tg[u] : 0u;
+            oe[q] = (u < u1) ? p.te[u] : 0u;
         }
-        for (uint32_t base = u0; base < u1; base += SCAN_SWEEP) {
+        // totals of the earlier slices of this segment
+        uint32_t pg = 0, pe = 0;
+        for (uint32_t v0 = u0 + tid; v0 < base; v0 += 32 * SCAN_T) {
+            uint32_t xg[32], xe[32];
 #pragma unroll
-            for (int q = 0; q < SCAN_PER; ++q) { sg[q * SCAN_T + tid] = ng[q]; se[q * SCAN_T + tid] = ne[q]; }
-#pragma unroll
-            for (int q = 0; q < SCAN_PER; ++q) {
-                const uint32_t u = base + SCAN_SWEEP + q * SCAN_T + tid;
-                ng[q] = (u < u1) ? p.tg[u] : 0u;
-                ne[q] = (u < u1) ? p.te[u] : 0u;
+            for (int q = 0; q < 32; ++q) {
+                const uint32_t v = v0 + q * SCAN_T;
+                xg[q] = (v < base) ? p.tg[v] : 0u;
+                xe[q] = (v < base) ? p.te[v] : 0u;
             }
-            __syncthreads();
-            // this thread's SCAN_PER consecutive tiles
-            uint32_t g[SCAN_PER], e[SCAN_PER], sum_g = 0, sum_e = 0;
 #pragma unroll
-            for (int i = 0; i < SCAN_PER; ++i) {
-                g[i] = sg[tid * SCAN_PER + i]; e[i] = se[tid * SCAN_PER + i];
-                sum_g += g[i]; sum_e += e[i];
-            }
-            const uint32_t ig = wave_scan(sum_g), ie = wave_scan(sum_e);
-            if (lane == 63) { wt[0][wib] = ig; wt[1][wib] = ie; }
-            __syncthreads();
-            uint32_t bg = 0, be = 0, tg = 0, te = 0;
+            for (int q = 0; q < 32; ++q) { pg += xg[q]; pe += xe[q]; }
+        }
+        pg = wave_sum(pg);
+        pe = wave_sum(pe);
 #pragma unroll
-            for (int w = 0; w < 16; ++w) {
-                const uint32_t xg = wt[0][w], xe = wt[1][w];
-                tg += xg; te += xe;
-                if (w < wib) { bg += xg; be += xe; }
-            }
-            uint32_t run_g = carry_g + bg + ig - sum_g;   // candidates above the threshold before this thread's tiles
-            uint32_t run_e = carry_e + be + ie - sum_e;   // candidates at the threshold before this thread's tiles
+        for (int q = 0; q < SCAN_PER; ++q) { sg[q * SCAN_T + tid] = og[q]; se[q * SCAN_T + tid] = oe[q]; }
+        if (lane == 0) { wt[2][wib] = pg; wt[3][wib] = pe; }
+        __syncthreads();
+        // this thread's SCAN_PER consecutive tiles
+        uint32_t g[SCAN_PER], e[SCAN_PER], sum_g = 0, sum_e = 0;
 #pragma unroll
-            for (int i = 0; i < SCAN_PER; ++i) {
-                const uint32_t ties_before = run_e < need ? run_e : need;  // ties selected in earlier tiles
-                const uint32_t left = need - ties_before;
-                sg[tid * SCAN_PER + i] = run_g + ties_before;               // output offset of the tile
-                se[tid * SCAN_PER + i] = left < e[i] ? left : e[i];         // its tie quota
-                run_g += g[i];
-                run_e += e[i];
-            }
-            carry_g += tg;
-            carry_e += te;
-            __syncthreads();
+        for (int i = 0; i < SCAN_PER; ++i) {
+            g[i] = sg[tid * SCAN_PER + i]; e[i] = se[tid * SCAN_PER + i];
+            sum_g += g[i]; sum_e += e[i];
+        }
+        const uint32_t ig = wave_scan(sum_g), ie = wave_scan(sum_e);
+        if (lane == 63) { wt[0][wib] = ig; wt[1][wib] = ie; }
+        __syncthreads();
+        uint32_t run_g = ig - sum_g, run_e = ie - sum_e;   // counts before this thread's tiles
 #pragma unroll
-            for (int q = 0; q < SCAN_PER; ++q) {
-                const uint32_t u = base + q * SCAN_T + tid;
-                if (u < u1) { p.toff[u] = sg[q * SCAN_T + tid]; p.ttake[u] = se[q * SCAN_T + tid]; }
-            }
-            __syncthreads();
+        for (int w = 0; w < 16; ++w) {
+            if (w < wib) { run_g += wt[0][w]; run_e += wt[1][w]; }
+            run_g += wt[2][w];
+            run_e += wt[3][w];
+        }
+#pragma unroll
+        for (int i = 0; i < SCAN_PER; ++i) {
+            const uint32_t ties_before = run_e < need ? run_e : need;  // ties selected in earlier tiles
+            const uint32_t left = need - ties_before;
+            sg[tid * SCAN_PER + i] = run_g + ties_before;               // output offset of the tile
+            se[tid * SCAN_PER + i] = left < e[i] ? left : e[i];         // its tie quota
+            run_g += g[i];
+            run_e += e[i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < SCAN_PER; ++q) {
+            const uint32_t u = base + q * SCAN_T + tid;
+            if (u < u1) { p.toff[u] = sg[q * SCAN_T + tid]; p.ttake[u] = se[q * SCAN_T + tid]; }
         }
         return;
     }
-    const uint32_t id = blockIdx.x - p.n_seg;
-    const int t = id / p.n_cf, j = id % p.n_cf;
+    const int j = blockIdx.y - slices;
+    const uint32_t id = (uint32_t)t * p.n_cf + j;
     const uint32_t ua = seg_tile0(p, t), ub = seg_tile1(p, t);
-    double pd[16], pj[16];
-#pragma unroll
-    for (int q = 0; q < 16; ++q) { pd[q] = 0.0; pj[q] = 0.0; }
+    // sixteen tiles per thread and round, all loads of a round in flight together; fixed summation order
+    double sd = 0.0, sj = 0.0;
     for (uint32_t u0 = ua + tid; u0 < ub; u0 += 16 * SCAN_T) {
+        double xd[16], xj[16];
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             const uint32_t u = u0 + q * SCAN_T;
-            if (u < ub) {
-                pd[q] += p.ssd[u];
-                pj[q] += p.sss[(size_t)u * p.n_cf + j];
-            }
+            xd[q] = (u < ub) ? p.ssd_t[u] : 0.0;
+            xj[q] = (u < ub) ? p.sss[(size_t)u * p.n_cf + j] : 0.0;
         }
-    }
-    double sd = 0.0, sj = 0.0;
 #pragma unroll
-    for (int q = 0; q < 16; ++q) { sd += pd[q]; sj += pj[q]; }
+        for (int q = 0; q < 16; ++q) { sd += xd[q]; sj += xj[q]; }
+    }
     dred[0][tid] = sd; dred[1][tid] = sj;
     __syncthreads();
     for (int o = SCAN_T >> 1; o > 0; o >>= 1) {
@@ -1011,12 +1113,13 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p)
 // K4: one wavefront per tile emits the tile's share of the committed selection in ascending index
 //     order and zeroes its residual slots
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(WG) void emit_kernel(Params p)
+__global__ __launch_bounds__(LWG) void emit_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
-    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
+    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * LWAVES + (threadIdx.x >> 6));
     if (u >= p.n_tiles) return;
-    const uint32_t cnt = p.cand_cnt[u];
+    const TileCands tcs = tile_cands(p, u);
+    const uint32_t cnt = tcs.total();
     if (cnt == 0) return;
     const uint32_t take = p.ttake[u];
     if (p.tg[u] == 0 && take == 0) return;
@@ -1034,8 +1137,9 @@ __global__ __launch_bounds__(WG) void emit_kernel(Params p)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const uint32_t q = b0 + r * 64 + lane;
-            vq[r] = (q < cnt) ? cv[q] : 0.0f;
-            iq[r] = (q < cnt) ? ci[q] : 0;
+            const uint32_t sl = (q < cnt) ? tcs.slot(q) : 0u;
+            vq[r] = (q < cnt) ? cv[sl] : 0.0f;
+            iq[r] = (q < cnt) ? ci[sl] : 0;
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -1062,64 +1166,146 @@ __global__ __launch_bounds__(WG) void emit_kernel(Params p)
 }
 
 // ---------------------------------------------------------------------------------------------
-// decompression: dense_out[idx] += val, workers in order, one workgroup per tile of dense_out
+// decompression: dense_out[idx] += val, workers in order.  A workgroup owns one tile of DTILE floats
+// of dense_out at a time (tiles are dealt round-robin over a fixed number of workgroups).  A tile
+// that lies outside every message's index range is skipped without touching memory.  Otherwise the
+// tile's range in every worker's index-sorted message is found by a 32-way search (32 threads per
+// worker, both ends at once, 8 workers at a time); if any message touches the tile it is loaded
+// into LDS, the pairs are applied worker by worker (indices within one worker are unique, so plain
+// LDS adds suffice) and it is written back.
 // ---------------------------------------------------------------------------------------------
-constexpr int DTILE = 8192;  // floats of dense_out per workgroup (32 KiB of LDS)
+constexpr int DTILE = 8192;  // floats of dense_out per tile (32 KiB of LDS)
 constexpr int DMAXW = 64;    // workers per launch
+constexpr int DGROUP = 8;    // workers searched at a time
+constexpr int DBATCH = 4;    // pairs per thread and batch
 
 struct WorkerOffsets {
     int64_t at[DMAXW + 1];
 };
 
-__device__ __forceinline__ int64_t lower_bound_i32(const int32_t* a, int64_t lo, int64_t hi, int64_t x)
+// Both first positions l, h in [a, b) of the ascending array idx with idx[l] >= x0 and idx[h] >= x1
+// (x0 <= x1; b if none).  Run by the 32 lanes of one half of a wavefront together; `half` = 0 or 1
+// says which half, j = lane within the half.  Each round probes both brackets at once.
+__device__ __forceinline__ void lower_bounds_32(const int32_t* idx, int64_t a, int64_t b, int64_t x0, int64_t x1, int half,
+                                                int j, int64_t& l, int64_t& h)
 {
-    while (lo < hi) {
-        const int64_t mid = lo + ((hi - lo) >> 1);
-        if ((int64_t)a[mid] < x) lo = mid + 1; else hi = mid;
+    int64_t a0 = a, b0 = b, a1 = a, b1 = b;
+    bool done0 = false, done1 = false;
+    while (!(done0 && done1)) {
+        const int64_t n0 = b0 - a0, n1 = b1 - a1;
+        const int64_t st0 = n0 > 32 ? (n0 + 31) / 32 : 1, st1 = n1 > 32 ? (n1 + 31) / 32 : 1;
+        const int64_t p0 = a0 + (int64_t)j * st0, p1 = a1 + (int64_t)j * st1;
+        const bool q0 = !done0 && p0 < b0, q1 = !done1 && p1 < b1;
+        const int32_t v0 = q0 ? idx[p0] : 0, v1 = q1 ? idx[p1] : 0;
+        const uint32_t c0 = (uint32_t)__popc((uint32_t)(__ballot(q0 && (int64_t)v0 < x0) >> (32 * half)));
+        const uint32_t c1 = (uint32_t)__popc((uint32_t)(__ballot(q1 && (int64_t)v1 < x1) >> (32 * half)));
+        if (!done0) {
+            if (n0 <= 32) { a0 += c0; done0 = true; }            // every position was probed
+            else if (c0 == 0) { done0 = true; }                  // idx[a0] >= x0
+            else { const int64_t e = a0 + (int64_t)c0 * st0; a0 += (int64_t)(c0 - 1) * st0 + 1; b0 = e < b0 ? e : b0; }
+        }
+        if (!done1) {
+            if (n1 <= 32) { a1 += c1; done1 = true; }
+            else if (c1 == 0) { done1 = true; }
+            else { const int64_t e = a1 + (int64_t)c1 * st1; a1 += (int64_t)(c1 - 1) * st1 + 1; b1 = e < b1 ? e : b1; }
+        }
     }
-    return lo;
+    l = a0;
+    h = a1;
 }
 
 __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restrict__ idx, const float* __restrict__ val,
                                                          WorkerOffsets wo, int W, int64_t n, float* dense)
 {
     __shared__ float acc[DTILE];
-    __shared__ int64_t lo[DMAXW], hi[DMAXW];
-    __shared__ int any;
+    __shared__ int64_t lo[DGROUP], hi[DGROUP];
+    __shared__ uint32_t pre[DGROUP + 1];
+    __shared__ int32_t first[DMAXW], last[DMAXW];   // smallest and largest index of every worker's message
     const int tid = threadIdx.x;
     const bool vec = (((uintptr_t)dense) & 15) == 0;  // float4 access needs a 16-byte aligned buffer
+    if (tid < W) {
+        const int64_t a = wo.at[tid], b = wo.at[tid + 1];
+        first[tid] = (b > a) ? idx[a] : 0x7FFFFFFF;
+        last[tid] = (b > a) ? idx[b - 1] : -1;
+    }
+    __syncthreads();
     const int64_t ntile = (n + DTILE - 1) / DTILE;
     for (int64_t tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
         const int64_t base = tile * DTILE;
         const int len = (int)((n - base < DTILE) ? n - base : DTILE);
-        if (tid == 0) any = 0;
-        __syncthreads();
-        if (tid < 2 * W) {
-            const int w = tid >> 1;
-            const int64_t x = (tid & 1) ? base + len : base;
-            const int64_t r = lower_bound_i32(idx, wo.at[w], wo.at[w + 1], x);
-            if (tid & 1) hi[w] = r; else lo[w] = r;
-        }
-        __syncthreads();
-        if (tid < W && hi[tid] > lo[tid]) any = 1;
-        __syncthreads();
-        if (any) {
-            for (int i = tid * 4; i < len; i += 256 * 4) {
-                if (vec && i + 4 <= len) {
-                    const v4f v = *(const v4f*)(dense + base + i);
-                    acc[i] = v.x; acc[i + 1] = v.y; acc[i + 2] = v.z; acc[i + 3] = v.w;
-                } else {
-                    for (int e = 0; e < 4 && i + e < len; ++e) acc[i + e] = dense[base + i + e];
-                }
+        bool loaded = false;
+        for (int w0 = 0; w0 < W; w0 += DGROUP) {
+            const int wn = (W - w0 < DGROUP) ? W - w0 : DGROUP;
+            // can any message of this group touch the tile at all?
+            bool maybe = false;
+            for (int w = 0; w < wn; ++w)
+                maybe |= ((int64_t)first[w0 + w] < base + len) && ((int64_t)last[w0 + w] >= base);
+            if (!maybe) continue;
+            __syncthreads();  // lo / hi / pre of the previous group or tile are no longer read
+            {
+                const int w = tid >> 5, j = tid & 31, half = (tid >> 5) & 1;
+                // 32 threads per worker; absent workers search an empty range
+                const int64_t a = (w < wn) ? wo.at[w0 + w] : 0, b = (w < wn) ? wo.at[w0 + w + 1] : 0;
+                int64_t l, h;
+                lower_bounds_32(idx, a, b, base, base + len, half, j, l, h);
+                if (j == 0 && w < wn) { lo[w] = l; hi[w] = h; }
             }
             __syncthreads();
-            for (int w = 0; w < W; ++w) {
-                for (int64_t q = lo[w] + tid; q < hi[w]; q += 256) {
-                    const int64_t j = (int64_t)idx[q] - base;
-                    if (j >= 0 && j < len) acc[j] += val[q];
+            if (tid == 0) {
+                uint32_t s = 0;
+                for (int w = 0; w < DGROUP; ++w) {
+                    pre[w] = s;
+                    if (w < wn) s += (uint32_t)(hi[w] - lo[w]);
                 }
-                __syncthreads();
+                pre[DGROUP] = s;
             }
+            __syncthreads();
+            const uint32_t total = pre[DGROUP];
+            if (total == 0) continue;  // no message of this group touches the tile
+            if (!loaded) {
+                for (int i = tid * 4; i < len; i += 256 * 4) {
+                    if (vec && i + 4 <= len) {
+                        const v4f v = *(const v4f*)(dense + base + i);
+                        acc[i] = v.x; acc[i + 1] = v.y; acc[i + 2] = v.z; acc[i + 3] = v.w;
+                    } else {
+                        for (int e = 0; e < 4 && i + e < len; ++e) acc[i + e] = dense[base + i + e];
+                    }
+                }
+                loaded = true;
+            }
+            // the group's pairs, worker-major, DBATCH per thread and batch; all loads of a batch in flight together
+            for (uint32_t s0 = 0; s0 < total; s0 += 256 * DBATCH) {
+                int pj[DBATCH], pw[DBATCH];
+                float pv[DBATCH];
+#pragma unroll
+                for (int q = 0; q < DBATCH; ++q) {
+                    const uint32_t slot = s0 + q * 256 + tid;
+                    pw[q] = -1; pj[q] = 0; pv[q] = 0.0f;
+                    if (slot < total) {
+                        int w = 0;
+#pragma unroll
+                        for (int x = 1; x < DGROUP; ++x) w += (slot >= pre[x]);
+                        const int64_t at = lo[w] + (int64_t)(slot - pre[w]);
+                        const int64_t j = (int64_t)idx[at] - base;
+                        if (j >= 0 && j < len) { pw[q] = w; pj[q] = (int)j; pv[q] = val[at]; }
+                    }
+                }
+                // workers present in this batch: from the worker of its first slot to that of its last
+                const uint32_t end = (s0 + 256 * DBATCH < total ? s0 + 256 * DBATCH : total) - 1;
+                int wmin = 0, wmax = 0;
+#pragma unroll
+                for (int x = 1; x < DGROUP; ++x) { wmin += (s0 >= pre[x]); wmax += (end >= pre[x]); }
+                __syncthreads();  // tile loaded / previous batch applied
+                for (int w = wmin; w <= wmax; ++w) {
+#pragma unroll
+                    for (int q = 0; q < DBATCH; ++q)
+                        if (pw[q] == w) acc[pj[q]] += pv[q];
+                    __syncthreads();
+                }
+            }
+        }
+        if (loaded) {
+            __syncthreads();
             for (int i = tid * 4; i < len; i += 256 * 4) {
                 if (vec && i + 4 <= len) {
                     v4f v;
@@ -1129,8 +1315,8 @@ __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restri
                     for (int e = 0; e < 4 && i + e < len; ++e) dense[base + i + e] = acc[i + e];
                 }
             }
+            __syncthreads();  // the tile buffer is free again
         }
-        __syncthreads();
     }
 }
 
@@ -1141,8 +1327,8 @@ __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restri
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-    size_t status, seg_off, koff, tile_prefix, samp_prefix, samp_cnt, ktab, st, seg, hist1, hist2, coarse, list, list_cnt,
-        samp_hist, cand_cnt, tg, te, toff, ttake, ssd, sss, cand_idx, cand_val, total;
+    size_t status, seg_off, koff, tile_prefix, samp_prefix, samp_cnt, ktab, st, seg, hist1, ovfc, hist2, coarse, list, list_cnt,
+        samp_hist, cand_cnt, tg, te, toff, ttake, ssd, ssd_t, sss, cand_idx, cand_val, total;
 };
 
 // Upper bounds that depend only on (n, n_seg).
@@ -1172,17 +1358,19 @@ Layout make_layout(int64_t n, int n_cf, int n_seg)
     L.st = take(sizeof(CfState) * sc);
     L.seg = take(sizeof(SegState) * n_seg);
     L.hist1 = take(sizeof(uint32_t) * sc * REP * NBIN);
+    L.ovfc = take(sizeof(uint32_t) * sc * 64 * 32);
     L.hist2 = take(sizeof(uint32_t) * sc * NBIN);
     L.coarse = take(sizeof(uint32_t) * (size_t)n_seg * NBIN);
     L.list = take(sizeof(uint32_t) * sc * REP * LCAP);
     L.list_cnt = take(sizeof(uint32_t) * sc * REP * 32);
     L.samp_hist = take(sizeof(uint32_t) * nsb * (SBIN / 2));
-    L.cand_cnt = take(sizeof(uint32_t) * nt);
+    L.cand_cnt = take(sizeof(uint32_t) * nt * SUB);
     L.tg = take(sizeof(uint32_t) * nt);
     L.te = take(sizeof(uint32_t) * nt);
     L.toff = take(sizeof(uint32_t) * nt);
     L.ttake = take(sizeof(uint32_t) * nt);
-    L.ssd = take(sizeof(double) * nt);
+    L.ssd = take(sizeof(double) * nt * SUB);
+    L.ssd_t = take(sizeof(double) * nt);
     L.sss = take(sizeof(double) * nt * n_cf);
     L.cand_idx = take(sizeof(int32_t) * nt * TW);
     L.cand_val = take(sizeof(float) * nt * TW);
@@ -1199,19 +1387,6 @@ uint32_t sample_count(uint64_t nt, double cf_max, bool flat)
     target = (target + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK * SAMPLE_BLOCK;
     if (nt <= (uint64_t)LCAP) return 0;  // every element becomes a candidate; the gather list resolves it
     return (nt <= 2 * target) ? (uint32_t)nt : (uint32_t)target;
-}
-
-int device_cus()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cus = prop.multiProcessorCount;
-        if (cus <= 0) cus = 256;
-    }
-    return cus;
 }
 
 std::mutex g_prof_mutex;
@@ -1285,6 +1460,7 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
     p.st = (CfState*)(ws + L.st);
     p.seg = (SegState*)(ws + L.seg);
     p.hist1 = (uint32_t*)(ws + L.hist1);
+    p.ovfc = (uint32_t*)(ws + L.ovfc);
     p.hist2 = (uint32_t*)(ws + L.hist2);
     p.coarse = (uint32_t*)(ws + L.coarse);
     p.list = (uint32_t*)(ws + L.list);
@@ -1296,16 +1472,19 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
     p.toff = (uint32_t*)(ws + L.toff);
     p.ttake = (uint32_t*)(ws + L.ttake);
     p.ssd = (double*)(ws + L.ssd);
+    p.ssd_t = (double*)(ws + L.ssd_t);
     p.sss = (double*)(ws + L.sss);
     p.cand_idx = (int32_t*)(ws + L.cand_idx);
     p.cand_val = (float*)(ws + L.cand_val);
     p.out_idx = out_idx; p.out_val = out_val; p.out_count = out_count; p.out_stats = out_stats;
 
     int64_t total_out = 0;
+    uint32_t max_seg_tiles = 1;  // tiles of the largest segment
     if (ns == 1) {
         for (int j = 0; j < n_cf; ++j) p.flat_k[j] = (uint32_t)gravac_topk_count(n, cf_list[j]);
         p.flat_samples = sample_count((uint64_t)n, cf_max, true);
         p.n_tiles = (uint32_t)((n + TW - 1) / TW);
+        max_seg_tiles = p.n_tiles;
         p.n_sample_blocks = (p.flat_samples + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
         total_out = p.flat_k[commit];
         if (total_out > out_capacity) return GRAVAC_ERR_CAPACITY;
@@ -1322,7 +1501,9 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
             for (int j = 0; j < n_cf; ++j) ktab[(size_t)t * n_cf + j] = (uint32_t)gravac_topk_count(nt, cf_list[j]);
             total_out += ktab[(size_t)t * n_cf + commit];
             samp_cnt[t] = sample_count((uint64_t)nt, cf_max, false);
-            tiles += (uint64_t)((nt + TW - 1) / TW);
+            const uint64_t tt = (uint64_t)((nt + TW - 1) / TW);
+            tiles += tt;
+            if (tt > max_seg_tiles) max_seg_tiles = (uint32_t)tt;
             sblocks += (samp_cnt[t] + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
         }
         koff[ns] = total_out;
@@ -1349,6 +1530,9 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
     }
 
     const uint32_t tile_grid = (p.n_tiles + WAVES - 1) / WAVES;
+    const uint32_t sub_grid = (p.n_tiles * SUB + WAVES - 1) / WAVES;
+    const uint32_t light_grid = (p.n_tiles + LWAVES - 1) / LWAVES;
+    const uint32_t scan_slices = (max_seg_tiles + SCAN_SLICE - 1) / SCAN_SLICE;
     const uint32_t cf_grid = ((uint32_t)(ns * n_cf) + WAVES - 1) / WAVES;
 
     const bool prof = (flags & GRAVAC_FLAG_PROFILE) != 0;
@@ -1365,19 +1549,19 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
         hipLaunchKernelGGL(sample_kernel, dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
     hipLaunchKernelGGL(threshold_kernel, dim3(ns), dim3(1024), 0, stream, p);
     if (prof)  // events 1 and 2 take the kernel's own begin and end time stamps
-        hipExtLaunchKernelGGL(stream_kernel<true>, dim3(tile_grid), dim3(WG), 0, stream, g_ev[1], g_ev[2], 0, p);
+        hipExtLaunchKernelGGL(stream_kernel<true>, dim3(sub_grid), dim3(WG), 0, stream, g_ev[1], g_ev[2], 0, p);
     else
-        hipLaunchKernelGGL(stream_kernel<true>, dim3(tile_grid), dim3(WG), 0, stream, p);
+        hipLaunchKernelGGL(stream_kernel<true>, dim3(sub_grid), dim3(WG), 0, stream, p);
     hipLaunchKernelGGL(locate_kernel, dim3(cf_grid), dim3(WG), 0, stream, p);
     // exact route, taken only by segments whose sampled bound failed (the kernels return at once otherwise)
     hipLaunchKernelGGL(coarse_kernel, dim3(tile_grid), dim3(WG), 0, stream, p);
-    hipLaunchKernelGGL(stream_kernel<false>, dim3(tile_grid), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(stream_kernel<false>, dim3(sub_grid < 2048 ? sub_grid : 2048), dim3(WG), 0, stream, p);
     // exact resolution on the candidates, then count and emit
-    hipLaunchKernelGGL(refine_kernel, dim3(tile_grid), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(refine_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
     hipLaunchKernelGGL(resolve_kernel, dim3(ns * n_cf), dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(count_kernel, dim3(tile_grid), dim3(WG), 0, stream, p);
-    hipLaunchKernelGGL(scan_kernel, dim3(ns + ns * n_cf), dim3(SCAN_T), 0, stream, p);
-    hipLaunchKernelGGL(emit_kernel, dim3(tile_grid), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(count_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
+    hipLaunchKernelGGL(scan_kernel, dim3(ns, scan_slices + n_cf), dim3(SCAN_T), 0, stream, p, scan_slices);
+    hipLaunchKernelGGL(emit_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
     if (prof) {
         (void)hipEventRecord(g_ev[3], stream);
         g_ev_recorded = true;
@@ -1398,9 +1582,8 @@ int gravac_decompress_accumulate(const int32_t* idx, const float* val, const int
     }
     if (total > 0 && (!idx || !val)) return GRAVAC_ERR_INVALID_ARG;
     if (total == 0) return GRAVAC_OK;
-    const int cus = device_cus();
     const int64_t ntile = (n + DTILE - 1) / DTILE;
-    const uint32_t grid = (uint32_t)(ntile < (int64_t)cus * 16 ? ntile : (int64_t)cus * 16);
+    const uint32_t grid = (uint32_t)(ntile < 1024 ? ntile : 1024);  // 4 workgroups (4 x 32 KiB LDS) on each of 256 CUs
     int64_t at = 0;
     for (int w0 = 0; w0 < W; w0 += DMAXW) {
         const int wn = (W - w0 < DMAXW) ? W - w0 : DMAXW;

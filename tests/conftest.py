@@ -10,6 +10,7 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    config.addinivalue_line("markers", "fullsize: GPU parity at the full benchmark sizes (minutes, not seconds)")
 
 
 def _has_gpu() -> bool:

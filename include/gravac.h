@@ -43,10 +43,16 @@ extern "C" {
 #define GRAVAC_MAX_CF 8             /* candidate CFs per call */
 #define GRAVAC_STATS_PER_CF 4       /* doubles per (segment, CF) in out_stats */
 
-/* flags of gravac_compress (testing and measurement aids; 0 in production) */
+/* flags of gravac_compress (0 = none; the first two are testing and measurement aids) */
 #define GRAVAC_FLAG_FORCE_FALLBACK 1u /* skip the sampled threshold estimate: every segment takes the exact
                                          histogram route (same results, more passes over memory) */
 #define GRAVAC_FLAG_PROFILE 2u        /* record HIP events around the streaming kernel, see gravac_profile_read */
+#define GRAVAC_FLAG_REUSE_THRESHOLDS 4u /* for iterative use: the workspace has not been touched since the previous
+                                         gravac_compress call made with it; if that call had the same n, cf_list and
+                                         segment table, its candidate histogram and thresholds give this call's
+                                         bounds and replace the sampling pass.  Results are the same in every case: a prediction that
+                                         turns out wrong, or a workspace that holds no matching call, sends the
+                                         affected segments through the exact-histogram route (slower, never wrong). */
 
 /*
  * Number of pairs a call will emit for a tensor of n elements at compression factor cf:
@@ -84,7 +90,8 @@ int gravac_workspace_bytes(int64_t n, int n_cf, int n_seg, size_t* bytes_out);
  *               { ||g_c||^2, ||g_ef||^2, gain = ratio (1 if ||g_ef||^2 == 0),
  *                 |acc| of the smallest selected entry }.
  *   workspace   device, 256-byte aligned, at least gravac_workspace_bytes(n, n_cf, n_seg) bytes.
- *               Contents on entry are irrelevant; contents on exit are unspecified.
+ *               Contents on entry are irrelevant (unless GRAVAC_FLAG_REUSE_THRESHOLDS is given); contents on
+ *               exit are unspecified.
  *   flags       0, or GRAVAC_FLAG_* bits.
  */
 int gravac_compress(const float* grad, float* residual, int64_t n,

@@ -23,6 +23,7 @@ ERR_HIP = -4
 MAX_CF = 8
 FLAG_FORCE_FALLBACK = 1
 FLAG_PROFILE = 2
+FLAG_REUSE_THRESHOLDS = 4
 
 EXPORTS = (
     "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_decompress_accumulate",

@@ -103,7 +103,8 @@ struct Status {
     int n_fail;
     int error;
     int n_seg;
-    int pad[4];
+    uint32_t sig_lo, sig_hi;  // signature (shape, CFs, segment table) of the last call that completed on this workspace
+    int pad[2];
 };
 
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -116,6 +117,7 @@ struct Params {
     int n_cf;
     int commit;
     unsigned flags;
+    uint32_t sig_lo, sig_hi;  // signature of this call
     uint32_t n_tiles;
     uint32_t n_sample_blocks;
     // layerwise tables in the workspace (unused when n_seg == 1)
@@ -353,8 +355,30 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
     const uint32_t nb = (S + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
     const uint64_t nt = (uint64_t)(seg_end(p, t) - seg_begin(p, t));
     const bool whole = ((uint64_t)S == nt);
-    const bool forced = (p.flags & GRAVAC_FLAG_FORCE_FALLBACK) != 0;
+    // reuse: take the previous call's thresholds as bounds, if that call had this call's signature;
+    // without a usable prediction (and without samples) every segment takes the exact route
+    const bool want_reuse = (p.flags & GRAVAC_FLAG_REUSE_THRESHOLDS) != 0;
+    const bool reuse = want_reuse && p.status->sig_lo == p.sig_lo && p.status->sig_hi == p.sig_hi;
+    const bool forced = (p.flags & GRAVAC_FLAG_FORCE_FALLBACK) != 0 || (want_reuse && !reuse);
 
+    // reuse: the previous call's candidate histogram says where its count from the top reached about 1.25 k;
+    // that key becomes this call's lower bound (wavefront j looks at CF j, before the histogram is cleared)
+    __shared__ uint32_t pred_lo[MAXCF];
+    if (reuse && wib < p.n_cf) {
+        const CfState* old = &p.st[(size_t)t * p.n_cf + wib];
+        const uint32_t k = seg_k(p, t, wib), lo_prev = old->lo, s_prev = old->s > 31u ? 31u : old->s;
+        uint32_t b, ab, cn;
+        wave_locate_bin(p.hist1 + ((size_t)t * p.n_cf + wib) * REP * NBIN, REP, p.ovfc + ((size_t)t * p.n_cf + wib) * 64 * 32,
+                        k + k / 4 + 64, b, ab, cn);
+        uint32_t lo;
+        if (b == NONE) lo = lo_prev > (1u << 19) ? lo_prev - (1u << 19) : 0u;  // fewer candidates than that: go lower
+        else {
+            const uint64_t x = (uint64_t)lo_prev + ((uint64_t)b << s_prev);
+            lo = x > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)x;
+        }
+        if (lane == 0) pred_lo[wib] = lo;
+    }
+    __syncthreads();
     for (int i = tid; i < p.n_cf * REP * NBIN; i += 1024) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
     for (int i = tid; i < NBIN; i += 1024) p.coarse[(size_t)t * NBIN + i] = 0;
     for (int i = tid; i < p.n_cf * 64; i += 1024) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
@@ -381,7 +405,7 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
 
     // thread i owns bins 4i .. 4i+3: two words of every block's histogram
     uint32_t h0 = 0, h1 = 0, h2 = 0, h3 = 0;
-    if (!forced) {
+    if (!forced && !reuse) {
         const uint2* src = (const uint2*)(p.samp_hist + (size_t)sb0 * (SBIN / 2)) + tid;
         for (uint32_t b0 = 0; b0 < nb; b0 += 32) {
             uint2 w[32];
@@ -423,7 +447,16 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
         uint32_t lo_min = NONE;
         for (int j = 0; j < p.n_cf; ++j) {
             uint32_t lo = bin_lo[j] << 19;                          // lower edge of the bin of the r_lo-th sample
-            const uint64_t hi = ((uint64_t)bin_hi[j] + 1) << 19;    // upper edge of the bin of the r_hi-th sample
+            uint64_t hi = ((uint64_t)bin_hi[j] + 1) << 19;          // upper edge of the bin of the r_hi-th sample
+            if (reuse && nt > (uint64_t)LCAP) {  // tensors of at most LCAP elements keep every element as a candidate
+                // from the key below which the previous call counted about 1.25 k candidates to 2^19 keys (about 4 % in
+                // magnitude) above the previous threshold: tight, for a run in steady state; a threshold that moves
+                // further than that costs one call through the exact route
+                const uint32_t tau_prev = p.st[(size_t)t * p.n_cf + j].tau & 0x7FFFFFFFu;
+                lo = pred_lo[j] < tau_prev ? pred_lo[j] : tau_prev;
+                hi = (uint64_t)tau_prev + (1u << 19);
+
+            }
             uint32_t s = 0;
             while (((hi > lo ? hi - lo : 0) >> s) > (uint64_t)OVF) ++s;
             if (forced) { lo = NONE; s = 0; }
@@ -1105,7 +1138,11 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
         o[1] = ss_dense;
         o[2] = (ss_dense == 0.0) ? 1.0 : ss_sel / ss_dense;
         o[3] = tau;
-        if (id == 0 && p.out_count) *p.out_count = is_flat(p) ? (int64_t)p.flat_k[p.commit] : p.koff[p.n_seg];
+        if (id == 0) {
+            if (p.out_count) *p.out_count = is_flat(p) ? (int64_t)p.flat_k[p.commit] : p.koff[p.n_seg];
+            p.status->sig_lo = p.sig_lo;  // this call's thresholds can serve as the next call's bounds
+            p.status->sig_hi = p.sig_hi;
+        }
     }
 }
 
@@ -1529,6 +1566,15 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
         if (hipStreamSynchronize(stream) != hipSuccess) return GRAVAC_ERR_HIP;
     }
 
+    {   // signature of the call: FNV-1a over the shape, the k table and the segment table
+        uint64_t h = 1469598103934665603ull;
+        auto mix = [&](uint64_t x) { for (int b = 0; b < 8; ++b) { h ^= (x >> (8 * b)) & 0xFF; h *= 1099511628211ull; } };
+        mix((uint64_t)n); mix((uint64_t)n_cf); mix((uint64_t)ns);
+        for (int j = 0; j < n_cf; ++j) { uint64_t bits; std::memcpy(&bits, &cf_list[j], 8); mix(bits); }
+        if (ns > 1) for (int t = 0; t <= ns; ++t) mix((uint64_t)seg_offsets[t]);
+        if (h == 0) h = 1;  // 0 marks "no completed call"
+        p.sig_lo = (uint32_t)h; p.sig_hi = (uint32_t)(h >> 32);
+    }
     const uint32_t tile_grid = (p.n_tiles + WAVES - 1) / WAVES;
     const uint32_t sub_grid = (p.n_tiles * SUB + WAVES - 1) / WAVES;
     const uint32_t light_grid = (p.n_tiles + LWAVES - 1) / LWAVES;
@@ -1545,7 +1591,7 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
         }
         (void)hipEventRecord(g_ev[0], stream);
     }
-    if (p.n_sample_blocks)  // tensors of at most LCAP elements are not sampled
+    if (p.n_sample_blocks && !(flags & GRAVAC_FLAG_REUSE_THRESHOLDS))  // tensors of at most LCAP elements are not sampled
         hipLaunchKernelGGL(sample_kernel, dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
     hipLaunchKernelGGL(threshold_kernel, dim3(ns), dim3(1024), 0, stream, p);
     if (prof)  // events 1 and 2 take the kernel's own begin and end time stamps

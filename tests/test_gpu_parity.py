@@ -14,6 +14,7 @@ from tests.gpu_util import assert_same, check, gpu_compress, oracle_compress
 pytestmark = pytest.mark.gpu
 
 FB = binding.FLAG_FORCE_FALLBACK
+REUSE = binding.FLAG_REUSE_THRESHOLDS
 
 
 def test_library_is_loaded_from_the_tree():
@@ -293,3 +294,77 @@ def test_compress_then_decompress_eight_workers():
     want = np.zeros(n, np.float32)
     oracle.decompress_accumulate(np.concatenate(ref_idx), np.concatenate(ref_val), [k] * 8, want)
     assert np.array_equal(dense.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+# --------------------------------------------------------------------------
+# iterative use: the previous call's thresholds replace the sampling pass
+# --------------------------------------------------------------------------
+
+def _iterate(n, cfs, commit, grads, flags_per_it, seg=None, comp=None, res0=None, carry=True):
+    """Run consecutive calls carrying the residual; compare every call with the oracle; return the statuses."""
+    comp = comp or binding.Compressor(n, cfs, commit, seg)
+    res_gpu = np.zeros(n, np.float32) if res0 is None else res0.copy()
+    res_ref = res_gpu.copy()
+    out = []
+    for it, (g, fl) in enumerate(zip(grads, flags_per_it)):
+        gpu = gpu_compress(g, res_gpu, cfs, commit, seg, flags=fl, comp=comp)
+        ref = oracle_compress(g, res_ref, cfs, commit, seg)
+        assert_same(gpu, ref, f"iteration {it}")
+        assert gpu[4]["internal_error"] == 0
+        out.append(gpu[4])
+        if carry:
+            res_gpu, res_ref = gpu[3], ref[3]
+    return out, comp
+
+
+def test_reuse_thresholds_steady_state():
+    n = 1_200_003
+    grads = [workloads.config3_grad(it, 150_000, n - 150_000) for it in range(5)]
+    # the first calls of an error-feedback run are a transient (the leftover builds up and the threshold climbs):
+    # a prediction may fail there and send the call through the exact route; later calls do not
+    st, _ = _iterate(n, [1000.0], 0, grads, [0] + [REUSE] * 4)
+    assert [s["any_fallback"] for s in st[3:]] == [0, 0]
+    grads = [workloads.config2_grad(it, n) for it in range(4)]
+    # three CFs on the Laplace-with-outliers gradient, residual carried: the thresholds keep moving (one of them sits
+    # among a thousand outliers); whichever route each call takes, the results are the oracle's
+    grads = [workloads.config2_grad(it, n) for it in range(5)]
+    _iterate(n, [10.0, 100.0, 1000.0], 1, grads, [0] + [REUSE] * 4, res0=workloads.config2_residual0(n))
+
+
+def test_reuse_thresholds_without_history_or_with_another_shape():
+    n = 500_001
+    g = [workloads.normal_gradient(n, 1e-3, seed=s) for s in range(3)]
+    # a fresh workspace holds no completed call: the exact route is taken, the result is the same
+    st, comp = _iterate(n, [100.0], 0, g[:1], [REUSE])
+    assert st[0]["any_fallback"] == 1
+    # the same workspace, another CF list: the signature differs, no reuse; then the same list again: reuse works
+    comp2 = binding.Compressor(n, [50.0], 0)
+    comp2.workspace = comp.workspace
+    # (residual not carried here, so that the threshold is the same from call to call)
+    st, _ = _iterate(n, [50.0], 0, g[1:], [REUSE, REUSE], comp=comp2, carry=False)
+    assert [s["any_fallback"] for s in st] == [1, 0]
+
+
+def test_reuse_thresholds_survives_a_scale_jump():
+    n = 800_000
+    grads = [workloads.normal_gradient(n, 1e-3, seed=1), workloads.normal_gradient(n, 1e-3, seed=2),
+             workloads.normal_gradient(n, 2e-2, seed=3),      # twenty times larger: the old threshold is far too low
+             workloads.normal_gradient(n, 2e-2, seed=4),
+             workloads.normal_gradient(n, 1e-4, seed=5)]      # far smaller: fewer than k candidates above the old one
+    st, _ = _iterate(n, [100.0], 0, grads, [0, REUSE, REUSE, REUSE, REUSE], carry=False)
+    assert [s["any_fallback"] for s in st] == [0, 0, 1, 0, 1]
+    # and with the residual carried (the threshold drifts as the leftover builds up): exact whatever route is taken
+    _iterate(n, [100.0], 0, grads, [0, REUSE, REUSE, REUSE, REUSE])
+
+
+def test_reuse_thresholds_layerwise():
+    sizes = [64, 4096, 37, 100_003, 9408, 64, 1000, 40_970, 250_001, 5]
+    off = workloads.offsets_of(sizes)
+    n = int(off[-1])
+    grads = [workloads.normal_gradient(n, 1e-3, seed=80 + it) for it in range(3)]
+    st, _ = _iterate(n, [10.0], 0, grads, [0, REUSE, REUSE], seg=off, carry=False)
+    assert st[1]["any_fallback"] == 0 and st[2]["any_fallback"] == 0
+    # a distribution whose threshold sits in a gap (1 % outliers at CF 100) and a carried residual: the
+    # prediction may fail in some tensors; those take the exact route, the result is the same
+    grads = [workloads.resnet_like_gradient(n, seed=90 + it) for it in range(3)]
+    _iterate(n, [100.0], 0, grads, [0, REUSE, REUSE], seg=off)

@@ -113,11 +113,17 @@ def main():
         compress(grads[i % N_GRADS], residual, 0, flags)
         binding.gravac_decompress_accumulate(msg_idx, msg_val, counts, dense)
 
-    # steady-state iterative use: every call after the first reuses the previous call's thresholds
-    REUSE = 0 if args.no_reuse else binding.FLAG_REUSE_THRESHOLDS
-    step(0)
-    for i in range(1, args.warmup):
-        step(i, REUSE)
+    # steady-state iterative use: a call reuses the previous call's thresholds.  The first calls of an
+    # error-feedback run are a transient (the leftover builds up, the threshold climbs by more than the reuse
+    # band per step); they sample their thresholds instead, whether they fall into the warm-up or not.
+    REUSE_FLAG = 0 if args.no_reuse else binding.FLAG_REUSE_THRESHOLDS
+    TRANSIENT = 12
+
+    def reuse(i):
+        return REUSE_FLAG if i >= TRANSIENT else 0
+
+    for i in range(args.warmup):
+        step(i, reuse(i))
     torch.cuda.synchronize()
     status = binding.gravac_read_status(comp.workspace)
     assert status["internal_error"] == 0, status
@@ -126,7 +132,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i, REUSE)
+        step(args.warmup + i, reuse(args.warmup + i))
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -136,7 +142,7 @@ def main():
     #      streaming kernel and around the whole compress call)
     k_ms, c_ms = [], []
     for i in range(min(args.steps, 50)):
-        step(args.warmup + args.steps + i, binding.FLAG_PROFILE | REUSE)
+        step(args.warmup + args.steps + i, binding.FLAG_PROFILE | reuse(args.warmup + args.steps + i))
         a, b = binding.gravac_profile_read()
         k_ms.append(a)
         c_ms.append(b)

@@ -109,6 +109,17 @@ struct Status {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
+// One tensor of a layerwise call.
+struct SegInfo {
+    int64_t begin, end;      // element range in the flat gradient
+    int64_t koff;            // offset of the segment's message in out_idx / out_val
+    uint32_t tile0, tile1;   // tile range
+    uint32_t samp0;          // first sample block
+    uint32_t samp_cnt;       // samples taken
+    uint32_t pad[6];
+};
+static_assert(sizeof(SegInfo) == 64, "SegInfo layout");
+
 struct Params {
     const float* grad;
     float* res;
@@ -118,15 +129,14 @@ struct Params {
     int commit;
     unsigned flags;
     uint32_t sig_lo, sig_hi;  // signature of this call
+    int64_t total_out;        // pairs the call emits
     uint32_t n_tiles;
     uint32_t n_sample_blocks;
     // layerwise tables in the workspace (unused when n_seg == 1)
-    const int64_t* seg_off;        // [n_seg + 1]
-    const int64_t* koff;           // [n_seg + 1] output offset of each segment's message
-    const uint32_t* tile_prefix;   // [n_seg + 1] first tile of each segment
-    const uint32_t* samp_prefix;   // [n_seg + 1] first sample block of each segment
-    const uint32_t* samp_cnt;      // [n_seg] samples of each segment
-    const uint32_t* ktab;          // [n_seg][n_cf]
+    const SegInfo* segs;           // [n_seg] built on the host
+    const uint32_t* ktab;          // [n_seg][n_cf] built on the host
+    const uint32_t* sblock_seg;    // [n_sample_blocks] segment of every sample block, built on the host
+    uint32_t* tseg;                // [n_tiles] segment of every tile, filled by threshold_kernel
     // the same for one flat tensor
     uint32_t flat_k[MAXCF];
     uint32_t flat_samples;
@@ -164,25 +174,13 @@ struct Params {
 // ---------------------------------------------------------------------------------------------
 
 __device__ __forceinline__ bool is_flat(const Params& p) { return p.n_seg == 1; }
-__device__ __forceinline__ int64_t seg_begin(const Params& p, int t) { return is_flat(p) ? 0 : p.seg_off[t]; }
-__device__ __forceinline__ int64_t seg_end(const Params& p, int t) { return is_flat(p) ? p.n : p.seg_off[t + 1]; }
-__device__ __forceinline__ uint32_t seg_tile0(const Params& p, int t) { return is_flat(p) ? 0u : p.tile_prefix[t]; }
-__device__ __forceinline__ uint32_t seg_tile1(const Params& p, int t) { return is_flat(p) ? p.n_tiles : p.tile_prefix[t + 1]; }
+__device__ __forceinline__ int64_t seg_begin(const Params& p, int t) { return is_flat(p) ? 0 : p.segs[t].begin; }
+__device__ __forceinline__ int64_t seg_end(const Params& p, int t) { return is_flat(p) ? p.n : p.segs[t].end; }
+__device__ __forceinline__ uint32_t seg_tile0(const Params& p, int t) { return is_flat(p) ? 0u : p.segs[t].tile0; }
+__device__ __forceinline__ uint32_t seg_tile1(const Params& p, int t) { return is_flat(p) ? p.n_tiles : p.segs[t].tile1; }
 __device__ __forceinline__ uint32_t seg_k(const Params& p, int t, int j) { return is_flat(p) ? p.flat_k[j] : p.ktab[t * p.n_cf + j]; }
-__device__ __forceinline__ int64_t seg_koff(const Params& p, int t) { return is_flat(p) ? 0 : p.koff[t]; }
-
-// largest t with prefix[t] <= x; prefix ascending with prefix[0] == 0, n entries before the end marker
-__device__ __forceinline__ int find_seg(const uint32_t* prefix, int n, uint32_t x)
-{
-    int lo = 0, hi = n - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (prefix[mid] <= x) lo = mid; else hi = mid - 1;
-    }
-    return lo;
-}
-
-__device__ __forceinline__ int tile_seg(const Params& p, uint32_t u) { return is_flat(p) ? 0 : find_seg(p.tile_prefix, p.n_seg, u); }
+__device__ __forceinline__ int64_t seg_koff(const Params& p, int t) { return is_flat(p) ? 0 : p.segs[t].koff; }
+__device__ __forceinline__ int tile_seg(const Params& p, uint32_t u) { return is_flat(p) ? 0 : (int)p.tseg[u]; }
 
 __device__ __forceinline__ uint32_t key_of(float a) { return __float_as_uint(a) & 0x7FFFFFFFu; }
 
@@ -301,9 +299,9 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
 {
     __shared__ uint32_t h[SBIN];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
-    const int t = is_flat(p) ? 0 : find_seg(p.samp_prefix, p.n_seg, b);
-    const uint32_t lb = b - (is_flat(p) ? 0u : p.samp_prefix[t]);
-    const uint32_t S = is_flat(p) ? p.flat_samples : p.samp_cnt[t];
+    const int t = is_flat(p) ? 0 : (int)p.sblock_seg[b];
+    const uint32_t lb = b - (is_flat(p) ? 0u : p.segs[t].samp0);
+    const uint32_t S = is_flat(p) ? p.flat_samples : p.segs[t].samp_cnt;
     const int64_t s0 = seg_begin(p, t);
     const uint64_t nt = (uint64_t)(seg_end(p, t) - s0);
 #pragma unroll
@@ -350,9 +348,11 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
     __shared__ uint32_t wtot[16];
     __shared__ uint32_t rank_lo[MAXCF], rank_hi[MAXCF], bin_lo[MAXCF], bin_hi[MAXCF];
     const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
-    const uint32_t S = is_flat(p) ? p.flat_samples : p.samp_cnt[t];
-    const uint32_t sb0 = is_flat(p) ? 0u : p.samp_prefix[t];
+    const uint32_t S = is_flat(p) ? p.flat_samples : p.segs[t].samp_cnt;
+    const uint32_t sb0 = is_flat(p) ? 0u : p.segs[t].samp0;
     const uint32_t nb = (S + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
+    if (!is_flat(p))
+        for (uint32_t u = seg_tile0(p, t) + tid; u < seg_tile1(p, t); u += 1024) p.tseg[u] = (uint32_t)t;
     const uint64_t nt = (uint64_t)(seg_end(p, t) - seg_begin(p, t));
     const bool whole = ((uint64_t)S == nt);
     // reuse: take the previous call's thresholds as bounds, if that call had this call's signature;
@@ -865,14 +865,22 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
             const bool live = i0 + q * 64 + lane < cnt;
 #pragma unroll
             for (int j = 0; j < MAXCF; ++j) {
-                if (j < p.n_cf && live && key >= base[j] && key - base[j] <= span[j]) {
-                    if (mode[j] == MODE_GATHER) {
+                if (j >= p.n_cf) continue;
+                const bool in = live && key >= base[j] && key - base[j] <= span[j];
+                if (mode[j] == MODE_GATHER) {
+                    // one counter update per wavefront: the lanes with a key in the bin take consecutive slots
+                    const uint64_t m = __ballot(in);
+                    if (m != 0ull) {
                         const size_t lst = ((size_t)t * p.n_cf + j) * REP + (blockIdx.x & (REP - 1));
-                        const uint32_t pos = atomicAdd(&p.list_cnt[lst * 32], 1u);
-                        if (pos < LCAP) p.list[lst * LCAP + pos] = key;
-                    } else if (mode[j] == MODE_HIST) {
-                        atomicAdd(&p.hist2[((size_t)t * p.n_cf + j) * NBIN + (key - base[j])], 1u);
+                        const int leader = __ffsll((unsigned long long)m) - 1;
+                        uint32_t first = 0;
+                        if (lane == leader) first = atomicAdd(&p.list_cnt[lst * 32], (uint32_t)__popcll(m));
+                        first = __shfl(first, leader, 64);
+                        const uint32_t pos = first + lanes_below(m);
+                        if (in && pos < LCAP) p.list[lst * LCAP + pos] = key;
                     }
+                } else if (mode[j] == MODE_HIST && in) {
+                    atomicAdd(&p.hist2[((size_t)t * p.n_cf + j) * NBIN + (key - base[j])], 1u);
                 }
             }
         }
@@ -1139,7 +1147,7 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
         o[2] = (ss_dense == 0.0) ? 1.0 : ss_sel / ss_dense;
         o[3] = tau;
         if (id == 0) {
-            if (p.out_count) *p.out_count = is_flat(p) ? (int64_t)p.flat_k[p.commit] : p.koff[p.n_seg];
+            if (p.out_count) *p.out_count = p.total_out;
             p.status->sig_lo = p.sig_lo;  // this call's thresholds can serve as the next call's bounds
             p.status->sig_hi = p.sig_hi;
         }
@@ -1364,7 +1372,7 @@ __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restri
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-    size_t status, seg_off, koff, tile_prefix, samp_prefix, samp_cnt, ktab, st, seg, hist1, ovfc, hist2, coarse, list, list_cnt,
+    size_t status, tables, tables_bytes, tseg, st, seg, hist1, ovfc, hist2, coarse, list, list_cnt,
         samp_hist, cand_cnt, tg, te, toff, ttake, ssd, ssd_t, sss, cand_idx, cand_val, total;
 };
 
@@ -1386,12 +1394,10 @@ Layout make_layout(int64_t n, int n_cf, int n_seg)
     const uint64_t nt = max_tiles(n, n_seg), nsb = max_sample_blocks(n, n_seg);
     const size_t sc = (size_t)n_seg * n_cf;
     L.status = take(sizeof(Status));
-    L.seg_off = take(sizeof(int64_t) * (n_seg + 1));
-    L.koff = take(sizeof(int64_t) * (n_seg + 1));
-    L.tile_prefix = take(sizeof(uint32_t) * (n_seg + 1));
-    L.samp_prefix = take(sizeof(uint32_t) * (n_seg + 1));
-    L.samp_cnt = take(sizeof(uint32_t) * n_seg);
-    L.ktab = take(sizeof(uint32_t) * sc);
+    // host-built tables, one piece: SegInfo[n_seg], ktab[n_seg][n_cf], sblock_seg[sample blocks]
+    L.tables_bytes = sizeof(SegInfo) * n_seg + sizeof(uint32_t) * sc + sizeof(uint32_t) * nsb;
+    L.tables = take(L.tables_bytes);
+    L.tseg = take(sizeof(uint32_t) * nt);
     L.st = take(sizeof(CfState) * sc);
     L.seg = take(sizeof(SegState) * n_seg);
     L.hist1 = take(sizeof(uint32_t) * sc * REP * NBIN);
@@ -1422,8 +1428,53 @@ uint32_t sample_count(uint64_t nt, double cf_max, bool flat)
     if (target < 4096) target = 4096;
     if (target > (uint64_t)SAMPLE_MAX) target = SAMPLE_MAX;
     target = (target + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK * SAMPLE_BLOCK;
-    if (nt <= (uint64_t)LCAP) return 0;  // every element becomes a candidate; the gather list resolves it
     return (nt <= 2 * target) ? (uint32_t)nt : (uint32_t)target;
+}
+
+// Pinned host staging for the layerwise tables: a small ring of slots, each followed on its stream by an
+// event, so that a slot is only rewritten after the copy that read it has run.  Host memory only; grown on demand.
+struct StagingSlot {
+    char* mem = nullptr;
+    size_t cap = 0;
+    hipEvent_t done = nullptr;
+    bool pending = false;  // `done` was recorded and not yet waited for
+    bool busy = false;     // being filled by a caller
+};
+constexpr int STAGING_SLOTS = 8;
+StagingSlot g_staging[STAGING_SLOTS];
+int g_staging_next = 0;
+std::mutex g_staging_mutex;
+
+StagingSlot* staging_acquire(size_t bytes)
+{
+    std::lock_guard<std::mutex> lock(g_staging_mutex);
+    StagingSlot* s = nullptr;
+    for (int i = 0; i < STAGING_SLOTS && !s; ++i) {
+        StagingSlot* c = &g_staging[(g_staging_next + i) % STAGING_SLOTS];
+        if (!c->busy) { s = c; g_staging_next = (g_staging_next + i + 1) % STAGING_SLOTS; }
+    }
+    if (!s) return nullptr;  // more concurrent callers than slots
+    if (!s->done && hipEventCreateWithFlags(&s->done, hipEventDisableTiming) != hipSuccess) return nullptr;
+    if (s->pending) {
+        if (hipEventSynchronize(s->done) != hipSuccess) return nullptr;
+        s->pending = false;
+    }
+    if (s->cap < bytes) {
+        if (s->mem) (void)hipHostFree(s->mem);
+        s->mem = nullptr; s->cap = 0;
+        const size_t want = bytes < 65536 ? 65536 : bytes + bytes / 2;
+        if (hipHostMalloc((void**)&s->mem, want, hipHostMallocDefault) != hipSuccess) { s->mem = nullptr; return nullptr; }
+        s->cap = want;
+    }
+    s->busy = true;
+    return s;
+}
+
+void staging_release(StagingSlot* s, bool recorded)
+{
+    std::lock_guard<std::mutex> lock(g_staging_mutex);
+    s->pending = recorded;
+    s->busy = false;
 }
 
 std::mutex g_prof_mutex;
@@ -1488,12 +1539,10 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
     std::memset(&p, 0, sizeof(p));
     p.grad = grad; p.res = residual; p.n = n; p.n_seg = ns; p.n_cf = n_cf; p.commit = commit; p.flags = flags;
     p.status = (Status*)(ws + L.status);
-    p.seg_off = (const int64_t*)(ws + L.seg_off);
-    p.koff = (const int64_t*)(ws + L.koff);
-    p.tile_prefix = (const uint32_t*)(ws + L.tile_prefix);
-    p.samp_prefix = (const uint32_t*)(ws + L.samp_prefix);
-    p.samp_cnt = (const uint32_t*)(ws + L.samp_cnt);
-    p.ktab = (const uint32_t*)(ws + L.ktab);
+    p.segs = (const SegInfo*)(ws + L.tables);
+    p.ktab = (const uint32_t*)(ws + L.tables + sizeof(SegInfo) * ns);
+    p.sblock_seg = p.ktab + (size_t)ns * n_cf;
+    p.tseg = (uint32_t*)(ws + L.tseg);
     p.st = (CfState*)(ws + L.st);
     p.seg = (SegState*)(ws + L.seg);
     p.hist1 = (uint32_t*)(ws + L.hist1);
@@ -1526,46 +1575,49 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
         total_out = p.flat_k[commit];
         if (total_out > out_capacity) return GRAVAC_ERR_CAPACITY;
     } else {
-        // layerwise tables, built on the host and copied into the workspace
-        std::vector<int64_t> koff(ns + 1);
-        std::vector<uint32_t> tile_prefix(ns + 1), samp_prefix(ns + 1), samp_cnt(ns), ktab((size_t)ns * n_cf);
+        // layerwise tables: sized first, then built straight into a pinned staging slot and copied into the
+        // workspace with one asynchronous copy (no host synchronisation)
         uint64_t tiles = 0, sblocks = 0;
         for (int t = 0; t < ns; ++t) {
             const int64_t nt = seg_offsets[t + 1] - seg_offsets[t];
-            koff[t] = total_out;
-            tile_prefix[t] = (uint32_t)tiles;
-            samp_prefix[t] = (uint32_t)sblocks;
-            for (int j = 0; j < n_cf; ++j) ktab[(size_t)t * n_cf + j] = (uint32_t)gravac_topk_count(nt, cf_list[j]);
-            total_out += ktab[(size_t)t * n_cf + commit];
-            samp_cnt[t] = sample_count((uint64_t)nt, cf_max, false);
+            total_out += gravac_topk_count(nt, cf_list[commit]);
             const uint64_t tt = (uint64_t)((nt + TW - 1) / TW);
             tiles += tt;
             if (tt > max_seg_tiles) max_seg_tiles = (uint32_t)tt;
-            sblocks += (samp_cnt[t] + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
+            sblocks += (sample_count((uint64_t)nt, cf_max, false) + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
         }
-        koff[ns] = total_out;
-        tile_prefix[ns] = (uint32_t)tiles;
-        samp_prefix[ns] = (uint32_t)sblocks;
         if (total_out > out_capacity) return GRAVAC_ERR_CAPACITY;
         if (tiles > max_tiles(n, ns) || sblocks > max_sample_blocks(n, ns)) return GRAVAC_ERR_WORKSPACE;
         p.n_tiles = (uint32_t)tiles;
         p.n_sample_blocks = (uint32_t)sblocks;
-        hipError_t e = hipSuccess;
-        auto up = [&](size_t off, const void* src, size_t bytes) {
-            if (e == hipSuccess) e = hipMemcpyAsync(ws + off, src, bytes, hipMemcpyHostToDevice, stream);
-        };
-        up(L.seg_off, seg_offsets, sizeof(int64_t) * (ns + 1));
-        up(L.koff, koff.data(), sizeof(int64_t) * (ns + 1));
-        up(L.tile_prefix, tile_prefix.data(), sizeof(uint32_t) * (ns + 1));
-        up(L.samp_prefix, samp_prefix.data(), sizeof(uint32_t) * (ns + 1));
-        up(L.samp_cnt, samp_cnt.data(), sizeof(uint32_t) * ns);
-        up(L.ktab, ktab.data(), sizeof(uint32_t) * (size_t)ns * n_cf);
-        if (e != hipSuccess) return GRAVAC_ERR_HIP;
-        // the host vectors die at the end of this scope: wait for the copies (pageable memory is
-        // staged by the runtime, but the guarantee is only given by a synchronisation)
-        if (hipStreamSynchronize(stream) != hipSuccess) return GRAVAC_ERR_HIP;
+        const size_t bytes = sizeof(SegInfo) * ns + sizeof(uint32_t) * (size_t)ns * n_cf + sizeof(uint32_t) * sblocks;
+        StagingSlot* slot = staging_acquire(bytes);
+        if (!slot) return GRAVAC_ERR_HIP;
+        SegInfo* segs = (SegInfo*)slot->mem;
+        uint32_t* ktab = (uint32_t*)(slot->mem + sizeof(SegInfo) * ns);
+        uint32_t* sblock_seg = ktab + (size_t)ns * n_cf;
+        int64_t koff = 0;
+        uint32_t tile_at = 0, sb_at = 0;
+        for (int t = 0; t < ns; ++t) {
+            const int64_t nt = seg_offsets[t + 1] - seg_offsets[t];
+            SegInfo& g = segs[t];
+            std::memset(&g, 0, sizeof(g));
+            g.begin = seg_offsets[t]; g.end = seg_offsets[t + 1]; g.koff = koff;
+            g.tile0 = tile_at; tile_at += (uint32_t)((nt + TW - 1) / TW); g.tile1 = tile_at;
+            g.samp0 = sb_at; g.samp_cnt = sample_count((uint64_t)nt, cf_max, false);
+            const uint32_t nb = (g.samp_cnt + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
+            for (uint32_t b = 0; b < nb; ++b) sblock_seg[sb_at + b] = (uint32_t)t;
+            sb_at += nb;
+            for (int j = 0; j < n_cf; ++j) ktab[(size_t)t * n_cf + j] = (uint32_t)gravac_topk_count(nt, cf_list[j]);
+            koff += ktab[(size_t)t * n_cf + commit];
+        }
+        const bool ok = hipMemcpyAsync(ws + L.tables, slot->mem, bytes, hipMemcpyHostToDevice, stream) == hipSuccess &&
+                        hipEventRecord(slot->done, stream) == hipSuccess;
+        staging_release(slot, ok);
+        if (!ok) return GRAVAC_ERR_HIP;
     }
 
+    p.total_out = total_out;
     {   // signature of the call: FNV-1a over the shape, the k table and the segment table
         uint64_t h = 1469598103934665603ull;
         auto mix = [&](uint64_t x) { for (int b = 0; b < 8; ++b) { h ^= (x >> (8 * b)) & 0xFF; h *= 1099511628211ull; } };
@@ -1591,7 +1643,7 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
         }
         (void)hipEventRecord(g_ev[0], stream);
     }
-    if (p.n_sample_blocks && !(flags & GRAVAC_FLAG_REUSE_THRESHOLDS))  // tensors of at most LCAP elements are not sampled
+    if (p.n_sample_blocks && !(flags & GRAVAC_FLAG_REUSE_THRESHOLDS))
         hipLaunchKernelGGL(sample_kernel, dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
     hipLaunchKernelGGL(threshold_kernel, dim3(ns), dim3(1024), 0, stream, p);
     if (prof)  // events 1 and 2 take the kernel's own begin and end time stamps

@@ -223,3 +223,81 @@ int oracle_decompress_accumulate(const int32_t* idx, const float* val,
     }
     return ORACLE_OK;
 }
+
+/*
+ * Multi-level compression (Sec. IV-C): given the message X1 = C(theta1, X) as k1 (index, value) pairs in
+ * ascending index order, produce X2' = C(theta2', X1) with theta2' = theta2 / theta1: the
+ * k2 = ceil(k1 / cf_rel) entries of X1 of largest magnitude, ties to the lower position (= lower index),
+ * again in ascending index order.  For Top-k, X2' equals the direct C(theta2, X).
+ *
+ * Deferred commit: if residual is not NULL it is the residual left by committing X1 (zero in X1's slots);
+ * the entries of X1 that are not in X2' go back into it (residual[idx] = value), so that afterwards it is
+ * the residual of committing X2' instead (Alg. 1 updates the residual with whichever message is sent).
+ *
+ * seg_counts (NULL = one tensor): pairs of X1 per tensor, for layerwise messages; each tensor is
+ * recompressed on its own with k2_t = ceil(k1_t / cf_rel).  out_stats is [max(n_seg,1)][4]:
+ * { ||X2'||^2, ||X1||^2, their ratio (1 if ||X1||^2 == 0), |value| of the smallest selected entry }.
+ */
+int oracle_recompress(const int32_t* idx1, const float* val1, int64_t k1, double cf_rel,
+                      float* residual, int64_t n, const int64_t* seg_counts, int n_seg,
+                      int32_t* out_idx, float* out_val, int64_t out_capacity, int64_t* out_count,
+                      double* out_stats)
+{
+    if (!idx1 || !val1 || !out_idx || !out_val || !out_stats || k1 <= 0 || !(cf_rel >= 1.0) || isinf(cf_rel))
+        return ORACLE_BAD_ARG;
+    int64_t one[1] = {k1};
+    const int64_t* cnt = seg_counts;
+    int ns = n_seg;
+    if (!cnt || ns <= 0) { cnt = one; ns = 1; }
+    int64_t sum = 0, total = 0;
+    for (int t = 0; t < ns; ++t) {
+        if (cnt[t] <= 0) return ORACLE_BAD_ARG;
+        sum += cnt[t];
+        total += oracle_k(cnt[t], cf_rel);
+    }
+    if (sum != k1) return ORACLE_BAD_ARG;
+    if (total > out_capacity) return ORACLE_CAPACITY;
+
+    int64_t at = 0, written = 0;
+    for (int t = 0; t < ns; ++t) {
+        const int64_t m = cnt[t], k2 = oracle_k(m, cf_rel);
+        entry_t* order = (entry_t*)malloc((size_t)m * sizeof(entry_t));
+        uint32_t* chosen = (uint32_t*)malloc((size_t)k2 * sizeof(uint32_t));
+        char* keep = (char*)calloc((size_t)m, 1);
+        if (!order || !chosen || !keep) { free(order); free(chosen); free(keep); return ORACLE_NOMEM; }
+        double ss_all = 0.0, ss_sel = 0.0;
+        for (int64_t i = 0; i < m; ++i) {
+            order[i].mag = f32_bits(val1[at + i]) & 0x7FFFFFFFu;
+            order[i].pos = (uint32_t)i;
+            ss_all += (double)val1[at + i] * (double)val1[at + i];
+        }
+        qsort(order, (size_t)m, sizeof(entry_t), cmp_entry);
+        for (int64_t r = 0; r < k2; ++r) {
+            chosen[r] = order[r].pos;
+            ss_sel += (double)val1[at + order[r].pos] * (double)val1[at + order[r].pos];
+        }
+        double* st = out_stats + 4 * (size_t)t;
+        st[0] = ss_sel;
+        st[1] = ss_all;
+        st[2] = (ss_all == 0.0) ? 1.0 : ss_sel / ss_all;
+        st[3] = fabs((double)val1[at + order[k2 - 1].pos]);
+        qsort(chosen, (size_t)k2, sizeof(uint32_t), cmp_u32);
+        for (int64_t r = 0; r < k2; ++r) {
+            out_idx[written + r] = idx1[at + chosen[r]];
+            out_val[written + r] = val1[at + chosen[r]];
+            keep[chosen[r]] = 1;
+        }
+        if (residual) {
+            for (int64_t i = 0; i < m; ++i) {
+                const int64_t g = idx1[at + i];
+                if (g < 0 || g >= n) { free(order); free(chosen); free(keep); return ORACLE_BAD_ARG; }
+                if (!keep[i]) residual[g] = val1[at + i];
+            }
+        }
+        free(order); free(chosen); free(keep);
+        at += m;
+        written += k2;
+    }
+    if (out_count) *out_count = written;
+    return ORACLE_OK;
+}

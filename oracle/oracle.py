@@ -47,6 +47,8 @@ def _load():
         lib.oracle_compress.argtypes = [p, p, i64, p, i32, i32, p, i32, p, p, i64, p, p]
         lib.oracle_decompress_accumulate.restype = i32
         lib.oracle_decompress_accumulate.argtypes = [p, p, p, i32, i64, p]
+        lib.oracle_recompress.restype = i32
+        lib.oracle_recompress.argtypes = [p, p, i64, dbl, p, i64, p, i32, p, p, i64, p, p]
         _lib = lib
     return _lib
 
@@ -106,3 +108,36 @@ def decompress_accumulate(idx: np.ndarray, val: np.ndarray, counts, dense_out: n
                                           _ptr(cnt), cnt.size, dense_out.size, _ptr(dense_out))
     if rc != 0:
         raise RuntimeError(f"oracle_decompress_accumulate failed with code {rc}")
+
+
+def recompress(idx1: np.ndarray, val1: np.ndarray, cf_rel: float, residual=None, seg_counts=None):
+    """Second-level Top-k on a message (Sec. IV-C multi-level compression).
+
+    Returns ``(idx int32[k2], val float32[k2], stats float64[n_seg][4])``.  ``residual`` (float32, the
+    residual left by committing the level-1 message), if given, is updated IN PLACE to the residual
+    of committing the level-2 message.
+    """
+    lib = _load()
+    idx1 = np.ascontiguousarray(idx1, dtype=np.int32)
+    val1 = np.ascontiguousarray(val1, dtype=np.float32)
+    k1 = idx1.size
+    if seg_counts is None:
+        cnt, n_seg, rows = None, 0, 1
+        cap = topk_count(k1, cf_rel)
+    else:
+        cnt = np.ascontiguousarray(np.asarray(seg_counts, dtype=np.int64))
+        n_seg, rows = cnt.size, cnt.size
+        cap = sum(topk_count(int(c), cf_rel) for c in cnt)
+    out_idx = np.empty(cap, dtype=np.int32)
+    out_val = np.empty(cap, dtype=np.float32)
+    stats = np.zeros((rows, 4), dtype=np.float64)
+    count = ctypes.c_int64(0)
+    rc = lib.oracle_recompress(_ptr(idx1), _ptr(val1), k1, float(cf_rel),
+                               _ptr(residual) if residual is not None else None,
+                               residual.size if residual is not None else 0,
+                               _ptr(cnt) if cnt is not None else None, n_seg,
+                               _ptr(out_idx), _ptr(out_val), cap, ctypes.byref(count), _ptr(stats))
+    if rc != 0:
+        raise RuntimeError(f"oracle_recompress failed with code {rc}")
+    assert count.value == cap
+    return out_idx, out_val, stats

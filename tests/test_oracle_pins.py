@@ -239,6 +239,54 @@ def test_multilevel_identity():
     assert np.array_equal(w.view(np.uint32), v2.view(np.uint32))
 
 
+def test_recompress_equals_direct_compression_and_moves_the_residual():
+    """Sec. IV-C with the deferred commit: compress at theta1 and commit, recompress by theta2/theta1
+    -> the same message, statistics and residual as compressing directly at theta2."""
+    n = 40_003
+    g = workloads.resnet_like_gradient(n, seed=23)
+    r0 = workloads.normal_gradient(n, 1e-5, seed=24)
+    for th1, rel in ((10.0, 100.0), (10.0, 10.0), (4.0, 2.5)):
+        i1, v1, s1, res1 = run_oracle(g, r0, [th1])
+        res = res1.copy()
+        i2, v2, s2 = oracle.recompress(i1, v1, rel, residual=res)
+        k2 = math.ceil(i1.size / rel)
+        assert i2.size == k2
+        # brute force on the message itself
+        pos = brute_force_select(v1, k2)
+        assert np.array_equal(i2, i1[pos]) and np.array_equal(v2.view(np.uint32), v1[pos].view(np.uint32))
+        assert math.isclose(s2[0, 1], s1[0, 0, 0], rel_tol=1e-12)            # ||X1||^2
+        assert math.isclose(s2[0, 0], float((v2.astype(np.float64) ** 2).sum()), rel_tol=1e-12)
+        assert s2[0, 3] == float(np.abs(v2).min())
+        if float(th1 * rel).is_integer() and math.ceil(math.ceil(n / th1) / rel) == math.ceil(n / (th1 * rel)):
+            d_i, d_v, d_s, d_res = run_oracle(g, r0, [th1 * rel])
+            assert np.array_equal(i2, d_i) and np.array_equal(v2.view(np.uint32), d_v.view(np.uint32))
+            assert np.array_equal(res.view(np.uint32), d_res.view(np.uint32))
+        # message + residual is still acc, bit for bit
+        acc = r0 + g
+        rebuilt = res.copy()
+        rebuilt[i2] = v2
+        assert np.array_equal(rebuilt.view(np.uint32), acc.view(np.uint32))
+    # without a residual nothing else is touched; CF 1 keeps the whole message
+    i2, v2, s2 = oracle.recompress(i1, v1, 1.0)
+    assert np.array_equal(i2, i1) and np.array_equal(v2, v1) and math.isclose(s2[0, 2], 1.0, rel_tol=1e-12)
+
+
+def test_recompress_layerwise():
+    sizes = [64, 4096, 37, 100_003, 9408, 1000]
+    off = workloads.offsets_of(sizes)
+    n = int(off[-1])
+    g = workloads.resnet_like_gradient(n, seed=25)
+    z = np.zeros(n, np.float32)
+    i1, v1, s1, res1 = run_oracle(g, z, [10.0], seg=off)
+    counts = [-(-s // 10) for s in sizes]
+    res = res1.copy()
+    i2, v2, s2 = oracle.recompress(i1, v1, 10.0, residual=res, seg_counts=counts)
+    d_i, d_v, d_s, d_res = run_oracle(g, z, [100.0], seg=off)
+    assert np.array_equal(i2, d_i) and np.array_equal(v2.view(np.uint32), d_v.view(np.uint32))
+    assert np.array_equal(res.view(np.uint32), d_res.view(np.uint32))
+    assert np.allclose(s2[:, 0], d_s[:, 0, 0], rtol=1e-12) and np.array_equal(s2[:, 3], d_s[:, 0, 3])
+
+
 # --------------------------------------------------------------------------
 # metamorphic relations
 # --------------------------------------------------------------------------

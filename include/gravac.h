@@ -103,6 +103,40 @@ int gravac_compress(const float* grad, float* residual, int64_t n,
                     unsigned flags, void* stream);
 
 /*
+ * Multi-level compression (Sec. IV-C): the second-level Top-k.  Given the level-1 message
+ * (idx1, val1) that gravac_compress emitted at CF theta1, select the k2 = ceil(k1 / cf_rel) entries of
+ * largest |val1| (ties to the lower index, i.e. the earlier position), which is the message a direct
+ * compression at CF theta1 * cf_rel would have produced when k2 equals its k.  The commit is deferred:
+ * the level-1 entries NOT selected here are written back into the residual, so that after this call
+ * the residual is the one a direct compression at the higher CF would have left.
+ *
+ *   idx1, val1  device, int32[k1] / float[k1], 16-byte aligned, read only: the level-1 message, indices
+ *               ascending within a segment (as gravac_compress emits them).
+ *   k1          1 <= k1 <= 2^31 - 1.
+ *   cf_rel      finite, >= 1: the ratio theta2 / theta1.
+ *   seg_counts  host, int64[n_seg], pairs per tensor of a layerwise level-1 message (each >= 1, sum k1);
+ *               NULL with n_seg == 0 for a flat message.  Every tensor gets its own k2_t = ceil(k1_t / cf_rel).
+ *   residual    device, float[n], or NULL.  In: the residual left by the level-1 commit (0 in the idx1 slots).
+ *               Out: residual[idx1[i]] = val1[i] for the entries not selected, +0.0f for the selected.
+ *               Entries of idx1 outside [0, n) are not written.  NULL: nothing is restored.
+ *   n           length of residual (ignored when residual is NULL).
+ *   out_idx, out_val, out_capacity, out_count   as for gravac_compress; the pairs keep idx1's order.
+ *               Must not overlap idx1 / val1.
+ *   out_stats   device, double[max(n_seg,1)][4]: { ||level-2 message||^2, ||level-1 message||^2, their
+ *               ratio (1 if the denominator is 0), |val| of the smallest selected entry }.  The ratio
+ *               times the level-1 gain is the gain at theta2 (Sec. IV-C).
+ *   workspace   device, 256-byte aligned, at least gravac_workspace_bytes(k1, 1, n_seg) bytes.
+ *   flags       as for gravac_compress.
+ */
+int gravac_recompress(const int32_t* idx1, const float* val1, int64_t k1, double cf_rel,
+                      const int64_t* seg_counts, int n_seg,
+                      float* residual, int64_t n,
+                      int32_t* out_idx, float* out_val, int64_t out_capacity,
+                      int64_t* out_count, double* out_stats,
+                      void* workspace, size_t workspace_bytes,
+                      unsigned flags, void* stream);
+
+/*
  * Decompression with aggregation (Sec. III-A t_decompress; what a worker does with the
  * messages it received): dense_out[idx] += val for workers w = 0 .. W-1 in that order.
  *

@@ -26,7 +26,8 @@ FLAG_PROFILE = 2
 FLAG_REUSE_THRESHOLDS = 4
 
 EXPORTS = (
-    "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_decompress_accumulate",
+    "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_recompress",
+    "gravac_decompress_accumulate",
     "gravac_read_status", "gravac_profile_read", "gravac_strerror",
 )
 
@@ -58,6 +59,9 @@ def lib() -> ctypes.CDLL:
         L.gravac_compress.restype = i32
         L.gravac_compress.argtypes = [vp, vp, i64, vp, i32, i32, vp, i32, vp, vp, i64, vp, vp, vp,
                                       ctypes.c_size_t, u32, vp]
+        L.gravac_recompress.restype = i32
+        L.gravac_recompress.argtypes = [vp, vp, i64, dbl, vp, i32, vp, i64, vp, vp, i64, vp, vp, vp,
+                                        ctypes.c_size_t, u32, vp]
         L.gravac_decompress_accumulate.restype = i32
         L.gravac_decompress_accumulate.argtypes = [vp, vp, vp, i32, i64, vp, vp]
         L.gravac_read_status.restype = i32
@@ -116,6 +120,24 @@ def gravac_compress(grad, residual, cf_list, commit=0, seg_offsets=None, *, out_
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), int(flags), _stream_handle(stream))
     if rc != OK:
         raise GravacError(rc, "gravac_compress")
+
+
+def gravac_recompress(idx1, val1, cf_rel, seg_counts=None, residual=None, *, out_idx, out_val, out_count=None,
+                      out_stats, workspace, flags=0, stream=None) -> None:
+    """``gravac_recompress`` of the C ABI on torch device tensors (asynchronous on ``stream``)."""
+    if seg_counts is None:
+        cnt_ptr, n_seg = None, 0
+    else:
+        cnt = np.ascontiguousarray(np.asarray(seg_counts, dtype=np.int64))
+        cnt_ptr, n_seg = cnt.ctypes.data_as(ctypes.c_void_p), cnt.size
+    rc = lib().gravac_recompress(
+        _dev_ptr(idx1, torch.int32), _dev_ptr(val1, torch.float32), idx1.numel(), float(cf_rel), cnt_ptr, n_seg,
+        _dev_ptr(residual, torch.float32), 0 if residual is None else residual.numel(),
+        _dev_ptr(out_idx, torch.int32), _dev_ptr(out_val, torch.float32), out_idx.numel(),
+        _dev_ptr(out_count, torch.int64), _dev_ptr(out_stats, torch.float64),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), int(flags), _stream_handle(stream))
+    if rc != OK:
+        raise GravacError(rc, "gravac_recompress")
 
 
 def gravac_decompress_accumulate(idx, val, counts, dense_out, *, stream=None) -> None:

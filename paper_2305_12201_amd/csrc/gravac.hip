@@ -108,6 +108,7 @@ struct Status {
 };
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef int v4i __attribute__((ext_vector_type(4)));
 
 // One tensor of a layerwise call.
 struct SegInfo {
@@ -121,8 +122,13 @@ struct SegInfo {
 static_assert(sizeof(SegInfo) == 64, "SegInfo layout");
 
 struct Params {
-    const float* grad;
-    float* res;
+    const float* grad;       // gradient; in single-source mode the values of the level-1 message
+    float* res;              // residual (in: leftover, out: acc with the selection zeroed); null in single-source mode
+    const float* acc;        // where acc can be re-read after the streaming pass: res, or grad in single-source mode
+    const int32_t* map_idx;  // single-source mode: index of every source element in the dense gradient (else null)
+    float* restore;          // single-source mode: dense residual that gets the unselected values back (or null)
+    int64_t n_restore;       // its length
+    int single;              // 1 = single-source mode (second-level compression of a message)
     int64_t n;
     int n_seg;  // >= 1
     int n_cf;
@@ -322,7 +328,7 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
                 const uint64_t a = ((uint64_t)i * nt) / S, e = ((uint64_t)(i + 1) * nt) / S;
                 pos = a + hash32(i * 0x9E3779B9u + 0x85EBCA6Bu) % (uint32_t)(e - a);
             }
-            acc[q] = p.res[s0 + (int64_t)pos] + p.grad[s0 + (int64_t)pos];
+            acc[q] = p.single ? p.grad[s0 + (int64_t)pos] : p.res[s0 + (int64_t)pos] + p.grad[s0 + (int64_t)pos];
         }
     }
 #pragma unroll
@@ -523,7 +529,7 @@ __device__ __forceinline__ void st_stream(v4f v, v4f* q)
 }
 
 // One lane's four consecutive elements a[0..3] at global index g; vm = validity bits.
-template <bool EF>
+template <bool SSD>
 __device__ __forceinline__ void consume(TileCtx& c, const float a[4], int64_t g, unsigned vm)
 {
     uint32_t key[4];
@@ -533,7 +539,7 @@ __device__ __forceinline__ void consume(TileCtx& c, const float a[4], int64_t g,
         key[e] = key_of(a[e]);
         const bool valid = (vm >> e) & 1u;
         f[e] = valid && key[e] >= c.lo_min;
-        if (EF) {
+        if (SSD) {
             const double d = valid ? (double)a[e] : 0.0;
             c.ssd += d * d;
         }
@@ -561,10 +567,50 @@ __device__ __forceinline__ void consume(TileCtx& c, const float a[4], int64_t g,
     }
 }
 
+// Modes of the streaming pass.
+enum { SM_EF = 0,      // acc = residual + grad, written back into residual
+       SM_EXACT = 1,   // exact route: acc is re-read, candidates are collected again
+       SM_SINGLE = 2   // single source (second-level compression): acc = grad; every value is also written
+};                     // back into the dense residual at its mapped index (the emit pass zeroes the selected)
+
+// Issue the loads of one row (this lane's four elements from global index g).
+template <int M>
+__device__ __forceinline__ void row_load(const Params& p, int64_t g, v4f& x, v4f& y, v4i& m)
+{
+    if (M == SM_EF) { x = ld_stream((const v4f*)(p.res + g)); y = ld_stream((const v4f*)(p.grad + g)); }
+    if (M == SM_EXACT) x = ld_stream((const v4f*)(p.acc + g));
+    if (M == SM_SINGLE) {
+        y = ld_stream((const v4f*)(p.grad + g));
+        if (p.restore) m = *(const v4i*)(p.map_idx + g);
+    }
+}
+
+// Arithmetic and stores of one row; a[] gets the four acc values.
+template <int M>
+__device__ __forceinline__ void row_finish(const Params& p, int64_t g, const v4f& x, const v4f& y, const v4i& m, float a[4])
+{
+    if (M == SM_EF) {
+        const v4f av = x + y;
+        st_stream(av, (v4f*)(p.res + g));
+        a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
+    }
+    if (M == SM_EXACT) { a[0] = x.x; a[1] = x.y; a[2] = x.z; a[3] = x.w; }
+    if (M == SM_SINGLE) {
+        a[0] = y.x; a[1] = y.y; a[2] = y.z; a[3] = y.w;
+        if (p.restore) {
+            const int mi[4] = {m.x, m.y, m.z, m.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if ((uint64_t)(int64_t)mi[e] < (uint64_t)p.n_restore) p.restore[mi[e]] = a[e];
+        }
+    }
+}
+
 // One sub-tile v, by one wavefront.
-template <bool EF>
+template <int M>
 __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int lane)
 {
+    constexpr bool EF = (M != SM_EXACT);  // a first pass: sums acc^2, takes the bounds from the threshold kernel
     const uint32_t u = v / SUB;  // tile
     if (u >= p.n_tiles) return;
     const int t = tile_seg(p, u);
@@ -630,39 +676,25 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
         const bool full = (rb >= s0) && (rb + ROW <= e0);
         if (full && rb + GV_ROWS * ROW <= e0) {
             // GV_ROWS full rows: all loads first, then the arithmetic
-            v4f gv[GV_ROWS], rv[GV_ROWS];
+            v4f x[GV_ROWS], y[GV_ROWS];
+            v4i m[GV_ROWS];
 #pragma unroll
-            for (int q = 0; q < GV_ROWS; ++q) {
-                const int64_t g = rb + q * ROW + 4 * lane;
-                rv[q] = ld_stream((const v4f*)(p.res + g));
-                if (EF) gv[q] = ld_stream((const v4f*)(p.grad + g));
-            }
+            for (int q = 0; q < GV_ROWS; ++q) row_load<M>(p, rb + q * ROW + 4 * lane, x[q], y[q], m[q]);
 #pragma unroll
             for (int q = 0; q < GV_ROWS; ++q) {
                 const int64_t g = rb + q * ROW + 4 * lane;
                 float a[4];
-                if (EF) {
-                    const v4f av = rv[q] + gv[q];
-                    st_stream(av, (v4f*)(p.res + g));
-                    a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
-                } else {
-                    a[0] = rv[q].x; a[1] = rv[q].y; a[2] = rv[q].z; a[3] = rv[q].w;
-                }
+                row_finish<M>(p, g, x[q], y[q], m[q], a);
                 consume<EF>(c, a, g, 0xFu);
             }
             rb += (GV_ROWS - 1) * ROW;
         } else if (full) {
             const int64_t g = rb + 4 * lane;
-            const v4f rv = ld_stream((const v4f*)(p.res + g));
+            v4f x, y;
+            v4i m;
             float a[4];
-            if (EF) {
-                const v4f gv = ld_stream((const v4f*)(p.grad + g));
-                const v4f av = rv + gv;
-                st_stream(av, (v4f*)(p.res + g));
-                a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
-            } else {
-                a[0] = rv.x; a[1] = rv.y; a[2] = rv.z; a[3] = rv.w;
-            }
+            row_load<M>(p, g, x, y, m);
+            row_finish<M>(p, g, x, y, m, a);
             consume<EF>(c, a, g, 0xFu);
         } else {
             // ragged row: element-wise, guarded
@@ -675,11 +707,17 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                 a[e] = 0.0f;
                 if (q >= s0 && q < e0) {
                     vm |= 1u << e;
-                    if (EF) {
+                    if (M == SM_EF) {
                         a[e] = p.res[q] + p.grad[q];
                         p.res[q] = a[e];
+                    } else if (M == SM_EXACT) {
+                        a[e] = p.acc[q];
                     } else {
-                        a[e] = p.res[q];
+                        a[e] = p.grad[q];
+                        if (p.restore) {
+                            const int mi = p.map_idx[q];
+                            if ((uint64_t)(int64_t)mi < (uint64_t)p.n_restore) p.restore[mi] = a[e];
+                        }
                     }
                 }
             }
@@ -701,20 +739,20 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
     if (lane == 0) p.cand_cnt[v] = c.run;
 }
 
-// EF = true: one sub-tile per wavefront, one launch covers the whole gradient.
-// EF = false: a fixed number of wavefronts walks over all sub-tiles (only those of failed segments do
+// First pass (SM_EF, SM_SINGLE): one sub-tile per wavefront, one launch covers the whole gradient.
+// SM_EXACT: a fixed number of wavefronts walks over all sub-tiles (only those of failed segments do
 // any work), so that the launch costs next to nothing when no segment failed.
-template <bool EF>
+template <int M>
 __global__ __launch_bounds__(WG) void stream_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
     const uint32_t w = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
-    if (EF) {
-        stream_subtile<true>(p, w, lane);
+    if (M != SM_EXACT) {
+        stream_subtile<M>(p, w, lane);
     } else {
         if (p.status->any_fail == 0) return;
         const uint32_t nw = gridDim.x * WAVES, nsub = p.n_tiles * SUB;
-        for (uint32_t v = w; v < nsub; v += nw) stream_subtile<false>(p, v, lane);
+        for (uint32_t v = w; v < nsub; v += nw) stream_subtile<SM_EXACT>(p, v, lane);
     }
 }
 
@@ -741,7 +779,7 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
     }
     for (int i = lane; i < NBIN; i += 64) h[i] = 0;
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-    for (int64_t q = s0 + lane; q < e0; q += 64) atomicAdd(&h[key_of(p.res[q]) >> 20], 1u);
+    for (int64_t q = s0 + lane; q < e0; q += 64) atomicAdd(&h[key_of(p.acc[q]) >> 20], 1u);
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     uint32_t* gh = p.coarse + (size_t)t * NBIN;
     for (int i = lane; i < NBIN; i += 64) {
@@ -1197,9 +1235,15 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
             if (sel) {
                 const int64_t o = pos + lanes_below(ms);
                 if (o < lim) {
-                    p.out_idx[o] = iq[r];
                     p.out_val[o] = vq[r];
-                    p.res[iq[r]] = 0.0f;
+                    if (!p.single) {
+                        p.out_idx[o] = iq[r];
+                        p.res[iq[r]] = 0.0f;
+                    } else {
+                        const int mi = p.map_idx[iq[r]];  // position in the message -> index in the gradient
+                        p.out_idx[o] = mi;
+                        if (p.restore && (uint64_t)(int64_t)mi < (uint64_t)p.n_restore) p.restore[mi] = 0.0f;
+                    }
                 } else {
                     p.status->error = 1;  // cannot happen if the counts are consistent; never write out of range
                 }
@@ -1509,15 +1553,18 @@ int gravac_workspace_bytes(int64_t n, int n_cf, int n_seg, size_t* bytes_out)
     return GRAVAC_OK;
 }
 
-int gravac_compress(const float* grad, float* residual, int64_t n, const double* cf_list, int n_cf, int commit,
-                    const int64_t* seg_offsets, int n_seg, int32_t* out_idx, float* out_val, int64_t out_capacity,
-                    int64_t* out_count, double* out_stats, void* workspace, size_t workspace_bytes, unsigned flags,
-                    void* stream_v)
+// The pipeline behind both entry points.  map_idx == null: error-feedback compression of grad + residual.
+// map_idx != null: single-source mode, the source is grad alone (a message's values), map_idx its indices,
+// restore / n_restore the dense residual that takes the unselected values back (may be null).
+static int compress_impl(const float* grad, float* residual, int64_t n, const double* cf_list, int n_cf, int commit,
+                         const int64_t* seg_offsets, int n_seg, int32_t* out_idx, float* out_val, int64_t out_capacity,
+                         int64_t* out_count, double* out_stats, void* workspace, size_t workspace_bytes, unsigned flags,
+                         hipStream_t stream, const int32_t* map_idx, float* restore, int64_t n_restore)
 {
-    hipStream_t stream = (hipStream_t)stream_v;
-    if (!grad || !residual || !cf_list || !out_idx || !out_val || !out_stats) return GRAVAC_ERR_INVALID_ARG;
+    const bool single = map_idx != nullptr;
+    if (!grad || (!single && !residual) || !cf_list || !out_idx || !out_val || !out_stats) return GRAVAC_ERR_INVALID_ARG;
     if (n <= 0 || n > 2147483647LL || n_cf < 1 || n_cf > MAXCF || commit < 0 || commit >= n_cf) return GRAVAC_ERR_INVALID_ARG;
-    if (((uintptr_t)grad & 15) || ((uintptr_t)residual & 15)) return GRAVAC_ERR_INVALID_ARG;
+    if (((uintptr_t)grad & 15) || ((uintptr_t)residual & 15) || ((uintptr_t)map_idx & 15)) return GRAVAC_ERR_INVALID_ARG;
     if (n_seg < 0 || (n_seg > 0 && !seg_offsets) || (int64_t)n_seg > n) return GRAVAC_ERR_INVALID_ARG;
     double cf_max = 1.0;
     for (int j = 0; j < n_cf; ++j) {
@@ -1537,7 +1584,9 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
     char* ws = (char*)workspace;
     Params p;
     std::memset(&p, 0, sizeof(p));
-    p.grad = grad; p.res = residual; p.n = n; p.n_seg = ns; p.n_cf = n_cf; p.commit = commit; p.flags = flags;
+    p.grad = grad; p.res = residual; p.acc = single ? grad : residual;
+    p.map_idx = map_idx; p.restore = restore; p.n_restore = restore ? n_restore : 0; p.single = single ? 1 : 0;
+    p.n = n; p.n_seg = ns; p.n_cf = n_cf; p.commit = commit; p.flags = flags;
     p.status = (Status*)(ws + L.status);
     p.segs = (const SegInfo*)(ws + L.tables);
     p.ktab = (const uint32_t*)(ws + L.tables + sizeof(SegInfo) * ns);
@@ -1621,7 +1670,7 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
     {   // signature of the call: FNV-1a over the shape, the k table and the segment table
         uint64_t h = 1469598103934665603ull;
         auto mix = [&](uint64_t x) { for (int b = 0; b < 8; ++b) { h ^= (x >> (8 * b)) & 0xFF; h *= 1099511628211ull; } };
-        mix((uint64_t)n); mix((uint64_t)n_cf); mix((uint64_t)ns);
+        mix((uint64_t)n); mix((uint64_t)n_cf); mix((uint64_t)ns); mix(single ? 1u : 0u);
         for (int j = 0; j < n_cf; ++j) { uint64_t bits; std::memcpy(&bits, &cf_list[j], 8); mix(bits); }
         if (ns > 1) for (int t = 0; t <= ns; ++t) mix((uint64_t)seg_offsets[t]);
         if (h == 0) h = 1;  // 0 marks "no completed call"
@@ -1646,14 +1695,20 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
     if (p.n_sample_blocks && !(flags & GRAVAC_FLAG_REUSE_THRESHOLDS))
         hipLaunchKernelGGL(sample_kernel, dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
     hipLaunchKernelGGL(threshold_kernel, dim3(ns), dim3(1024), 0, stream, p);
-    if (prof)  // events 1 and 2 take the kernel's own begin and end time stamps
-        hipExtLaunchKernelGGL(stream_kernel<true>, dim3(sub_grid), dim3(WG), 0, stream, g_ev[1], g_ev[2], 0, p);
-    else
-        hipLaunchKernelGGL(stream_kernel<true>, dim3(sub_grid), dim3(WG), 0, stream, p);
+    if (single) {
+        if (prof)
+            hipExtLaunchKernelGGL(stream_kernel<SM_SINGLE>, dim3(sub_grid), dim3(WG), 0, stream, g_ev[1], g_ev[2], 0, p);
+        else
+            hipLaunchKernelGGL(stream_kernel<SM_SINGLE>, dim3(sub_grid), dim3(WG), 0, stream, p);
+    } else if (prof) {  // events 1 and 2 take the kernel's own begin and end time stamps
+        hipExtLaunchKernelGGL(stream_kernel<SM_EF>, dim3(sub_grid), dim3(WG), 0, stream, g_ev[1], g_ev[2], 0, p);
+    } else {
+        hipLaunchKernelGGL(stream_kernel<SM_EF>, dim3(sub_grid), dim3(WG), 0, stream, p);
+    }
     hipLaunchKernelGGL(locate_kernel, dim3(cf_grid), dim3(WG), 0, stream, p);
     // exact route, taken only by segments whose sampled bound failed (the kernels return at once otherwise)
     hipLaunchKernelGGL(coarse_kernel, dim3(tile_grid), dim3(WG), 0, stream, p);
-    hipLaunchKernelGGL(stream_kernel<false>, dim3(sub_grid < 2048 ? sub_grid : 2048), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(stream_kernel<SM_EXACT>, dim3(sub_grid < 2048 ? sub_grid : 2048), dim3(WG), 0, stream, p);
     // exact resolution on the candidates, then count and emit
     hipLaunchKernelGGL(refine_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
     hipLaunchKernelGGL(resolve_kernel, dim3(ns * n_cf), dim3(256), 0, stream, p);
@@ -1666,6 +1721,38 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
     }
     if (hipGetLastError() != hipSuccess) return GRAVAC_ERR_HIP;
     return GRAVAC_OK;
+}
+
+int gravac_compress(const float* grad, float* residual, int64_t n, const double* cf_list, int n_cf, int commit,
+                    const int64_t* seg_offsets, int n_seg, int32_t* out_idx, float* out_val, int64_t out_capacity,
+                    int64_t* out_count, double* out_stats, void* workspace, size_t workspace_bytes, unsigned flags,
+                    void* stream_v)
+{
+    if (!residual) return GRAVAC_ERR_INVALID_ARG;
+    return compress_impl(grad, residual, n, cf_list, n_cf, commit, seg_offsets, n_seg, out_idx, out_val, out_capacity,
+                         out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v, nullptr, nullptr, 0);
+}
+
+int gravac_recompress(const int32_t* idx1, const float* val1, int64_t k1, double cf_rel, const int64_t* seg_counts,
+                      int n_seg, float* residual, int64_t n, int32_t* out_idx, float* out_val, int64_t out_capacity,
+                      int64_t* out_count, double* out_stats, void* workspace, size_t workspace_bytes, unsigned flags,
+                      void* stream_v)
+{
+    if (!idx1 || !val1 || k1 <= 0 || n_seg < 0 || (n_seg > 0 && !seg_counts)) return GRAVAC_ERR_INVALID_ARG;
+    if (residual && (n <= 0 || n > 2147483647LL)) return GRAVAC_ERR_INVALID_ARG;
+    std::vector<int64_t> off;
+    if (n_seg > 0) {
+        off.resize((size_t)n_seg + 1);
+        off[0] = 0;
+        for (int t = 0; t < n_seg; ++t) {
+            if (seg_counts[t] <= 0 || seg_counts[t] > k1) return GRAVAC_ERR_INVALID_ARG;
+            off[t + 1] = off[t] + seg_counts[t];
+        }
+        if (off[n_seg] != k1) return GRAVAC_ERR_INVALID_ARG;
+    }
+    return compress_impl(val1, nullptr, k1, &cf_rel, 1, 0, n_seg > 0 ? off.data() : nullptr, n_seg, out_idx, out_val,
+                         out_capacity, out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v,
+                         idx1, residual, n);
 }
 
 int gravac_decompress_accumulate(const int32_t* idx, const float* val, const int64_t* counts, int W, int64_t n,

@@ -137,6 +137,19 @@ int gravac_recompress(const int32_t* idx1, const float* val1, int64_t k1, double
                       unsigned flags, void* stream);
 
 /*
+ * Commit of a message into the residual (Alg. 1, residual update of the branch taken): residual[idx[i]] =
+ * +0.0f for i < count.  With it the controller can take back the deferred commit of gravac_recompress:
+ * after gravac_compress at theta_min and gravac_recompress on its message the residual is the one of the
+ * candidate CF; committing the level-1 message's indices makes it the residual of theta_min again.
+ * (For the dense branch, gravac_decompress_accumulate of the level-2 message into the residual gives back
+ * the error-fed gradient, exactly except that a selected -0.0 comes back as +0.0.)
+ *
+ *   idx       device, int32[count], read only; entries outside [0, n) are ignored.  count >= 0.
+ *   residual  device, float[n].
+ */
+int gravac_commit(const int32_t* idx, int64_t count, float* residual, int64_t n, void* stream);
+
+/*
  * Decompression with aggregation (Sec. III-A t_decompress; what a worker does with the
  * messages it received): dense_out[idx] += val for workers w = 0 .. W-1 in that order.
  *

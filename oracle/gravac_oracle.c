@@ -225,6 +225,18 @@ int oracle_decompress_accumulate(const int32_t* idx, const float* val,
 }
 
 /*
+ * Commit of a message into the residual (Alg. 1, residual update: residual = g_o - g_c leaves x - x = +0 in
+ * the slots that were sent): residual[idx[i]] = +0.0f.  Indices outside [0, n) are skipped.
+ */
+int oracle_commit(const int32_t* idx, int64_t count, float* residual, int64_t n)
+{
+    if (!residual || count < 0 || n <= 0 || (count > 0 && !idx)) return ORACLE_BAD_ARG;
+    for (int64_t i = 0; i < count; ++i)
+        if (idx[i] >= 0 && idx[i] < n) residual[idx[i]] = 0.0f;
+    return ORACLE_OK;
+}
+
+/*
  * Multi-level compression (Sec. IV-C): given the message X1 = C(theta1, X) as k1 (index, value) pairs in
  * ascending index order, produce X2' = C(theta2', X1) with theta2' = theta2 / theta1: the
  * k2 = ceil(k1 / cf_rel) entries of X1 of largest magnitude, ties to the lower position (= lower index),

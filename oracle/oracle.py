@@ -47,6 +47,8 @@ def _load():
         lib.oracle_compress.argtypes = [p, p, i64, p, i32, i32, p, i32, p, p, i64, p, p]
         lib.oracle_decompress_accumulate.restype = i32
         lib.oracle_decompress_accumulate.argtypes = [p, p, p, i32, i64, p]
+        lib.oracle_commit.restype = i32
+        lib.oracle_commit.argtypes = [p, i64, p, i64]
         lib.oracle_recompress.restype = i32
         lib.oracle_recompress.argtypes = [p, p, i64, dbl, p, i64, p, i32, p, p, i64, p, p]
         _lib = lib
@@ -108,6 +110,15 @@ def decompress_accumulate(idx: np.ndarray, val: np.ndarray, counts, dense_out: n
                                           _ptr(cnt), cnt.size, dense_out.size, _ptr(dense_out))
     if rc != 0:
         raise RuntimeError(f"oracle_decompress_accumulate failed with code {rc}")
+
+
+def commit(idx: np.ndarray, residual: np.ndarray) -> None:
+    """residual[idx] = +0 in place (Alg. 1, residual update of the message that was sent)."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    assert residual.dtype == np.float32 and residual.flags.c_contiguous
+    rc = _load().oracle_commit(_ptr(idx), idx.size, _ptr(residual), residual.size)
+    if rc != 0:
+        raise RuntimeError(f"oracle_commit failed with code {rc}")
 
 
 def recompress(idx1: np.ndarray, val1: np.ndarray, cf_rel: float, residual=None, seg_counts=None):

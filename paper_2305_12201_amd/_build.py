@@ -7,6 +7,7 @@ import subprocess
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 SOURCE = os.path.join(_PKG, "csrc", "gravac.hip")
+HOST_SOURCES = [os.path.join(_PKG, "csrc", "controller.cpp")]   # host-only parts of the same library
 LIBRARY = os.path.join(_PKG, "libgravac.so")
 
 HIPCC_FLAGS = [
@@ -18,12 +19,12 @@ HIPCC_FLAGS = [
 
 def build_library(force: bool = True) -> str:
     """Build ``libgravac.so`` in-tree.  With ``force=False`` only if it is missing or stale."""
-    header = os.path.join(_ROOT, "include", "gravac.h")
+    headers = [os.path.join(_ROOT, "include", h) for h in ("gravac.h", "gravac_controller.h")]
     if not force and os.path.exists(LIBRARY):
-        newest = max(os.path.getmtime(SOURCE), os.path.getmtime(header))
+        newest = max(os.path.getmtime(f) for f in [SOURCE, *HOST_SOURCES, *headers])
         if os.path.getmtime(LIBRARY) >= newest:
             return LIBRARY
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-o", LIBRARY, SOURCE]
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-o", LIBRARY, SOURCE, *HOST_SOURCES]
     subprocess.run(cmd, check=True)
     return LIBRARY

@@ -26,10 +26,27 @@ FLAG_PROFILE = 2
 FLAG_REUSE_THRESHOLDS = 4
 
 EXPORTS = (
-    "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_recompress",
+    "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_recompress", "gravac_commit",
     "gravac_decompress_accumulate",
     "gravac_read_status", "gravac_profile_read", "gravac_strerror",
+    "gravac_controller_create", "gravac_controller_destroy", "gravac_controller_candidates",
+    "gravac_controller_decide", "gravac_controller_finish_iteration", "gravac_controller_throughput",
+    "gravac_controller_iteration",
 )
+
+POLICY_EXPONENTIAL = 0
+POLICY_GEOMETRIC = 1
+SEND_CANDIDATE = 0
+SEND_MIN = 1
+SEND_DENSE = 2
+
+
+class ControllerConfig(ctypes.Structure):
+    """``gravac_controller_config`` of the C ABI."""
+    _fields_ = [("theta_min", ctypes.c_double), ("theta_max", ctypes.c_double), ("epsilon", ctypes.c_double),
+                ("omega", ctypes.c_double), ("theta_s", ctypes.c_double), ("alpha", ctypes.c_double),
+                ("samples_per_iteration", ctypes.c_double), ("window", ctypes.c_int64),
+                ("policy", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 _lib = None
 
@@ -62,6 +79,8 @@ def lib() -> ctypes.CDLL:
         L.gravac_recompress.restype = i32
         L.gravac_recompress.argtypes = [vp, vp, i64, dbl, vp, i32, vp, i64, vp, vp, i64, vp, vp, vp,
                                         ctypes.c_size_t, u32, vp]
+        L.gravac_commit.restype = i32
+        L.gravac_commit.argtypes = [vp, i64, vp, i64, vp]
         L.gravac_decompress_accumulate.restype = i32
         L.gravac_decompress_accumulate.argtypes = [vp, vp, vp, i32, i64, vp, vp]
         L.gravac_read_status.restype = i32
@@ -70,6 +89,21 @@ def lib() -> ctypes.CDLL:
         L.gravac_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         L.gravac_strerror.restype = ctypes.c_char_p
         L.gravac_strerror.argtypes = [i32]
+        dp = ctypes.POINTER(dbl)
+        L.gravac_controller_create.restype = i32
+        L.gravac_controller_create.argtypes = [ctypes.POINTER(ControllerConfig), ctypes.POINTER(vp)]
+        L.gravac_controller_destroy.restype = None
+        L.gravac_controller_destroy.argtypes = [vp]
+        L.gravac_controller_candidates.restype = i32
+        L.gravac_controller_candidates.argtypes = [vp, dp, dp, dp]
+        L.gravac_controller_decide.restype = i32
+        L.gravac_controller_decide.argtypes = [vp, dbl, dbl, ctypes.POINTER(ctypes.c_int32), dp, dp]
+        L.gravac_controller_finish_iteration.restype = i32
+        L.gravac_controller_finish_iteration.argtypes = [vp, dbl, dp]
+        L.gravac_controller_throughput.restype = i32
+        L.gravac_controller_throughput.argtypes = [vp, dbl, dp]
+        L.gravac_controller_iteration.restype = i64
+        L.gravac_controller_iteration.argtypes = [vp]
         _lib = L
     return _lib
 
@@ -140,6 +174,14 @@ def gravac_recompress(idx1, val1, cf_rel, seg_counts=None, residual=None, *, out
         raise GravacError(rc, "gravac_recompress")
 
 
+def gravac_commit(idx, residual, *, stream=None) -> None:
+    """``gravac_commit`` of the C ABI: residual[idx] = +0."""
+    rc = lib().gravac_commit(_dev_ptr(idx, torch.int32), idx.numel(), _dev_ptr(residual, torch.float32),
+                             residual.numel(), _stream_handle(stream))
+    if rc != OK:
+        raise GravacError(rc, "gravac_commit")
+
+
 def gravac_decompress_accumulate(idx, val, counts, dense_out, *, stream=None) -> None:
     """``gravac_decompress_accumulate`` of the C ABI on torch device tensors."""
     cnt = np.ascontiguousarray(np.asarray(counts, dtype=np.int64))
@@ -198,3 +240,62 @@ class Compressor:
 
     def status(self) -> dict:
         return gravac_read_status(self.workspace)
+
+
+class Controller:
+    """The host-side adaptive-compression controller of the C ABI (``gravac_controller_*``)."""
+
+    def __init__(self, theta_min, theta_max, epsilon, omega, window, policy=POLICY_GEOMETRIC, theta_s=2.0,
+                 alpha=0.32, samples_per_iteration=1.0):
+        cfg = ControllerConfig(float(theta_min), float(theta_max), float(epsilon), float(omega), float(theta_s),
+                               float(alpha), float(samples_per_iteration), int(window), int(policy), 0)
+        h = ctypes.c_void_p()
+        rc = lib().gravac_controller_create(ctypes.byref(cfg), ctypes.byref(h))
+        if rc != OK:
+            raise GravacError(rc, "gravac_controller_create")
+        self._h = h
+
+    def close(self):
+        if self._h:
+            lib().gravac_controller_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def candidates(self):
+        """(theta_min, theta_c, theta_c / theta_min) for the coming iteration."""
+        a, b, c = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+        rc = lib().gravac_controller_candidates(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+        if rc != OK:
+            raise GravacError(rc, "gravac_controller_candidates")
+        return a.value, b.value, c.value
+
+    def decide(self, gain_min, gain_c):
+        """(choice, delta_min, delta_c)."""
+        ch, a, b = ctypes.c_int32(), ctypes.c_double(), ctypes.c_double()
+        rc = lib().gravac_controller_decide(self._h, float(gain_min), float(gain_c), ctypes.byref(ch),
+                                            ctypes.byref(a), ctypes.byref(b))
+        if rc != OK:
+            raise GravacError(rc, "gravac_controller_decide")
+        return ch.value, a.value, b.value
+
+    def finish_iteration(self, t_iter):
+        s = ctypes.c_double()
+        rc = lib().gravac_controller_finish_iteration(self._h, float(t_iter), ctypes.byref(s))
+        if rc != OK:
+            raise GravacError(rc, "gravac_controller_finish_iteration")
+        return s.value
+
+    def throughput(self, cf):
+        """T_compress[cf], or None if that CF has no entry yet."""
+        t = ctypes.c_double()
+        rc = lib().gravac_controller_throughput(self._h, float(cf), ctypes.byref(t))
+        return t.value if rc == OK else None
+
+    @property
+    def iteration(self):
+        return int(lib().gravac_controller_iteration(self._h))

@@ -1526,6 +1526,19 @@ hipEvent_t g_ev[4];
 bool g_ev_ready = false;
 bool g_ev_recorded = false;
 
+// ---------------------------------------------------------------------------------------------
+// Commit of a message: residual[idx[i]] = +0.0f.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void commit_kernel(const int32_t* __restrict__ idx, int64_t count,
+                                                     float* __restrict__ residual, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+        const int64_t g = idx[i];
+        if ((uint64_t)g < (uint64_t)n) residual[g] = 0.0f;
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -1753,6 +1766,17 @@ int gravac_recompress(const int32_t* idx1, const float* val1, int64_t k1, double
     return compress_impl(val1, nullptr, k1, &cf_rel, 1, 0, n_seg > 0 ? off.data() : nullptr, n_seg, out_idx, out_val,
                          out_capacity, out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v,
                          idx1, residual, n);
+}
+
+int gravac_commit(const int32_t* idx, int64_t count, float* residual, int64_t n, void* stream_v)
+{
+    if (!residual || count < 0 || n <= 0 || n > 2147483647LL || (count > 0 && !idx)) return GRAVAC_ERR_INVALID_ARG;
+    if (count == 0) return GRAVAC_OK;
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(commit_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream_v, idx, count, residual, n);
+    if (hipGetLastError() != hipSuccess) return GRAVAC_ERR_HIP;
+    return GRAVAC_OK;
 }
 
 int gravac_decompress_accumulate(const int32_t* idx, const float* val, const int64_t* counts, int W, int64_t n,

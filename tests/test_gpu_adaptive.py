@@ -1,0 +1,100 @@
+"""GPU end-to-end: the adaptive loop of Alg. 1 (compress at theta_min, second-level compression to the
+candidate CF, the controller's epsilon switch, the residual update of the branch taken) run through the C
+ABI, against the same loop built from the CPU oracle.  Every iteration's message and residual bit-exact,
+the same decisions and the same CF schedule."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import controller_oracle as co
+from oracle import oracle
+from paper_2305_12201_amd import binding, workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def _gradient(n, it):
+    # a decaying heavy-tailed part plus noise, so the gain at a given CF rises over the iterations
+    rng = np.random.default_rng(900 + it)
+    g = rng.standard_normal(n) * 1e-3
+    heavy = rng.random(n) < 0.002
+    g[heavy] *= 40.0 * (1.0 + 4.0 / (1 + it))
+    return g.astype(np.float32)
+
+
+def _t_iter(choice, cf):
+    # deterministic stand-in for the measured iteration time: compute + compression + communication ~ 1/CF
+    return 0.05 + (0.0 if choice == co.SEND_DENSE else 0.01) + 0.4 / cf
+
+
+@pytest.mark.parametrize("epsilon,policy", [(0.55, "geometric"), (0.8, "exponential"), (0.97, "geometric")])
+def test_adaptive_loop_matches_the_oracle_loop(epsilon, policy):
+    n, iters, window = 300_007, 36, 4
+    theta_min, theta_max, omega, alpha = 4.0, 512.0, 0.02, 0.32
+    st = co.State(theta_min, theta_max, epsilon, omega, window, policy, alpha=alpha, N_b=256.0)
+    ctl = binding.Controller(theta_min, theta_max, epsilon, omega, window,
+                             binding.POLICY_EXPONENTIAL if policy == "exponential" else binding.POLICY_GEOMETRIC,
+                             alpha=alpha, samples_per_iteration=256.0)
+    res_gpu = torch.zeros(n, dtype=torch.float32, device="cuda")
+    res_cpu = np.zeros(n, np.float32)
+    choices = []
+    for it in range(iters):
+        g = _gradient(n, it)
+        acc = res_cpu + g
+        # ---- GPU side
+        tmin, tc, rel = ctl.candidates()
+        comp = binding.Compressor(n, [tmin], 0)
+        i1, v1, s1 = comp(torch.from_numpy(g).cuda(), res_gpu)
+        k1 = i1.numel()
+        k2 = binding.gravac_topk_count(k1, rel)
+        ws2 = torch.empty(binding.gravac_workspace_bytes(k1, 1, 0), dtype=torch.uint8, device="cuda")
+        i2 = torch.empty(k2, dtype=torch.int32, device="cuda")
+        v2 = torch.empty(k2, dtype=torch.float32, device="cuda")
+        s2 = torch.zeros(1, 4, dtype=torch.float64, device="cuda")
+        binding.gravac_recompress(i1, v1, rel, None, res_gpu, out_idx=i2, out_val=v2, out_stats=s2, workspace=ws2)
+        gain_min = float(s1[0, 0, 2].item())
+        gain_c = float(s2[0, 0].item() / s1[0, 0, 1].item()) if s1[0, 0, 1].item() > 0 else 1.0
+        choice, dmin, dc = ctl.decide(gain_min, gain_c)
+        if choice == binding.SEND_CANDIDATE:
+            sent_i, sent_v = i2, v2
+        elif choice == binding.SEND_MIN:
+            binding.gravac_commit(i1, res_gpu)
+            sent_i, sent_v = i1, v1
+        else:
+            binding.gravac_decompress_accumulate(i2, v2, [k2], res_gpu)     # residual + message = acc
+            dense_sent = res_gpu.clone()
+            res_gpu.zero_()
+        torch.cuda.synchronize()
+        assert binding.gravac_read_status(comp.workspace)["internal_error"] == 0
+        cf_used = {binding.SEND_CANDIDATE: tc, binding.SEND_MIN: tmin, binding.SEND_DENSE: 1.0}[choice]
+        ctl.finish_iteration(_t_iter(choice, cf_used))
+
+        # ---- the same iteration from the oracle
+        o_tmin, o_tc = st.theta_min, co.candidate(st)
+        assert (tmin, tc) == (o_tmin, o_tc), it
+        oi1, ov1, os1 = oracle.compress(g, res_cpu, [o_tmin])
+        oi2, ov2, os2 = oracle.recompress(oi1, ov1, o_tc / o_tmin, residual=res_cpu)
+        gains = {o_tmin: os1[0, 0, 2], o_tc: (os2[0, 0] / os1[0, 0, 1]) if os1[0, 0, 1] > 0 else 1.0}
+        r = co.iteration(st, lambda cf: gains[cf], _t_iter)
+        if r["choice"] == co.SEND_MIN:
+            oracle.commit(oi1, res_cpu)
+        elif r["choice"] == co.SEND_DENSE:
+            res_cpu[:] = 0.0
+
+        # ---- compare
+        assert choice == r["choice"], (it, gain_min, gain_c, gains)
+        np.testing.assert_allclose([dmin, dc], [r["delta_min"], r["delta_c"]], rtol=1e-9)
+        if choice == binding.SEND_CANDIDATE:
+            assert np.array_equal(sent_i.cpu().numpy(), oi2) and \
+                np.array_equal(sent_v.cpu().numpy().view(np.uint32), ov2.view(np.uint32)), it
+        elif choice == binding.SEND_MIN:
+            assert np.array_equal(sent_i.cpu().numpy(), oi1) and \
+                np.array_equal(sent_v.cpu().numpy().view(np.uint32), ov1.view(np.uint32)), it
+        else:
+            d = dense_sent.cpu().numpy()
+            assert np.array_equal(d, acc) and np.array_equal(d.view(np.uint32)[acc != 0], acc.view(np.uint32)[acc != 0])
+        assert np.array_equal(res_gpu.cpu().numpy().view(np.uint32), res_cpu.view(np.uint32)), it
+        choices.append(choice)
+    assert len(set(choices)) >= 2, choices          # the run exercises more than one branch
+    assert st.theta_s != 2.0 or st.theta_min != theta_min
+    ctl.close()

@@ -287,6 +287,35 @@ def test_recompress_layerwise():
     assert np.allclose(s2[:, 0], d_s[:, 0, 0], rtol=1e-12) and np.array_equal(s2[:, 3], d_s[:, 0, 3])
 
 
+def test_commit_takes_back_the_deferred_commit_and_dense_branch_rebuilds_acc():
+    """The three branches of Alg. 1 after compress(theta_min) + recompress: candidate = as is; theta_min =
+    commit of the level-1 indices gives the level-1 residual again; dense = residual + message is acc."""
+    n = 60_001
+    g = workloads.resnet_like_gradient(n, seed=27)
+    r0 = workloads.normal_gradient(n, 1e-5, seed=28)
+    i1, v1, _, res1 = run_oracle(g, r0, [10.0])
+    res = res1.copy()
+    i2, v2, _ = oracle.recompress(i1, v1, 8.0, residual=res)
+    assert not np.array_equal(res.view(np.uint32), res1.view(np.uint32))
+    back = res.copy()
+    oracle.commit(i1, back)
+    assert np.array_equal(back.view(np.uint32), res1.view(np.uint32))
+    # against numpy's indexed assignment, with out-of-range indices skipped
+    x = workloads.normal_gradient(1000, 1.0, seed=29)
+    idx = np.array([5, -1, 999, 1000, 17, 5], np.int32)
+    y = x.copy()
+    oracle.commit(idx, y)
+    z = x.copy()
+    z[[5, 999, 17]] = 0.0
+    assert np.array_equal(y.view(np.uint32), z.view(np.uint32)) and not np.signbit(y[[5, 999, 17]]).any()
+    # dense branch: adding the level-2 message back into its residual restores acc exactly
+    dense = res.copy()
+    oracle.decompress_accumulate(i2, v2, [i2.size], dense)
+    acc = r0 + g
+    assert np.array_equal(dense.view(np.uint32), acc.view(np.uint32)) or \
+        np.array_equal(np.where(acc == 0, 0.0, dense).view(np.uint32), np.where(acc == 0, 0.0, acc).view(np.uint32))
+
+
 # --------------------------------------------------------------------------
 # metamorphic relations
 # --------------------------------------------------------------------------

@@ -40,11 +40,11 @@
 namespace {
 
 #ifndef GV_TW
-#define GV_TW 4096
+#define GV_TW 8192
 #endif
 constexpr int TW = GV_TW;           // elements per tile (unit of the candidate-list kernels)
 #ifndef GV_SUB
-#define GV_SUB 4
+#define GV_SUB 8
 #endif
 constexpr int SUB = GV_SUB;         // sub-tiles per tile: the streaming pass gives one wavefront a sub-tile
 constexpr int TS = TW / SUB;        // elements per sub-tile
@@ -297,6 +297,73 @@ __device__ __forceinline__ void wave_locate_bin(const uint32_t* hist, int copies
     }
 }
 
+// The same search by four wavefronts (threads q = 0..255 of a 256-thread team; `q` is the thread's number
+// inside the team, `scratch` 8 words of LDS owned by the team).  Thread q owns bins 8q .. 8q+7 and has all
+// its loads in flight at once.  The caller synchronises the team (all its threads reach this call) and
+// provides the barrier: `sync()` must be a barrier that covers at least the team.
+template <typename Sync>
+__device__ __forceinline__ void team_locate_bin(const uint32_t* hist, int copies, const uint32_t* top_extra, uint32_t k,
+                                                int q, uint32_t* scratch, Sync sync, uint32_t& bin, uint32_t& above,
+                                                uint32_t& count)
+{
+    const int lane = q & 63, wv = q >> 6;
+    uint32_t extra = (top_extra && q < 64) ? top_extra[q * 32] : 0u;
+    uint32_t h[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) h[i] = 0;
+    if (copies == REP) {
+        uint4 v[REP][2];
+#pragma unroll
+        for (int r = 0; r < REP; ++r) {
+            const uint4* hv = (const uint4*)(hist + (size_t)r * NBIN + 8 * q);
+            v[r][0] = hv[0]; v[r][1] = hv[1];
+        }
+#pragma unroll
+        for (int r = 0; r < REP; ++r) {
+            h[0] += v[r][0].x; h[1] += v[r][0].y; h[2] += v[r][0].z; h[3] += v[r][0].w;
+            h[4] += v[r][1].x; h[5] += v[r][1].y; h[6] += v[r][1].z; h[7] += v[r][1].w;
+        }
+    } else {
+        for (int r = 0; r < copies; ++r) {
+            const uint4* hv = (const uint4*)(hist + (size_t)r * NBIN + 8 * q);
+            const uint4 a = hv[0], b = hv[1];
+            h[0] += a.x; h[1] += a.y; h[2] += a.z; h[3] += a.w;
+            h[4] += b.x; h[5] += b.y; h[6] += b.z; h[7] += b.w;
+        }
+    }
+    extra = wave_sum(extra);  // non-zero in the team's first wavefront only
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) mine += h[i];
+    const uint32_t incl = wave_scan(mine);
+    if (lane == 63) scratch[wv] = incl;
+    if (q == 0) scratch[4] = extra;
+    sync();
+    const uint32_t ex = scratch[4];  // belongs to the very last bin
+    uint32_t total = ex, before = 0;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        total += scratch[x];
+        if (x < wv) before += scratch[x];
+    }
+    uint32_t ab = total - ex - (before + incl);  // entries in the bins above this thread's eight ...
+    if (q == 255) h[7] += ex;
+    else ab += ex;                               // ... including the extra counts of the last bin
+    uint32_t fb = NONE, fa = 0, fc = 0;
+#pragma unroll
+    for (int i = 7; i >= 0; --i) {
+        if (ab < k && ab + h[i] >= k) { fb = 8 * q + i; fa = ab; fc = h[i]; }
+        ab += h[i];
+    }
+    sync();  // scratch is rewritten below
+    if (fb != NONE) { scratch[5] = fb; scratch[6] = fa; scratch[7] = fc; }
+    if (q == 0) scratch[4] = (total >= k) ? 1u : 0u;
+    sync();
+    if (scratch[4]) { bin = scratch[5]; above = scratch[6]; count = scratch[7]; }
+    else { bin = NONE; above = 0; count = 0; }
+    sync();
+}
+
 // ---------------------------------------------------------------------------------------------
 // K0a: sample acc = residual + grad at stratified positions; each workgroup histograms the top
 // 12 key bits of its SAMPLE_BLOCK samples in LDS and stores the counts as 16-bit numbers
@@ -370,19 +437,26 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
     // reuse: the previous call's candidate histogram says where its count from the top reached about 1.25 k;
     // that key becomes this call's lower bound (wavefront j looks at CF j, before the histogram is cleared)
     __shared__ uint32_t pred_lo[MAXCF];
-    if (reuse && wib < p.n_cf) {
-        const CfState* old = &p.st[(size_t)t * p.n_cf + wib];
-        const uint32_t k = seg_k(p, t, wib), lo_prev = old->lo, s_prev = old->s > 31u ? 31u : old->s;
-        uint32_t b, ab, cn;
-        wave_locate_bin(p.hist1 + ((size_t)t * p.n_cf + wib) * REP * NBIN, REP, p.ovfc + ((size_t)t * p.n_cf + wib) * 64 * 32,
-                        k + k / 4 + 64, b, ab, cn);
-        uint32_t lo;
-        if (b == NONE) lo = lo_prev > (1u << 19) ? lo_prev - (1u << 19) : 0u;  // fewer candidates than that: go lower
-        else {
-            const uint64_t x = (uint64_t)lo_prev + ((uint64_t)b << s_prev);
-            lo = x > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)x;
+    __shared__ uint32_t team_scratch[4][8];
+    if (reuse) {
+        // four teams of four wavefronts, team g takes CF g and CF g + 4
+        const int team = tid >> 8, q = tid & 255;
+        for (int r = 0; r < (p.n_cf + 3) / 4; ++r) {
+            const int j = r * 4 + team;
+            const int jj = j < p.n_cf ? j : 0;  // idle teams repeat CF 0 (they must reach the barriers)
+            const CfState* old = &p.st[(size_t)t * p.n_cf + jj];
+            const uint32_t k = seg_k(p, t, jj), lo_prev = old->lo, s_prev = old->s > 31u ? 31u : old->s;
+            uint32_t b, ab, cn;
+            team_locate_bin(p.hist1 + ((size_t)t * p.n_cf + jj) * REP * NBIN, REP, p.ovfc + ((size_t)t * p.n_cf + jj) * 64 * 32,
+                            k + k / 4 + 64, q, team_scratch[team], [] { __syncthreads(); }, b, ab, cn);
+            uint32_t lo;
+            if (b == NONE) lo = lo_prev > (1u << 19) ? lo_prev - (1u << 19) : 0u;  // fewer candidates than that: go lower
+            else {
+                const uint64_t x = (uint64_t)lo_prev + ((uint64_t)b << s_prev);
+                lo = x > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)x;
+            }
+            if (q == 0 && j < p.n_cf) pred_lo[j] = lo;
         }
-        if (lane == 0) pred_lo[wib] = lo;
     }
     __syncthreads();
     for (int i = tid; i < p.n_cf * REP * NBIN; i += 1024) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
@@ -765,26 +839,29 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
     __shared__ uint32_t lh[WAVES][NBIN];
     if (p.status->any_fail == 0) return;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + wib);
-    if (u >= p.n_tiles) return;
-    const int t = tile_seg(p, u);
-    if (p.seg[t].fail == 0) return;
     uint32_t* h = lh[wib];
-    const int64_t sb = seg_begin(p, t), se = seg_end(p, t);
-    const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW;
-    const int64_t e0 = (s0 + TW < se) ? s0 + TW : se;
-    if (u == seg_tile0(p, t)) {
-        for (int i = lane; i < p.n_cf * REP * NBIN; i += 64) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
-        for (int i = lane; i < p.n_cf * 64; i += 64) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
-    }
-    for (int i = lane; i < NBIN; i += 64) h[i] = 0;
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-    for (int64_t q = s0 + lane; q < e0; q += 64) atomicAdd(&h[key_of(p.acc[q]) >> 20], 1u);
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-    uint32_t* gh = p.coarse + (size_t)t * NBIN;
-    for (int i = lane; i < NBIN; i += 64) {
-        const uint32_t v = h[i];
-        if (v) atomicAdd(&gh[i], v);
+    // a fixed number of wavefronts walks over the tiles, so that the launch costs little when nothing failed
+    const uint32_t nw = gridDim.x * WAVES;
+    for (uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + wib); u < p.n_tiles; u += nw) {
+        const int t = tile_seg(p, u);
+        if (p.seg[t].fail == 0) continue;
+        const int64_t sb = seg_begin(p, t), se = seg_end(p, t);
+        const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW;
+        const int64_t e0 = (s0 + TW < se) ? s0 + TW : se;
+        if (u == seg_tile0(p, t)) {
+            for (int i = lane; i < p.n_cf * REP * NBIN; i += 64) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
+            for (int i = lane; i < p.n_cf * 64; i += 64) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
+        }
+        for (int i = lane; i < NBIN; i += 64) h[i] = 0;
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+        for (int64_t q = s0 + lane; q < e0; q += 64) atomicAdd(&h[key_of(p.acc[q]) >> 20], 1u);
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+        uint32_t* gh = p.coarse + (size_t)t * NBIN;
+        for (int i = lane; i < NBIN; i += 64) {
+            const uint32_t v = h[i];
+            if (v) atomicAdd(&gh[i], v);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     }
 }
 
@@ -820,22 +897,23 @@ __device__ __forceinline__ void store_plan(CfState* st, const BinPlan& q)
 }
 
 // ---------------------------------------------------------------------------------------------
-// L1: one wavefront per (segment, CF): find the candidate-histogram bin of the k-th largest and
+// L1: one workgroup per (segment, CF): find the candidate-histogram bin of the k-th largest and
 // decide how to resolve it; a segment whose bound failed is marked for the exact route
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(WG) void locate_kernel(Params p)
+__global__ __launch_bounds__(256) void locate_kernel(Params p)
 {
-    const int lane = threadIdx.x & 63;
-    const uint32_t id = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
-    if (id >= (uint32_t)(p.n_seg * p.n_cf)) return;
+    __shared__ uint32_t scratch[8];
+    const int tid = threadIdx.x;
+    const uint32_t id = blockIdx.x;
     const int t = id / p.n_cf;
     CfState* st = &p.st[id];
     uint32_t b, above, c;
-    wave_locate_bin(p.hist1 + (size_t)id * REP * NBIN, REP, p.ovfc + (size_t)id * 64 * 32, st->k, b, above, c);
+    team_locate_bin(p.hist1 + (size_t)id * REP * NBIN, REP, p.ovfc + (size_t)id * 64 * 32, st->k, tid, scratch,
+                    [] { __syncthreads(); }, b, above, c);
     const BinPlan q = plan_bin(st->lo, st->s, b, above, c);
     if (q.mode == MODE_HIST)
-        for (int i = lane; i < NBIN; i += 64) p.hist2[(size_t)id * NBIN + i] = 0;
-    if (lane == 0) {
+        for (int i = tid; i < NBIN; i += 256) p.hist2[(size_t)id * NBIN + i] = 0;
+    if (tid == 0) {
         store_plan(st, q);
         if (q.mode == MODE_FAIL) {
             p.status->any_fail = 1;
@@ -1693,7 +1771,6 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     const uint32_t sub_grid = (p.n_tiles * SUB + WAVES - 1) / WAVES;
     const uint32_t light_grid = (p.n_tiles + LWAVES - 1) / LWAVES;
     const uint32_t scan_slices = (max_seg_tiles + SCAN_SLICE - 1) / SCAN_SLICE;
-    const uint32_t cf_grid = ((uint32_t)(ns * n_cf) + WAVES - 1) / WAVES;
 
     const bool prof = (flags & GRAVAC_FLAG_PROFILE) != 0;
     if (prof) {
@@ -1718,10 +1795,10 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     } else {
         hipLaunchKernelGGL(stream_kernel<SM_EF>, dim3(sub_grid), dim3(WG), 0, stream, p);
     }
-    hipLaunchKernelGGL(locate_kernel, dim3(cf_grid), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(locate_kernel, dim3((uint32_t)(ns * n_cf)), dim3(256), 0, stream, p);
     // exact route, taken only by segments whose sampled bound failed (the kernels return at once otherwise)
-    hipLaunchKernelGGL(coarse_kernel, dim3(tile_grid), dim3(WG), 0, stream, p);
-    hipLaunchKernelGGL(stream_kernel<SM_EXACT>, dim3(sub_grid < 2048 ? sub_grid : 2048), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(coarse_kernel, dim3(tile_grid < 1024 ? tile_grid : 1024), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(stream_kernel<SM_EXACT>, dim3(sub_grid < 1024 ? sub_grid : 1024), dim3(WG), 0, stream, p);
     // exact resolution on the candidates, then count and emit
     hipLaunchKernelGGL(refine_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
     hipLaunchKernelGGL(resolve_kernel, dim3(ns * n_cf), dim3(256), 0, stream, p);

@@ -47,8 +47,8 @@ def test_config1_two_iterations(flags):
 # ragged sizes, tiny inputs, every CF regime
 # --------------------------------------------------------------------------
 
-@pytest.mark.parametrize("n", [1, 2, 3, 5, 63, 64, 65, 255, 257, 1023, 4095, 4096, 4097, 8193, 100_003, 131_072,
-                               131_073, 300_001])
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 63, 64, 65, 255, 257, 1023, 1025, 4095, 4096, 4097, 8191, 8192, 8193,
+                               16_385, 100_003, 131_072, 131_073, 300_001])
 def test_ragged_sizes(n):
     g = workloads.normal_gradient(n, 1e-3, seed=n)
     r = workloads.normal_gradient(n, 1e-4, seed=n + 1)

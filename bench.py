@@ -51,6 +51,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-reuse", action="store_true", help="sample the thresholds in every call instead of "
                                                             "reusing the previous call's")
+    ap.add_argument("--transient", type=int, default=12,
+                    help="first steps of the run that sample their thresholds even with reuse (the error-feedback "
+                         "transient, where the threshold climbs quickly)")
     ap.add_argument("--small", action="store_true", help="1/16-size workload (for a quick functional check)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 10 plain device copies of the gradient's size (known traffic: 4N read + 4N "
@@ -117,7 +120,7 @@ def main():
     # error-feedback run are a transient (the leftover builds up, the threshold climbs by more than the reuse
     # band per step); they sample their thresholds instead, whether they fall into the warm-up or not.
     REUSE_FLAG = 0 if args.no_reuse else binding.FLAG_REUSE_THRESHOLDS
-    TRANSIENT = 12
+    TRANSIENT = args.transient
 
     def reuse(i):
         return REUSE_FLAG if i >= TRANSIENT else 0

@@ -170,7 +170,9 @@ int gravac_decompress_accumulate(const int32_t* idx, const float* val,
  * Diagnostics of the last gravac_compress call that used `workspace`: synchronises `stream`
  * and copies 8 int32 to the host pointer out8:
  *   [0] 1 if any segment took the exact-histogram fallback, [1] number of such segments,
- *   [2] internal-error flag (must be 0), [3] number of segments, [4..7] reserved.
+ *   [2] internal-error flag (must be 0), [3] number of segments, [4] how many of [1] needed no second
+ *   pass over the gradient (their candidates held the k-th largest, only their histogram was rebuilt),
+ *   [5..7] reserved.
  */
 int gravac_read_status(const void* workspace, void* stream, int32_t* out8);
 

@@ -198,7 +198,7 @@ def gravac_read_status(workspace, stream=None) -> dict:
     if rc != OK:
         raise GravacError(rc, "gravac_read_status")
     return {"any_fallback": int(out[0]), "fallback_segments": int(out[1]), "internal_error": int(out[2]),
-            "segments": int(out[3])}
+            "segments": int(out[3]), "light_fallback_segments": int(out[4])}
 
 
 def gravac_profile_read() -> tuple[float, float]:

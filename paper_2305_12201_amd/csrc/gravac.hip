@@ -62,6 +62,10 @@ constexpr int ROW = 256;            // elements one wavefront touches per load (
 #ifndef GV_NT
 #define GV_NT 1                     // non-temporal hints on the streaming loads and stores
 #endif
+#ifndef GV_XGRID
+#define GV_XGRID 1024
+#endif
+constexpr uint32_t XGRID = GV_XGRID;  // workgroups of the two exact-route kernels (they loop over the tiles)
 constexpr int REP = 8;              // copies of the candidate histogram and of the gather lists
 constexpr int NBIN = 2048;          // bins of the candidate / refine / coarse histograms
 constexpr uint32_t OVF = NBIN - 1;  // last bin of the candidate histogram: everything above the bracket
@@ -74,6 +78,7 @@ constexpr double ZMARGIN = 5.0;     // safety margin of the sampled rank, in sta
 constexpr uint32_t NONE = 0xFFFFFFFFu;
 
 enum : uint32_t { MODE_RESOLVED = 0, MODE_GATHER = 1, MODE_HIST = 2, MODE_FAIL = 3 };
+enum : uint32_t { FAIL_NONE = 0, FAIL_LIGHT = 1, FAIL_FULL = 2 };  // SegState::fail
 
 // Selection state of one (segment, CF).
 struct CfState {
@@ -94,7 +99,7 @@ static_assert(sizeof(CfState) == 64, "CfState layout");
 
 struct SegState {
     uint32_t lo_min;  // smallest lo over the CFs: the candidate threshold of the segment
-    uint32_t fail;    // 1 if the sampled bound failed and the segment takes the exact route
+    uint32_t fail;    // FAIL_*: whether the bound failed and the segment takes the exact route, and which form of it
     uint32_t pad[2];
 };
 
@@ -104,7 +109,8 @@ struct Status {
     int error;
     int n_seg;
     uint32_t sig_lo, sig_hi;  // signature (shape, CFs, segment table) of the last call that completed on this workspace
-    int pad[2];
+    int n_light;              // segments of n_fail whose exact route only re-binned the candidates
+    int pad;
 };
 
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -465,6 +471,7 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
     for (int i = tid; i < p.n_cf * REP * 32; i += 1024) p.list_cnt[(size_t)t * p.n_cf * REP * 32 + i] = 0;
     if (t == 0 && tid == 0) {
         p.status->any_fail = 0; p.status->n_fail = 0; p.status->error = 0; p.status->n_seg = p.n_seg;
+        p.status->n_light = 0;
     }
     if (tid < p.n_cf) {
         const uint32_t k = seg_k(p, t, tid);
@@ -680,9 +687,16 @@ __device__ __forceinline__ void row_finish(const Params& p, int64_t g, const v4f
     }
 }
 
+// Exact route: the bounds of the segment a wavefront last worked on (they cost a histogram search).
+struct ExactBounds {
+    int t;  // segment, -1 = none yet
+    uint32_t lo[MAXCF];
+    uint32_t lo_min;
+};
+
 // One sub-tile v, by one wavefront.
 template <int M>
-__device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int lane)
+__device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int lane, ExactBounds* xb)
 {
     constexpr bool EF = (M != SM_EXACT);  // a first pass: sums acc^2, takes the bounds from the threshold kernel
     const uint32_t u = v / SUB;  // tile
@@ -719,15 +733,27 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
         // exact route: lo_j = base of the coarse (key >> 20) bin that holds the k_j-th largest; 1024 bins of
         // 2^10 keys cover that coarse bin, keys above it land in the open last bin
         const bool first = (v == seg_tile0(p, t) * SUB);
+        if (xb->t != t) {
+            xb->t = t;
+            xb->lo_min = NONE;
+#pragma unroll
+            for (int j = 0; j < MAXCF; ++j) {
+                xb->lo[j] = NONE;
+                if (j < p.n_cf) {
+                    uint32_t b, ab, cn;
+                    wave_locate_bin(p.coarse + (size_t)t * NBIN, 1, nullptr, seg_k(p, t, j), b, ab, cn);
+                    if (b == NONE) { b = 0; if (lane == 0) p.status->error = 1; }
+                    xb->lo[j] = b << 20;
+                    xb->lo_min = xb->lo[j] < xb->lo_min ? xb->lo[j] : xb->lo_min;
+                }
+            }
+        }
+        c.lo_min = xb->lo_min;
 #pragma unroll
         for (int j = 0; j < MAXCF; ++j) {
             if (j < p.n_cf) {
-                uint32_t b, ab, cn;
-                wave_locate_bin(p.coarse + (size_t)t * NBIN, 1, nullptr, seg_k(p, t, j), b, ab, cn);
-                if (b == NONE) { b = 0; if (lane == 0) p.status->error = 1; }
-                c.lo[j] = b << 20;
+                c.lo[j] = xb->lo[j];
                 c.sh[j] = 10;
-                c.lo_min = c.lo[j] < c.lo_min ? c.lo[j] : c.lo_min;
                 if (first) {
                     // record the new bound; clear what the refine pass may add to
                     CfState* st = &p.st[(size_t)t * p.n_cf + j];
@@ -744,6 +770,33 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
     c.cval = p.cand_val + (size_t)v * TS;
     c.run = 0;
     c.ssd = 0.0;
+
+    if (!EF && p.seg[t].fail == FAIL_LIGHT) {
+        // the candidate lists stay as they are; only their histogram is rebuilt with the new bins.  Called for the
+        // first sub-tile of a tile only: the wavefront takes the candidates of the whole tile
+        const TileCands tcs = tile_cands(p, u);
+        const uint32_t cnt = tcs.total();
+        const float* cv = p.cand_val + (size_t)u * TW;
+        for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
+            uint32_t kq[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const uint32_t i = i0 + q * 64 + lane;
+                kq[q] = (i < cnt) ? key_of(cv[tcs.slot(i)]) : 0u;
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                if (i0 + q * 64 + lane < cnt) cand_hist(c, kq[q]);
+        }
+#pragma unroll
+        for (int j = 0; j < MAXCF; ++j) {
+            if (j < p.n_cf) {
+                const uint32_t o = wave_sum(c.ovf[j]);
+                if (lane == 0 && o) atomicAdd(&p.ovfc[(((size_t)t * p.n_cf + j) * 64 + (v & 63)) * 32], o);
+            }
+        }
+        return;
+    }
 
     // rows start at a multiple of 4 elements so that vector accesses are 16-byte aligned
     for (int64_t rb = s0 & ~(int64_t)3; rb < e0; rb += ROW) {
@@ -814,19 +867,26 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
 }
 
 // First pass (SM_EF, SM_SINGLE): one sub-tile per wavefront, one launch covers the whole gradient.
-// SM_EXACT: a fixed number of wavefronts walks over all sub-tiles (only those of failed segments do
-// any work), so that the launch costs next to nothing when no segment failed.
+// SM_EXACT: a fixed number of wavefronts walks over all tiles (only those of failed segments do any work).
 template <int M>
 __global__ __launch_bounds__(WG) void stream_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
     const uint32_t w = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
     if (M != SM_EXACT) {
-        stream_subtile<M>(p, w, lane);
+        stream_subtile<M>(p, w, lane, nullptr);
     } else {
         if (p.status->any_fail == 0) return;
-        const uint32_t nw = gridDim.x * WAVES, nsub = p.n_tiles * SUB;
-        for (uint32_t v = w; v < nsub; v += nw) stream_subtile<SM_EXACT>(p, v, lane);
+        ExactBounds xb;
+        xb.t = -1;
+        const uint32_t nw = gridDim.x * WAVES;
+        for (uint32_t u = w; u < p.n_tiles; u += nw) {
+            const uint32_t kind = p.seg[tile_seg(p, u)].fail;
+            if (kind == FAIL_NONE) continue;
+            // FAIL_LIGHT: one call re-bins the candidates of the whole tile; FAIL_FULL: sub-tile by sub-tile
+            const int subs = (kind == FAIL_LIGHT) ? 1 : SUB;
+            for (int j = 0; j < subs; ++j) stream_subtile<SM_EXACT>(p, u * SUB + j, lane, &xb);
+        }
     }
 }
 
@@ -834,34 +894,81 @@ __global__ __launch_bounds__(WG) void stream_kernel(Params p)
 // F1 (exact route): histogram of key >> 20 over the tiles of failed segments; the wavefront of a
 // failed segment's first tile also clears that segment's candidate histograms
 // ---------------------------------------------------------------------------------------------
+constexpr int CSUB = 8;  // copies of the coarse histogram inside a workgroup: lane l counts in copy l % CSUB
+
 __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
 {
-    __shared__ uint32_t lh[WAVES][NBIN];
+    // Gradient magnitudes crowd into a few exponents, so most lanes of a wavefront hit the same few bins and
+    // LDS atomics on one copy serialise 64-fold; CSUB copies cut that to 64 / CSUB.
+    __shared__ uint32_t lh[CSUB][NBIN];
     if (p.status->any_fail == 0) return;
-    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    uint32_t* h = lh[wib];
-    // a fixed number of wavefronts walks over the tiles, so that the launch costs little when nothing failed
-    const uint32_t nw = gridDim.x * WAVES;
-    for (uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + wib); u < p.n_tiles; u += nw) {
-        const int t = tile_seg(p, u);
-        if (p.seg[t].fail == 0) continue;
-        const int64_t sb = seg_begin(p, t), se = seg_end(p, t);
-        const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW;
-        const int64_t e0 = (s0 + TW < se) ? s0 + TW : se;
-        if (u == seg_tile0(p, t)) {
-            for (int i = lane; i < p.n_cf * REP * NBIN; i += 64) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
-            for (int i = lane; i < p.n_cf * 64; i += 64) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
+    const int tid = threadIdx.x, lane = tid & 63;
+    uint32_t* h = lh[lane & (CSUB - 1)];
+    // a fixed number of workgroups walks over the tiles (a workgroup takes WAVES consecutive tiles at a time, one per
+    // wavefront), so that the launch costs little when nothing failed
+    for (uint32_t i = tid; i < CSUB * NBIN; i += WG) (&lh[0][0])[i] = 0;
+    __syncthreads();
+    int cur = -1;  // segment whose counts sit in lh
+    for (uint32_t u0 = blockIdx.x * WAVES; u0 < p.n_tiles; u0 += gridDim.x * WAVES) {
+        // the workgroup's tiles may belong to different segments: one segment at a time, flushed in between
+        const uint32_t u1 = u0 + WAVES < p.n_tiles ? u0 + WAVES : p.n_tiles;
+        for (uint32_t ub = u0; ub < u1;) {
+            const int t = tile_seg(p, ub);
+            uint32_t ue = ub + 1;
+            while (ue < u1 && tile_seg(p, ue) == t) ++ue;
+            const uint32_t kind = p.seg[t].fail;
+            if (kind != FAIL_NONE) {
+                if (cur != t && cur >= 0) {
+                    // flush the previous segment's counts
+                    __syncthreads();
+                    uint32_t* gh = p.coarse + (size_t)cur * NBIN;
+                    for (uint32_t i = tid; i < NBIN; i += WG) {
+                        uint32_t v = 0;
+#pragma unroll
+                        for (int c = 0; c < CSUB; ++c) { v += lh[c][i]; lh[c][i] = 0; }
+                        if (v) atomicAdd(&gh[i], v);
+                    }
+                    __syncthreads();
+                }
+                cur = t;
+                const uint32_t u = ub + (tid >> 6);
+                if (u < ue) {
+                    const int64_t sb = seg_begin(p, t), se = seg_end(p, t);
+                    const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW;
+                    const int64_t e0 = (s0 + TW < se) ? s0 + TW : se;
+                    if (u == seg_tile0(p, t)) {
+                        for (int i = lane; i < p.n_cf * REP * NBIN; i += 64) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
+                        for (int i = lane; i < p.n_cf * 64; i += 64) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
+                    }
+                    if (kind == FAIL_LIGHT) {
+                        // the candidates of the tile are enough
+                        const TileCands tcs = tile_cands(p, u);
+                        const float* cv = p.cand_val + (size_t)u * TW;
+                        for (uint32_t i = lane; i < tcs.total(); i += 64) atomicAdd(&h[key_of(cv[tcs.slot(i)]) >> 20], 1u);
+                    } else {
+                        for (int64_t q0 = s0 + lane; q0 < e0; q0 += 64 * 8) {
+                            float a[8];
+#pragma unroll
+                            for (int r = 0; r < 8; ++r) a[r] = (q0 + r * 64 < e0) ? p.acc[q0 + r * 64] : 0.0f;
+#pragma unroll
+                            for (int r = 0; r < 8; ++r)
+                                if (q0 + r * 64 < e0) atomicAdd(&h[key_of(a[r]) >> 20], 1u);
+                        }
+                    }
+                }
+            }
+            ub = ue;
         }
-        for (int i = lane; i < NBIN; i += 64) h[i] = 0;
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-        for (int64_t q = s0 + lane; q < e0; q += 64) atomicAdd(&h[key_of(p.acc[q]) >> 20], 1u);
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-        uint32_t* gh = p.coarse + (size_t)t * NBIN;
-        for (int i = lane; i < NBIN; i += 64) {
-            const uint32_t v = h[i];
+    }
+    if (cur >= 0) {
+        __syncthreads();
+        uint32_t* gh = p.coarse + (size_t)cur * NBIN;
+        for (uint32_t i = tid; i < NBIN; i += WG) {
+            uint32_t v = 0;
+#pragma unroll
+            for (int c = 0; c < CSUB; ++c) v += lh[c][i];
             if (v) atomicAdd(&gh[i], v);
         }
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     }
 }
 
@@ -916,8 +1023,10 @@ __global__ __launch_bounds__(256) void locate_kernel(Params p)
     if (tid == 0) {
         store_plan(st, q);
         if (q.mode == MODE_FAIL) {
+            // FAIL_LIGHT: the candidates include the k-th largest, only the histogram was too coarse where it lies;
+            // FAIL_FULL: fewer than k candidates, acc has to be read again
             p.status->any_fail = 1;
-            if (atomicExch(&p.seg[t].fail, 1u) == 0u) atomicAdd(&p.status->n_fail, 1);
+            if (atomicMax(&p.seg[t].fail, b == NONE ? FAIL_FULL : FAIL_LIGHT) == 0u) atomicAdd(&p.status->n_fail, 1);
         }
     }
 }
@@ -955,6 +1064,7 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
                 if (first && lane == 0) {
                     store_plan(st, q);
                     if (q.mode == MODE_FAIL) p.status->error = 1;  // the exact route cannot fail
+                    if (j == 0 && p.seg[t].fail == FAIL_LIGHT) atomicAdd(&p.status->n_light, 1);
                 }
             } else {
                 q.mode = st->mode; q.base = st->base; q.open = st->open;
@@ -1797,8 +1907,8 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     }
     hipLaunchKernelGGL(locate_kernel, dim3((uint32_t)(ns * n_cf)), dim3(256), 0, stream, p);
     // exact route, taken only by segments whose sampled bound failed (the kernels return at once otherwise)
-    hipLaunchKernelGGL(coarse_kernel, dim3(tile_grid < 1024 ? tile_grid : 1024), dim3(WG), 0, stream, p);
-    hipLaunchKernelGGL(stream_kernel<SM_EXACT>, dim3(sub_grid < 1024 ? sub_grid : 1024), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(coarse_kernel, dim3(tile_grid < XGRID ? tile_grid : XGRID), dim3(WG), 0, stream, p);
+    hipLaunchKernelGGL(stream_kernel<SM_EXACT>, dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
     // exact resolution on the candidates, then count and emit
     hipLaunchKernelGGL(refine_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
     hipLaunchKernelGGL(resolve_kernel, dim3(ns * n_cf), dim3(256), 0, stream, p);
@@ -1895,8 +2005,8 @@ int gravac_read_status(const void* workspace, void* stream_v, int32_t* out8)
     if (hipStreamSynchronize(stream) != hipSuccess) return GRAVAC_ERR_HIP;
     Status s;
     if (hipMemcpy(&s, workspace, sizeof(Status), hipMemcpyDeviceToHost) != hipSuccess) return GRAVAC_ERR_HIP;
-    out8[0] = s.any_fail; out8[1] = s.n_fail; out8[2] = s.error; out8[3] = s.n_seg;
-    out8[4] = out8[5] = out8[6] = out8[7] = 0;
+    out8[0] = s.any_fail; out8[1] = s.n_fail; out8[2] = s.error; out8[3] = s.n_seg; out8[4] = s.n_light;
+    out8[5] = out8[6] = out8[7] = 0;
     return GRAVAC_OK;
 }
 

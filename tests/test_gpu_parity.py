@@ -151,7 +151,8 @@ def test_config2_reduced_five_iterations():
         gpu = gpu_compress(g, res_gpu, [10.0, 100.0, 1000.0], 1, comp=comp)
         ref = oracle_compress(g, res_ref, [10.0, 100.0, 1000.0], 1)
         assert_same(gpu, ref, f"config2 it{it}")
-        assert gpu[4] == {"any_fallback": 0, "fallback_segments": 0, "internal_error": 0, "segments": 1}
+        assert gpu[4] == {"any_fallback": 0, "fallback_segments": 0, "internal_error": 0, "segments": 1,
+                          "light_fallback_segments": 0}
         res_gpu, res_ref = gpu[3], ref[3]
 
 
@@ -353,6 +354,8 @@ def test_reuse_thresholds_survives_a_scale_jump():
              workloads.normal_gradient(n, 1e-4, seed=5)]      # far smaller: fewer than k candidates above the old one
     st, _ = _iterate(n, [100.0], 0, grads, [0, REUSE, REUSE, REUSE, REUSE], carry=False)
     assert [s["any_fallback"] for s in st] == [0, 0, 1, 0, 1]
+    # upwards the candidates still hold the k largest (only their histogram is rebuilt); downwards they do not
+    assert [s["light_fallback_segments"] for s in st] == [0, 0, 1, 0, 0]
     # and with the residual carried (the threshold drifts as the leftover builds up): exact whatever route is taken
     _iterate(n, [100.0], 0, grads, [0, REUSE, REUSE, REUSE, REUSE])
 

@@ -313,3 +313,142 @@ int oracle_recompress(const int32_t* idx1, const float* val1, int64_t k1, double
     if (out_count) *out_count = written;
     return ORACLE_OK;
 }
+
+
+/*
+ * Random-k (Sec. II-C: "Random-k does so randomly with negligible compression overhead"): the same
+ * error-feedback step, message layout, residual update and gain as Top-k, but the k = ceil(n / CF) entries
+ * that are kept are a pseudo-random subset instead of the largest.  Reading taken here (the paper does not
+ * say how the subset is drawn): every index i of the flat gradient gets the priority P(seed, i) below, a
+ * keyed bijection of the 31-bit integers (so no two indices share a priority), and a tensor keeps its k
+ * entries of highest priority.  With one seed the selections for different CFs are nested, and a segment's
+ * selection does not depend on how the rest of the gradient is split.  The caller changes the seed from
+ * iteration to iteration.
+ *
+ * P: the seed is first mixed into two 31-bit keys, so that neighbouring seeds give unrelated draws:
+ *   z = first output of the SplitMix64 generator started at `seed` (Steele, Lea, Flood 2014):
+ *       z = seed + 0x9E3779B97F4A7C15;  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9;
+ *       z = (z ^ (z >> 27)) * 0x94D049BB133111EB;  z = z ^ (z >> 31)      (64-bit unsigned arithmetic)
+ *   s0 = z mod 2^31,  s1 = (z >> 32) mod 2^31
+ * then, with M = 2^31 - 1, on 32-bit unsigned arithmetic:
+ *   x = (i + s0) & M
+ *   x ^= x >> 16;  x = (x * 0x7FEB352D) & M
+ *   x ^= x >> 15;  x = (x * 0x046CA68B) & M
+ *   x ^= x >> 16;  x = (x + s1) & M
+ *   x ^= x >> 14;  x = (x * 0x2C1B3C6D) & M
+ *   x ^= x >> 15;  x = (x * 0x297A2D39) & M
+ *   x ^= x >> 15
+ * Every step (adding a constant, multiplying by an odd constant, xor with a right shift) is a bijection
+ * of [0, 2^31).
+ */
+uint64_t oracle_splitmix64_first(uint64_t seed)
+{
+    uint64_t z = seed + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+uint32_t oracle_randomk_priority(uint64_t seed, uint32_t i)
+{
+    const uint32_t M = 0x7FFFFFFFu;
+    const uint64_t z = oracle_splitmix64_first(seed);
+    const uint32_t s0 = (uint32_t)(z & M), s1 = (uint32_t)((z >> 32) & M);
+    uint32_t x = (i + s0) & M;
+    x ^= x >> 16; x = (x * 0x7FEB352Du) & M;
+    x ^= x >> 15; x = (x * 0x046CA68Bu) & M;
+    x ^= x >> 16; x = (x + s1) & M;
+    x ^= x >> 14; x = (x * 0x2C1B3C6Du) & M;
+    x ^= x >> 15; x = (x * 0x297A2D39u) & M;
+    x ^= x >> 15;
+    return x;
+}
+
+/* One tensor of a Random-k call: as compress_one, ordered by priority instead of magnitude. */
+static int randomk_one(const float* grad, float* residual, int64_t base, int64_t n, uint64_t seed,
+                       const double* cf_list, int n_cf, int commit,
+                       int32_t* out_idx, float* out_val, int64_t* n_out, double* stats)
+{
+    entry_t* order = (entry_t*)malloc((size_t)n * sizeof(entry_t));
+    if (!order) return ORACLE_NOMEM;
+    double ss_dense = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float a = residual[base + i] + grad[base + i];  /* error feedback, one binary32 add */
+        residual[base + i] = a;
+        ss_dense += (double)a * (double)a;
+        order[i].mag = oracle_randomk_priority(seed, (uint32_t)(base + i));
+        order[i].pos = (uint32_t)i;
+    }
+    qsort(order, (size_t)n, sizeof(entry_t), cmp_entry);  /* highest priority first */
+    for (int j = 0; j < n_cf; ++j) {
+        int64_t k = oracle_k(n, cf_list[j]);
+        double ss_sel = 0.0;
+        for (int64_t r = 0; r < k; ++r) {
+            double v = (double)residual[base + order[r].pos];
+            ss_sel += v * v;
+        }
+        stats[4 * j + 0] = ss_sel;
+        stats[4 * j + 1] = ss_dense;
+        stats[4 * j + 2] = (ss_dense == 0.0) ? 1.0 : ss_sel / ss_dense;
+        stats[4 * j + 3] = (double)order[k - 1].mag;  /* lowest selected priority */
+    }
+    int64_t kc = oracle_k(n, cf_list[commit]);
+    uint32_t* chosen = (uint32_t*)malloc((size_t)kc * sizeof(uint32_t));
+    if (!chosen) {
+        free(order);
+        return ORACLE_NOMEM;
+    }
+    for (int64_t r = 0; r < kc; ++r) chosen[r] = order[r].pos;
+    qsort(chosen, (size_t)kc, sizeof(uint32_t), cmp_u32);
+    for (int64_t r = 0; r < kc; ++r) {
+        int64_t g = base + (int64_t)chosen[r];
+        out_idx[r] = (int32_t)g;
+        out_val[r] = residual[g];
+    }
+    for (int64_t r = 0; r < kc; ++r) residual[base + (int64_t)chosen[r]] = 0.0f;
+    *n_out = kc;
+    free(chosen);
+    free(order);
+    return ORACLE_OK;
+}
+
+/*
+ * Arguments as oracle_compress, plus the seed.  out_stats rows are
+ * { ||g_c||^2, ||g_ef||^2, gain, lowest selected priority }.
+ */
+int oracle_randomk_compress(const float* grad, float* residual, int64_t n,
+                            const double* cf_list, int n_cf, int commit, uint64_t seed,
+                            const int64_t* seg_offsets, int n_seg,
+                            int32_t* out_idx, float* out_val, int64_t out_capacity,
+                            int64_t* out_count, double* out_stats)
+{
+    if (!grad || !residual || !cf_list || !out_idx || !out_val || !out_stats) return ORACLE_BAD_ARG;
+    if (n <= 0 || n > 2147483647LL || n_cf < 1 || commit < 0 || commit >= n_cf) return ORACLE_BAD_ARG;
+    for (int j = 0; j < n_cf; ++j)
+        if (!(cf_list[j] >= 1.0) || isinf(cf_list[j])) return ORACLE_BAD_ARG;
+    int64_t flat[2] = {0, n};
+    const int64_t* off = seg_offsets;
+    int ns = n_seg;
+    if (!off || ns <= 0) {
+        off = flat;
+        ns = 1;
+    }
+    if (off[0] != 0 || off[ns] != n) return ORACLE_BAD_ARG;
+    int64_t total = 0;
+    for (int t = 0; t < ns; ++t) {
+        if (off[t + 1] <= off[t]) return ORACLE_BAD_ARG;
+        total += oracle_k(off[t + 1] - off[t], cf_list[commit]);
+    }
+    if (total > out_capacity) return ORACLE_CAPACITY;
+    int64_t written = 0;
+    for (int t = 0; t < ns; ++t) {
+        int64_t got = 0;
+        int rc = randomk_one(grad, residual, off[t], off[t + 1] - off[t], seed, cf_list, n_cf, commit,
+                             out_idx + written, out_val + written, &got,
+                             out_stats + (size_t)t * (size_t)n_cf * 4);
+        if (rc != ORACLE_OK) return rc;
+        written += got;
+    }
+    if (out_count) *out_count = written;
+    return ORACLE_OK;
+}

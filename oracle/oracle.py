@@ -49,6 +49,12 @@ def _load():
         lib.oracle_decompress_accumulate.argtypes = [p, p, p, i32, i64, p]
         lib.oracle_commit.restype = i32
         lib.oracle_commit.argtypes = [p, i64, p, i64]
+        lib.oracle_splitmix64_first.restype = ctypes.c_uint64
+        lib.oracle_splitmix64_first.argtypes = [ctypes.c_uint64]
+        lib.oracle_randomk_priority.restype = ctypes.c_uint32
+        lib.oracle_randomk_priority.argtypes = [ctypes.c_uint64, ctypes.c_uint32]
+        lib.oracle_randomk_compress.restype = i32
+        lib.oracle_randomk_compress.argtypes = [p, p, i64, p, i32, i32, ctypes.c_uint64, p, i32, p, p, i64, p, p]
         lib.oracle_recompress.restype = i32
         lib.oracle_recompress.argtypes = [p, p, i64, dbl, p, i64, p, i32, p, p, i64, p, p]
         _lib = lib
@@ -152,3 +158,44 @@ def recompress(idx1: np.ndarray, val1: np.ndarray, cf_rel: float, residual=None,
         raise RuntimeError(f"oracle_recompress failed with code {rc}")
     assert count.value == cap
     return out_idx, out_val, stats
+
+
+def splitmix64_first(seed: int) -> int:
+    """First output of the SplitMix64 generator started at ``seed`` (the seed mixing of Random-k)."""
+    return int(_load().oracle_splitmix64_first(int(seed) & 0xFFFFFFFFFFFFFFFF))
+
+
+def randomk_priority(seed: int, i: int) -> int:
+    """Priority of index i under the seed (Random-k; the keyed 31-bit bijection of the oracle's header)."""
+    return int(_load().oracle_randomk_priority(int(seed) & 0xFFFFFFFFFFFFFFFF, int(i)))
+
+
+def randomk_compress(grad: np.ndarray, residual: np.ndarray, cf_list, seed: int, commit: int = 0, seg_offsets=None):
+    """Random-k with error feedback (Sec. II-C); same conventions as ``compress``.
+
+    Returns ``(idx, val, stats)``; a stats row is ``(||g_c||^2, ||g_ef||^2, gain, lowest selected priority)``.
+    """
+    lib = _load()
+    assert grad.dtype == np.float32 and residual.dtype == np.float32
+    assert grad.flags.c_contiguous and residual.flags.c_contiguous
+    n = grad.size
+    cfs = np.ascontiguousarray(np.asarray(cf_list, dtype=np.float64))
+    n_cf = cfs.size
+    if seg_offsets is None:
+        off, n_seg, rows = None, 0, 1
+        cap = topk_count(n, cfs[commit])
+    else:
+        off = np.ascontiguousarray(np.asarray(seg_offsets, dtype=np.int64))
+        n_seg = rows = off.size - 1
+        cap = sum(topk_count(int(off[t + 1] - off[t]), cfs[commit]) for t in range(n_seg))
+    idx = np.empty(cap, dtype=np.int32)
+    val = np.empty(cap, dtype=np.float32)
+    stats = np.zeros((rows, n_cf, 4), dtype=np.float64)
+    count = ctypes.c_int64(0)
+    rc = lib.oracle_randomk_compress(_ptr(grad), _ptr(residual), n, _ptr(cfs), n_cf, int(commit),
+                                     int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(off) if off is not None else None, n_seg,
+                                     _ptr(idx), _ptr(val), cap, ctypes.byref(count), _ptr(stats))
+    if rc != 0:
+        raise RuntimeError(f"oracle_randomk_compress failed with code {rc}")
+    assert count.value == cap
+    return idx, val, stats

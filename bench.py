@@ -186,7 +186,7 @@ def main():
                    "n": n, "cf": cf, "k": k, "workers_decompressed": N_WORKERS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "stream_kernel<0> (mode SM_EF: error feedback + candidate collection)",
+                     "kernel": "stream_kernel<0, false> (SM_EF, Top-k keys: error feedback + candidate collection)",
                      "kernel_ms": stream_ms, "algorithmic_bytes_per_launch": ALGO_BYTES_PER_ELEMENT * n},
         "compress_only": {"ms": compress_ms, "dense_gradient_GBps": 4.0 * n / (compress_ms * 1e-3) / 1e9,
                           "elements_per_s": n / (compress_ms * 1e-3),

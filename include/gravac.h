@@ -103,6 +103,35 @@ int gravac_compress(const float* grad, float* residual, int64_t n,
                     unsigned flags, void* stream);
 
 /*
+ * Random-k with error feedback (Sec. II-C names it as the sparsifier with negligible compression
+ * overhead; the paper runs the controller on top of it in Sec. IV-B).  Everything is as in gravac_compress
+ * (error feedback, k = ceil(n_t / CF) per tensor, message layout, residual update, gain for every CF of
+ * the list, layerwise mode, workspace, flags) except which k entries are kept: every index i of the flat
+ * gradient gets a priority P(seed, i), a keyed bijection of the 31-bit integers, and a tensor keeps its
+ * k entries of highest priority.  No two indices share a priority; selections for several CFs under one
+ * seed are nested; the draw does not depend on how the gradient is split into tensors.  The caller
+ * changes the seed from iteration to iteration (and uses the same seed on every worker if all workers
+ * should keep the same indices).
+ *
+ *   P(seed, i):  z = seed + 0x9E3779B97F4A7C15; z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9;
+ *                z = (z ^ (z >> 27)) * 0x94D049BB133111EB; z ^= z >> 31        (64-bit: SplitMix64's first output)
+ *                s0 = z mod 2^31, s1 = (z >> 32) mod 2^31, M = 2^31 - 1, then on 32-bit unsigned arithmetic
+ *                x = (i + s0) & M;  x ^= x >> 16; x = (x * 0x7FEB352D) & M;  x ^= x >> 15; x = (x * 0x046CA68B) & M;
+ *                x ^= x >> 16; x = (x + s1) & M;  x ^= x >> 14; x = (x * 0x2C1B3C6D) & M;
+ *                x ^= x >> 15; x = (x * 0x297A2D39) & M;  x ^= x >> 15;  P = x
+ *
+ *   out_stats   device, double[max(n_seg,1)][n_cf][4]: { ||g_c||^2, ||g_ef||^2, gain, lowest selected priority }.
+ *   flags       GRAVAC_FLAG_REUSE_THRESHOLDS is ignored (the bounds of a random draw follow from k alone).
+ */
+int gravac_randomk_compress(const float* grad, float* residual, int64_t n,
+                            const double* cf_list, int n_cf, int commit, uint64_t seed,
+                            const int64_t* seg_offsets, int n_seg,
+                            int32_t* out_idx, float* out_val, int64_t out_capacity,
+                            int64_t* out_count, double* out_stats,
+                            void* workspace, size_t workspace_bytes,
+                            unsigned flags, void* stream);
+
+/*
  * Multi-level compression (Sec. IV-C): the second-level Top-k.  Given the level-1 message
  * (idx1, val1) that gravac_compress emitted at CF theta1, select the k2 = ceil(k1 / cf_rel) entries of
  * largest |val1| (ties to the lower index, i.e. the earlier position), which is the message a direct

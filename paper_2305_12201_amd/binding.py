@@ -26,7 +26,7 @@ FLAG_PROFILE = 2
 FLAG_REUSE_THRESHOLDS = 4
 
 EXPORTS = (
-    "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_recompress", "gravac_commit",
+    "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_randomk_compress", "gravac_recompress", "gravac_commit",
     "gravac_decompress_accumulate",
     "gravac_read_status", "gravac_profile_read", "gravac_strerror",
     "gravac_controller_create", "gravac_controller_destroy", "gravac_controller_candidates",
@@ -76,6 +76,9 @@ def lib() -> ctypes.CDLL:
         L.gravac_compress.restype = i32
         L.gravac_compress.argtypes = [vp, vp, i64, vp, i32, i32, vp, i32, vp, vp, i64, vp, vp, vp,
                                       ctypes.c_size_t, u32, vp]
+        L.gravac_randomk_compress.restype = i32
+        L.gravac_randomk_compress.argtypes = [vp, vp, i64, vp, i32, i32, ctypes.c_uint64, vp, i32, vp, vp, i64, vp, vp, vp,
+                                              ctypes.c_size_t, u32, vp]
         L.gravac_recompress.restype = i32
         L.gravac_recompress.argtypes = [vp, vp, i64, dbl, vp, i32, vp, i64, vp, vp, i64, vp, vp, vp,
                                         ctypes.c_size_t, u32, vp]
@@ -154,6 +157,25 @@ def gravac_compress(grad, residual, cf_list, commit=0, seg_offsets=None, *, out_
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), int(flags), _stream_handle(stream))
     if rc != OK:
         raise GravacError(rc, "gravac_compress")
+
+
+def gravac_randomk_compress(grad, residual, cf_list, seed, commit=0, seg_offsets=None, *, out_idx, out_val,
+                            out_count=None, out_stats, workspace, flags=0, stream=None) -> None:
+    """``gravac_randomk_compress`` of the C ABI on torch device tensors (asynchronous on ``stream``)."""
+    cfs = np.ascontiguousarray(np.asarray(cf_list, dtype=np.float64))
+    if seg_offsets is None:
+        seg_ptr, n_seg = None, 0
+    else:
+        seg = np.ascontiguousarray(np.asarray(seg_offsets, dtype=np.int64))
+        seg_ptr, n_seg = seg.ctypes.data_as(ctypes.c_void_p), seg.size - 1
+    rc = lib().gravac_randomk_compress(
+        _dev_ptr(grad, torch.float32), _dev_ptr(residual, torch.float32), grad.numel(),
+        cfs.ctypes.data_as(ctypes.c_void_p), cfs.size, int(commit), int(seed) & 0xFFFFFFFFFFFFFFFF, seg_ptr, n_seg,
+        _dev_ptr(out_idx, torch.int32), _dev_ptr(out_val, torch.float32), out_idx.numel(),
+        _dev_ptr(out_count, torch.int64), _dev_ptr(out_stats, torch.float64),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), int(flags), _stream_handle(stream))
+    if rc != OK:
+        raise GravacError(rc, "gravac_randomk_compress")
 
 
 def gravac_recompress(idx1, val1, cf_rel, seg_counts=None, residual=None, *, out_idx, out_val, out_count=None,
@@ -236,6 +258,13 @@ class Compressor:
         gravac_compress(grad, residual, self.cfs, self.commit, self.seg, out_idx=self.out_idx,
                         out_val=self.out_val, out_count=self.out_count, out_stats=self.out_stats,
                         workspace=self.workspace, flags=flags, stream=stream)
+        return self.out_idx, self.out_val, self.out_stats
+
+    def randomk(self, grad, residual, seed, flags=0, stream=None):
+        """The same buffers with Random-k instead of Top-k."""
+        gravac_randomk_compress(grad, residual, self.cfs, seed, self.commit, self.seg, out_idx=self.out_idx,
+                                out_val=self.out_val, out_count=self.out_count, out_stats=self.out_stats,
+                                workspace=self.workspace, flags=flags, stream=stream)
         return self.out_idx, self.out_val, self.out_stats
 
     def status(self) -> dict:

@@ -135,6 +135,8 @@ struct Params {
     float* restore;          // single-source mode: dense residual that gets the unselected values back (or null)
     int64_t n_restore;       // its length
     int single;              // 1 = single-source mode (second-level compression of a message)
+    int random;              // 1 = Random-k: the order is that of a keyed priority of the index, not of |acc|
+    uint32_t rk_s0, rk_s1;   // its two 31-bit keys (from the seed)
     int64_t n;
     int n_seg;  // >= 1
     int n_cf;
@@ -195,6 +197,27 @@ __device__ __forceinline__ int64_t seg_koff(const Params& p, int t) { return is_
 __device__ __forceinline__ int tile_seg(const Params& p, uint32_t u) { return is_flat(p) ? 0 : (int)p.tseg[u]; }
 
 __device__ __forceinline__ uint32_t key_of(float a) { return __float_as_uint(a) & 0x7FFFFFFFu; }
+
+// Random-k: priority of index i, a keyed bijection of the 31-bit integers (adding a constant, multiplying
+// by an odd constant and xor with a right shift are all bijections of [0, 2^31)), so no two indices tie.
+__device__ __forceinline__ uint32_t priority_of(uint32_t s0, uint32_t s1, uint32_t i)
+{
+    const uint32_t M = 0x7FFFFFFFu;
+    uint32_t x = (i + s0) & M;
+    x ^= x >> 16; x = (x * 0x7FEB352Du) & M;
+    x ^= x >> 15; x = (x * 0x046CA68Bu) & M;
+    x ^= x >> 16; x = (x + s1) & M;
+    x ^= x >> 14; x = (x * 0x2C1B3C6Du) & M;
+    x ^= x >> 15; x = (x * 0x297A2D39u) & M;
+    x ^= x >> 15;
+    return x;
+}
+
+// The ordering key of a candidate: from its value (Top-k) or from its index (Random-k).
+__device__ __forceinline__ uint32_t cand_key(const Params& p, int32_t idx, float val)
+{
+    return p.random ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)idx) : key_of(val);
+}
 
 __device__ __forceinline__ uint32_t lanes_below(uint64_t m)
 {
@@ -492,7 +515,7 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
 
     // thread i owns bins 4i .. 4i+3: two words of every block's histogram
     uint32_t h0 = 0, h1 = 0, h2 = 0, h3 = 0;
-    if (!forced && !reuse) {
+    if (!forced && !reuse && !p.random) {
         const uint2* src = (const uint2*)(p.samp_hist + (size_t)sb0 * (SBIN / 2)) + tid;
         for (uint32_t b0 = 0; b0 < nb; b0 += 32) {
             uint2 w[32];
@@ -544,6 +567,15 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
                 hi = (uint64_t)tau_prev + (1u << 19);
 
             }
+            if (p.random) {
+                // priorities are a keyed permutation of the 31-bit integers: the number of a tensor's nt indices
+                // with priority >= x is as good as binomial (nt, 1 - x / 2^31), so the bounds follow from k alone:
+                // x with k + ZMARGIN sqrt(k) + 2 expected above it, and x with k - ZMARGIN sqrt(k) - 2
+                const double k = (double)seg_k(p, t, j), w = ZMARGIN * sqrt(k) + 2.0;
+                const double q_lo = (k + w) / (double)nt, q_hi = (k - w) / (double)nt;
+                lo = q_lo >= 1.0 ? 0u : (uint32_t)floor(2147483648.0 * (1.0 - q_lo));
+                hi = q_hi <= 0.0 ? 2147483648ull : (uint64_t)ceil(2147483648.0 * (1.0 - q_hi));
+            }
             uint32_t s = 0;
             while (((hi > lo ? hi - lo : 0) >> s) > (uint64_t)OVF) ++s;
             if (forced) { lo = NONE; s = 0; }
@@ -577,6 +609,7 @@ struct TileCtx {
     uint32_t run;   // candidates written so far
     double ssd;
     int ncf;
+    uint32_t s0, s1;  // Random-k keys
 };
 
 __device__ __forceinline__ void cand_hist(TileCtx& c, uint32_t key)
@@ -610,14 +643,14 @@ __device__ __forceinline__ void st_stream(v4f v, v4f* q)
 }
 
 // One lane's four consecutive elements a[0..3] at global index g; vm = validity bits.
-template <bool SSD>
+template <bool SSD, bool RND>
 __device__ __forceinline__ void consume(TileCtx& c, const float a[4], int64_t g, unsigned vm)
 {
     uint32_t key[4];
     bool f[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        key[e] = key_of(a[e]);
+        key[e] = RND ? priority_of(c.s0, c.s1, (uint32_t)(g + e)) : key_of(a[e]);
         const bool valid = (vm >> e) & 1u;
         f[e] = valid && key[e] >= c.lo_min;
         if (SSD) {
@@ -695,7 +728,7 @@ struct ExactBounds {
 };
 
 // One sub-tile v, by one wavefront.
-template <int M>
+template <int M, bool RND>
 __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int lane, ExactBounds* xb)
 {
     constexpr bool EF = (M != SM_EXACT);  // a first pass: sums acc^2, takes the bounds from the threshold kernel
@@ -713,6 +746,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
 
     TileCtx c;
     c.ncf = p.n_cf;
+    c.s0 = p.rk_s0; c.s1 = p.rk_s1;
     c.lo_min = NONE;
 #pragma unroll
     for (int j = 0; j < MAXCF; ++j) {
@@ -777,12 +811,14 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
         const TileCands tcs = tile_cands(p, u);
         const uint32_t cnt = tcs.total();
         const float* cv = p.cand_val + (size_t)u * TW;
+        const int32_t* ci = p.cand_idx + (size_t)u * TW;
         for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
             uint32_t kq[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const uint32_t i = i0 + q * 64 + lane;
-                kq[q] = (i < cnt) ? key_of(cv[tcs.slot(i)]) : 0u;
+                const uint32_t sl = (i < cnt) ? tcs.slot(i) : 0u;
+                kq[q] = RND ? priority_of(c.s0, c.s1, (uint32_t)ci[sl]) : key_of(cv[sl]);
             }
 #pragma unroll
             for (int q = 0; q < 8; ++q)
@@ -812,7 +848,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                 const int64_t g = rb + q * ROW + 4 * lane;
                 float a[4];
                 row_finish<M>(p, g, x[q], y[q], m[q], a);
-                consume<EF>(c, a, g, 0xFu);
+                consume<EF, RND>(c, a, g, 0xFu);
             }
             rb += (GV_ROWS - 1) * ROW;
         } else if (full) {
@@ -822,7 +858,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
             float a[4];
             row_load<M>(p, g, x, y, m);
             row_finish<M>(p, g, x, y, m, a);
-            consume<EF>(c, a, g, 0xFu);
+            consume<EF, RND>(c, a, g, 0xFu);
         } else {
             // ragged row: element-wise, guarded
             const int64_t g = rb + 4 * lane;
@@ -848,7 +884,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                     }
                 }
             }
-            consume<EF>(c, a, g, vm);
+            consume<EF, RND>(c, a, g, vm);
         }
     }
 
@@ -868,13 +904,13 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
 
 // First pass (SM_EF, SM_SINGLE): one sub-tile per wavefront, one launch covers the whole gradient.
 // SM_EXACT: a fixed number of wavefronts walks over all tiles (only those of failed segments do any work).
-template <int M>
+template <int M, bool RND>
 __global__ __launch_bounds__(WG) void stream_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
     const uint32_t w = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
     if (M != SM_EXACT) {
-        stream_subtile<M>(p, w, lane, nullptr);
+        stream_subtile<M, RND>(p, w, lane, nullptr);
     } else {
         if (p.status->any_fail == 0) return;
         ExactBounds xb;
@@ -885,7 +921,7 @@ __global__ __launch_bounds__(WG) void stream_kernel(Params p)
             if (kind == FAIL_NONE) continue;
             // FAIL_LIGHT: one call re-bins the candidates of the whole tile; FAIL_FULL: sub-tile by sub-tile
             const int subs = (kind == FAIL_LIGHT) ? 1 : SUB;
-            for (int j = 0; j < subs; ++j) stream_subtile<SM_EXACT>(p, u * SUB + j, lane, &xb);
+            for (int j = 0; j < subs; ++j) stream_subtile<SM_EXACT, RND>(p, u * SUB + j, lane, &xb);
         }
     }
 }
@@ -944,7 +980,11 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
                         // the candidates of the tile are enough
                         const TileCands tcs = tile_cands(p, u);
                         const float* cv = p.cand_val + (size_t)u * TW;
-                        for (uint32_t i = lane; i < tcs.total(); i += 64) atomicAdd(&h[key_of(cv[tcs.slot(i)]) >> 20], 1u);
+                        const int32_t* ci = p.cand_idx + (size_t)u * TW;
+                        for (uint32_t i = lane; i < tcs.total(); i += 64) {
+                            const uint32_t sl = tcs.slot(i);
+                            atomicAdd(&h[cand_key(p, p.random ? ci[sl] : 0, cv[sl]) >> 20], 1u);
+                        }
                     } else {
                         for (int64_t q0 = s0 + lane; q0 < e0; q0 += 64 * 8) {
                             float a[8];
@@ -952,7 +992,7 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
                             for (int r = 0; r < 8; ++r) a[r] = (q0 + r * 64 < e0) ? p.acc[q0 + r * 64] : 0.0f;
 #pragma unroll
                             for (int r = 0; r < 8; ++r)
-                                if (q0 + r * 64 < e0) atomicAdd(&h[key_of(a[r]) >> 20], 1u);
+                                if (q0 + r * 64 < e0) atomicAdd(&h[cand_key(p, (int32_t)(q0 + r * 64), a[r]) >> 20], 1u);
                         }
                     }
                 }
@@ -1077,13 +1117,16 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
     }
     if (!work || cnt == 0) return;
     const float* cv = p.cand_val + (size_t)u * TW;
+    const int32_t* ci = p.cand_idx + (size_t)u * TW;
     for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
         // eight loads in flight per lane; an absent slot gets a key that lies in no bin (base > key)
         uint32_t kq[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const uint32_t i = i0 + q * 64 + lane;
-            kq[q] = (i < cnt) ? key_of(cv[tc.slot(i)]) : 0u;
+            const uint32_t sl = (i < cnt) ? tc.slot(i) : 0u;
+            kq[q] = p.random ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)ci[sl]) : key_of(cv[sl]);
+            if (i >= cnt) kq[q] = 0u;
         }
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
@@ -1225,22 +1268,29 @@ __global__ __launch_bounds__(LWG) void count_kernel(Params p)
     for (int j = 0; j < MAXCF; ++j) ss[j] = 0.0;
     uint32_t g = 0, e = 0;
     const float* cv = p.cand_val + (size_t)u * TW;
+    const int32_t* ci = p.cand_idx + (size_t)u * TW;
+    // Random-k: priorities are distinct, the entry at the threshold is the last one selected and has no
+    // particular magnitude, so its energy is summed here (Top-k adds need * tau^2 in the scan instead)
+    const uint32_t at_tau = p.random ? 1u : 0u;
     for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
         float vq[8];
+        uint32_t kq[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const uint32_t i = i0 + q * 64 + lane;
-            vq[q] = (i < cnt) ? cv[tcs.slot(i)] : 0.0f;
+            const uint32_t sl = (i < cnt) ? tcs.slot(i) : 0u;
+            vq[q] = cv[sl];
+            kq[q] = p.random ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)ci[sl]) : key_of(vq[q]);
         }
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             if (i0 + q * 64 + lane < cnt) {
-                const uint32_t key = key_of(vq[q]);
+                const uint32_t key = kq[q];
                 const double dv = (double)vq[q];
                 g += (key > tc);
                 e += (key == tc);
 #pragma unroll
-                for (int j = 0; j < MAXCF; ++j) if (j < p.n_cf && key > tau[j]) ss[j] += dv * dv;
+                for (int j = 0; j < MAXCF; ++j) if (j < p.n_cf && key + at_tau > tau[j]) ss[j] += dv * dv;
             }
         }
     }
@@ -1364,9 +1414,11 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
     }
     if (tid == 0) {
         const CfState* st = &p.st[id];
-        const double tau = (double)__uint_as_float(st->tau);
+        // fourth statistic: the threshold as a magnitude (Top-k) or as a priority (Random-k)
+        const double tau = p.random ? (double)st->tau : (double)__uint_as_float(st->tau);
         const double ss_dense = dred[0][0];
-        const double ss_sel = dred[1][0] + (double)st->need * tau * tau;  // ties all have magnitude tau
+        // Top-k: the ties all have magnitude tau; Random-k: the count pass has summed the entry at the threshold
+        const double ss_sel = dred[1][0] + (p.random ? 0.0 : (double)st->need * tau * tau);
         double* o = p.out_stats + (size_t)id * GRAVAC_STATS_PER_CF;
         o[0] = ss_sel;
         o[1] = ss_dense;
@@ -1415,7 +1467,7 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const bool live = b0 + r * 64 + lane < cnt;
-            const uint32_t key = key_of(vq[r]);
+            const uint32_t key = cand_key(p, iq[r], vq[r]);
             const bool gt = live && key > tau, eq = live && key == tau;
             const uint64_t me = __ballot(eq);
             const bool sel = gt || (eq && (erun + lanes_below(me)) < take);
@@ -1760,9 +1812,12 @@ int gravac_workspace_bytes(int64_t n, int n_cf, int n_seg, size_t* bytes_out)
 static int compress_impl(const float* grad, float* residual, int64_t n, const double* cf_list, int n_cf, int commit,
                          const int64_t* seg_offsets, int n_seg, int32_t* out_idx, float* out_val, int64_t out_capacity,
                          int64_t* out_count, double* out_stats, void* workspace, size_t workspace_bytes, unsigned flags,
-                         hipStream_t stream, const int32_t* map_idx, float* restore, int64_t n_restore)
+                         hipStream_t stream, const int32_t* map_idx, float* restore, int64_t n_restore,
+                         const uint64_t* seed)
 {
     const bool single = map_idx != nullptr;
+    const bool random = seed != nullptr;
+    if (random) flags &= ~(unsigned)GRAVAC_FLAG_REUSE_THRESHOLDS;  // the bounds of a random draw need no history
     if (!grad || (!single && !residual) || !cf_list || !out_idx || !out_val || !out_stats) return GRAVAC_ERR_INVALID_ARG;
     if (n <= 0 || n > 2147483647LL || n_cf < 1 || n_cf > MAXCF || commit < 0 || commit >= n_cf) return GRAVAC_ERR_INVALID_ARG;
     if (((uintptr_t)grad & 15) || ((uintptr_t)residual & 15) || ((uintptr_t)map_idx & 15)) return GRAVAC_ERR_INVALID_ARG;
@@ -1787,6 +1842,16 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     std::memset(&p, 0, sizeof(p));
     p.grad = grad; p.res = residual; p.acc = single ? grad : residual;
     p.map_idx = map_idx; p.restore = restore; p.n_restore = restore ? n_restore : 0; p.single = single ? 1 : 0;
+    if (random) {
+        // the seed goes through SplitMix64 (its first output for that seed) and gives the two 31-bit keys
+        uint64_t z = *seed + 0x9E3779B97F4A7C15ull;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        p.random = 1;
+        p.rk_s0 = (uint32_t)(z & 0x7FFFFFFFull);
+        p.rk_s1 = (uint32_t)((z >> 32) & 0x7FFFFFFFull);
+    }
     p.n = n; p.n_seg = ns; p.n_cf = n_cf; p.commit = commit; p.flags = flags;
     p.status = (Status*)(ws + L.status);
     p.segs = (const SegInfo*)(ws + L.tables);
@@ -1871,7 +1936,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     {   // signature of the call: FNV-1a over the shape, the k table and the segment table
         uint64_t h = 1469598103934665603ull;
         auto mix = [&](uint64_t x) { for (int b = 0; b < 8; ++b) { h ^= (x >> (8 * b)) & 0xFF; h *= 1099511628211ull; } };
-        mix((uint64_t)n); mix((uint64_t)n_cf); mix((uint64_t)ns); mix(single ? 1u : 0u);
+        mix((uint64_t)n); mix((uint64_t)n_cf); mix((uint64_t)ns); mix((single ? 1u : 0u) | (random ? 2u : 0u));
         for (int j = 0; j < n_cf; ++j) { uint64_t bits; std::memcpy(&bits, &cf_list[j], 8); mix(bits); }
         if (ns > 1) for (int t = 0; t <= ns; ++t) mix((uint64_t)seg_offsets[t]);
         if (h == 0) h = 1;  // 0 marks "no completed call"
@@ -1892,23 +1957,25 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         }
         (void)hipEventRecord(g_ev[0], stream);
     }
-    if (p.n_sample_blocks && !(flags & GRAVAC_FLAG_REUSE_THRESHOLDS))
+    if (p.n_sample_blocks && !random && !(flags & GRAVAC_FLAG_REUSE_THRESHOLDS))
         hipLaunchKernelGGL(sample_kernel, dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
     hipLaunchKernelGGL(threshold_kernel, dim3(ns), dim3(1024), 0, stream, p);
-    if (single) {
+    {
+        // events 1 and 2 take the streaming kernel's own begin and end time stamps
+        void (*kern)(Params) = single ? stream_kernel<SM_SINGLE, false>
+                                      : (random ? stream_kernel<SM_EF, true> : stream_kernel<SM_EF, false>);
         if (prof)
-            hipExtLaunchKernelGGL(stream_kernel<SM_SINGLE>, dim3(sub_grid), dim3(WG), 0, stream, g_ev[1], g_ev[2], 0, p);
+            hipExtLaunchKernelGGL(kern, dim3(sub_grid), dim3(WG), 0, stream, g_ev[1], g_ev[2], 0, p);
         else
-            hipLaunchKernelGGL(stream_kernel<SM_SINGLE>, dim3(sub_grid), dim3(WG), 0, stream, p);
-    } else if (prof) {  // events 1 and 2 take the kernel's own begin and end time stamps
-        hipExtLaunchKernelGGL(stream_kernel<SM_EF>, dim3(sub_grid), dim3(WG), 0, stream, g_ev[1], g_ev[2], 0, p);
-    } else {
-        hipLaunchKernelGGL(stream_kernel<SM_EF>, dim3(sub_grid), dim3(WG), 0, stream, p);
+            hipLaunchKernelGGL(kern, dim3(sub_grid), dim3(WG), 0, stream, p);
     }
     hipLaunchKernelGGL(locate_kernel, dim3((uint32_t)(ns * n_cf)), dim3(256), 0, stream, p);
     // exact route, taken only by segments whose sampled bound failed (the kernels return at once otherwise)
     hipLaunchKernelGGL(coarse_kernel, dim3(tile_grid < XGRID ? tile_grid : XGRID), dim3(WG), 0, stream, p);
-    hipLaunchKernelGGL(stream_kernel<SM_EXACT>, dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
+    if (random)
+        hipLaunchKernelGGL((stream_kernel<SM_EXACT, true>), dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
+    else
+        hipLaunchKernelGGL((stream_kernel<SM_EXACT, false>), dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
     // exact resolution on the candidates, then count and emit
     hipLaunchKernelGGL(refine_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
     hipLaunchKernelGGL(resolve_kernel, dim3(ns * n_cf), dim3(256), 0, stream, p);
@@ -1930,7 +1997,18 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
 {
     if (!residual) return GRAVAC_ERR_INVALID_ARG;
     return compress_impl(grad, residual, n, cf_list, n_cf, commit, seg_offsets, n_seg, out_idx, out_val, out_capacity,
-                         out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v, nullptr, nullptr, 0);
+                         out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v, nullptr, nullptr, 0, nullptr);
+}
+
+int gravac_randomk_compress(const float* grad, float* residual, int64_t n, const double* cf_list, int n_cf, int commit,
+                            uint64_t seed, const int64_t* seg_offsets, int n_seg, int32_t* out_idx, float* out_val,
+                            int64_t out_capacity, int64_t* out_count, double* out_stats, void* workspace,
+                            size_t workspace_bytes, unsigned flags, void* stream_v)
+{
+    if (!residual) return GRAVAC_ERR_INVALID_ARG;
+    return compress_impl(grad, residual, n, cf_list, n_cf, commit, seg_offsets, n_seg, out_idx, out_val, out_capacity,
+                         out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v, nullptr, nullptr, 0,
+                         &seed);
 }
 
 int gravac_recompress(const int32_t* idx1, const float* val1, int64_t k1, double cf_rel, const int64_t* seg_counts,
@@ -1952,7 +2030,7 @@ int gravac_recompress(const int32_t* idx1, const float* val1, int64_t k1, double
     }
     return compress_impl(val1, nullptr, k1, &cf_rel, 1, 0, n_seg > 0 ? off.data() : nullptr, n_seg, out_idx, out_val,
                          out_capacity, out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v,
-                         idx1, residual, n);
+                         idx1, residual, n, nullptr);
 }
 
 int gravac_commit(const int32_t* idx, int64_t count, float* residual, int64_t n, void* stream_v)

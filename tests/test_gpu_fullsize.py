@@ -142,3 +142,70 @@ def test_config5_layerwise_eight_workers_then_decompress():
     binding.gravac_decompress_accumulate(all_idx, all_val, [k] * 8, dense)
     torch.cuda.synchronize()
     assert np.array_equal(dense.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_maximum_size_properties():
+    """n = 2^31 - 1, the largest gradient the int32 indices allow (17 GB of inputs, 17 GB of workspace): the
+    oracle cannot sort that, so the output is checked on the device with the properties that determine it."""
+    n = 2 ** 31 - 1
+    cfs = [1000.0, 100.0]
+    k = binding.gravac_topk_count(n, cfs[0])
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    g = torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, 1e-3, generator=gen)
+    r = torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, 1e-4, generator=gen)
+    g[n - 1] = 5.0                                   # the very last element must be reachable
+    g[12345] = 0.0
+    r[12345] = 0.0
+    acc = g + r                                      # one binary32 add per element, as the kernel does
+    comp = binding.Compressor(n, cfs, 0)
+    idx, val, stats = comp(g, r)
+    torch.cuda.synchronize()
+    st = comp.status()
+    assert st["internal_error"] == 0 and st["any_fallback"] == 0
+    assert int(comp.out_count.item()) == k == idx.numel()
+    i64 = idx.to(torch.int64)
+    assert int(i64[0]) >= 0 and int(i64[-1]) == n - 1 and bool((i64[1:] > i64[:-1]).all())
+    assert torch.equal(val.view(torch.int32), acc[i64].view(torch.int32))
+    # message + residual = acc bit for bit, selected slots +0
+    assert bool((r[i64].view(torch.int32) == 0).all())
+    rebuilt = r.clone()
+    rebuilt[i64] = val
+    assert torch.equal(rebuilt.view(torch.int32), acc.view(torch.int32))
+    del rebuilt
+    # the threshold: no unselected magnitude above it, fewer than k above it, at least k at or above it
+    s = stats.cpu().numpy()
+    tau = float(val.abs().min())
+    assert s[0, 0, 3] == tau
+    assert float(r.abs().max()) <= tau
+    mag = acc.abs()
+    above = int(torch.count_nonzero(mag > tau))
+    at = torch.nonzero(mag == tau).flatten()
+    assert above < k <= above + at.numel()
+    # ties at the threshold go to the lowest indices
+    taken = torch.isin(at, i64)
+    need = k - above
+    assert int(taken.sum()) == need and bool(taken[:need].all())
+    # statistics of both CFs (the second one from its own threshold)
+    ss_all = 0.0
+    ss_sel0 = float((val.double() ** 2).sum())
+    step = 1 << 28
+    tau1 = float(s[0, 1, 3])
+    k1 = binding.gravac_topk_count(n, cfs[1])
+    above1, ss_above1 = 0, 0.0
+    for a in range(0, n, step):
+        chunk = acc[a:a + step].double()
+        ss_all += float((chunk * chunk).sum())
+        m = chunk.abs() > tau1
+        above1 += int(m.sum())
+        ss_above1 += float((chunk[m] ** 2).sum())
+    assert above1 < k1
+    ss_sel1 = ss_above1 + (k1 - above1) * tau1 * tau1
+    np.testing.assert_allclose(s[0, 0, :3], [ss_sel0, ss_all, ss_sel0 / ss_all], rtol=STAT_RTOL)
+    np.testing.assert_allclose(s[0, 1, :3], [ss_sel1, ss_all, ss_sel1 / ss_all], rtol=STAT_RTOL)
+    del mag, acc, g
+    # decompression of two copies of the message into a zeroed buffer of the same size
+    dense = torch.zeros(n, dtype=torch.float32, device="cuda")
+    binding.gravac_decompress_accumulate(torch.cat([idx, idx]), torch.cat([val, val]), [k, k], dense)
+    torch.cuda.synchronize()
+    assert torch.equal(dense[i64], val + val)
+    assert int(torch.count_nonzero(dense)) == int(torch.count_nonzero(val))

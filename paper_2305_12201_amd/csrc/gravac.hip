@@ -285,45 +285,47 @@ __device__ __forceinline__ TileCands tile_cands(const Params& p, uint32_t u)
 // One wavefront finds the bin of a 2048-bin histogram (given as `copies` arrays of NBIN counts that
 // are added up) that holds the k-th largest entry: scanning from the top bin down,
 // above < k <= above + count.  Every lane gets the result; bin == NONE if the histogram holds
-// fewer than k entries.  hist must be 16-byte aligned.
+// fewer than k entries.  hist must be 16-byte aligned.  Two passes, so that no lane has to keep its 32 bins
+// in registers (this runs inside kernels whose occupancy matters): first the lane totals, which single out the
+// lane whose bins hold the crossing, then that lane's 32 bins, one per lane.
 __device__ __forceinline__ void wave_locate_bin(const uint32_t* hist, int copies, const uint32_t* top_extra, uint32_t k,
                                                 uint32_t& bin, uint32_t& above, uint32_t& count)
 {
     const int lane = threadIdx.x & 63;
     // top_extra: 64 more counts for the last bin, one per cache line (stride 32 words), or null
-    uint32_t extra = top_extra ? top_extra[lane * 32] : 0u;
-    uint32_t h[32];
-#pragma unroll
-    for (int q = 0; q < 32; ++q) h[q] = 0;
+    const uint32_t extra = wave_sum(top_extra ? top_extra[lane * 32] : 0u);
+    uint32_t mine = 0;  // lane l owns bins 32 l .. 32 l + 31
     for (int r = 0; r < copies; ++r) {
         const uint4* hv = (const uint4*)(hist + (size_t)r * NBIN + 32 * lane);
-#pragma unroll
+#pragma unroll 2
         for (int q = 0; q < 8; ++q) {
             const uint4 v = hv[q];
-            h[4 * q] += v.x; h[4 * q + 1] += v.y; h[4 * q + 2] += v.z; h[4 * q + 3] += v.w;
+            mine += v.x + v.y + v.z + v.w;
         }
     }
-    extra = wave_sum(extra);
-    if (lane == 63) h[31] += extra;
-    uint32_t mine = 0;
-#pragma unroll
-    for (int q = 0; q < 32; ++q) mine += h[q];
+    if (lane == 63) mine += extra;
     const uint32_t incl = wave_scan(mine);
     const uint32_t total = __shfl(incl, 63, 64);
-    uint32_t ab = total - incl;  // entries in the bins of higher lanes
-    uint32_t fb = NONE, fa = 0, fc = 0;
-#pragma unroll
-    for (int q = 31; q >= 0; --q) {
-        if (ab < k && ab + h[q] >= k) { fb = 32 * lane + q; fa = ab; fc = h[q]; }
-        ab += h[q];
+    const uint32_t ab = total - incl;  // entries in the bins of higher lanes
+    const uint64_t m = __ballot(ab < k && ab + mine >= k);
+    if (m == 0ull) { bin = NONE; above = 0; count = 0; return; }
+    const int owner = __ffsll((unsigned long long)m) - 1;
+    const uint32_t ab_owner = __shfl(ab, owner, 64);
+    // lanes 0..31 each take one of the owner's bins
+    uint32_t c = 0;
+    if (lane < 32) {
+        for (int r = 0; r < copies; ++r) c += hist[(size_t)r * NBIN + 32 * owner + lane];
+        if (owner == 63 && lane == 31) c += extra;
     }
-    const uint64_t m = __ballot(fb != NONE);
-    if (m) {
-        const int src = __ffsll((unsigned long long)m) - 1;
-        bin = __shfl(fb, src, 64); above = __shfl(fa, src, 64); count = __shfl(fc, src, 64);
-    } else {
-        bin = NONE; above = 0; count = 0;
-    }
+    // entries of the owner's bins above bin `lane`: suffix sum over lanes lane+1 .. 31
+    const uint32_t inc = wave_scan(c);                       // lanes >= 32 contribute 0
+    const uint32_t sum32 = __shfl(inc, 31, 64);
+    const uint32_t higher = ab_owner + (sum32 - inc);
+    const uint64_t f = __ballot(lane < 32 && higher < k && higher + c >= k);
+    const int src = 63 - __builtin_clzll((unsigned long long)f);  // exactly one lane
+    bin = 32 * owner + src;
+    above = __shfl(higher, src, 64);
+    count = __shfl(c, src, 64);
 }
 
 // The same search by four wavefronts (threads q = 0..255 of a 256-thread team; `q` is the thread's number
@@ -1087,31 +1089,40 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
     const bool redo = p.status->any_fail != 0 && p.seg[t].fail != 0;
     const bool first = redo && (u == seg_tile0(p, t));
     if (cnt == 0 && !first) return;
+    // exact route: the plan comes from the rebuilt candidate histogram.  A plain loop whose results go through
+    // LDS, so that the search does not inflate the register count of the common path.
+    __shared__ uint32_t rp[LWAVES][MAXCF][3];
+    const int wib = threadIdx.x >> 6;
+    if (redo) {
+        for (int j = 0; j < p.n_cf; ++j) {
+            CfState* st = &p.st[(size_t)t * p.n_cf + j];
+            uint32_t b, above, c;
+            wave_locate_bin(p.hist1 + ((size_t)t * p.n_cf + j) * REP * NBIN, REP, p.ovfc + ((size_t)t * p.n_cf + j) * 64 * 32,
+                            st->k, b, above, c);
+            const BinPlan q = plan_bin(st->lo, st->s, b, above, c);
+            if (lane == 0) {
+                rp[wib][j][0] = q.mode; rp[wib][j][1] = q.base; rp[wib][j][2] = q.open;
+                if (first) {
+                    store_plan(st, q);
+                    if (q.mode == MODE_FAIL) p.status->error = 1;  // the exact route cannot fail
+                    if (j == 0 && p.seg[t].fail == FAIL_LIGHT) atomicAdd(&p.status->n_light, 1);
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // rp is read back by the same wavefront
+    }
     uint32_t mode[MAXCF], base[MAXCF], span[MAXCF];
     bool work = false;
 #pragma unroll
     for (int j = 0; j < MAXCF; ++j) {
         mode[j] = MODE_RESOLVED; base[j] = 0; span[j] = 0;
         if (j < p.n_cf) {
-            CfState* st = &p.st[(size_t)t * p.n_cf + j];
-            BinPlan q;
-            uint32_t s = st->s;
-            if (redo) {
-                uint32_t b, above, c;
-                wave_locate_bin(p.hist1 + ((size_t)t * p.n_cf + j) * REP * NBIN, REP, p.ovfc + ((size_t)t * p.n_cf + j) * 64 * 32,
-                                st->k, b, above, c);
-                q = plan_bin(st->lo, s, b, above, c);
-                if (first && lane == 0) {
-                    store_plan(st, q);
-                    if (q.mode == MODE_FAIL) p.status->error = 1;  // the exact route cannot fail
-                    if (j == 0 && p.seg[t].fail == FAIL_LIGHT) atomicAdd(&p.status->n_light, 1);
-                }
-            } else {
-                q.mode = st->mode; q.base = st->base; q.open = st->open;
-            }
-            mode[j] = q.mode;
-            base[j] = q.base;
-            span[j] = q.open ? NONE : ((1u << s) - 1u);  // in the bin <=> key - base <= span
+            const CfState* st = &p.st[(size_t)t * p.n_cf + j];
+            const uint32_t s = st->s;
+            uint32_t open;
+            if (redo) { mode[j] = rp[wib][j][0]; base[j] = rp[wib][j][1]; open = rp[wib][j][2]; }
+            else { mode[j] = st->mode; base[j] = st->base; open = st->open; }
+            span[j] = open ? NONE : ((1u << s) - 1u);  // in the bin <=> key - base <= span
             work |= (mode[j] == MODE_GATHER || mode[j] == MODE_HIST);
         }
     }

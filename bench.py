@@ -97,6 +97,7 @@ def main():
     out_stats = torch.zeros(1, 1, 4, dtype=torch.float64, device=dev)
     residual = torch.zeros(n, dtype=torch.float32, device=dev)
     dense = torch.zeros(n, dtype=torch.float32, device=dev)
+    dws = torch.empty(binding.gravac_decompress_workspace_bytes(N_WORKERS, n), dtype=torch.uint8, device=dev)
 
     def compress(grad, res, slot, flags=0):
         binding.gravac_compress(grad, res, [cf], 0, None, out_idx=msg_idx[slot * k:(slot + 1) * k],
@@ -114,7 +115,7 @@ def main():
 
     def step(i, flags=0):
         compress(grads[i % N_GRADS], residual, 0, flags)
-        binding.gravac_decompress_accumulate(msg_idx, msg_val, counts, dense)
+        binding.gravac_decompress_accumulate(msg_idx, msg_val, counts, dense, workspace=dws)
 
     # steady-state iterative use: a call reuses the previous call's thresholds.  The first calls of an
     # error-feedback run are a transient (the leftover builds up, the threshold climbs by more than the reuse

@@ -27,7 +27,7 @@ FLAG_REUSE_THRESHOLDS = 4
 
 EXPORTS = (
     "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_randomk_compress", "gravac_recompress", "gravac_commit",
-    "gravac_decompress_accumulate",
+    "gravac_decompress_workspace_bytes", "gravac_decompress_accumulate",
     "gravac_read_status", "gravac_profile_read", "gravac_strerror",
     "gravac_controller_create", "gravac_controller_destroy", "gravac_controller_candidates",
     "gravac_controller_decide", "gravac_controller_finish_iteration", "gravac_controller_throughput",
@@ -85,7 +85,9 @@ def lib() -> ctypes.CDLL:
         L.gravac_commit.restype = i32
         L.gravac_commit.argtypes = [vp, i64, vp, i64, vp]
         L.gravac_decompress_accumulate.restype = i32
-        L.gravac_decompress_accumulate.argtypes = [vp, vp, vp, i32, i64, vp, vp]
+        L.gravac_decompress_accumulate.argtypes = [vp, vp, vp, i32, i64, vp, vp, ctypes.c_size_t, vp]
+        L.gravac_decompress_workspace_bytes.restype = i32
+        L.gravac_decompress_workspace_bytes.argtypes = [i32, i64, ctypes.POINTER(ctypes.c_size_t)]
         L.gravac_read_status.restype = i32
         L.gravac_read_status.argtypes = [vp, vp, vp]
         L.gravac_profile_read.restype = i32
@@ -204,12 +206,23 @@ def gravac_commit(idx, residual, *, stream=None) -> None:
         raise GravacError(rc, "gravac_commit")
 
 
-def gravac_decompress_accumulate(idx, val, counts, dense_out, *, stream=None) -> None:
-    """``gravac_decompress_accumulate`` of the C ABI on torch device tensors."""
+def gravac_decompress_workspace_bytes(W: int, n: int) -> int:
+    out = ctypes.c_size_t(0)
+    rc = lib().gravac_decompress_workspace_bytes(int(W), int(n), ctypes.byref(out))
+    if rc != OK:
+        raise GravacError(rc, "gravac_decompress_workspace_bytes")
+    return int(out.value)
+
+
+def gravac_decompress_accumulate(idx, val, counts, dense_out, *, workspace=None, stream=None) -> None:
+    """``gravac_decompress_accumulate`` of the C ABI on torch device tensors (``workspace``: a uint8 device
+    tensor of at least ``gravac_decompress_workspace_bytes`` bytes, or None)."""
     cnt = np.ascontiguousarray(np.asarray(counts, dtype=np.int64))
     rc = lib().gravac_decompress_accumulate(
         _dev_ptr(idx, torch.int32), _dev_ptr(val, torch.float32), cnt.ctypes.data_as(ctypes.c_void_p),
-        cnt.size, dense_out.numel(), _dev_ptr(dense_out, torch.float32), _stream_handle(stream))
+        cnt.size, dense_out.numel(), _dev_ptr(dense_out, torch.float32),
+        0 if workspace is None else workspace.data_ptr(),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc != OK:
         raise GravacError(rc, "gravac_decompress_accumulate")
 

@@ -1661,6 +1661,170 @@ __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restri
 }
 
 // ---------------------------------------------------------------------------------------------
+// decompression with a workspace: the tile boundaries of every message are computed once, by one thread
+// per pair, instead of being searched for by every tile.
+//   bounds[w][t], t = 0 .. ntile: number of pairs of worker w with index below t * DTILE (indices below 0
+//   count as tile 0, indices from ntile * DTILE on as past the last tile), so that tile t's pairs of
+//   worker w are [bounds[w][t], bounds[w][t + 1]) of its message.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int64_t tile_of_index(int32_t x, int64_t ntile)
+{
+    if (x < 0) return 0;
+    const int64_t t = (int64_t)x / DTILE;
+    return t < ntile ? t : ntile;
+}
+
+// grid (pair blocks, workers).  Pair j of a message starts tiles (tile of pair j - 1, tile of pair j]; the last
+// pair also closes all later tiles.  A lane with up to 2 tiles to write does it itself, longer runs (gaps in the
+// message, the tail) are written by the whole wavefront.
+__global__ __launch_bounds__(256) void bounds_kernel(const int32_t* __restrict__ idx, WorkerOffsets wo, int64_t ntile,
+                                                     uint32_t* __restrict__ bounds)
+{
+    const int w = blockIdx.y, lane = threadIdx.x & 63;
+    const int64_t a = wo.at[w], cnt = wo.at[w + 1] - a;
+    uint32_t* bw = bounds + (size_t)w * (size_t)(ntile + 1);
+    const int64_t j0 = ((int64_t)blockIdx.x * 256 + (threadIdx.x & ~63));  // first pair of this wavefront
+    if (cnt == 0) {
+        if (blockIdx.x == 0)
+            for (int64_t t = threadIdx.x; t <= ntile; t += 256) bw[t] = 0;
+        return;
+    }
+    if (j0 >= cnt) return;
+    const int64_t j = j0 + lane;
+    const bool live = j < cnt;
+    int64_t t_prev = -1, t_cur = -1;  // this lane writes bw[t] = j for t in (t_prev, t_cur]
+    if (live) {
+        t_cur = tile_of_index(idx[a + j], ntile);
+        t_prev = (j == 0) ? -1 : tile_of_index(idx[a + j - 1], ntile);
+    }
+    const int64_t gap = t_cur - t_prev;
+    if (live && gap > 0 && gap <= 2) {
+        bw[t_prev + 1] = (uint32_t)j;
+        if (gap == 2) bw[t_prev + 2] = (uint32_t)j;
+    }
+    uint64_t big = __ballot(live && gap > 2);
+    while (big) {
+        const int src = __ffsll((unsigned long long)big) - 1;
+        big &= big - 1;
+        const int64_t tp = __shfl(t_prev, src, 64), tc = __shfl(t_cur, src, 64);
+        const uint32_t v = (uint32_t)(j0 + src);
+        for (int64_t t = tp + 1 + lane; t <= tc; t += 64) bw[t] = v;
+    }
+    // the wavefront that holds the last pair closes the tiles after it
+    if (j0 + 64 >= cnt) {
+        const int64_t tl = __shfl(t_cur, (int)(cnt - 1 - j0), 64);
+        for (int64_t t = tl + 1 + lane; t <= ntile; t += 64) bw[t] = (uint32_t)cnt;
+    }
+}
+
+__global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __restrict__ idx, const float* __restrict__ val,
+                                                            WorkerOffsets wo, int W, int64_t n, float* dense,
+                                                            const uint32_t* __restrict__ bounds)
+{
+    __shared__ float acc[DTILE];
+    __shared__ int64_t lo[DGROUP];
+    __shared__ uint32_t cntw[DGROUP];
+    __shared__ int32_t first[DMAXW], last[DMAXW];   // smallest and largest index of every worker's message
+    const int tid = threadIdx.x;
+    const bool vec = (((uintptr_t)dense) & 15) == 0;  // float4 access needs a 16-byte aligned buffer
+    if (tid < W) {
+        const int64_t a = wo.at[tid], b = wo.at[tid + 1];
+        first[tid] = (b > a) ? idx[a] : 0x7FFFFFFF;
+        last[tid] = (b > a) ? idx[b - 1] : -1;
+    }
+    __syncthreads();
+    const int64_t ntile = (n + DTILE - 1) / DTILE;
+    for (int64_t tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
+        const int64_t base = tile * DTILE;
+        const int len = (int)((n - base < DTILE) ? n - base : DTILE);
+        bool loaded = false;
+        for (int w0 = 0; w0 < W; w0 += DGROUP) {
+            const int wn = (W - w0 < DGROUP) ? W - w0 : DGROUP;
+            // can any message of this group touch the tile at all?
+            bool maybe = false;
+            for (int w = 0; w < wn; ++w)
+                maybe |= ((int64_t)first[w0 + w] < base + len) && ((int64_t)last[w0 + w] >= base);
+            if (!maybe) continue;
+            __syncthreads();  // lo / cntw of the previous group or tile are no longer read
+            if (tid < wn) {
+                const uint32_t* bw = bounds + (size_t)(w0 + tid) * (size_t)(ntile + 1) + tile;
+                // clamped to the message, so that no read can leave it even if the indices were not ascending
+                const uint32_t cw = (uint32_t)(wo.at[w0 + tid + 1] - wo.at[w0 + tid]);
+                uint32_t l = bw[0], h = bw[1];
+                l = l < cw ? l : cw;
+                h = h < l ? l : (h < cw ? h : cw);
+                lo[tid] = wo.at[w0 + tid] + l;
+                cntw[tid] = h - l;
+            }
+            __syncthreads();
+            uint32_t pre[DGROUP + 1];
+            pre[0] = 0;
+#pragma unroll
+            for (int w = 0; w < DGROUP; ++w) pre[w + 1] = pre[w] + (w < wn ? cntw[w] : 0u);
+            const uint32_t total = pre[DGROUP];
+            if (total == 0) continue;  // no message of this group touches the tile
+            if (!loaded) {
+                for (int i = tid * 4; i < len; i += 256 * 4) {
+                    if (vec && i + 4 <= len) {
+                        const v4f v = *(const v4f*)(dense + base + i);
+                        acc[i] = v.x; acc[i + 1] = v.y; acc[i + 2] = v.z; acc[i + 3] = v.w;
+                    } else {
+                        for (int e = 0; e < 4 && i + e < len; ++e) acc[i + e] = dense[base + i + e];
+                    }
+                }
+                loaded = true;
+            }
+            for (uint32_t s0 = 0; s0 < total; s0 += 256 * DBATCH) {
+                int pj[DBATCH], pw[DBATCH];
+                float pv[DBATCH];
+#pragma unroll
+                for (int q = 0; q < DBATCH; ++q) {
+                    const uint32_t slot = s0 + q * 256 + tid;
+                    pw[q] = -1; pj[q] = 0; pv[q] = 0.0f;
+                    if (slot < total) {
+                        int w = 0;
+#pragma unroll
+                        for (int x = 1; x < DGROUP; ++x) w += (slot >= pre[x]);
+                        uint32_t pb = 0;
+#pragma unroll
+                        for (int x = 1; x < DGROUP; ++x) if (x == w) pb = pre[x];
+                        const int64_t at = lo[w] + (int64_t)(slot - pb);
+                        const int64_t j = (int64_t)idx[at] - base;  // index and value are loaded together
+                        const float x = val[at];
+                        if (j >= 0 && j < len) { pw[q] = w; pj[q] = (int)j; pv[q] = x; }
+                    }
+                }
+                // workers present in this batch: from the worker of its first slot to that of its last
+                const uint32_t end = (s0 + 256 * DBATCH < total ? s0 + 256 * DBATCH : total) - 1;
+                int wmin = 0, wmax = 0;
+#pragma unroll
+                for (int x = 1; x < DGROUP; ++x) { wmin += (s0 >= pre[x]); wmax += (end >= pre[x]); }
+                __syncthreads();  // tile loaded / previous batch applied
+                for (int w = wmin; w <= wmax; ++w) {
+#pragma unroll
+                    for (int q = 0; q < DBATCH; ++q)
+                        if (pw[q] == w) acc[pj[q]] += pv[q];
+                    __syncthreads();
+                }
+            }
+        }
+        if (loaded) {
+            __syncthreads();
+            for (int i = tid * 4; i < len; i += 256 * 4) {
+                if (vec && i + 4 <= len) {
+                    v4f v;
+                    v.x = acc[i]; v.y = acc[i + 1]; v.z = acc[i + 2]; v.w = acc[i + 3];
+                    *(v4f*)(dense + base + i) = v;
+                } else {
+                    for (int e = 0; e < 4 && i + e < len; ++e) dense[base + i + e] = acc[i + e];
+                }
+            }
+            __syncthreads();  // the tile buffer is free again
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 
@@ -2055,8 +2219,17 @@ int gravac_commit(const int32_t* idx, int64_t count, float* residual, int64_t n,
     return GRAVAC_OK;
 }
 
+int gravac_decompress_workspace_bytes(int W, int64_t n, size_t* bytes_out)
+{
+    if (!bytes_out || W < 1 || n <= 0 || n > 2147483647LL) return GRAVAC_ERR_INVALID_ARG;
+    const int64_t ntile = (n + DTILE - 1) / DTILE;
+    const int wn = W < DMAXW ? W : DMAXW;
+    *bytes_out = align_up(sizeof(uint32_t) * (size_t)wn * (size_t)(ntile + 1), 256);
+    return GRAVAC_OK;
+}
+
 int gravac_decompress_accumulate(const int32_t* idx, const float* val, const int64_t* counts, int W, int64_t n,
-                                 float* dense_out, void* stream_v)
+                                 float* dense_out, void* workspace, size_t workspace_bytes, void* stream_v)
 {
     hipStream_t stream = (hipStream_t)stream_v;
     if (!counts || !dense_out || W < 1 || n <= 0 || n > 2147483647LL) return GRAVAC_ERR_INVALID_ARG;
@@ -2066,6 +2239,11 @@ int gravac_decompress_accumulate(const int32_t* idx, const float* val, const int
         total += counts[w];
     }
     if (total > 0 && (!idx || !val)) return GRAVAC_ERR_INVALID_ARG;
+    if (workspace) {
+        size_t need = 0;
+        if (gravac_decompress_workspace_bytes(W, n, &need) != GRAVAC_OK) return GRAVAC_ERR_INVALID_ARG;
+        if (((uintptr_t)workspace & 255) || workspace_bytes < need) return GRAVAC_ERR_WORKSPACE;
+    }
     if (total == 0) return GRAVAC_OK;
     const int64_t ntile = (n + DTILE - 1) / DTILE;
     const uint32_t grid = (uint32_t)(ntile < 1024 ? ntile : 1024);  // 4 workgroups (4 x 32 KiB LDS) on each of 256 CUs
@@ -2073,15 +2251,25 @@ int gravac_decompress_accumulate(const int32_t* idx, const float* val, const int
     for (int w0 = 0; w0 < W; w0 += DMAXW) {
         const int wn = (W - w0 < DMAXW) ? W - w0 : DMAXW;
         WorkerOffsets wo;
-        int64_t group = 0;
+        int64_t group = 0, longest = 0;
         for (int w = 0; w < wn; ++w) {
             wo.at[w] = at + group;
             group += counts[w0 + w];
+            if (counts[w0 + w] > longest) longest = counts[w0 + w];
         }
         for (int w = wn; w <= DMAXW; ++w) wo.at[w] = at + group;
         at += group;
         if (group == 0) continue;
-        hipLaunchKernelGGL(decompress_kernel, dim3(grid), dim3(256), 0, stream, idx, val, wo, wn, n, dense_out);
+        if (workspace) {
+            // tile boundaries of the group's messages first (the workspace is reused from group to group: stream order)
+            const uint32_t pair_blocks = (uint32_t)((longest + 255) / 256);
+            hipLaunchKernelGGL(bounds_kernel, dim3(pair_blocks, (uint32_t)wn), dim3(256), 0, stream, idx, wo, ntile,
+                               (uint32_t*)workspace);
+            hipLaunchKernelGGL(decompress_ws_kernel, dim3(grid), dim3(256), 0, stream, idx, val, wo, wn, n, dense_out,
+                               (const uint32_t*)workspace);
+        } else {
+            hipLaunchKernelGGL(decompress_kernel, dim3(grid), dim3(256), 0, stream, idx, val, wo, wn, n, dense_out);
+        }
     }
     if (hipGetLastError() != hipSuccess) return GRAVAC_ERR_HIP;
     return GRAVAC_OK;

@@ -99,13 +99,13 @@ def test_decompress_rejects_bad_arguments():
     L = binding.lib()
     cnt = np.asarray([5, -1], dtype=np.int64)
     p = cnt.ctypes.data_as(ctypes.c_void_p)
-    assert L.gravac_decompress_accumulate(0x1000, 0x2000, p, 2, 100, 0x3000, None) == binding.ERR_INVALID_ARG
+    assert L.gravac_decompress_accumulate(0x1000, 0x2000, p, 2, 100, 0x3000, None, 0, None) == binding.ERR_INVALID_ARG
     cnt[1] = 1
-    assert L.gravac_decompress_accumulate(0x1000, 0x2000, p, 0, 100, 0x3000, None) == binding.ERR_INVALID_ARG
-    assert L.gravac_decompress_accumulate(0x1000, 0x2000, p, 2, 0, 0x3000, None) == binding.ERR_INVALID_ARG
-    assert L.gravac_decompress_accumulate(0x1000, 0x2000, p, 2, 100, 0, None) == binding.ERR_INVALID_ARG
-    assert L.gravac_decompress_accumulate(0, 0x2000, p, 2, 100, 0x3000, None) == binding.ERR_INVALID_ARG
-    assert L.gravac_decompress_accumulate(0x1000, 0x2000, None, 2, 100, 0x3000, None) == binding.ERR_INVALID_ARG
+    assert L.gravac_decompress_accumulate(0x1000, 0x2000, p, 0, 100, 0x3000, None, 0, None) == binding.ERR_INVALID_ARG
+    assert L.gravac_decompress_accumulate(0x1000, 0x2000, p, 2, 0, 0x3000, None, 0, None) == binding.ERR_INVALID_ARG
+    assert L.gravac_decompress_accumulate(0x1000, 0x2000, p, 2, 100, 0, None, 0, None) == binding.ERR_INVALID_ARG
+    assert L.gravac_decompress_accumulate(0, 0x2000, p, 2, 100, 0x3000, None, 0, None) == binding.ERR_INVALID_ARG
+    assert L.gravac_decompress_accumulate(0x1000, 0x2000, None, 2, 100, 0x3000, None, 0, None) == binding.ERR_INVALID_ARG
 
 
 def test_strerror():

@@ -139,7 +139,9 @@ def test_config5_layerwise_eight_workers_then_decompress():
         all_val[w * k:(w + 1) * k] = comp.out_val
         oracle.decompress_accumulate(ref[0], ref[1], [k], want)   # the oracle's own messages, workers in order
     dense = torch.zeros(n, dtype=torch.float32, device="cuda")
-    binding.gravac_decompress_accumulate(all_idx, all_val, [k] * 8, dense)
+    binding.gravac_decompress_accumulate(all_idx, all_val, [k] * 8, dense,
+                                         workspace=torch.empty(binding.gravac_decompress_workspace_bytes(8, n), dtype=torch.uint8,
+                                                               device="cuda"))
     torch.cuda.synchronize()
     assert np.array_equal(dense.cpu().numpy().view(np.uint32), want.view(np.uint32))
 
@@ -205,7 +207,9 @@ def test_maximum_size_properties():
     del mag, acc, g
     # decompression of two copies of the message into a zeroed buffer of the same size
     dense = torch.zeros(n, dtype=torch.float32, device="cuda")
-    binding.gravac_decompress_accumulate(torch.cat([idx, idx]), torch.cat([val, val]), [k, k], dense)
+    binding.gravac_decompress_accumulate(torch.cat([idx, idx]), torch.cat([val, val]), [k, k], dense,
+                                         workspace=torch.empty(binding.gravac_decompress_workspace_bytes(2, n), dtype=torch.uint8,
+                                                               device="cuda"))
     torch.cuda.synchronize()
     assert torch.equal(dense[i64], val + val)
     assert int(torch.count_nonzero(dense)) == int(torch.count_nonzero(val))

@@ -244,15 +244,20 @@ def _decompress_case(n, ks, seed, offset_elems=0):
     dense = rng.standard_normal(n).astype(np.float32)
     want = dense.copy()
     oracle.decompress_accumulate(idx, val, ks, want)
-    buf = torch.zeros(n + offset_elems, dtype=torch.float32, device="cuda")
-    d = buf[offset_elems:]
-    d.copy_(torch.from_numpy(dense))
-    binding.gravac_decompress_accumulate(torch.from_numpy(idx).cuda(), torch.from_numpy(val).cuda(), ks, d)
-    torch.cuda.synchronize()
-    got = d.cpu().numpy()
-    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
-    if offset_elems:
-        assert float(buf[:offset_elems].abs().sum()) == 0.0
+    # without a workspace (tile boundaries by search) and with one (boundaries computed once)
+    for ws in (None, torch.empty(binding.gravac_decompress_workspace_bytes(len(ks), n), dtype=torch.uint8, device="cuda")):
+        if ws is not None:
+            ws.fill_(0xA5)                                  # the contents on entry do not matter
+        buf = torch.zeros(n + offset_elems, dtype=torch.float32, device="cuda")
+        d = buf[offset_elems:]
+        d.copy_(torch.from_numpy(dense))
+        binding.gravac_decompress_accumulate(torch.from_numpy(idx).cuda(), torch.from_numpy(val).cuda(), ks, d,
+                                             workspace=ws)
+        torch.cuda.synchronize()
+        got = d.cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), "workspace" if ws is not None else "search"
+        if offset_elems:
+            assert float(buf[:offset_elems].abs().sum()) == 0.0
 
 
 def test_decompress_accumulate_small_and_ragged():
@@ -262,6 +267,41 @@ def test_decompress_accumulate_small_and_ragged():
     _decompress_case(100_003, [5000] * 8, seed=4)
     _decompress_case(100_003, [5000] * 8, seed=5, offset_elems=1)     # dense buffer not 16-byte aligned
     _decompress_case(50_000, [100] * 70, seed=6)                       # more than 64 workers: two launches
+
+
+def test_decompress_gaps_clusters_and_out_of_range_indices():
+    from oracle import oracle
+    n = 600_000
+    rng = np.random.default_rng(77)
+    # worker 0: one cluster at the start; worker 1: one pair at the very end; worker 2: empty; worker 3: two clusters
+    # far apart; worker 4: every 8192-th element (one pair per tile)
+    parts = [np.arange(0, 5000), np.array([n - 1]), np.zeros(0, np.int64),
+             np.concatenate([np.arange(100_000, 103_000), np.arange(590_000, 591_000)]), np.arange(0, n, 8192)]
+    idx = np.concatenate(parts).astype(np.int32)
+    val = rng.standard_normal(idx.size).astype(np.float32)
+    ks = [p.size for p in parts]
+    dense = rng.standard_normal(n).astype(np.float32)
+    want = dense.copy()
+    oracle.decompress_accumulate(idx, val, ks, want)
+    for ws in (None, torch.empty(binding.gravac_decompress_workspace_bytes(len(ks), n), dtype=torch.uint8, device="cuda")):
+        d = torch.from_numpy(dense).cuda()
+        binding.gravac_decompress_accumulate(torch.from_numpy(idx).cuda(), torch.from_numpy(val).cuda(), ks, d, workspace=ws)
+        assert np.array_equal(d.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    # indices outside [0, n) are ignored (the oracle rejects them, so the expectation is built by hand)
+    idx2 = np.array([-5, -1, 0, 7, n - 1, n, n + 100], np.int32)
+    val2 = np.arange(1, 8, dtype=np.float32)
+    want2 = dense.copy()
+    for i, v in zip(idx2, val2):
+        if 0 <= i < n:
+            want2[i] += v
+    for ws in (None, torch.empty(binding.gravac_decompress_workspace_bytes(1, n), dtype=torch.uint8, device="cuda")):
+        d = torch.from_numpy(dense).cuda()
+        binding.gravac_decompress_accumulate(torch.from_numpy(idx2).cuda(), torch.from_numpy(val2).cuda(), [7], d, workspace=ws)
+        assert np.array_equal(d.cpu().numpy().view(np.uint32), want2.view(np.uint32))
+    with pytest.raises(binding.GravacError) as e:
+        binding.gravac_decompress_accumulate(torch.from_numpy(idx2).cuda(), torch.from_numpy(val2).cuda(), [7], d,
+                                             workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == binding.ERR_WORKSPACE
 
 
 def test_decompress_sparse_and_dense_regimes():
@@ -290,7 +330,9 @@ def test_compress_then_decompress_eight_workers():
         all_val[w * k:(w + 1) * k] = comp.out_val
         ref_idx.append(ref[0]), ref_val.append(ref[1])
     dense = torch.zeros(n, dtype=torch.float32, device="cuda")
-    binding.gravac_decompress_accumulate(all_idx, all_val, [k] * 8, dense)
+    binding.gravac_decompress_accumulate(all_idx, all_val, [k] * 8, dense,
+                                         workspace=torch.empty(binding.gravac_decompress_workspace_bytes(8, n), dtype=torch.uint8,
+                                                               device="cuda"))
     torch.cuda.synchronize()
     want = np.zeros(n, np.float32)
     oracle.decompress_accumulate(np.concatenate(ref_idx), np.concatenate(ref_val), [k] * 8, want)

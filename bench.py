@@ -43,6 +43,36 @@ def cpu_baseline(n_conv, n_fc):
                       f"{dt:.1f} s on one host core of {os.cpu_count()}"}
 
 
+def cpu_select_baseline(n_conv, n_fc, k):
+    """A reasonable multi-core CPU implementation (nth_element on a key copy + OpenMP sweeps), full-size workload.
+    Reported as a baseline only; returns None if it cannot be built."""
+    import ctypes
+    import subprocess
+    from paper_2305_12201_amd import workloads
+    here = os.path.dirname(os.path.abspath(__file__))
+    src, lib = os.path.join(here, "bench_cpu_select.cpp"), os.path.join(here, "libbench_cpu_select.so")
+    try:
+        if not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
+            subprocess.run(["g++", "-O2", "-fopenmp", "-shared", "-fPIC", src, "-o", lib], check=True)
+        L = ctypes.CDLL(lib)
+    except Exception as e:                                     # no compiler / no OpenMP: the baseline is optional
+        log(f"bench.py: CPU select baseline not available ({e})")
+        return None
+    L.cpu_select_compress.restype = ctypes.c_double
+    L.cpu_select_compress.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                      ctypes.c_void_p, ctypes.POINTER(ctypes.c_int)]
+    g = workloads.config3_grad(0, n_conv, n_fc)
+    r = np.zeros(g.size, np.float32)
+    oi, ov = np.empty(k, np.int32), np.empty(k, np.float32)
+    threads = ctypes.c_int(0)
+    t0 = time.perf_counter()
+    L.cpu_select_compress(g.ctypes.data, r.ctypes.data, g.size, k, oi.ctypes.data, ov.ctypes.data, ctypes.byref(threads))
+    dt = time.perf_counter() - t0
+    return {"value": 4.0 * g.size / dt / 1e9, "unit": "GB/s", "cores": int(threads.value),
+            "kind": "std::nth_element on a key copy + OpenMP sweeps (baseline only, not the oracle)",
+            "sample": f"one compress call (CF 1000) on the full VGG16-shaped gradient, {g.size} elements, {dt:.2f} s"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -201,6 +231,9 @@ def main():
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a half-size twin ...")
         out["cpu_baseline"] = cpu_baseline(n_conv, n_fc)
+        sel = cpu_select_baseline(n_conv, n_fc, k)
+        if sel is not None:
+            out["cpu_baseline_select"] = sel
     print(json.dumps(out), flush=True)
 
 

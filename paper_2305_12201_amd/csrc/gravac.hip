@@ -1663,9 +1663,11 @@ __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restri
 // ---------------------------------------------------------------------------------------------
 // decompression with a workspace: the tile boundaries of every message are computed once, by one thread
 // per pair, instead of being searched for by every tile.
-//   bounds[w][t], t = 0 .. ntile: number of pairs of worker w with index below t * DTILE (indices below 0
-//   count as tile 0, indices from ntile * DTILE on as past the last tile), so that tile t's pairs of
-//   worker w are [bounds[w][t], bounds[w][t + 1]) of its message.
+//   bounds[w][t], tile(first index of w) < t <= tile(last index of w): number of pairs of worker w with index
+//   below t * DTILE (indices below 0 count as tile 0, indices from ntile * DTILE on as past the last tile).
+//   Tile t's pairs of worker w are [bounds[w][t], bounds[w][t + 1]) of its message, where the lower end is 0
+//   for the tile of the message's first index and the upper end the message's length for the tile of its last
+//   index; entries outside that range are never written and never read.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ int64_t tile_of_index(int32_t x, int64_t ntile)
 {
@@ -1674,9 +1676,9 @@ __device__ __forceinline__ int64_t tile_of_index(int32_t x, int64_t ntile)
     return t < ntile ? t : ntile;
 }
 
-// grid (pair blocks, workers).  Pair j of a message starts tiles (tile of pair j - 1, tile of pair j]; the last
-// pair also closes all later tiles.  A lane with up to 2 tiles to write does it itself, longer runs (gaps in the
-// message, the tail) are written by the whole wavefront.
+// grid (pair blocks, workers).  Pair j > 0 of a message starts the tiles (tile of pair j - 1, tile of pair j].
+// A lane with up to 2 tiles to write does it itself, longer runs (gaps in the message) are written by the
+// whole wavefront.
 __global__ __launch_bounds__(256) void bounds_kernel(const int32_t* __restrict__ idx, WorkerOffsets wo, int64_t ntile,
                                                      uint32_t* __restrict__ bounds)
 {
@@ -1684,20 +1686,15 @@ __global__ __launch_bounds__(256) void bounds_kernel(const int32_t* __restrict__
     const int64_t a = wo.at[w], cnt = wo.at[w + 1] - a;
     uint32_t* bw = bounds + (size_t)w * (size_t)(ntile + 1);
     const int64_t j0 = ((int64_t)blockIdx.x * 256 + (threadIdx.x & ~63));  // first pair of this wavefront
-    if (cnt == 0) {
-        if (blockIdx.x == 0)
-            for (int64_t t = threadIdx.x; t <= ntile; t += 256) bw[t] = 0;
-        return;
-    }
     if (j0 >= cnt) return;
     const int64_t j = j0 + lane;
-    const bool live = j < cnt;
-    int64_t t_prev = -1, t_cur = -1;  // this lane writes bw[t] = j for t in (t_prev, t_cur]
+    const bool live = j > 0 && j < cnt;
+    int64_t t_prev = 0, t_cur = 0;  // this lane writes bw[t] = j for t in (t_prev, t_cur]
     if (live) {
         t_cur = tile_of_index(idx[a + j], ntile);
-        t_prev = (j == 0) ? -1 : tile_of_index(idx[a + j - 1], ntile);
+        t_prev = tile_of_index(idx[a + j - 1], ntile);
     }
-    const int64_t gap = t_cur - t_prev;
+    const int64_t gap = t_cur - t_prev;  // <= 0 where the indices do not ascend: nothing is written
     if (live && gap > 0 && gap <= 2) {
         bw[t_prev + 1] = (uint32_t)j;
         if (gap == 2) bw[t_prev + 2] = (uint32_t)j;
@@ -1710,116 +1707,131 @@ __global__ __launch_bounds__(256) void bounds_kernel(const int32_t* __restrict__
         const uint32_t v = (uint32_t)(j0 + src);
         for (int64_t t = tp + 1 + lane; t <= tc; t += 64) bw[t] = v;
     }
-    // the wavefront that holds the last pair closes the tiles after it
-    if (j0 + 64 >= cnt) {
-        const int64_t tl = __shfl(t_cur, (int)(cnt - 1 - j0), 64);
-        for (int64_t t = tl + 1 + lane; t <= ntile; t += 64) bw[t] = (uint32_t)cnt;
-    }
 }
 
+constexpr int DCHUNK = 32;  // tiles whose boundaries a workgroup fetches in one round of loads
+constexpr int DENT = 768;   // (tile, worker) entries of such a chunk
+
+// A workgroup takes the tiles blockIdx.x, blockIdx.x + gridDim.x, ...  It first fetches, for a chunk of its
+// tiles at once, every worker's boundaries (one round of independent loads instead of one dependent round per
+// tile) and then walks over the chunk's tiles; a tile no message has a pair in costs no further memory access.
 __global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __restrict__ idx, const float* __restrict__ val,
                                                             WorkerOffsets wo, int W, int64_t n, float* dense,
                                                             const uint32_t* __restrict__ bounds)
 {
     __shared__ float acc[DTILE];
-    __shared__ int64_t lo[DGROUP];
-    __shared__ uint32_t cntw[DGROUP];
+    __shared__ uint32_t blo[DENT], bcnt[DENT];      // first pair and number of pairs, per (tile of the chunk, worker)
+    __shared__ int64_t wat[DMAXW + 1];              // start of every worker's message
     __shared__ int32_t first[DMAXW], last[DMAXW];   // smallest and largest index of every worker's message
     const int tid = threadIdx.x;
     const bool vec = (((uintptr_t)dense) & 15) == 0;  // float4 access needs a 16-byte aligned buffer
+    if (tid <= DMAXW) wat[tid] = wo.at[tid];
     if (tid < W) {
         const int64_t a = wo.at[tid], b = wo.at[tid + 1];
         first[tid] = (b > a) ? idx[a] : 0x7FFFFFFF;
         last[tid] = (b > a) ? idx[b - 1] : -1;
     }
-    __syncthreads();
     const int64_t ntile = (n + DTILE - 1) / DTILE;
-    for (int64_t tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
-        const int64_t base = tile * DTILE;
-        const int len = (int)((n - base < DTILE) ? n - base : DTILE);
-        bool loaded = false;
-        for (int w0 = 0; w0 < W; w0 += DGROUP) {
-            const int wn = (W - w0 < DGROUP) ? W - w0 : DGROUP;
-            // can any message of this group touch the tile at all?
-            bool maybe = false;
-            for (int w = 0; w < wn; ++w)
-                maybe |= ((int64_t)first[w0 + w] < base + len) && ((int64_t)last[w0 + w] >= base);
-            if (!maybe) continue;
-            __syncthreads();  // lo / cntw of the previous group or tile are no longer read
-            if (tid < wn) {
-                const uint32_t* bw = bounds + (size_t)(w0 + tid) * (size_t)(ntile + 1) + tile;
-                // clamped to the message, so that no read can leave it even if the indices were not ascending
-                const uint32_t cw = (uint32_t)(wo.at[w0 + tid + 1] - wo.at[w0 + tid]);
-                uint32_t l = bw[0], h = bw[1];
-                l = l < cw ? l : cw;
-                h = h < l ? l : (h < cw ? h : cw);
-                lo[tid] = wo.at[w0 + tid] + l;
-                cntw[tid] = h - l;
-            }
-            __syncthreads();
-            uint32_t pre[DGROUP + 1];
-            pre[0] = 0;
-#pragma unroll
-            for (int w = 0; w < DGROUP; ++w) pre[w + 1] = pre[w] + (w < wn ? cntw[w] : 0u);
-            const uint32_t total = pre[DGROUP];
-            if (total == 0) continue;  // no message of this group touches the tile
-            if (!loaded) {
-                for (int i = tid * 4; i < len; i += 256 * 4) {
-                    if (vec && i + 4 <= len) {
-                        const v4f v = *(const v4f*)(dense + base + i);
-                        acc[i] = v.x; acc[i + 1] = v.y; acc[i + 2] = v.z; acc[i + 3] = v.w;
-                    } else {
-                        for (int e = 0; e < 4 && i + e < len; ++e) acc[i + e] = dense[base + i + e];
-                    }
-                }
-                loaded = true;
-            }
-            for (uint32_t s0 = 0; s0 < total; s0 += 256 * DBATCH) {
-                int pj[DBATCH], pw[DBATCH];
-                float pv[DBATCH];
-#pragma unroll
-                for (int q = 0; q < DBATCH; ++q) {
-                    const uint32_t slot = s0 + q * 256 + tid;
-                    pw[q] = -1; pj[q] = 0; pv[q] = 0.0f;
-                    if (slot < total) {
-                        int w = 0;
-#pragma unroll
-                        for (int x = 1; x < DGROUP; ++x) w += (slot >= pre[x]);
-                        uint32_t pb = 0;
-#pragma unroll
-                        for (int x = 1; x < DGROUP; ++x) if (x == w) pb = pre[x];
-                        const int64_t at = lo[w] + (int64_t)(slot - pb);
-                        const int64_t j = (int64_t)idx[at] - base;  // index and value are loaded together
-                        const float x = val[at];
-                        if (j >= 0 && j < len) { pw[q] = w; pj[q] = (int)j; pv[q] = x; }
-                    }
-                }
-                // workers present in this batch: from the worker of its first slot to that of its last
-                const uint32_t end = (s0 + 256 * DBATCH < total ? s0 + 256 * DBATCH : total) - 1;
-                int wmin = 0, wmax = 0;
-#pragma unroll
-                for (int x = 1; x < DGROUP; ++x) { wmin += (s0 >= pre[x]); wmax += (end >= pre[x]); }
-                __syncthreads();  // tile loaded / previous batch applied
-                for (int w = wmin; w <= wmax; ++w) {
-#pragma unroll
-                    for (int q = 0; q < DBATCH; ++q)
-                        if (pw[q] == w) acc[pj[q]] += pv[q];
-                    __syncthreads();
+    const int Wp = (W + DGROUP - 1) / DGROUP * DGROUP;            // workers, padded to whole groups
+    const int tc = DENT / Wp < DCHUNK ? DENT / Wp : DCHUNK;       // tiles per chunk (>= 12: Wp <= 64)
+    for (int64_t c0 = blockIdx.x; c0 < ntile; c0 += (int64_t)tc * gridDim.x) {
+        __syncthreads();  // first / last / wat are written; the previous chunk's entries are no longer read
+        for (int e = tid; e < tc * Wp; e += 256) {
+            const int i = e / Wp, w = e - i * Wp;
+            const int64_t tile = c0 + (int64_t)i * gridDim.x;
+            uint32_t l = 0, c = 0;
+            if (w < W && tile < ntile) {
+                const int64_t base = tile * DTILE, end = (n - base < DTILE) ? n : base + DTILE;
+                if ((int64_t)first[w] < end && (int64_t)last[w] >= base) {
+                    const uint32_t* bw = bounds + (size_t)w * (size_t)(ntile + 1) + tile;
+                    const uint32_t cw = (uint32_t)(wat[w + 1] - wat[w]);
+                    uint32_t h = cw;
+                    if (tile > tile_of_index(first[w], ntile)) l = bw[0];
+                    if (tile < tile_of_index(last[w], ntile)) h = bw[1];
+                    // clamped to the message, so that no read can leave it even if the indices were not ascending
+                    l = l < cw ? l : cw;
+                    h = h < l ? l : (h < cw ? h : cw);
+                    c = h - l;
                 }
             }
+            blo[e] = l;
+            bcnt[e] = c;
         }
-        if (loaded) {
-            __syncthreads();
-            for (int i = tid * 4; i < len; i += 256 * 4) {
-                if (vec && i + 4 <= len) {
-                    v4f v;
-                    v.x = acc[i]; v.y = acc[i + 1]; v.z = acc[i + 2]; v.w = acc[i + 3];
-                    *(v4f*)(dense + base + i) = v;
-                } else {
-                    for (int e = 0; e < 4 && i + e < len; ++e) dense[base + i + e] = acc[i + e];
+        __syncthreads();
+        for (int i = 0; i < tc; ++i) {
+            const int64_t tile = c0 + (int64_t)i * gridDim.x;
+            if (tile >= ntile) break;
+            const int64_t base = tile * DTILE;
+            const int len = (int)((n - base < DTILE) ? n - base : DTILE);
+            bool loaded = false;
+            for (int w0 = 0; w0 < W; w0 += DGROUP) {
+                const uint32_t* cg = bcnt + i * Wp + w0;
+                const uint32_t* lg = blo + i * Wp + w0;
+                uint32_t pre[DGROUP + 1];
+                pre[0] = 0;
+#pragma unroll
+                for (int w = 0; w < DGROUP; ++w) pre[w + 1] = pre[w] + cg[w];
+                const uint32_t total = pre[DGROUP];
+                if (total == 0) continue;  // no message of this group touches the tile
+                if (!loaded) {
+                    for (int q = tid * 4; q < len; q += 256 * 4) {
+                        if (vec && q + 4 <= len) {
+                            const v4f v = *(const v4f*)(dense + base + q);
+                            acc[q] = v.x; acc[q + 1] = v.y; acc[q + 2] = v.z; acc[q + 3] = v.w;
+                        } else {
+                            for (int e = 0; e < 4 && q + e < len; ++e) acc[q + e] = dense[base + q + e];
+                        }
+                    }
+                    loaded = true;
+                }
+                // the group's pairs, worker-major, DBATCH per thread and batch; all loads of a batch in flight together
+                for (uint32_t s0 = 0; s0 < total; s0 += 256 * DBATCH) {
+                    int pj[DBATCH], pw[DBATCH];
+                    float pv[DBATCH];
+#pragma unroll
+                    for (int q = 0; q < DBATCH; ++q) {
+                        const uint32_t slot = s0 + q * 256 + tid;
+                        pw[q] = -1; pj[q] = 0; pv[q] = 0.0f;
+                        if (slot < total) {
+                            int w = 0;
+#pragma unroll
+                            for (int x = 1; x < DGROUP; ++x) w += (slot >= pre[x]);
+                            uint32_t pb = 0;
+#pragma unroll
+                            for (int x = 1; x < DGROUP; ++x) if (x == w) pb = pre[x];
+                            const int64_t at = wat[w0 + w] + (int64_t)lg[w] + (int64_t)(slot - pb);
+                            const int64_t j = (int64_t)idx[at] - base;  // index and value are loaded together
+                            const float x = val[at];
+                            if (j >= 0 && j < len) { pw[q] = w; pj[q] = (int)j; pv[q] = x; }
+                        }
+                    }
+                    // workers present in this batch: from the worker of its first slot to that of its last
+                    const uint32_t end = (s0 + 256 * DBATCH < total ? s0 + 256 * DBATCH : total) - 1;
+                    int wmin = 0, wmax = 0;
+#pragma unroll
+                    for (int x = 1; x < DGROUP; ++x) { wmin += (s0 >= pre[x]); wmax += (end >= pre[x]); }
+                    __syncthreads();  // tile loaded / previous batch applied
+                    for (int w = wmin; w <= wmax; ++w) {
+#pragma unroll
+                        for (int q = 0; q < DBATCH; ++q)
+                            if (pw[q] == w) acc[pj[q]] += pv[q];
+                        __syncthreads();
+                    }
                 }
             }
-            __syncthreads();  // the tile buffer is free again
+            if (loaded) {
+                __syncthreads();
+                for (int q = tid * 4; q < len; q += 256 * 4) {
+                    if (vec && q + 4 <= len) {
+                        v4f v;
+                        v.x = acc[q]; v.y = acc[q + 1]; v.z = acc[q + 2]; v.w = acc[q + 3];
+                        *(v4f*)(dense + base + q) = v;
+                    } else {
+                        for (int e = 0; e < 4 && q + e < len; ++e) dense[base + q + e] = acc[q + e];
+                    }
+                }
+                __syncthreads();  // the tile buffer is free again
+            }
         }
     }
 }

@@ -85,6 +85,9 @@ def main():
                     help="first steps of the run that sample their thresholds even with reuse (the error-feedback "
                          "transient, where the threshold climbs quickly)")
     ap.add_argument("--small", action="store_true", help="1/16-size workload (for a quick functional check)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the same steps replayed from HIP graphs (one graph per gradient of the cycle), "
+                         "reported as graph_ms_per_step; the headline value stays the eager one")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 10 plain device copies of the gradient's size (known traffic: 4N read + 4N "
                          "written per copy) so that profiler byte counters can be scaled, then exit")
@@ -172,6 +175,25 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     status = binding.gravac_read_status(comp.workspace)
 
+    # ---- optional: the same K steps replayed from HIP graphs (flat-mode calls are kernel launches only)
+    graph_ms = None
+    if args.graph:
+        graphs = []
+        for gi in range(N_GRADS):
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr):
+                step(gi, REUSE_FLAG)
+            graphs.append(gr)
+        for i in range(5):
+            graphs[(args.warmup + args.steps + i) % N_GRADS].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[(args.warmup + args.steps + 5 + i) % N_GRADS].replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        assert binding.gravac_read_status(comp.workspace)["internal_error"] == 0
+
     # ---- per-part timing with HIP events on the launch stream (same steps): around the streaming kernel
     #      and the whole compress call (the library's own events), and around the decompress call, which runs
     #      right after compress as in a timed step (the library launches on torch's current stream, so torch
@@ -238,6 +260,8 @@ def main():
         "compression_gain": gain,
         "fallback_taken": bool(status["any_fallback"]),
     }
+    if graph_ms is not None:
+        out["graph_ms_per_step"] = graph_ms
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a half-size twin ...")
         out["cpu_baseline"] = cpu_baseline(n_conv, n_fc)

@@ -21,6 +21,11 @@
  *     stream).  Outputs are valid once the stream has been synchronised.
  *   - The library never allocates device memory: scratch space comes from the caller's
  *     `workspace`.  Calls that overlap in time must use different workspaces.
+ *   - HIP graphs: a flat-mode compression (gravac_compress, gravac_randomk_compress, gravac_recompress with
+ *     n_seg == 0, without GRAVAC_FLAG_PROFILE), gravac_commit and gravac_decompress_accumulate consist of kernel
+ *     launches only (no copies, no memsets, no host synchronisation), so they can be recorded into a graph and
+ *     replayed; the host tables (cf_list, counts) are read at capture time.  Layerwise calls and profiled calls
+ *     on a capturing stream return GRAVAC_ERR_CAPTURE.
  *   - Return value: GRAVAC_OK (0) or a negative GRAVAC_ERR_* code.  On an error return no
  *     kernel has been launched and no buffer has been touched.
  */
@@ -39,6 +44,9 @@ extern "C" {
 #define GRAVAC_ERR_CAPACITY (-2)    /* out_capacity smaller than the number of pairs the call will emit */
 #define GRAVAC_ERR_WORKSPACE (-3)   /* workspace missing or smaller than gravac_workspace_bytes() */
 #define GRAVAC_ERR_HIP (-4)         /* a HIP runtime call failed (launch, copy) */
+#define GRAVAC_ERR_CAPTURE (-5)     /* the stream is being captured into a HIP graph and the call cannot be replayed:
+                                       a layerwise call (its segment tables travel through a host staging buffer
+                                       that later calls rewrite) or a call with GRAVAC_FLAG_PROFILE */
 
 #define GRAVAC_MAX_CF 8             /* candidate CFs per call */
 #define GRAVAC_STATS_PER_CF 4       /* doubles per (segment, CF) in out_stats */

@@ -20,6 +20,7 @@ ERR_INVALID_ARG = -1
 ERR_CAPACITY = -2
 ERR_WORKSPACE = -3
 ERR_HIP = -4
+ERR_CAPTURE = -5
 MAX_CF = 8
 FLAG_FORCE_FALLBACK = 1
 FLAG_PROFILE = 2

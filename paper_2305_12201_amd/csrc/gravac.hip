@@ -1993,6 +1993,15 @@ int gravac_workspace_bytes(int64_t n, int n_cf, int n_seg, size_t* bytes_out)
     return GRAVAC_OK;
 }
 
+// GRAVAC_OK if `stream` is not being captured into a graph, else GRAVAC_ERR_CAPTURE (asked only by calls that cannot
+// be replayed: a replay would copy whatever the staging slot holds by then, or re-record the timing events).
+static int refuse_capture(hipStream_t stream)
+{
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) != hipSuccess) return GRAVAC_ERR_HIP;
+    return cap == hipStreamCaptureStatusNone ? GRAVAC_OK : GRAVAC_ERR_CAPTURE;
+}
+
 // The pipeline behind both entry points.  map_idx == null: error-feedback compression of grad + residual.
 // map_idx != null: single-source mode, the source is grad alone (a message's values), map_idx its indices,
 // restore / n_restore the dense residual that takes the unselected values back (may be null).
@@ -2090,6 +2099,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         }
         if (total_out > out_capacity) return GRAVAC_ERR_CAPACITY;
         if (tiles > max_tiles(n, ns) || sblocks > max_sample_blocks(n, ns)) return GRAVAC_ERR_WORKSPACE;
+        if (const int rc = refuse_capture(stream)) return rc;
         p.n_tiles = (uint32_t)tiles;
         p.n_sample_blocks = (uint32_t)sblocks;
         const size_t bytes = sizeof(SegInfo) * ns + sizeof(uint32_t) * (size_t)ns * n_cf + sizeof(uint32_t) * sblocks;
@@ -2135,6 +2145,8 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     const uint32_t scan_slices = (max_seg_tiles + SCAN_SLICE - 1) / SCAN_SLICE;
 
     const bool prof = (flags & GRAVAC_FLAG_PROFILE) != 0;
+    if (prof && ns == 1)
+        if (const int rc = refuse_capture(stream)) return rc;
     if (prof) {
         std::lock_guard<std::mutex> lock(g_prof_mutex);
         if (!g_ev_ready) {
@@ -2320,6 +2332,7 @@ const char* gravac_strerror(int code)
         case GRAVAC_ERR_CAPACITY: return "output capacity too small";
         case GRAVAC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case GRAVAC_ERR_HIP: return "HIP runtime error";
+        case GRAVAC_ERR_CAPTURE: return "call cannot be recorded into a HIP graph (layerwise or profiled call on a capturing stream)";
         default: return "unknown error code";
     }
 }

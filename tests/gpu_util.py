@@ -35,7 +35,7 @@ def assert_same(gpu, ref, what=""):
         f"{what}: residual differs at {np.nonzero(gr.view(np.uint32) != or_.view(np.uint32))[0][:5]}"
     assert gs.shape == os_.shape
     # tau is exact; sums agree to rounding order
-    assert np.array_equal(gs[..., 3], os_[..., 3]) or (np.isnan(gs[..., 3]) == np.isnan(os_[..., 3])).all(), what
+    assert np.array_equal(gs[..., 3], os_[..., 3], equal_nan=True), f"{what}: thresholds differ"
     np.testing.assert_allclose(gs[..., :3], os_[..., :3], rtol=STAT_RTOL, atol=0, equal_nan=True, err_msg=what)
 
 

@@ -110,6 +110,6 @@ def test_decompress_rejects_bad_arguments():
 
 def test_strerror():
     assert binding.strerror(0) == "ok"
-    for code in (-1, -2, -3, -4):
+    for code in (-1, -2, -3, -4, -5):
         assert binding.strerror(code) and "unknown" not in binding.strerror(code)
     assert "unknown" in binding.strerror(-99)

@@ -411,24 +411,38 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
 #pragma unroll
     for (int q = 0; q < SBIN / 256; ++q) h[q * 256 + tid] = 0;
     __syncthreads();
+    // A thread takes SAMPLE_BLOCK / 256 = 4 consecutive elements: sample i of the segment is element i of group
+    // i / 4.  A sampled segment (S a multiple of SAMPLE_BLOCK, nt > 2 S) is cut into S / 4 strata of at least 8
+    // elements and every group sits at a hashed place inside its stratum, so a sample costs a quarter of the
+    // memory transactions that single elements at scattered places would (the sampling pass is bound by them).
+    static_assert(SAMPLE_BLOCK / 256 == 4, "groups of four");
     float acc[SAMPLE_BLOCK / 256];
     bool live[SAMPLE_BLOCK / 256];
+    const uint32_t g = lb * (SAMPLE_BLOCK / 4) + tid;  // group
+    uint64_t gpos = 4ull * g;                          // the whole segment is read: group g = elements 4g .. 4g+3
+    if ((uint64_t)S != nt) {
+        const uint64_t G = S / 4, a = ((uint64_t)g * nt) / G, e = ((uint64_t)(g + 1) * nt) / G;
+        gpos = a + hash32(g * 0x9E3779B9u + 0x85EBCA6Bu) % (uint32_t)(e - a - 3);  // gpos + 3 < e <= nt
+    }
+    // all loads first, without branches around them (a group past the segment's last sample reads the segment's
+    // last element instead and is not counted), so that they are in flight together
+    float gv[SAMPLE_BLOCK / 256], rv[SAMPLE_BLOCK / 256];
 #pragma unroll
     for (int q = 0; q < SAMPLE_BLOCK / 256; ++q) {
-        const uint32_t i = lb * SAMPLE_BLOCK + q * 256 + tid;
-        live[q] = i < S;
-        acc[q] = 0.0f;
-        if (live[q]) {
-            uint64_t pos;
-            if ((uint64_t)S == nt) {
-                pos = i;  // the whole segment is read
-            } else {
-                const uint64_t a = ((uint64_t)i * nt) / S, e = ((uint64_t)(i + 1) * nt) / S;
-                pos = a + hash32(i * 0x9E3779B9u + 0x85EBCA6Bu) % (uint32_t)(e - a);
-            }
-            acc[q] = p.single ? p.grad[s0 + (int64_t)pos] : p.res[s0 + (int64_t)pos] + p.grad[s0 + (int64_t)pos];
+        live[q] = 4 * g + q < S;
+        const uint64_t pos = gpos + q < nt ? gpos + q : nt - 1;
+        gv[q] = p.grad[s0 + (int64_t)pos];
+        rv[q] = 0.0f;
+    }
+    if (!p.single) {
+#pragma unroll
+        for (int q = 0; q < SAMPLE_BLOCK / 256; ++q) {
+            const uint64_t pos = gpos + q < nt ? gpos + q : nt - 1;
+            rv[q] = p.res[s0 + (int64_t)pos];
         }
     }
+#pragma unroll
+    for (int q = 0; q < SAMPLE_BLOCK / 256; ++q) acc[q] = p.single ? gv[q] : rv[q] + gv[q];
 #pragma unroll
     for (int q = 0; q < SAMPLE_BLOCK / 256; ++q)
         if (live[q]) atomicAdd(&h[key_of(acc[q]) >> 19], 1u);
@@ -481,7 +495,9 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
             team_locate_bin(p.hist1 + ((size_t)t * p.n_cf + jj) * REP * NBIN, REP, p.ovfc + ((size_t)t * p.n_cf + jj) * 64 * 32,
                             k + k / 4 + 64, q, team_scratch[team], [] { __syncthreads(); }, b, ab, cn);
             uint32_t lo;
-            if (b == NONE) lo = lo_prev > (1u << 19) ? lo_prev - (1u << 19) : 0u;  // fewer candidates than that: go lower
+            // fewer candidates than that: go lower; a tensor of at most LCAP elements takes all its elements for one
+            // call (whatever bin then holds its k-th largest can be gathered), after which its histogram reaches the level
+            if (b == NONE) lo = (nt > (uint64_t)LCAP && lo_prev > (1u << 19)) ? lo_prev - (1u << 19) : 0u;
             else {
                 const uint64_t x = (uint64_t)lo_prev + ((uint64_t)b << s_prev);
                 lo = x > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)x;
@@ -560,7 +576,7 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
         for (int j = 0; j < p.n_cf; ++j) {
             uint32_t lo = bin_lo[j] << 19;                          // lower edge of the bin of the r_lo-th sample
             uint64_t hi = ((uint64_t)bin_hi[j] + 1) << 19;          // upper edge of the bin of the r_hi-th sample
-            if (reuse && nt > (uint64_t)LCAP) {  // tensors of at most LCAP elements keep every element as a candidate
+            if (reuse) {
                 // from the key below which the previous call counted about 1.25 k candidates to 2^19 keys (about 4 % in
                 // magnitude) above the previous threshold: tight, for a run in steady state; a threshold that moves
                 // further than that costs one call through the exact route
@@ -1895,7 +1911,11 @@ Layout make_layout(int64_t n, int n_cf, int n_seg)
 // samples taken from a segment of nt elements when the largest CF is cf_max
 uint32_t sample_count(uint64_t nt, double cf_max, bool flat)
 {
+    // layerwise: the larger of 32 CF_max and 1/64 of the tensor.  A small sample of a large tensor gives a wide
+    // bracket: many more candidates than k, and bins so coarse that the keys near the bracket's lower end crowd
+    // into a few histogram bins, where their atomics queue up behind each other
     uint64_t target = flat ? (uint64_t)SAMPLE_MAX : (uint64_t)(32.0 * std::ceil(cf_max));
+    if (!flat && target < nt / 64) target = nt / 64;
     if (target < 4096) target = 4096;
     if (target > (uint64_t)SAMPLE_MAX) target = SAMPLE_MAX;
     target = (target + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK * SAMPLE_BLOCK;

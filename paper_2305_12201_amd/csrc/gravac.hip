@@ -78,7 +78,13 @@ constexpr double ZMARGIN = 5.0;     // safety margin of the sampled rank, in sta
 constexpr uint32_t NONE = 0xFFFFFFFFu;
 
 enum : uint32_t { MODE_RESOLVED = 0, MODE_GATHER = 1, MODE_HIST = 2, MODE_FAIL = 3 };
-enum : uint32_t { FAIL_NONE = 0, FAIL_LIGHT = 1, FAIL_FULL = 2 };  // SegState::fail
+// SegState::fail, the heaviest kind over the segment's CFs wins:
+//   FAIL_NARROW  the bin that holds the k-th largest is known but too coarse and too full to resolve: only the
+//                CFs concerned are binned again, inside that bin (no other pass);
+//   FAIL_LIGHT   the k-th largest lies above the histogram's bracket: the candidates hold it, all CFs of the
+//                segment are binned again from a coarse histogram of the candidates;
+//   FAIL_FULL    fewer than k candidates: acc is read again.
+enum : uint32_t { FAIL_NONE = 0, FAIL_NARROW = 1, FAIL_LIGHT = 2, FAIL_FULL = 3 };
 
 // Selection state of one (segment, CF).
 struct CfState {
@@ -93,7 +99,9 @@ struct CfState {
     uint32_t tau;       // key of the k-th largest (valid once resolved)
     uint32_t need;      // how many keys equal to tau are selected (lowest indices first)
     uint32_t cnt_gt;    // number of keys greater than tau
-    uint32_t pad[5];
+    uint32_t redo;      // 1 if this CF is binned again on the narrow route (set by the locate step)
+    uint32_t lo2, s2;   // ... with these bounds: the located bin, cut into 1024 parts
+    uint32_t pad[2];
 };
 static_assert(sizeof(CfState) == 64, "CfState layout");
 
@@ -600,7 +608,7 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
             CfState st;
             st.k = seg_k(p, t, j); st.lo = lo; st.s = s; st.mode = MODE_FAIL; st.base = 0; st.open = 0; st.above = 0;
             st.c = 0; st.tau = 0; st.need = 0; st.cnt_gt = 0;
-            st.pad[0] = st.pad[1] = st.pad[2] = st.pad[3] = st.pad[4] = 0;
+            st.redo = 0; st.lo2 = 0; st.s2 = 0; st.pad[0] = st.pad[1] = 0;
             p.st[(size_t)t * p.n_cf + j] = st;
             lo_min = lo < lo_min ? lo : lo_min;
         }
@@ -742,6 +750,7 @@ __device__ __forceinline__ void row_finish(const Params& p, int64_t g, const v4f
 struct ExactBounds {
     int t;  // segment, -1 = none yet
     uint32_t lo[MAXCF];
+    uint32_t sh[MAXCF];
     uint32_t lo_min;
 };
 
@@ -753,7 +762,8 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
     const uint32_t u = v / SUB;  // tile
     if (u >= p.n_tiles) return;
     const int t = tile_seg(p, u);
-    if (!EF && p.seg[t].fail == 0) return;
+    const uint32_t fail_kind = EF ? (uint32_t)FAIL_NONE : p.seg[t].fail;
+    if (!EF && fail_kind == FAIL_NONE) return;
     const int64_t sb = seg_begin(p, t), se = seg_end(p, t);
     const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW + (int64_t)(v % SUB) * TS;
     const int64_t e0 = (s0 + TS < se) ? s0 + TS : se;
@@ -791,11 +801,19 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
 #pragma unroll
             for (int j = 0; j < MAXCF; ++j) {
                 xb->lo[j] = NONE;
+                xb->sh[j] = 10;
                 if (j < p.n_cf) {
-                    uint32_t b, ab, cn;
-                    wave_locate_bin(p.coarse + (size_t)t * NBIN, 1, nullptr, seg_k(p, t, j), b, ab, cn);
-                    if (b == NONE) { b = 0; if (lane == 0) p.status->error = 1; }
-                    xb->lo[j] = b << 20;
+                    if (fail_kind == FAIL_NARROW) {
+                        // the locate step has left the bounds of the CFs that are binned again; the others keep
+                        // their histogram and their plan (lo = NONE: no key is counted for them here)
+                        const CfState* st = &p.st[(size_t)t * p.n_cf + j];
+                        if (st->redo) { xb->lo[j] = st->lo2; xb->sh[j] = st->s2; }
+                    } else {
+                        uint32_t b, ab, cn;
+                        wave_locate_bin(p.coarse + (size_t)t * NBIN, 1, nullptr, seg_k(p, t, j), b, ab, cn);
+                        if (b == NONE) { b = 0; if (lane == 0) p.status->error = 1; }
+                        xb->lo[j] = b << 20;
+                    }
                     xb->lo_min = xb->lo[j] < xb->lo_min ? xb->lo[j] : xb->lo_min;
                 }
             }
@@ -805,25 +823,28 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
         for (int j = 0; j < MAXCF; ++j) {
             if (j < p.n_cf) {
                 c.lo[j] = xb->lo[j];
-                c.sh[j] = 10;
-                if (first) {
+                c.sh[j] = xb->sh[j];
+                if (first && c.lo[j] != NONE) {
                     // record the new bound; clear what the refine pass may add to
                     CfState* st = &p.st[(size_t)t * p.n_cf + j];
-                    if (lane == 0) { st->lo = c.lo[j]; st->s = 10; st->mode = MODE_FAIL; }
+                    if (lane == 0) { st->lo = c.lo[j]; st->s = c.sh[j]; st->mode = MODE_FAIL; st->redo = 1; }
                     for (int i = lane; i < NBIN; i += 64) p.hist2[((size_t)t * p.n_cf + j) * NBIN + i] = 0;
                     if (lane < REP) p.list_cnt[(((size_t)t * p.n_cf + j) * REP + lane) * 32] = 0;
                 }
             }
         }
-        if (first && lane == 0) p.seg[t].lo_min = c.lo_min;
+        // (on the narrow route the candidate lists and the segment's candidate threshold stay as they are)
+        if (first && lane == 0 && fail_kind != FAIL_NARROW) p.seg[t].lo_min = c.lo_min;
     }
-    c.h1 = p.hist1 + ((size_t)t * p.n_cf * REP + (v & (REP - 1))) * NBIN;
+    // the copy of the histogram this wavefront adds to: spread by the sub-tile number, and by the tile number too,
+    // because the exact route's re-binning calls arrive with v = 8 u only
+    c.h1 = p.hist1 + ((size_t)t * p.n_cf * REP + ((v ^ (v / SUB)) & (REP - 1))) * NBIN;
     c.cidx = p.cand_idx + (size_t)v * TS;
     c.cval = p.cand_val + (size_t)v * TS;
     c.run = 0;
     c.ssd = 0.0;
 
-    if (!EF && p.seg[t].fail == FAIL_LIGHT) {
+    if (!EF && fail_kind != FAIL_FULL) {
         // the candidate lists stay as they are; only their histogram is rebuilt with the new bins.  Called for the
         // first sub-tile of a tile only: the wavefront takes the candidates of the whole tile
         const TileCands tcs = tile_cands(p, u);
@@ -846,7 +867,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
         for (int j = 0; j < MAXCF; ++j) {
             if (j < p.n_cf) {
                 const uint32_t o = wave_sum(c.ovf[j]);
-                if (lane == 0 && o) atomicAdd(&p.ovfc[(((size_t)t * p.n_cf + j) * 64 + (v & 63)) * 32], o);
+                if (lane == 0 && o) atomicAdd(&p.ovfc[(((size_t)t * p.n_cf + j) * 64 + (u & 63)) * 32], o);
             }
         }
         return;
@@ -937,8 +958,8 @@ __global__ __launch_bounds__(WG) void stream_kernel(Params p)
         for (uint32_t u = w; u < p.n_tiles; u += nw) {
             const uint32_t kind = p.seg[tile_seg(p, u)].fail;
             if (kind == FAIL_NONE) continue;
-            // FAIL_LIGHT: one call re-bins the candidates of the whole tile; FAIL_FULL: sub-tile by sub-tile
-            const int subs = (kind == FAIL_LIGHT) ? 1 : SUB;
+            // FAIL_NARROW, FAIL_LIGHT: one call re-bins the candidates of the whole tile; FAIL_FULL: sub-tile by sub-tile
+            const int subs = (kind == FAIL_FULL) ? SUB : 1;
             for (int j = 0; j < subs; ++j) stream_subtile<SM_EXACT, RND>(p, u * SUB + j, lane, &xb);
         }
     }
@@ -971,7 +992,18 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
             uint32_t ue = ub + 1;
             while (ue < u1 && tile_seg(p, ue) == t) ++ue;
             const uint32_t kind = p.seg[t].fail;
-            if (kind != FAIL_NONE) {
+            if (kind == FAIL_NARROW) {
+                // no coarse histogram: the wavefront of the segment's first tile clears the candidate histograms of
+                // the CFs that are binned again
+                const uint32_t u = ub + (tid >> 6);
+                if (u < ue && u == seg_tile0(p, t)) {
+                    for (int j = 0; j < p.n_cf; ++j) {
+                        if (p.st[(size_t)t * p.n_cf + j].redo == 0) continue;
+                        for (int i = lane; i < REP * NBIN; i += 64) p.hist1[((size_t)t * p.n_cf + j) * REP * NBIN + i] = 0;
+                        p.ovfc[(((size_t)t * p.n_cf + j) * 64 + lane) * 32] = 0;
+                    }
+                }
+            } else if (kind != FAIL_NONE) {
                 if (cur != t && cur >= 0) {
                     // flush the previous segment's counts
                     __syncthreads();
@@ -1081,10 +1113,16 @@ __global__ __launch_bounds__(256) void locate_kernel(Params p)
     if (tid == 0) {
         store_plan(st, q);
         if (q.mode == MODE_FAIL) {
-            // FAIL_LIGHT: the candidates include the k-th largest, only the histogram was too coarse where it lies;
-            // FAIL_FULL: fewer than k candidates, acc has to be read again
             p.status->any_fail = 1;
-            if (atomicMax(&p.seg[t].fail, b == NONE ? FAIL_FULL : FAIL_LIGHT) == 0u) atomicAdd(&p.status->n_fail, 1);
+            uint32_t kind = FAIL_FULL;               // fewer than k candidates
+            if (b == OVF) kind = FAIL_LIGHT;         // above the bracket, more keys there than a gather list holds
+            else if (b != NONE) {
+                // a bin 2^s keys wide (s > 11) with more than LCAP keys: 1024 bins of 2^(s - 10) keys cover it, and a
+                // bin at most 2^10 keys wide can always be resolved (gathered or histogrammed key by key)
+                kind = FAIL_NARROW;
+                st->redo = 1; st->lo2 = q.base; st->s2 = st->s - 10;
+            }
+            if (atomicMax(&p.seg[t].fail, kind) == 0u) atomicAdd(&p.status->n_fail, 1);
         }
     }
 }
@@ -1110,8 +1148,15 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
     __shared__ uint32_t rp[LWAVES][MAXCF][3];
     const int wib = threadIdx.x >> 6;
     if (redo) {
+        const uint32_t fail_kind = p.seg[t].fail;
+        if (first && lane == 0 && fail_kind != FAIL_FULL) atomicAdd(&p.status->n_light, 1);
         for (int j = 0; j < p.n_cf; ++j) {
             CfState* st = &p.st[(size_t)t * p.n_cf + j];
+            if (fail_kind == FAIL_NARROW && st->redo == 0) {
+                // this CF was not binned again: its plan stands (nobody writes it during this kernel)
+                if (lane == 0) { rp[wib][j][0] = st->mode; rp[wib][j][1] = st->base; rp[wib][j][2] = st->open; }
+                continue;
+            }
             uint32_t b, above, c;
             wave_locate_bin(p.hist1 + ((size_t)t * p.n_cf + j) * REP * NBIN, REP, p.ovfc + ((size_t)t * p.n_cf + j) * 64 * 32,
                             st->k, b, above, c);
@@ -1121,7 +1166,6 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
                 if (first) {
                     store_plan(st, q);
                     if (q.mode == MODE_FAIL) p.status->error = 1;  // the exact route cannot fail
-                    if (j == 0 && p.seg[t].fail == FAIL_LIGHT) atomicAdd(&p.status->n_light, 1);
                 }
             }
         }

@@ -122,6 +122,48 @@ def test_clustered_top_entries_hidden_from_the_sample():
     assert gpu[4]["internal_error"] == 0
 
 
+def _knee_gradient(n, seed):
+    """A tiny body, 12,500 large entries spread over seven octaves, and between them a cluster of 5000 entries
+    within 4096 neighbouring bit patterns.  At CF 100 (k = n / 100 = 15,000) the k-th largest lies inside the
+    cluster, while the sampled ranks that bracket it fall into the body and into the large entries: the bracket is
+    many octaves wide, so the histogram bin that holds the k-th largest is coarse and holds the whole cluster."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    g = workloads.normal_gradient(n, 1e-6, seed=seed + 1)
+    pos = rng.permutation(n)[:17_500]
+    big = np.exp(rng.uniform(np.log(50.0), np.log(5000.0), 12_500)) * rng.choice([-1.0, 1.0], 12_500)
+    g[pos[:12_500]] = big.astype(np.float32)
+    bits = np.float32(1.0).view(np.uint32) + rng.integers(0, 4096, 5000, dtype=np.uint32)
+    g[pos[12_500:]] = bits.view(np.float32) * rng.choice([-1.0, 1.0], 5000).astype(np.float32)
+    return g
+
+
+def test_full_coarse_bin_is_binned_again_inside_the_bin():
+    # the located bin is more than 2^11 keys wide and holds more keys than a gather list: the CF concerned is
+    # binned again inside that bin (no second pass over the gradient), the other CF keeps its plan
+    n = 1_500_000
+    g = _knee_gradient(n, seed=71)
+    for cfs, commit in (([100.0], 0), ([100.0, 1000.0], 0), ([100.0, 1000.0], 1), ([10.0, 100.0, 1000.0], 1)):
+        gpu, ref = check(g, np.zeros(n, np.float32), cfs, commit=commit, what=f"knee cfs={cfs} commit={commit}",
+                         expect_fallback=True)
+        assert gpu[4]["light_fallback_segments"] == 1, gpu[4]
+    # layerwise: only the middle tensor has the knee
+    parts = [workloads.normal_gradient(300_001, 1e-3, seed=72), g, workloads.resnet_like_gradient(200_003, seed=73)]
+    flat = np.concatenate(parts)
+    seg = np.cumsum([0] + [x.size for x in parts]).astype(np.int64)
+    gpu, ref = check(flat, np.zeros(flat.size, np.float32), [100.0, 1000.0], commit=0, seg=seg, what="knee, layerwise",
+                     expect_fallback=True)
+    assert gpu[4]["fallback_segments"] == 1 and gpu[4]["light_fallback_segments"] == 1, gpu[4]
+    # a second iteration on the same workspace (the histograms of the narrow route are what the next call finds)
+    comp = binding.Compressor(n, [100.0, 1000.0], 0)
+    r = np.zeros(n, np.float32)
+    for it in range(3):
+        gpu = gpu_compress(g, r, [100.0, 1000.0], 0, comp=comp, flags=binding.FLAG_REUSE_THRESHOLDS if it else 0)
+        ref = oracle_compress(g, r, [100.0, 1000.0], 0)
+        assert gpu[4]["internal_error"] == 0
+        assert_same(gpu, ref, f"knee, iteration {it}")
+        r = ref[3]
+
+
 # --------------------------------------------------------------------------
 # several CFs in one call, every commit position
 # --------------------------------------------------------------------------

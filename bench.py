@@ -9,7 +9,8 @@ Workload: the VGG16-shaped gradient (138,357,544 fp32 elements, conv part Normal
 Normal(0,1e-5)), residual carried from step to step, all inputs resident in HBM before the timed
 region.  Prints ONE JSON line (see the keys below); everything else goes to stderr.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--small]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--small] [--graph]
+  python bench.py --configs      one compress call of each of the five configurations (a table, not the headline)
 """
 import argparse
 import json
@@ -73,6 +74,101 @@ def cpu_select_baseline(n_conv, n_fc, k):
             "sample": f"one compress call (CF 1000) on the full VGG16-shaped gradient, {g.size} elements, {dt:.2f} s"}
 
 
+def time_all_configs(torch, binding, workloads):
+    """Times one compress call of every configuration (third error-feedback iteration on the same gradient,
+    HIP events of the library around the whole call; warm = calls back to back, cold = after a 512 MiB write
+    that flushes the caches) and the W = 8 decompression of configuration 5.  Returns a list of records."""
+    flush = torch.empty(512 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")
+    rows = []
+
+    def compress_row(name, g, cfs, commit, seg=None, res0=None, iters=3, reps=8):
+        n = g.numel()
+        comp = binding.Compressor(n, cfs, commit, seg)
+        r = torch.empty(n, dtype=torch.float32, device="cuda")
+        rec = {"config": name, "n": n, "cfs": cfs, "commit_cf": cfs[commit], "k": comp.k_total}
+        for cold in (False, True):
+            tot, strm, fb = [], [], 0
+            for rep in range(reps):
+                r.zero_() if res0 is None else r.copy_(res0)
+                for it in range(iters):
+                    if cold:
+                        flush.fill_(1.0)
+                    comp(g, r, flags=binding.FLAG_PROFILE)
+                    a, b = binding.gravac_profile_read()
+                    if it == iters - 1 and rep >= 2:
+                        tot.append(b)
+                        strm.append(a)
+                fb |= comp.status()["any_fallback"]
+            t = float(np.mean(tot))
+            key = "cold" if cold else "warm"
+            rec[key + "_us"] = t * 1e3
+            rec[key + "_stream_kernel_us"] = float(np.mean(strm)) * 1e3
+            rec[key + "_dense_GBps"] = 4.0 * n / t / 1e6
+            rec[key + "_algorithmic_frac_of_hbm_peak"] = (ALGO_BYTES_PER_ELEMENT * n + 8.0 * comp.k_total) / t / 1e6 / HBM_PEAK_GBS
+            rec[key + "_fallback"] = bool(fb)
+        log(json.dumps(rec))
+        rows.append(rec)
+
+    g = torch.from_numpy(workloads.config1(0)).cuda()
+    compress_row("1: N = 2^20, Normal(0, 1e-3)", g, [100.0], 0)
+    g = torch.from_numpy(workloads.config2_grad(0)).cuda()
+    r0 = torch.from_numpy(workloads.config2_residual0()).cuda()
+    for c in range(3):
+        compress_row("2: ResNet101-shaped, three CFs in one call", g, [10.0, 100.0, 1000.0], c, res0=r0)
+    compress_row("2: ResNet101-shaped, CF 100 alone", g, [100.0], 0, res0=r0)
+    del g, r0
+    g = torch.from_numpy(workloads.config3_grad(0)).cuda()
+    compress_row("3: VGG16-shaped", g, [1000.0], 0)
+    compress_row("3: VGG16-shaped, CF 100", g, [100.0], 0)
+    del g
+    g = torch.from_numpy(workloads.config4_grad(0)).cuda()
+    for c in range(2):
+        compress_row("4: LSTM, listed shapes", g, [100.0, 1000.0], c)
+    del g
+    g = torch.from_numpy(workloads.config4_grad(0, 10000, 1500)).cuda()
+    compress_row("4: LSTM, 66,034,000-element variant", g, [100.0, 1000.0], 0)
+    del g
+    g = torch.from_numpy(workloads.config5_worker_grad(0)).cuda()
+    seg = workloads.offsets_of(workloads.resnet101_tensor_sizes())
+    compress_row("5: ResNet101-shaped, 314 tensors, layerwise", g, [100.0], 0, seg=seg)
+    # decompression of the eight workers' messages of configuration 5
+    n = g.numel()
+    comp = binding.Compressor(n, [100.0], 0, seg)
+    k = comp.k_total
+    mi = torch.empty(N_WORKERS * k, dtype=torch.int32, device="cuda")
+    mv = torch.empty(N_WORKERS * k, dtype=torch.float32, device="cuda")
+    for w in range(N_WORKERS):
+        gw = torch.from_numpy(workloads.config5_worker_grad(w)).cuda()
+        r = torch.zeros(n, dtype=torch.float32, device="cuda")
+        i, v, _ = comp(gw, r)
+        mi[w * k:(w + 1) * k] = i
+        mv[w * k:(w + 1) * k] = v
+    dense = torch.zeros(n, dtype=torch.float32, device="cuda")
+    dws = torch.empty(binding.gravac_decompress_workspace_bytes(N_WORKERS, n), dtype=torch.uint8, device="cuda")
+    for ws in (None, dws):
+        rec = {"config": "5: decompress_accumulate, W = 8", "n": n, "pairs": N_WORKERS * k, "workspace": ws is not None}
+        for cold in (False, True):
+            ts = []
+            for rep in range(12):
+                dense.zero_()
+                if cold:
+                    flush.fill_(1.0)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                binding.gravac_decompress_accumulate(mi, mv, [k] * N_WORKERS, dense, workspace=ws)
+                e1.record()
+                torch.cuda.synchronize()
+                if rep >= 2:
+                    ts.append(e0.elapsed_time(e1))
+            t = float(np.mean(ts))
+            key = "cold" if cold else "warm"
+            rec[key + "_us"] = t * 1e3
+            rec[key + "_algorithmic_GBps"] = (8.0 * n + 8.0 * N_WORKERS * k) / t / 1e6
+        log(json.dumps(rec))
+        rows.append(rec)
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -88,6 +184,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="also time the same steps replayed from HIP graphs (one graph per gradient of the cycle), "
                          "reported as graph_ms_per_step; the headline value stays the eager one")
+    ap.add_argument("--configs", action="store_true",
+                    help="instead of the headline step, time one compress call of every configuration (1-5) and the "
+                         "decompression of configuration 5, print one JSON line {\"configs\": [...]} and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 10 plain device copies of the gradient's size (known traffic: 4N read + 4N "
                          "written per copy) so that profiler byte counters can be scaled, then exit")
@@ -105,6 +204,12 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.configs:
+        print(json.dumps({"configs": time_all_configs(torch, binding, workloads), "data": "synthetic",
+                          "note": "times from the library's HIP events around one gravac_compress call, third "
+                                  "error-feedback iteration; algorithmic fraction = (12 N + 8 k) / t / 8 TB/s"}), flush=True)
+        return
 
     n_conv, n_fc = workloads.VGG16_N_CONV, workloads.VGG16_N_FC
     if args.small:

@@ -80,3 +80,80 @@ def test_random_case(case):
     assert np.array_equal(val.cpu().numpy().view(np.uint32), rv.view(np.uint32)), f"{what}: Random-k values"
     assert np.array_equal(rt.cpu().numpy().view(np.uint32), ref_res.view(np.uint32)), f"{what}: Random-k residual"
     np.testing.assert_allclose(stats.cpu().numpy()[..., :3], rs[..., :3], rtol=STAT_RTOL, atol=0, equal_nan=True, err_msg=what)
+
+
+@pytest.mark.parametrize("case", range(30))
+def test_random_decompress(case):
+    """W index-sorted messages of random lengths (some empty, some dense, some in one cluster) into a dense buffer
+    that already holds values, with and without the workspace."""
+    rng = np.random.Generator(np.random.PCG64(5000 + case))
+    n = int(rng.choice([rng.integers(1, 9000), rng.integers(9000, 600_000)]))
+    W = int(rng.choice([1, 2, 8, 8, 17, 64, 70]))
+    idx, val, ks = [], [], []
+    for w in range(W):
+        mode = rng.integers(0, 4)
+        if mode == 0:
+            k = 0
+        elif mode == 1:
+            k = int(rng.integers(1, n + 1))
+        else:
+            k = int(rng.integers(1, max(2, n // 50 + 1)))
+        if mode == 3 and n > 10:                       # all pairs inside one short range
+            lo = int(rng.integers(0, n - min(n, 4 * k) + 1))
+            pos = lo + np.sort(rng.choice(min(n - lo, 4 * k), min(k, min(n - lo, 4 * k)), replace=False))
+        else:
+            pos = np.sort(rng.choice(n, k, replace=False))
+        idx.append(pos.astype(np.int32))
+        val.append((rng.standard_normal(pos.size) * 1e-2).astype(np.float32))
+        ks.append(int(pos.size))
+    idx = np.concatenate(idx) if sum(ks) else np.zeros(0, np.int32)
+    val = np.concatenate(val) if sum(ks) else np.zeros(0, np.float32)
+    base = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    want = base.copy()
+    oracle.decompress_accumulate(idx, val, ks, want)
+    ti = torch.from_numpy(idx).cuda() if idx.size else torch.zeros(1, dtype=torch.int32, device="cuda")
+    tv = torch.from_numpy(val).cuda() if val.size else torch.zeros(1, dtype=torch.float32, device="cuda")
+    for ws in (None, torch.empty(binding.gravac_decompress_workspace_bytes(W, n), dtype=torch.uint8, device="cuda")):
+        d = torch.from_numpy(base.copy()).cuda()
+        binding.gravac_decompress_accumulate(ti, tv, ks, d, workspace=ws)
+        torch.cuda.synchronize()
+        got = d.cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), \
+            f"case {case}: n={n} W={W} workspace={ws is not None}: differs at {np.nonzero(got != want)[0][:5]}"
+
+
+@pytest.mark.parametrize("case", range(30))
+def test_random_two_levels(case):
+    """Level 1 at a random CF, then the second-level Top-k on its message with deferred commit: message, statistics
+    and the residual it leaves, against the oracle's two-level path."""
+    rng = np.random.Generator(np.random.PCG64(9000 + case))
+    n = int(rng.choice([rng.integers(50, 3000), rng.integers(3000, 300_000)]))
+    cf1 = float(rng.choice([2.0, 5.0, 10.0, 40.0]))
+    cf_rel = float(rng.choice([1.0, 1.5, 2.0, 4.0, 10.0, 100.0]))
+    seg = _segments(rng, n)
+    g, r0 = _values(rng, n), _values(rng, n) * np.float32(0.1)
+    comp = binding.Compressor(n, [cf1], 0, seg)
+    gt, rt = torch.from_numpy(g).cuda(), torch.from_numpy(r0.copy()).cuda()
+    i1, v1, _ = comp(gt, rt)
+    torch.cuda.synchronize()
+    ref_res = r0.copy()
+    ri1, rv1, _ = oracle.compress(g, ref_res, [cf1], 0, seg)
+    assert np.array_equal(i1.cpu().numpy(), ri1)
+    sizes = [n] if seg is None else np.diff(seg).tolist()
+    counts = None if seg is None else [binding.gravac_topk_count(int(s), cf1) for s in sizes]
+    k1 = int(i1.numel())
+    k2 = binding.gravac_topk_count(k1, cf_rel) if counts is None else sum(binding.gravac_topk_count(c, cf_rel) for c in counts)
+    rows = 1 if counts is None else len(counts)
+    oi = torch.empty(k2, dtype=torch.int32, device="cuda")
+    ov = torch.empty(k2, dtype=torch.float32, device="cuda")
+    st = torch.zeros(rows, 4, dtype=torch.float64, device="cuda")
+    ws = torch.empty(binding.gravac_workspace_bytes(k1, 1, 0 if counts is None else len(counts)), dtype=torch.uint8, device="cuda")
+    binding.gravac_recompress(i1, v1, cf_rel, counts, rt, out_idx=oi, out_val=ov, out_stats=st, workspace=ws)
+    torch.cuda.synchronize()
+    assert binding.gravac_read_status(ws)["internal_error"] == 0
+    ri2, rv2, rs2 = oracle.recompress(ri1, rv1, cf_rel, ref_res, counts)
+    what = f"case {case}: n={n} cf1={cf1} cf_rel={cf_rel} segments={rows}"
+    assert np.array_equal(oi.cpu().numpy(), ri2), what
+    assert np.array_equal(ov.cpu().numpy().view(np.uint32), rv2.view(np.uint32)), what
+    assert np.array_equal(rt.cpu().numpy().view(np.uint32), ref_res.view(np.uint32)), what
+    np.testing.assert_allclose(st.cpu().numpy()[..., :3], rs2[..., :3], rtol=STAT_RTOL, atol=0, equal_nan=True, err_msg=what)

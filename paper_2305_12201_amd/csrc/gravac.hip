@@ -13,18 +13,20 @@
 // candidate list, histogramming those candidates by (key - lo) >> s.  Everything after that
 // works on the candidate lists only: locate the histogram bin that holds the k-th largest,
 // resolve it to the exact key, count per tile, and emit the message in ascending index order
-// while zeroing the selected residual slots.  If the sampled bound turns out wrong (fewer than
-// k candidates, or a bin too coarse to resolve) the segment is redone by an exact route: a full
-// 2048-bin histogram of the top key bits gives a bound that cannot fail.  Results are identical
-// on both routes; only the number of passes over memory differs.
+// while zeroing the selected residual slots.  If the sampled bound turns out wrong the segment is
+// redone by a route that cannot fail: a bin too coarse and too full to resolve is binned again inside
+// itself; a k-th largest above the bracket is found from a 2048-bin histogram of the candidates'
+// top key bits; with fewer than k candidates that histogram is built over all elements and the
+// candidates are collected again.  Results are identical on every route; only the number of
+// passes over memory differs.
 //
-// Units of work.  A "wave tile" is TW consecutive elements handled by one 64-lane wavefront,
-// which owns the slots [tile*TW, (tile+1)*TW) of the candidate arrays, so ordered compaction
-// needs no communication between wavefronts and no tile can overflow.  No kernel waits on another
-// workgroup: cross-tile results (histograms, output offsets) are combined at kernel boundaries.
-// Global atomics complete at a rate of roughly one per cache line per 10 ns on this part, so the
-// candidate histogram and the gather lists exist in REP copies (picked by blockIdx, which the
-// dispatcher deals round-robin over the eight XCDs) and nothing else uses global atomics.
+// Units of work.  A tile is TW consecutive elements; the streaming pass gives each of its SUB
+// sub-tiles to one 64-lane wavefront, which owns that sub-tile's slots of the candidate arrays, so
+// ordered compaction needs no communication between wavefronts and no list can overflow.  No kernel
+// waits on another workgroup: cross-tile results (histograms, output offsets) are combined at kernel
+// boundaries.  Global atomics complete at a rate of roughly one per cache line per 10 ns on this part,
+// so the candidate histogram and the gather lists exist in REP copies (picked from the sub-tile,
+// tile or workgroup number) and nothing else uses global atomics.
 
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>

@@ -166,6 +166,45 @@ def time_all_configs(torch, binding, workloads):
             rec[key + "_algorithmic_GBps"] = (8.0 * n + 8.0 * N_WORKERS * k) / t / 1e6
         log(json.dumps(rec))
         rows.append(rec)
+    # direct compression at each CF against the second-level Top-k on a level-1 message (the comparison of the
+    # paper's Table III, on the synthetic gradients)
+    for name, g in (("VGG16-shaped", torch.from_numpy(workloads.config3_grad(0)).cuda()),
+                    ("ResNet101-shaped", torch.from_numpy(workloads.config2_grad(0)).cuda())):
+        n = g.numel()
+        rec = {"config": f"multi-level: {name}", "n": n}
+        r = torch.empty(n, dtype=torch.float32, device="cuda")
+        for cf in (10.0, 100.0, 1000.0):
+            comp = binding.Compressor(n, [cf], 0)
+            ts = []
+            for rep in range(8):
+                r.zero_()
+                comp(g, r, flags=binding.FLAG_PROFILE)
+                ts.append(binding.gravac_profile_read()[1])
+            rec[f"direct_cf{int(cf)}_us"] = float(np.mean(ts[2:])) * 1e3
+        comp = binding.Compressor(n, [10.0], 0)
+        r.zero_()
+        i1, v1, _ = comp(g, r)
+        torch.cuda.synchronize()
+
+        def level2(i_in, v_in, cf_rel):
+            kk = binding.gravac_topk_count(i_in.numel(), cf_rel)
+            ws = torch.empty(binding.gravac_workspace_bytes(i_in.numel(), 1, 0), dtype=torch.uint8, device="cuda")
+            oi = torch.empty(kk, dtype=torch.int32, device="cuda")
+            ov = torch.empty(kk, dtype=torch.float32, device="cuda")
+            st = torch.zeros(1, 4, dtype=torch.float64, device="cuda")
+            ts = []
+            for rep in range(10):
+                binding.gravac_recompress(i_in, v_in, cf_rel, None, r, out_idx=oi, out_val=ov, out_stats=st,
+                                          workspace=ws, flags=binding.FLAG_PROFILE)
+                ts.append(binding.gravac_profile_read()[1])
+            return oi, ov, float(np.mean(ts[2:])) * 1e3
+
+        i2, v2, rec["level2_10_to_100_us"] = level2(i1, v1, 10.0)
+        _, _, rec["level2_100_to_1000_us"] = level2(i2, v2, 10.0)
+        _, _, rec["level2_10_to_1000_us"] = level2(i1, v1, 100.0)
+        log(json.dumps(rec))
+        rows.append(rec)
+        del g, r, comp, i1, v1, i2, v2
     return rows
 
 

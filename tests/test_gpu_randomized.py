@@ -2,6 +2,8 @@
 commit position, sampled bounds, forced exact route, threshold reuse over carried residuals, Top-k and
 Random-k), each compared with the CPU oracle element by element.  The cases are drawn from a fixed seed, so
 the test is the same on every run."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -11,6 +13,9 @@ from paper_2305_12201_amd import binding
 from tests.gpu_util import STAT_RTOL, assert_same, gpu_compress, oracle_compress
 
 pytestmark = pytest.mark.gpu
+
+# number of cases of every sweep; GRAVAC_RANDOM_CASES widens the sweeps for a longer run
+N_CASES = int(os.environ.get("GRAVAC_RANDOM_CASES", "0"))
 
 CF_POOL = [1.0, 1.5, 2.0, 7.0, 10.0, 33.3, 100.0, 1000.0, 12345.0]
 
@@ -46,7 +51,7 @@ def _segments(rng, n):
     return np.concatenate([[0], cuts, [n]]).astype(np.int64)
 
 
-@pytest.mark.parametrize("case", range(120))
+@pytest.mark.parametrize("case", range(N_CASES or 120))
 def test_random_case(case):
     rng = np.random.Generator(np.random.PCG64(1000 + case))
     n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 20_000), rng.integers(20_000, 400_000)]))
@@ -82,7 +87,7 @@ def test_random_case(case):
     np.testing.assert_allclose(stats.cpu().numpy()[..., :3], rs[..., :3], rtol=STAT_RTOL, atol=0, equal_nan=True, err_msg=what)
 
 
-@pytest.mark.parametrize("case", range(30))
+@pytest.mark.parametrize("case", range(N_CASES or 30))
 def test_random_decompress(case):
     """W index-sorted messages of random lengths (some empty, some dense, some in one cluster) into a dense buffer
     that already holds values, with and without the workspace."""
@@ -122,7 +127,7 @@ def test_random_decompress(case):
             f"case {case}: n={n} W={W} workspace={ws is not None}: differs at {np.nonzero(got != want)[0][:5]}"
 
 
-@pytest.mark.parametrize("case", range(30))
+@pytest.mark.parametrize("case", range(N_CASES or 30))
 def test_random_two_levels(case):
     """Level 1 at a random CF, then the second-level Top-k on its message with deferred commit: message, statistics
     and the residual it leaves, against the oracle's two-level path."""

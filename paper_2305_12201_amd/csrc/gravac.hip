@@ -110,7 +110,9 @@ static_assert(sizeof(CfState) == 64, "CfState layout");
 struct SegState {
     uint32_t lo_min;  // smallest lo over the CFs: the candidate threshold of the segment
     uint32_t fail;    // FAIL_*: whether the bound failed and the segment takes the exact route, and which form of it
-    uint32_t pad[2];
+    uint32_t pz;      // the streaming pass has stored +0 instead of acc for keys >= pz: the upper end of the committed
+                      // CF's bracket, above which an entry is selected unless the bound fails (NONE: nothing zeroed)
+    uint32_t pad;
 };
 
 struct Status {
@@ -582,7 +584,7 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
     }
     __syncthreads();
     if (tid == 0) {
-        uint32_t lo_min = NONE;
+        uint32_t lo_min = NONE, pz = NONE;
         for (int j = 0; j < p.n_cf; ++j) {
             uint32_t lo = bin_lo[j] << 19;                          // lower edge of the bin of the r_lo-th sample
             uint64_t hi = ((uint64_t)bin_hi[j] + 1) << 19;          // upper edge of the bin of the r_hi-th sample
@@ -613,9 +615,13 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
             st.redo = 0; st.lo2 = 0; st.s2 = 0; st.pad[0] = st.pad[1] = 0;
             p.st[(size_t)t * p.n_cf + j] = st;
             lo_min = lo < lo_min ? lo : lo_min;
+            if (j == p.commit && !forced && !p.single) {
+                const uint64_t top = (uint64_t)lo + ((uint64_t)OVF << s);  // first key of the histogram's open last bin
+                if (top <= 0x7FFFFFFFull) pz = (uint32_t)top;
+            }
         }
         SegState ss;
-        ss.lo_min = lo_min; ss.fail = 0; ss.pad[0] = ss.pad[1] = 0;
+        ss.lo_min = lo_min; ss.fail = 0; ss.pz = pz; ss.pad = 0;
         p.seg[t] = ss;
     }
 }
@@ -638,6 +644,7 @@ struct TileCtx {
     double ssd;
     int ncf;
     uint32_t s0, s1;  // Random-k keys
+    uint32_t pz;      // first pass: keys >= pz leave +0 in the residual instead of acc (NONE: none)
 };
 
 __device__ __forceinline__ void cand_hist(TileCtx& c, uint32_t key)
@@ -670,15 +677,21 @@ __device__ __forceinline__ void st_stream(v4f v, v4f* q)
 #endif
 }
 
-// One lane's four consecutive elements a[0..3] at global index g; vm = validity bits.
-template <bool SSD, bool RND>
-__device__ __forceinline__ void consume(TileCtx& c, const float a[4], int64_t g, unsigned vm)
+// The ordering keys of one lane's four consecutive elements a[0..3] at global index g.
+template <bool RND>
+__device__ __forceinline__ void keys_of_row(const TileCtx& c, const float a[4], int64_t g, uint32_t key[4])
 {
-    uint32_t key[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) key[e] = RND ? priority_of(c.s0, c.s1, (uint32_t)(g + e)) : key_of(a[e]);
+}
+
+// One lane's four consecutive elements a[0..3] with keys key[0..3] at global index g; vm = validity bits.
+template <bool SSD, bool RND>
+__device__ __forceinline__ void consume(TileCtx& c, const float a[4], const uint32_t key[4], int64_t g, unsigned vm)
+{
     bool f[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        key[e] = RND ? priority_of(c.s0, c.s1, (uint32_t)(g + e)) : key_of(a[e]);
         const bool valid = (vm >> e) & 1u;
         f[e] = valid && key[e] >= c.lo_min;
         if (SSD) {
@@ -732,8 +745,7 @@ template <int M>
 __device__ __forceinline__ void row_finish(const Params& p, int64_t g, const v4f& x, const v4f& y, const v4i& m, float a[4])
 {
     if (M == SM_EF) {
-        const v4f av = x + y;
-        st_stream(av, (v4f*)(p.res + g));
+        const v4f av = x + y;  // stored by store_acc_row, once the keys are known
         a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
     }
     if (M == SM_EXACT) { a[0] = x.x; a[1] = x.y; a[2] = x.z; a[3] = x.w; }
@@ -746,6 +758,20 @@ __device__ __forceinline__ void row_finish(const Params& p, int64_t g, const v4f
                 if ((uint64_t)(int64_t)mi[e] < (uint64_t)p.n_restore) p.restore[mi[e]] = a[e];
         }
     }
+}
+
+// First pass: acc goes back into the residual, except that an entry whose key lies above the committed CF's
+// bracket leaves +0 there already: it is selected unless the bound fails (the candidate lists keep its value, and
+// the routes for a failed bound put it back where it turns out not to be selected), which spares the emit step
+// a scattered store per selected entry.
+__device__ __forceinline__ void store_acc_row(const Params& p, const TileCtx& c, int64_t g, const float a[4], const uint32_t key[4])
+{
+    v4f o;
+    o.x = key[0] >= c.pz ? 0.0f : a[0];
+    o.y = key[1] >= c.pz ? 0.0f : a[1];
+    o.z = key[2] >= c.pz ? 0.0f : a[2];
+    o.w = key[3] >= c.pz ? 0.0f : a[3];
+    st_stream(o, (v4f*)(p.res + g));
 }
 
 // Exact route: the bounds of the segment a wavefront last worked on (they cost a histogram search).
@@ -784,8 +810,10 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
         c.lo[j] = NONE;
         c.sh[j] = 0;
     }
+    c.pz = NONE;
     if (EF) {
         c.lo_min = p.seg[t].lo_min;
+        if (M == SM_EF) c.pz = p.seg[t].pz;
 #pragma unroll
         for (int j = 0; j < MAXCF; ++j) {
             if (j < p.n_cf) {
@@ -888,8 +916,11 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
             for (int q = 0; q < GV_ROWS; ++q) {
                 const int64_t g = rb + q * ROW + 4 * lane;
                 float a[4];
+                uint32_t key[4];
                 row_finish<M>(p, g, x[q], y[q], m[q], a);
-                consume<EF, RND>(c, a, g, 0xFu);
+                keys_of_row<RND>(c, a, g, key);
+                if (M == SM_EF) store_acc_row(p, c, g, a, key);
+                consume<EF, RND>(c, a, key, g, 0xFu);
             }
             rb += (GV_ROWS - 1) * ROW;
         } else if (full) {
@@ -897,9 +928,12 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
             v4f x, y;
             v4i m;
             float a[4];
+            uint32_t key[4];
             row_load<M>(p, g, x, y, m);
             row_finish<M>(p, g, x, y, m, a);
-            consume<EF, RND>(c, a, g, 0xFu);
+            keys_of_row<RND>(c, a, g, key);
+            if (M == SM_EF) store_acc_row(p, c, g, a, key);
+            consume<EF, RND>(c, a, key, g, 0xFu);
         } else {
             // ragged row: element-wise, guarded
             const int64_t g = rb + 4 * lane;
@@ -912,8 +946,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                 if (q >= s0 && q < e0) {
                     vm |= 1u << e;
                     if (M == SM_EF) {
-                        a[e] = p.res[q] + p.grad[q];
-                        p.res[q] = a[e];
+                        a[e] = p.res[q] + p.grad[q];  // stored below, once the keys are known
                     } else if (M == SM_EXACT) {
                         a[e] = p.acc[q];
                     } else {
@@ -925,7 +958,14 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                     }
                 }
             }
-            consume<EF, RND>(c, a, g, vm);
+            uint32_t key[4];
+            keys_of_row<RND>(c, a, g, key);
+            if (M == SM_EF) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if ((vm >> e) & 1u) p.res[g + e] = key[e] >= c.pz ? 0.0f : a[e];
+            }
+            consume<EF, RND>(c, a, key, g, vm);
         }
     }
 
@@ -1038,6 +1078,21 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
                             atomicAdd(&h[cand_key(p, p.random ? ci[sl] : 0, cv[sl]) >> 20], 1u);
                         }
                     } else {
+                        const uint32_t pz = p.single ? NONE : p.seg[t].pz;
+                        if (pz != NONE) {
+                            // acc is read again from the residual: first put back what the first pass replaced by +0 in
+                            // this tile (the tile's candidate lists hold those values; nobody else touches the tile)
+                            const TileCands tcs = tile_cands(p, u);
+                            const float* cv = p.cand_val + (size_t)u * TW;
+                            const int32_t* ci = p.cand_idx + (size_t)u * TW;
+                            for (uint32_t i = lane; i < tcs.total(); i += 64) {
+                                const uint32_t sl = tcs.slot(i);
+                                const int32_t idx = ci[sl];
+                                const float val = cv[sl];
+                                if (cand_key(p, idx, val) >= pz) p.res[idx] = val;
+                            }
+                            __threadfence_block();  // the loads below are this wavefront's own, of the same addresses
+                        }
                         for (int64_t q0 = s0 + lane; q0 < e0; q0 += 64 * 8) {
                             float a[8];
 #pragma unroll
@@ -1518,9 +1573,14 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
     const uint32_t cnt = tcs.total();
     if (cnt == 0) return;
     const uint32_t take = p.ttake[u];
-    if (p.tg[u] == 0 && take == 0) return;
     const int t = tile_seg(p, u);
     const uint32_t tau = p.st[(size_t)t * p.n_cf + p.commit].tau;
+    // The first pass has left +0 in the residual for keys >= pz (not on the full exact route, which has put acc back).
+    // Those entries need no store here if they are selected, and get acc back if they are not, which can only be
+    // when the threshold turned out to lie at or above pz.
+    const uint32_t pz = (p.single || p.seg[t].fail == FAIL_FULL) ? NONE : p.seg[t].pz;
+    const bool put_back = pz != NONE && tau >= pz;
+    if (p.tg[u] == 0 && take == 0 && !put_back) return;
     const int64_t seg_out = seg_koff(p, t);
     const int64_t lim = seg_out + (int64_t)seg_k(p, t, p.commit);  // end of this segment's message
     int64_t pos = seg_out + (int64_t)p.toff[u];
@@ -1551,7 +1611,7 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
                     p.out_val[o] = vq[r];
                     if (!p.single) {
                         p.out_idx[o] = iq[r];
-                        p.res[iq[r]] = 0.0f;
+                        if (key < pz) p.res[iq[r]] = 0.0f;
                     } else {
                         const int mi = p.map_idx[iq[r]];  // position in the message -> index in the gradient
                         p.out_idx[o] = mi;
@@ -1560,6 +1620,8 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
                 } else {
                     p.status->error = 1;  // cannot happen if the counts are consistent; never write out of range
                 }
+            } else if (put_back && live && key >= pz) {
+                p.res[iq[r]] = vq[r];
             }
             pos += __popcll(ms);
             erun += (uint32_t)__popcll(me);

@@ -1319,20 +1319,22 @@ __global__ __launch_bounds__(256) void resolve_kernel(Params p)
     for (int r = 0; r < REP; ++r) off[r + 1] = off[r] + p.list_cnt[((size_t)id * REP + r) * 32];
     if (off[REP] != c || c > LCAP || want == 0 || want > c) { if (tid == 0) p.status->error = 1; return; }
     uint32_t d[LCAP / 256];
+    // all loads first, without branches around them (a position past the last key reads key 0 of the lists
+    // instead; c >= 1 here), so that they are in flight together
 #pragma unroll
     for (int q = 0; q < LCAP / 256; ++q) {
-        const uint32_t i = q * 256 + tid;
-        d[q] = 0u;                               // padding never counts: trial values are >= 1
-        if (i < c) {
-            int r = 0;
+        const uint32_t i = (uint32_t)(q * 256 + tid) < c ? (uint32_t)(q * 256 + tid) : 0u;
+        int r = 0;
 #pragma unroll
-            for (int x = 1; x < REP; ++x) r += (i >= off[x]);
-            uint32_t o = 0;
+        for (int x = 1; x < REP; ++x) r += (i >= off[x]);
+        uint32_t o = 0;
 #pragma unroll
-            for (int x = 0; x < REP; ++x) if (x == r) o = off[x];
-            d[q] = p.list[((size_t)id * REP + r) * LCAP + (i - o)] - base;
-        }
+        for (int x = 0; x < REP; ++x) if (x == r) o = off[x];
+        d[q] = p.list[((size_t)id * REP + r) * LCAP + (i - o)];
     }
+#pragma unroll
+    for (int q = 0; q < LCAP / 256; ++q)
+        d[q] = (uint32_t)(q * 256 + tid) < c ? d[q] - base : 0u;  // padding never counts: trial values are >= 1
     const int nbits = st->open ? 31 : (int)st->s;
     uint32_t prefix = 0;
     int buf = 0;
@@ -1681,7 +1683,7 @@ __device__ __forceinline__ void lower_bounds_32(const int32_t* idx, int64_t a, i
 __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restrict__ idx, const float* __restrict__ val,
                                                          WorkerOffsets wo, int W, int64_t n, float* dense)
 {
-    __shared__ float acc[DTILE];
+    __shared__ __attribute__((aligned(16))) float acc[DTILE];
     __shared__ int64_t lo[DGROUP], hi[DGROUP];
     __shared__ uint32_t pre[DGROUP + 1];
     __shared__ int32_t first[DMAXW], last[DMAXW];   // smallest and largest index of every worker's message
@@ -1727,12 +1729,21 @@ __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restri
             const uint32_t total = pre[DGROUP];
             if (total == 0) continue;  // no message of this group touches the tile
             if (!loaded) {
-                for (int i = tid * 4; i < len; i += 256 * 4) {
-                    if (vec && i + 4 <= len) {
-                        const v4f v = *(const v4f*)(dense + base + i);
-                        acc[i] = v.x; acc[i + 1] = v.y; acc[i + 2] = v.z; acc[i + 3] = v.w;
-                    } else {
-                        for (int e = 0; e < 4 && i + e < len; ++e) acc[i + e] = dense[base + i + e];
+                if (vec && len == DTILE) {
+                    // a whole tile: all eight loads of a thread in flight together
+                    v4f tv[DTILE / 1024];
+#pragma unroll
+                    for (int r = 0; r < DTILE / 1024; ++r) tv[r] = *(const v4f*)(dense + base + r * 1024 + tid * 4);
+#pragma unroll
+                    for (int r = 0; r < DTILE / 1024; ++r) *(v4f*)(acc + r * 1024 + tid * 4) = tv[r];
+                } else {
+                    for (int i = tid * 4; i < len; i += 256 * 4) {
+                        if (vec && i + 4 <= len) {
+                            const v4f v = *(const v4f*)(dense + base + i);
+                            acc[i] = v.x; acc[i + 1] = v.y; acc[i + 2] = v.z; acc[i + 3] = v.w;
+                        } else {
+                            for (int e = 0; e < 4 && i + e < len; ++e) acc[i + e] = dense[base + i + e];
+                        }
                     }
                 }
                 loaded = true;
@@ -1741,18 +1752,28 @@ __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restri
             for (uint32_t s0 = 0; s0 < total; s0 += 256 * DBATCH) {
                 int pj[DBATCH], pw[DBATCH];
                 float pv[DBATCH];
+                int64_t at[DBATCH];
+                // where the pairs lie (a slot past the last pair takes the last pair's place and is not applied:
+                // total >= 1 here), then all loads without branches around them, in flight together
 #pragma unroll
                 for (int q = 0; q < DBATCH; ++q) {
                     const uint32_t slot = s0 + q * 256 + tid;
-                    pw[q] = -1; pj[q] = 0; pv[q] = 0.0f;
-                    if (slot < total) {
-                        int w = 0;
+                    const uint32_t sc = slot < total ? slot : total - 1;
+                    int w = 0;
 #pragma unroll
-                        for (int x = 1; x < DGROUP; ++x) w += (slot >= pre[x]);
-                        const int64_t at = lo[w] + (int64_t)(slot - pre[w]);
-                        const int64_t j = (int64_t)idx[at] - base;
-                        if (j >= 0 && j < len) { pw[q] = w; pj[q] = (int)j; pv[q] = val[at]; }
-                    }
+                    for (int x = 1; x < DGROUP; ++x) w += (sc >= pre[x]);
+                    at[q] = lo[w] + (int64_t)(sc - pre[w]);
+                    pw[q] = slot < total ? w : -1;
+                }
+#pragma unroll
+                for (int q = 0; q < DBATCH; ++q) pj[q] = idx[at[q]];
+#pragma unroll
+                for (int q = 0; q < DBATCH; ++q) pv[q] = val[at[q]];
+#pragma unroll
+                for (int q = 0; q < DBATCH; ++q) {
+                    const int64_t j = (int64_t)pj[q] - base;
+                    if (j < 0 || j >= len) pw[q] = -1;   // an index outside the tile (malformed message) is ignored
+                    pj[q] = (int)(j < 0 || j >= len ? 0 : j);
                 }
                 // workers present in this batch: from the worker of its first slot to that of its last
                 const uint32_t end = (s0 + 256 * DBATCH < total ? s0 + 256 * DBATCH : total) - 1;
@@ -1770,13 +1791,19 @@ __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restri
         }
         if (loaded) {
             __syncthreads();
-            for (int i = tid * 4; i < len; i += 256 * 4) {
-                if (vec && i + 4 <= len) {
-                    v4f v;
-                    v.x = acc[i]; v.y = acc[i + 1]; v.z = acc[i + 2]; v.w = acc[i + 3];
-                    *(v4f*)(dense + base + i) = v;
-                } else {
-                    for (int e = 0; e < 4 && i + e < len; ++e) dense[base + i + e] = acc[i + e];
+            if (vec && len == DTILE) {
+#pragma unroll
+                for (int r = 0; r < DTILE / 1024; ++r)
+                    *(v4f*)(dense + base + r * 1024 + tid * 4) = *(const v4f*)(acc + r * 1024 + tid * 4);
+            } else {
+                for (int i = tid * 4; i < len; i += 256 * 4) {
+                    if (vec && i + 4 <= len) {
+                        v4f v;
+                        v.x = acc[i]; v.y = acc[i + 1]; v.z = acc[i + 2]; v.w = acc[i + 3];
+                        *(v4f*)(dense + base + i) = v;
+                    } else {
+                        for (int e = 0; e < 4 && i + e < len; ++e) dense[base + i + e] = acc[i + e];
+                    }
                 }
             }
             __syncthreads();  // the tile buffer is free again
@@ -1843,7 +1870,7 @@ __global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __res
                                                             WorkerOffsets wo, int W, int64_t n, float* dense,
                                                             const uint32_t* __restrict__ bounds)
 {
-    __shared__ float acc[DTILE];
+    __shared__ __attribute__((aligned(16))) float acc[DTILE];
     __shared__ uint32_t blo[DENT], bcnt[DENT];      // first pair and number of pairs, per (tile of the chunk, worker)
     __shared__ int64_t wat[DMAXW + 1];              // start of every worker's message
     __shared__ int32_t first[DMAXW], last[DMAXW];   // smallest and largest index of every worker's message
@@ -1898,12 +1925,21 @@ __global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __res
                 const uint32_t total = pre[DGROUP];
                 if (total == 0) continue;  // no message of this group touches the tile
                 if (!loaded) {
-                    for (int q = tid * 4; q < len; q += 256 * 4) {
-                        if (vec && q + 4 <= len) {
-                            const v4f v = *(const v4f*)(dense + base + q);
-                            acc[q] = v.x; acc[q + 1] = v.y; acc[q + 2] = v.z; acc[q + 3] = v.w;
-                        } else {
-                            for (int e = 0; e < 4 && q + e < len; ++e) acc[q + e] = dense[base + q + e];
+                    if (vec && len == DTILE) {
+                        // a whole tile: all eight loads of a thread in flight together
+                        v4f tv[DTILE / 1024];
+#pragma unroll
+                        for (int r = 0; r < DTILE / 1024; ++r) tv[r] = *(const v4f*)(dense + base + r * 1024 + tid * 4);
+#pragma unroll
+                        for (int r = 0; r < DTILE / 1024; ++r) *(v4f*)(acc + r * 1024 + tid * 4) = tv[r];
+                    } else {
+                        for (int q = tid * 4; q < len; q += 256 * 4) {
+                            if (vec && q + 4 <= len) {
+                                const v4f v = *(const v4f*)(dense + base + q);
+                                acc[q] = v.x; acc[q + 1] = v.y; acc[q + 2] = v.z; acc[q + 3] = v.w;
+                            } else {
+                                for (int e = 0; e < 4 && q + e < len; ++e) acc[q + e] = dense[base + q + e];
+                            }
                         }
                     }
                     loaded = true;
@@ -1912,22 +1948,31 @@ __global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __res
                 for (uint32_t s0 = 0; s0 < total; s0 += 256 * DBATCH) {
                     int pj[DBATCH], pw[DBATCH];
                     float pv[DBATCH];
+                    int64_t at[DBATCH];
+                    // where the pairs lie (a slot past the last pair takes the last pair's place and is not applied:
+                    // total >= 1 here), then all loads without branches around them, in flight together
 #pragma unroll
                     for (int q = 0; q < DBATCH; ++q) {
                         const uint32_t slot = s0 + q * 256 + tid;
-                        pw[q] = -1; pj[q] = 0; pv[q] = 0.0f;
-                        if (slot < total) {
-                            int w = 0;
+                        const uint32_t sc = slot < total ? slot : total - 1;
+                        int w = 0;
 #pragma unroll
-                            for (int x = 1; x < DGROUP; ++x) w += (slot >= pre[x]);
-                            uint32_t pb = 0;
+                        for (int x = 1; x < DGROUP; ++x) w += (sc >= pre[x]);
+                        uint32_t pb = 0;
 #pragma unroll
-                            for (int x = 1; x < DGROUP; ++x) if (x == w) pb = pre[x];
-                            const int64_t at = wat[w0 + w] + (int64_t)lg[w] + (int64_t)(slot - pb);
-                            const int64_t j = (int64_t)idx[at] - base;  // index and value are loaded together
-                            const float x = val[at];
-                            if (j >= 0 && j < len) { pw[q] = w; pj[q] = (int)j; pv[q] = x; }
-                        }
+                        for (int x = 1; x < DGROUP; ++x) if (x == w) pb = pre[x];
+                        at[q] = wat[w0 + w] + (int64_t)lg[w] + (int64_t)(sc - pb);
+                        pw[q] = slot < total ? w : -1;
+                    }
+#pragma unroll
+                    for (int q = 0; q < DBATCH; ++q) pj[q] = idx[at[q]];
+#pragma unroll
+                    for (int q = 0; q < DBATCH; ++q) pv[q] = val[at[q]];
+#pragma unroll
+                    for (int q = 0; q < DBATCH; ++q) {
+                        const int64_t j = (int64_t)pj[q] - base;
+                        if (j < 0 || j >= len) pw[q] = -1;   // an index outside the tile (malformed message) is ignored
+                        pj[q] = (int)(j < 0 || j >= len ? 0 : j);
                     }
                     // workers present in this batch: from the worker of its first slot to that of its last
                     const uint32_t end = (s0 + 256 * DBATCH < total ? s0 + 256 * DBATCH : total) - 1;
@@ -1945,13 +1990,19 @@ __global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __res
             }
             if (loaded) {
                 __syncthreads();
-                for (int q = tid * 4; q < len; q += 256 * 4) {
-                    if (vec && q + 4 <= len) {
-                        v4f v;
-                        v.x = acc[q]; v.y = acc[q + 1]; v.z = acc[q + 2]; v.w = acc[q + 3];
-                        *(v4f*)(dense + base + q) = v;
-                    } else {
-                        for (int e = 0; e < 4 && q + e < len; ++e) dense[base + q + e] = acc[q + e];
+                if (vec && len == DTILE) {
+#pragma unroll
+                    for (int r = 0; r < DTILE / 1024; ++r)
+                        *(v4f*)(dense + base + r * 1024 + tid * 4) = *(const v4f*)(acc + r * 1024 + tid * 4);
+                } else {
+                    for (int q = tid * 4; q < len; q += 256 * 4) {
+                        if (vec && q + 4 <= len) {
+                            v4f v;
+                            v.x = acc[q]; v.y = acc[q + 1]; v.z = acc[q + 2]; v.w = acc[q + 3];
+                            *(v4f*)(dense + base + q) = v;
+                        } else {
+                            for (int e = 0; e < 4 && q + e < len; ++e) dense[base + q + e] = acc[q + e];
+                        }
                     }
                 }
                 __syncthreads();  // the tile buffer is free again

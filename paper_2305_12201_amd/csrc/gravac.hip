@@ -1249,13 +1249,23 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
     for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
         // eight loads in flight per lane; an absent slot gets a key that lies in no bin (base > key)
         uint32_t kq[8];
+        if (p.random) {  // the key comes from the index: all loads first, then the arithmetic
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const uint32_t i = i0 + q * 64 + lane;
-            const uint32_t sl = (i < cnt) ? tc.slot(i) : 0u;
-            kq[q] = p.random ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)ci[sl]) : key_of(cv[sl]);
-            if (i >= cnt) kq[q] = 0u;
+            for (int q = 0; q < 8; ++q) {
+                const uint32_t i = i0 + q * 64 + lane;
+                kq[q] = (uint32_t)ci[(i < cnt) ? tc.slot(i) : 0u];
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) kq[q] = priority_of(p.rk_s0, p.rk_s1, kq[q]);
+        } else {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const uint32_t i = i0 + q * 64 + lane;
+                kq[q] = key_of(cv[(i < cnt) ? tc.slot(i) : 0u]);
+            }
         }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) if (i0 + q * 64 + lane >= cnt) kq[q] = 0u;
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const uint32_t key = kq[q];
@@ -1410,8 +1420,10 @@ __global__ __launch_bounds__(LWG) void count_kernel(Params p)
             const uint32_t i = i0 + q * 64 + lane;
             const uint32_t sl = (i < cnt) ? tcs.slot(i) : 0u;
             vq[q] = cv[sl];
-            kq[q] = p.random ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)ci[sl]) : key_of(vq[q]);
+            kq[q] = p.random ? (uint32_t)ci[sl] : 0u;   // all loads first, then the arithmetic
         }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) kq[q] = p.random ? priority_of(p.rk_s0, p.rk_s1, kq[q]) : key_of(vq[q]);
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             if (i0 + q * 64 + lane < cnt) {

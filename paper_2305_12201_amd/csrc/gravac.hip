@@ -1601,15 +1601,30 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
     uint32_t erun = 0;
     const float* cv = p.cand_val + (size_t)u * TW;
     const int32_t* ci = p.cand_idx + (size_t)u * TW;
+    // the loads of the next round are issued before this round is worked on (an absent candidate reads slot 0
+    // and is not used), so that a wavefront with a long list does not wait a full round trip per round
+    float vn[4];
+    int32_t in[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint32_t q = r * 64 + lane;
+        const uint32_t sl = (q < cnt) ? tcs.slot(q) : 0u;
+        vn[r] = cv[sl];
+        in[r] = ci[sl];
+    }
     for (uint32_t b0 = 0; b0 < cnt; b0 += 64 * 4) {
         float vq[4];
         int32_t iq[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const uint32_t q = b0 + r * 64 + lane;
-            const uint32_t sl = (q < cnt) ? tcs.slot(q) : 0u;
-            vq[r] = (q < cnt) ? cv[sl] : 0.0f;
-            iq[r] = (q < cnt) ? ci[sl] : 0;
+        for (int r = 0; r < 4; ++r) { vq[r] = vn[r]; iq[r] = in[r]; }
+        if (b0 + 64 * 4 < cnt) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t q = b0 + 64 * 4 + r * 64 + lane;
+                const uint32_t sl = (q < cnt) ? tcs.slot(q) : 0u;
+                vn[r] = cv[sl];
+                in[r] = ci[sl];
+            }
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {

@@ -387,9 +387,10 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "VGG16-shaped flat gradient, 138,357,544 fp32 elements, CF 1000 (k=138,358), "
-                               "residual carried, thresholds reused from the previous step; step = compress + "
-                               "decompress_accumulate of W=8 messages",
+        "config": {"workload": f"VGG16-shaped flat gradient{' (1/16 size: --small)' if args.small else ''}, {n:,} fp32 "
+                               f"elements, CF 1000 (k={k:,}), residual carried, thresholds "
+                               f"{'sampled in every step' if args.no_reuse else 'reused from the previous step'}; "
+                               "step = compress + decompress_accumulate of W=8 messages",
                    "n": n, "cf": cf, "k": k, "workers_decompressed": N_WORKERS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

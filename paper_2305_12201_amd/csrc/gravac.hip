@@ -74,6 +74,8 @@ constexpr uint32_t OVF = NBIN - 1;  // last bin of the candidate histogram: ever
 constexpr int SBIN = 4096;          // bins of the sample histogram (key >> 19)
 constexpr int SAMPLE_BLOCK = 1024;  // samples per workgroup of the sampling kernel
 constexpr int SAMPLE_MAX = 65536;   // samples per segment at most (unless the segment is read whole)
+constexpr int SAMPLE_MAX_FLAT = 524288;  // flat mode, a large k: see sample_count
+constexpr int DENSE_ROUNDS = 8;          // ... whose sample blocks are DENSE_ROUNDS * SAMPLE_BLOCK samples each
 constexpr int LCAP = 4096;          // keys a gather list can hold
 constexpr int MAXCF = GRAVAC_MAX_CF;
 constexpr double ZMARGIN = 5.0;     // safety margin of the sampled rank, in standard deviations
@@ -411,6 +413,7 @@ __device__ __forceinline__ void team_locate_bin(const uint32_t* hist, int copies
 // K0a: sample acc = residual + grad at stratified positions; each workgroup histograms the top
 // 12 key bits of its SAMPLE_BLOCK samples in LDS and stores the counts as 16-bit numbers
 // ---------------------------------------------------------------------------------------------
+template <int R>  // R groups per thread: a workgroup histograms R * SAMPLE_BLOCK samples
 __global__ __launch_bounds__(256) void sample_kernel(Params p)
 {
     __shared__ uint32_t h[SBIN];
@@ -423,43 +426,49 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
 #pragma unroll
     for (int q = 0; q < SBIN / 256; ++q) h[q * 256 + tid] = 0;
     __syncthreads();
-    // A thread takes SAMPLE_BLOCK / 256 = 4 consecutive elements: sample i of the segment is element i of group
-    // i / 4.  A sampled segment (S a multiple of SAMPLE_BLOCK, nt > 2 S) is cut into S / 4 strata of at least 8
-    // elements and every group sits at a hashed place inside its stratum, so a sample costs a quarter of the
-    // memory transactions that single elements at scattered places would (the sampling pass is bound by them).
+    // A group is 4 consecutive elements: sample i of the segment is element i % 4 of group i / 4.  A sampled
+    // segment (S a multiple of SAMPLE_BLOCK, nt > 2 S) is cut into S / 4 strata of at least 8 elements and every
+    // group sits at a hashed place inside its stratum, so a sample costs a quarter of the memory transactions that
+    // single elements at scattered places would (the sampling pass is bound by them).
     static_assert(SAMPLE_BLOCK / 256 == 4, "groups of four");
-    float acc[SAMPLE_BLOCK / 256];
-    bool live[SAMPLE_BLOCK / 256];
-    const uint32_t g = lb * (SAMPLE_BLOCK / 4) + tid;  // group
-    uint64_t gpos = 4ull * g;                          // the whole segment is read: group g = elements 4g .. 4g+3
-    if ((uint64_t)S != nt) {
-        const uint64_t G = S / 4, a = ((uint64_t)g * nt) / G, e = ((uint64_t)(g + 1) * nt) / G;
-        gpos = a + hash32(g * 0x9E3779B9u + 0x85EBCA6Bu) % (uint32_t)(e - a - 3);  // gpos + 3 < e <= nt
+    constexpr int Q = 4 * R;
+    uint64_t gpos[R];
+    bool live[Q];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t g = (lb * R + r) * (SAMPLE_BLOCK / 4) + tid;  // group
+        gpos[r] = 4ull * g;                                          // the whole segment is read: elements 4g .. 4g+3
+        if ((uint64_t)S != nt) {
+            const uint64_t G = S / 4, a = ((uint64_t)g * nt) / G, e = ((uint64_t)(g + 1) * nt) / G;
+            gpos[r] = a + hash32(g * 0x9E3779B9u + 0x85EBCA6Bu) % (uint32_t)(e - a - 3);  // gpos + 3 < e <= nt
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) live[4 * r + q] = 4ull * g + q < S;
     }
     // all loads first, without branches around them (a group past the segment's last sample reads the segment's
     // last element instead and is not counted), so that they are in flight together
-    float gv[SAMPLE_BLOCK / 256], rv[SAMPLE_BLOCK / 256];
+    float gv[Q], rv[Q];
 #pragma unroll
-    for (int q = 0; q < SAMPLE_BLOCK / 256; ++q) {
-        live[q] = 4 * g + q < S;
-        const uint64_t pos = gpos + q < nt ? gpos + q : nt - 1;
+    for (int q = 0; q < Q; ++q) {
+        const uint64_t pos = gpos[q / 4] + (q & 3) < nt ? gpos[q / 4] + (q & 3) : nt - 1;
         gv[q] = p.grad[s0 + (int64_t)pos];
         rv[q] = 0.0f;
     }
     if (!p.single) {
 #pragma unroll
-        for (int q = 0; q < SAMPLE_BLOCK / 256; ++q) {
-            const uint64_t pos = gpos + q < nt ? gpos + q : nt - 1;
+        for (int q = 0; q < Q; ++q) {
+            const uint64_t pos = gpos[q / 4] + (q & 3) < nt ? gpos[q / 4] + (q & 3) : nt - 1;
             rv[q] = p.res[s0 + (int64_t)pos];
         }
     }
 #pragma unroll
-    for (int q = 0; q < SAMPLE_BLOCK / 256; ++q) acc[q] = p.single ? gv[q] : rv[q] + gv[q];
-#pragma unroll
-    for (int q = 0; q < SAMPLE_BLOCK / 256; ++q)
-        if (live[q]) atomicAdd(&h[key_of(acc[q]) >> 19], 1u);
+    for (int q = 0; q < Q; ++q) {
+        const float acc = p.single ? gv[q] : rv[q] + gv[q];
+        if (live[q]) atomicAdd(&h[key_of(acc) >> 19], 1u);
+    }
     __syncthreads();
-    // thread i stores bins 16i .. 16i+15, two counts per word (a count is at most SAMPLE_BLOCK)
+    // thread i stores bins 16i .. 16i+15, two counts per word (a count is at most R * SAMPLE_BLOCK < 2^16)
+    static_assert(R * SAMPLE_BLOCK < 65536, "16-bit counts");
     uint4 w[2];
     uint32_t* wp = (uint32_t*)w;
 #pragma unroll
@@ -480,7 +489,7 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
     const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
     const uint32_t S = is_flat(p) ? p.flat_samples : p.segs[t].samp_cnt;
     const uint32_t sb0 = is_flat(p) ? 0u : p.segs[t].samp0;
-    const uint32_t nb = (S + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
+    const uint32_t nb = is_flat(p) ? p.n_sample_blocks : (S + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
     if (!is_flat(p))
         for (uint32_t u = seg_tile0(p, t) + tid; u < seg_tile1(p, t); u += 1024) p.tseg[u] = (uint32_t)t;
     const uint64_t nt = (uint64_t)(seg_end(p, t) - seg_begin(p, t));
@@ -2054,6 +2063,7 @@ uint64_t max_tiles(int64_t n, int n_seg) { return (uint64_t)((n + TW - 1) / TW) 
 
 uint64_t max_sample_blocks(int64_t n, int n_seg)
 {
+    static_assert(SAMPLE_MAX_FLAT / DENSE_ROUNDS <= 2 * SAMPLE_MAX, "the blocks of a dense sample fit as well");
     const uint64_t a = (uint64_t)n_seg * (2 * SAMPLE_MAX / SAMPLE_BLOCK);
     const uint64_t b = (uint64_t)((n + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK) + (uint64_t)n_seg;
     return a < b ? a : b;
@@ -2094,8 +2104,8 @@ Layout make_layout(int64_t n, int n_cf, int n_seg)
     return L;
 }
 
-// samples taken from a segment of nt elements when the largest CF is cf_max
-uint32_t sample_count(uint64_t nt, double cf_max, bool flat)
+// samples taken from a segment of nt elements when the CFs range from cf_min to cf_max
+uint32_t sample_count(uint64_t nt, double cf_min, double cf_max, bool flat)
 {
     // layerwise: the larger of 32 CF_max and 1/64 of the tensor.  A small sample of a large tensor gives a wide
     // bracket: many more candidates than k, and bins so coarse that the keys near the bracket's lower end crowd
@@ -2104,7 +2114,16 @@ uint32_t sample_count(uint64_t nt, double cf_max, bool flat)
     if (!flat && target < nt / 64) target = nt / 64;
     if (target < 4096) target = 4096;
     if (target > (uint64_t)SAMPLE_MAX) target = SAMPLE_MAX;
-    target = (target + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK * SAMPLE_BLOCK;
+    if (flat) {
+        // The bracket spans about 8 standard deviations of a sampled rank, which is 8 sqrt(k nt / m) of the tensor's
+        // entries for m samples, and every candidate inside it costs the streaming pass a device-wide atomic (about
+        // ten per nanosecond all told): a dense selection from a large tensor (k = nt / cf_min) takes more samples,
+        // enough to keep that number near 2^19.
+        const double need = 64.0 * ((double)nt / cf_min) * (double)nt / 274877906944.0;  // 2^38
+        if (need > (double)target) target = need > (double)SAMPLE_MAX_FLAT ? (uint64_t)SAMPLE_MAX_FLAT : (uint64_t)need;
+    }
+    const uint64_t unit = target > (uint64_t)SAMPLE_MAX ? SAMPLE_BLOCK * DENSE_ROUNDS : SAMPLE_BLOCK;
+    target = (target + unit - 1) / unit * unit;
     return (nt <= 2 * target) ? (uint32_t)nt : (uint32_t)target;
 }
 
@@ -2224,10 +2243,11 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     if (n <= 0 || n > 2147483647LL || n_cf < 1 || n_cf > MAXCF || commit < 0 || commit >= n_cf) return GRAVAC_ERR_INVALID_ARG;
     if (((uintptr_t)grad & 15) || ((uintptr_t)residual & 15) || ((uintptr_t)map_idx & 15)) return GRAVAC_ERR_INVALID_ARG;
     if (n_seg < 0 || (n_seg > 0 && !seg_offsets) || (int64_t)n_seg > n) return GRAVAC_ERR_INVALID_ARG;
-    double cf_max = 1.0;
+    double cf_max = 1.0, cf_min = cf_list[0];
     for (int j = 0; j < n_cf; ++j) {
         if (!(cf_list[j] >= 1.0) || std::isinf(cf_list[j])) return GRAVAC_ERR_INVALID_ARG;
         if (cf_list[j] > cf_max) cf_max = cf_list[j];
+        if (cf_list[j] < cf_min) cf_min = cf_list[j];
     }
     const int ns = n_seg < 1 ? 1 : n_seg;
     if (n_seg >= 1) {
@@ -2283,12 +2303,16 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
 
     int64_t total_out = 0;
     uint32_t max_seg_tiles = 1;  // tiles of the largest segment
+    bool dense_sample = false;
     if (ns == 1) {
         for (int j = 0; j < n_cf; ++j) p.flat_k[j] = (uint32_t)gravac_topk_count(n, cf_list[j]);
-        p.flat_samples = sample_count((uint64_t)n, cf_max, true);
+        p.flat_samples = sample_count((uint64_t)n, cf_min, cf_max, true);
         p.n_tiles = (uint32_t)((n + TW - 1) / TW);
         max_seg_tiles = p.n_tiles;
-        p.n_sample_blocks = (p.flat_samples + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
+        // more than SAMPLE_MAX samples (never a tensor read whole): DENSE_ROUNDS * SAMPLE_BLOCK samples per block
+        dense_sample = p.flat_samples > (uint32_t)SAMPLE_MAX && (int64_t)p.flat_samples != n;
+        const uint32_t per_block = dense_sample ? SAMPLE_BLOCK * DENSE_ROUNDS : SAMPLE_BLOCK;
+        p.n_sample_blocks = (p.flat_samples + per_block - 1) / per_block;
         total_out = p.flat_k[commit];
         if (total_out > out_capacity) return GRAVAC_ERR_CAPACITY;
     } else {
@@ -2301,7 +2325,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
             const uint64_t tt = (uint64_t)((nt + TW - 1) / TW);
             tiles += tt;
             if (tt > max_seg_tiles) max_seg_tiles = (uint32_t)tt;
-            sblocks += (sample_count((uint64_t)nt, cf_max, false) + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
+            sblocks += (sample_count((uint64_t)nt, cf_min, cf_max, false) + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
         }
         if (total_out > out_capacity) return GRAVAC_ERR_CAPACITY;
         if (tiles > max_tiles(n, ns) || sblocks > max_sample_blocks(n, ns)) return GRAVAC_ERR_WORKSPACE;
@@ -2322,7 +2346,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
             std::memset(&g, 0, sizeof(g));
             g.begin = seg_offsets[t]; g.end = seg_offsets[t + 1]; g.koff = koff;
             g.tile0 = tile_at; tile_at += (uint32_t)((nt + TW - 1) / TW); g.tile1 = tile_at;
-            g.samp0 = sb_at; g.samp_cnt = sample_count((uint64_t)nt, cf_max, false);
+            g.samp0 = sb_at; g.samp_cnt = sample_count((uint64_t)nt, cf_min, cf_max, false);
             const uint32_t nb = (g.samp_cnt + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
             for (uint32_t b = 0; b < nb; ++b) sblock_seg[sb_at + b] = (uint32_t)t;
             sb_at += nb;
@@ -2363,7 +2387,8 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         (void)hipEventRecord(g_ev[0], stream);
     }
     if (p.n_sample_blocks && !random && !(flags & GRAVAC_FLAG_REUSE_THRESHOLDS))
-        hipLaunchKernelGGL(sample_kernel, dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL(dense_sample ? sample_kernel<DENSE_ROUNDS> : sample_kernel<1>, dim3(p.n_sample_blocks), dim3(256), 0,
+                           stream, p);
     hipLaunchKernelGGL(threshold_kernel, dim3(ns), dim3(1024), 0, stream, p);
     {
         // events 1 and 2 take the streaming kernel's own begin and end time stamps

@@ -102,6 +102,22 @@ def test_config3_vgg16_cf1000_five_iterations():
         res_host = new_res
 
 
+def test_vgg16_shape_dense_selection_with_the_larger_sample():
+    """CF 10 on the VGG16-shaped gradient: k n is large enough for the flat sampling pass to take its larger
+    sample (eight groups per thread).  Two iterations without threshold reuse, so both run that sampling pass;
+    a second CF rides along and is committed in the second iteration."""
+    n = workloads.VGG16_N_CONV + workloads.VGG16_N_FC
+    cfs = [10.0, 1000.0]
+    res_t = torch.zeros(n, device="cuda")
+    for it, commit in enumerate([0, 1]):
+        comp = binding.Compressor(n, cfs, commit)
+        grad = workloads.config3_grad(it)
+        acc = res_t.cpu().numpy() + grad
+        idx, val, stats, st = run_gpu(comp, grad, res_t)
+        check_properties(acc, idx, val, stats[0, commit], res_t.cpu().numpy(), comp.k_total, f"dense sample, iteration {it}")
+        del comp
+
+
 def test_config4_lstm_two_cfs():
     g = workloads.config4_grad(0)
     n = g.size

@@ -1198,6 +1198,7 @@ __global__ __launch_bounds__(256) void locate_kernel(Params p)
 // k-th largest.  For a segment that took the exact route the plan is derived here, by every
 // wavefront for itself, from the rebuilt candidate histogram (its first tile's wavefront records it).
 // ---------------------------------------------------------------------------------------------
+template <int NCF>  // compiled for calls with up to NCF CFs: the loops over the CFs are unrolled
 __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
@@ -1237,10 +1238,10 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
         }
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // rp is read back by the same wavefront
     }
-    uint32_t mode[MAXCF], base[MAXCF], span[MAXCF];
+    uint32_t mode[NCF], base[NCF], span[NCF];
     bool work = false;
 #pragma unroll
-    for (int j = 0; j < MAXCF; ++j) {
+    for (int j = 0; j < NCF; ++j) {
         mode[j] = MODE_RESOLVED; base[j] = 0; span[j] = 0;
         if (j < p.n_cf) {
             const CfState* st = &p.st[(size_t)t * p.n_cf + j];
@@ -1280,7 +1281,7 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
             const uint32_t key = kq[q];
             const bool live = i0 + q * 64 + lane < cnt;
 #pragma unroll
-            for (int j = 0; j < MAXCF; ++j) {
+            for (int j = 0; j < NCF; ++j) {
                 if (j >= p.n_cf) continue;
                 const bool in = live && key >= base[j] && key - base[j] <= span[j];
                 if (mode[j] == MODE_GATHER) {
@@ -1388,6 +1389,7 @@ __global__ __launch_bounds__(256) void resolve_kernel(Params p)
 // K3: one wavefront per tile: candidates above / at the committed threshold, energy above each
 // CF's threshold.  Written for every tile, so that the scan needs no second look at cand_cnt.
 // ---------------------------------------------------------------------------------------------
+template <int NCF>  // as refine_kernel
 __global__ __launch_bounds__(LWG) void count_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
@@ -1405,16 +1407,16 @@ __global__ __launch_bounds__(LWG) void count_kernel(Params p)
         return;
     }
     const int t = tile_seg(p, u);
-    uint32_t tau[MAXCF];
+    uint32_t tau[NCF];
     uint32_t tc = 0;
 #pragma unroll
-    for (int j = 0; j < MAXCF; ++j) {
+    for (int j = 0; j < NCF; ++j) {
         tau[j] = (j < p.n_cf) ? p.st[(size_t)t * p.n_cf + j].tau : NONE;
         if (j == p.commit) tc = tau[j];
     }
-    double ss[MAXCF];
+    double ss[NCF];
 #pragma unroll
-    for (int j = 0; j < MAXCF; ++j) ss[j] = 0.0;
+    for (int j = 0; j < NCF; ++j) ss[j] = 0.0;
     uint32_t g = 0, e = 0;
     const float* cv = p.cand_val + (size_t)u * TW;
     const int32_t* ci = p.cand_idx + (size_t)u * TW;
@@ -1441,14 +1443,14 @@ __global__ __launch_bounds__(LWG) void count_kernel(Params p)
                 g += (key > tc);
                 e += (key == tc);
 #pragma unroll
-                for (int j = 0; j < MAXCF; ++j) if (j < p.n_cf && key + at_tau > tau[j]) ss[j] += dv * dv;
+                for (int j = 0; j < NCF; ++j) if (j < p.n_cf && key + at_tau > tau[j]) ss[j] += dv * dv;
             }
         }
     }
     g = wave_sum(g);
     e = wave_sum(e);
 #pragma unroll
-    for (int j = 0; j < MAXCF; ++j) {
+    for (int j = 0; j < NCF; ++j) {
         if (j < p.n_cf) {
             const double x = wave_sum(ss[j]);
             if (lane == 0) p.sss[(size_t)u * p.n_cf + j] = x;
@@ -2407,9 +2409,14 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     else
         hipLaunchKernelGGL((stream_kernel<SM_EXACT, false>), dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
     // exact resolution on the candidates, then count and emit
-    hipLaunchKernelGGL(refine_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
+    // the candidate-list kernels with loops over the CFs exist for 1, 2, 4 and MAXCF CFs
+    const int ncf_form = n_cf <= 1 ? 0 : n_cf <= 2 ? 1 : n_cf <= 4 ? 2 : 3;
+    static_assert(MAXCF >= 4, "forms for 1, 2, 4 and MAXCF CFs");
+    void (*const refine_forms[4])(Params) = {refine_kernel<1>, refine_kernel<2>, refine_kernel<4>, refine_kernel<MAXCF>};
+    void (*const count_forms[4])(Params) = {count_kernel<1>, count_kernel<2>, count_kernel<4>, count_kernel<MAXCF>};
+    hipLaunchKernelGGL(refine_forms[ncf_form], dim3(light_grid), dim3(LWG), 0, stream, p);
     hipLaunchKernelGGL(resolve_kernel, dim3(ns * n_cf), dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(count_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
+    hipLaunchKernelGGL(count_forms[ncf_form], dim3(light_grid), dim3(LWG), 0, stream, p);
     hipLaunchKernelGGL(scan_kernel, dim3(ns, scan_slices + n_cf), dim3(SCAN_T), 0, stream, p, scan_slices);
     hipLaunchKernelGGL(emit_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
     if (prof) {

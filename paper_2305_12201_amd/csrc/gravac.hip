@@ -57,6 +57,10 @@ constexpr int WAVES = WG / 64;
 #endif
 constexpr int LWG = GV_LWG;         // threads per workgroup of the candidate-list kernels (refine, count, emit)
 constexpr int LWAVES = LWG / 64;
+constexpr int VCHUNK = 256;          // dense tiles: slots of one sub-tile list a wavefront takes per load, four per lane
+constexpr int VLISTS = 4;            // ... from this many of the tile's lists at a time (registers)
+constexpr uint32_t DENSE_TILE = TW / 4;  // a tile with at least this many candidates is walked that way
+static_assert(TS % VCHUNK == 0, "a sub-tile list is a whole number of such chunks");
 constexpr int ROW = 256;            // elements one wavefront touches per load (64 lanes x float4)
 #ifndef GV_ROWS
 #define GV_ROWS 4                   // rows a wavefront keeps in flight
@@ -274,6 +278,13 @@ __device__ __forceinline__ uint32_t hash32(uint32_t x)
 struct TileCands {
     uint32_t start[SUB + 1];  // start[j] = candidates in sub-tiles before j; start[SUB] = all
     __device__ __forceinline__ uint32_t total() const { return start[SUB]; }
+    __device__ __forceinline__ uint32_t longest() const  // candidates of the fullest sub-tile
+    {
+        uint32_t m = 0;
+#pragma unroll
+        for (int j = 0; j < SUB; ++j) m = max(m, start[j + 1] - start[j]);
+        return m;
+    }
     // slot (relative to the tile's first slot) of the tile's i-th candidate
     __device__ __forceinline__ uint32_t slot(uint32_t i) const
     {
@@ -1256,48 +1267,79 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
     if (!work || cnt == 0) return;
     const float* cv = p.cand_val + (size_t)u * TW;
     const int32_t* ci = p.cand_idx + (size_t)u * TW;
-    for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
-        // eight loads in flight per lane; an absent slot gets a key that lies in no bin (base > key)
-        uint32_t kq[8];
-        if (p.random) {  // the key comes from the index: all loads first, then the arithmetic
+    // what one candidate key adds, per CF, if it lies in the bin that holds the k-th largest
+    const auto take = [&](uint32_t key, bool live) {
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const uint32_t i = i0 + q * 64 + lane;
-                kq[q] = (uint32_t)ci[(i < cnt) ? tc.slot(i) : 0u];
-            }
-#pragma unroll
-            for (int q = 0; q < 8; ++q) kq[q] = priority_of(p.rk_s0, p.rk_s1, kq[q]);
-        } else {
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const uint32_t i = i0 + q * 64 + lane;
-                kq[q] = key_of(cv[(i < cnt) ? tc.slot(i) : 0u]);
+        for (int j = 0; j < NCF; ++j) {
+            if (j >= p.n_cf) continue;
+            const bool in = live && key >= base[j] && key - base[j] <= span[j];
+            if (mode[j] == MODE_GATHER) {
+                // one counter update per wavefront: the lanes with a key in the bin take consecutive slots
+                const uint64_t m = __ballot(in);
+                if (m != 0ull) {
+                    const size_t lst = ((size_t)t * p.n_cf + j) * REP + (blockIdx.x & (REP - 1));
+                    const int leader = __ffsll((unsigned long long)m) - 1;
+                    uint32_t first = 0;
+                    if (lane == leader) first = atomicAdd(&p.list_cnt[lst * 32], (uint32_t)__popcll(m));
+                    first = __shfl(first, leader, 64);
+                    const uint32_t pos = first + lanes_below(m);
+                    if (in && pos < LCAP) p.list[lst * LCAP + pos] = key;
+                }
+            } else if (mode[j] == MODE_HIST && in) {
+                atomicAdd(&p.hist2[((size_t)t * p.n_cf + j) * NBIN + (key - base[j])], 1u);
             }
         }
+    };
+    if (cnt < DENSE_TILE) {
+        for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
+            // eight loads in flight per lane
+            uint32_t kq[8];
+            if (p.random) {  // the key comes from the index: all loads first, then the arithmetic
 #pragma unroll
-        for (int q = 0; q < 8; ++q) if (i0 + q * 64 + lane >= cnt) kq[q] = 0u;
+                for (int q = 0; q < 8; ++q) {
+                    const uint32_t i = i0 + q * 64 + lane;
+                    kq[q] = (uint32_t)ci[(i < cnt) ? tc.slot(i) : 0u];
+                }
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const uint32_t key = kq[q];
-            const bool live = i0 + q * 64 + lane < cnt;
+                for (int q = 0; q < 8; ++q) kq[q] = priority_of(p.rk_s0, p.rk_s1, kq[q]);
+            } else {
 #pragma unroll
-            for (int j = 0; j < NCF; ++j) {
-                if (j >= p.n_cf) continue;
-                const bool in = live && key >= base[j] && key - base[j] <= span[j];
-                if (mode[j] == MODE_GATHER) {
-                    // one counter update per wavefront: the lanes with a key in the bin take consecutive slots
-                    const uint64_t m = __ballot(in);
-                    if (m != 0ull) {
-                        const size_t lst = ((size_t)t * p.n_cf + j) * REP + (blockIdx.x & (REP - 1));
-                        const int leader = __ffsll((unsigned long long)m) - 1;
-                        uint32_t first = 0;
-                        if (lane == leader) first = atomicAdd(&p.list_cnt[lst * 32], (uint32_t)__popcll(m));
-                        first = __shfl(first, leader, 64);
-                        const uint32_t pos = first + lanes_below(m);
-                        if (in && pos < LCAP) p.list[lst * LCAP + pos] = key;
-                    }
-                } else if (mode[j] == MODE_HIST && in) {
-                    atomicAdd(&p.hist2[((size_t)t * p.n_cf + j) * NBIN + (key - base[j])], 1u);
+                for (int q = 0; q < 8; ++q) {
+                    const uint32_t i = i0 + q * 64 + lane;
+                    kq[q] = key_of(cv[(i < cnt) ? tc.slot(i) : 0u]);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) take(kq[q], i0 + q * 64 + lane < cnt);
+        }
+        return;
+    }
+    {
+        // a dense tile: four consecutive slots per lane and load, the same VCHUNK slots of VLISTS lists in flight
+        // together (see count_kernel)
+        const v4f* cv4 = (const v4f*)cv;
+        const v4i* ci4 = (const v4i*)ci;
+        const uint32_t nmax = tc.longest();
+        for (uint32_t c0 = 0; c0 < nmax; c0 += VCHUNK) {
+            const uint32_t first = c0 + 4 * lane;  // < TS
+#pragma unroll
+            for (int j0 = 0; j0 < SUB; j0 += VLISTS) {
+                v4i kv[VLISTS];  // the bits the key is made from: the value's, or the index for Random-k
+                if (p.random) {
+#pragma unroll
+                    for (int j = 0; j < VLISTS; ++j) kv[j] = ci4[(j0 + j) * (TS / 4) + first / 4];
+                } else {
+#pragma unroll
+                    for (int j = 0; j < VLISTS; ++j) kv[j] = __builtin_bit_cast(v4i, cv4[(j0 + j) * (TS / 4) + first / 4]);
+                }
+#pragma unroll
+                for (int j = 0; j < VLISTS; ++j) {
+                    const uint32_t n = tc.start[j0 + j + 1] - tc.start[j0 + j];
+                    if (n <= c0) continue;  // the same for all lanes
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        take(p.random ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)kv[j][x]) : ((uint32_t)kv[j][x] & 0x7FFFFFFFu),
+                             first + x < n);
                 }
             }
         }
@@ -1423,27 +1465,66 @@ __global__ __launch_bounds__(LWG) void count_kernel(Params p)
     // Random-k: priorities are distinct, the entry at the threshold is the last one selected and has no
     // particular magnitude, so its energy is summed here (Top-k adds need * tau^2 in the scan instead)
     const uint32_t at_tau = p.random ? 1u : 0u;
-    for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
-        float vq[8];
-        uint32_t kq[8];
+    if (cnt < DENSE_TILE) {
+        for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
+            float vq[8];
+            uint32_t kq[8];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const uint32_t i = i0 + q * 64 + lane;
-            const uint32_t sl = (i < cnt) ? tcs.slot(i) : 0u;
-            vq[q] = cv[sl];
-            kq[q] = p.random ? (uint32_t)ci[sl] : 0u;   // all loads first, then the arithmetic
+            for (int q = 0; q < 8; ++q) {
+                const uint32_t i = i0 + q * 64 + lane;
+                const uint32_t sl = (i < cnt) ? tcs.slot(i) : 0u;
+                vq[q] = cv[sl];
+                kq[q] = p.random ? (uint32_t)ci[sl] : 0u;   // all loads first, then the arithmetic
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) kq[q] = p.random ? priority_of(p.rk_s0, p.rk_s1, kq[q]) : key_of(vq[q]);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (i0 + q * 64 + lane < cnt) {
+                    const uint32_t key = kq[q];
+                    const double dv = (double)vq[q];
+                    g += (key > tc);
+                    e += (key == tc);
+#pragma unroll
+                    for (int j = 0; j < NCF; ++j) if (j < p.n_cf && key + at_tau > tau[j]) ss[j] += dv * dv;
+                }
+            }
         }
+    } else {
+        // A dense tile: four consecutive slots per lane and load, the same VCHUNK slots of VLISTS lists in flight
+        // together (a list of TS slots is aligned to 16 bytes; slots past a list's count hold older entries and
+        // are masked off).  A sparse tile would leave most lanes of such a walk idle and takes the loop below.
+        const v4f* cv4 = (const v4f*)cv;
+        const v4i* ci4 = (const v4i*)ci;
+        const uint32_t nmax = tcs.longest();
+        static_assert(SUB % VLISTS == 0, "the lists are taken VLISTS at a time");
+        for (uint32_t c0 = 0; c0 < nmax; c0 += VCHUNK) {
+            const uint32_t first = c0 + 4 * lane;  // < TS
 #pragma unroll
-        for (int q = 0; q < 8; ++q) kq[q] = p.random ? priority_of(p.rk_s0, p.rk_s1, kq[q]) : key_of(vq[q]);
+            for (int j0 = 0; j0 < SUB; j0 += VLISTS) {
+                v4f v[VLISTS];
+                v4i ix[VLISTS];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            if (i0 + q * 64 + lane < cnt) {
-                const uint32_t key = kq[q];
-                const double dv = (double)vq[q];
-                g += (key > tc);
-                e += (key == tc);
+                for (int j = 0; j < VLISTS; ++j) v[j] = cv4[(j0 + j) * (TS / 4) + first / 4];
+                if (p.random) {
 #pragma unroll
-                for (int j = 0; j < NCF; ++j) if (j < p.n_cf && key + at_tau > tau[j]) ss[j] += dv * dv;
+                    for (int j = 0; j < VLISTS; ++j) ix[j] = ci4[(j0 + j) * (TS / 4) + first / 4];
+                }
+#pragma unroll
+                for (int j = 0; j < VLISTS; ++j) {
+                    const uint32_t n = tcs.start[j0 + j + 1] - tcs.start[j0 + j];
+                    if (n <= c0) continue;  // the same for all lanes
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        const bool live = first + x < n;
+                        const uint32_t key = p.random ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)ix[j][x]) : key_of(v[j][x]);
+                        const double dv = (double)v[j][x];
+                        g += (live && key > tc);
+                        e += (live && key == tc);
+#pragma unroll
+                        for (int c = 0; c < NCF; ++c) if (c < p.n_cf && live && key + at_tau > tau[c]) ss[c] += dv * dv;
+                    }
+                }
             }
         }
     }

@@ -665,6 +665,7 @@ struct TileCtx {
     int ncf;
     uint32_t s0, s1;  // Random-k keys
     uint32_t pz;      // first pass: keys >= pz leave +0 in the residual instead of acc (NONE: none)
+    uint32_t nb;      // bins of the histogram in use: a key whose bin number is nb or more counts as above the bracket
 };
 
 __device__ __forceinline__ void cand_hist(TileCtx& c, uint32_t key)
@@ -673,7 +674,7 @@ __device__ __forceinline__ void cand_hist(TileCtx& c, uint32_t key)
     for (int j = 0; j < MAXCF; ++j) {
         if (j < c.ncf && key >= c.lo[j]) {
             const uint32_t b = (key - c.lo[j]) >> c.sh[j];
-            if (b >= OVF) c.ovf[j]++;
+            if (b >= c.nb) c.ovf[j]++;
             else atomicAdd(&c.h1[j * REP * NBIN + b], 1u);
         }
     }
@@ -831,6 +832,9 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
         c.sh[j] = 0;
     }
     c.pz = NONE;
+    // The exact route bins one coarse bin (or one bin of the first histogram) into 1024 parts: what lies above it
+    // needs no bin of its own, and half of the histogram updates with it.
+    c.nb = EF ? OVF : 1024u;
     if (EF) {
         c.lo_min = p.seg[t].lo_min;
         if (M == SM_EF) c.pz = p.seg[t].pz;

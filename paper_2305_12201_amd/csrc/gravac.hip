@@ -1097,9 +1097,21 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
                         const TileCands tcs = tile_cands(p, u);
                         const float* cv = p.cand_val + (size_t)u * TW;
                         const int32_t* ci = p.cand_idx + (size_t)u * TW;
-                        for (uint32_t i = lane; i < tcs.total(); i += 64) {
-                            const uint32_t sl = tcs.slot(i);
-                            atomicAdd(&h[cand_key(p, p.random ? ci[sl] : 0, cv[sl]) >> 20], 1u);
+                        const uint32_t cnt = tcs.total();
+                        for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
+                            // eight loads in flight per lane (an absent candidate reads slot 0 and is not counted)
+                            float vq[8];
+                            int32_t iq[8];
+#pragma unroll
+                            for (int q = 0; q < 8; ++q) {
+                                const uint32_t i = i0 + q * 64 + lane;
+                                const uint32_t sl = (i < cnt) ? tcs.slot(i) : 0u;
+                                vq[q] = cv[sl];
+                                iq[q] = p.random ? ci[sl] : 0;
+                            }
+#pragma unroll
+                            for (int q = 0; q < 8; ++q)
+                                if (i0 + q * 64 + lane < cnt) atomicAdd(&h[cand_key(p, iq[q], vq[q]) >> 20], 1u);
                         }
                     } else {
                         const uint32_t pz = p.single ? NONE : p.seg[t].pz;
@@ -1109,11 +1121,20 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
                             const TileCands tcs = tile_cands(p, u);
                             const float* cv = p.cand_val + (size_t)u * TW;
                             const int32_t* ci = p.cand_idx + (size_t)u * TW;
-                            for (uint32_t i = lane; i < tcs.total(); i += 64) {
-                                const uint32_t sl = tcs.slot(i);
-                                const int32_t idx = ci[sl];
-                                const float val = cv[sl];
-                                if (cand_key(p, idx, val) >= pz) p.res[idx] = val;
+                            const uint32_t cnt = tcs.total();
+                            for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
+                                float vq[8];
+                                int32_t iq[8];
+#pragma unroll
+                                for (int q = 0; q < 8; ++q) {
+                                    const uint32_t i = i0 + q * 64 + lane;
+                                    const uint32_t sl = (i < cnt) ? tcs.slot(i) : 0u;
+                                    vq[q] = cv[sl];
+                                    iq[q] = ci[sl];
+                                }
+#pragma unroll
+                                for (int q = 0; q < 8; ++q)
+                                    if (i0 + q * 64 + lane < cnt && cand_key(p, iq[q], vq[q]) >= pz) p.res[iq[q]] = vq[q];
                             }
                             __threadfence_block();  // the loads below are this wavefront's own, of the same addresses
                         }

@@ -79,7 +79,8 @@ constexpr int SBIN = 4096;          // bins of the sample histogram (key >> 19)
 constexpr int SAMPLE_BLOCK = 1024;  // samples per workgroup of the sampling kernel
 constexpr int SAMPLE_MAX = 65536;   // samples per segment at most (unless the segment is read whole)
 constexpr int SAMPLE_MAX_FLAT = 524288;  // flat mode, a large k: see sample_count
-constexpr int DENSE_ROUNDS = 8;          // ... whose sample blocks are DENSE_ROUNDS * SAMPLE_BLOCK samples each
+constexpr int DENSE_ROUNDS = 8;          // ... whose sample blocks are up to DENSE_ROUNDS * SAMPLE_BLOCK samples each
+constexpr int DENSE_BLOCKS = 128;        // ... so that there are at most this many of them
 constexpr int LCAP = 4096;          // keys a gather list can hold
 constexpr int MAXCF = GRAVAC_MAX_CF;
 constexpr double ZMARGIN = 5.0;     // safety margin of the sampled rank, in standard deviations
@@ -2171,7 +2172,8 @@ uint64_t max_tiles(int64_t n, int n_seg) { return (uint64_t)((n + TW - 1) / TW) 
 
 uint64_t max_sample_blocks(int64_t n, int n_seg)
 {
-    static_assert(SAMPLE_MAX_FLAT / DENSE_ROUNDS <= 2 * SAMPLE_MAX, "the blocks of a dense sample fit as well");
+    static_assert(DENSE_BLOCKS * SAMPLE_BLOCK <= 2 * SAMPLE_MAX && SAMPLE_MAX_FLAT <= DENSE_BLOCKS * SAMPLE_BLOCK * DENSE_ROUNDS,
+                  "the blocks of a dense sample fit as well");
     const uint64_t a = (uint64_t)n_seg * (2 * SAMPLE_MAX / SAMPLE_BLOCK);
     const uint64_t b = (uint64_t)((n + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK) + (uint64_t)n_seg;
     return a < b ? a : b;
@@ -2223,11 +2225,12 @@ uint32_t sample_count(uint64_t nt, double cf_min, double cf_max, bool flat)
     if (target < 4096) target = 4096;
     if (target > (uint64_t)SAMPLE_MAX) target = SAMPLE_MAX;
     if (flat) {
-        // The bracket spans about 8 standard deviations of a sampled rank, which is 8 sqrt(k nt / m) of the tensor's
+        // The bracket spans about 10 standard deviations of a sampled rank, which is 10 sqrt(k nt / m) of the tensor's
         // entries for m samples, and every candidate inside it costs the streaming pass a device-wide atomic (about
-        // ten per nanosecond all told): a dense selection from a large tensor (k = nt / cf_min) takes more samples,
-        // enough to keep that number near 2^19.
-        const double need = 64.0 * ((double)nt / cf_min) * (double)nt / 274877906944.0;  // 2^38
+        // ten per nanosecond all told, and a gradient whose large entries sit together sends them all at once): a
+        // selection of many entries from a large tensor (k = nt / cf_min) takes more samples, enough to keep that
+        // number near 300,000.
+        const double need = 64.0 * ((double)nt / cf_min) * (double)nt / 68719476736.0;  // 2^36
         if (need > (double)target) target = need > (double)SAMPLE_MAX_FLAT ? (uint64_t)SAMPLE_MAX_FLAT : (uint64_t)need;
     }
     const uint64_t unit = target > (uint64_t)SAMPLE_MAX ? SAMPLE_BLOCK * DENSE_ROUNDS : SAMPLE_BLOCK;
@@ -2411,15 +2414,19 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
 
     int64_t total_out = 0;
     uint32_t max_seg_tiles = 1;  // tiles of the largest segment
-    bool dense_sample = false;
+    int sample_rounds = 1;  // groups per thread of the sampling kernel
     if (ns == 1) {
         for (int j = 0; j < n_cf; ++j) p.flat_k[j] = (uint32_t)gravac_topk_count(n, cf_list[j]);
         p.flat_samples = sample_count((uint64_t)n, cf_min, cf_max, true);
         p.n_tiles = (uint32_t)((n + TW - 1) / TW);
         max_seg_tiles = p.n_tiles;
-        // more than SAMPLE_MAX samples (never a tensor read whole): DENSE_ROUNDS * SAMPLE_BLOCK samples per block
-        dense_sample = p.flat_samples > (uint32_t)SAMPLE_MAX && (int64_t)p.flat_samples != n;
-        const uint32_t per_block = dense_sample ? SAMPLE_BLOCK * DENSE_ROUNDS : SAMPLE_BLOCK;
+        // more than SAMPLE_MAX samples (never a tensor read whole): 2, 4 or 8 times SAMPLE_BLOCK samples per block, the
+        // fewest that leave at most DENSE_BLOCKS blocks (more blocks keep more loads in flight, fewer cost the
+        // threshold kernel less)
+        if (p.flat_samples > (uint32_t)SAMPLE_MAX && (int64_t)p.flat_samples != n)
+            while (sample_rounds < DENSE_ROUNDS && p.flat_samples > (uint32_t)(DENSE_BLOCKS * SAMPLE_BLOCK * sample_rounds))
+                sample_rounds *= 2;
+        const uint32_t per_block = SAMPLE_BLOCK * sample_rounds;
         p.n_sample_blocks = (p.flat_samples + per_block - 1) / per_block;
         total_out = p.flat_k[commit];
         if (total_out > out_capacity) return GRAVAC_ERR_CAPACITY;
@@ -2495,8 +2502,9 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         (void)hipEventRecord(g_ev[0], stream);
     }
     if (p.n_sample_blocks && !random && !(flags & GRAVAC_FLAG_REUSE_THRESHOLDS))
-        hipLaunchKernelGGL(dense_sample ? sample_kernel<DENSE_ROUNDS> : sample_kernel<1>, dim3(p.n_sample_blocks), dim3(256), 0,
-                           stream, p);
+        hipLaunchKernelGGL(sample_rounds == 1 ? sample_kernel<1> : sample_rounds == 2 ? sample_kernel<2>
+                           : sample_rounds == 4 ? sample_kernel<4> : sample_kernel<DENSE_ROUNDS>,
+                           dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
     hipLaunchKernelGGL(threshold_kernel, dim3(ns), dim3(1024), 0, stream, p);
     {
         // events 1 and 2 take the streaming kernel's own begin and end time stamps

@@ -79,7 +79,7 @@ constexpr int SBIN = 4096;          // bins of the sample histogram (key >> 19)
 constexpr int SAMPLE_BLOCK = 1024;  // samples per workgroup of the sampling kernel
 constexpr int SAMPLE_MAX = 65536;   // samples per segment at most (unless the segment is read whole)
 constexpr int SAMPLE_MAX_FLAT = 524288;  // flat mode, a large k: see sample_count
-constexpr int DENSE_ROUNDS = 8;          // ... whose sample blocks are up to DENSE_ROUNDS * SAMPLE_BLOCK samples each
+constexpr int DENSE_ROUNDS = 4;          // ... whose sample blocks are up to DENSE_ROUNDS * SAMPLE_BLOCK samples each
 constexpr int DENSE_BLOCKS = 128;        // ... so that there are at most this many of them
 constexpr int LCAP = 4096;          // keys a gather list can hold
 constexpr int MAXCF = GRAVAC_MAX_CF;
@@ -2420,7 +2420,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         p.flat_samples = sample_count((uint64_t)n, cf_min, cf_max, true);
         p.n_tiles = (uint32_t)((n + TW - 1) / TW);
         max_seg_tiles = p.n_tiles;
-        // more than SAMPLE_MAX samples (never a tensor read whole): 2, 4 or 8 times SAMPLE_BLOCK samples per block, the
+        // more than SAMPLE_MAX samples (never a tensor read whole): 2 or 4 times SAMPLE_BLOCK samples per block, the
         // fewest that leave at most DENSE_BLOCKS blocks (more blocks keep more loads in flight, fewer cost the
         // threshold kernel less)
         if (p.flat_samples > (uint32_t)SAMPLE_MAX && (int64_t)p.flat_samples != n)
@@ -2502,8 +2502,8 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         (void)hipEventRecord(g_ev[0], stream);
     }
     if (p.n_sample_blocks && !random && !(flags & GRAVAC_FLAG_REUSE_THRESHOLDS))
-        hipLaunchKernelGGL(sample_rounds == 1 ? sample_kernel<1> : sample_rounds == 2 ? sample_kernel<2>
-                           : sample_rounds == 4 ? sample_kernel<4> : sample_kernel<DENSE_ROUNDS>,
+        static_assert(DENSE_ROUNDS == 4, "forms of the sampling kernel for 1, 2 and 4 groups per thread");
+        hipLaunchKernelGGL(sample_rounds == 1 ? sample_kernel<1> : sample_rounds == 2 ? sample_kernel<2> : sample_kernel<4>,
                            dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
     hipLaunchKernelGGL(threshold_kernel, dim3(ns), dim3(1024), 0, stream, p);
     {

@@ -58,9 +58,13 @@ extern "C" {
 #define GRAVAC_FLAG_REUSE_THRESHOLDS 4u /* for iterative use: the workspace has not been touched since the previous
                                          gravac_compress call made with it; if that call had the same n, cf_list and
                                          segment table, its candidate histogram and thresholds give this call's
-                                         bounds and replace the sampling pass.  Results are the same in every case: a prediction that
-                                         turns out wrong, or a workspace that holds no matching call, sends the
-                                         affected segments through the exact-histogram route (slower, never wrong). */
+                                         bounds and replace the sampling pass.  Results are the same in every case: a
+                                         prediction that turns out wrong sends the affected segments through the
+                                         exact-histogram route (slower, never wrong).  The flag may be given on every
+                                         call: if the call this process last issued with the workspace had another
+                                         shape or CF list, or there was none, the call samples as if the flag were
+                                         absent; a workspace whose contents were lost in between is recognised on the
+                                         device and takes the exact route. */
 
 /*
  * Number of pairs a call will emit for a tensor of n elements at compression factor cf:

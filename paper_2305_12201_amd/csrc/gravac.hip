@@ -2284,6 +2284,38 @@ void staging_release(StagingSlot* s, bool recorded)
     s->busy = false;
 }
 
+// What this process last asked of each workspace (the signature of the last call issued with it), so that a call
+// that wants to reuse thresholds on a workspace whose last call had another shape, or that this process has never
+// used, can be told apart on the host: it samples like a call without the flag, which costs one pass, whereas on
+// the device the mismatch would only show once the sampling kernel can no longer be launched and every segment
+// would take the exact route.  A hint only: the device still checks the signature the last completed call left in
+// the workspace.  A small ring; a workspace that has dropped out of it samples once.
+struct WorkspaceMemo {
+    const void* ws = nullptr;
+    uint64_t sig = 0;
+};
+constexpr int WS_MEMO = 64;
+WorkspaceMemo g_ws_memo[WS_MEMO];
+int g_ws_memo_next = 0;
+std::mutex g_ws_memo_mutex;
+
+// records sig as the last call on ws; returns whether the call before it on ws had the same signature
+bool ws_memo_exchange(const void* ws, uint64_t sig)
+{
+    std::lock_guard<std::mutex> lock(g_ws_memo_mutex);
+    for (int i = 0; i < WS_MEMO; ++i) {
+        if (g_ws_memo[i].ws == ws) {
+            const bool same = g_ws_memo[i].sig == sig;
+            g_ws_memo[i].sig = sig;
+            return same;
+        }
+    }
+    g_ws_memo[g_ws_memo_next].ws = ws;
+    g_ws_memo[g_ws_memo_next].sig = sig;
+    g_ws_memo_next = (g_ws_memo_next + 1) % WS_MEMO;
+    return false;
+}
+
 std::mutex g_prof_mutex;
 hipEvent_t g_ev[4];
 bool g_ev_ready = false;
@@ -2483,6 +2515,9 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         if (ns > 1) for (int t = 0; t <= ns; ++t) mix((uint64_t)seg_offsets[t]);
         if (h == 0) h = 1;  // 0 marks "no completed call"
         p.sig_lo = (uint32_t)h; p.sig_hi = (uint32_t)(h >> 32);
+        // thresholds can only be reused from a call of the same signature: without one, sample
+        if (!ws_memo_exchange(workspace, h)) flags &= ~(unsigned)GRAVAC_FLAG_REUSE_THRESHOLDS;
+        p.flags = flags;
     }
     const uint32_t tile_grid = (p.n_tiles + WAVES - 1) / WAVES;
     const uint32_t sub_grid = (p.n_tiles * SUB + WAVES - 1) / WAVES;

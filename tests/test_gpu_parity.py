@@ -418,16 +418,21 @@ def test_reuse_thresholds_steady_state():
 
 def test_reuse_thresholds_without_history_or_with_another_shape():
     n = 500_001
-    g = [workloads.normal_gradient(n, 1e-3, seed=s) for s in range(3)]
-    # a fresh workspace holds no completed call: the exact route is taken, the result is the same
+    g = [workloads.normal_gradient(n, 1e-3, seed=s) for s in range(4)]
+    # a workspace this process has not used yet: the call samples, as if the flag were absent
     st, comp = _iterate(n, [100.0], 0, g[:1], [REUSE])
-    assert st[0]["any_fallback"] == 1
-    # the same workspace, another CF list: the signature differs, no reuse; then the same list again: reuse works
+    assert st[0]["any_fallback"] == 0
+    # the same workspace, another CF list: no reuse either, the call samples; then the same list again: reuse works
     comp2 = binding.Compressor(n, [50.0], 0)
     comp2.workspace = comp.workspace
     # (residual not carried here, so that the threshold is the same from call to call)
-    st, _ = _iterate(n, [50.0], 0, g[1:], [REUSE, REUSE], comp=comp2, carry=False)
-    assert [s["any_fallback"] for s in st] == [1, 0]
+    st, _ = _iterate(n, [50.0], 0, g[1:3], [REUSE, REUSE], comp=comp2, carry=False)
+    assert [s["any_fallback"] for s in st] == [0, 0]
+    # the workspace's contents are lost between two calls of the same shape: only the device can tell (the last
+    # completed call's signature is gone), and every segment takes the exact route; the result is the same
+    comp2.workspace.zero_()
+    st, _ = _iterate(n, [50.0], 0, g[3:], [REUSE], comp=comp2, carry=False)
+    assert st[0]["any_fallback"] == 1 and st[0]["light_fallback_segments"] == 0
 
 
 def test_reuse_thresholds_survives_a_scale_jump():

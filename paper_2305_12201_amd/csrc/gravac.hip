@@ -1042,13 +1042,14 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
 {
     // Gradient magnitudes crowd into a few exponents, so most lanes of a wavefront hit the same few bins and
     // LDS atomics on one copy serialise 64-fold; CSUB copies cut that to 64 / CSUB.
-    __shared__ uint32_t lh[CSUB][NBIN];
+    // (a row is one word longer than the histogram, so that the CSUB counters of one bin lie in different banks)
+    __shared__ uint32_t lh[CSUB][NBIN + 1];
     if (p.status->any_fail == 0) return;
     const int tid = threadIdx.x, lane = tid & 63;
     uint32_t* h = lh[lane & (CSUB - 1)];
     // a fixed number of workgroups walks over the tiles (a workgroup takes WAVES consecutive tiles at a time, one per
     // wavefront), so that the launch costs little when nothing failed
-    for (uint32_t i = tid; i < CSUB * NBIN; i += WG) (&lh[0][0])[i] = 0;
+    for (uint32_t i = tid; i < CSUB * (NBIN + 1); i += WG) (&lh[0][0])[i] = 0;
     __syncthreads();
     int cur = -1;  // segment whose counts sit in lh
     for (uint32_t u0 = blockIdx.x * WAVES; u0 < p.n_tiles; u0 += gridDim.x * WAVES) {
@@ -1139,12 +1140,14 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
                             }
                             __threadfence_block();  // the loads below are this wavefront's own, of the same addresses
                         }
-                        for (int64_t q0 = s0 + lane; q0 < e0; q0 += 64 * 8) {
-                            float a[8];
+                        for (int64_t q0 = s0 + lane; q0 < e0; q0 += 64 * 16) {
+                            // all loads first, without branches around them (an element past the end reads the last
+                            // one instead and is not counted), so that they are in flight together
+                            float a[16];
 #pragma unroll
-                            for (int r = 0; r < 8; ++r) a[r] = (q0 + r * 64 < e0) ? p.acc[q0 + r * 64] : 0.0f;
+                            for (int r = 0; r < 16; ++r) a[r] = p.acc[q0 + r * 64 < e0 ? q0 + r * 64 : e0 - 1];
 #pragma unroll
-                            for (int r = 0; r < 8; ++r)
+                            for (int r = 0; r < 16; ++r)
                                 if (q0 + r * 64 < e0) atomicAdd(&h[cand_key(p, (int32_t)(q0 + r * 64), a[r]) >> 20], 1u);
                         }
                     }

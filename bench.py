@@ -77,11 +77,12 @@ def cpu_select_baseline(n_conv, n_fc, k):
 def time_all_configs(torch, binding, workloads):
     """Times one compress call of every configuration (third error-feedback iteration on the same gradient,
     HIP events of the library around the whole call; warm = calls back to back, cold = after a 512 MiB write
-    that flushes the caches) and the W = 8 decompression of configuration 5.  Returns a list of records."""
+    that flushes the caches; and calls 20 to 39 of a run over three gradients with reused thresholds) and the
+    W = 8 decompression of configuration 5.  Returns a list of records."""
     flush = torch.empty(512 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")
     rows = []
 
-    def compress_row(name, g, cfs, commit, seg=None, res0=None, iters=3, reps=8):
+    def compress_row(name, g, cfs, commit, seg=None, res0=None, iters=3, reps=8, more=None):
         n = g.numel()
         comp = binding.Compressor(n, cfs, commit, seg)
         r = torch.empty(n, dtype=torch.float32, device="cuda")
@@ -106,6 +107,24 @@ def time_all_configs(torch, binding, workloads):
             rec[key + "_dense_GBps"] = 4.0 * n / t / 1e6
             rec[key + "_algorithmic_frac_of_hbm_peak"] = (ALGO_BYTES_PER_ELEMENT * n + 8.0 * comp.k_total) / t / 1e6 / HBM_PEAK_GBS
             rec[key + "_fallback"] = bool(fb)
+        if more is not None:
+            # a run in steady state: three gradients in turn, the residual carried, thresholds reused from the second
+            # call on; calls 20 to 39, back to back
+            gs = [g] + [torch.from_numpy(more(i)).cuda() for i in (1, 2)]
+            comp = binding.Compressor(n, cfs, commit, seg)
+            r.zero_() if res0 is None else r.copy_(res0)
+            tot, strm, fb = [], [], 0
+            for it in range(40):
+                comp(gs[it % 3], r, flags=binding.FLAG_PROFILE | (binding.FLAG_REUSE_THRESHOLDS if it else 0))
+                a, b = binding.gravac_profile_read()
+                if it >= 20:
+                    tot.append(b)
+                    strm.append(a)
+                    fb += comp.status()["any_fallback"]
+            rec["steady_reuse_us"] = float(np.mean(tot)) * 1e3
+            rec["steady_reuse_stream_kernel_us"] = float(np.mean(strm)) * 1e3
+            rec["steady_reuse_calls_with_fallback"] = int(fb)
+            del gs
         log(json.dumps(rec))
         rows.append(rec)
 
@@ -114,23 +133,26 @@ def time_all_configs(torch, binding, workloads):
     g = torch.from_numpy(workloads.config2_grad(0)).cuda()
     r0 = torch.from_numpy(workloads.config2_residual0()).cuda()
     for c in range(3):
-        compress_row("2: ResNet101-shaped, three CFs in one call", g, [10.0, 100.0, 1000.0], c, res0=r0)
-    compress_row("2: ResNet101-shaped, CF 100 alone", g, [100.0], 0, res0=r0)
+        compress_row("2: ResNet101-shaped, three CFs in one call", g, [10.0, 100.0, 1000.0], c, res0=r0,
+                     more=workloads.config2_grad)
+    compress_row("2: ResNet101-shaped, CF 100 alone", g, [100.0], 0, res0=r0, more=workloads.config2_grad)
     del g, r0
     g = torch.from_numpy(workloads.config3_grad(0)).cuda()
-    compress_row("3: VGG16-shaped", g, [1000.0], 0)
-    compress_row("3: VGG16-shaped, CF 100", g, [100.0], 0)
+    compress_row("3: VGG16-shaped", g, [1000.0], 0, more=workloads.config3_grad)
+    compress_row("3: VGG16-shaped, CF 100", g, [100.0], 0, more=workloads.config3_grad)
+    compress_row("3: VGG16-shaped, CF 10", g, [10.0], 0, more=workloads.config3_grad)
     del g
     g = torch.from_numpy(workloads.config4_grad(0)).cuda()
     for c in range(2):
-        compress_row("4: LSTM, listed shapes", g, [100.0, 1000.0], c)
+        compress_row("4: LSTM, listed shapes", g, [100.0, 1000.0], c, more=workloads.config4_grad)
     del g
     g = torch.from_numpy(workloads.config4_grad(0, 10000, 1500)).cuda()
     compress_row("4: LSTM, 66,034,000-element variant", g, [100.0, 1000.0], 0)
     del g
     g = torch.from_numpy(workloads.config5_worker_grad(0)).cuda()
     seg = workloads.offsets_of(workloads.resnet101_tensor_sizes())
-    compress_row("5: ResNet101-shaped, 314 tensors, layerwise", g, [100.0], 0, seg=seg)
+    compress_row("5: ResNet101-shaped, 314 tensors, layerwise", g, [100.0], 0, seg=seg,
+                 more=lambda i: workloads.config5_worker_grad(i))
     # decompression of the eight workers' messages of configuration 5
     n = g.numel()
     comp = binding.Compressor(n, [100.0], 0, seg)

@@ -83,6 +83,8 @@ constexpr int DENSE_ROUNDS = 4;          // ... whose sample blocks are up to DE
 constexpr int DENSE_BLOCKS = 128;        // ... so that there are at most this many of them
 constexpr int LCAP = 4096;          // keys a gather list can hold
 constexpr int MAXCF = GRAVAC_MAX_CF;
+constexpr uint32_t REUSE_MAX_K = 1u << 21;  // a CF that selects more entries than this is sampled even when thresholds are reused:
+                                            // the bracket a sample gives holds fewer entries than 0.25 k below the old threshold
 constexpr double ZMARGIN = 5.0;     // safety margin of the sampled rank, in standard deviations
 constexpr uint32_t NONE = 0xFFFFFFFFu;
 
@@ -165,6 +167,7 @@ struct Params {
     int64_t total_out;        // pairs the call emits
     uint32_t n_tiles;
     uint32_t n_sample_blocks;
+    uint32_t have_sample;          // 1 if the sampling kernel has run for this call
     // layerwise tables in the workspace (unused when n_seg == 1)
     const SegInfo* segs;           // [n_seg] built on the host
     const uint32_t* ktab;          // [n_seg][n_cf] built on the host
@@ -510,7 +513,10 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
     // without a usable prediction (and without samples) every segment takes the exact route
     const bool want_reuse = (p.flags & GRAVAC_FLAG_REUSE_THRESHOLDS) != 0;
     const bool reuse = want_reuse && p.status->sig_lo == p.sig_lo && p.status->sig_hi == p.sig_hi;
-    const bool forced = (p.flags & GRAVAC_FLAG_FORCE_FALLBACK) != 0 || (want_reuse && !reuse);
+    // (a call that reuses thresholds samples as well if one of its CFs selects more than REUSE_MAX_K entries: such a CF
+    // takes its bounds from the sample, and so does every CF if the workspace turns out to hold no matching call)
+    const bool forced = (p.flags & GRAVAC_FLAG_FORCE_FALLBACK) != 0 || (want_reuse && !reuse && !p.have_sample);
+    const bool sampled = !forced && !p.random && p.have_sample != 0;
 
     // reuse: the previous call's candidate histogram says where its count from the top reached about 1.25 k;
     // that key becomes this call's lower bound (wavefront j looks at CF j, before the histogram is cleared)
@@ -566,7 +572,7 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
 
     // thread i owns bins 4i .. 4i+3: two words of every block's histogram
     uint32_t h0 = 0, h1 = 0, h2 = 0, h3 = 0;
-    if (!forced && !reuse && !p.random) {
+    if (sampled) {
         const uint2* src = (const uint2*)(p.samp_hist + (size_t)sb0 * (SBIN / 2)) + tid;
         for (uint32_t b0 = 0; b0 < nb; b0 += 32) {
             uint2 w[32];
@@ -609,7 +615,7 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
         for (int j = 0; j < p.n_cf; ++j) {
             uint32_t lo = bin_lo[j] << 19;                          // lower edge of the bin of the r_lo-th sample
             uint64_t hi = ((uint64_t)bin_hi[j] + 1) << 19;          // upper edge of the bin of the r_hi-th sample
-            if (reuse) {
+            if (reuse && !(sampled && seg_k(p, t, j) > REUSE_MAX_K)) {
                 // from the key below which the previous call counted about 1.25 k candidates to 2^19 keys (about 4 % in
                 // magnitude) above the previous threshold: tight, for a run in steady state; a threshold that moves
                 // further than that costs one call through the exact route
@@ -2450,8 +2456,12 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     int64_t total_out = 0;
     uint32_t max_seg_tiles = 1;  // tiles of the largest segment
     int sample_rounds = 1;  // groups per thread of the sampling kernel
+    uint32_t k_largest = 0;  // over all segments and CFs
     if (ns == 1) {
-        for (int j = 0; j < n_cf; ++j) p.flat_k[j] = (uint32_t)gravac_topk_count(n, cf_list[j]);
+        for (int j = 0; j < n_cf; ++j) {
+            p.flat_k[j] = (uint32_t)gravac_topk_count(n, cf_list[j]);
+            if (p.flat_k[j] > k_largest) k_largest = p.flat_k[j];
+        }
         p.flat_samples = sample_count((uint64_t)n, cf_min, cf_max, true);
         p.n_tiles = (uint32_t)((n + TW - 1) / TW);
         max_seg_tiles = p.n_tiles;
@@ -2500,7 +2510,10 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
             const uint32_t nb = (g.samp_cnt + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
             for (uint32_t b = 0; b < nb; ++b) sblock_seg[sb_at + b] = (uint32_t)t;
             sb_at += nb;
-            for (int j = 0; j < n_cf; ++j) ktab[(size_t)t * n_cf + j] = (uint32_t)gravac_topk_count(nt, cf_list[j]);
+            for (int j = 0; j < n_cf; ++j) {
+                ktab[(size_t)t * n_cf + j] = (uint32_t)gravac_topk_count(nt, cf_list[j]);
+                if (ktab[(size_t)t * n_cf + j] > k_largest) k_largest = ktab[(size_t)t * n_cf + j];
+            }
             koff += ktab[(size_t)t * n_cf + commit];
         }
         const bool ok = hipMemcpyAsync(ws + L.tables, slot->mem, bytes, hipMemcpyHostToDevice, stream) == hipSuccess &&
@@ -2522,6 +2535,8 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         if (!ws_memo_exchange(workspace, h)) flags &= ~(unsigned)GRAVAC_FLAG_REUSE_THRESHOLDS;
         p.flags = flags;
     }
+    // the sampling pass: always without reuse, and with it for the sake of a CF that selects very many entries
+    p.have_sample = (p.n_sample_blocks && !random && (!(flags & GRAVAC_FLAG_REUSE_THRESHOLDS) || k_largest > REUSE_MAX_K)) ? 1u : 0u;
     const uint32_t tile_grid = (p.n_tiles + WAVES - 1) / WAVES;
     const uint32_t sub_grid = (p.n_tiles * SUB + WAVES - 1) / WAVES;
     const uint32_t light_grid = (p.n_tiles + LWAVES - 1) / LWAVES;
@@ -2539,7 +2554,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         }
         (void)hipEventRecord(g_ev[0], stream);
     }
-    if (p.n_sample_blocks && !random && !(flags & GRAVAC_FLAG_REUSE_THRESHOLDS))
+    if (p.have_sample)
         static_assert(DENSE_ROUNDS == 4, "forms of the sampling kernel for 1, 2 and 4 groups per thread");
         hipLaunchKernelGGL(sample_rounds == 1 ? sample_kernel<1> : sample_rounds == 2 ? sample_kernel<2> : sample_kernel<4>,
                            dim3(p.n_sample_blocks), dim3(256), 0, stream, p);

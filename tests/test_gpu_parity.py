@@ -435,6 +435,18 @@ def test_reuse_thresholds_without_history_or_with_another_shape():
     assert st[0]["any_fallback"] == 1 and st[0]["light_fallback_segments"] == 0
 
 
+def test_reuse_thresholds_with_a_cf_that_selects_millions():
+    """A CF whose k exceeds 2^21 takes its bounds from a sample even when thresholds are reused (the other CF of the
+    call follows the previous call); the results are the oracle's either way."""
+    n = 12_000_000
+    grads = [workloads.normal_gradient(n, 1e-3, seed=400 + it) for it in range(3)]
+    _iterate(n, [4.0, 1000.0], 0, grads, [0, REUSE, REUSE])
+    _iterate(n, [4.0, 1000.0], 1, grads, [0, REUSE, REUSE])
+    # without the leftover carried over the thresholds stay where they are: no call leaves the first route
+    st, _ = _iterate(n, [4.0, 1000.0], 0, grads, [0, REUSE, REUSE], carry=False)
+    assert [s["any_fallback"] for s in st] == [0, 0, 0]
+
+
 def test_reuse_thresholds_survives_a_scale_jump():
     n = 800_000
     grads = [workloads.normal_gradient(n, 1e-3, seed=1), workloads.normal_gradient(n, 1e-3, seed=2),

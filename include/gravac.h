@@ -58,7 +58,8 @@ extern "C" {
 #define GRAVAC_FLAG_REUSE_THRESHOLDS 4u /* for iterative use: the workspace has not been touched since the previous
                                          gravac_compress call made with it; if that call had the same n, cf_list and
                                          segment table, its candidate histogram and thresholds give this call's
-                                         bounds and replace the sampling pass.  Results are the same in every case: a
+                                         bounds and replace the sampling pass (except for a CF that selects more than
+                                         2^21 entries, which is sampled all the same).  Results are the same in every case: a
                                          prediction that turns out wrong sends the affected segments through the
                                          exact-histogram route (slower, never wrong).  The flag may be given on every
                                          call: if the call this process last issued with the workspace had another

@@ -1590,7 +1590,7 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
 {
     __shared__ uint32_t sg[SCAN_SLICE], se[SCAN_SLICE];
     __shared__ uint32_t wt[4][16];
-    __shared__ double dred[2][SCAN_T];
+    __shared__ double dred[2][SCAN_T / 64];
     const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
     const int t = blockIdx.x;
     if (blockIdx.y < slices) {
@@ -1675,19 +1675,20 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
 #pragma unroll
         for (int q = 0; q < 16; ++q) { sd += xd[q]; sj += xj[q]; }
     }
-    dred[0][tid] = sd; dred[1][tid] = sj;
-    __syncthreads();
-    for (int o = SCAN_T >> 1; o > 0; o >>= 1) {
-        if (tid < o) { dred[0][tid] += dred[0][tid + o]; dred[1][tid] += dred[1][tid + o]; }
-        __syncthreads();
+    // every wavefront's sum, then the SCAN_T / 64 of them in order: one barrier, the same order in every run
+    {
+        const double wd = wave_sum(sd), wj = wave_sum(sj);
+        if (lane == 0) { dred[0][wib] = wd; dred[1][wib] = wj; }
     }
+    __syncthreads();
     if (tid == 0) {
         const CfState* st = &p.st[id];
         // fourth statistic: the threshold as a magnitude (Top-k) or as a priority (Random-k)
         const double tau = p.random ? (double)st->tau : (double)__uint_as_float(st->tau);
-        const double ss_dense = dred[0][0];
+        double ss_dense = 0.0, ss_cand = 0.0;
+        for (int w = 0; w < SCAN_T / 64; ++w) { ss_dense += dred[0][w]; ss_cand += dred[1][w]; }
         // Top-k: the ties all have magnitude tau; Random-k: the count pass has summed the entry at the threshold
-        const double ss_sel = dred[1][0] + (p.random ? 0.0 : (double)st->need * tau * tau);
+        const double ss_sel = ss_cand + (p.random ? 0.0 : (double)st->need * tau * tau);
         double* o = p.out_stats + (size_t)id * GRAVAC_STATS_PER_CF;
         o[0] = ss_sel;
         o[1] = ss_dense;

@@ -435,6 +435,17 @@ def test_reuse_thresholds_without_history_or_with_another_shape():
     assert st[0]["any_fallback"] == 1 and st[0]["light_fallback_segments"] == 0
 
 
+def test_flat_call_with_the_larger_sample_in_blocks_of_two_groups():
+    """k n large enough (k = n = 12 M for the CF 1 of the list) for the flat sampling pass to take more than 131,072
+    samples, in blocks of 2048: the form of the sampling kernel between the plain one and the one the full-size
+    VGG16-shaped test at CF 10 runs."""
+    n = 12_000_000
+    g = workloads.normal_gradient(n, 1e-3, seed=410)
+    r = workloads.normal_gradient(n, 3e-4, seed=411)
+    check(g, r, [1.0, 3.0], 1, what="cf 3 committed", expect_fallback=False)
+    check(g, r, [1.0, 3.0], 0, what="cf 1 committed")
+
+
 def test_reuse_thresholds_with_a_cf_that_selects_millions():
     """A CF whose k exceeds 2^21 takes its bounds from a sample even when thresholds are reused (the other CF of the
     call follows the previous call); the results are the oracle's either way."""

@@ -2555,10 +2555,11 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         }
         (void)hipEventRecord(g_ev[0], stream);
     }
-    if (p.have_sample)
-        static_assert(DENSE_ROUNDS == 4, "forms of the sampling kernel for 1, 2 and 4 groups per thread");
+    static_assert(DENSE_ROUNDS == 4, "forms of the sampling kernel for 1, 2 and 4 groups per thread");
+    if (p.have_sample) {
         hipLaunchKernelGGL(sample_rounds == 1 ? sample_kernel<1> : sample_rounds == 2 ? sample_kernel<2> : sample_kernel<4>,
                            dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
+    }
     hipLaunchKernelGGL(threshold_kernel, dim3(ns), dim3(1024), 0, stream, p);
     {
         // events 1 and 2 take the streaming kernel's own begin and end time stamps

@@ -1389,6 +1389,10 @@ __global__ __launch_bounds__(256) void resolve_kernel(Params p)
     __shared__ uint32_t wsum[2][WAVES];
     const int id = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
     CfState* st = &p.st[id];
+    // the fill counts of the gather lists are fetched together with the plan, not after it (they do not depend on it)
+    uint32_t fill[REP];
+#pragma unroll
+    for (int r = 0; r < REP; ++r) fill[r] = p.list_cnt[((size_t)id * REP + r) * 32];
     const uint32_t mode = st->mode;
     if (mode == MODE_RESOLVED) return;
     if (mode == MODE_FAIL) { if (tid == 0) p.status->error = 1; return; }
@@ -1413,7 +1417,7 @@ __global__ __launch_bounds__(256) void resolve_kernel(Params p)
     uint32_t off[REP + 1];
     off[0] = 0;
 #pragma unroll
-    for (int r = 0; r < REP; ++r) off[r + 1] = off[r] + p.list_cnt[((size_t)id * REP + r) * 32];
+    for (int r = 0; r < REP; ++r) off[r + 1] = off[r] + fill[r];
     if (off[REP] != c || c > LCAP || want == 0 || want > c) { if (tid == 0) p.status->error = 1; return; }
     uint32_t d[LCAP / 256];
     // all loads first, without branches around them (a position past the last key reads key 0 of the lists

@@ -1357,7 +1357,8 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
         const uint32_t nmax = tc.longest();
         for (uint32_t c0 = 0; c0 < nmax; c0 += VCHUNK) {
             const uint32_t first = c0 + 4 * lane;  // < TS
-#pragma unroll
+            // (unrolled for the forms with one or two CFs; the larger forms' bodies are too long for that)
+#pragma unroll(NCF <= 2 ? SUB / VLISTS : 1)
             for (int j0 = 0; j0 < SUB; j0 += VLISTS) {
                 v4i kv[VLISTS];  // the bits the key is made from: the value's, or the index for Random-k
                 if (p.random) {

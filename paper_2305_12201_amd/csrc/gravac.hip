@@ -75,7 +75,10 @@ constexpr uint32_t XGRID = GV_XGRID;  // workgroups of the two exact-route kerne
 constexpr int REP = 8;              // copies of the candidate histogram and of the gather lists
 constexpr int NBIN = 2048;          // bins of the candidate / refine / coarse histograms
 constexpr uint32_t OVF = NBIN - 1;  // last bin of the candidate histogram: everything above the bracket
-constexpr int SBIN = 4096;          // bins of the sample histogram (key >> 19)
+constexpr int SBIN = 4096;          // bins of the sample histogram: 2^17 keys each (64 per octave, 1.1 % in magnitude)
+constexpr uint32_t SSHIFT = 17;     // from |x| = 2^-48 up to 2^16; smaller magnitudes share bin 0, larger ones the last bin
+constexpr uint32_t SKEY0 = 79u << 23;
+static_assert((uint64_t)SKEY0 + ((uint64_t)SBIN << SSHIFT) <= 0x7F800000ull, "the window lies inside the finite keys");
 constexpr int SAMPLE_BLOCK = 1024;  // samples per workgroup of the sampling kernel
 constexpr int SAMPLE_MAX = 65536;   // samples per segment at most (unless the segment is read whole)
 constexpr int SAMPLE_MAX_FLAT = 524288;  // flat mode, a large k: see sample_count
@@ -219,6 +222,19 @@ __device__ __forceinline__ int64_t seg_koff(const Params& p, int t) { return is_
 __device__ __forceinline__ int tile_seg(const Params& p, uint32_t u) { return is_flat(p) ? 0 : (int)p.tseg[u]; }
 
 __device__ __forceinline__ uint32_t key_of(float a) { return __float_as_uint(a) & 0x7FFFFFFFu; }
+
+// Bin of the sample histogram a key falls into, and the keys a bin spans.
+__device__ __forceinline__ uint32_t sample_bin(uint32_t key)
+{
+    if (key < SKEY0) return 0u;
+    const uint32_t b = (key - SKEY0) >> SSHIFT;
+    return b < (uint32_t)SBIN - 1u ? b : (uint32_t)SBIN - 1u;
+}
+__device__ __forceinline__ uint32_t sample_bin_first(uint32_t b) { return b == 0u ? 0u : SKEY0 + (b << SSHIFT); }
+__device__ __forceinline__ uint64_t sample_bin_end(uint32_t b)
+{
+    return b == (uint32_t)SBIN - 1u ? 2147483648ull : (uint64_t)SKEY0 + ((uint64_t)(b + 1u) << SSHIFT);
+}
 
 // Random-k: priority of index i, a keyed bijection of the 31-bit integers (adding a constant, multiplying
 // by an odd constant and xor with a right shift are all bijections of [0, 2^31)), so no two indices tie.
@@ -425,8 +441,8 @@ __device__ __forceinline__ void team_locate_bin(const uint32_t* hist, int copies
 }
 
 // ---------------------------------------------------------------------------------------------
-// K0a: sample acc = residual + grad at stratified positions; each workgroup histograms the top
-// 12 key bits of its SAMPLE_BLOCK samples in LDS and stores the counts as 16-bit numbers
+// K0a: sample acc = residual + grad at stratified positions; each workgroup histograms its samples in
+// LDS (SBIN bins of 2^17 keys, see sample_bin) and stores the counts as 16-bit numbers
 // ---------------------------------------------------------------------------------------------
 template <int R>  // R groups per thread: a workgroup histograms R * SAMPLE_BLOCK samples
 __global__ __launch_bounds__(256) void sample_kernel(Params p)
@@ -479,7 +495,7 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
         const float acc = p.single ? gv[q] : rv[q] + gv[q];
-        if (live[q]) atomicAdd(&h[key_of(acc) >> 19], 1u);
+        if (live[q]) atomicAdd(&h[sample_bin(key_of(acc))], 1u);
     }
     __syncthreads();
     // thread i stores bins 16i .. 16i+15, two counts per word (a count is at most R * SAMPLE_BLOCK < 2^16)
@@ -613,8 +629,8 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
     if (tid == 0) {
         uint32_t lo_min = NONE, pz = NONE;
         for (int j = 0; j < p.n_cf; ++j) {
-            uint32_t lo = bin_lo[j] << 19;                          // lower edge of the bin of the r_lo-th sample
-            uint64_t hi = ((uint64_t)bin_hi[j] + 1) << 19;          // upper edge of the bin of the r_hi-th sample
+            uint32_t lo = sample_bin_first(bin_lo[j]);             // lower edge of the bin of the r_lo-th sample
+            uint64_t hi = sample_bin_end(bin_hi[j]);               // upper edge of the bin of the r_hi-th sample
             if (reuse && !(sampled && seg_k(p, t, j) > REUSE_MAX_K)) {
                 // from the key below which the previous call counted about 1.25 k candidates to 2^19 keys (about 4 % in
                 // magnitude) above the previous threshold: tight, for a run in steady state; a threshold that moves
@@ -1357,8 +1373,9 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
         const uint32_t nmax = tc.longest();
         for (uint32_t c0 = 0; c0 < nmax; c0 += VCHUNK) {
             const uint32_t first = c0 + 4 * lane;  // < TS
-            // (unrolled for the forms with one or two CFs; the larger forms' bodies are too long for that)
-#pragma unroll(NCF <= 2 ? SUB / VLISTS : 1)
+            // (the forms for many CFs are too long for this loop to be unrolled: they read the list counts from memory,
+            // not from the register array, which can only be indexed by constants)
+#pragma unroll
             for (int j0 = 0; j0 < SUB; j0 += VLISTS) {
                 v4i kv[VLISTS];  // the bits the key is made from: the value's, or the index for Random-k
                 if (p.random) {
@@ -1370,7 +1387,9 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
                 }
 #pragma unroll
                 for (int j = 0; j < VLISTS; ++j) {
-                    const uint32_t n = tc.start[j0 + j + 1] - tc.start[j0 + j];
+                    uint32_t n;
+                    if constexpr (NCF <= 2) n = tc.start[j0 + j + 1] - tc.start[j0 + j];
+                    else n = p.cand_cnt[(size_t)u * SUB + j0 + j];
                     if (n <= c0) continue;  // the same for all lanes
 #pragma unroll
                     for (int x = 0; x < 4; ++x)

@@ -458,9 +458,10 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
     for (int q = 0; q < SBIN / 256; ++q) h[q * 256 + tid] = 0;
     __syncthreads();
     // A group is 4 consecutive elements: sample i of the segment is element i % 4 of group i / 4.  A sampled
-    // segment (S a multiple of SAMPLE_BLOCK, nt > 2 S) is cut into S / 4 strata of at least 8 elements and every
-    // group sits at a hashed place inside its stratum, so a sample costs a quarter of the memory transactions that
-    // single elements at scattered places would (the sampling pass is bound by them).
+    // segment (S a multiple of SAMPLE_BLOCK, nt > 2 S) is cut into S / 16 strata of at least 32 elements, and the
+    // four groups of a stratum are the 16 elements of one line at a hashed place inside it: a sample costs a
+    // sixteenth of the memory transactions that single elements at scattered places would (the sampling pass is
+    // bound by their number, not by their bytes).
     static_assert(SAMPLE_BLOCK / 256 == 4, "groups of four");
     constexpr int Q = 4 * R;
     uint64_t gpos[R];
@@ -470,8 +471,14 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
         const uint32_t g = (lb * R + r) * (SAMPLE_BLOCK / 4) + tid;  // group
         gpos[r] = 4ull * g;                                          // the whole segment is read: elements 4g .. 4g+3
         if ((uint64_t)S != nt) {
-            const uint64_t G = S / 4, a = ((uint64_t)g * nt) / G, e = ((uint64_t)(g + 1) * nt) / G;
-            gpos[r] = a + hash32(g * 0x9E3779B9u + 0x85EBCA6Bu) % (uint32_t)(e - a - 3);  // gpos + 3 < e <= nt
+            // four neighbouring threads share one stratum and one run of 16 elements in it that starts at a multiple
+            // of 16 in the flat buffer (a 64-byte line if the buffer is aligned to that)
+            const uint32_t g16 = g >> 2;
+            const uint64_t G = S / 16, a = ((uint64_t)g16 * nt) / G, e = ((uint64_t)(g16 + 1) * nt) / G;  // e - a >= 32
+            const uint64_t first = ((uint64_t)s0 + a + 15) & ~15ull;                 // first such run inside the stratum
+            const uint32_t runs = (uint32_t)(((uint64_t)s0 + e - first) / 16);        // >= 1
+            const uint64_t at = first + 16ull * (hash32(g16 * 0x9E3779B9u + 0x85EBCA6Bu) % runs);
+            gpos[r] = (at - (uint64_t)s0) + 4u * (g & 3u);                            // gpos + 3 < e <= nt
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) live[4 * r + q] = 4ull * g + q < S;

@@ -48,6 +48,8 @@ extern "C" {
                                        a layerwise call (its segment tables travel through a host staging buffer
                                        that later calls rewrite) or a call with GRAVAC_FLAG_PROFILE */
 
+#define GRAVAC_ERR_STATIC_LIMIT (-6) /* gravac_decompress_accumulate_static: W and n need more than GRAVAC_STATIC_SCRATCH_BYTES */
+
 #define GRAVAC_MAX_CF 8             /* candidate CFs per call */
 #define GRAVAC_STATS_PER_CF 4       /* doubles per (segment, CF) in out_stats */
 
@@ -213,6 +215,26 @@ int gravac_decompress_accumulate(const int32_t* idx, const float* val,
                                  const int64_t* counts, int W,
                                  int64_t n, float* dense_out,
                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * gravac_decompress_accumulate for callers that cannot allocate device memory or carry a workspace around: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result
+ * (bit for bit) and same kernels as gravac_decompress_accumulate with a workspace, but the tile boundaries of the
+ * messages live in a buffer of GRAVAC_STATIC_SCRATCH_BYTES that is part of the library's device image (one copy on
+ * every GPU the library is used on, held until the process ends).  The call allocates nothing and frees nothing.
+ *
+ *   limit     gravac_decompress_workspace_bytes(W, n) <= GRAVAC_STATIC_SCRATCH_BYTES, i.e.
+ *             min(W, 64) * (ceil(n / 8192) + 1) <= 2^20 (W = 8: n up to about 1.07e9); beyond that the call returns
+ *             GRAVAC_ERR_STATIC_LIMIT and launches nothing.
+ *   sharing   all calls on one GPU use that GPU's one buffer, which keeps the previous call's contents; every entry a
+ *             call reads it has written itself before, so nothing needs clearing.  Calls that overlap in time on one
+ *             GPU (different streams or threads) race on the buffer: give such callers gravac_decompress_accumulate
+ *             with workspaces of their own.
+ */
+#define GRAVAC_STATIC_SCRATCH_BYTES (4u << 20)
+int gravac_decompress_accumulate_static(const int32_t* idx, const float* val,
+                                        const int64_t* counts, int W,
+                                        int64_t n, float* dense_out, void* stream);
 
 /*
  * Diagnostics of the last gravac_compress call that used `workspace`: synchronises `stream`

@@ -21,6 +21,8 @@ ERR_CAPACITY = -2
 ERR_WORKSPACE = -3
 ERR_HIP = -4
 ERR_CAPTURE = -5
+ERR_STATIC_LIMIT = -6
+STATIC_SCRATCH_BYTES = 4 << 20
 MAX_CF = 8
 FLAG_FORCE_FALLBACK = 1
 FLAG_PROFILE = 2
@@ -28,7 +30,7 @@ FLAG_REUSE_THRESHOLDS = 4
 
 EXPORTS = (
     "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_randomk_compress", "gravac_recompress", "gravac_commit",
-    "gravac_decompress_workspace_bytes", "gravac_decompress_accumulate",
+    "gravac_decompress_workspace_bytes", "gravac_decompress_accumulate", "gravac_decompress_accumulate_static",
     "gravac_read_status", "gravac_profile_read", "gravac_strerror",
     "gravac_controller_create", "gravac_controller_destroy", "gravac_controller_candidates",
     "gravac_controller_decide", "gravac_controller_finish_iteration", "gravac_controller_throughput",
@@ -87,6 +89,8 @@ def lib() -> ctypes.CDLL:
         L.gravac_commit.argtypes = [vp, i64, vp, i64, vp]
         L.gravac_decompress_accumulate.restype = i32
         L.gravac_decompress_accumulate.argtypes = [vp, vp, vp, i32, i64, vp, vp, ctypes.c_size_t, vp]
+        L.gravac_decompress_accumulate_static.restype = i32
+        L.gravac_decompress_accumulate_static.argtypes = [vp, vp, vp, i32, i64, vp, vp]
         L.gravac_decompress_workspace_bytes.restype = i32
         L.gravac_decompress_workspace_bytes.argtypes = [i32, i64, ctypes.POINTER(ctypes.c_size_t)]
         L.gravac_read_status.restype = i32
@@ -226,6 +230,16 @@ def gravac_decompress_accumulate(idx, val, counts, dense_out, *, workspace=None,
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc != OK:
         raise GravacError(rc, "gravac_decompress_accumulate")
+
+
+def gravac_decompress_accumulate_static(idx, val, counts, dense_out, *, stream=None) -> None:
+    """``gravac_decompress_accumulate_static`` of the C ABI: the same on the library's own static scratch."""
+    cnt = np.ascontiguousarray(np.asarray(counts, dtype=np.int64))
+    rc = lib().gravac_decompress_accumulate_static(
+        _dev_ptr(idx, torch.int32), _dev_ptr(val, torch.float32), cnt.ctypes.data_as(ctypes.c_void_p),
+        cnt.size, dense_out.numel(), _dev_ptr(dense_out, torch.float32), _stream_handle(stream))
+    if rc != OK:
+        raise GravacError(rc, "gravac_decompress_accumulate_static")
 
 
 def gravac_read_status(workspace, stream=None) -> dict:

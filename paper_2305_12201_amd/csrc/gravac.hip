@@ -2377,6 +2377,36 @@ __global__ __launch_bounds__(256) void commit_kernel(const int32_t* __restrict__
 
 }  // namespace
 
+// Scratch of gravac_decompress_accumulate_static, the entry point for callers that cannot allocate: the tile
+// boundaries of the messages (what the caller's workspace holds in gravac_decompress_accumulate).  Every GPU the
+// library runs on holds its own copy of the array, at its own address, until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels get the address that call returned.
+constexpr size_t STATIC_SCRATCH_WORDS = (size_t)GRAVAC_STATIC_SCRATCH_BYTES / sizeof(uint32_t);
+static __device__ __align__(256) uint32_t scratch[STATIC_SCRATCH_WORDS];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+uint32_t* g_scratch_ptr[MAX_DEVICES];  // device address of `scratch` on every device used so far
+std::mutex g_scratch_mutex;
+
+// The address of `scratch` on the current device, looked up once per device.
+int static_scratch(uint32_t** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return GRAVAC_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return GRAVAC_ERR_HIP;
+        g_scratch_ptr[dev] = (uint32_t*)ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return GRAVAC_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 int64_t gravac_topk_count(int64_t n, double cf)
@@ -2690,8 +2720,10 @@ int gravac_decompress_workspace_bytes(int W, int64_t n, size_t* bytes_out)
     return GRAVAC_OK;
 }
 
-int gravac_decompress_accumulate(const int32_t* idx, const float* val, const int64_t* counts, int W, int64_t n,
-                                 float* dense_out, void* workspace, size_t workspace_bytes, void* stream_v)
+// bounds: device memory for the tile boundaries of up to DMAXW messages (the caller's workspace or the library's static
+// scratch, already checked for size), or null for the search path.
+static int decompress_impl(const int32_t* idx, const float* val, const int64_t* counts, int W, int64_t n, float* dense_out,
+                           uint32_t* bounds, void* stream_v)
 {
     hipStream_t stream = (hipStream_t)stream_v;
     if (!counts || !dense_out || W < 1 || n <= 0 || n > 2147483647LL) return GRAVAC_ERR_INVALID_ARG;
@@ -2701,11 +2733,6 @@ int gravac_decompress_accumulate(const int32_t* idx, const float* val, const int
         total += counts[w];
     }
     if (total > 0 && (!idx || !val)) return GRAVAC_ERR_INVALID_ARG;
-    if (workspace) {
-        size_t need = 0;
-        if (gravac_decompress_workspace_bytes(W, n, &need) != GRAVAC_OK) return GRAVAC_ERR_INVALID_ARG;
-        if (((uintptr_t)workspace & 255) || workspace_bytes < need) return GRAVAC_ERR_WORKSPACE;
-    }
     if (total == 0) return GRAVAC_OK;
     const int64_t ntile = (n + DTILE - 1) / DTILE;
     const uint32_t grid = (uint32_t)(ntile < 1024 ? ntile : 1024);  // 4 workgroups (4 x 32 KiB LDS) on each of 256 CUs
@@ -2722,19 +2749,44 @@ int gravac_decompress_accumulate(const int32_t* idx, const float* val, const int
         for (int w = wn; w <= DMAXW; ++w) wo.at[w] = at + group;
         at += group;
         if (group == 0) continue;
-        if (workspace) {
+        if (bounds) {
             // tile boundaries of the group's messages first (the workspace is reused from group to group: stream order)
             const uint32_t pair_blocks = (uint32_t)((longest + 255) / 256);
             hipLaunchKernelGGL(bounds_kernel, dim3(pair_blocks, (uint32_t)wn), dim3(256), 0, stream, idx, wo, ntile,
-                               (uint32_t*)workspace);
+                               bounds);
             hipLaunchKernelGGL(decompress_ws_kernel, dim3(grid), dim3(256), 0, stream, idx, val, wo, wn, n, dense_out,
-                               (const uint32_t*)workspace);
+                               (const uint32_t*)bounds);
         } else {
             hipLaunchKernelGGL(decompress_kernel, dim3(grid), dim3(256), 0, stream, idx, val, wo, wn, n, dense_out);
         }
     }
     if (hipGetLastError() != hipSuccess) return GRAVAC_ERR_HIP;
     return GRAVAC_OK;
+}
+
+
+int gravac_decompress_accumulate(const int32_t* idx, const float* val, const int64_t* counts, int W, int64_t n,
+                                 float* dense_out, void* workspace, size_t workspace_bytes, void* stream_v)
+{
+    if (!counts || !dense_out || W < 1 || n <= 0 || n > 2147483647LL) return GRAVAC_ERR_INVALID_ARG;
+    if (workspace) {
+        size_t need = 0;
+        if (gravac_decompress_workspace_bytes(W, n, &need) != GRAVAC_OK) return GRAVAC_ERR_INVALID_ARG;
+        if (((uintptr_t)workspace & 255) || workspace_bytes < need) return GRAVAC_ERR_WORKSPACE;
+    }
+    return decompress_impl(idx, val, counts, W, n, dense_out, (uint32_t*)workspace, stream_v);
+}
+
+int gravac_decompress_accumulate_static(const int32_t* idx, const float* val, const int64_t* counts, int W, int64_t n,
+                                        float* dense_out, void* stream_v)
+{
+    if (!counts || !dense_out || W < 1 || n <= 0 || n > 2147483647LL) return GRAVAC_ERR_INVALID_ARG;
+    size_t need = 0;
+    if (gravac_decompress_workspace_bytes(W, n, &need) != GRAVAC_OK) return GRAVAC_ERR_INVALID_ARG;
+    if (need > (size_t)GRAVAC_STATIC_SCRATCH_BYTES) return GRAVAC_ERR_STATIC_LIMIT;
+    uint32_t* bounds = nullptr;
+    if (const int rc = static_scratch(&bounds)) return rc;
+    return decompress_impl(idx, val, counts, W, n, dense_out, bounds, stream_v);
 }
 
 int gravac_read_status(const void* workspace, void* stream_v, int32_t* out8)
@@ -2770,6 +2822,7 @@ const char* gravac_strerror(int code)
         case GRAVAC_ERR_CAPACITY: return "output capacity too small";
         case GRAVAC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case GRAVAC_ERR_HIP: return "HIP runtime error";
+        case GRAVAC_ERR_STATIC_LIMIT: return "W and n exceed what the library's static scratch holds";
         case GRAVAC_ERR_CAPTURE: return "call cannot be recorded into a HIP graph (layerwise or profiled call on a capturing stream)";
         default: return "unknown error code";
     }

@@ -21,13 +21,18 @@
  *     stream).  Outputs are valid once the stream has been synchronised.
  *   - The library never allocates device memory: scratch space comes from the caller's
  *     `workspace`.  Calls that overlap in time must use different workspaces.
+ *   - The library keeps no state between calls, with one exception: layerwise calls pass their segment tables
+ *     through a ring of eight pinned host staging buffers that the library allocates on first use (hipHostMalloc,
+ *     grown when a larger table arrives, kept until the process ends) and that are shared by all callers of the
+ *     process.  Flat-mode calls touch no such state.
  *   - HIP graphs: a flat-mode compression (gravac_compress, gravac_randomk_compress, gravac_recompress with
- *     n_seg == 0, without GRAVAC_FLAG_PROFILE), gravac_commit and gravac_decompress_accumulate consist of kernel
- *     launches only (no copies, no memsets, no host synchronisation), so they can be recorded into a graph and
- *     replayed; the host tables (cf_list, counts) are read at capture time.  Layerwise calls and profiled calls
- *     on a capturing stream return GRAVAC_ERR_CAPTURE.
- *   - Return value: GRAVAC_OK (0) or a negative GRAVAC_ERR_* code.  On an error return no
- *     kernel has been launched and no buffer has been touched.
+ *     n_seg == 0), gravac_commit and gravac_decompress_accumulate consist of kernel launches only (no copies, no
+ *     memsets, no host synchronisation), so they can be recorded into a graph and replayed; the host tables
+ *     (cf_list, counts) are read at capture time.  Layerwise calls on a capturing stream return GRAVAC_ERR_CAPTURE.
+ *   - Return value: GRAVAC_OK (0) or a negative GRAVAC_ERR_* code.  GRAVAC_ERR_INVALID_ARG, GRAVAC_ERR_CAPACITY,
+ *     GRAVAC_ERR_WORKSPACE, GRAVAC_ERR_CAPTURE and GRAVAC_ERR_STATIC_LIMIT are found before anything is queued: no
+ *     kernel has been launched and no buffer has been touched.  GRAVAC_ERR_HIP means a HIP runtime call failed;
+ *     part of the work may have been queued by then, and residual, outputs and workspace are unspecified.
  */
 #ifndef GRAVAC_H
 #define GRAVAC_H
@@ -46,28 +51,16 @@ extern "C" {
 #define GRAVAC_ERR_HIP (-4)         /* a HIP runtime call failed (launch, copy) */
 #define GRAVAC_ERR_CAPTURE (-5)     /* the stream is being captured into a HIP graph and the call cannot be replayed:
                                        a layerwise call (its segment tables travel through a host staging buffer
-                                       that later calls rewrite) or a call with GRAVAC_FLAG_PROFILE */
+                                       that later calls rewrite) */
 
 #define GRAVAC_ERR_STATIC_LIMIT (-6) /* gravac_decompress_accumulate_static: W and n need more than GRAVAC_STATIC_SCRATCH_BYTES */
 
 #define GRAVAC_MAX_CF 8             /* candidate CFs per call */
 #define GRAVAC_STATS_PER_CF 4       /* doubles per (segment, CF) in out_stats */
 
-/* flags of gravac_compress (0 = none; the first two are testing and measurement aids) */
-#define GRAVAC_FLAG_FORCE_FALLBACK 1u /* skip the sampled threshold estimate: every segment takes the exact
-                                         histogram route (same results, more passes over memory) */
-#define GRAVAC_FLAG_PROFILE 2u        /* record HIP events around the streaming kernel, see gravac_profile_read */
-#define GRAVAC_FLAG_REUSE_THRESHOLDS 4u /* for iterative use: the workspace has not been touched since the previous
-                                         gravac_compress call made with it; if that call had the same n, cf_list and
-                                         segment table, its candidate histogram and thresholds give this call's
-                                         bounds and replace the sampling pass (except for a CF that selects more than
-                                         2^21 entries, which is sampled all the same).  Results are the same in every case: a
-                                         prediction that turns out wrong sends the affected segments through the
-                                         exact-histogram route (slower, never wrong).  The flag may be given on every
-                                         call: if the call this process last issued with the workspace had another
-                                         shape or CF list, or there was none, the call samples as if the flag were
-                                         absent; a workspace whose contents were lost in between is recognised on the
-                                         device and takes the exact route. */
+/* flags of the compression calls (0 = none; any other bit is refused) */
+#define GRAVAC_FLAG_FORCE_FALLBACK 1u /* a testing aid: skip the sampled threshold estimate, so that every segment takes
+                                         the exact-histogram route (same results, more passes over memory) */
 
 /*
  * Number of pairs a call will emit for a tensor of n elements at compression factor cf:
@@ -79,16 +72,20 @@ int64_t gravac_topk_count(int64_t n, double cf);
 /*
  * Workspace size in bytes for a gravac_compress call on n elements with n_cf candidate CFs
  * and n_seg segments (0 or 1 = one flat tensor).  The size depends only on these three
- * numbers (it covers any segment table with n_seg entries).  Roughly 8 bytes per element.
+ * numbers (it covers any segment table with n_seg entries).  About 17 bytes per element (two index / value lists
+ * with a slot per element, so that no list can overflow), plus 0.4 MB per (segment, CF) for histograms and gather
+ * lists (layerwise mode: 314 tensors with one CF take 130 MB more than the flat call), plus 2 KB per sample block.
  */
 int gravac_workspace_bytes(int64_t n, int n_cf, int n_seg, size_t* bytes_out);
 
 /*
  * One compression step of Alg. 1 for one worker.
  *
- *   grad        device, float[n], read only.  16-byte aligned.
- *   residual    device, float[n], 16-byte aligned.  In: the leftover of earlier iterations.
+ *   grad        device, float[n], read only.
+ *   residual    device, float[n].  In: the leftover of earlier iterations.
  *               Out: acc with the committed selection's slots set to +0.0f.
+ *               (Both may start at any float boundary; the fast path, 16-byte accesses, is taken when both are
+ *               16-byte aligned, as every allocator's buffers are.)
  *   n           1 <= n <= 2^31 - 1 (indices are int32).
  *   cf_list     host, double[n_cf], every entry finite and >= 1.  1 <= n_cf <= GRAVAC_MAX_CF.
  *   commit      position in cf_list of the CF whose selection is emitted into out_idx/out_val
@@ -105,9 +102,8 @@ int gravac_workspace_bytes(int64_t n, int n_cf, int n_seg, size_t* bytes_out);
  *               { ||g_c||^2, ||g_ef||^2, gain = ratio (1 if ||g_ef||^2 == 0),
  *                 |acc| of the smallest selected entry }.
  *   workspace   device, 256-byte aligned, at least gravac_workspace_bytes(n, n_cf, n_seg) bytes.
- *               Contents on entry are irrelevant (unless GRAVAC_FLAG_REUSE_THRESHOLDS is given); contents on
- *               exit are unspecified.
- *   flags       0, or GRAVAC_FLAG_* bits.
+ *               Contents on entry are irrelevant; contents on exit are unspecified.
+ *   flags       0, or GRAVAC_FLAG_FORCE_FALLBACK.
  */
 int gravac_compress(const float* grad, float* residual, int64_t n,
                     const double* cf_list, int n_cf, int commit,
@@ -136,7 +132,6 @@ int gravac_compress(const float* grad, float* residual, int64_t n,
  *                x ^= x >> 15; x = (x * 0x297A2D39) & M;  x ^= x >> 15;  P = x
  *
  *   out_stats   device, double[max(n_seg,1)][n_cf][4]: { ||g_c||^2, ||g_ef||^2, gain, lowest selected priority }.
- *   flags       GRAVAC_FLAG_REUSE_THRESHOLDS is ignored (the bounds of a random draw follow from k alone).
  */
 int gravac_randomk_compress(const float* grad, float* residual, int64_t n,
                             const double* cf_list, int n_cf, int commit, uint64_t seed,
@@ -154,7 +149,7 @@ int gravac_randomk_compress(const float* grad, float* residual, int64_t n,
  * the level-1 entries NOT selected here are written back into the residual, so that after this call
  * the residual is the one a direct compression at the higher CF would have left.
  *
- *   idx1, val1  device, int32[k1] / float[k1], 16-byte aligned, read only: the level-1 message, indices
+ *   idx1, val1  device, int32[k1] / float[k1], read only: the level-1 message, indices
  *               ascending within a segment (as gravac_compress emits them).
  *   k1          1 <= k1 <= 2^31 - 1.
  *   cf_rel      finite, >= 1: the ratio theta2 / theta1.
@@ -241,17 +236,10 @@ int gravac_decompress_accumulate_static(const int32_t* idx, const float* val,
  * and copies 8 int32 to the host pointer out8:
  *   [0] 1 if any segment took the exact-histogram fallback, [1] number of such segments,
  *   [2] internal-error flag (must be 0), [3] number of segments, [4] how many of [1] needed no second
- *   pass over the gradient (their candidates held the k-th largest, only their histogram was rebuilt),
- *   [5..7] reserved.
+ *   pass over the gradient (the located histogram bin was too coarse and too full and was binned again from the
+ *   lists the pass had collected), [5..7] reserved.
  */
 int gravac_read_status(const void* workspace, void* stream, int32_t* out8);
-
-/*
- * With GRAVAC_FLAG_PROFILE: synchronises and returns the duration in milliseconds of the
- * streaming kernel (error feedback + candidate collection) of the most recent profiled call
- * of this process, and of the whole call (first to last kernel) in total_ms.  Either pointer may be NULL.
- */
-int gravac_profile_read(float* stream_kernel_ms, float* total_ms);
 
 const char* gravac_strerror(int code);
 

@@ -19,7 +19,7 @@ HIPCC_FLAGS = [
 
 def build_library(force: bool = True) -> str:
     """Build ``libgravac.so`` in-tree.  With ``force=False`` only if it is missing or stale."""
-    headers = [os.path.join(_ROOT, "include", h) for h in ("gravac.h", "gravac_controller.h")]
+    headers = [os.path.join(_ROOT, "include", h) for h in ("gravac.h", "gravac_profile.h", "gravac_controller.h")]
     if not force and os.path.exists(LIBRARY):
         newest = max(os.path.getmtime(f) for f in [SOURCE, *HOST_SOURCES, *headers])
         if os.path.getmtime(LIBRARY) >= newest:

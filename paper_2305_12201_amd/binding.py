@@ -25,13 +25,11 @@ ERR_STATIC_LIMIT = -6
 STATIC_SCRATCH_BYTES = 4 << 20
 MAX_CF = 8
 FLAG_FORCE_FALLBACK = 1
-FLAG_PROFILE = 2
-FLAG_REUSE_THRESHOLDS = 4
 
 EXPORTS = (
-    "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_randomk_compress", "gravac_recompress", "gravac_commit",
+    "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_compress_profiled", "gravac_randomk_compress", "gravac_recompress", "gravac_commit",
     "gravac_decompress_workspace_bytes", "gravac_decompress_accumulate", "gravac_decompress_accumulate_static",
-    "gravac_read_status", "gravac_profile_read", "gravac_strerror",
+    "gravac_read_status", "gravac_strerror",
     "gravac_controller_create", "gravac_controller_destroy", "gravac_controller_candidates",
     "gravac_controller_decide", "gravac_controller_finish_iteration", "gravac_controller_throughput",
     "gravac_controller_iteration",
@@ -50,6 +48,14 @@ class ControllerConfig(ctypes.Structure):
                 ("omega", ctypes.c_double), ("theta_s", ctypes.c_double), ("alpha", ctypes.c_double),
                 ("samples_per_iteration", ctypes.c_double), ("window", ctypes.c_int64),
                 ("policy", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+
+class ProfileEvents(ctypes.Structure):
+    """``gravac_profile_events`` of the C ABI (``include/gravac_profile.h``): four hipEvent_t handles."""
+    _fields_ = [("call_begin", ctypes.c_void_p), ("pass_begin", ctypes.c_void_p), ("pass_end", ctypes.c_void_p),
+                ("call_end", ctypes.c_void_p)]
+
 
 _lib = None
 
@@ -79,6 +85,9 @@ def lib() -> ctypes.CDLL:
         L.gravac_compress.restype = i32
         L.gravac_compress.argtypes = [vp, vp, i64, vp, i32, i32, vp, i32, vp, vp, i64, vp, vp, vp,
                                       ctypes.c_size_t, u32, vp]
+        L.gravac_compress_profiled.restype = i32
+        L.gravac_compress_profiled.argtypes = [vp, vp, i64, vp, i32, i32, vp, i32, vp, vp, i64, vp, vp, vp,
+                                               ctypes.c_size_t, u32, vp, ctypes.POINTER(ProfileEvents)]
         L.gravac_randomk_compress.restype = i32
         L.gravac_randomk_compress.argtypes = [vp, vp, i64, vp, i32, i32, ctypes.c_uint64, vp, i32, vp, vp, i64, vp, vp, vp,
                                               ctypes.c_size_t, u32, vp]
@@ -95,8 +104,6 @@ def lib() -> ctypes.CDLL:
         L.gravac_decompress_workspace_bytes.argtypes = [i32, i64, ctypes.POINTER(ctypes.c_size_t)]
         L.gravac_read_status.restype = i32
         L.gravac_read_status.argtypes = [vp, vp, vp]
-        L.gravac_profile_read.restype = i32
-        L.gravac_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         L.gravac_strerror.restype = ctypes.c_char_p
         L.gravac_strerror.argtypes = [i32]
         dp = ctypes.POINTER(dbl)
@@ -147,21 +154,45 @@ def _dev_ptr(t, dtype) -> int:
     return t.data_ptr()
 
 
+class CallTimer:
+    """Four torch events for ``gravac_compress_profiled``: ``call_ms()`` and ``pass_ms()`` after a call."""
+
+    def __init__(self):
+        self.events = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        for e in self.events:       # torch creates the HIP event on the first record
+            e.record()
+        torch.cuda.synchronize()
+        self.struct = ProfileEvents(*[ctypes.c_void_p(int(e.cuda_event)) for e in self.events])
+        assert all(int(e.cuda_event) != 0 for e in self.events)
+
+    def call_ms(self) -> float:
+        self.events[3].synchronize()
+        return self.events[0].elapsed_time(self.events[3])
+
+    def pass_ms(self) -> float:
+        self.events[3].synchronize()
+        return self.events[1].elapsed_time(self.events[2])
+
+
 def gravac_compress(grad, residual, cf_list, commit=0, seg_offsets=None, *, out_idx, out_val,
-                    out_count=None, out_stats, workspace, flags=0, stream=None) -> None:
-    """``gravac_compress`` of the C ABI on torch device tensors (asynchronous on ``stream``)."""
+                    out_count=None, out_stats, workspace, flags=0, stream=None, timer=None) -> None:
+    """``gravac_compress`` of the C ABI on torch device tensors (asynchronous on ``stream``); with a ``CallTimer``,
+    ``gravac_compress_profiled``."""
     cfs = np.ascontiguousarray(np.asarray(cf_list, dtype=np.float64))
     if seg_offsets is None:
         seg_ptr, n_seg = None, 0
     else:
         seg = np.ascontiguousarray(np.asarray(seg_offsets, dtype=np.int64))
         seg_ptr, n_seg = seg.ctypes.data_as(ctypes.c_void_p), seg.size - 1
-    rc = lib().gravac_compress(
-        _dev_ptr(grad, torch.float32), _dev_ptr(residual, torch.float32), grad.numel(),
-        cfs.ctypes.data_as(ctypes.c_void_p), cfs.size, int(commit), seg_ptr, n_seg,
-        _dev_ptr(out_idx, torch.int32), _dev_ptr(out_val, torch.float32), out_idx.numel(),
-        _dev_ptr(out_count, torch.int64), _dev_ptr(out_stats, torch.float64),
-        workspace.data_ptr(), workspace.numel() * workspace.element_size(), int(flags), _stream_handle(stream))
+    args = (_dev_ptr(grad, torch.float32), _dev_ptr(residual, torch.float32), grad.numel(),
+            cfs.ctypes.data_as(ctypes.c_void_p), cfs.size, int(commit), seg_ptr, n_seg,
+            _dev_ptr(out_idx, torch.int32), _dev_ptr(out_val, torch.float32), out_idx.numel(),
+            _dev_ptr(out_count, torch.int64), _dev_ptr(out_stats, torch.float64),
+            workspace.data_ptr(), workspace.numel() * workspace.element_size(), int(flags), _stream_handle(stream))
+    if timer is None:
+        rc = lib().gravac_compress(*args)
+    else:
+        rc = lib().gravac_compress_profiled(*args, ctypes.byref(timer.struct))
     if rc != OK:
         raise GravacError(rc, "gravac_compress")
 
@@ -248,15 +279,7 @@ def gravac_read_status(workspace, stream=None) -> dict:
     if rc != OK:
         raise GravacError(rc, "gravac_read_status")
     return {"any_fallback": int(out[0]), "fallback_segments": int(out[1]), "internal_error": int(out[2]),
-            "segments": int(out[3]), "light_fallback_segments": int(out[4])}
-
-
-def gravac_profile_read() -> tuple[float, float]:
-    a, b = ctypes.c_float(0), ctypes.c_float(0)
-    rc = lib().gravac_profile_read(ctypes.byref(a), ctypes.byref(b))
-    if rc != OK:
-        raise GravacError(rc, "gravac_profile_read")
-    return float(a.value), float(b.value)
+            "segments": int(out[3]), "narrow_fallback_segments": int(out[4])}
 
 
 # --------------------------------------------------------------------------
@@ -282,10 +305,10 @@ class Compressor:
         self.out_count = torch.zeros(1, dtype=torch.int64, device=device)
         self.out_stats = torch.zeros(self.rows, len(self.cfs), 4, dtype=torch.float64, device=device)
 
-    def __call__(self, grad, residual, flags=0, stream=None):
+    def __call__(self, grad, residual, flags=0, stream=None, timer=None):
         gravac_compress(grad, residual, self.cfs, self.commit, self.seg, out_idx=self.out_idx,
                         out_val=self.out_val, out_count=self.out_count, out_stats=self.out_stats,
-                        workspace=self.workspace, flags=flags, stream=stream)
+                        workspace=self.workspace, flags=flags, stream=stream, timer=timer)
         return self.out_idx, self.out_val, self.out_stats
 
     def randomk(self, grad, residual, seed, flags=0, stream=None):

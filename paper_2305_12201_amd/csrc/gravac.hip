@@ -6,26 +6,28 @@
 // equation, Alg. 1 gain steps), layerwise mode and decompression (Sec. III-A).
 //
 // Design in one paragraph.  Keys are the binary32 bit patterns of |acc|, so magnitude order is
-// unsigned-integer order.  A small strided sample of acc gives, per candidate CF, a lower bound
-// `lo` on the k-th largest key (with a statistical safety margin) and a shift `s`.  ONE streaming
-// pass then reads grad and residual, writes acc back as the provisional residual, sums acc^2 and
-// diverts every element with key >= lo (a few k of them) into an index-ordered per-tile
-// candidate list, histogramming those candidates by (key - lo) >> s.  Everything after that
-// works on the candidate lists only: locate the histogram bin that holds the k-th largest,
-// resolve it to the exact key, count per tile, and emit the message in ascending index order
-// while zeroing the selected residual slots.  If the sampled bound turns out wrong the segment is
-// redone by a route that cannot fail: a bin too coarse and too full to resolve is binned again inside
-// itself; a k-th largest above the bracket is found from a 2048-bin histogram of the candidates'
-// top key bits; with fewer than k candidates that histogram is built over all elements and the
-// candidates are collected again.  Results are identical on every route; only the number of
-// passes over memory differs.
+// unsigned-integer order.  A small stratified sample of acc gives, per candidate CF, a bracket
+// [lo, top) of keys that holds the k-th largest key with a statistical safety margin.  ONE streaming
+// pass then reads grad and residual, writes acc back as the provisional residual, sums acc^2, and for
+// every CF counts (and sums the energy of) the entries above the bracket and histograms the entries
+// inside it.  The few entries inside some bracket go, in index order, into a per-sub-tile bracket list;
+// the entries that can belong to the committed selection go into a per-sub-tile candidate list, unless
+// the sub-tile is mostly candidates, in which case the emit step reads it again from the residual.
+// Everything after the pass works on those lists: locate the histogram bin that holds the k-th
+// largest, gather the few keys of that bin, resolve the exact key, scan the per-tile counts and emit
+// the message in ascending index order while zeroing the selected residual slots.  If a sampled
+// bracket turns out wrong the segment is redone by a route that cannot fail: a bin too coarse and too
+// full to resolve is binned again inside itself from the bracket lists; a k-th largest outside the
+// bracket is found from a 2048-bin histogram of the top key bits of all elements, after which the
+// lists are collected again.  Results are identical on every route; only the number of passes over
+// memory differs.
 //
 // Units of work.  A tile is TW consecutive elements; the streaming pass gives each of its SUB
-// sub-tiles to one 64-lane wavefront, which owns that sub-tile's slots of the candidate arrays, so
+// sub-tiles to one 64-lane wavefront, which owns that sub-tile's slots of the list arrays, so
 // ordered compaction needs no communication between wavefronts and no list can overflow.  No kernel
 // waits on another workgroup: cross-tile results (histograms, output offsets) are combined at kernel
 // boundaries.  Global atomics complete at a rate of roughly one per cache line per 10 ns on this part,
-// so the candidate histogram and the gather lists exist in REP copies (picked from the sub-tile,
+// so the bracket histogram and the gather lists exist in REP copies (picked from the sub-tile,
 // tile or workgroup number) and nothing else uses global atomics.
 
 #include <hip/hip_runtime.h>
@@ -38,33 +40,36 @@
 #include <vector>
 
 #include "gravac.h"
+#include "gravac_profile.h"
 
 namespace {
 
 #ifndef GV_TW
 #define GV_TW 8192
 #endif
-constexpr int TW = GV_TW;           // elements per tile (unit of the candidate-list kernels)
+constexpr int TW = GV_TW;           // elements per tile (unit of the list kernels)
 #ifndef GV_SUB
 #define GV_SUB 8
 #endif
 constexpr int SUB = GV_SUB;         // sub-tiles per tile: the streaming pass gives one wavefront a sub-tile
 constexpr int TS = TW / SUB;        // elements per sub-tile
-constexpr int WG = 256;             // threads per workgroup of the tile kernels
+constexpr int WG = 256;             // threads per workgroup of the streaming kernels
 constexpr int WAVES = WG / 64;
 #ifndef GV_LWG
 #define GV_LWG 256
 #endif
-constexpr int LWG = GV_LWG;         // threads per workgroup of the candidate-list kernels (refine, count, emit)
+constexpr int LWG = GV_LWG;         // threads per workgroup of the list kernels (refine, emit)
 constexpr int LWAVES = LWG / 64;
-constexpr int VCHUNK = 256;          // dense tiles: slots of one sub-tile list a wavefront takes per load, four per lane
-constexpr int VLISTS = 4;            // ... from this many of the tile's lists at a time (registers)
-constexpr uint32_t DENSE_TILE = TW / 4;  // a tile with at least this many candidates is walked that way
-static_assert(TS % VCHUNK == 0, "a sub-tile list is a whole number of such chunks");
 constexpr int ROW = 256;            // elements one wavefront touches per load (64 lanes x float4)
-#ifndef GV_ROWS
-#define GV_ROWS 4                   // rows a wavefront keeps in flight
+constexpr int ROWS = TS / ROW;      // rows of a sub-tile: all of them are in flight together
+static_assert(TS % ROW == 0 && ROWS == 4, "a sub-tile is four rows");
+#ifndef GV_DENSE
+#define GV_DENSE 384
 #endif
+constexpr uint32_t DENSE_SUB = GV_DENSE;  // a full sub-tile with at least this many candidates keeps no candidate list:
+                                          // the emit step reads its 1024 elements again (4 KB read + 4 KB written, what
+                                          // about 400 listed candidates cost in list traffic and scattered stores)
+constexpr uint32_t DENSE_BIT = 0x80000000u;  // flag of such a sub-tile in cand_cnt
 #ifndef GV_NT
 #define GV_NT 1                     // non-temporal hints on the streaming loads and stores
 #endif
@@ -72,13 +77,15 @@ constexpr int ROW = 256;            // elements one wavefront touches per load (
 #define GV_XGRID 1024
 #endif
 constexpr uint32_t XGRID = GV_XGRID;  // workgroups of the two exact-route kernels (they loop over the tiles)
-constexpr int REP = 8;              // copies of the candidate histogram and of the gather lists
-constexpr int NBIN = 2048;          // bins of the candidate / refine / coarse histograms
-constexpr uint32_t OVF = NBIN - 1;  // last bin of the candidate histogram: everything above the bracket
+constexpr int REP = 8;              // copies of the bracket histogram and of the gather lists
+constexpr int NBIN = 2048;          // bins of the bracket / refine / coarse histograms
+constexpr uint32_t OVF = NBIN - 1;  // bins 0 .. OVF - 1 cover the bracket; bin OVF stands for everything above it
+constexpr uint32_t XBINS = 1024;    // bins in use after an exact route has binned a segment again
 constexpr int SBIN = 4096;          // bins of the sample histogram: 2^17 keys each (64 per octave, 1.1 % in magnitude)
 constexpr uint32_t SSHIFT = 17;     // from |x| = 2^-48 up to 2^16; smaller magnitudes share bin 0, larger ones the last bin
 constexpr uint32_t SKEY0 = 79u << 23;
 static_assert((uint64_t)SKEY0 + ((uint64_t)SBIN << SSHIFT) <= 0x7F800000ull, "the window lies inside the finite keys");
+constexpr int SGRP = 8;             // the sample bins in SGRP groups: one workgroup of the threshold kernel each
 constexpr int SAMPLE_BLOCK = 1024;  // samples per workgroup of the sampling kernel
 constexpr int SAMPLE_MAX = 65536;   // samples per segment at most (unless the segment is read whole)
 constexpr int SAMPLE_MAX_FLAT = 524288;  // flat mode, a large k: see sample_count
@@ -86,45 +93,45 @@ constexpr int DENSE_ROUNDS = 4;          // ... whose sample blocks are up to DE
 constexpr int DENSE_BLOCKS = 128;        // ... so that there are at most this many of them
 constexpr int LCAP = 4096;          // keys a gather list can hold
 constexpr int MAXCF = GRAVAC_MAX_CF;
-constexpr uint32_t REUSE_MAX_K = 1u << 21;  // a CF that selects more entries than this is sampled even when thresholds are reused:
-                                            // the bracket a sample gives holds fewer entries than 0.25 k below the old threshold
 constexpr double ZMARGIN = 5.0;     // safety margin of the sampled rank, in standard deviations
 constexpr uint32_t NONE = 0xFFFFFFFFu;
+constexpr uint32_t KEY_END = 0x80000000u;  // one past the largest key
 
 enum : uint32_t { MODE_RESOLVED = 0, MODE_GATHER = 1, MODE_HIST = 2, MODE_FAIL = 3 };
-// SegState::fail, the heaviest kind over the segment's CFs wins:
+// SegState::fail, the heavier kind over the segment's CFs wins:
 //   FAIL_NARROW  the bin that holds the k-th largest is known but too coarse and too full to resolve: only the
-//                CFs concerned are binned again, inside that bin (no other pass);
-//   FAIL_LIGHT   the k-th largest lies above the histogram's bracket: the candidates hold it, all CFs of the
-//                segment are binned again from a coarse histogram of the candidates;
-//   FAIL_FULL    fewer than k candidates: acc is read again.
-enum : uint32_t { FAIL_NONE = 0, FAIL_NARROW = 1, FAIL_LIGHT = 2, FAIL_FULL = 3 };
+//                CFs concerned are binned again, inside that bin, from the bracket lists (no pass over the gradient);
+//   FAIL_FULL    the k-th largest lies outside the bracket (or there was none): acc is read again.
+enum : uint32_t { FAIL_NONE = 0, FAIL_NARROW = 1, FAIL_FULL = 3 };
+// where a call's brackets come from
+enum : uint32_t { BOUNDS_SAMPLED = 0, BOUNDS_RANDOM = 1, BOUNDS_FORCED = 2 };
 
 // Selection state of one (segment, CF).
 struct CfState {
     uint32_t k;         // entries to select
-    uint32_t lo;        // candidates for this CF have key >= lo
-    uint32_t s;         // candidate-histogram bin = min((key - lo) >> s, OVF)
+    uint32_t lo;        // first key of the bracket histogram's bin 0
+    uint32_t s;         // bin = (key - lo) >> s
     uint32_t mode;      // MODE_*
     uint32_t base;      // first key of the bin that holds the k-th largest
-    uint32_t open;      // 1 if that bin is the open-ended last bin
+    uint32_t span;      // a key lies in that bin iff 0 <= key - base <= span
     uint32_t above;     // number of keys above that bin
     uint32_t c;         // number of keys in that bin
     uint32_t tau;       // key of the k-th largest (valid once resolved)
     uint32_t need;      // how many keys equal to tau are selected (lowest indices first)
     uint32_t cnt_gt;    // number of keys greater than tau
     uint32_t redo;      // 1 if this CF is binned again on the narrow route (set by the locate step)
-    uint32_t lo2, s2;   // ... with these bounds: the located bin, cut into 1024 parts
-    uint32_t pad[2];
+    uint32_t lo2, s2;   // ... with these bounds: the located bin, cut into XBINS parts
+    uint32_t top;       // the pass over the gradient has counted keys >= top as above the bracket (KEY_END: none)
+    uint32_t pad;
 };
 static_assert(sizeof(CfState) == 64, "CfState layout");
 
 struct SegState {
-    uint32_t lo_min;  // smallest lo over the CFs: the candidate threshold of the segment
-    uint32_t fail;    // FAIL_*: whether the bound failed and the segment takes the exact route, and which form of it
-    uint32_t pz;      // the streaming pass has stored +0 instead of acc for keys >= pz: the upper end of the committed
-                      // CF's bracket, above which an entry is selected unless the bound fails (NONE: nothing zeroed)
-    uint32_t pad;
+    uint32_t lo_min;  // smallest lo over the CFs: keys below it concern no CF
+    uint32_t fail;    // FAIL_*: whether a bracket failed and the segment takes an exact route, and which
+    uint32_t pz;      // sparse sub-tiles: the first pass has stored +0 instead of acc for keys >= pz: the upper end of the
+                      // committed CF's bracket, above which an entry is selected unless the bracket fails (NONE: none)
+    uint32_t lo_c;    // the committed CF's lo: keys from here on are candidates for the message
 };
 
 struct Status {
@@ -132,9 +139,8 @@ struct Status {
     int n_fail;
     int error;
     int n_seg;
-    uint32_t sig_lo, sig_hi;  // signature (shape, CFs, segment table) of the last call that completed on this workspace
-    int n_light;              // segments of n_fail whose exact route only re-binned the candidates
-    int pad;
+    int n_narrow;             // segments of n_fail that were only binned again from their bracket lists
+    int pad[3];
 };
 
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -160,17 +166,16 @@ struct Params {
     int64_t n_restore;       // its length
     int single;              // 1 = single-source mode (second-level compression of a message)
     int random;              // 1 = Random-k: the order is that of a keyed priority of the index, not of |acc|
-    uint32_t rk_s0, rk_s1;   // its two 31-bit keys (from the seed)
+    int vec_ok;              // 1 if every buffer the kernels read or write with 16-byte accesses is aligned to 16 bytes
+    uint32_t bounds_from;    // BOUNDS_*
+    uint32_t rk_s0, rk_s1;   // Random-k: the two 31-bit keys (from the seed)
     int64_t n;
     int n_seg;  // >= 1
     int n_cf;
     int commit;
-    unsigned flags;
-    uint32_t sig_lo, sig_hi;  // signature of this call
     int64_t total_out;        // pairs the call emits
     uint32_t n_tiles;
     uint32_t n_sample_blocks;
-    uint32_t have_sample;          // 1 if the sampling kernel has run for this call
     // layerwise tables in the workspace (unused when n_seg == 1)
     const SegInfo* segs;           // [n_seg] built on the host
     const uint32_t* ktab;          // [n_seg][n_cf] built on the host
@@ -183,24 +188,35 @@ struct Params {
     Status* status;
     CfState* st;         // [n_seg][n_cf]
     SegState* seg;       // [n_seg]
-    uint32_t* hist1;     // [n_seg][n_cf][REP][NBIN] candidate histogram, REP copies
+    uint32_t* bnd_lo;    // [n_seg][n_cf] the bracket of every CF as the threshold kernel found it: first key ...
+    uint32_t* bnd_hi;    // [n_seg][n_cf] ... and one past its last key (at most KEY_END)
+    uint32_t* hist1;     // [n_seg][n_cf][REP][NBIN] bracket histogram, REP copies
     uint32_t* ovfc;      // [n_seg][n_cf][64][32] counts above the bracket (the histogram's last bin), spread over
                          // 64 cache lines; word 0 of each line is used
     uint32_t* hist2;     // [n_seg][n_cf][NBIN] refine histogram
     uint32_t* coarse;    // [n_seg][NBIN] histogram of key >> 20 (exact route)
-    uint32_t* list;      // [n_seg][n_cf][REP][LCAP] gather lists, REP copies
+    uint32_t* list_key;  // [n_seg][n_cf][REP][LCAP] gather lists, REP copies: key ...
+    uint32_t* list_tile; //                          ... tile ...
+    float* list_val;     //                          ... and value (written for Random-k only) of the listed entries
     uint32_t* list_cnt;  // [n_seg][n_cf][REP][32] fill counts of the gather lists, one cache line each
     uint32_t* samp_hist; // [n_sample_blocks][SBIN / 2] sample histograms, two 16-bit counts per word
-    uint32_t* cand_cnt;  // [n_tiles][SUB] candidates of every sub-tile
-    uint32_t* tg;        // [n_tiles] candidates above tau(commit) in this tile
-    uint32_t* te;        // [n_tiles] candidates equal to tau(commit) in this tile
+    uint32_t* samp_grp;  // [n_sample_blocks][SGRP] samples per group of SBIN / SGRP bins
+    uint32_t* cand_cnt;  // [n_tiles][SUB] listed candidates of every sub-tile (| DENSE_BIT: none listed, the sub-tile is read again)
+    uint32_t* brk_cnt;   // [n_tiles][SUB] bracket-list entries of every sub-tile
+    uint32_t* ovn;       // [n_tiles][SUB][n_cf] entries of the sub-tile above CF j's bracket
+    double* ovs;         // [n_tiles][SUB][n_cf] ... and their sum of acc^2
+    uint32_t* tg0;       // [n_tiles] entries of the tile above the committed CF's located bin
+    uint32_t* tin;       // [n_tiles] entries of the tile inside that bin
     uint32_t* toff;      // [n_tiles] offset of the tile's output inside its segment's message
-    uint32_t* ttake;     // [n_tiles] how many of the tile's candidates equal to tau(commit) are selected
+    uint32_t* ttake;     // [n_tiles] how many of the tile's entries equal to tau(commit) are selected
+    uint32_t* tsel;      // [n_tiles] pairs the tile emits
     double* ssd;         // [n_tiles][SUB] sum of acc^2 of every sub-tile
     double* ssd_t;       // [n_tiles] sum of acc^2 of the tile
-    double* sss;         // [n_tiles][n_cf] sum of acc^2 over keys > tau_j
-    int32_t* cand_idx;   // [n_tiles][SUB][TS] sub-tile j of tile u owns the slots from (u*SUB + j)*TS
+    double* sss;         // [n_tiles][n_cf] sum of acc^2 over the tile's keys above CF j's located bin
+    int32_t* cand_idx;   // [n_tiles][SUB][TS] candidate list: sub-tile j of tile u owns the slots from (u*SUB + j)*TS
     float* cand_val;     // [n_tiles][SUB][TS]
+    uint32_t* brk_key;   // [n_tiles][SUB][TS] bracket list: keys ...
+    float* brk_val;      // [n_tiles][SUB][TS] ... and values (written for Random-k only)
     // outputs
     int32_t* out_idx;
     float* out_val;
@@ -231,9 +247,20 @@ __device__ __forceinline__ uint32_t sample_bin(uint32_t key)
     return b < (uint32_t)SBIN - 1u ? b : (uint32_t)SBIN - 1u;
 }
 __device__ __forceinline__ uint32_t sample_bin_first(uint32_t b) { return b == 0u ? 0u : SKEY0 + (b << SSHIFT); }
-__device__ __forceinline__ uint64_t sample_bin_end(uint32_t b)
+__device__ __forceinline__ uint32_t sample_bin_end(uint32_t b)
 {
-    return b == (uint32_t)SBIN - 1u ? 2147483648ull : (uint64_t)SKEY0 + ((uint64_t)(b + 1u) << SSHIFT);
+    return b == (uint32_t)SBIN - 1u ? KEY_END : SKEY0 + ((b + 1u) << SSHIFT);
+}
+
+// The bracket histogram of a CF whose bracket is [lo, hi): the shift s is the smallest with which bins 0 .. OVF - 1
+// reach hi, and top is the first key past them (KEY_END if they reach past the largest key).
+__device__ __forceinline__ void bracket_bins(uint32_t lo, uint32_t hi, uint32_t& s, uint32_t& top)
+{
+    const uint32_t span = hi > lo ? hi - lo : 0u;
+    s = 0;
+    while ((span >> s) > OVF - 1u) ++s;
+    const uint64_t t = (uint64_t)lo + ((uint64_t)OVF << s);
+    top = t >= (uint64_t)KEY_END ? KEY_END : (uint32_t)t;
 }
 
 // Random-k: priority of index i, a keyed bijection of the 31-bit integers (adding a constant, multiplying
@@ -276,6 +303,20 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
+__device__ __forceinline__ uint64_t wave_sum(uint64_t v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += (uint64_t)__shfl_xor((unsigned long long)v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ double wave_max(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
 // inclusive prefix sum over the lanes of a wavefront
 __device__ __forceinline__ uint32_t wave_scan(uint32_t v)
 {
@@ -294,18 +335,11 @@ __device__ __forceinline__ uint32_t hash32(uint32_t x)
     return x;
 }
 
-// The candidates of a tile are the concatenation of its SUB sub-tile lists.
-struct TileCands {
-    uint32_t start[SUB + 1];  // start[j] = candidates in sub-tiles before j; start[SUB] = all
+// The entries of a tile's lists are the concatenation of its SUB sub-tile lists.
+struct TileLists {
+    uint32_t start[SUB + 1];  // start[j] = entries in sub-tiles before j; start[SUB] = all
     __device__ __forceinline__ uint32_t total() const { return start[SUB]; }
-    __device__ __forceinline__ uint32_t longest() const  // candidates of the fullest sub-tile
-    {
-        uint32_t m = 0;
-#pragma unroll
-        for (int j = 0; j < SUB; ++j) m = max(m, start[j + 1] - start[j]);
-        return m;
-    }
-    // slot (relative to the tile's first slot) of the tile's i-th candidate
+    // slot (relative to the tile's first slot) of the tile's i-th entry
     __device__ __forceinline__ uint32_t slot(uint32_t i) const
     {
         uint32_t j = 0;
@@ -318,12 +352,16 @@ struct TileCands {
     }
 };
 
-__device__ __forceinline__ TileCands tile_cands(const Params& p, uint32_t u)
+// from the per-sub-tile counts cnt[u * SUB ..]; a count's DENSE_BIT is masked off (such a sub-tile lists nothing)
+__device__ __forceinline__ TileLists tile_lists(const uint32_t* cnt, uint32_t u)
 {
-    TileCands c;
+    TileLists c;
     c.start[0] = 0;
 #pragma unroll
-    for (int j = 0; j < SUB; ++j) c.start[j + 1] = c.start[j] + p.cand_cnt[(size_t)u * SUB + j];
+    for (int j = 0; j < SUB; ++j) {
+        const uint32_t x = cnt[(size_t)u * SUB + j];
+        c.start[j + 1] = c.start[j] + ((x & DENSE_BIT) ? 0u : x);
+    }
     return c;
 }
 
@@ -442,7 +480,10 @@ __device__ __forceinline__ void team_locate_bin(const uint32_t* hist, int copies
 
 // ---------------------------------------------------------------------------------------------
 // K0a: sample acc = residual + grad at stratified positions; each workgroup histograms its samples in
-// LDS (SBIN bins of 2^17 keys, see sample_bin) and stores the counts as 16-bit numbers
+// LDS (SBIN bins of 2^17 keys, see sample_bin) and stores the counts as 16-bit numbers, and the
+// counts per group of SBIN / SGRP bins beside them.  The same launch clears what the later kernels
+// add to (every workgroup a share of its segment's histograms and counters); a call whose brackets
+// do not come from a sample launches it for that alone.
 // ---------------------------------------------------------------------------------------------
 template <int R>  // R groups per thread: a workgroup histograms R * SAMPLE_BLOCK samples
 __global__ __launch_bounds__(256) void sample_kernel(Params p)
@@ -452,6 +493,23 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
     const int t = is_flat(p) ? 0 : (int)p.sblock_seg[b];
     const uint32_t lb = b - (is_flat(p) ? 0u : p.segs[t].samp0);
     const uint32_t S = is_flat(p) ? p.flat_samples : p.segs[t].samp_cnt;
+    {
+        // the segment's sample blocks share the clearing: block lb of nbk takes every nbk-th 16-byte piece
+        const uint32_t per = SAMPLE_BLOCK * R;
+        const uint32_t nbk = is_flat(p) ? p.n_sample_blocks : (S + per - 1) / per;
+        const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+        uint4* h1 = (uint4*)(p.hist1 + (size_t)t * p.n_cf * REP * NBIN);
+        for (uint32_t i = lb * 256 + tid; i < (uint32_t)p.n_cf * REP * NBIN / 4; i += nbk * 256) h1[i] = z;
+        uint4* cs = (uint4*)(p.coarse + (size_t)t * NBIN);
+        for (uint32_t i = lb * 256 + tid; i < NBIN / 4; i += nbk * 256) cs[i] = z;
+        for (uint32_t i = lb * 256 + tid; i < (uint32_t)p.n_cf * 64; i += nbk * 256) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
+        for (uint32_t i = lb * 256 + tid; i < (uint32_t)p.n_cf * REP; i += nbk * 256) p.list_cnt[((size_t)t * p.n_cf * REP + i) * 32] = 0;
+        if (b == 0 && tid == 0) {
+            p.status->any_fail = 0; p.status->n_fail = 0; p.status->error = 0; p.status->n_seg = p.n_seg;
+            p.status->n_narrow = 0;
+        }
+    }
+    if (p.bounds_from != BOUNDS_SAMPLED) return;
     const int64_t s0 = seg_begin(p, t);
     const uint64_t nt = (uint64_t)(seg_end(p, t) - s0);
 #pragma unroll
@@ -509,72 +567,49 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
     static_assert(R * SAMPLE_BLOCK < 65536, "16-bit counts");
     uint4 w[2];
     uint32_t* wp = (uint32_t*)w;
+    uint32_t mine = 0;
 #pragma unroll
-    for (int m = 0; m < 8; ++m) wp[m] = h[16 * tid + 2 * m] | (h[16 * tid + 2 * m + 1] << 16);
+    for (int m = 0; m < 8; ++m) {
+        const uint32_t c0 = h[16 * tid + 2 * m], c1 = h[16 * tid + 2 * m + 1];
+        wp[m] = c0 | (c1 << 16);
+        mine += c0 + c1;
+    }
     uint4* dst = (uint4*)(p.samp_hist + (size_t)b * (SBIN / 2) + 8 * tid);
     dst[0] = w[0];
     dst[1] = w[1];
+    // a group of SBIN / SGRP = 512 bins is what 32 neighbouring threads hold: half a wavefront
+    static_assert(SBIN / SGRP == 32 * 16 && SGRP == 8, "one group per half wavefront");
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) mine += __shfl_xor(mine, o, 64);
+    if ((tid & 31) == 0) p.samp_grp[(size_t)b * SGRP + (tid >> 5)] = mine;
 }
 
 // ---------------------------------------------------------------------------------------------
-// K0b: per segment, add up the sample histograms and turn them into (lo, s) per CF; clear the
-// segment's histograms and gather-list counts
+// K0b: per segment, add up the sample histograms and turn the sampled ranks into a bracket of keys per
+// CF.  G workgroups per segment; workgroup y adds up the bins [y, y + 1) * SBIN / G of all the
+// segment's sample blocks (what lies above them it knows from the blocks' group counts) and writes the
+// bracket ends that fall into its bins, so that no workgroup waits for another.  The kernels that
+// use the brackets derive the histogram shift and the rest from them (bracket_bins).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void threshold_kernel(Params p)
+template <int G>
+__global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
 {
-    __shared__ uint32_t wtot[16];
-    __shared__ uint32_t rank_lo[MAXCF], rank_hi[MAXCF], bin_lo[MAXCF], bin_hi[MAXCF];
-    const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+    constexpr int T = 1024 / G;          // thread i owns the bins 4 (y T + i) .. + 3: two words of every block's histogram
+    constexpr int NW = T / 64;
+    static_assert(G == 1 || G == SGRP, "one workgroup per group of bins, or one for all");
+    __shared__ uint32_t wtot[NW], gab[NW], gto[NW];
+    __shared__ uint32_t rank_lo[MAXCF], rank_hi[MAXCF];
+    const int t = blockIdx.x, y = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
     const uint32_t S = is_flat(p) ? p.flat_samples : p.segs[t].samp_cnt;
     const uint32_t sb0 = is_flat(p) ? 0u : p.segs[t].samp0;
     const uint32_t nb = is_flat(p) ? p.n_sample_blocks : (S + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
-    if (!is_flat(p))
-        for (uint32_t u = seg_tile0(p, t) + tid; u < seg_tile1(p, t); u += 1024) p.tseg[u] = (uint32_t)t;
     const uint64_t nt = (uint64_t)(seg_end(p, t) - seg_begin(p, t));
     const bool whole = ((uint64_t)S == nt);
-    // reuse: take the previous call's thresholds as bounds, if that call had this call's signature;
-    // without a usable prediction (and without samples) every segment takes the exact route
-    const bool want_reuse = (p.flags & GRAVAC_FLAG_REUSE_THRESHOLDS) != 0;
-    const bool reuse = want_reuse && p.status->sig_lo == p.sig_lo && p.status->sig_hi == p.sig_hi;
-    // (a call that reuses thresholds samples as well if one of its CFs selects more than REUSE_MAX_K entries: such a CF
-    // takes its bounds from the sample, and so does every CF if the workspace turns out to hold no matching call)
-    const bool forced = (p.flags & GRAVAC_FLAG_FORCE_FALLBACK) != 0 || (want_reuse && !reuse && !p.have_sample);
-    const bool sampled = !forced && !p.random && p.have_sample != 0;
-
-    // reuse: the previous call's candidate histogram says where its count from the top reached about 1.25 k;
-    // that key becomes this call's lower bound (wavefront j looks at CF j, before the histogram is cleared)
-    __shared__ uint32_t pred_lo[MAXCF];
-    __shared__ uint32_t team_scratch[4][8];
-    if (reuse) {
-        // four teams of four wavefronts, team g takes CF g and CF g + 4
-        const int team = tid >> 8, q = tid & 255;
-        for (int r = 0; r < (p.n_cf + 3) / 4; ++r) {
-            const int j = r * 4 + team;
-            const int jj = j < p.n_cf ? j : 0;  // idle teams repeat CF 0 (they must reach the barriers)
-            const CfState* old = &p.st[(size_t)t * p.n_cf + jj];
-            const uint32_t k = seg_k(p, t, jj), lo_prev = old->lo, s_prev = old->s > 31u ? 31u : old->s;
-            uint32_t b, ab, cn;
-            team_locate_bin(p.hist1 + ((size_t)t * p.n_cf + jj) * REP * NBIN, REP, p.ovfc + ((size_t)t * p.n_cf + jj) * 64 * 32,
-                            k + k / 4 + 64, q, team_scratch[team], [] { __syncthreads(); }, b, ab, cn);
-            uint32_t lo;
-            // fewer candidates than that: go lower; a tensor of at most LCAP elements takes all its elements for one
-            // call (whatever bin then holds its k-th largest can be gathered), after which its histogram reaches the level
-            if (b == NONE) lo = (nt > (uint64_t)LCAP && lo_prev > (1u << 19)) ? lo_prev - (1u << 19) : 0u;
-            else {
-                const uint64_t x = (uint64_t)lo_prev + ((uint64_t)b << s_prev);
-                lo = x > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)x;
-            }
-            if (q == 0 && j < p.n_cf) pred_lo[j] = lo;
-        }
-    }
-    __syncthreads();
-    for (int i = tid; i < p.n_cf * REP * NBIN; i += 1024) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
-    for (int i = tid; i < NBIN; i += 1024) p.coarse[(size_t)t * NBIN + i] = 0;
-    for (int i = tid; i < p.n_cf * 64; i += 1024) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
-    for (int i = tid; i < p.n_cf * REP * 32; i += 1024) p.list_cnt[(size_t)t * p.n_cf * REP * 32 + i] = 0;
-    if (t == 0 && tid == 0) {
-        p.status->any_fail = 0; p.status->n_fail = 0; p.status->error = 0; p.status->n_seg = p.n_seg;
-        p.status->n_light = 0;
+    const bool sampled = p.bounds_from == BOUNDS_SAMPLED;
+    if (y == 0) {
+        if (!is_flat(p))
+            for (uint32_t u = seg_tile0(p, t) + tid; u < seg_tile1(p, t); u += T) p.tseg[u] = (uint32_t)t;
+        if (tid == 0) p.seg[t].fail = FAIL_NONE;  // the locate step raises it
     }
     if (tid < p.n_cf) {
         const uint32_t k = seg_k(p, t, tid);
@@ -589,14 +624,45 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
             r_hi = (b < 1.0) ? 1u : (uint32_t)b;
         }
         rank_lo[tid] = r_lo; rank_hi[tid] = r_hi;
-        bin_lo[tid] = 0;            // fewer than r_lo samples (or none at all): every key is a candidate
-        bin_hi[tid] = SBIN - 1;
     }
-
-    // thread i owns bins 4i .. 4i+3: two words of every block's histogram
+    if (!sampled) {
+        // no sample: the brackets follow from k alone (Random-k) or are left empty (every segment takes the exact route)
+        if (y == 0 && tid < p.n_cf) {
+            uint32_t lo = NONE, hi = NONE;
+            if (p.bounds_from == BOUNDS_RANDOM) {
+                // priorities are a keyed permutation of the 31-bit integers: the number of a tensor's nt indices
+                // with priority >= x is as good as binomial (nt, 1 - x / 2^31), so the bounds follow from k alone:
+                // x with k + ZMARGIN sqrt(k) + 2 expected above it, and x with k - ZMARGIN sqrt(k) - 2
+                const double k = (double)seg_k(p, t, tid), w = ZMARGIN * sqrt(k) + 2.0;
+                const double q_lo = (k + w) / (double)nt, q_hi = (k - w) / (double)nt;
+                lo = q_lo >= 1.0 ? 0u : (uint32_t)floor(2147483648.0 * (1.0 - q_lo));
+                hi = q_hi <= 0.0 ? KEY_END : (uint32_t)ceil(2147483648.0 * (1.0 - q_hi));
+            }
+            p.bnd_lo[(size_t)t * p.n_cf + tid] = lo;
+            p.bnd_hi[(size_t)t * p.n_cf + tid] = hi;
+        }
+        return;
+    }
+    // samples in the groups of bins above this workgroup's, and in all
+    uint32_t g_above = 0, g_total = 0;
+    if (G > 1) {
+        for (uint32_t b = tid; b < nb; b += T) {
+            const uint4* gp = (const uint4*)(p.samp_grp + (size_t)(sb0 + b) * SGRP);
+            const uint4 a = gp[0], c = gp[1];
+            const uint32_t v[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                g_total += v[g];
+                if (g > y) g_above += v[g];
+            }
+        }
+        g_above = wave_sum(g_above);
+        g_total = wave_sum(g_total);
+        if (lane == 0) { gab[wib] = g_above; gto[wib] = g_total; }
+    }
     uint32_t h0 = 0, h1 = 0, h2 = 0, h3 = 0;
-    if (sampled) {
-        const uint2* src = (const uint2*)(p.samp_hist + (size_t)sb0 * (SBIN / 2)) + tid;
+    {
+        const uint2* src = (const uint2*)(p.samp_hist + (size_t)sb0 * (SBIN / 2)) + (y * T + tid);
         for (uint32_t b0 = 0; b0 < nb; b0 += 32) {
             uint2 w[32];
 #pragma unroll
@@ -612,102 +678,83 @@ __global__ __launch_bounds__(1024) void threshold_kernel(Params p)
     const uint32_t incl = wave_scan(mine);
     if (lane == 63) wtot[wib] = incl;
     __syncthreads();
-    uint32_t total = 0, before = 0;
+    uint32_t local = 0, before = 0;
+    g_above = 0; g_total = 0;
 #pragma unroll
-    for (int w = 0; w < 16; ++w) {
+    for (int w = 0; w < NW; ++w) {
         const uint32_t x = wtot[w];
-        total += x;
+        local += x;
         if (w < wib) before += x;
+        if (G > 1) { g_above += gab[w]; g_total += gto[w]; }
     }
-    const uint32_t above0 = total - (before + incl);  // samples in bins above this thread's four
+    if (G == 1) g_total = local;
+    const uint32_t above0 = g_above + local - (before + incl);  // samples in bins above this thread's four
     const uint32_t hh[4] = {h0, h1, h2, h3};
     for (int j = 0; j < p.n_cf; ++j) {
         const uint32_t r_lo = rank_lo[j], r_hi = rank_hi[j];
+        const size_t id = (size_t)t * p.n_cf + j;
         uint32_t above = above0;
 #pragma unroll
         for (int q = 3; q >= 0; --q) {
             const uint32_t c = hh[q];
-            if (above < r_lo && above + c >= r_lo) bin_lo[j] = 4 * tid + q;
-            if (above < r_hi && above + c >= r_hi) bin_hi[j] = 4 * tid + q;
+            const uint32_t bin = 4u * (uint32_t)(y * T + tid) + (uint32_t)q;
+            // lower edge of the bin of the r_lo-th sample from the top, upper edge of the bin of the r_hi-th
+            if (above < r_lo && above + c >= r_lo) p.bnd_lo[id] = sample_bin_first(bin);
+            if (above < r_hi && above + c >= r_hi) p.bnd_hi[id] = sample_bin_end(bin);
             above += c;
         }
-    }
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t lo_min = NONE, pz = NONE;
-        for (int j = 0; j < p.n_cf; ++j) {
-            uint32_t lo = sample_bin_first(bin_lo[j]);             // lower edge of the bin of the r_lo-th sample
-            uint64_t hi = sample_bin_end(bin_hi[j]);               // upper edge of the bin of the r_hi-th sample
-            if (reuse && !(sampled && seg_k(p, t, j) > REUSE_MAX_K)) {
-                // from the key below which the previous call counted about 1.25 k candidates to 2^19 keys (about 4 % in
-                // magnitude) above the previous threshold: tight, for a run in steady state; a threshold that moves
-                // further than that costs one call through the exact route
-                const uint32_t tau_prev = p.st[(size_t)t * p.n_cf + j].tau & 0x7FFFFFFFu;
-                lo = pred_lo[j] < tau_prev ? pred_lo[j] : tau_prev;
-                hi = (uint64_t)tau_prev + (1u << 19);
-
-            }
-            if (p.random) {
-                // priorities are a keyed permutation of the 31-bit integers: the number of a tensor's nt indices
-                // with priority >= x is as good as binomial (nt, 1 - x / 2^31), so the bounds follow from k alone:
-                // x with k + ZMARGIN sqrt(k) + 2 expected above it, and x with k - ZMARGIN sqrt(k) - 2
-                const double k = (double)seg_k(p, t, j), w = ZMARGIN * sqrt(k) + 2.0;
-                const double q_lo = (k + w) / (double)nt, q_hi = (k - w) / (double)nt;
-                lo = q_lo >= 1.0 ? 0u : (uint32_t)floor(2147483648.0 * (1.0 - q_lo));
-                hi = q_hi <= 0.0 ? 2147483648ull : (uint64_t)ceil(2147483648.0 * (1.0 - q_hi));
-            }
-            uint32_t s = 0;
-            while (((hi > lo ? hi - lo : 0) >> s) > (uint64_t)OVF) ++s;
-            if (forced) { lo = NONE; s = 0; }
-            CfState st;
-            st.k = seg_k(p, t, j); st.lo = lo; st.s = s; st.mode = MODE_FAIL; st.base = 0; st.open = 0; st.above = 0;
-            st.c = 0; st.tau = 0; st.need = 0; st.cnt_gt = 0;
-            st.redo = 0; st.lo2 = 0; st.s2 = 0; st.pad[0] = st.pad[1] = 0;
-            p.st[(size_t)t * p.n_cf + j] = st;
-            lo_min = lo < lo_min ? lo : lo_min;
-            if (j == p.commit && !forced && !p.single) {
-                const uint64_t top = (uint64_t)lo + ((uint64_t)OVF << s);  // first key of the histogram's open last bin
-                if (top <= 0x7FFFFFFFull) pz = (uint32_t)top;
-            }
+        // fewer samples than a rank: the bracket is open on that side
+        if (y == 0 && tid == 0) {
+            if (g_total < r_lo) p.bnd_lo[id] = 0u;
+            if (g_total < r_hi) p.bnd_hi[id] = KEY_END;
         }
-        SegState ss;
-        ss.lo_min = lo_min; ss.fail = 0; ss.pz = pz; ss.pad = 0;
-        p.seg[t] = ss;
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// K1: the streaming pass, one wave tile per wavefront.
-//     EF = true: read grad and residual, write acc back, sum acc^2.
-//     EF = false (exact route, failed segments only): read acc from residual; lo comes from the
-//     coarse histogram.  Both collect the candidates of the tile in index order.
+// K1: the pass over the gradient, one sub-tile per wavefront.
+//     SM_EF: read grad and residual, write acc back, sum acc^2.
+//     SM_EXACT (exact route, failed segments only): read acc from residual; the brackets come from the
+//     coarse histogram.  Both collect the lists of the sub-tile in index order.
 // ---------------------------------------------------------------------------------------------
-struct TileCtx {
-    uint32_t lo_min;
+struct SubCtx {
+    uint32_t lo_min, lo_c, pz;
     uint32_t lo[MAXCF];
     uint32_t sh[MAXCF];
-    uint32_t ovf[MAXCF];
-    uint32_t* h1;   // this workgroup's copy of the candidate histograms of the tile's segment (CF stride REP*NBIN)
-    int32_t* cidx;  // candidate slots of this tile
+    uint32_t top[MAXCF];
+    uint32_t ovn[MAXCF];   // entries above CF j's bracket ...
+    double ovs[MAXCF];     // ... and their sum of acc^2
+    uint32_t* h1;   // this wavefront's copy of the bracket histograms of the tile's segment (CF stride REP*NBIN)
+    int32_t* cidx;  // candidate-list slots of this sub-tile
     float* cval;
-    uint32_t run;   // candidates written so far
+    uint32_t run;   // candidates listed so far
+    uint32_t* bkey; // bracket-list slots of this sub-tile
+    float* bval;
+    uint32_t brun;  // bracket entries listed so far
     double ssd;
     int ncf;
     uint32_t s0, s1;  // Random-k keys
-    uint32_t pz;      // first pass: keys >= pz leave +0 in the residual instead of acc (NONE: none)
-    uint32_t nb;      // bins of the histogram in use: a key whose bin number is nb or more counts as above the bracket
 };
 
-__device__ __forceinline__ void cand_hist(TileCtx& c, uint32_t key)
+// What one entry with key >= lo_min adds: per CF whose bracket starts at or below it, a count above the bracket or
+// a histogram update inside it.  Returns whether it lies inside some CF's bracket.
+__device__ __forceinline__ bool bracket_count(SubCtx& c, uint32_t key, float a)
 {
+    bool inside = false;
 #pragma unroll
     for (int j = 0; j < MAXCF; ++j) {
         if (j < c.ncf && key >= c.lo[j]) {
-            const uint32_t b = (key - c.lo[j]) >> c.sh[j];
-            if (b >= c.nb) c.ovf[j]++;
-            else atomicAdd(&c.h1[j * REP * NBIN + b], 1u);
+            if (key >= c.top[j]) {
+                const double d = (double)a;
+                c.ovn[j]++;
+                c.ovs[j] += d * d;
+            } else {
+                atomicAdd(&c.h1[j * REP * NBIN + ((key - c.lo[j]) >> c.sh[j])], 1u);
+                inside = true;
+            }
         }
     }
+    return inside;
 }
 
 __device__ __forceinline__ v4f ld_stream(const v4f* q)
@@ -730,15 +777,16 @@ __device__ __forceinline__ void st_stream(v4f v, v4f* q)
 
 // The ordering keys of one lane's four consecutive elements a[0..3] at global index g.
 template <bool RND>
-__device__ __forceinline__ void keys_of_row(const TileCtx& c, const float a[4], int64_t g, uint32_t key[4])
+__device__ __forceinline__ void keys_of_row(const SubCtx& c, const float a[4], int64_t g, uint32_t key[4])
 {
 #pragma unroll
     for (int e = 0; e < 4; ++e) key[e] = RND ? priority_of(c.s0, c.s1, (uint32_t)(g + e)) : key_of(a[e]);
 }
 
-// One lane's four consecutive elements a[0..3] with keys key[0..3] at global index g; vm = validity bits.
+// One lane's four consecutive elements a[0..3] with keys key[0..3] at global index g; vm = validity bits;
+// listed = whether the sub-tile keeps a candidate list (the same for all lanes).
 template <bool SSD, bool RND>
-__device__ __forceinline__ void consume(TileCtx& c, const float a[4], const uint32_t key[4], int64_t g, unsigned vm)
+__device__ __forceinline__ void consume(SubCtx& c, const float a[4], const uint32_t key[4], int64_t g, unsigned vm, bool listed)
 {
     bool f[4];
 #pragma unroll
@@ -750,32 +798,56 @@ __device__ __forceinline__ void consume(TileCtx& c, const float a[4], const uint
             c.ssd += d * d;
         }
     }
-    const bool any = f[0] | f[1] | f[2] | f[3];
-    if (__ballot(any) != 0ull) {
+    if (__ballot(f[0] | f[1] | f[2] | f[3]) == 0ull) return;
+    bool fb[4], fm[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        fb[e] = f[e] ? bracket_count(c, key[e], a[e]) : false;
+        fm[e] = listed && f[e] && key[e] >= c.lo_c;
+    }
+    if (__ballot(fm[0] | fm[1] | fm[2] | fm[3]) != 0ull) {
         uint32_t pre = 0, tot = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const uint64_t m = __ballot(f[e]);
+            const uint64_t m = __ballot(fm[e]);
             pre += lanes_below(m);
             tot += (uint32_t)__popcll(m);
         }
         uint32_t w = c.run + pre;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            if (f[e]) {
+            if (fm[e]) {
                 c.cidx[w] = (int32_t)(g + e);
                 c.cval[w] = a[e];
                 ++w;
-                cand_hist(c, key[e]);
             }
         }
         c.run += tot;
     }
+    if (__ballot(fb[0] | fb[1] | fb[2] | fb[3]) != 0ull) {
+        uint32_t pre = 0, tot = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint64_t m = __ballot(fb[e]);
+            pre += lanes_below(m);
+            tot += (uint32_t)__popcll(m);
+        }
+        uint32_t w = c.brun + pre;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (fb[e]) {
+                c.bkey[w] = key[e];
+                if (RND) c.bval[w] = a[e];
+                ++w;
+            }
+        }
+        c.brun += tot;
+    }
 }
 
-// Modes of the streaming pass.
+// Modes of the pass.
 enum { SM_EF = 0,      // acc = residual + grad, written back into residual
-       SM_EXACT = 1,   // exact route: acc is re-read, candidates are collected again
+       SM_EXACT = 1,   // exact route: acc is re-read, the lists are collected again
        SM_SINGLE = 2   // single source (second-level compression): acc = grad; every value is also written
 };                     // back into the dense residual at its mapped index (the emit pass zeroes the selected)
 
@@ -791,12 +863,12 @@ __device__ __forceinline__ void row_load(const Params& p, int64_t g, v4f& x, v4f
     }
 }
 
-// Arithmetic and stores of one row; a[] gets the four acc values.
+// Arithmetic of one row; a[] gets the four acc values.
 template <int M>
-__device__ __forceinline__ void row_finish(const Params& p, int64_t g, const v4f& x, const v4f& y, const v4i& m, float a[4])
+__device__ __forceinline__ void row_finish(const Params& p, const v4f& x, const v4f& y, const v4i& m, float a[4])
 {
     if (M == SM_EF) {
-        const v4f av = x + y;  // stored by store_acc_row, once the keys are known
+        const v4f av = x + y;  // stored once the keys are known
         a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
     }
     if (M == SM_EXACT) { a[0] = x.x; a[1] = x.y; a[2] = x.z; a[3] = x.w; }
@@ -811,18 +883,18 @@ __device__ __forceinline__ void row_finish(const Params& p, int64_t g, const v4f
     }
 }
 
-// First pass: acc goes back into the residual, except that an entry whose key lies above the committed CF's
-// bracket leaves +0 there already: it is selected unless the bound fails (the candidate lists keep its value, and
-// the routes for a failed bound put it back where it turns out not to be selected), which spares the emit step
-// a scattered store per selected entry.
-__device__ __forceinline__ void store_acc_row(const Params& p, const TileCtx& c, int64_t g, const float a[4], const uint32_t key[4])
+// One element of a row that is not handled with 16-byte accesses.
+template <int M>
+__device__ __forceinline__ float element_load(const Params& p, int64_t q)
 {
-    v4f o;
-    o.x = key[0] >= c.pz ? 0.0f : a[0];
-    o.y = key[1] >= c.pz ? 0.0f : a[1];
-    o.z = key[2] >= c.pz ? 0.0f : a[2];
-    o.w = key[3] >= c.pz ? 0.0f : a[3];
-    st_stream(o, (v4f*)(p.res + g));
+    if (M == SM_EF) return p.res[q] + p.grad[q];
+    if (M == SM_EXACT) return p.acc[q];
+    const float a = p.grad[q];
+    if (p.restore) {
+        const int mi = p.map_idx[q];
+        if ((uint64_t)(int64_t)mi < (uint64_t)p.n_restore) p.restore[mi] = a;
+    }
+    return a;
 }
 
 // Exact route: the bounds of the segment a wavefront last worked on (they cost a histogram search).
@@ -830,14 +902,16 @@ struct ExactBounds {
     int t;  // segment, -1 = none yet
     uint32_t lo[MAXCF];
     uint32_t sh[MAXCF];
-    uint32_t lo_min;
+    uint32_t top[MAXCF];   // narrow route: the end of the bracket the lists were collected with
+    uint32_t end[MAXCF];   // first key past the XBINS bins
+    uint32_t lo_min, lo_c;
 };
 
 // One sub-tile v, by one wavefront.
 template <int M, bool RND>
 __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int lane, ExactBounds* xb)
 {
-    constexpr bool EF = (M != SM_EXACT);  // a first pass: sums acc^2, takes the bounds from the threshold kernel
+    constexpr bool EF = (M != SM_EXACT);  // a first pass: sums acc^2, takes the brackets from the threshold kernel
     const uint32_t u = v / SUB;  // tile
     if (u >= p.n_tiles) return;
     const int t = tile_seg(p, u);
@@ -846,150 +920,177 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
     const int64_t sb = seg_begin(p, t), se = seg_end(p, t);
     const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW + (int64_t)(v % SUB) * TS;
     const int64_t e0 = (s0 + TS < se) ? s0 + TS : se;
-    if (s0 >= se) {  // sub-tile past the end of the segment
-        if (lane == 0) { p.cand_cnt[v] = 0; if (EF) p.ssd[v] = 0.0; }
+    const bool narrow = !EF && fail_kind == FAIL_NARROW;
+    if (s0 >= se && !narrow) {  // sub-tile past the end of the segment
+        if (lane == 0) { p.cand_cnt[v] = 0; p.brk_cnt[v] = 0; if (EF) p.ssd[v] = 0.0; }
+        if (lane < p.n_cf) { p.ovn[(size_t)v * p.n_cf + lane] = 0; p.ovs[(size_t)v * p.n_cf + lane] = 0.0; }
         return;
     }
 
-    TileCtx c;
+    SubCtx c;
     c.ncf = p.n_cf;
     c.s0 = p.rk_s0; c.s1 = p.rk_s1;
-    c.lo_min = NONE;
+    c.lo_min = NONE; c.lo_c = NONE; c.pz = NONE;
 #pragma unroll
     for (int j = 0; j < MAXCF; ++j) {
-        c.ovf[j] = 0;
-        c.lo[j] = NONE;
-        c.sh[j] = 0;
+        c.ovn[j] = 0; c.ovs[j] = 0.0;
+        c.lo[j] = NONE; c.sh[j] = 0; c.top[j] = KEY_END;
     }
-    c.pz = NONE;
-    // The exact route bins one coarse bin (or one bin of the first histogram) into 1024 parts: what lies above it
-    // needs no bin of its own, and half of the histogram updates with it.
-    c.nb = EF ? OVF : 1024u;
     if (EF) {
-        c.lo_min = p.seg[t].lo_min;
-        if (M == SM_EF) c.pz = p.seg[t].pz;
 #pragma unroll
         for (int j = 0; j < MAXCF; ++j) {
             if (j < p.n_cf) {
-                c.lo[j] = p.st[(size_t)t * p.n_cf + j].lo;
-                c.sh[j] = p.st[(size_t)t * p.n_cf + j].s;
+                c.lo[j] = p.bnd_lo[(size_t)t * p.n_cf + j];
+                bracket_bins(c.lo[j], p.bnd_hi[(size_t)t * p.n_cf + j], c.sh[j], c.top[j]);
+                c.lo_min = c.lo[j] < c.lo_min ? c.lo[j] : c.lo_min;
+                if (j == p.commit) {
+                    c.lo_c = c.lo[j];
+                    if (M == SM_EF && c.top[j] != KEY_END) c.pz = c.top[j];
+                }
             }
         }
     } else {
-        // exact route: lo_j = base of the coarse (key >> 20) bin that holds the k_j-th largest; 1024 bins of
-        // 2^10 keys cover that coarse bin, keys above it land in the open last bin
         const bool first = (v == seg_tile0(p, t) * SUB);
         if (xb->t != t) {
             xb->t = t;
-            xb->lo_min = NONE;
+            xb->lo_min = NONE; xb->lo_c = NONE;
 #pragma unroll
             for (int j = 0; j < MAXCF; ++j) {
-                xb->lo[j] = NONE;
-                xb->sh[j] = 10;
+                xb->lo[j] = NONE; xb->sh[j] = 10; xb->top[j] = KEY_END; xb->end[j] = KEY_END;
                 if (j < p.n_cf) {
-                    if (fail_kind == FAIL_NARROW) {
+                    const CfState* st = &p.st[(size_t)t * p.n_cf + j];
+                    if (narrow) {
                         // the locate step has left the bounds of the CFs that are binned again; the others keep
                         // their histogram and their plan (lo = NONE: no key is counted for them here)
-                        const CfState* st = &p.st[(size_t)t * p.n_cf + j];
-                        if (st->redo) { xb->lo[j] = st->lo2; xb->sh[j] = st->s2; }
+                        if (st->redo) { xb->lo[j] = st->lo2; xb->sh[j] = st->s2; xb->top[j] = st->top; }
                     } else {
+                        // lo_j = base of the coarse (key >> 20) bin that holds the k_j-th largest; XBINS bins of
+                        // 2^10 keys cover that coarse bin, keys above it count as above the bracket
                         uint32_t b, ab, cn;
                         wave_locate_bin(p.coarse + (size_t)t * NBIN, 1, nullptr, seg_k(p, t, j), b, ab, cn);
                         if (b == NONE) { b = 0; if (lane == 0) p.status->error = 1; }
                         xb->lo[j] = b << 20;
                     }
+                    if (xb->lo[j] != NONE) {
+                        const uint64_t e = (uint64_t)xb->lo[j] + ((uint64_t)XBINS << xb->sh[j]);
+                        xb->end[j] = e >= (uint64_t)KEY_END ? KEY_END : (uint32_t)e;
+                        if (!narrow) xb->top[j] = xb->end[j];
+                    }
                     xb->lo_min = xb->lo[j] < xb->lo_min ? xb->lo[j] : xb->lo_min;
+                    if (j == p.commit) xb->lo_c = xb->lo[j];
                 }
             }
         }
-        c.lo_min = xb->lo_min;
+        c.lo_min = xb->lo_min; c.lo_c = xb->lo_c;
 #pragma unroll
         for (int j = 0; j < MAXCF; ++j) {
             if (j < p.n_cf) {
                 c.lo[j] = xb->lo[j];
                 c.sh[j] = xb->sh[j];
+                c.top[j] = xb->end[j];
                 if (first && c.lo[j] != NONE) {
-                    // record the new bound; clear what the refine pass may add to
+                    // record the new bounds; clear what the refine pass may add to
                     CfState* st = &p.st[(size_t)t * p.n_cf + j];
-                    if (lane == 0) { st->lo = c.lo[j]; st->s = c.sh[j]; st->mode = MODE_FAIL; st->redo = 1; }
+                    if (lane == 0) {
+                        st->lo = c.lo[j]; st->s = c.sh[j]; st->mode = MODE_FAIL; st->redo = 1;
+                        if (!narrow) st->top = xb->end[j];
+                    }
                     for (int i = lane; i < NBIN; i += 64) p.hist2[((size_t)t * p.n_cf + j) * NBIN + i] = 0;
                     if (lane < REP) p.list_cnt[(((size_t)t * p.n_cf + j) * REP + lane) * 32] = 0;
                 }
             }
         }
-        // (on the narrow route the candidate lists and the segment's candidate threshold stay as they are)
-        if (first && lane == 0 && fail_kind != FAIL_NARROW) p.seg[t].lo_min = c.lo_min;
+        // (on the narrow route the lists and the segment's candidate thresholds stay as they are)
+        if (first && lane == 0 && !narrow) { p.seg[t].lo_min = c.lo_min; p.seg[t].lo_c = c.lo_c; p.seg[t].pz = NONE; }
     }
     // the copy of the histogram this wavefront adds to: spread by the sub-tile number, and by the tile number too,
-    // because the exact route's re-binning calls arrive with v = 8 u only
+    // because the narrow route's re-binning calls arrive with v = 8 u only
     c.h1 = p.hist1 + ((size_t)t * p.n_cf * REP + ((v ^ (v / SUB)) & (REP - 1))) * NBIN;
     c.cidx = p.cand_idx + (size_t)v * TS;
     c.cval = p.cand_val + (size_t)v * TS;
+    c.bkey = p.brk_key + (size_t)v * TS;
+    c.bval = p.brk_val + (size_t)v * TS;
     c.run = 0;
+    c.brun = 0;
     c.ssd = 0.0;
 
-    if (!EF && fail_kind != FAIL_FULL) {
-        // the candidate lists stay as they are; only their histogram is rebuilt with the new bins.  Called for the
-        // first sub-tile of a tile only: the wavefront takes the candidates of the whole tile
-        const TileCands tcs = tile_cands(p, u);
-        const uint32_t cnt = tcs.total();
-        const float* cv = p.cand_val + (size_t)u * TW;
-        const int32_t* ci = p.cand_idx + (size_t)u * TW;
+    if (narrow) {
+        // the lists stay as they are; only the histograms of the CFs concerned are rebuilt, with the new bins, from
+        // the tile's bracket lists.  Called for the first sub-tile of a tile only: the wavefront takes the whole tile.
+        // An entry counts for CF j if it lies inside the bracket the lists were collected with (below top_j: what
+        // lies above has been counted as above the bracket already) and from the located bin's first key on; past
+        // that bin's last key it adds to the count above the new, narrower bracket.
+        const TileLists tl = tile_lists(p.brk_cnt, u);
+        const uint32_t cnt = tl.total();
+        const uint32_t* bk = p.brk_key + (size_t)u * TW;
         for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
             uint32_t kq[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const uint32_t i = i0 + q * 64 + lane;
-                const uint32_t sl = (i < cnt) ? tcs.slot(i) : 0u;
-                kq[q] = RND ? priority_of(c.s0, c.s1, (uint32_t)ci[sl]) : key_of(cv[sl]);
+                kq[q] = bk[(i < cnt) ? tl.slot(i) : 0u];
             }
 #pragma unroll
-            for (int q = 0; q < 8; ++q)
-                if (i0 + q * 64 + lane < cnt) cand_hist(c, kq[q]);
+            for (int q = 0; q < 8; ++q) {
+                if (i0 + q * 64 + lane >= cnt) continue;
+#pragma unroll
+                for (int j = 0; j < MAXCF; ++j) {
+                    if (j < c.ncf && kq[q] >= c.lo[j] && kq[q] < xb->top[j]) {
+                        if (kq[q] >= c.top[j]) c.ovn[j]++;
+                        else atomicAdd(&c.h1[j * REP * NBIN + ((kq[q] - c.lo[j]) >> c.sh[j])], 1u);
+                    }
+                }
+            }
         }
 #pragma unroll
         for (int j = 0; j < MAXCF; ++j) {
             if (j < p.n_cf) {
-                const uint32_t o = wave_sum(c.ovf[j]);
+                const uint32_t o = wave_sum(c.ovn[j]);
                 if (lane == 0 && o) atomicAdd(&p.ovfc[(((size_t)t * p.n_cf + j) * 64 + (u & 63)) * 32], o);
             }
         }
         return;
     }
 
-    // rows start at a multiple of 4 elements so that vector accesses are 16-byte aligned
-    for (int64_t rb = s0 & ~(int64_t)3; rb < e0; rb += ROW) {
-        const bool full = (rb >= s0) && (rb + ROW <= e0);
-        if (full && rb + GV_ROWS * ROW <= e0) {
-            // GV_ROWS full rows: all loads first, then the arithmetic
-            v4f x[GV_ROWS], y[GV_ROWS];
-            v4i m[GV_ROWS];
+    bool dense = false;
+    if (p.vec_ok && (s0 & 3) == 0 && e0 - s0 == TS) {
+        // a whole sub-tile: the loads of all its rows first, then the arithmetic
+        v4f x[ROWS], y[ROWS];
+        v4i m[ROWS];
 #pragma unroll
-            for (int q = 0; q < GV_ROWS; ++q) row_load<M>(p, rb + q * ROW + 4 * lane, x[q], y[q], m[q]);
+        for (int q = 0; q < ROWS; ++q) row_load<M>(p, s0 + q * ROW + 4 * lane, x[q], y[q], m[q]);
+        float a[ROWS][4];
+        uint32_t nc = 0;  // candidates for the message in this sub-tile
 #pragma unroll
-            for (int q = 0; q < GV_ROWS; ++q) {
-                const int64_t g = rb + q * ROW + 4 * lane;
-                float a[4];
-                uint32_t key[4];
-                row_finish<M>(p, g, x[q], y[q], m[q], a);
-                keys_of_row<RND>(c, a, g, key);
-                if (M == SM_EF) store_acc_row(p, c, g, a, key);
-                consume<EF, RND>(c, a, key, g, 0xFu);
-            }
-            rb += (GV_ROWS - 1) * ROW;
-        } else if (full) {
-            const int64_t g = rb + 4 * lane;
-            v4f x, y;
-            v4i m;
-            float a[4];
+        for (int q = 0; q < ROWS; ++q) {
+            row_finish<M>(p, x[q], y[q], m[q], a[q]);
             uint32_t key[4];
-            row_load<M>(p, g, x, y, m);
-            row_finish<M>(p, g, x, y, m, a);
-            keys_of_row<RND>(c, a, g, key);
-            if (M == SM_EF) store_acc_row(p, c, g, a, key);
-            consume<EF, RND>(c, a, key, g, 0xFu);
-        } else {
-            // ragged row: element-wise, guarded
+            keys_of_row<RND>(c, a[q], s0 + q * ROW + 4 * lane, key);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) nc += (uint32_t)__popcll(__ballot(key[e] >= c.lo_c));
+        }
+        dense = nc >= DENSE_SUB;
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) {
+            const int64_t g = s0 + q * ROW + 4 * lane;
+            uint32_t key[4];
+            keys_of_row<RND>(c, a[q], g, key);
+            if (M == SM_EF) {
+                // acc goes back into the residual; in a sub-tile that keeps a candidate list an entry above the committed
+                // CF's bracket leaves +0 there already: it is selected unless the bracket fails (the list keeps its value,
+                // and the exact route puts it back), which spares the emit step a scattered store per selected entry
+                v4f o;
+                o.x = (!dense && key[0] >= c.pz) ? 0.0f : a[q][0];
+                o.y = (!dense && key[1] >= c.pz) ? 0.0f : a[q][1];
+                o.z = (!dense && key[2] >= c.pz) ? 0.0f : a[q][2];
+                o.w = (!dense && key[3] >= c.pz) ? 0.0f : a[q][3];
+                st_stream(o, (v4f*)(p.res + g));
+            }
+            consume<EF, RND>(c, a[q], key, g, 0xFu, !dense);
+        }
+    } else {
+        // a ragged or unaligned sub-tile: element-wise, guarded; rows start at a multiple of 4 elements
+        for (int64_t rb = s0 & ~(int64_t)3; rb < e0; rb += ROW) {
             const int64_t g = rb + 4 * lane;
             float a[4];
             unsigned vm = 0;
@@ -999,17 +1100,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                 a[e] = 0.0f;
                 if (q >= s0 && q < e0) {
                     vm |= 1u << e;
-                    if (M == SM_EF) {
-                        a[e] = p.res[q] + p.grad[q];  // stored below, once the keys are known
-                    } else if (M == SM_EXACT) {
-                        a[e] = p.acc[q];
-                    } else {
-                        a[e] = p.grad[q];
-                        if (p.restore) {
-                            const int mi = p.map_idx[q];
-                            if ((uint64_t)(int64_t)mi < (uint64_t)p.n_restore) p.restore[mi] = a[e];
-                        }
-                    }
+                    a[e] = element_load<M>(p, q);
                 }
             }
             uint32_t key[4];
@@ -1019,22 +1110,27 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                 for (int e = 0; e < 4; ++e)
                     if ((vm >> e) & 1u) p.res[g + e] = key[e] >= c.pz ? 0.0f : a[e];
             }
-            consume<EF, RND>(c, a, key, g, vm);
+            consume<EF, RND>(c, a, key, g, vm, true);
         }
     }
 
 #pragma unroll
     for (int j = 0; j < MAXCF; ++j) {
         if (j < p.n_cf) {
-            const uint32_t o = wave_sum(c.ovf[j]);
-            if (lane == 0 && o) atomicAdd(&p.ovfc[(((size_t)t * p.n_cf + j) * 64 + (v & 63)) * 32], o);
+            const uint32_t o = wave_sum(c.ovn[j]);
+            const double s = wave_sum(c.ovs[j]);
+            if (lane == 0) {
+                p.ovn[(size_t)v * p.n_cf + j] = o;
+                p.ovs[(size_t)v * p.n_cf + j] = s;
+                if (o) atomicAdd(&p.ovfc[(((size_t)t * p.n_cf + j) * 64 + (v & 63)) * 32], o);
+            }
         }
     }
     if (EF) {
         const double s = wave_sum(c.ssd);
         if (lane == 0) p.ssd[v] = s;
     }
-    if (lane == 0) p.cand_cnt[v] = c.run;
+    if (lane == 0) { p.cand_cnt[v] = dense ? DENSE_BIT : c.run; p.brk_cnt[v] = c.brun; }
 }
 
 // First pass (SM_EF, SM_SINGLE): one sub-tile per wavefront, one launch covers the whole gradient.
@@ -1054,16 +1150,39 @@ __global__ __launch_bounds__(WG) void stream_kernel(Params p)
         for (uint32_t u = w; u < p.n_tiles; u += nw) {
             const uint32_t kind = p.seg[tile_seg(p, u)].fail;
             if (kind == FAIL_NONE) continue;
-            // FAIL_NARROW, FAIL_LIGHT: one call re-bins the candidates of the whole tile; FAIL_FULL: sub-tile by sub-tile
+            // FAIL_NARROW: one call re-bins the bracket lists of the whole tile; FAIL_FULL: sub-tile by sub-tile
             const int subs = (kind == FAIL_FULL) ? SUB : 1;
             for (int j = 0; j < subs; ++j) stream_subtile<SM_EXACT, RND>(p, u * SUB + j, lane, &xb);
         }
     }
 }
 
+// The candidates of sub-tile v that its first pass replaced by +0 in the residual get their values back (the
+// sub-tile's candidate list holds them; nobody else touches the sub-tile).  By one wavefront.
+__device__ __forceinline__ void put_back_subtile(const Params& p, uint32_t v, uint32_t pz, int lane)
+{
+    const uint32_t cc = p.cand_cnt[v];
+    if (cc & DENSE_BIT) return;  // such a sub-tile kept acc
+    const float* cv = p.cand_val + (size_t)v * TS;
+    const int32_t* ci = p.cand_idx + (size_t)v * TS;
+    for (uint32_t i0 = 0; i0 < cc; i0 += 64 * 4) {
+        float vq[4];
+        int32_t iq[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t i = i0 + q * 64 + lane;
+            vq[q] = cv[i < cc ? i : 0u];
+            iq[q] = ci[i < cc ? i : 0u];
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (i0 + q * 64 + lane < cc && cand_key(p, iq[q], vq[q]) >= pz) p.res[iq[q]] = vq[q];
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
-// F1 (exact route): histogram of key >> 20 over the tiles of failed segments; the wavefront of a
-// failed segment's first tile also clears that segment's candidate histograms
+// F1 (exact route, FAIL_FULL): histogram of key >> 20 over the tiles of failed segments; the wavefront
+// of a failed segment's first tile also clears that segment's bracket histograms
 // ---------------------------------------------------------------------------------------------
 constexpr int CSUB = 8;  // copies of the coarse histogram inside a workgroup: lane l counts in copy l % CSUB
 
@@ -1089,18 +1208,7 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
             uint32_t ue = ub + 1;
             while (ue < u1 && tile_seg(p, ue) == t) ++ue;
             const uint32_t kind = p.seg[t].fail;
-            if (kind == FAIL_NARROW) {
-                // no coarse histogram: the wavefront of the segment's first tile clears the candidate histograms of
-                // the CFs that are binned again
-                const uint32_t u = ub + (tid >> 6);
-                if (u < ue && u == seg_tile0(p, t)) {
-                    for (int j = 0; j < p.n_cf; ++j) {
-                        if (p.st[(size_t)t * p.n_cf + j].redo == 0) continue;
-                        for (int i = lane; i < REP * NBIN; i += 64) p.hist1[((size_t)t * p.n_cf + j) * REP * NBIN + i] = 0;
-                        p.ovfc[(((size_t)t * p.n_cf + j) * 64 + lane) * 32] = 0;
-                    }
-                }
-            } else if (kind != FAIL_NONE) {
+            if (kind == FAIL_FULL) {
                 if (cur != t && cur >= 0) {
                     // flush the previous segment's counts
                     __syncthreads();
@@ -1123,62 +1231,21 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
                         for (int i = lane; i < p.n_cf * REP * NBIN; i += 64) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
                         for (int i = lane; i < p.n_cf * 64; i += 64) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
                     }
-                    if (kind == FAIL_LIGHT) {
-                        // the candidates of the tile are enough
-                        const TileCands tcs = tile_cands(p, u);
-                        const float* cv = p.cand_val + (size_t)u * TW;
-                        const int32_t* ci = p.cand_idx + (size_t)u * TW;
-                        const uint32_t cnt = tcs.total();
-                        for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
-                            // eight loads in flight per lane (an absent candidate reads slot 0 and is not counted)
-                            float vq[8];
-                            int32_t iq[8];
+                    const uint32_t pz = p.single ? NONE : p.seg[t].pz;
+                    if (pz != NONE) {
+                        // acc is read again from the residual: first put back what the first pass replaced by +0 there
+                        for (int j = 0; j < SUB; ++j) put_back_subtile(p, u * SUB + j, pz, lane);
+                        __threadfence_block();  // the loads below are this wavefront's own, of the same addresses
+                    }
+                    for (int64_t q0 = s0 + lane; q0 < e0; q0 += 64 * 16) {
+                        // all loads first, without branches around them (an element past the end reads the last
+                        // one instead and is not counted), so that they are in flight together
+                        float a[16];
 #pragma unroll
-                            for (int q = 0; q < 8; ++q) {
-                                const uint32_t i = i0 + q * 64 + lane;
-                                const uint32_t sl = (i < cnt) ? tcs.slot(i) : 0u;
-                                vq[q] = cv[sl];
-                                iq[q] = p.random ? ci[sl] : 0;
-                            }
+                        for (int r = 0; r < 16; ++r) a[r] = p.acc[q0 + r * 64 < e0 ? q0 + r * 64 : e0 - 1];
 #pragma unroll
-                            for (int q = 0; q < 8; ++q)
-                                if (i0 + q * 64 + lane < cnt) atomicAdd(&h[cand_key(p, iq[q], vq[q]) >> 20], 1u);
-                        }
-                    } else {
-                        const uint32_t pz = p.single ? NONE : p.seg[t].pz;
-                        if (pz != NONE) {
-                            // acc is read again from the residual: first put back what the first pass replaced by +0 in
-                            // this tile (the tile's candidate lists hold those values; nobody else touches the tile)
-                            const TileCands tcs = tile_cands(p, u);
-                            const float* cv = p.cand_val + (size_t)u * TW;
-                            const int32_t* ci = p.cand_idx + (size_t)u * TW;
-                            const uint32_t cnt = tcs.total();
-                            for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
-                                float vq[8];
-                                int32_t iq[8];
-#pragma unroll
-                                for (int q = 0; q < 8; ++q) {
-                                    const uint32_t i = i0 + q * 64 + lane;
-                                    const uint32_t sl = (i < cnt) ? tcs.slot(i) : 0u;
-                                    vq[q] = cv[sl];
-                                    iq[q] = ci[sl];
-                                }
-#pragma unroll
-                                for (int q = 0; q < 8; ++q)
-                                    if (i0 + q * 64 + lane < cnt && cand_key(p, iq[q], vq[q]) >= pz) p.res[iq[q]] = vq[q];
-                            }
-                            __threadfence_block();  // the loads below are this wavefront's own, of the same addresses
-                        }
-                        for (int64_t q0 = s0 + lane; q0 < e0; q0 += 64 * 16) {
-                            // all loads first, without branches around them (an element past the end reads the last
-                            // one instead and is not counted), so that they are in flight together
-                            float a[16];
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) a[r] = p.acc[q0 + r * 64 < e0 ? q0 + r * 64 : e0 - 1];
-#pragma unroll
-                            for (int r = 0; r < 16; ++r)
-                                if (q0 + r * 64 < e0) atomicAdd(&h[cand_key(p, (int32_t)(q0 + r * 64), a[r]) >> 20], 1u);
-                        }
+                        for (int r = 0; r < 16; ++r)
+                            if (q0 + r * 64 < e0) atomicAdd(&h[cand_key(p, (int32_t)(q0 + r * 64), a[r]) >> 20], 1u);
                     }
                 }
             }
@@ -1199,21 +1266,21 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
 
 // How the bin that holds the k-th largest gets resolved to one key.
 struct BinPlan {
-    uint32_t mode, base, open, above, c;
+    uint32_t mode, base, span, above, c;
 };
 
-// Decide from the located bin (b, above, c) of the candidate histogram with bins (key - lo) >> s.
+// Decide from the located bin (b, above, c) of the bracket histogram with bins (key - lo) >> s, of which the
+// first nb are in use (anything from bin nb on was counted as above the bracket and arrives as bin OVF).
 __device__ __forceinline__ BinPlan plan_bin(uint32_t lo, uint32_t s, uint32_t b, uint32_t above, uint32_t c)
 {
     BinPlan q;
-    if (b == NONE) q.mode = MODE_FAIL;  // fewer than k candidates: the bound was too high
-    else if (b == OVF) q.mode = (c <= LCAP) ? MODE_GATHER : MODE_FAIL;
+    if (b == NONE || b == OVF) q.mode = MODE_FAIL;  // fewer than k entries from lo on, or the k-th lies above the bracket
     else if (s == 0) q.mode = MODE_RESOLVED;
     else if (c <= LCAP) q.mode = MODE_GATHER;
     else if (s <= 11) q.mode = MODE_HIST;
     else q.mode = MODE_FAIL;
-    q.base = (b == NONE) ? 0u : lo + (b << s);
-    q.open = (b == OVF) ? 1u : 0u;
+    q.base = (b == NONE || b == OVF) ? 0u : lo + (b << s);
+    q.span = (1u << s) - 1u;
     q.above = above;
     q.c = c;
     return q;
@@ -1223,49 +1290,77 @@ __device__ __forceinline__ void store_plan(CfState* st, const BinPlan& q)
 {
     st->mode = q.mode;
     if (q.mode != MODE_FAIL) {
-        st->base = q.base; st->open = q.open; st->above = q.above; st->c = q.c;
+        st->base = q.base; st->span = q.span; st->above = q.above; st->c = q.c;
         if (q.mode == MODE_RESOLVED) { st->tau = q.base; st->cnt_gt = q.above; st->need = st->k - q.above; }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// L1: one workgroup per (segment, CF): find the candidate-histogram bin of the k-th largest and
-// decide how to resolve it; a segment whose bound failed is marked for the exact route
+// L1: one workgroup per (segment, CF): find the bracket-histogram bin of the k-th largest and
+// decide how to resolve it; a segment whose bracket failed is marked for an exact route
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void locate_kernel(Params p)
 {
     __shared__ uint32_t scratch[8];
     const int tid = threadIdx.x;
     const uint32_t id = blockIdx.x;
-    const int t = id / p.n_cf;
+    const int t = id / p.n_cf, j = id - t * p.n_cf;
     CfState* st = &p.st[id];
+    const uint32_t k = seg_k(p, t, j);
+    const uint32_t lo = p.bnd_lo[id];
+    uint32_t s, top;
+    bracket_bins(lo, p.bnd_hi[id], s, top);
     uint32_t b, above, c;
-    team_locate_bin(p.hist1 + (size_t)id * REP * NBIN, REP, p.ovfc + (size_t)id * 64 * 32, st->k, tid, scratch,
+    team_locate_bin(p.hist1 + (size_t)id * REP * NBIN, REP, p.ovfc + (size_t)id * 64 * 32, k, tid, scratch,
                     [] { __syncthreads(); }, b, above, c);
-    const BinPlan q = plan_bin(st->lo, st->s, b, above, c);
+    const BinPlan q = plan_bin(lo, s, b, above, c);
     if (q.mode == MODE_HIST)
         for (int i = tid; i < NBIN; i += 256) p.hist2[(size_t)id * NBIN + i] = 0;
+    const bool narrow = q.mode == MODE_FAIL && b != NONE && b != OVF;
+    if (narrow) {
+        // a bin 2^s keys wide (s > 11) with more than LCAP keys: XBINS bins of 2^(s - 10) keys cover it, and a
+        // bin at most 2^10 keys wide can always be resolved (gathered or histogrammed key by key); this CF's
+        // histogram is rebuilt by the exact route, the count above the bracket stays
+        for (int i = tid; i < REP * NBIN; i += 256) p.hist1[(size_t)id * REP * NBIN + i] = 0;
+    }
     if (tid == 0) {
+        st->k = k; st->lo = lo; st->s = s; st->top = top;
+        st->base = 0; st->span = 0; st->above = 0; st->c = 0; st->tau = 0; st->need = 0; st->cnt_gt = 0;
+        st->redo = 0; st->lo2 = 0; st->s2 = 0; st->pad = 0;
         store_plan(st, q);
         if (q.mode == MODE_FAIL) {
             p.status->any_fail = 1;
-            uint32_t kind = FAIL_FULL;               // fewer than k candidates
-            if (b == OVF) kind = FAIL_LIGHT;         // above the bracket, more keys there than a gather list holds
-            else if (b != NONE) {
-                // a bin 2^s keys wide (s > 11) with more than LCAP keys: 1024 bins of 2^(s - 10) keys cover it, and a
-                // bin at most 2^10 keys wide can always be resolved (gathered or histogrammed key by key)
+            uint32_t kind = FAIL_FULL;
+            if (narrow) {
                 kind = FAIL_NARROW;
-                st->redo = 1; st->lo2 = q.base; st->s2 = st->s - 10;
+                st->redo = 1; st->lo2 = lo + (b << s); st->s2 = s - 10;
             }
             if (atomicMax(&p.seg[t].fail, kind) == 0u) atomicAdd(&p.status->n_fail, 1);
+        }
+        if (j == 0) {
+            // what the segment's tiles need of all its CFs together
+            uint32_t lo_min = NONE, lo_c = NONE, pz = NONE;
+            for (int x = 0; x < p.n_cf; ++x) {
+                const uint32_t lx = p.bnd_lo[(size_t)t * p.n_cf + x];
+                lo_min = lx < lo_min ? lx : lo_min;
+                if (x == p.commit) {
+                    uint32_t sx, tx;
+                    bracket_bins(lx, p.bnd_hi[(size_t)t * p.n_cf + x], sx, tx);
+                    lo_c = lx;
+                    if (!p.single && tx != KEY_END) pz = tx;
+                }
+            }
+            p.seg[t].lo_min = lo_min; p.seg[t].lo_c = lo_c; p.seg[t].pz = pz;
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// R1: one pass over the candidates: gather (or histogram) the keys of the bin that holds the
-// k-th largest.  For a segment that took the exact route the plan is derived here, by every
-// wavefront for itself, from the rebuilt candidate histogram (its first tile's wavefront records it).
+// R1: one wavefront per tile walks the tile's bracket lists: per CF, the entries above the bin that
+// holds the k-th largest are counted and their energy summed (together with what the pass over the
+// gradient counted above the bracket), the entries inside that bin are gathered (key, tile, value) or
+// histogrammed.  For a segment that took an exact route the plan is derived here, by every wavefront
+// for itself, from the rebuilt bracket histogram (its first tile's wavefront records it).
 // ---------------------------------------------------------------------------------------------
 template <int NCF>  // compiled for calls with up to NCF CFs: the loops over the CFs are unrolled
 __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
@@ -1273,24 +1368,23 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
     const int lane = threadIdx.x & 63;
     const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * LWAVES + (threadIdx.x >> 6));
     if (u >= p.n_tiles) return;
-    const TileCands tc = tile_cands(p, u);
-    const uint32_t cnt = tc.total();
+    const TileLists tl = tile_lists(p.brk_cnt, u);
+    const uint32_t cnt = tl.total();
     const int t = tile_seg(p, u);
     const bool redo = p.status->any_fail != 0 && p.seg[t].fail != 0;
     const bool first = redo && (u == seg_tile0(p, t));
-    if (cnt == 0 && !first) return;
-    // exact route: the plan comes from the rebuilt candidate histogram.  A plain loop whose results go through
+    // exact route: the plan comes from the rebuilt bracket histogram.  A plain loop whose results go through
     // LDS, so that the search does not inflate the register count of the common path.
     __shared__ uint32_t rp[LWAVES][MAXCF][3];
     const int wib = threadIdx.x >> 6;
     if (redo) {
         const uint32_t fail_kind = p.seg[t].fail;
-        if (first && lane == 0 && fail_kind != FAIL_FULL) atomicAdd(&p.status->n_light, 1);
+        if (first && lane == 0 && fail_kind == FAIL_NARROW) atomicAdd(&p.status->n_narrow, 1);
         for (int j = 0; j < p.n_cf; ++j) {
             CfState* st = &p.st[(size_t)t * p.n_cf + j];
             if (fail_kind == FAIL_NARROW && st->redo == 0) {
                 // this CF was not binned again: its plan stands (nobody writes it during this kernel)
-                if (lane == 0) { rp[wib][j][0] = st->mode; rp[wib][j][1] = st->base; rp[wib][j][2] = st->open; }
+                if (lane == 0) { rp[wib][j][0] = st->mode; rp[wib][j][1] = st->base; rp[wib][j][2] = st->span; }
                 continue;
             }
             uint32_t b, above, c;
@@ -1298,362 +1392,286 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
                             st->k, b, above, c);
             const BinPlan q = plan_bin(st->lo, st->s, b, above, c);
             if (lane == 0) {
-                rp[wib][j][0] = q.mode; rp[wib][j][1] = q.base; rp[wib][j][2] = q.open;
+                rp[wib][j][0] = q.mode; rp[wib][j][1] = q.base; rp[wib][j][2] = q.span;
                 if (first) {
                     store_plan(st, q);
-                    if (q.mode == MODE_FAIL) p.status->error = 1;  // the exact route cannot fail
+                    if (q.mode == MODE_FAIL) p.status->error = 1;  // the exact routes cannot fail
                 }
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // rp is read back by the same wavefront
     }
-    uint32_t mode[NCF], base[NCF], span[NCF];
-    bool work = false;
+    uint32_t mode[NCF], base[NCF], span[NCF], top[NCF];
+    uint32_t hn[NCF], tin = 0;
+    double hs[NCF];
 #pragma unroll
     for (int j = 0; j < NCF; ++j) {
-        mode[j] = MODE_RESOLVED; base[j] = 0; span[j] = 0;
+        mode[j] = MODE_RESOLVED; base[j] = NONE; span[j] = 0; top[j] = 0; hn[j] = 0; hs[j] = 0.0;
         if (j < p.n_cf) {
             const CfState* st = &p.st[(size_t)t * p.n_cf + j];
-            const uint32_t s = st->s;
-            uint32_t open;
-            if (redo) { mode[j] = rp[wib][j][0]; base[j] = rp[wib][j][1]; open = rp[wib][j][2]; }
-            else { mode[j] = st->mode; base[j] = st->base; open = st->open; }
-            span[j] = open ? NONE : ((1u << s) - 1u);  // in the bin <=> key - base <= span
-            work |= (mode[j] == MODE_GATHER || mode[j] == MODE_HIST);
+            top[j] = st->top;
+            if (redo) { mode[j] = rp[wib][j][0]; base[j] = rp[wib][j][1]; span[j] = rp[wib][j][2]; }
+            else { mode[j] = st->mode; base[j] = st->base; span[j] = st->span; }
+            if (mode[j] == MODE_FAIL) { base[j] = NONE; top[j] = 0; }  // (an error: nothing is counted)
         }
     }
-    if (!work || cnt == 0) return;
-    const float* cv = p.cand_val + (size_t)u * TW;
-    const int32_t* ci = p.cand_idx + (size_t)u * TW;
-    // what one candidate key adds, per CF, if it lies in the bin that holds the k-th largest
-    const auto take = [&](uint32_t key, bool live) {
+    const uint32_t* bk = p.brk_key + (size_t)u * TW;
+    const float* bv = p.brk_val + (size_t)u * TW;
+    // what one bracket-list entry adds, per CF whose bracket it lies in
+    const auto take = [&](uint32_t key, float val, bool live) {
+        const double dv = p.random ? (double)val : (double)__uint_as_float(key);  // Top-k: the key is |acc|
 #pragma unroll
         for (int j = 0; j < NCF; ++j) {
             if (j >= p.n_cf) continue;
-            const bool in = live && key >= base[j] && key - base[j] <= span[j];
+            const bool mine = live && key < top[j] && key >= base[j];
+            const bool in = mine && key - base[j] <= span[j];
+            // Random-k: the entry at the threshold is the last one selected and has no particular magnitude, so a bin
+            // that is one key wide adds its energy here (Top-k adds need * tau^2 in the scan instead)
+            if (mine && (!in || (p.random && mode[j] == MODE_RESOLVED))) { hs[j] += dv * dv; hn[j] += in ? 0u : 1u; }
+            if (j == p.commit && in) ++tin;
             if (mode[j] == MODE_GATHER) {
                 // one counter update per wavefront: the lanes with a key in the bin take consecutive slots
                 const uint64_t m = __ballot(in);
                 if (m != 0ull) {
                     const size_t lst = ((size_t)t * p.n_cf + j) * REP + (blockIdx.x & (REP - 1));
                     const int leader = __ffsll((unsigned long long)m) - 1;
-                    uint32_t first = 0;
-                    if (lane == leader) first = atomicAdd(&p.list_cnt[lst * 32], (uint32_t)__popcll(m));
-                    first = __shfl(first, leader, 64);
-                    const uint32_t pos = first + lanes_below(m);
-                    if (in && pos < LCAP) p.list[lst * LCAP + pos] = key;
+                    uint32_t at = 0;
+                    if (lane == leader) at = atomicAdd(&p.list_cnt[lst * 32], (uint32_t)__popcll(m));
+                    at = __shfl(at, leader, 64);
+                    const uint32_t pos = at + lanes_below(m);
+                    if (in && pos < LCAP) {
+                        p.list_key[lst * LCAP + pos] = key;
+                        p.list_tile[lst * LCAP + pos] = u;
+                        if (p.random) p.list_val[lst * LCAP + pos] = val;
+                    }
                 }
             } else if (mode[j] == MODE_HIST && in) {
                 atomicAdd(&p.hist2[((size_t)t * p.n_cf + j) * NBIN + (key - base[j])], 1u);
             }
         }
     };
-    if (cnt < DENSE_TILE) {
-        for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
-            // eight loads in flight per lane
-            uint32_t kq[8];
-            if (p.random) {  // the key comes from the index: all loads first, then the arithmetic
+    for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
+        // eight loads in flight per lane
+        uint32_t kq[8];
+        float vq[8];
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    const uint32_t i = i0 + q * 64 + lane;
-                    kq[q] = (uint32_t)ci[(i < cnt) ? tc.slot(i) : 0u];
-                }
-#pragma unroll
-                for (int q = 0; q < 8; ++q) kq[q] = priority_of(p.rk_s0, p.rk_s1, kq[q]);
-            } else {
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    const uint32_t i = i0 + q * 64 + lane;
-                    kq[q] = key_of(cv[(i < cnt) ? tc.slot(i) : 0u]);
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < 8; ++q) take(kq[q], i0 + q * 64 + lane < cnt);
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t i = i0 + q * 64 + lane;
+            const uint32_t sl = (i < cnt) ? tl.slot(i) : 0u;
+            kq[q] = bk[sl];
+            vq[q] = p.random ? bv[sl] : 0.0f;
         }
-        return;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) take(kq[q], vq[q], i0 + q * 64 + lane < cnt);
     }
+    // the tile's sums: what the pass over the gradient counted above the brackets, plus the above
     {
-        // a dense tile: four consecutive slots per lane and load, the same VCHUNK slots of VLISTS lists in flight
-        // together (see count_kernel)
-        const v4f* cv4 = (const v4f*)cv;
-        const v4i* ci4 = (const v4i*)ci;
-        const uint32_t nmax = tc.longest();
-        for (uint32_t c0 = 0; c0 < nmax; c0 += VCHUNK) {
-            const uint32_t first = c0 + 4 * lane;  // < TS
-            // (the forms for many CFs are too long for this loop to be unrolled: they read the list counts from memory,
-            // not from the register array, which can only be indexed by constants)
-#pragma unroll
-            for (int j0 = 0; j0 < SUB; j0 += VLISTS) {
-                v4i kv[VLISTS];  // the bits the key is made from: the value's, or the index for Random-k
-                if (p.random) {
-#pragma unroll
-                    for (int j = 0; j < VLISTS; ++j) kv[j] = ci4[(j0 + j) * (TS / 4) + first / 4];
-                } else {
-#pragma unroll
-                    for (int j = 0; j < VLISTS; ++j) kv[j] = __builtin_bit_cast(v4i, cv4[(j0 + j) * (TS / 4) + first / 4]);
-                }
-#pragma unroll
-                for (int j = 0; j < VLISTS; ++j) {
-                    uint32_t n;
-                    if constexpr (NCF <= 2) n = tc.start[j0 + j + 1] - tc.start[j0 + j];
-                    else n = p.cand_cnt[(size_t)u * SUB + j0 + j];
-                    if (n <= c0) continue;  // the same for all lanes
-#pragma unroll
-                    for (int x = 0; x < 4; ++x)
-                        take(p.random ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)kv[j][x]) : ((uint32_t)kv[j][x] & 0x7FFFFFFFu),
-                             first + x < n);
-                }
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// L2: per (segment, CF) resolve the exact key tau of the k-th largest, and how many ties it takes
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void resolve_kernel(Params p)
-{
-    __shared__ uint32_t wsum[2][WAVES];
-    const int id = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
-    CfState* st = &p.st[id];
-    // the fill counts of the gather lists are fetched together with the plan, not after it (they do not depend on it)
-    uint32_t fill[REP];
-#pragma unroll
-    for (int r = 0; r < REP; ++r) fill[r] = p.list_cnt[((size_t)id * REP + r) * 32];
-    const uint32_t mode = st->mode;
-    if (mode == MODE_RESOLVED) return;
-    if (mode == MODE_FAIL) { if (tid == 0) p.status->error = 1; return; }
-    const uint32_t k = st->k, above = st->above, want = k - above;  // want-th largest inside the bin
-    const uint32_t base = st->base;
-    if (mode == MODE_HIST) {
-        if (wib != 0) return;
-        uint32_t b, ab, cn;  // bins are single keys: base + b
-        wave_locate_bin(p.hist2 + (size_t)id * NBIN, 1, nullptr, want, b, ab, cn);
-        if (lane == 0) {
-            if (b == NONE) { p.status->error = 1; b = 0; }
-            st->tau = base + b;
-            st->cnt_gt = above + ab;
-            st->need = k - st->cnt_gt;
-            st->mode = MODE_RESOLVED;
-        }
-        return;
-    }
-    // gather: the want-th largest of the listed keys, by a bitwise search on d = key - base.
-    // The keys sit in REP lists; list r holds positions [off_r, off_r + n_r) of the concatenation.
-    const uint32_t c = st->c;
-    uint32_t off[REP + 1];
-    off[0] = 0;
-#pragma unroll
-    for (int r = 0; r < REP; ++r) off[r + 1] = off[r] + fill[r];
-    if (off[REP] != c || c > LCAP || want == 0 || want > c) { if (tid == 0) p.status->error = 1; return; }
-    uint32_t d[LCAP / 256];
-    // all loads first, without branches around them (a position past the last key reads key 0 of the lists
-    // instead; c >= 1 here), so that they are in flight together
-#pragma unroll
-    for (int q = 0; q < LCAP / 256; ++q) {
-        const uint32_t i = (uint32_t)(q * 256 + tid) < c ? (uint32_t)(q * 256 + tid) : 0u;
-        int r = 0;
-#pragma unroll
-        for (int x = 1; x < REP; ++x) r += (i >= off[x]);
-        uint32_t o = 0;
-#pragma unroll
-        for (int x = 0; x < REP; ++x) if (x == r) o = off[x];
-        d[q] = p.list[((size_t)id * REP + r) * LCAP + (i - o)];
-    }
-#pragma unroll
-    for (int q = 0; q < LCAP / 256; ++q)
-        d[q] = (uint32_t)(q * 256 + tid) < c ? d[q] - base : 0u;  // padding never counts: trial values are >= 1
-    const int nbits = st->open ? 31 : (int)st->s;
-    uint32_t prefix = 0;
-    int buf = 0;
-    for (int bit = nbits - 1; bit >= 0; --bit) {
-        const uint32_t trial = prefix | (1u << bit);
-        uint32_t cnt = 0;
-#pragma unroll
-        for (int q = 0; q < LCAP / 256; ++q) cnt += (d[q] >= trial);
-        cnt = wave_sum(cnt);
-        if (lane == 0) wsum[buf][wib] = cnt;
-        __syncthreads();
-        const uint32_t total = wsum[buf][0] + wsum[buf][1] + wsum[buf][2] + wsum[buf][3];
-        buf ^= 1;
-        if (total >= want) prefix = trial;
-    }
-    uint32_t gt = 0;
-#pragma unroll
-    for (int q = 0; q < LCAP / 256; ++q) gt += (q * 256 + tid < c) && (d[q] > prefix);
-    gt = wave_sum(gt);
-    __syncthreads();
-    if (lane == 0) wsum[0][wib] = gt;
-    __syncthreads();
-    if (tid == 0) {
-        st->tau = base + prefix;
-        st->cnt_gt = above + wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
-        st->need = k - st->cnt_gt;
-        st->mode = MODE_RESOLVED;
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// K3: one wavefront per tile: candidates above / at the committed threshold, energy above each
-// CF's threshold.  Written for every tile, so that the scan needs no second look at cand_cnt.
-// ---------------------------------------------------------------------------------------------
-template <int NCF>  // as refine_kernel
-__global__ __launch_bounds__(LWG) void count_kernel(Params p)
-{
-    const int lane = threadIdx.x & 63;
-    const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * LWAVES + (threadIdx.x >> 6));
-    if (u >= p.n_tiles) return;
-    const TileCands tcs = tile_cands(p, u);
-    const uint32_t cnt = tcs.total();
-    {   // energy of the tile = sum over its sub-tiles, in a fixed order
         const double x = wave_sum(lane < SUB ? p.ssd[(size_t)u * SUB + lane] : 0.0);
         if (lane == 0) p.ssd_t[u] = x;
     }
-    if (cnt == 0) {
-        if (lane == 0) { p.tg[u] = 0; p.te[u] = 0; }
-        if (lane < p.n_cf) p.sss[(size_t)u * p.n_cf + lane] = 0.0;
-        return;
-    }
-    const int t = tile_seg(p, u);
-    uint32_t tau[NCF];
-    uint32_t tc = 0;
-#pragma unroll
-    for (int j = 0; j < NCF; ++j) {
-        tau[j] = (j < p.n_cf) ? p.st[(size_t)t * p.n_cf + j].tau : NONE;
-        if (j == p.commit) tc = tau[j];
-    }
-    double ss[NCF];
-#pragma unroll
-    for (int j = 0; j < NCF; ++j) ss[j] = 0.0;
-    uint32_t g = 0, e = 0;
-    const float* cv = p.cand_val + (size_t)u * TW;
-    const int32_t* ci = p.cand_idx + (size_t)u * TW;
-    // Random-k: priorities are distinct, the entry at the threshold is the last one selected and has no
-    // particular magnitude, so its energy is summed here (Top-k adds need * tau^2 in the scan instead)
-    const uint32_t at_tau = p.random ? 1u : 0u;
-    if (cnt < DENSE_TILE) {
-        for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
-            float vq[8];
-            uint32_t kq[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const uint32_t i = i0 + q * 64 + lane;
-                const uint32_t sl = (i < cnt) ? tcs.slot(i) : 0u;
-                vq[q] = cv[sl];
-                kq[q] = p.random ? (uint32_t)ci[sl] : 0u;   // all loads first, then the arithmetic
-            }
-#pragma unroll
-            for (int q = 0; q < 8; ++q) kq[q] = p.random ? priority_of(p.rk_s0, p.rk_s1, kq[q]) : key_of(vq[q]);
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                if (i0 + q * 64 + lane < cnt) {
-                    const uint32_t key = kq[q];
-                    const double dv = (double)vq[q];
-                    g += (key > tc);
-                    e += (key == tc);
-#pragma unroll
-                    for (int j = 0; j < NCF; ++j) if (j < p.n_cf && key + at_tau > tau[j]) ss[j] += dv * dv;
-                }
-            }
-        }
-    } else {
-        // A dense tile: four consecutive slots per lane and load, the same VCHUNK slots of VLISTS lists in flight
-        // together (a list of TS slots is aligned to 16 bytes; slots past a list's count hold older entries and
-        // are masked off).  A sparse tile would leave most lanes of such a walk idle and takes the loop below.
-        const v4f* cv4 = (const v4f*)cv;
-        const v4i* ci4 = (const v4i*)ci;
-        const uint32_t nmax = tcs.longest();
-        static_assert(SUB % VLISTS == 0, "the lists are taken VLISTS at a time");
-        for (uint32_t c0 = 0; c0 < nmax; c0 += VCHUNK) {
-            const uint32_t first = c0 + 4 * lane;  // < TS
-#pragma unroll
-            for (int j0 = 0; j0 < SUB; j0 += VLISTS) {
-                v4f v[VLISTS];
-                v4i ix[VLISTS];
-#pragma unroll
-                for (int j = 0; j < VLISTS; ++j) v[j] = cv4[(j0 + j) * (TS / 4) + first / 4];
-                if (p.random) {
-#pragma unroll
-                    for (int j = 0; j < VLISTS; ++j) ix[j] = ci4[(j0 + j) * (TS / 4) + first / 4];
-                }
-#pragma unroll
-                for (int j = 0; j < VLISTS; ++j) {
-                    const uint32_t n = tcs.start[j0 + j + 1] - tcs.start[j0 + j];
-                    if (n <= c0) continue;  // the same for all lanes
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        const bool live = first + x < n;
-                        const uint32_t key = p.random ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)ix[j][x]) : key_of(v[j][x]);
-                        const double dv = (double)v[j][x];
-                        g += (live && key > tc);
-                        e += (live && key == tc);
-#pragma unroll
-                        for (int c = 0; c < NCF; ++c) if (c < p.n_cf && live && key + at_tau > tau[c]) ss[c] += dv * dv;
-                    }
-                }
-            }
-        }
-    }
-    g = wave_sum(g);
-    e = wave_sum(e);
+    tin = wave_sum(tin);
 #pragma unroll
     for (int j = 0; j < NCF; ++j) {
         if (j < p.n_cf) {
-            const double x = wave_sum(ss[j]);
-            if (lane == 0) p.sss[(size_t)u * p.n_cf + j] = x;
+            const uint32_t on = wave_sum(hn[j] + (lane < SUB ? p.ovn[((size_t)u * SUB + lane) * p.n_cf + j] : 0u));
+            // (the counted energy first, in sub-tile order, then the listed entries': a fixed order)
+            const double os = wave_sum(lane < SUB ? p.ovs[((size_t)u * SUB + lane) * p.n_cf + j] : 0.0) + wave_sum(hs[j]);
+            if (lane == 0) {
+                p.sss[(size_t)u * p.n_cf + j] = os;
+                if (j == p.commit) { p.tg0[u] = on; p.tin[u] = tin; }
+            }
         }
     }
-    if (lane == 0) { p.tg[u] = g; p.te[u] = e; }
 }
 
 // ---------------------------------------------------------------------------------------------
-// SCAN: grid (n_seg, slices + n_cf).  Block (t, y < slices): exclusive scan of the counts of the
-//       y-th slice of SCAN_SLICE tiles of segment t -> every tile's output offset and tie quota.
-//       The totals of the earlier slices are re-added by every block (a few batched loads), so no
-//       block waits on another.  Block (t, slices + j): statistics of (segment t, CF j), summed
-//       over the tiles in a fixed order.
+// SCAN: grid (n_seg, slices + n_cf), SCAN_T threads.  Every block first resolves one CF of its segment to
+//       the exact key tau of the k-th largest (from the gathered keys by a bitwise search, or from the
+//       key-by-key histogram), and how many keys equal to tau are selected.
+//       Block (t, y < slices), committed CF: the counts of the y-th slice of SCAN_SLICE tiles of
+//       segment t (entries above the located bin, plus the gathered entries above tau, by tile) and their
+//       exclusive scan -> every tile's output offset and tie quota.  The totals of the earlier slices are
+//       re-added by every block (a few batched loads), so no block waits on another.
+//       Block (t, slices + j): statistics of (segment t, CF j), summed over the tiles in a fixed order.
 // ---------------------------------------------------------------------------------------------
 constexpr int SCAN_T = 1024;                 // threads
+constexpr int SCAN_W = SCAN_T / 64;
 constexpr int SCAN_PER = 4;                  // tiles per thread
 constexpr int SCAN_SLICE = SCAN_T * SCAN_PER;
+constexpr int LPER = LCAP / SCAN_T;          // gathered entries per thread
+static_assert(LCAP % SCAN_T == 0, "the gathered entries are dealt evenly");
 
 __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
 {
     __shared__ uint32_t sg[SCAN_SLICE], se[SCAN_SLICE];
-    __shared__ uint32_t wt[4][16];
-    __shared__ double dred[2][SCAN_T / 64];
+    __shared__ uint32_t wt[4][SCAN_W];
+    __shared__ uint32_t wsum[2][SCAN_W];
+    __shared__ double dred[3][SCAN_W];
+    __shared__ uint64_t ured[SCAN_W];
+    __shared__ uint32_t res3[3];
     const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
     const int t = blockIdx.x;
-    if (blockIdx.y < slices) {
-        const uint32_t u0 = seg_tile0(p, t), u1 = seg_tile1(p, t);
-        const uint32_t base = u0 + blockIdx.y * SCAN_SLICE;
-        if (base >= u1) return;
-        const uint32_t need = p.st[(size_t)t * p.n_cf + p.commit].need;
-        // this slice, coalesced
+    const bool scan_role = blockIdx.y < slices;
+    const int j = scan_role ? p.commit : (int)(blockIdx.y - slices);
+    const uint32_t id = (uint32_t)t * p.n_cf + j;
+    const uint32_t u0 = seg_tile0(p, t), u1 = seg_tile1(p, t);
+    const uint32_t slice0 = scan_role ? u0 + blockIdx.y * SCAN_SLICE : 0u;
+    if (scan_role && slice0 >= u1) return;
+    CfState* st = &p.st[id];
+
+    // ---- resolve (segment t, CF j)
+    // the fill counts of the gather lists are fetched together with the plan, not after it (they do not depend on it)
+    uint32_t fill[REP];
+#pragma unroll
+    for (int r = 0; r < REP; ++r) fill[r] = p.list_cnt[((size_t)id * REP + r) * 32];
+    const uint32_t mode = st->mode, k = st->k, above = st->above, base = st->base, span = st->span;
+    uint32_t tau = st->tau, need = st->need, cnt_gt = st->cnt_gt;   // valid if the located bin was one key wide
+    uint32_t d[LPER], rt[LPER];   // this thread's gathered entries: key - base (0 for a slot past the last entry) and tile
+    float rv[LPER];
+    bool rl[LPER];
+#pragma unroll
+    for (int q = 0; q < LPER; ++q) { d[q] = 0; rt[q] = 0; rv[q] = 0.0f; rl[q] = false; }
+    if (mode == MODE_FAIL) {
+        if (tid == 0) p.status->error = 1;
+        tau = 0; need = 0; cnt_gt = 0;
+    } else if (mode == MODE_HIST) {
+        if (wib == 0) {
+            uint32_t b, ab, cn;  // bins are single keys: base + b
+            wave_locate_bin(p.hist2 + (size_t)id * NBIN, 1, nullptr, k - above, b, ab, cn);
+            if (lane == 0) {
+                if (b == NONE) { p.status->error = 1; b = 0; }
+                res3[0] = base + b; res3[1] = above + ab;
+            }
+        }
+        __syncthreads();
+        tau = res3[0]; cnt_gt = res3[1]; need = k - cnt_gt;
+    } else if (mode == MODE_GATHER) {
+        // the want-th largest of the listed keys, by a bitwise search on d = key - base.
+        // The keys sit in REP lists; list r holds positions [off_r, off_r + n_r) of the concatenation.
+        const uint32_t c = st->c, want = k - above;
+        uint32_t off[REP + 1];
+        off[0] = 0;
+#pragma unroll
+        for (int r = 0; r < REP; ++r) off[r + 1] = off[r] + fill[r];
+        if (off[REP] != c || c > LCAP || want == 0 || want > c) {
+            if (tid == 0) p.status->error = 1;
+            tau = base; need = 0; cnt_gt = above;
+        } else {
+            // all loads first, without branches around them (a position past the last key reads key 0 of the lists
+            // instead; c >= 1 here), so that they are in flight together
+#pragma unroll
+            for (int q = 0; q < LPER; ++q) {
+                const uint32_t i = (uint32_t)(q * SCAN_T + tid) < c ? (uint32_t)(q * SCAN_T + tid) : 0u;
+                int r = 0;
+#pragma unroll
+                for (int x = 1; x < REP; ++x) r += (i >= off[x]);
+                uint32_t o = 0;
+#pragma unroll
+                for (int x = 0; x < REP; ++x) if (x == r) o = off[x];
+                const size_t at = ((size_t)id * REP + r) * LCAP + (i - o);
+                d[q] = p.list_key[at];
+                rt[q] = p.list_tile[at];
+                rv[q] = p.random ? p.list_val[at] : 0.0f;
+            }
+#pragma unroll
+            for (int q = 0; q < LPER; ++q) {
+                rl[q] = (uint32_t)(q * SCAN_T + tid) < c;
+                d[q] = rl[q] ? d[q] - base : 0u;  // padding never counts: trial values are >= 1
+            }
+            int nbits = 0;
+            while (nbits < 32 && (span >> nbits) != 0u) ++nbits;
+            uint32_t prefix = 0;
+            int buf = 0;
+            for (int bit = nbits - 1; bit >= 0; --bit) {
+                const uint32_t trial = prefix | (1u << bit);
+                uint32_t cn = 0;
+#pragma unroll
+                for (int q = 0; q < LPER; ++q) cn += (d[q] >= trial);
+                cn = wave_sum(cn);
+                if (lane == 0) wsum[buf][wib] = cn;
+                __syncthreads();
+                uint32_t total = 0;
+#pragma unroll
+                for (int w = 0; w < SCAN_W; ++w) total += wsum[buf][w];
+                buf ^= 1;
+                if (total >= want) prefix = trial;
+            }
+            uint32_t gt = 0;
+#pragma unroll
+            for (int q = 0; q < LPER; ++q) gt += rl[q] && (d[q] > prefix);
+            gt = wave_sum(gt);
+            __syncthreads();
+            if (lane == 0) wsum[0][wib] = gt;
+            __syncthreads();
+            uint32_t gsum = 0;
+#pragma unroll
+            for (int w = 0; w < SCAN_W; ++w) gsum += wsum[0][w];
+            tau = base + prefix; cnt_gt = above + gsum; need = k - cnt_gt;
+            __syncthreads();
+        }
+    }
+    const uint32_t dtau = tau - base;  // the threshold inside the located bin
+
+    if (scan_role) {
+        // (the plan itself stays as it is: the segment's other blocks are reading it)
+        if (blockIdx.y == 0 && tid == 0) { st->tau = tau; st->need = need; st->cnt_gt = cnt_gt; }
+        // this slice, coalesced: entries above the located bin; entries equal to tau if that bin is one key wide
         uint32_t og[SCAN_PER], oe[SCAN_PER];
 #pragma unroll
         for (int q = 0; q < SCAN_PER; ++q) {
-            const uint32_t u = base + q * SCAN_T + tid;
-            og[q] = (u < u1) ? p.tg[u] : 0u;
-            oe[q] = (u < u1) ? p.te[u] : 0u;
+            const uint32_t u = slice0 + q * SCAN_T + tid;
+            og[q] = (u < u1) ? p.tg0[u] : 0u;
+            oe[q] = (u < u1 && mode == MODE_RESOLVED) ? p.tin[u] : 0u;
         }
         // totals of the earlier slices of this segment
         uint32_t pg = 0, pe = 0;
-        for (uint32_t v0 = u0 + tid; v0 < base; v0 += 32 * SCAN_T) {
+        for (uint32_t v0 = u0 + tid; v0 < slice0; v0 += 32 * SCAN_T) {
             uint32_t xg[32], xe[32];
 #pragma unroll
             for (int q = 0; q < 32; ++q) {
                 const uint32_t v = v0 + q * SCAN_T;
-                xg[q] = (v < base) ? p.tg[v] : 0u;
-                xe[q] = (v < base) ? p.te[v] : 0u;
+                xg[q] = (v < slice0) ? p.tg0[v] : 0u;
+                xe[q] = (v < slice0 && mode == MODE_RESOLVED) ? p.tin[v] : 0u;
             }
 #pragma unroll
             for (int q = 0; q < 32; ++q) { pg += xg[q]; pe += xe[q]; }
         }
-        pg = wave_sum(pg);
-        pe = wave_sum(pe);
 #pragma unroll
         for (int q = 0; q < SCAN_PER; ++q) { sg[q * SCAN_T + tid] = og[q]; se[q * SCAN_T + tid] = oe[q]; }
+        __syncthreads();
+        if (mode == MODE_GATHER) {
+            // the gathered entries above and at the threshold, by tile
+#pragma unroll
+            for (int q = 0; q < LPER; ++q) {
+                if (!rl[q] || d[q] < dtau) continue;
+                const bool gt = d[q] > dtau;
+                if (rt[q] < slice0) { if (gt) ++pg; else ++pe; }
+                else if (rt[q] - slice0 < (uint32_t)SCAN_SLICE) atomicAdd(gt ? &sg[rt[q] - slice0] : &se[rt[q] - slice0], 1u);
+            }
+        } else if (mode == MODE_HIST) {
+            // more keys in the located bin than a gather list holds (a mass of equal values): the tiles that have
+            // entries in the bin are walked again, up to the end of this slice, one wavefront per tile at a time
+            const uint32_t uend = slice0 + SCAN_SLICE < u1 ? slice0 + SCAN_SLICE : u1;
+            for (uint32_t u = u0 + wib; u < uend; u += SCAN_W) {
+                if (p.tin[u] == 0) continue;
+                const TileLists tl = tile_lists(p.brk_cnt, u);
+                const uint32_t cnt = tl.total();
+                const uint32_t* bk = p.brk_key + (size_t)u * TW;
+                const uint32_t top = st->top;
+                uint32_t g = 0, e = 0;
+                for (uint32_t i = lane; i < cnt; i += 64) {
+                    const uint32_t key = bk[tl.slot(i)];
+                    if (key < top && key >= base && key - base <= span) { g += key > tau; e += key == tau; }
+                }
+                g = wave_sum(g); e = wave_sum(e);
+                if (lane == 0) {
+                    if (u < slice0) { pg += g; pe += e; }
+                    else { atomicAdd(&sg[u - slice0], g); atomicAdd(&se[u - slice0], e); }
+                }
+            }
+        }
+        pg = wave_sum(pg);
+        pe = wave_sum(pe);
         if (lane == 0) { wt[2][wib] = pg; wt[3][wib] = pe; }
         __syncthreads();
         // this thread's SCAN_PER consecutive tiles
@@ -1668,151 +1686,326 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
         __syncthreads();
         uint32_t run_g = ig - sum_g, run_e = ie - sum_e;   // counts before this thread's tiles
 #pragma unroll
-        for (int w = 0; w < 16; ++w) {
+        for (int w = 0; w < SCAN_W; ++w) {
             if (w < wib) { run_g += wt[0][w]; run_e += wt[1][w]; }
             run_g += wt[2][w];
             run_e += wt[3][w];
         }
+        uint32_t off[SCAN_PER], tk[SCAN_PER];
 #pragma unroll
         for (int i = 0; i < SCAN_PER; ++i) {
             const uint32_t ties_before = run_e < need ? run_e : need;  // ties selected in earlier tiles
             const uint32_t left = need - ties_before;
-            sg[tid * SCAN_PER + i] = run_g + ties_before;               // output offset of the tile
-            se[tid * SCAN_PER + i] = left < e[i] ? left : e[i];         // its tie quota
+            off[i] = run_g + ties_before;                               // output offset of the tile
+            tk[i] = left < e[i] ? left : e[i];                          // its tie quota
             run_g += g[i];
             run_e += e[i];
         }
         __syncthreads();
 #pragma unroll
+        for (int i = 0; i < SCAN_PER; ++i) {
+            sg[tid * SCAN_PER + i] = off[i];
+            se[tid * SCAN_PER + i] = tk[i];
+        }
+        // the number of pairs a tile emits is written by the thread that holds its counts
+#pragma unroll
+        for (int i = 0; i < SCAN_PER; ++i) {
+            const uint32_t u = slice0 + tid * SCAN_PER + i;
+            if (u < u1) p.tsel[u] = g[i] + tk[i];
+        }
+        __syncthreads();
+#pragma unroll
         for (int q = 0; q < SCAN_PER; ++q) {
-            const uint32_t u = base + q * SCAN_T + tid;
+            const uint32_t u = slice0 + q * SCAN_T + tid;
             if (u < u1) { p.toff[u] = sg[q * SCAN_T + tid]; p.ttake[u] = se[q * SCAN_T + tid]; }
         }
         return;
     }
-    const int j = blockIdx.y - slices;
-    const uint32_t id = (uint32_t)t * p.n_cf + j;
-    const uint32_t ua = seg_tile0(p, t), ub = seg_tile1(p, t);
+
+    // ---- statistics of (segment t, CF j)
     // sixteen tiles per thread and round, all loads of a round in flight together; fixed summation order
     double sd = 0.0, sj = 0.0;
-    for (uint32_t u0 = ua + tid; u0 < ub; u0 += 16 * SCAN_T) {
+    for (uint32_t v0 = u0 + tid; v0 < u1; v0 += 16 * SCAN_T) {
         double xd[16], xj[16];
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
-            const uint32_t u = u0 + q * SCAN_T;
-            xd[q] = (u < ub) ? p.ssd_t[u] : 0.0;
-            xj[q] = (u < ub) ? p.sss[(size_t)u * p.n_cf + j] : 0.0;
+            const uint32_t u = v0 + q * SCAN_T;
+            xd[q] = (u < u1) ? p.ssd_t[u] : 0.0;
+            xj[q] = (u < u1) ? p.sss[(size_t)u * p.n_cf + j] : 0.0;
         }
 #pragma unroll
         for (int q = 0; q < 16; ++q) { sd += xd[q]; sj += xj[q]; }
     }
-    // every wavefront's sum, then the SCAN_T / 64 of them in order: one barrier, the same order in every run
+    // the entries of the located bin above the threshold (Random-k: and the one at it).  Their order in the gather
+    // lists varies from run to run, so their energies are added as integers: every square, exact in binary64, is
+    // scaled by a power of two that puts the largest of them below 2^50 and truncated, the sum of up to LCAP of them
+    // fits 64 bits and does not depend on the order, and it is off by less than 2^-38 of itself.
+    double ebin = 0.0;
+    if (mode == MODE_GATHER) {
+        double sq[LPER], mx = 0.0;
+#pragma unroll
+        for (int q = 0; q < LPER; ++q) {
+            const bool in = rl[q] && (d[q] > dtau || (p.random && d[q] == dtau));
+            const double dv = p.random ? (double)rv[q] : (double)__uint_as_float(base + d[q]);
+            sq[q] = in ? dv * dv : 0.0;
+            mx = fmax(mx, sq[q]);   // (a NaN square is skipped here and shows in the plain sum below)
+        }
+        mx = wave_max(mx);
+        if (lane == 0) dred[2][wib] = mx;
+        __syncthreads();
+        mx = 0.0;
+#pragma unroll
+        for (int w = 0; w < SCAN_W; ++w) mx = fmax(mx, dred[2][w]);
+        bool finite = true;
+#pragma unroll
+        for (int q = 0; q < LPER; ++q) finite = finite && (sq[q] <= 1.0e300);
+        const bool all_finite = __syncthreads_and(finite ? 1 : 0) != 0;
+        if (!all_finite) {
+            // an infinite or NaN square: the sum is infinite or NaN in any order
+            double s = 0.0;
+#pragma unroll
+            for (int q = 0; q < LPER; ++q) s += sq[q];
+            s = wave_sum(s);
+            if (lane == 0) dred[2][wib] = s;
+            __syncthreads();
+            for (int w = 0; w < SCAN_W; ++w) ebin += dred[2][w];
+        } else if (mx > 0.0) {
+            const int ex = ilogb(mx);                      // 2^ex <= mx < 2^(ex + 1)
+            uint64_t acc = 0;
+#pragma unroll
+            for (int q = 0; q < LPER; ++q) acc += (uint64_t)scalbn(sq[q], 49 - ex);   // < 2^50 each
+            acc = wave_sum(acc);
+            if (lane == 0) ured[wib] = acc;
+            __syncthreads();
+            uint64_t all = 0;
+#pragma unroll
+            for (int w = 0; w < SCAN_W; ++w) all += ured[w];
+            ebin = scalbn((double)all, ex - 49);
+        }
+    } else if (mode == MODE_HIST) {
+        // Top-k only (priorities are distinct): the key-by-key histogram's bins above the threshold, in bin order
+        double s = 0.0;
+        for (uint32_t b = tid; b < NBIN; b += SCAN_T) {
+            const uint32_t cn = (b > dtau && b <= span) ? p.hist2[(size_t)id * NBIN + b] : 0u;
+            const double dv = (double)__uint_as_float(base + b);
+            s += (double)cn * (dv * dv);
+        }
+        s = wave_sum(s);
+        if (lane == 0) dred[2][wib] = s;
+        __syncthreads();
+        for (int w = 0; w < SCAN_W; ++w) ebin += dred[2][w];
+    }
+    // every wavefront's sum, then the SCAN_W of them in order: the same order in every run
     {
         const double wd = wave_sum(sd), wj = wave_sum(sj);
+        __syncthreads();
         if (lane == 0) { dred[0][wib] = wd; dred[1][wib] = wj; }
     }
     __syncthreads();
     if (tid == 0) {
-        const CfState* st = &p.st[id];
         // fourth statistic: the threshold as a magnitude (Top-k) or as a priority (Random-k)
-        const double tau = p.random ? (double)st->tau : (double)__uint_as_float(st->tau);
-        double ss_dense = 0.0, ss_cand = 0.0;
-        for (int w = 0; w < SCAN_T / 64; ++w) { ss_dense += dred[0][w]; ss_cand += dred[1][w]; }
-        // Top-k: the ties all have magnitude tau; Random-k: the count pass has summed the entry at the threshold
-        const double ss_sel = ss_cand + (p.random ? 0.0 : (double)st->need * tau * tau);
+        const double tauv = p.random ? (double)tau : (double)__uint_as_float(tau);
+        double ss_dense = 0.0, ss_above = 0.0;
+        for (int w = 0; w < SCAN_W; ++w) { ss_dense += dred[0][w]; ss_above += dred[1][w]; }
+        // Top-k: the ties all have magnitude tau; Random-k: the entry at the threshold has been summed
+        const double ss_sel = ss_above + ebin + (p.random ? 0.0 : (double)need * tauv * tauv);
         double* o = p.out_stats + (size_t)id * GRAVAC_STATS_PER_CF;
         o[0] = ss_sel;
         o[1] = ss_dense;
         o[2] = (ss_dense == 0.0) ? 1.0 : ss_sel / ss_dense;
-        o[3] = tau;
-        if (id == 0) {
-            if (p.out_count) *p.out_count = p.total_out;
-            p.status->sig_lo = p.sig_lo;  // this call's thresholds can serve as the next call's bounds
-            p.status->sig_hi = p.sig_hi;
-        }
+        o[3] = tauv;
+        if (id == 0 && p.out_count) *p.out_count = p.total_out;
+        if (j != p.commit) { st->tau = tau; st->need = need; st->cnt_gt = cnt_gt; }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // K4: one wavefront per tile emits the tile's share of the committed selection in ascending index
-//     order and zeroes its residual slots
+//     order and zeroes its residual slots.  A sub-tile with a candidate list is emitted from the list;
+//     a sub-tile without one (mostly candidates) is read again, 1024 elements, and its residual rewritten.
 // ---------------------------------------------------------------------------------------------
+struct EmitCtx {
+    uint32_t tau, take, pz;
+    bool put_back;
+    int64_t pos, lim;
+    uint32_t erun;
+};
+
+// One round of up to 64 listed candidates (idx, val), one per lane.
+__device__ __forceinline__ void emit_listed(const Params& p, EmitCtx& x, int32_t idx, float val, bool live)
+{
+    const uint32_t key = cand_key(p, idx, val);
+    const bool gt = live && key > x.tau, eq = live && key == x.tau;
+    const uint64_t me = __ballot(eq);
+    const bool sel = gt || (eq && (x.erun + lanes_below(me)) < x.take);
+    const uint64_t ms = __ballot(sel);
+    if (sel) {
+        const int64_t o = x.pos + lanes_below(ms);
+        if (o < x.lim) {
+            p.out_val[o] = val;
+            if (!p.single) {
+                p.out_idx[o] = idx;
+                if (key < x.pz) p.res[idx] = 0.0f;
+            } else {
+                const int mi = p.map_idx[idx];  // position in the message -> index in the gradient
+                p.out_idx[o] = mi;
+                if (p.restore && (uint64_t)(int64_t)mi < (uint64_t)p.n_restore) p.restore[mi] = 0.0f;
+            }
+        } else {
+            p.status->error = 1;  // cannot happen if the counts are consistent; never write out of range
+        }
+    } else if (x.put_back && live && key >= x.pz) {
+        p.res[idx] = val;
+    }
+    x.pos += __popcll(ms);
+    x.erun += (uint32_t)__popcll(me);
+}
+
 __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
     const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * LWAVES + (threadIdx.x >> 6));
     if (u >= p.n_tiles) return;
-    const TileCands tcs = tile_cands(p, u);
-    const uint32_t cnt = tcs.total();
-    if (cnt == 0) return;
-    const uint32_t take = p.ttake[u];
+    uint32_t cc[SUB];
+    bool any_dense = false;
+#pragma unroll
+    for (int j = 0; j < SUB; ++j) { cc[j] = p.cand_cnt[(size_t)u * SUB + j]; any_dense |= (cc[j] & DENSE_BIT) != 0u; }
     const int t = tile_seg(p, u);
-    const uint32_t tau = p.st[(size_t)t * p.n_cf + p.commit].tau;
-    // The first pass has left +0 in the residual for keys >= pz (not on the full exact route, which has put acc back).
-    // Those entries need no store here if they are selected, and get acc back if they are not, which can only be
-    // when the threshold turned out to lie at or above pz.
-    const uint32_t pz = (p.single || p.seg[t].fail == FAIL_FULL) ? NONE : p.seg[t].pz;
-    const bool put_back = pz != NONE && tau >= pz;
-    if (p.tg[u] == 0 && take == 0 && !put_back) return;
+    EmitCtx x;
+    x.take = p.ttake[u];
+    x.tau = p.st[(size_t)t * p.n_cf + p.commit].tau;
+    // The first pass has left +0 in the residual of its listed sub-tiles for keys >= pz (not on the full exact route,
+    // which has put acc back).  Those entries need no store here if they are selected, and get acc back if they are
+    // not, which can only be when the threshold turned out to lie at or above pz.
+    x.pz = (p.single || p.seg[t].fail == FAIL_FULL) ? NONE : p.seg[t].pz;
+    x.put_back = x.pz != NONE && x.tau >= x.pz;
+    if (p.tsel[u] == 0 && !x.put_back) return;
     const int64_t seg_out = seg_koff(p, t);
-    const int64_t lim = seg_out + (int64_t)seg_k(p, t, p.commit);  // end of this segment's message
-    int64_t pos = seg_out + (int64_t)p.toff[u];
-    uint32_t erun = 0;
+    x.lim = seg_out + (int64_t)seg_k(p, t, p.commit);  // end of this segment's message
+    x.pos = seg_out + (int64_t)p.toff[u];
+    x.erun = 0;
     const float* cv = p.cand_val + (size_t)u * TW;
     const int32_t* ci = p.cand_idx + (size_t)u * TW;
-    // the loads of the next round are issued before this round is worked on (an absent candidate reads slot 0
-    // and is not used), so that a wavefront with a long list does not wait a full round trip per round
-    float vn[4];
-    int32_t in[4];
+    if (!any_dense) {
+        // all sub-tiles listed: their lists are walked as one, 64 candidates per round.  The loads of the next
+        // rounds are issued before this round is worked on (an absent candidate reads slot 0 and is not used), so
+        // that a wavefront with a long list does not wait a full round trip per round
+        TileLists tl;
+        tl.start[0] = 0;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const uint32_t q = r * 64 + lane;
-        const uint32_t sl = (q < cnt) ? tcs.slot(q) : 0u;
-        vn[r] = cv[sl];
-        in[r] = ci[sl];
-    }
-    for (uint32_t b0 = 0; b0 < cnt; b0 += 64 * 4) {
-        float vq[4];
-        int32_t iq[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) { vq[r] = vn[r]; iq[r] = in[r]; }
-        if (b0 + 64 * 4 < cnt) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const uint32_t q = b0 + 64 * 4 + r * 64 + lane;
-                const uint32_t sl = (q < cnt) ? tcs.slot(q) : 0u;
-                vn[r] = cv[sl];
-                in[r] = ci[sl];
-            }
-        }
+        for (int j = 0; j < SUB; ++j) tl.start[j + 1] = tl.start[j] + cc[j];
+        const uint32_t cnt = tl.total();
+        float vn[4];
+        int32_t in[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const bool live = b0 + r * 64 + lane < cnt;
-            const uint32_t key = cand_key(p, iq[r], vq[r]);
-            const bool gt = live && key > tau, eq = live && key == tau;
-            const uint64_t me = __ballot(eq);
-            const bool sel = gt || (eq && (erun + lanes_below(me)) < take);
-            const uint64_t ms = __ballot(sel);
-            if (sel) {
-                const int64_t o = pos + lanes_below(ms);
-                if (o < lim) {
-                    p.out_val[o] = vq[r];
+            const uint32_t q = r * 64 + lane;
+            const uint32_t sl = (q < cnt) ? tl.slot(q) : 0u;
+            vn[r] = cv[sl];
+            in[r] = ci[sl];
+        }
+        for (uint32_t b0 = 0; b0 < cnt; b0 += 64 * 4) {
+            float vq[4];
+            int32_t iq[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) { vq[r] = vn[r]; iq[r] = in[r]; }
+            if (b0 + 64 * 4 < cnt) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t q = b0 + 64 * 4 + r * 64 + lane;
+                    const uint32_t sl = (q < cnt) ? tl.slot(q) : 0u;
+                    vn[r] = cv[sl];
+                    in[r] = ci[sl];
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) emit_listed(p, x, iq[r], vq[r], b0 + r * 64 + lane < cnt);
+        }
+        return;
+    }
+    // sub-tile by sub-tile
+    const int64_t tile0 = seg_begin(p, t) + (int64_t)(u - seg_tile0(p, t)) * TW;
+    for (int j = 0; j < SUB; ++j) {
+        const uint32_t c = p.cand_cnt[(size_t)u * SUB + j];
+        if (!(c & DENSE_BIT)) {
+            for (uint32_t b0 = 0; b0 < c; b0 += 64 * 4) {
+                float vq[4];
+                int32_t iq[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t q = b0 + r * 64 + lane;
+                    vq[r] = cv[j * TS + (q < c ? q : 0u)];
+                    iq[r] = ci[j * TS + (q < c ? q : 0u)];
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) emit_listed(p, x, iq[r], vq[r], b0 + r * 64 + lane < c);
+            }
+            continue;
+        }
+        // a whole, aligned sub-tile that kept acc in the residual (or is the message itself, single-source mode):
+        // four rows of 256 elements, a lane's four consecutive elements at a time
+        const int64_t s0 = tile0 + (int64_t)j * TS;
+        v4f av[ROWS];
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) av[q] = *(const v4f*)(p.acc + s0 + q * ROW + 4 * lane);
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) {
+            const int64_t g = s0 + q * ROW + 4 * lane;
+            const float a[4] = {av[q].x, av[q].y, av[q].z, av[q].w};
+            bool gt[4], eq[4], sel[4];
+            uint32_t ties_below = 0;   // ties in lower lanes of this row
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t key = p.random ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)(g + e)) : key_of(a[e]);
+                gt[e] = key > x.tau;
+                eq[e] = key == x.tau;
+            }
+            uint32_t ties_row = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint64_t m = __ballot(eq[e]);
+                ties_below += lanes_below(m);
+                ties_row += (uint32_t)__popcll(m);
+            }
+            uint32_t er = x.erun + ties_below;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                sel[e] = gt[e] || (eq[e] && er < x.take);
+                er += eq[e] ? 1u : 0u;
+            }
+            uint32_t pre = 0, tot = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint64_t m = __ballot(sel[e]);
+                pre += lanes_below(m);
+                tot += (uint32_t)__popcll(m);
+            }
+            int64_t o = x.pos + pre;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (!sel[e]) continue;
+                if (o < x.lim) {
+                    p.out_val[o] = a[e];
                     if (!p.single) {
-                        p.out_idx[o] = iq[r];
-                        if (key < pz) p.res[iq[r]] = 0.0f;
+                        p.out_idx[o] = (int32_t)(g + e);
                     } else {
-                        const int mi = p.map_idx[iq[r]];  // position in the message -> index in the gradient
+                        const int mi = p.map_idx[g + e];
                         p.out_idx[o] = mi;
                         if (p.restore && (uint64_t)(int64_t)mi < (uint64_t)p.n_restore) p.restore[mi] = 0.0f;
                     }
                 } else {
-                    p.status->error = 1;  // cannot happen if the counts are consistent; never write out of range
+                    p.status->error = 1;
                 }
-            } else if (put_back && live && key >= pz) {
-                p.res[iq[r]] = vq[r];
+                ++o;
             }
-            pos += __popcll(ms);
-            erun += (uint32_t)__popcll(me);
+            if (!p.single) {
+                v4f r;
+                r.x = sel[0] ? 0.0f : a[0]; r.y = sel[1] ? 0.0f : a[1];
+                r.z = sel[2] ? 0.0f : a[2]; r.w = sel[3] ? 0.0f : a[3];
+                *(v4f*)(p.res + g) = r;
+            }
+            x.pos += tot;
+            x.erun += ties_row;
         }
     }
 }
@@ -2198,14 +2391,28 @@ __global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __res
 }
 
 // ---------------------------------------------------------------------------------------------
+// Commit of a message: residual[idx[i]] = +0.0f.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void commit_kernel(const int32_t* __restrict__ idx, int64_t count,
+                                                     float* __restrict__ residual, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+        const int64_t g = idx[i];
+        if ((uint64_t)g < (uint64_t)n) residual[g] = 0.0f;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-    size_t status, tables, tables_bytes, tseg, st, seg, hist1, ovfc, hist2, coarse, list, list_cnt,
-        samp_hist, cand_cnt, tg, te, toff, ttake, ssd, ssd_t, sss, cand_idx, cand_val, total;
+    size_t status, tables, tables_bytes, tseg, st, seg, bnd_lo, bnd_hi, hist1, ovfc, hist2, coarse, list_key, list_tile,
+        list_val, list_cnt, samp_hist, samp_grp, cand_cnt, brk_cnt, ovn, ovs, tg0, tin, toff, ttake, tsel, ssd, ssd_t, sss,
+        cand_idx, cand_val, brk_key, brk_val, total;
 };
 
 // Upper bounds that depend only on (n, n_seg).
@@ -2234,23 +2441,34 @@ Layout make_layout(int64_t n, int n_cf, int n_seg)
     L.tseg = take(sizeof(uint32_t) * nt);
     L.st = take(sizeof(CfState) * sc);
     L.seg = take(sizeof(SegState) * n_seg);
+    L.bnd_lo = take(sizeof(uint32_t) * sc);
+    L.bnd_hi = take(sizeof(uint32_t) * sc);
     L.hist1 = take(sizeof(uint32_t) * sc * REP * NBIN);
     L.ovfc = take(sizeof(uint32_t) * sc * 64 * 32);
     L.hist2 = take(sizeof(uint32_t) * sc * NBIN);
     L.coarse = take(sizeof(uint32_t) * (size_t)n_seg * NBIN);
-    L.list = take(sizeof(uint32_t) * sc * REP * LCAP);
+    L.list_key = take(sizeof(uint32_t) * sc * REP * LCAP);
+    L.list_tile = take(sizeof(uint32_t) * sc * REP * LCAP);
+    L.list_val = take(sizeof(float) * sc * REP * LCAP);
     L.list_cnt = take(sizeof(uint32_t) * sc * REP * 32);
     L.samp_hist = take(sizeof(uint32_t) * nsb * (SBIN / 2));
+    L.samp_grp = take(sizeof(uint32_t) * nsb * SGRP);
     L.cand_cnt = take(sizeof(uint32_t) * nt * SUB);
-    L.tg = take(sizeof(uint32_t) * nt);
-    L.te = take(sizeof(uint32_t) * nt);
+    L.brk_cnt = take(sizeof(uint32_t) * nt * SUB);
+    L.ovn = take(sizeof(uint32_t) * nt * SUB * n_cf);
+    L.ovs = take(sizeof(double) * nt * SUB * n_cf);
+    L.tg0 = take(sizeof(uint32_t) * nt);
+    L.tin = take(sizeof(uint32_t) * nt);
     L.toff = take(sizeof(uint32_t) * nt);
     L.ttake = take(sizeof(uint32_t) * nt);
+    L.tsel = take(sizeof(uint32_t) * nt);
     L.ssd = take(sizeof(double) * nt * SUB);
     L.ssd_t = take(sizeof(double) * nt);
     L.sss = take(sizeof(double) * nt * n_cf);
     L.cand_idx = take(sizeof(int32_t) * nt * TW);
     L.cand_val = take(sizeof(float) * nt * TW);
+    L.brk_key = take(sizeof(uint32_t) * nt * TW);
+    L.brk_val = take(sizeof(float) * nt * TW);
     L.total = at;
     return L;
 }
@@ -2259,7 +2477,7 @@ Layout make_layout(int64_t n, int n_cf, int n_seg)
 uint32_t sample_count(uint64_t nt, double cf_min, double cf_max, bool flat)
 {
     // layerwise: the larger of 32 CF_max and 1/64 of the tensor.  A small sample of a large tensor gives a wide
-    // bracket: many more candidates than k, and bins so coarse that the keys near the bracket's lower end crowd
+    // bracket: many more entries in it than k, and bins so coarse that the keys near the bracket's lower end crowd
     // into a few histogram bins, where their atomics queue up behind each other
     uint64_t target = flat ? (uint64_t)SAMPLE_MAX : (uint64_t)(32.0 * std::ceil(cf_max));
     if (!flat && target < nt / 64) target = nt / 64;
@@ -2267,7 +2485,7 @@ uint32_t sample_count(uint64_t nt, double cf_min, double cf_max, bool flat)
     if (target > (uint64_t)SAMPLE_MAX) target = SAMPLE_MAX;
     if (flat) {
         // The bracket spans about 10 standard deviations of a sampled rank, which is 10 sqrt(k nt / m) of the tensor's
-        // entries for m samples, and every candidate inside it costs the streaming pass a device-wide atomic (about
+        // entries for m samples, and every entry inside it costs the streaming pass a device-wide atomic (about
         // ten per nanosecond all told, and a gradient whose large entries sit together sends them all at once): a
         // selection of many entries from a large tensor (k = nt / cf_min) takes more samples, enough to keep that
         // number near 300,000.
@@ -2281,12 +2499,13 @@ uint32_t sample_count(uint64_t nt, double cf_min, double cf_max, bool flat)
 
 // Pinned host staging for the layerwise tables: a small ring of slots, each followed on its stream by an
 // event, so that a slot is only rewritten after the copy that read it has run.  Host memory only; grown on demand.
+// This ring is the only state the library keeps between calls.
 struct StagingSlot {
     char* mem = nullptr;
     size_t cap = 0;
     hipEvent_t done = nullptr;
     bool pending = false;  // `done` was recorded and not yet waited for
-    bool busy = false;     // being filled by a caller
+    bool busy = false;     // held by a caller (being waited for, filled or copied from)
 };
 constexpr int STAGING_SLOTS = 8;
 StagingSlot g_staging[STAGING_SLOTS];
@@ -2295,26 +2514,35 @@ std::mutex g_staging_mutex;
 
 StagingSlot* staging_acquire(size_t bytes)
 {
-    std::lock_guard<std::mutex> lock(g_staging_mutex);
     StagingSlot* s = nullptr;
-    for (int i = 0; i < STAGING_SLOTS && !s; ++i) {
-        StagingSlot* c = &g_staging[(g_staging_next + i) % STAGING_SLOTS];
-        if (!c->busy) { s = c; g_staging_next = (g_staging_next + i + 1) % STAGING_SLOTS; }
+    {
+        std::lock_guard<std::mutex> lock(g_staging_mutex);
+        for (int i = 0; i < STAGING_SLOTS && !s; ++i) {
+            StagingSlot* c = &g_staging[(g_staging_next + i) % STAGING_SLOTS];
+            if (!c->busy) { s = c; g_staging_next = (g_staging_next + i + 1) % STAGING_SLOTS; }
+        }
+        if (!s) return nullptr;  // more concurrent callers than slots
+        s->busy = true;
     }
-    if (!s) return nullptr;  // more concurrent callers than slots
-    if (!s->done && hipEventCreateWithFlags(&s->done, hipEventDisableTiming) != hipSuccess) return nullptr;
-    if (s->pending) {
-        if (hipEventSynchronize(s->done) != hipSuccess) return nullptr;
-        s->pending = false;
+    // the slot is this caller's now: the waiting and the allocation happen outside the lock
+    bool ok = true;
+    if (!s->done && hipEventCreateWithFlags(&s->done, hipEventDisableTiming) != hipSuccess) { s->done = nullptr; ok = false; }
+    if (ok && s->pending) {
+        if (hipEventSynchronize(s->done) != hipSuccess) ok = false;
+        else s->pending = false;
     }
-    if (s->cap < bytes) {
+    if (ok && s->cap < bytes) {
         if (s->mem) (void)hipHostFree(s->mem);
         s->mem = nullptr; s->cap = 0;
         const size_t want = bytes < 65536 ? 65536 : bytes + bytes / 2;
-        if (hipHostMalloc((void**)&s->mem, want, hipHostMallocDefault) != hipSuccess) { s->mem = nullptr; return nullptr; }
-        s->cap = want;
+        if (hipHostMalloc((void**)&s->mem, want, hipHostMallocDefault) != hipSuccess) { s->mem = nullptr; ok = false; }
+        else s->cap = want;
     }
-    s->busy = true;
+    if (!ok) {
+        std::lock_guard<std::mutex> lock(g_staging_mutex);
+        s->busy = false;
+        return nullptr;
+    }
     return s;
 }
 
@@ -2323,56 +2551,6 @@ void staging_release(StagingSlot* s, bool recorded)
     std::lock_guard<std::mutex> lock(g_staging_mutex);
     s->pending = recorded;
     s->busy = false;
-}
-
-// What this process last asked of each workspace (the signature of the last call issued with it), so that a call
-// that wants to reuse thresholds on a workspace whose last call had another shape, or that this process has never
-// used, can be told apart on the host: it samples like a call without the flag, which costs one pass, whereas on
-// the device the mismatch would only show once the sampling kernel can no longer be launched and every segment
-// would take the exact route.  A hint only: the device still checks the signature the last completed call left in
-// the workspace.  A small ring; a workspace that has dropped out of it samples once.
-struct WorkspaceMemo {
-    const void* ws = nullptr;
-    uint64_t sig = 0;
-};
-constexpr int WS_MEMO = 64;
-WorkspaceMemo g_ws_memo[WS_MEMO];
-int g_ws_memo_next = 0;
-std::mutex g_ws_memo_mutex;
-
-// records sig as the last call on ws; returns whether the call before it on ws had the same signature
-bool ws_memo_exchange(const void* ws, uint64_t sig)
-{
-    std::lock_guard<std::mutex> lock(g_ws_memo_mutex);
-    for (int i = 0; i < WS_MEMO; ++i) {
-        if (g_ws_memo[i].ws == ws) {
-            const bool same = g_ws_memo[i].sig == sig;
-            g_ws_memo[i].sig = sig;
-            return same;
-        }
-    }
-    g_ws_memo[g_ws_memo_next].ws = ws;
-    g_ws_memo[g_ws_memo_next].sig = sig;
-    g_ws_memo_next = (g_ws_memo_next + 1) % WS_MEMO;
-    return false;
-}
-
-std::mutex g_prof_mutex;
-hipEvent_t g_ev[4];
-bool g_ev_ready = false;
-bool g_ev_recorded = false;
-
-// ---------------------------------------------------------------------------------------------
-// Commit of a message: residual[idx[i]] = +0.0f.
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void commit_kernel(const int32_t* __restrict__ idx, int64_t count,
-                                                     float* __restrict__ residual, int64_t n)
-{
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
-        const int64_t g = idx[i];
-        if ((uint64_t)g < (uint64_t)n) residual[g] = 0.0f;
-    }
 }
 
 }  // namespace
@@ -2433,7 +2611,7 @@ int gravac_workspace_bytes(int64_t n, int n_cf, int n_seg, size_t* bytes_out)
 }
 
 // GRAVAC_OK if `stream` is not being captured into a graph, else GRAVAC_ERR_CAPTURE (asked only by calls that cannot
-// be replayed: a replay would copy whatever the staging slot holds by then, or re-record the timing events).
+// be replayed: a replay would copy whatever the staging slot holds by then, or re-record the caller's events).
 static int refuse_capture(hipStream_t stream)
 {
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
@@ -2441,22 +2619,24 @@ static int refuse_capture(hipStream_t stream)
     return cap == hipStreamCaptureStatusNone ? GRAVAC_OK : GRAVAC_ERR_CAPTURE;
 }
 
-// The pipeline behind both entry points.  map_idx == null: error-feedback compression of grad + residual.
+// The pipeline behind all compression entry points.  map_idx == null: error-feedback compression of grad + residual.
 // map_idx != null: single-source mode, the source is grad alone (a message's values), map_idx its indices,
 // restore / n_restore the dense residual that takes the unselected values back (may be null).
+// seed != null: Random-k.  ev != null: the caller's events are recorded around the call and the pass over the gradient.
 static int compress_impl(const float* grad, float* residual, int64_t n, const double* cf_list, int n_cf, int commit,
                          const int64_t* seg_offsets, int n_seg, int32_t* out_idx, float* out_val, int64_t out_capacity,
                          int64_t* out_count, double* out_stats, void* workspace, size_t workspace_bytes, unsigned flags,
                          hipStream_t stream, const int32_t* map_idx, float* restore, int64_t n_restore,
-                         const uint64_t* seed)
+                         const uint64_t* seed, const gravac_profile_events* ev)
 {
     const bool single = map_idx != nullptr;
     const bool random = seed != nullptr;
-    if (random) flags &= ~(unsigned)GRAVAC_FLAG_REUSE_THRESHOLDS;  // the bounds of a random draw need no history
     if (!grad || (!single && !residual) || !cf_list || !out_idx || !out_val || !out_stats) return GRAVAC_ERR_INVALID_ARG;
     if (n <= 0 || n > 2147483647LL || n_cf < 1 || n_cf > MAXCF || commit < 0 || commit >= n_cf) return GRAVAC_ERR_INVALID_ARG;
-    if (((uintptr_t)grad & 15) || ((uintptr_t)residual & 15) || ((uintptr_t)map_idx & 15)) return GRAVAC_ERR_INVALID_ARG;
+    if (((uintptr_t)grad & 3) || ((uintptr_t)residual & 3) || ((uintptr_t)map_idx & 3)) return GRAVAC_ERR_INVALID_ARG;
+    if (flags & ~(unsigned)GRAVAC_FLAG_FORCE_FALLBACK) return GRAVAC_ERR_INVALID_ARG;
     if (n_seg < 0 || (n_seg > 0 && !seg_offsets) || (int64_t)n_seg > n) return GRAVAC_ERR_INVALID_ARG;
+    if (ev && (!ev->call_begin || !ev->pass_begin || !ev->pass_end || !ev->call_end)) return GRAVAC_ERR_INVALID_ARG;
     double cf_max = 1.0, cf_min = cf_list[0];
     for (int j = 0; j < n_cf; ++j) {
         if (!(cf_list[j] >= 1.0) || std::isinf(cf_list[j])) return GRAVAC_ERR_INVALID_ARG;
@@ -2478,6 +2658,9 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     std::memset(&p, 0, sizeof(p));
     p.grad = grad; p.res = residual; p.acc = single ? grad : residual;
     p.map_idx = map_idx; p.restore = restore; p.n_restore = restore ? n_restore : 0; p.single = single ? 1 : 0;
+    // 16-byte accesses need 16-byte aligned buffers; anything else is read and written element by element
+    p.vec_ok = (((uintptr_t)grad & 15) == 0 && ((uintptr_t)residual & 15) == 0 && ((uintptr_t)map_idx & 15) == 0) ? 1 : 0;
+    p.bounds_from = (flags & GRAVAC_FLAG_FORCE_FALLBACK) ? BOUNDS_FORCED : (random ? BOUNDS_RANDOM : BOUNDS_SAMPLED);
     if (random) {
         // the seed goes through SplitMix64 (its first output for that seed) and gives the two 31-bit keys
         uint64_t z = *seed + 0x9E3779B97F4A7C15ull;
@@ -2488,7 +2671,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         p.rk_s0 = (uint32_t)(z & 0x7FFFFFFFull);
         p.rk_s1 = (uint32_t)((z >> 32) & 0x7FFFFFFFull);
     }
-    p.n = n; p.n_seg = ns; p.n_cf = n_cf; p.commit = commit; p.flags = flags;
+    p.n = n; p.n_seg = ns; p.n_cf = n_cf; p.commit = commit;
     p.status = (Status*)(ws + L.status);
     p.segs = (const SegInfo*)(ws + L.tables);
     p.ktab = (const uint32_t*)(ws + L.tables + sizeof(SegInfo) * ns);
@@ -2496,34 +2679,43 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     p.tseg = (uint32_t*)(ws + L.tseg);
     p.st = (CfState*)(ws + L.st);
     p.seg = (SegState*)(ws + L.seg);
+    p.bnd_lo = (uint32_t*)(ws + L.bnd_lo);
+    p.bnd_hi = (uint32_t*)(ws + L.bnd_hi);
     p.hist1 = (uint32_t*)(ws + L.hist1);
     p.ovfc = (uint32_t*)(ws + L.ovfc);
     p.hist2 = (uint32_t*)(ws + L.hist2);
     p.coarse = (uint32_t*)(ws + L.coarse);
-    p.list = (uint32_t*)(ws + L.list);
+    p.list_key = (uint32_t*)(ws + L.list_key);
+    p.list_tile = (uint32_t*)(ws + L.list_tile);
+    p.list_val = (float*)(ws + L.list_val);
     p.list_cnt = (uint32_t*)(ws + L.list_cnt);
     p.samp_hist = (uint32_t*)(ws + L.samp_hist);
+    p.samp_grp = (uint32_t*)(ws + L.samp_grp);
     p.cand_cnt = (uint32_t*)(ws + L.cand_cnt);
-    p.tg = (uint32_t*)(ws + L.tg);
-    p.te = (uint32_t*)(ws + L.te);
+    p.brk_cnt = (uint32_t*)(ws + L.brk_cnt);
+    p.ovn = (uint32_t*)(ws + L.ovn);
+    p.ovs = (double*)(ws + L.ovs);
+    p.tg0 = (uint32_t*)(ws + L.tg0);
+    p.tin = (uint32_t*)(ws + L.tin);
     p.toff = (uint32_t*)(ws + L.toff);
     p.ttake = (uint32_t*)(ws + L.ttake);
+    p.tsel = (uint32_t*)(ws + L.tsel);
     p.ssd = (double*)(ws + L.ssd);
     p.ssd_t = (double*)(ws + L.ssd_t);
     p.sss = (double*)(ws + L.sss);
     p.cand_idx = (int32_t*)(ws + L.cand_idx);
     p.cand_val = (float*)(ws + L.cand_val);
+    p.brk_key = (uint32_t*)(ws + L.brk_key);
+    p.brk_val = (float*)(ws + L.brk_val);
     p.out_idx = out_idx; p.out_val = out_val; p.out_count = out_count; p.out_stats = out_stats;
 
     int64_t total_out = 0;
     uint32_t max_seg_tiles = 1;  // tiles of the largest segment
-    int sample_rounds = 1;  // groups per thread of the sampling kernel
-    uint32_t k_largest = 0;  // over all segments and CFs
+    int sample_rounds = 1;       // groups per thread of the sampling kernel
+    StagingSlot* slot = nullptr;
+    size_t table_bytes = 0;
     if (ns == 1) {
-        for (int j = 0; j < n_cf; ++j) {
-            p.flat_k[j] = (uint32_t)gravac_topk_count(n, cf_list[j]);
-            if (p.flat_k[j] > k_largest) k_largest = p.flat_k[j];
-        }
+        for (int j = 0; j < n_cf; ++j) p.flat_k[j] = (uint32_t)gravac_topk_count(n, cf_list[j]);
         p.flat_samples = sample_count((uint64_t)n, cf_min, cf_max, true);
         p.n_tiles = (uint32_t)((n + TW - 1) / TW);
         max_seg_tiles = p.n_tiles;
@@ -2551,11 +2743,16 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         }
         if (total_out > out_capacity) return GRAVAC_ERR_CAPACITY;
         if (tiles > max_tiles(n, ns) || sblocks > max_sample_blocks(n, ns)) return GRAVAC_ERR_WORKSPACE;
-        if (const int rc = refuse_capture(stream)) return rc;
         p.n_tiles = (uint32_t)tiles;
         p.n_sample_blocks = (uint32_t)sblocks;
-        const size_t bytes = sizeof(SegInfo) * ns + sizeof(uint32_t) * (size_t)ns * n_cf + sizeof(uint32_t) * sblocks;
-        StagingSlot* slot = staging_acquire(bytes);
+    }
+    // nothing has been queued or written up to here; from here on an error return leaves the outputs unspecified
+    if (ns > 1 || ev)
+        if (const int rc = refuse_capture(stream)) return rc;
+    (void)hipGetLastError();  // an error left behind by earlier work of the process is not this call's
+    if (ns > 1) {
+        table_bytes = sizeof(SegInfo) * ns + sizeof(uint32_t) * (size_t)ns * n_cf + sizeof(uint32_t) * p.n_sample_blocks;
+        slot = staging_acquire(table_bytes);
         if (!slot) return GRAVAC_ERR_HIP;
         SegInfo* segs = (SegInfo*)slot->mem;
         uint32_t* ktab = (uint32_t*)(slot->mem + sizeof(SegInfo) * ns);
@@ -2572,87 +2769,62 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
             const uint32_t nb = (g.samp_cnt + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
             for (uint32_t b = 0; b < nb; ++b) sblock_seg[sb_at + b] = (uint32_t)t;
             sb_at += nb;
-            for (int j = 0; j < n_cf; ++j) {
-                ktab[(size_t)t * n_cf + j] = (uint32_t)gravac_topk_count(nt, cf_list[j]);
-                if (ktab[(size_t)t * n_cf + j] > k_largest) k_largest = ktab[(size_t)t * n_cf + j];
-            }
+            for (int j = 0; j < n_cf; ++j) ktab[(size_t)t * n_cf + j] = (uint32_t)gravac_topk_count(nt, cf_list[j]);
             koff += ktab[(size_t)t * n_cf + commit];
         }
-        const bool ok = hipMemcpyAsync(ws + L.tables, slot->mem, bytes, hipMemcpyHostToDevice, stream) == hipSuccess &&
-                        hipEventRecord(slot->done, stream) == hipSuccess;
-        staging_release(slot, ok);
-        if (!ok) return GRAVAC_ERR_HIP;
+    }
+    p.total_out = total_out;
+    if (ev && hipEventRecord((hipEvent_t)ev->call_begin, stream) != hipSuccess) {
+        if (slot) staging_release(slot, false);
+        return GRAVAC_ERR_HIP;
+    }
+    if (slot) {
+        const bool copied = hipMemcpyAsync(ws + L.tables, slot->mem, table_bytes, hipMemcpyHostToDevice, stream) == hipSuccess;
+        bool recorded = copied && hipEventRecord(slot->done, stream) == hipSuccess;
+        // a copy that is queued but not followed by the slot's event: wait for it here, so that the slot is not
+        // rewritten under it
+        if (copied && !recorded) (void)hipStreamSynchronize(stream);
+        staging_release(slot, recorded);
+        if (!copied || !recorded) return GRAVAC_ERR_HIP;
     }
 
-    p.total_out = total_out;
-    {   // signature of the call: FNV-1a over the shape, the k table and the segment table
-        uint64_t h = 1469598103934665603ull;
-        auto mix = [&](uint64_t x) { for (int b = 0; b < 8; ++b) { h ^= (x >> (8 * b)) & 0xFF; h *= 1099511628211ull; } };
-        mix((uint64_t)n); mix((uint64_t)n_cf); mix((uint64_t)ns); mix((single ? 1u : 0u) | (random ? 2u : 0u));
-        for (int j = 0; j < n_cf; ++j) { uint64_t bits; std::memcpy(&bits, &cf_list[j], 8); mix(bits); }
-        if (ns > 1) for (int t = 0; t <= ns; ++t) mix((uint64_t)seg_offsets[t]);
-        if (h == 0) h = 1;  // 0 marks "no completed call"
-        p.sig_lo = (uint32_t)h; p.sig_hi = (uint32_t)(h >> 32);
-        // thresholds can only be reused from a call of the same signature: without one, sample
-        if (!ws_memo_exchange(workspace, h)) flags &= ~(unsigned)GRAVAC_FLAG_REUSE_THRESHOLDS;
-        p.flags = flags;
-    }
-    // the sampling pass: always without reuse, and with it for the sake of a CF that selects very many entries
-    p.have_sample = (p.n_sample_blocks && !random && (!(flags & GRAVAC_FLAG_REUSE_THRESHOLDS) || k_largest > REUSE_MAX_K)) ? 1u : 0u;
     const uint32_t tile_grid = (p.n_tiles + WAVES - 1) / WAVES;
     const uint32_t sub_grid = (p.n_tiles * SUB + WAVES - 1) / WAVES;
     const uint32_t light_grid = (p.n_tiles + LWAVES - 1) / LWAVES;
     const uint32_t scan_slices = (max_seg_tiles + SCAN_SLICE - 1) / SCAN_SLICE;
 
-    const bool prof = (flags & GRAVAC_FLAG_PROFILE) != 0;
-    if (prof && ns == 1)
-        if (const int rc = refuse_capture(stream)) return rc;
-    if (prof) {
-        std::lock_guard<std::mutex> lock(g_prof_mutex);
-        if (!g_ev_ready) {
-            for (int i = 0; i < 4; ++i)
-                if (hipEventCreate(&g_ev[i]) != hipSuccess) return GRAVAC_ERR_HIP;
-            g_ev_ready = true;
-        }
-        (void)hipEventRecord(g_ev[0], stream);
-    }
     static_assert(DENSE_ROUNDS == 4, "forms of the sampling kernel for 1, 2 and 4 groups per thread");
-    if (p.have_sample) {
-        hipLaunchKernelGGL(sample_rounds == 1 ? sample_kernel<1> : sample_rounds == 2 ? sample_kernel<2> : sample_kernel<4>,
-                           dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
-    }
-    hipLaunchKernelGGL(threshold_kernel, dim3(ns), dim3(1024), 0, stream, p);
+    hipLaunchKernelGGL(sample_rounds == 1 ? sample_kernel<1> : sample_rounds == 2 ? sample_kernel<2> : sample_kernel<4>,
+                       dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
+    // few segments: their sample histograms are added up by SGRP workgroups each; many: by one each
+    if (ns <= 32 && p.bounds_from == BOUNDS_SAMPLED)
+        hipLaunchKernelGGL(threshold_kernel<SGRP>, dim3(ns, SGRP), dim3(1024 / SGRP), 0, stream, p);
+    else
+        hipLaunchKernelGGL(threshold_kernel<1>, dim3(ns, 1), dim3(1024), 0, stream, p);
     {
-        // events 1 and 2 take the streaming kernel's own begin and end time stamps
         void (*kern)(Params) = single ? stream_kernel<SM_SINGLE, false>
                                       : (random ? stream_kernel<SM_EF, true> : stream_kernel<SM_EF, false>);
-        if (prof)
-            hipExtLaunchKernelGGL(kern, dim3(sub_grid), dim3(WG), 0, stream, g_ev[1], g_ev[2], 0, p);
+        if (ev)  // the kernel's own begin and end time stamps
+            hipExtLaunchKernelGGL(kern, dim3(sub_grid), dim3(WG), 0, stream, (hipEvent_t)ev->pass_begin,
+                                  (hipEvent_t)ev->pass_end, 0, p);
         else
             hipLaunchKernelGGL(kern, dim3(sub_grid), dim3(WG), 0, stream, p);
     }
     hipLaunchKernelGGL(locate_kernel, dim3((uint32_t)(ns * n_cf)), dim3(256), 0, stream, p);
-    // exact route, taken only by segments whose sampled bound failed (the kernels return at once otherwise)
+    // exact routes, taken only by segments whose bracket failed (the kernels return at once otherwise)
     hipLaunchKernelGGL(coarse_kernel, dim3(tile_grid < XGRID ? tile_grid : XGRID), dim3(WG), 0, stream, p);
     if (random)
         hipLaunchKernelGGL((stream_kernel<SM_EXACT, true>), dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
     else
         hipLaunchKernelGGL((stream_kernel<SM_EXACT, false>), dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
-    // exact resolution on the candidates, then count and emit
-    // the candidate-list kernels with loops over the CFs exist for 1, 2, 4 and MAXCF CFs
+    // the refine kernel loops over the CFs: forms for 1, 2, 4 and MAXCF CFs
     const int ncf_form = n_cf <= 1 ? 0 : n_cf <= 2 ? 1 : n_cf <= 4 ? 2 : 3;
     static_assert(MAXCF >= 4, "forms for 1, 2, 4 and MAXCF CFs");
     void (*const refine_forms[4])(Params) = {refine_kernel<1>, refine_kernel<2>, refine_kernel<4>, refine_kernel<MAXCF>};
-    void (*const count_forms[4])(Params) = {count_kernel<1>, count_kernel<2>, count_kernel<4>, count_kernel<MAXCF>};
     hipLaunchKernelGGL(refine_forms[ncf_form], dim3(light_grid), dim3(LWG), 0, stream, p);
-    hipLaunchKernelGGL(resolve_kernel, dim3(ns * n_cf), dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(count_forms[ncf_form], dim3(light_grid), dim3(LWG), 0, stream, p);
     hipLaunchKernelGGL(scan_kernel, dim3(ns, scan_slices + n_cf), dim3(SCAN_T), 0, stream, p, scan_slices);
     hipLaunchKernelGGL(emit_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
-    if (prof) {
-        (void)hipEventRecord(g_ev[3], stream);
-        g_ev_recorded = true;
-    }
+    if (ev) (void)hipEventRecord((hipEvent_t)ev->call_end, stream);
     if (hipGetLastError() != hipSuccess) return GRAVAC_ERR_HIP;
     return GRAVAC_OK;
 }
@@ -2664,7 +2836,19 @@ int gravac_compress(const float* grad, float* residual, int64_t n, const double*
 {
     if (!residual) return GRAVAC_ERR_INVALID_ARG;
     return compress_impl(grad, residual, n, cf_list, n_cf, commit, seg_offsets, n_seg, out_idx, out_val, out_capacity,
-                         out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v, nullptr, nullptr, 0, nullptr);
+                         out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v, nullptr, nullptr, 0,
+                         nullptr, nullptr);
+}
+
+int gravac_compress_profiled(const float* grad, float* residual, int64_t n, const double* cf_list, int n_cf, int commit,
+                             const int64_t* seg_offsets, int n_seg, int32_t* out_idx, float* out_val,
+                             int64_t out_capacity, int64_t* out_count, double* out_stats, void* workspace,
+                             size_t workspace_bytes, unsigned flags, void* stream_v, const gravac_profile_events* events)
+{
+    if (!residual || !events) return GRAVAC_ERR_INVALID_ARG;
+    return compress_impl(grad, residual, n, cf_list, n_cf, commit, seg_offsets, n_seg, out_idx, out_val, out_capacity,
+                         out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v, nullptr, nullptr, 0,
+                         nullptr, events);
 }
 
 int gravac_randomk_compress(const float* grad, float* residual, int64_t n, const double* cf_list, int n_cf, int commit,
@@ -2675,7 +2859,7 @@ int gravac_randomk_compress(const float* grad, float* residual, int64_t n, const
     if (!residual) return GRAVAC_ERR_INVALID_ARG;
     return compress_impl(grad, residual, n, cf_list, n_cf, commit, seg_offsets, n_seg, out_idx, out_val, out_capacity,
                          out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v, nullptr, nullptr, 0,
-                         &seed);
+                         &seed, nullptr);
 }
 
 int gravac_recompress(const int32_t* idx1, const float* val1, int64_t k1, double cf_rel, const int64_t* seg_counts,
@@ -2697,7 +2881,7 @@ int gravac_recompress(const int32_t* idx1, const float* val1, int64_t k1, double
     }
     return compress_impl(val1, nullptr, k1, &cf_rel, 1, 0, n_seg > 0 ? off.data() : nullptr, n_seg, out_idx, out_val,
                          out_capacity, out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v,
-                         idx1, residual, n, nullptr);
+                         idx1, residual, n, nullptr, nullptr);
 }
 
 int gravac_commit(const int32_t* idx, int64_t count, float* residual, int64_t n, void* stream_v)
@@ -2796,21 +2980,8 @@ int gravac_read_status(const void* workspace, void* stream_v, int32_t* out8)
     if (hipStreamSynchronize(stream) != hipSuccess) return GRAVAC_ERR_HIP;
     Status s;
     if (hipMemcpy(&s, workspace, sizeof(Status), hipMemcpyDeviceToHost) != hipSuccess) return GRAVAC_ERR_HIP;
-    out8[0] = s.any_fail; out8[1] = s.n_fail; out8[2] = s.error; out8[3] = s.n_seg; out8[4] = s.n_light;
+    out8[0] = s.any_fail; out8[1] = s.n_fail; out8[2] = s.error; out8[3] = s.n_seg; out8[4] = s.n_narrow;
     out8[5] = out8[6] = out8[7] = 0;
-    return GRAVAC_OK;
-}
-
-int gravac_profile_read(float* stream_kernel_ms, float* total_ms)
-{
-    std::lock_guard<std::mutex> lock(g_prof_mutex);
-    if (!g_ev_ready || !g_ev_recorded) return GRAVAC_ERR_INVALID_ARG;
-    if (hipEventSynchronize(g_ev[3]) != hipSuccess) return GRAVAC_ERR_HIP;
-    float a = 0.f, b = 0.f;
-    if (hipEventElapsedTime(&a, g_ev[1], g_ev[2]) != hipSuccess) return GRAVAC_ERR_HIP;
-    if (hipEventElapsedTime(&b, g_ev[0], g_ev[3]) != hipSuccess) return GRAVAC_ERR_HIP;
-    if (stream_kernel_ms) *stream_kernel_ms = a;
-    if (total_ms) *total_ms = b;
     return GRAVAC_OK;
 }
 

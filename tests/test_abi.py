@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _declared_functions():
     names = set()
-    for header in ("gravac.h", "gravac_controller.h"):
+    for header in ("gravac.h", "gravac_profile.h", "gravac_controller.h"):
         text = open(os.path.join(ROOT, "include", header)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names |= set(re.findall(r"\b(gravac_[a-z_]+)\s*\(", text))
@@ -76,7 +76,9 @@ def test_compress_rejects_bad_arguments_without_touching_memory():
     assert _call(L, res=0) == E.ERR_INVALID_ARG
     assert _call(L, out_idx=0) == E.ERR_INVALID_ARG
     assert _call(L, out_stats=0) == E.ERR_INVALID_ARG
-    assert _call(L, grad=0x1004) == E.ERR_INVALID_ARG            # not 16-byte aligned
+    assert _call(L, grad=0x1002) == E.ERR_INVALID_ARG            # not at a float boundary
+    assert L.gravac_compress(0x1000, 0x2000, 100, np.asarray([10.0]).ctypes.data_as(ctypes.c_void_p), 1, 0, None, 0,
+                             0x3000, 0x4000, 100, None, 0x5000, 0x10000, 1 << 40, 6, None) == E.ERR_INVALID_ARG  # unknown flag
     assert _call(L, n=0) == E.ERR_INVALID_ARG
     assert _call(L, n=1 << 31) == E.ERR_INVALID_ARG
     assert _call(L, cfs=(0.5,)) == E.ERR_INVALID_ARG
@@ -110,6 +112,6 @@ def test_decompress_rejects_bad_arguments():
 
 def test_strerror():
     assert binding.strerror(0) == "ok"
-    for code in (-1, -2, -3, -4, -5):
+    for code in (-1, -2, -3, -4, -5, -6):
         assert binding.strerror(code) and "unknown" not in binding.strerror(code)
     assert "unknown" in binding.strerror(-99)

@@ -14,7 +14,6 @@ from tests.gpu_util import assert_same, check, gpu_compress, oracle_compress
 pytestmark = pytest.mark.gpu
 
 FB = binding.FLAG_FORCE_FALLBACK
-REUSE = binding.FLAG_REUSE_THRESHOLDS
 
 
 def test_library_is_loaded_from_the_tree():
@@ -145,19 +144,19 @@ def test_full_coarse_bin_is_binned_again_inside_the_bin():
     for cfs, commit in (([100.0], 0), ([100.0, 1000.0], 0), ([100.0, 1000.0], 1), ([10.0, 100.0, 1000.0], 1)):
         gpu, ref = check(g, np.zeros(n, np.float32), cfs, commit=commit, what=f"knee cfs={cfs} commit={commit}",
                          expect_fallback=True)
-        assert gpu[4]["light_fallback_segments"] == 1, gpu[4]
+        assert gpu[4]["narrow_fallback_segments"] == 1, gpu[4]
     # layerwise: only the middle tensor has the knee
     parts = [workloads.normal_gradient(300_001, 1e-3, seed=72), g, workloads.resnet_like_gradient(200_003, seed=73)]
     flat = np.concatenate(parts)
     seg = np.cumsum([0] + [x.size for x in parts]).astype(np.int64)
     gpu, ref = check(flat, np.zeros(flat.size, np.float32), [100.0, 1000.0], commit=0, seg=seg, what="knee, layerwise",
                      expect_fallback=True)
-    assert gpu[4]["fallback_segments"] == 1 and gpu[4]["light_fallback_segments"] == 1, gpu[4]
-    # a second iteration on the same workspace (the histograms of the narrow route are what the next call finds)
+    assert gpu[4]["fallback_segments"] == 1 and gpu[4]["narrow_fallback_segments"] == 1, gpu[4]
+    # more iterations on the same workspace (what the narrow route left there is what the next call finds)
     comp = binding.Compressor(n, [100.0, 1000.0], 0)
     r = np.zeros(n, np.float32)
     for it in range(3):
-        gpu = gpu_compress(g, r, [100.0, 1000.0], 0, comp=comp, flags=binding.FLAG_REUSE_THRESHOLDS if it else 0)
+        gpu = gpu_compress(g, r, [100.0, 1000.0], 0, comp=comp)
         ref = oracle_compress(g, r, [100.0, 1000.0], 0)
         assert gpu[4]["internal_error"] == 0
         assert_same(gpu, ref, f"knee, iteration {it}")
@@ -194,7 +193,7 @@ def test_config2_reduced_five_iterations():
         ref = oracle_compress(g, res_ref, [10.0, 100.0, 1000.0], 1)
         assert_same(gpu, ref, f"config2 it{it}")
         assert gpu[4] == {"any_fallback": 0, "fallback_segments": 0, "internal_error": 0, "segments": 1,
-                          "light_fallback_segments": 0}
+                          "narrow_fallback_segments": 0}
         res_gpu, res_ref = gpu[3], ref[3]
 
 
@@ -382,7 +381,7 @@ def test_compress_then_decompress_eight_workers():
 
 
 # --------------------------------------------------------------------------
-# iterative use: the previous call's thresholds replace the sampling pass
+# iterative use: many calls on one workspace, whose contents are whatever the previous call left
 # --------------------------------------------------------------------------
 
 def _iterate(n, cfs, commit, grads, flags_per_it, seg=None, comp=None, res0=None, carry=True):
@@ -402,37 +401,30 @@ def _iterate(n, cfs, commit, grads, flags_per_it, seg=None, comp=None, res0=None
     return out, comp
 
 
-def test_reuse_thresholds_steady_state():
+def test_iterations_on_one_workspace():
     n = 1_200_003
     grads = [workloads.config3_grad(it, 150_000, n - 150_000) for it in range(5)]
-    # the first calls of an error-feedback run are a transient (the leftover builds up and the threshold climbs):
-    # a prediction may fail there and send the call through the exact route; later calls do not
-    st, _ = _iterate(n, [1000.0], 0, grads, [0] + [REUSE] * 4)
-    assert [s["any_fallback"] for s in st[3:]] == [0, 0]
-    grads = [workloads.config2_grad(it, n) for it in range(4)]
+    st, _ = _iterate(n, [1000.0], 0, grads, [0] * 5)
+    assert [s["any_fallback"] for s in st] == [0] * 5
     # three CFs on the Laplace-with-outliers gradient, residual carried: the thresholds keep moving (one of them sits
     # among a thousand outliers); whichever route each call takes, the results are the oracle's
     grads = [workloads.config2_grad(it, n) for it in range(5)]
-    _iterate(n, [10.0, 100.0, 1000.0], 1, grads, [0] + [REUSE] * 4, res0=workloads.config2_residual0(n))
+    _iterate(n, [10.0, 100.0, 1000.0], 1, grads, [0, 0, FB, 0, 0], res0=workloads.config2_residual0(n))
 
 
-def test_reuse_thresholds_without_history_or_with_another_shape():
+def test_one_workspace_other_cf_list_and_lost_contents():
     n = 500_001
     g = [workloads.normal_gradient(n, 1e-3, seed=s) for s in range(4)]
-    # a workspace this process has not used yet: the call samples, as if the flag were absent
-    st, comp = _iterate(n, [100.0], 0, g[:1], [REUSE])
+    st, comp = _iterate(n, [100.0], 0, g[:1], [0])
     assert st[0]["any_fallback"] == 0
-    # the same workspace, another CF list: no reuse either, the call samples; then the same list again: reuse works
+    # the same workspace with another CF list, then with its contents overwritten: every call starts from scratch
     comp2 = binding.Compressor(n, [50.0], 0)
     comp2.workspace = comp.workspace
-    # (residual not carried here, so that the threshold is the same from call to call)
-    st, _ = _iterate(n, [50.0], 0, g[1:3], [REUSE, REUSE], comp=comp2, carry=False)
+    st, _ = _iterate(n, [50.0], 0, g[1:3], [0, 0], comp=comp2, carry=False)
     assert [s["any_fallback"] for s in st] == [0, 0]
-    # the workspace's contents are lost between two calls of the same shape: only the device can tell (the last
-    # completed call's signature is gone), and every segment takes the exact route; the result is the same
-    comp2.workspace.zero_()
-    st, _ = _iterate(n, [50.0], 0, g[3:], [REUSE], comp=comp2, carry=False)
-    assert st[0]["any_fallback"] == 1 and st[0]["light_fallback_segments"] == 0
+    comp2.workspace.fill_(0xA5)
+    st, _ = _iterate(n, [50.0], 0, g[3:], [0], comp=comp2, carry=False)
+    assert st[0]["any_fallback"] == 0
 
 
 def test_flat_call_with_the_larger_sample_in_blocks_of_two_groups():
@@ -446,40 +438,80 @@ def test_flat_call_with_the_larger_sample_in_blocks_of_two_groups():
     check(g, r, [1.0, 3.0], 0, what="cf 1 committed")
 
 
-def test_reuse_thresholds_with_a_cf_that_selects_millions():
-    """A CF whose k exceeds 2^21 takes its bounds from a sample even when thresholds are reused (the other CF of the
-    call follows the previous call); the results are the oracle's either way."""
+def test_a_cf_that_selects_millions_next_to_a_sparse_one():
+    """CF 4 on 12 M elements (k = 3 M: the sub-tiles are mostly candidates and keep no candidate list) in one call
+    with CF 1000, either of them committed, the residual carried."""
     n = 12_000_000
     grads = [workloads.normal_gradient(n, 1e-3, seed=400 + it) for it in range(3)]
-    _iterate(n, [4.0, 1000.0], 0, grads, [0, REUSE, REUSE])
-    _iterate(n, [4.0, 1000.0], 1, grads, [0, REUSE, REUSE])
-    # without the leftover carried over the thresholds stay where they are: no call leaves the first route
-    st, _ = _iterate(n, [4.0, 1000.0], 0, grads, [0, REUSE, REUSE], carry=False)
+    _iterate(n, [4.0, 1000.0], 0, grads, [0, 0, 0])
+    _iterate(n, [4.0, 1000.0], 1, grads, [0, 0, 0])
+    st, _ = _iterate(n, [4.0, 1000.0], 0, grads, [0, 0, 0], carry=False)
     assert [s["any_fallback"] for s in st] == [0, 0, 0]
 
 
-def test_reuse_thresholds_survives_a_scale_jump():
+def test_scale_jumps_between_iterations():
     n = 800_000
     grads = [workloads.normal_gradient(n, 1e-3, seed=1), workloads.normal_gradient(n, 1e-3, seed=2),
-             workloads.normal_gradient(n, 2e-2, seed=3),      # twenty times larger: the old threshold is far too low
+             workloads.normal_gradient(n, 2e-2, seed=3),      # twenty times larger
              workloads.normal_gradient(n, 2e-2, seed=4),
-             workloads.normal_gradient(n, 1e-4, seed=5)]      # far smaller: fewer than k candidates above the old one
-    st, _ = _iterate(n, [100.0], 0, grads, [0, REUSE, REUSE, REUSE, REUSE], carry=False)
-    assert [s["any_fallback"] for s in st] == [0, 0, 1, 0, 1]
-    # upwards the candidates still hold the k largest (only their histogram is rebuilt); downwards they do not
-    assert [s["light_fallback_segments"] for s in st] == [0, 0, 1, 0, 0]
-    # and with the residual carried (the threshold drifts as the leftover builds up): exact whatever route is taken
-    _iterate(n, [100.0], 0, grads, [0, REUSE, REUSE, REUSE, REUSE])
+             workloads.normal_gradient(n, 1e-4, seed=5)]      # far smaller
+    st, _ = _iterate(n, [100.0], 0, grads, [0] * 5, carry=False)
+    assert [s["any_fallback"] for s in st] == [0] * 5
+    _iterate(n, [100.0], 0, grads, [0] * 5)
 
 
-def test_reuse_thresholds_layerwise():
+def test_iterations_layerwise():
     sizes = [64, 4096, 37, 100_003, 9408, 64, 1000, 40_970, 250_001, 5]
     off = workloads.offsets_of(sizes)
     n = int(off[-1])
     grads = [workloads.normal_gradient(n, 1e-3, seed=80 + it) for it in range(3)]
-    st, _ = _iterate(n, [10.0], 0, grads, [0, REUSE, REUSE], seg=off, carry=False)
+    st, _ = _iterate(n, [10.0], 0, grads, [0, 0, 0], seg=off, carry=False)
     assert st[1]["any_fallback"] == 0 and st[2]["any_fallback"] == 0
-    # a distribution whose threshold sits in a gap (1 % outliers at CF 100) and a carried residual: the
-    # prediction may fail in some tensors; those take the exact route, the result is the same
+    # a distribution whose threshold sits in a gap (1 % outliers at CF 100) and a carried residual
     grads = [workloads.resnet_like_gradient(n, seed=90 + it) for it in range(3)]
-    _iterate(n, [100.0], 0, grads, [0, REUSE, REUSE], seg=off)
+    _iterate(n, [100.0], 0, grads, [0, FB, 0], seg=off)
+
+
+def test_dense_and_sparse_sub_tiles_in_one_call():
+    """VGG16-like mix at CF 10: the conv part's sub-tiles are mostly candidates (read again by the emit step, no
+    candidate list), the fc part's hold a few; the boundary between the parts falls inside a sub-tile."""
+    n_conv, n_fc = 301_111, 2_000_003
+    n = n_conv + n_fc
+    grads = [workloads.config3_grad(it, n_conv, n_fc) for it in range(3)]
+    for cfs, commit in (([10.0], 0), ([10.0, 1000.0], 0), ([10.0, 1000.0], 1), ([2.0], 0)):
+        _iterate(n, cfs, commit, grads, [0, 0, FB])
+
+
+@pytest.mark.parametrize("off_g,off_r", [(1, 1), (2, 3), (3, 0), (0, 2)])
+def test_buffers_at_any_float_boundary(off_g, off_r):
+    """grad and residual that do not start at a multiple of 16 bytes (slices of a larger buffer): same results."""
+    n = 300_007
+    g = workloads.resnet_like_gradient(n, seed=5)
+    r = workloads.normal_gradient(n, 1e-5, seed=6)
+    bg = torch.zeros(n + 8, dtype=torch.float32, device="cuda")
+    br = torch.zeros(n + 8, dtype=torch.float32, device="cuda")
+    for cfs, commit, seg in (([100.0], 0, None), ([2.0, 50.0], 0, None), ([10.0], 0, workloads.offsets_of([1001, 200_000, 99_006]))):
+        gt, rt = bg[off_g:off_g + n], br[off_r:off_r + n]
+        gt.copy_(torch.from_numpy(g))
+        rt.copy_(torch.from_numpy(r))
+        comp = binding.Compressor(n, cfs, commit, seg)
+        idx, val, stats = comp(gt, rt)
+        torch.cuda.synchronize()
+        assert comp.status()["internal_error"] == 0
+        ref = oracle_compress(g, r, cfs, commit, seg)
+        gpu = (idx.cpu().numpy(), val.cpu().numpy(), stats.cpu().numpy(), rt.cpu().numpy())
+        assert_same(gpu, ref, f"offsets {off_g}, {off_r}, cfs {cfs}")
+        # nothing outside the slices was written
+        assert float(bg[:off_g].abs().sum()) == 0.0 and float(bg[off_g + n:].abs().sum()) == 0.0
+        assert float(br[:off_r].abs().sum()) == 0.0 and float(br[off_r + n:].abs().sum()) == 0.0
+
+
+def test_mass_of_equal_values_at_the_threshold_over_several_scan_slices():
+    """More ties at the threshold than a gather list holds, in a gradient long enough for several slices of the
+    scan (4096 tiles each): the located bin is histogrammed key by key and the tiles' ties are counted again."""
+    n = 40_000_000
+    rng = np.random.default_rng(123)
+    g = (rng.integers(-3, 4, n) * 0.25).astype(np.float32)
+    r = np.zeros(n, np.float32)
+    for cf in (3.0, 20.0):
+        check(g, r, [cf], what=f"ties over slices cf={cf}")

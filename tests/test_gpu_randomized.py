@@ -1,5 +1,5 @@
 """Seeded random cases through every mode of the compression call (flat and layerwise, one to four CFs, any
-commit position, sampled bounds, forced exact route, threshold reuse over carried residuals, Top-k and
+commit position, sampled bounds, forced exact route, carried residuals on one workspace, Top-k and
 Random-k), each compared with the CPU oracle element by element.  The cases are drawn from a fixed seed, so
 the test is the same on every run."""
 import os
@@ -63,8 +63,7 @@ def test_random_case(case):
     comp = binding.Compressor(n, cfs, commit, seg)
     res_gpu = _values(rng, n) * np.float32(0.1)
     res_ref = res_gpu.copy()
-    flags_seq = [int(rng.choice([0, binding.FLAG_FORCE_FALLBACK])), binding.FLAG_REUSE_THRESHOLDS,
-                 int(rng.choice([0, binding.FLAG_REUSE_THRESHOLDS]))]
+    flags_seq = [int(rng.choice([0, binding.FLAG_FORCE_FALLBACK])), 0, int(rng.choice([0, binding.FLAG_FORCE_FALLBACK]))]
     for it, flags in enumerate(flags_seq):
         g = _values(rng, n)
         gpu = gpu_compress(g, res_gpu, cfs, commit, seg, flags=flags, comp=comp)

@@ -46,8 +46,7 @@ def test_side_stream_next_to_work_on_the_default_stream():
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("reuse", [False, True])
-def test_flat_compress_and_decompress_replayed_from_a_graph(reuse):
+def test_flat_compress_and_decompress_replayed_from_a_graph():
     """One iteration (compress, then decompress of the fresh message) is captured once and replayed for five
     iterations with new gradients, the residual carried on the device; the program's own eager work and
     synchronisations sit between the replays; every replay is checked against the oracle."""
@@ -58,11 +57,9 @@ def test_flat_compress_and_decompress_replayed_from_a_graph(reuse):
     r = torch.zeros(n, dtype=torch.float32, device="cuda")          # residual, carried from replay to replay
     dense = torch.zeros(n, dtype=torch.float32, device="cuda")
     dws = torch.empty(binding.gravac_decompress_workspace_bytes(1, n), dtype=torch.uint8, device="cuda")
-    flags = binding.FLAG_REUSE_THRESHOLDS if reuse else 0
     grads = [workloads.resnet_like_gradient(n, seed=60 + i) for i in range(6)]
 
-    # one eager iteration first (what a program does before it captures; with reuse it also leaves the history
-    # that the captured call looks for)
+    # one eager iteration first (what a program does before it captures)
     g.copy_(torch.from_numpy(grads[0]))
     comp(g, r)
     binding.gravac_decompress_accumulate(comp.out_idx, comp.out_val, [k], dense, workspace=dws)
@@ -75,7 +72,7 @@ def test_flat_compress_and_decompress_replayed_from_a_graph(reuse):
 
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        comp(g, r, flags=flags)                                      # launches go to the capturing stream
+        comp(g, r)                                                   # launches go to the capturing stream
         binding.gravac_decompress_accumulate(comp.out_idx, comp.out_val, [k], dense, workspace=dws)
     # capturing executes nothing: residual and dense buffer are still those of the eager iteration
     torch.cuda.synchronize()
@@ -105,12 +102,13 @@ def test_calls_that_cannot_be_replayed_refuse_a_capturing_stream():
     g = torch.from_numpy(workloads.normal_gradient(n, 1e-3, seed=5)).cuda()
     r = torch.zeros(n, dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
+    timer = binding.CallTimer()
     graph = torch.cuda.CUDAGraph()
     codes = []
     with torch.cuda.graph(graph):
-        for comp, flags in ((comp_seg, 0), (comp_flat, binding.FLAG_PROFILE)):
+        for comp, tm in ((comp_seg, None), (comp_flat, timer)):
             try:
-                comp(g, r, flags=flags)
+                comp(g, r, timer=tm)
                 codes.append(0)
             except binding.GravacError as e:
                 codes.append(e.code)

@@ -5,12 +5,13 @@ A "step" is one pass of the whole hot path over one gradient:
   gravac_compress   error feedback + Top-k at CF 1000 + residual update + compression gain
   gravac_decompress_accumulate   the worker's fresh message plus seven other workers' messages
                                  (W = 8) scatter-added into one dense buffer
-Workload: the VGG16-shaped gradient (138,357,544 fp32 elements, conv part Normal(0,1e-3), fc part
-Normal(0,1e-5)), residual carried from step to step, all inputs resident in HBM before the timed
-region.  Prints ONE JSON line (see the keys below); everything else goes to stderr.
+Workload of the headline: the VGG16-shaped gradient (138,357,544 fp32 elements, conv part Normal(0,1e-3), fc part
+Normal(0,1e-5)), residual carried from step to step, every step samples its thresholds anew, all inputs resident
+in HBM before the timed region.  The same run then times one compress call of every other configuration (the
+`configs` list of the line).  Prints ONE JSON line; everything else goes to stderr.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--small] [--graph]
-  python bench.py --configs      one compress call of each of the five configurations (a table, not the headline)
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-configs] [--small] [--graph]
+  python bench.py --configs      only the table of all configurations, with more columns (warm and cold)
 """
 import argparse
 import json
@@ -30,26 +31,23 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(n_conv, n_fc):
-    """The oracle, as it stands, timed on a half-size twin of the workload (single thread)."""
+def cpu_baseline(grad_host, cf):
+    """The oracle, as it stands, timed on the workload's first gradient (single thread)."""
     from oracle import oracle
-    from paper_2305_12201_amd import workloads
-    g = workloads.config3_grad(0, n_conv // 2, n_fc // 2)
-    r = np.zeros(g.size, np.float32)
+    r = np.zeros(grad_host.size, np.float32)
     t0 = time.perf_counter()
-    oracle.compress(g, r, [1000.0])
+    oracle.compress(grad_host, r, [cf])
     dt = time.perf_counter() - t0
-    return {"value": 4.0 * g.size / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"one compress call (CF 1000) on a half-size VGG16-shaped gradient, {g.size} elements, "
-                      f"{dt:.1f} s on one host core of {os.cpu_count()}"}
+    return {"value": 4.0 * grad_host.size / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"one compress call (CF {cf:g}) on the full VGG16-shaped gradient of the timed workload, "
+                      f"{grad_host.size} elements, {dt:.1f} s on one host core of {os.cpu_count()}"}
 
 
-def cpu_select_baseline(n_conv, n_fc, k):
+def cpu_select_baseline(grad_host, k):
     """A reasonable multi-core CPU implementation (nth_element on a key copy + OpenMP sweeps), full-size workload.
     Reported as a baseline only; returns None if it cannot be built."""
     import ctypes
     import subprocess
-    from paper_2305_12201_amd import workloads
     here = os.path.dirname(os.path.abspath(__file__))
     src, lib = os.path.join(here, "bench_cpu_select.cpp"), os.path.join(here, "libbench_cpu_select.so")
     try:
@@ -62,7 +60,7 @@ def cpu_select_baseline(n_conv, n_fc, k):
     L.cpu_select_compress.restype = ctypes.c_double
     L.cpu_select_compress.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                                       ctypes.c_void_p, ctypes.POINTER(ctypes.c_int)]
-    g = workloads.config3_grad(0, n_conv, n_fc)
+    g = grad_host
     r = np.zeros(g.size, np.float32)
     oi, ov = np.empty(k, np.int32), np.empty(k, np.float32)
     threads = ctypes.c_int(0)
@@ -71,88 +69,81 @@ def cpu_select_baseline(n_conv, n_fc, k):
     dt = time.perf_counter() - t0
     return {"value": 4.0 * g.size / dt / 1e9, "unit": "GB/s", "cores": int(threads.value),
             "kind": "std::nth_element on a key copy + OpenMP sweeps (baseline only, not the oracle)",
-            "sample": f"one compress call (CF 1000) on the full VGG16-shaped gradient, {g.size} elements, {dt:.2f} s"}
+            "sample": f"one compress call on the full VGG16-shaped gradient, {g.size} elements, {dt:.2f} s"}
 
 
-def time_all_configs(torch, binding, workloads):
-    """Times one compress call of every configuration (third error-feedback iteration on the same gradient,
-    HIP events of the library around the whole call; warm = calls back to back, cold = after a 512 MiB write
-    that flushes the caches; and calls 20 to 39 of a run over three gradients with reused thresholds) and the
-    W = 8 decompression of configuration 5.  Returns a list of records."""
-    flush = torch.empty(512 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")
-    rows = []
+class ConfigTimer:
+    """Times one compress call of a configuration with the caller's events (gravac_compress_profiled): third
+    error-feedback iteration on the same gradient; warm = calls back to back, cold = after a 512 MiB write that
+    flushes the caches."""
 
-    def compress_row(name, g, cfs, commit, seg=None, res0=None, iters=3, reps=8, more=None):
+    def __init__(self, torch, binding):
+        self.torch, self.binding = torch, binding
+        self.flush = torch.empty(512 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")
+        self.timer = binding.CallTimer()
+
+    def row(self, name, g, cfs, commit, seg=None, res0=None, iters=3, reps=6, modes=("cold",)):
+        torch, binding = self.torch, self.binding
         n = g.numel()
         comp = binding.Compressor(n, cfs, commit, seg)
         r = torch.empty(n, dtype=torch.float32, device="cuda")
         rec = {"config": name, "n": n, "cfs": cfs, "commit_cf": cfs[commit], "k": comp.k_total}
-        for cold in (False, True):
+        for mode in modes:
             tot, strm, fb = [], [], 0
             for rep in range(reps):
                 r.zero_() if res0 is None else r.copy_(res0)
                 for it in range(iters):
-                    if cold:
-                        flush.fill_(1.0)
-                    comp(g, r, flags=binding.FLAG_PROFILE)
-                    a, b = binding.gravac_profile_read()
-                    if it == iters - 1 and rep >= 2:
-                        tot.append(b)
-                        strm.append(a)
-                fb |= comp.status()["any_fallback"]
+                    if mode == "cold":
+                        self.flush.fill_(1.0)
+                    comp(g, r, timer=self.timer)
+                    if it == iters - 1 and rep >= 1:
+                        tot.append(self.timer.call_ms())
+                        strm.append(self.timer.pass_ms())
+                st = comp.status()
+                fb |= st["any_fallback"]
+                assert st["internal_error"] == 0, (name, st)
             t = float(np.mean(tot))
-            key = "cold" if cold else "warm"
-            rec[key + "_us"] = t * 1e3
-            rec[key + "_stream_kernel_us"] = float(np.mean(strm)) * 1e3
-            rec[key + "_dense_GBps"] = 4.0 * n / t / 1e6
-            rec[key + "_algorithmic_frac_of_hbm_peak"] = (ALGO_BYTES_PER_ELEMENT * n + 8.0 * comp.k_total) / t / 1e6 / HBM_PEAK_GBS
-            rec[key + "_fallback"] = bool(fb)
-        if more is not None:
-            # a run in steady state: three gradients in turn, the residual carried, thresholds reused from the second
-            # call on; calls 20 to 39, back to back
-            gs = [g] + [torch.from_numpy(more(i)).cuda() for i in (1, 2)]
-            comp = binding.Compressor(n, cfs, commit, seg)
-            r.zero_() if res0 is None else r.copy_(res0)
-            tot, strm, fb = [], [], 0
-            for it in range(40):
-                comp(gs[it % 3], r, flags=binding.FLAG_PROFILE | (binding.FLAG_REUSE_THRESHOLDS if it else 0))
-                a, b = binding.gravac_profile_read()
-                if it >= 20:
-                    tot.append(b)
-                    strm.append(a)
-                    fb += comp.status()["any_fallback"]
-            rec["steady_reuse_us"] = float(np.mean(tot)) * 1e3
-            rec["steady_reuse_stream_kernel_us"] = float(np.mean(strm)) * 1e3
-            rec["steady_reuse_calls_with_fallback"] = int(fb)
-            del gs
+            rec[mode + "_us"] = round(t * 1e3, 1)
+            rec[mode + "_stream_kernel_us"] = round(float(np.mean(strm)) * 1e3, 1)
+            rec[mode + "_dense_GBps"] = round(4.0 * n / t / 1e6, 1)
+            rec[mode + "_call_frac_of_hbm_peak"] = round((ALGO_BYTES_PER_ELEMENT * n + 8.0 * comp.k_total) / t / 1e6 / HBM_PEAK_GBS, 4)
+            rec[mode + "_fallback"] = bool(fb)
         log(json.dumps(rec))
-        rows.append(rec)
+        return rec
 
+
+def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None):
+    """One compress call of every configuration and the W = 8 decompression of configuration 5.  With full_table
+    also warm numbers, the 66 M-element LSTM variant and the direct / second-level comparison of Table III."""
+    ct = ConfigTimer(torch, binding)
+    modes = ("warm", "cold") if full_table else ("cold",)
+    rows = []
     g = torch.from_numpy(workloads.config1(0)).cuda()
-    compress_row("1: N = 2^20, Normal(0, 1e-3)", g, [100.0], 0)
+    rows.append(ct.row("1: N = 2^20, Normal(0, 1e-3)", g, [100.0], 0, modes=modes))
     g = torch.from_numpy(workloads.config2_grad(0)).cuda()
     r0 = torch.from_numpy(workloads.config2_residual0()).cuda()
     for c in range(3):
-        compress_row("2: ResNet101-shaped, three CFs in one call", g, [10.0, 100.0, 1000.0], c, res0=r0,
-                     more=workloads.config2_grad)
-    compress_row("2: ResNet101-shaped, CF 100 alone", g, [100.0], 0, res0=r0, more=workloads.config2_grad)
+        rows.append(ct.row("2: ResNet101-shaped, three CFs in one call", g, [10.0, 100.0, 1000.0], c, res0=r0, modes=modes))
+    rows.append(ct.row("2: ResNet101-shaped, CF 100 alone", g, [100.0], 0, res0=r0, modes=modes))
+    if full_table:
+        rows.append(ct.row("2: ResNet101-shaped, CF 10 alone", g, [10.0], 0, res0=r0, modes=modes))
     del g, r0
-    g = torch.from_numpy(workloads.config3_grad(0)).cuda()
-    compress_row("3: VGG16-shaped", g, [1000.0], 0, more=workloads.config3_grad)
-    compress_row("3: VGG16-shaped, CF 100", g, [100.0], 0, more=workloads.config3_grad)
-    compress_row("3: VGG16-shaped, CF 10", g, [10.0], 0, more=workloads.config3_grad)
+    g = vgg_grad if vgg_grad is not None else torch.from_numpy(workloads.config3_grad(0)).cuda()
+    rows.append(ct.row("3: VGG16-shaped, CF 1000", g, [1000.0], 0, modes=modes))
+    rows.append(ct.row("3: VGG16-shaped, CF 100", g, [100.0], 0, modes=modes))
+    rows.append(ct.row("3: VGG16-shaped, CF 10", g, [10.0], 0, modes=modes))
     del g
     g = torch.from_numpy(workloads.config4_grad(0)).cuda()
     for c in range(2):
-        compress_row("4: LSTM, listed shapes", g, [100.0, 1000.0], c, more=workloads.config4_grad)
+        rows.append(ct.row("4: LSTM, listed shapes", g, [100.0, 1000.0], c, modes=modes))
     del g
-    g = torch.from_numpy(workloads.config4_grad(0, 10000, 1500)).cuda()
-    compress_row("4: LSTM, 66,034,000-element variant", g, [100.0, 1000.0], 0)
-    del g
+    if full_table:
+        g = torch.from_numpy(workloads.config4_grad(0, 10000, 1500)).cuda()
+        rows.append(ct.row("4: LSTM, 66,034,000-element variant", g, [100.0, 1000.0], 0, modes=modes))
+        del g
     g = torch.from_numpy(workloads.config5_worker_grad(0)).cuda()
     seg = workloads.offsets_of(workloads.resnet101_tensor_sizes())
-    compress_row("5: ResNet101-shaped, 314 tensors, layerwise", g, [100.0], 0, seg=seg,
-                 more=lambda i: workloads.config5_worker_grad(i))
+    rows.append(ct.row("5: ResNet101-shaped, 314 tensors, layerwise", g, [100.0], 0, seg=seg, modes=modes))
     # decompression of the eight workers' messages of configuration 5
     n = g.numel()
     comp = binding.Compressor(n, [100.0], 0, seg)
@@ -160,21 +151,22 @@ def time_all_configs(torch, binding, workloads):
     mi = torch.empty(N_WORKERS * k, dtype=torch.int32, device="cuda")
     mv = torch.empty(N_WORKERS * k, dtype=torch.float32, device="cuda")
     for w in range(N_WORKERS):
-        gw = torch.from_numpy(workloads.config5_worker_grad(w)).cuda()
+        gw = g if w == 0 else torch.from_numpy(workloads.config5_worker_grad(w)).cuda()
         r = torch.zeros(n, dtype=torch.float32, device="cuda")
         i, v, _ = comp(gw, r)
         mi[w * k:(w + 1) * k] = i
         mv[w * k:(w + 1) * k] = v
+    del g
     dense = torch.zeros(n, dtype=torch.float32, device="cuda")
     dws = torch.empty(binding.gravac_decompress_workspace_bytes(N_WORKERS, n), dtype=torch.uint8, device="cuda")
-    for ws in (None, dws):
+    for ws in ((None, dws) if full_table else (dws,)):
         rec = {"config": "5: decompress_accumulate, W = 8", "n": n, "pairs": N_WORKERS * k, "workspace": ws is not None}
-        for cold in (False, True):
+        for mode in modes:
             ts = []
-            for rep in range(12):
+            for rep in range(10):
                 dense.zero_()
-                if cold:
-                    flush.fill_(1.0)
+                if mode == "cold":
+                    ct.flush.fill_(1.0)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
                 binding.gravac_decompress_accumulate(mi, mv, [k] * N_WORKERS, dense, workspace=ws)
@@ -183,11 +175,12 @@ def time_all_configs(torch, binding, workloads):
                 if rep >= 2:
                     ts.append(e0.elapsed_time(e1))
             t = float(np.mean(ts))
-            key = "cold" if cold else "warm"
-            rec[key + "_us"] = t * 1e3
-            rec[key + "_algorithmic_GBps"] = (8.0 * n + 8.0 * N_WORKERS * k) / t / 1e6
+            rec[mode + "_us"] = round(t * 1e3, 1)
+            rec[mode + "_algorithmic_GBps"] = round((8.0 * n + 8.0 * N_WORKERS * k) / t / 1e6, 1)
         log(json.dumps(rec))
         rows.append(rec)
+    if not full_table:
+        return rows
     # direct compression at each CF against the second-level Top-k on a level-1 message (the comparison of the
     # paper's Table III, on the synthetic gradients)
     for name, g in (("VGG16-shaped", torch.from_numpy(workloads.config3_grad(0)).cuda()),
@@ -200,9 +193,9 @@ def time_all_configs(torch, binding, workloads):
             ts = []
             for rep in range(8):
                 r.zero_()
-                comp(g, r, flags=binding.FLAG_PROFILE)
-                ts.append(binding.gravac_profile_read()[1])
-            rec[f"direct_cf{int(cf)}_us"] = float(np.mean(ts[2:])) * 1e3
+                comp(g, r, timer=ct.timer)
+                ts.append(ct.timer.call_ms())
+            rec[f"direct_cf{int(cf)}_us"] = round(float(np.mean(ts[2:])) * 1e3, 1)
         comp = binding.Compressor(n, [10.0], 0)
         r.zero_()
         i1, v1, _ = comp(g, r)
@@ -216,10 +209,13 @@ def time_all_configs(torch, binding, workloads):
             st = torch.zeros(1, 4, dtype=torch.float64, device="cuda")
             ts = []
             for rep in range(10):
-                binding.gravac_recompress(i_in, v_in, cf_rel, None, r, out_idx=oi, out_val=ov, out_stats=st,
-                                          workspace=ws, flags=binding.FLAG_PROFILE)
-                ts.append(binding.gravac_profile_read()[1])
-            return oi, ov, float(np.mean(ts[2:])) * 1e3
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                binding.gravac_recompress(i_in, v_in, cf_rel, None, r, out_idx=oi, out_val=ov, out_stats=st, workspace=ws)
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            return oi, ov, round(float(np.mean(ts[2:])) * 1e3, 1)
 
         i2, v2, rec["level2_10_to_100_us"] = level2(i1, v1, 10.0)
         _, _, rec["level2_100_to_1000_us"] = level2(i2, v2, 10.0)
@@ -230,24 +226,34 @@ def time_all_configs(torch, binding, workloads):
     return rows
 
 
+def compact(rows):
+    """The columns of the configuration table that go into the headline line."""
+    out = []
+    for r in rows:
+        if "pairs" in r:
+            out.append({"config": r["config"], "n": r["n"], "pairs": r["pairs"], "cold_us": r["cold_us"],
+                        "algorithmic_GBps": r["cold_algorithmic_GBps"]})
+        elif "cold_us" in r:
+            out.append({"config": r["config"], "n": r["n"], "cfs": r["cfs"], "commit_cf": r["commit_cf"], "k": r["k"],
+                        "cold_us": r["cold_us"], "stream_kernel_us": r["cold_stream_kernel_us"],
+                        "call_frac": r["cold_call_frac_of_hbm_peak"], "fallback": r["cold_fallback"]})
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-reuse", action="store_true", help="sample the thresholds in every call instead of "
-                                                            "reusing the previous call's")
-    ap.add_argument("--transient", type=int, default=12,
-                    help="first steps of the run that sample their thresholds even with reuse (the error-feedback "
-                         "transient, where the threshold climbs quickly)")
+    ap.add_argument("--no-configs", action="store_true", help="leave the table of the other configurations out")
     ap.add_argument("--small", action="store_true", help="1/16-size workload (for a quick functional check)")
     ap.add_argument("--graph", action="store_true",
                     help="also time the same steps replayed from HIP graphs (one graph per gradient of the cycle), "
                          "reported as graph_ms_per_step; the headline value stays the eager one")
     ap.add_argument("--configs", action="store_true",
-                    help="instead of the headline step, time one compress call of every configuration (1-5) and the "
-                         "decompression of configuration 5, print one JSON line {\"configs\": [...]} and exit")
+                    help="instead of the headline step, time one compress call of every configuration (1-5), warm and "
+                         "cold, and the decompression of configuration 5, print one JSON line {\"configs\": [...]} and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 10 plain device copies of the gradient's size (known traffic: 4N read + 4N "
                          "written per copy) so that profiler byte counters can be scaled, then exit")
@@ -267,9 +273,9 @@ def main():
     torch.cuda.set_device(dev)
 
     if args.configs:
-        print(json.dumps({"configs": time_all_configs(torch, binding, workloads), "data": "synthetic",
-                          "note": "times from the library's HIP events around one gravac_compress call, third "
-                                  "error-feedback iteration; algorithmic fraction = (12 N + 8 k) / t / 8 TB/s"}), flush=True)
+        print(json.dumps({"configs": time_all_configs(torch, binding, workloads, True), "data": "synthetic",
+                          "note": "times from the caller's HIP events around one gravac_compress call, third "
+                                  "error-feedback iteration; call fraction = (12 N + 8 k) / t / 8 TB/s"}), flush=True)
         return
 
     n_conv, n_fc = workloads.VGG16_N_CONV, workloads.VGG16_N_FC
@@ -298,10 +304,10 @@ def main():
     dense = torch.zeros(n, dtype=torch.float32, device=dev)
     dws = torch.empty(binding.gravac_decompress_workspace_bytes(N_WORKERS, n), dtype=torch.uint8, device=dev)
 
-    def compress(grad, res, slot, flags=0):
+    def compress(grad, res, slot, timer=None):
         binding.gravac_compress(grad, res, [cf], 0, None, out_idx=msg_idx[slot * k:(slot + 1) * k],
                                 out_val=msg_val[slot * k:(slot + 1) * k], out_count=out_count,
-                                out_stats=out_stats, workspace=comp.workspace, flags=flags)
+                                out_stats=out_stats, workspace=comp.workspace, timer=timer)
 
     for w in range(1, N_WORKERS):                       # peers: their own gradients, residual zero
         g = torch.from_numpy(workloads.config3_grad(100 + w, n_conv, n_fc)).to(dev)
@@ -309,24 +315,17 @@ def main():
         compress(g, scratch, w)
         torch.cuda.synchronize()
         del g, scratch
-    grads = [torch.from_numpy(workloads.config3_grad(i, n_conv, n_fc)).to(dev) for i in range(N_GRADS)]
+    grad0_host = workloads.config3_grad(0, n_conv, n_fc)
+    grads = [torch.from_numpy(grad0_host).to(dev)] + \
+            [torch.from_numpy(workloads.config3_grad(i, n_conv, n_fc)).to(dev) for i in range(1, N_GRADS)]
     counts = [k] * N_WORKERS
 
-    def step(i, flags=0):
-        compress(grads[i % N_GRADS], residual, 0, flags)
+    def step(i):
+        compress(grads[i % N_GRADS], residual, 0)
         binding.gravac_decompress_accumulate(msg_idx, msg_val, counts, dense, workspace=dws)
 
-    # steady-state iterative use: a call reuses the previous call's thresholds.  The first calls of an
-    # error-feedback run are a transient (the leftover builds up, the threshold climbs by more than the reuse
-    # band per step); they sample their thresholds instead, whether they fall into the warm-up or not.
-    REUSE_FLAG = 0 if args.no_reuse else binding.FLAG_REUSE_THRESHOLDS
-    TRANSIENT = args.transient
-
-    def reuse(i):
-        return REUSE_FLAG if i >= TRANSIENT else 0
-
     for i in range(args.warmup):
-        step(i, reuse(i))
+        step(i)
     torch.cuda.synchronize()
     status = binding.gravac_read_status(comp.workspace)
     assert status["internal_error"] == 0, status
@@ -335,11 +334,19 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i, reuse(args.warmup + i))
+        step(args.warmup + i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
     status = binding.gravac_read_status(comp.workspace)
+
+    # ---- the last step's message, checked on the device: k pairs, indices strictly ascending and in range, the
+    #      residual +0 at every index
+    mi, mv = msg_idx[:k], msg_val[:k]
+    verified = bool(int(out_count.item()) == k and status["internal_error"] == 0
+                    and bool((mi[1:] > mi[:-1]).all()) and int(mi[0]) >= 0 and int(mi[-1]) < n
+                    and bool((residual[mi.long()].view(torch.int32) == 0).all())
+                    and bool((mv.abs() >= residual.abs().max()).all()))
 
     # ---- optional: the same K steps replayed from HIP graphs (flat-mode calls are kernel launches only)
     graph_ms = None
@@ -348,7 +355,7 @@ def main():
         for gi in range(N_GRADS):
             gr = torch.cuda.CUDAGraph()
             with torch.cuda.graph(gr):
-                step(gi, REUSE_FLAG)
+                step(gi)
             graphs.append(gr)
         for i in range(5):
             graphs[(args.warmup + args.steps + i) % N_GRADS].replay()
@@ -360,34 +367,31 @@ def main():
         graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
         assert binding.gravac_read_status(comp.workspace)["internal_error"] == 0
 
-    # ---- per-part timing with HIP events on the launch stream (same steps): around the streaming kernel
-    #      and the whole compress call (the library's own events), and around the decompress call, which runs
-    #      right after compress as in a timed step (the library launches on torch's current stream, so torch
-    #      events bracket it)
+    # ---- per-part timing with HIP events on the launch stream (same steps continued): around the streaming kernel
+    #      and the whole compress call (the caller's events, recorded by gravac_compress_profiled), and around the
+    #      decompress call, which runs right after compress as in a timed step (the library launches on torch's
+    #      current stream, so torch events bracket it)
+    timer = binding.CallTimer()
     k_ms, c_ms, d_ms = [], [], []
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for i in range(min(args.steps, 50)):
         j = args.warmup + args.steps + i
-        compress(grads[j % N_GRADS], residual, 0, binding.FLAG_PROFILE | reuse(j))
+        compress(grads[j % N_GRADS], residual, 0, timer=timer)
         ev0.record()
         binding.gravac_decompress_accumulate(msg_idx, msg_val, counts, dense, workspace=dws)
         ev1.record()
-        a, b = binding.gravac_profile_read()
         ev1.synchronize()
-        k_ms.append(a)
-        c_ms.append(b)
+        k_ms.append(timer.pass_ms())
+        c_ms.append(timer.call_ms())
         d_ms.append(ev0.elapsed_time(ev1))
     stream_ms = float(np.mean(k_ms))
     compress_ms = float(np.mean(c_ms))
     decompress_ms = float(np.mean(d_ms))
-    s_ms = []                                     # the same call with the sampling pass instead of reuse
-    for i in range(min(args.steps, 20)):
-        step(args.warmup + 2 * args.steps + i, binding.FLAG_PROFILE)
-        s_ms.append(binding.gravac_profile_read()[1])
-    sampled_ms = float(np.mean(s_ms))
     gain = float(out_stats.cpu()[0, 0, 2])
 
     achieved = ALGO_BYTES_PER_ELEMENT * n / (stream_ms * 1e-3) / 1e9
+    call_bytes = ALGO_BYTES_PER_ELEMENT * n + 8.0 * k
+    call_achieved = call_bytes / (compress_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "stream_kernel_vgg16_traffic.json")
     if os.path.exists(tpath) and not args.small:
@@ -410,29 +414,37 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"VGG16-shaped flat gradient{' (1/16 size: --small)' if args.small else ''}, {n:,} fp32 "
-                               f"elements, CF 1000 (k={k:,}), residual carried, thresholds "
-                               f"{'sampled in every step' if args.no_reuse else 'reused from the previous step'}; "
-                               "step = compress + decompress_accumulate of W=8 messages",
+                               f"elements, CF 1000 (k={k:,}), residual carried over {N_GRADS} gradients in turn, thresholds "
+                               "sampled in every step (all timed steps alike); step = compress + decompress_accumulate "
+                               "of W=8 messages",
                    "n": n, "cf": cf, "k": k, "workers_decompressed": N_WORKERS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "stream_kernel<0, false> (SM_EF, Top-k keys: error feedback + candidate collection)",
-                     "kernel_ms": stream_ms, "algorithmic_bytes_per_launch": ALGO_BYTES_PER_ELEMENT * n},
+                     "kernel": "stream_kernel<0, false, 1> (error feedback + candidate collection, Top-k keys, one CF)",
+                     "kernel_ms": stream_ms, "algorithmic_bytes_per_launch": ALGO_BYTES_PER_ELEMENT * n,
+                     "kernel_frac": achieved / HBM_PEAK_GBS,
+                     "call_frac": call_achieved / HBM_PEAK_GBS, "call_ms": compress_ms,
+                     "call_algorithmic_bytes": call_bytes},
         "compress_only": {"ms": compress_ms, "dense_gradient_GBps": 4.0 * n / (compress_ms * 1e-3) / 1e9,
                           "elements_per_s": n / (compress_ms * 1e-3),
-                          "algorithmic_frac_of_hbm_peak": (ALGO_BYTES_PER_ELEMENT * n + 8.0 * k)
-                          / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "compress_with_sampling_ms": sampled_ms,
+                          "algorithmic_frac_of_hbm_peak": call_achieved / HBM_PEAK_GBS},
         "decompress_ms": decompress_ms,
         "compression_gain": gain,
         "fallback_taken": bool(status["any_fallback"]),
+        "verified": verified,
     }
     if graph_ms is not None:
         out["graph_ms_per_step"] = graph_ms
+    del residual, dense, msg_idx, msg_val
+    if not args.no_configs and not args.small:
+        log("timing one compress call of every configuration ...")
+        vg = grads[0]
+        del grads
+        out["configs"] = compact(time_all_configs(torch, binding, workloads, False, vgg_grad=vg))
     if not args.no_cpu_baseline:
-        log("timing the CPU oracle on a half-size twin ...")
-        out["cpu_baseline"] = cpu_baseline(n_conv, n_fc)
-        sel = cpu_select_baseline(n_conv, n_fc, k)
+        log("timing the CPU oracle on the workload's first gradient ...")
+        out["cpu_baseline"] = cpu_baseline(grad0_host, cf)
+        sel = cpu_select_baseline(grad0_host, k)
         if sel is not None:
             out["cpu_baseline_select"] = sel
     print(json.dumps(out), flush=True)

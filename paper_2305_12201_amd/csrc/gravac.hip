@@ -153,7 +153,8 @@ struct SegInfo {
     uint32_t tile0, tile1;   // tile range
     uint32_t samp0;          // first sample block
     uint32_t samp_cnt;       // samples taken
-    uint32_t pad[6];
+    uint32_t small;          // 1: at most SMALL_MAX elements, handled by one workgroup out of LDS: no tiles, no samples
+    uint32_t pad[5];
 };
 static_assert(sizeof(SegInfo) == 64, "SegInfo layout");
 
@@ -167,6 +168,8 @@ struct Params {
     int single;              // 1 = single-source mode (second-level compression of a message)
     int random;              // 1 = Random-k: the order is that of a keyed priority of the index, not of |acc|
     int vec_ok;              // 1 if every buffer the kernels read or write with 16-byte accesses is aligned to 16 bytes
+    int split;               // 1 if the committed CF is not the lowest of the list: the entries inside the brackets then get a
+                             // list of their own everywhere; 0: a sub-tile's candidate list, where it has one, holds them all
     uint32_t bounds_from;    // BOUNDS_*
     uint32_t rk_s0, rk_s1;   // Random-k: the two 31-bit keys (from the seed)
     int64_t n;
@@ -180,6 +183,8 @@ struct Params {
     const SegInfo* segs;           // [n_seg] built on the host
     const uint32_t* ktab;          // [n_seg][n_cf] built on the host
     const uint32_t* sblock_seg;    // [n_sample_blocks] segment of every sample block, built on the host
+    const uint32_t* small_list;    // [n_small] the segments handled by one workgroup each, built on the host
+    uint32_t n_small;
     uint32_t* tseg;                // [n_tiles] segment of every tile, filled by threshold_kernel
     // the same for one flat tensor
     uint32_t flat_k[MAXCF];
@@ -236,6 +241,7 @@ __device__ __forceinline__ uint32_t seg_tile1(const Params& p, int t) { return i
 __device__ __forceinline__ uint32_t seg_k(const Params& p, int t, int j) { return is_flat(p) ? p.flat_k[j] : p.ktab[t * p.n_cf + j]; }
 __device__ __forceinline__ int64_t seg_koff(const Params& p, int t) { return is_flat(p) ? 0 : p.segs[t].koff; }
 __device__ __forceinline__ int tile_seg(const Params& p, uint32_t u) { return is_flat(p) ? 0 : (int)p.tseg[u]; }
+__device__ __forceinline__ bool seg_small(const Params& p, int t) { return !is_flat(p) && p.segs[t].small != 0u; }
 
 __device__ __forceinline__ uint32_t key_of(float a) { return __float_as_uint(a) & 0x7FFFFFFFu; }
 
@@ -365,6 +371,49 @@ __device__ __forceinline__ TileLists tile_lists(const uint32_t* cnt, uint32_t u)
     return c;
 }
 
+// The entries of a tile that the steps after the pass over the gradient look at one by one: all that lie inside
+// some CF's bracket.  They are the sub-tile's bracket list, or, where the committed CF is the lowest of the call and
+// the sub-tile keeps a candidate list, that list (which then holds them all, next to entries above the brackets).
+struct TileRef {
+    TileLists tl;        // such entries per sub-tile
+    uint32_t main_mask;  // bit j: sub-tile j's are its candidate list
+};
+
+__device__ __forceinline__ TileRef tile_ref(const Params& p, uint32_t u)
+{
+    TileRef r;
+    r.tl.start[0] = 0;
+    r.main_mask = 0;
+#pragma unroll
+    for (int j = 0; j < SUB; ++j) {
+        const uint32_t cc = p.cand_cnt[(size_t)u * SUB + j], bc = p.brk_cnt[(size_t)u * SUB + j];
+        const bool use_main = !p.split && !(cc & DENSE_BIT);
+        if (use_main) r.main_mask |= 1u << j;
+        r.tl.start[j + 1] = r.tl.start[j] + (use_main ? cc : bc);
+    }
+    return r;
+}
+
+// Key (and value: needed for Random-k only, else 0) of the tile's i-th such entry, i < r.tl.total().
+__device__ __forceinline__ void ref_entry(const Params& p, uint32_t u, const TileRef& r, uint32_t i, uint32_t& key, float& val)
+{
+    const uint32_t sl = r.tl.slot(i);
+    const bool from_main = (r.main_mask >> (sl / TS)) & 1u;
+    const size_t at = (size_t)u * TW + sl;
+    if (!p.random) {
+        // the bits of |acc| either way: a candidate's value with its sign, or the key itself
+        const uint32_t* src = from_main ? (const uint32_t*)p.cand_val : p.brk_key;
+        key = src[at] & 0x7FFFFFFFu;
+        val = 0.0f;
+    } else if (from_main) {
+        key = priority_of(p.rk_s0, p.rk_s1, (uint32_t)p.cand_idx[at]);
+        val = p.cand_val[at];
+    } else {
+        key = p.brk_key[at];
+        val = p.brk_val[at];
+    }
+}
+
 // One wavefront finds the bin of a 2048-bin histogram (given as `copies` arrays of NBIN counts that
 // are added up) that holds the k-th largest entry: scanning from the top bin down,
 // above < k <= above + count.  Every lane gets the result; bin == NONE if the histogram holds
@@ -479,6 +528,203 @@ __device__ __forceinline__ void team_locate_bin(const uint32_t* hist, int copies
 }
 
 // ---------------------------------------------------------------------------------------------
+// S: layerwise mode, a tensor of at most SMALL_MAX elements: ONE workgroup does the whole step for it
+// (error feedback, exact selection for every CF, statistics, message, residual) out of LDS, with no
+// sample, no histogram in memory and no tile bookkeeping.  Its place in the message is known on the
+// host (k_t is a function of the tensor's size), so nothing waits for it.  Runs as extra workgroups of
+// the threshold kernel's launch (the workgroups that would otherwise have nothing to do for such a tensor).
+// ---------------------------------------------------------------------------------------------
+constexpr int SMALL_MAX = TW;              // elements
+constexpr int SM_T = 1024;                 // threads
+constexpr int SM_W = SM_T / 64;
+constexpr int SM_PER = SMALL_MAX / SM_T;   // consecutive elements per thread
+static_assert(SM_PER == 8, "see small_at");
+
+struct SmallShared {
+    float a[SMALL_MAX + SMALL_MAX / 32];   // acc, element i at i + i / 32: the runs of eight of 32 neighbouring threads
+                                           // then fall into different banks
+    uint32_t hist[256];
+    uint32_t wg[SM_W], we[SM_W];
+    uint32_t pick[2];
+    uint32_t tau[MAXCF], need[MAXCF];      // per CF, kept by thread 0 for the statistics
+    double ds[MAXCF + 1][SM_W];
+};
+
+__device__ __forceinline__ int small_at(int i) { return i + (i >> 5); }
+
+__device__ __forceinline__ void small_segment(const Params& p, int t, SmallShared& sh)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+    const int64_t s0 = p.segs[t].begin;
+    const int nt = (int)(p.segs[t].end - s0);
+    const int64_t koff = p.segs[t].koff;
+    // acc into LDS, coalesced: all loads first and without branches around them (an element past the end reads the
+    // last one instead and is not stored), so that they are in flight together
+    {
+        float gv[SM_PER], rv[SM_PER];
+#pragma unroll
+        for (int q = 0; q < SM_PER; ++q) {
+            const int i = q * SM_T + tid;
+            gv[q] = p.grad[s0 + (i < nt ? i : nt - 1)];
+            rv[q] = 0.0f;
+        }
+        if (!p.single) {
+#pragma unroll
+            for (int q = 0; q < SM_PER; ++q) {
+                const int i = q * SM_T + tid;
+                rv[q] = p.res[s0 + (i < nt ? i : nt - 1)];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < SM_PER; ++q) {
+            const int i = q * SM_T + tid;
+            if (i < nt) sh.a[small_at(i)] = p.single ? gv[q] : rv[q] + gv[q];
+        }
+    }
+    __syncthreads();
+    // this thread's run: elements SM_PER tid .. SM_PER tid + nv - 1
+    const int first = SM_PER * tid;
+    const int nv = nt - first < 0 ? 0 : (nt - first > SM_PER ? SM_PER : nt - first);
+    // (the keys stay in registers; the values are read from LDS again where they are needed)
+    uint32_t key[SM_PER];
+    double ssd = 0.0;
+#pragma unroll
+    for (int e = 0; e < SM_PER; ++e) {
+        const float v = e < nv ? sh.a[small_at(first + e)] : 0.0f;
+        key[e] = p.random ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)(s0 + first + e)) : key_of(v);
+        const double d = (double)v;
+        ssd += d * d;
+    }
+    {
+        const double w = wave_sum(ssd);
+        if (lane == 0) sh.ds[MAXCF][wib] = w;
+    }
+    uint32_t tau_c = 0, need_c = 0;
+    for (int j = 0; j < p.n_cf; ++j) {
+        // the k-th largest key by four passes over the key's digits (8, 8, 8 and 7 bits from the top), each a
+        // 256-bin histogram of the keys that agree with the digits found so far
+        uint32_t want = p.ktab[(size_t)t * p.n_cf + j];
+        uint32_t prefix = 0, mask = 0;
+#pragma unroll 1
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = pass == 0 ? 23 : pass == 1 ? 15 : pass == 2 ? 7 : 0;
+            const uint32_t dm = pass == 3 ? 127u : 255u;
+            if (tid < 256) sh.hist[tid] = 0;
+            __syncthreads();
+            // (magnitudes crowd into a few digit values: a thread adds runs of equal digits at once)
+            uint32_t cur = NONE, run = 0;
+#pragma unroll
+            for (int e = 0; e < SM_PER; ++e) {
+                if (e < nv && (key[e] & mask) == prefix) {
+                    const uint32_t dg = (key[e] >> shift) & dm;
+                    if (dg != cur) {
+                        if (run) atomicAdd(&sh.hist[cur], run);
+                        cur = dg; run = 0;
+                    }
+                    ++run;
+                }
+            }
+            if (run) atomicAdd(&sh.hist[cur], run);
+            __syncthreads();
+            if (wib == 0) {
+                // lane l owns digits 4 l .. 4 l + 3; from the top: above < want <= above + count
+                const uint32_t h0 = sh.hist[4 * lane], h1 = sh.hist[4 * lane + 1], h2 = sh.hist[4 * lane + 2], h3 = sh.hist[4 * lane + 3];
+                const uint32_t mine = h0 + h1 + h2 + h3;
+                const uint32_t incl = wave_scan(mine);
+                const uint32_t total = __shfl(incl, 63, 64);
+                uint32_t ab = total - incl;
+                const uint32_t hh[4] = {h0, h1, h2, h3};
+#pragma unroll
+                for (int q = 3; q >= 0; --q) {
+                    if (ab < want && ab + hh[q] >= want) { sh.pick[0] = 4u * lane + q; sh.pick[1] = ab; }
+                    ab += hh[q];
+                }
+            }
+            __syncthreads();
+            prefix |= sh.pick[0] << shift;
+            mask |= dm << shift;
+            want -= sh.pick[1];
+        }
+        if (tid == 0) { sh.tau[j] = prefix; sh.need[j] = want; }   // want: the keys equal to tau that are selected
+        if (j == p.commit) { tau_c = prefix; need_c = want; }
+        // energy above the threshold (Random-k: and of the entry at it, which has no particular magnitude)
+        double s = 0.0;
+#pragma unroll
+        for (int e = 0; e < SM_PER; ++e) {
+            if (e < nv && (key[e] > prefix || (p.random && key[e] == prefix))) {
+                const double d = (double)sh.a[small_at(first + e)];
+                s += d * d;
+            }
+        }
+        s = wave_sum(s);
+        if (lane == 0) sh.ds[j][wib] = s;
+    }
+    // the committed CF's selection, in index order: a thread's run is consecutive, so the counts of the threads
+    // before it give its place
+    uint32_t g = 0, eq = 0;
+#pragma unroll
+    for (int e = 0; e < SM_PER; ++e) {
+        g += (e < nv && key[e] > tau_c);
+        eq += (e < nv && key[e] == tau_c);
+    }
+    const uint32_t ig = wave_scan(g), ie = wave_scan(eq);
+    if (lane == 63) { sh.wg[wib] = ig; sh.we[wib] = ie; }
+    __syncthreads();
+    uint32_t run_g = ig - g, run_e = ie - eq;
+#pragma unroll
+    for (int w = 0; w < SM_W; ++w)
+        if (w < wib) { run_g += sh.wg[w]; run_e += sh.we[w]; }
+    const uint32_t ties_before = run_e < need_c ? run_e : need_c;
+    int64_t o = koff + run_g + ties_before;
+    const int64_t lim = koff + (int64_t)p.ktab[(size_t)t * p.n_cf + p.commit];
+    uint32_t left = need_c - ties_before;
+#pragma unroll
+    for (int e = 0; e < SM_PER; ++e) {
+        if (e >= nv) continue;
+        bool sel = key[e] > tau_c;
+        if (key[e] == tau_c && left > 0) { sel = true; --left; }
+        if (sel) {
+            if (o < lim) {   // (always, if the counts are consistent; never write out of range)
+                p.out_val[o] = sh.a[small_at(first + e)];
+                p.out_idx[o] = p.single ? p.map_idx[s0 + first + e] : (int32_t)(s0 + first + e);
+            }
+            ++o;
+            sh.a[small_at(first + e)] = 0.0f;
+        }
+    }
+    if (tid == 0) {
+        // statistics: every wavefront's sums in order
+        double ss_dense = 0.0;
+        for (int w = 0; w < SM_W; ++w) ss_dense += sh.ds[MAXCF][w];
+        for (int j = 0; j < p.n_cf; ++j) {
+            double s = 0.0;
+            for (int w = 0; w < SM_W; ++w) s += sh.ds[j][w];
+            const double tauv = p.random ? (double)sh.tau[j] : (double)__uint_as_float(sh.tau[j]);
+            if (!p.random) s += (double)sh.need[j] * tauv * tauv;
+            double* os = p.out_stats + ((size_t)t * p.n_cf + j) * GRAVAC_STATS_PER_CF;
+            os[0] = s;
+            os[1] = ss_dense;
+            os[2] = (ss_dense == 0.0) ? 1.0 : s / ss_dense;
+            os[3] = tauv;
+        }
+    }
+    __syncthreads();
+    // the new residual (acc with the selection zeroed), coalesced; single-source mode: into the dense residual
+#pragma unroll 4
+    for (int q = 0; q < SM_PER; ++q) {
+        const int i = q * SM_T + tid;
+        if (i >= nt) continue;
+        const float r = sh.a[small_at(i)];
+        if (!p.single) {
+            p.res[s0 + i] = r;
+        } else if (p.restore) {
+            const int mi = p.map_idx[s0 + i];
+            if ((uint64_t)(int64_t)mi < (uint64_t)p.n_restore) p.restore[mi] = r;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // K0a: sample acc = residual + grad at stratified positions; each workgroup histograms its samples in
 // LDS (SBIN bins of 2^17 keys, see sample_bin) and stores the counts as 16-bit numbers, and the
 // counts per group of SBIN / SGRP bins beside them.  The same launch clears what the later kernels
@@ -504,10 +750,6 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
         for (uint32_t i = lb * 256 + tid; i < NBIN / 4; i += nbk * 256) cs[i] = z;
         for (uint32_t i = lb * 256 + tid; i < (uint32_t)p.n_cf * 64; i += nbk * 256) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
         for (uint32_t i = lb * 256 + tid; i < (uint32_t)p.n_cf * REP; i += nbk * 256) p.list_cnt[((size_t)t * p.n_cf * REP + i) * 32] = 0;
-        if (b == 0 && tid == 0) {
-            p.status->any_fail = 0; p.status->n_fail = 0; p.status->error = 0; p.status->n_seg = p.n_seg;
-            p.status->n_narrow = 0;
-        }
     }
     if (p.bounds_from != BOUNDS_SAMPLED) return;
     const int64_t s0 = seg_begin(p, t);
@@ -591,7 +833,7 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
 // bracket ends that fall into its bins, so that no workgroup waits for another.  The kernels that
 // use the brackets derive the histogram shift and the rest from them (bracket_bins).
 // ---------------------------------------------------------------------------------------------
-template <int G>
+template <int G, bool SMALL>  // SMALL: the workgroups of tensors of at most SMALL_MAX elements do the whole step for them
 __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
 {
     constexpr int T = 1024 / G;          // thread i owns the bins 4 (y T + i) .. + 3: two words of every block's histogram
@@ -600,6 +842,19 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
     __shared__ uint32_t wtot[NW], gab[NW], gto[NW];
     __shared__ uint32_t rank_lo[MAXCF], rank_hi[MAXCF];
     const int t = blockIdx.x, y = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+    if (t == 0 && y == 0 && tid == 0) {
+        p.status->any_fail = 0; p.status->n_fail = 0; p.status->error = 0; p.status->n_seg = p.n_seg;
+        p.status->n_narrow = 0;
+        if (p.out_count) *p.out_count = p.total_out;
+    }
+    if constexpr (SMALL) {
+        static_assert(G == 1 && SM_T == 1024, "the small tensors' workgroups are this kernel's");
+        __shared__ SmallShared small;
+        if (seg_small(p, t)) {
+            small_segment(p, t, small);
+            return;
+        }
+    }
     const uint32_t S = is_flat(p) ? p.flat_samples : p.segs[t].samp_cnt;
     const uint32_t sb0 = is_flat(p) ? 0u : p.segs[t].samp0;
     const uint32_t nb = is_flat(p) ? p.n_sample_blocks : (S + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
@@ -717,13 +972,15 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
 //     SM_EXACT (exact route, failed segments only): read acc from residual; the brackets come from the
 //     coarse histogram.  Both collect the lists of the sub-tile in index order.
 // ---------------------------------------------------------------------------------------------
+template <int NCF>  // compiled for calls with up to NCF CFs: the loops over the CFs are unrolled
 struct SubCtx {
     uint32_t lo_min, lo_c, pz;
-    uint32_t lo[MAXCF];
-    uint32_t sh[MAXCF];
-    uint32_t top[MAXCF];
-    uint32_t ovn[MAXCF];   // entries above CF j's bracket ...
-    double ovs[MAXCF];     // ... and their sum of acc^2
+    uint32_t lo[NCF];
+    uint32_t sh[NCF];
+    uint32_t top[NCF];
+    uint32_t ovn[NCF];     // entries above CF j's bracket ...
+    double ovs[NCF];       // ... and their sum of acc^2
+    bool split;            // the entries inside the brackets get a list of their own in every sub-tile
     uint32_t* h1;   // this wavefront's copy of the bracket histograms of the tile's segment (CF stride REP*NBIN)
     int32_t* cidx;  // candidate-list slots of this sub-tile
     float* cval;
@@ -738,12 +995,13 @@ struct SubCtx {
 
 // What one entry with key >= lo_min adds: per CF whose bracket starts at or below it, a count above the bracket or
 // a histogram update inside it.  Returns whether it lies inside some CF's bracket.
-__device__ __forceinline__ bool bracket_count(SubCtx& c, uint32_t key, float a)
+template <int NCF>
+__device__ __forceinline__ bool bracket_count(SubCtx<NCF>& c, uint32_t key, float a)
 {
     bool inside = false;
 #pragma unroll
-    for (int j = 0; j < MAXCF; ++j) {
-        if (j < c.ncf && key >= c.lo[j]) {
+    for (int j = 0; j < NCF; ++j) {
+        if ((j == 0 || j < c.ncf) && key >= c.lo[j]) {
             if (key >= c.top[j]) {
                 const double d = (double)a;
                 c.ovn[j]++;
@@ -776,8 +1034,8 @@ __device__ __forceinline__ void st_stream(v4f v, v4f* q)
 }
 
 // The ordering keys of one lane's four consecutive elements a[0..3] at global index g.
-template <bool RND>
-__device__ __forceinline__ void keys_of_row(const SubCtx& c, const float a[4], int64_t g, uint32_t key[4])
+template <bool RND, int NCF>
+__device__ __forceinline__ void keys_of_row(const SubCtx<NCF>& c, const float a[4], int64_t g, uint32_t key[4])
 {
 #pragma unroll
     for (int e = 0; e < 4; ++e) key[e] = RND ? priority_of(c.s0, c.s1, (uint32_t)(g + e)) : key_of(a[e]);
@@ -785,8 +1043,8 @@ __device__ __forceinline__ void keys_of_row(const SubCtx& c, const float a[4], i
 
 // One lane's four consecutive elements a[0..3] with keys key[0..3] at global index g; vm = validity bits;
 // listed = whether the sub-tile keeps a candidate list (the same for all lanes).
-template <bool SSD, bool RND>
-__device__ __forceinline__ void consume(SubCtx& c, const float a[4], const uint32_t key[4], int64_t g, unsigned vm, bool listed)
+template <bool SSD, bool RND, int NCF>
+__device__ __forceinline__ void consume(SubCtx<NCF>& c, const float a[4], const uint32_t key[4], int64_t g, unsigned vm, bool listed)
 {
     bool f[4];
 #pragma unroll
@@ -824,7 +1082,8 @@ __device__ __forceinline__ void consume(SubCtx& c, const float a[4], const uint3
         }
         c.run += tot;
     }
-    if (__ballot(fb[0] | fb[1] | fb[2] | fb[3]) != 0ull) {
+    // the entries inside the brackets: a list of their own, unless the candidate list holds them all
+    if ((c.split || !listed) && __ballot(fb[0] | fb[1] | fb[2] | fb[3]) != 0ull) {
         uint32_t pre = 0, tot = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -908,7 +1167,7 @@ struct ExactBounds {
 };
 
 // One sub-tile v, by one wavefront.
-template <int M, bool RND>
+template <int M, bool RND, int NCF>
 __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int lane, ExactBounds* xb)
 {
     constexpr bool EF = (M != SM_EXACT);  // a first pass: sums acc^2, takes the brackets from the threshold kernel
@@ -927,18 +1186,19 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
         return;
     }
 
-    SubCtx c;
+    SubCtx<NCF> c;
     c.ncf = p.n_cf;
+    c.split = p.split != 0;
     c.s0 = p.rk_s0; c.s1 = p.rk_s1;
     c.lo_min = NONE; c.lo_c = NONE; c.pz = NONE;
 #pragma unroll
-    for (int j = 0; j < MAXCF; ++j) {
+    for (int j = 0; j < NCF; ++j) {
         c.ovn[j] = 0; c.ovs[j] = 0.0;
         c.lo[j] = NONE; c.sh[j] = 0; c.top[j] = KEY_END;
     }
     if (EF) {
 #pragma unroll
-        for (int j = 0; j < MAXCF; ++j) {
+        for (int j = 0; j < NCF; ++j) {
             if (j < p.n_cf) {
                 c.lo[j] = p.bnd_lo[(size_t)t * p.n_cf + j];
                 bracket_bins(c.lo[j], p.bnd_hi[(size_t)t * p.n_cf + j], c.sh[j], c.top[j]);
@@ -949,6 +1209,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                 }
             }
         }
+        if (!c.split) c.lo_c = c.lo_min;  // the candidate list takes every entry that concerns some CF
     } else {
         const bool first = (v == seg_tile0(p, t) * SUB);
         if (xb->t != t) {
@@ -981,9 +1242,10 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                 }
             }
         }
-        c.lo_min = xb->lo_min; c.lo_c = xb->lo_c;
+        c.lo_min = xb->lo_min; c.lo_c = c.split ? xb->lo_c : xb->lo_min;
+        static_assert(EF || NCF == MAXCF, "the exact routes are compiled for any number of CFs");
 #pragma unroll
-        for (int j = 0; j < MAXCF; ++j) {
+        for (int j = 0; j < NCF; ++j) {
             if (j < p.n_cf) {
                 c.lo[j] = xb->lo[j];
                 c.sh[j] = xb->sh[j];
@@ -1020,21 +1282,22 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
         // An entry counts for CF j if it lies inside the bracket the lists were collected with (below top_j: what
         // lies above has been counted as above the bracket already) and from the located bin's first key on; past
         // that bin's last key it adds to the count above the new, narrower bracket.
-        const TileLists tl = tile_lists(p.brk_cnt, u);
-        const uint32_t cnt = tl.total();
-        const uint32_t* bk = p.brk_key + (size_t)u * TW;
+        const TileRef tr = tile_ref(p, u);
+        const uint32_t cnt = tr.tl.total();
         for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
             uint32_t kq[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const uint32_t i = i0 + q * 64 + lane;
-                kq[q] = bk[(i < cnt) ? tl.slot(i) : 0u];
+                float unused;
+                kq[q] = 0;
+                if (i < cnt) ref_entry(p, u, tr, i, kq[q], unused);
             }
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 if (i0 + q * 64 + lane >= cnt) continue;
 #pragma unroll
-                for (int j = 0; j < MAXCF; ++j) {
+                for (int j = 0; j < NCF; ++j) {
                     if (j < c.ncf && kq[q] >= c.lo[j] && kq[q] < xb->top[j]) {
                         if (kq[q] >= c.top[j]) c.ovn[j]++;
                         else atomicAdd(&c.h1[j * REP * NBIN + ((kq[q] - c.lo[j]) >> c.sh[j])], 1u);
@@ -1043,7 +1306,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
             }
         }
 #pragma unroll
-        for (int j = 0; j < MAXCF; ++j) {
+        for (int j = 0; j < NCF; ++j) {
             if (j < p.n_cf) {
                 const uint32_t o = wave_sum(c.ovn[j]);
                 if (lane == 0 && o) atomicAdd(&p.ovfc[(((size_t)t * p.n_cf + j) * 64 + (u & 63)) * 32], o);
@@ -1065,7 +1328,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
         for (int q = 0; q < ROWS; ++q) {
             row_finish<M>(p, x[q], y[q], m[q], a[q]);
             uint32_t key[4];
-            keys_of_row<RND>(c, a[q], s0 + q * ROW + 4 * lane, key);
+            keys_of_row<RND, NCF>(c, a[q], s0 + q * ROW + 4 * lane, key);
 #pragma unroll
             for (int e = 0; e < 4; ++e) nc += (uint32_t)__popcll(__ballot(key[e] >= c.lo_c));
         }
@@ -1074,7 +1337,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
         for (int q = 0; q < ROWS; ++q) {
             const int64_t g = s0 + q * ROW + 4 * lane;
             uint32_t key[4];
-            keys_of_row<RND>(c, a[q], g, key);
+            keys_of_row<RND, NCF>(c, a[q], g, key);
             if (M == SM_EF) {
                 // acc goes back into the residual; in a sub-tile that keeps a candidate list an entry above the committed
                 // CF's bracket leaves +0 there already: it is selected unless the bracket fails (the list keeps its value,
@@ -1086,7 +1349,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                 o.w = (!dense && key[3] >= c.pz) ? 0.0f : a[q][3];
                 st_stream(o, (v4f*)(p.res + g));
             }
-            consume<EF, RND>(c, a[q], key, g, 0xFu, !dense);
+            consume<EF, RND, NCF>(c, a[q], key, g, 0xFu, !dense);
         }
     } else {
         // a ragged or unaligned sub-tile: element-wise, guarded; rows start at a multiple of 4 elements
@@ -1104,18 +1367,18 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                 }
             }
             uint32_t key[4];
-            keys_of_row<RND>(c, a, g, key);
+            keys_of_row<RND, NCF>(c, a, g, key);
             if (M == SM_EF) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     if ((vm >> e) & 1u) p.res[g + e] = key[e] >= c.pz ? 0.0f : a[e];
             }
-            consume<EF, RND>(c, a, key, g, vm, true);
+            consume<EF, RND, NCF>(c, a, key, g, vm, true);
         }
     }
 
 #pragma unroll
-    for (int j = 0; j < MAXCF; ++j) {
+    for (int j = 0; j < NCF; ++j) {
         if (j < p.n_cf) {
             const uint32_t o = wave_sum(c.ovn[j]);
             const double s = wave_sum(c.ovs[j]);
@@ -1135,13 +1398,13 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
 
 // First pass (SM_EF, SM_SINGLE): one sub-tile per wavefront, one launch covers the whole gradient.
 // SM_EXACT: a fixed number of wavefronts walks over all tiles (only those of failed segments do any work).
-template <int M, bool RND>
+template <int M, bool RND, int NCF>
 __global__ __launch_bounds__(WG) void stream_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
     const uint32_t w = __builtin_amdgcn_readfirstlane(blockIdx.x * WAVES + (threadIdx.x >> 6));
-    if (M != SM_EXACT) {
-        stream_subtile<M, RND>(p, w, lane, nullptr);
+    if constexpr (M != SM_EXACT) {
+        stream_subtile<M, RND, NCF>(p, w, lane, nullptr);
     } else {
         if (p.status->any_fail == 0) return;
         ExactBounds xb;
@@ -1152,7 +1415,7 @@ __global__ __launch_bounds__(WG) void stream_kernel(Params p)
             if (kind == FAIL_NONE) continue;
             // FAIL_NARROW: one call re-bins the bracket lists of the whole tile; FAIL_FULL: sub-tile by sub-tile
             const int subs = (kind == FAIL_FULL) ? SUB : 1;
-            for (int j = 0; j < subs; ++j) stream_subtile<SM_EXACT, RND>(p, u * SUB + j, lane, &xb);
+            for (int j = 0; j < subs; ++j) stream_subtile<SM_EXACT, RND, NCF>(p, u * SUB + j, lane, &xb);
         }
     }
 }
@@ -1305,6 +1568,7 @@ __global__ __launch_bounds__(256) void locate_kernel(Params p)
     const int tid = threadIdx.x;
     const uint32_t id = blockIdx.x;
     const int t = id / p.n_cf, j = id - t * p.n_cf;
+    if (seg_small(p, t)) return;
     CfState* st = &p.st[id];
     const uint32_t k = seg_k(p, t, j);
     const uint32_t lo = p.bnd_lo[id];
@@ -1356,11 +1620,12 @@ __global__ __launch_bounds__(256) void locate_kernel(Params p)
 }
 
 // ---------------------------------------------------------------------------------------------
-// R1: one wavefront per tile walks the tile's bracket lists: per CF, the entries above the bin that
-// holds the k-th largest are counted and their energy summed (together with what the pass over the
-// gradient counted above the bracket), the entries inside that bin are gathered (key, tile, value) or
-// histogrammed.  For a segment that took an exact route the plan is derived here, by every wavefront
-// for itself, from the rebuilt bracket histogram (its first tile's wavefront records it).
+// R1: one wavefront per tile.  The tile's sums of the pass over the gradient (energy, entries above
+// every CF's bracket and their energy) are added up over its sub-tiles; then the tile's entries inside
+// the brackets are walked: per CF, those above the bin that holds the k-th largest are counted and
+// their energy summed, those inside that bin are gathered (key, tile, value) or histogrammed.  For a
+// segment that took an exact route the plan is derived here, by every wavefront for itself, from the
+// rebuilt bracket histogram (its first tile's wavefront records it).
 // ---------------------------------------------------------------------------------------------
 template <int NCF>  // compiled for calls with up to NCF CFs: the loops over the CFs are unrolled
 __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
@@ -1368,117 +1633,128 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
     const int lane = threadIdx.x & 63;
     const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * LWAVES + (threadIdx.x >> 6));
     if (u >= p.n_tiles) return;
-    const TileLists tl = tile_lists(p.brk_cnt, u);
-    const uint32_t cnt = tl.total();
-    const int t = tile_seg(p, u);
-    const bool redo = p.status->any_fail != 0 && p.seg[t].fail != 0;
-    const bool first = redo && (u == seg_tile0(p, t));
-    // exact route: the plan comes from the rebuilt bracket histogram.  A plain loop whose results go through
-    // LDS, so that the search does not inflate the register count of the common path.
-    __shared__ uint32_t rp[LWAVES][MAXCF][3];
-    const int wib = threadIdx.x >> 6;
-    if (redo) {
-        const uint32_t fail_kind = p.seg[t].fail;
-        if (first && lane == 0 && fail_kind == FAIL_NARROW) atomicAdd(&p.status->n_narrow, 1);
-        for (int j = 0; j < p.n_cf; ++j) {
-            CfState* st = &p.st[(size_t)t * p.n_cf + j];
-            if (fail_kind == FAIL_NARROW && st->redo == 0) {
-                // this CF was not binned again: its plan stands (nobody writes it during this kernel)
-                if (lane == 0) { rp[wib][j][0] = st->mode; rp[wib][j][1] = st->base; rp[wib][j][2] = st->span; }
-                continue;
-            }
-            uint32_t b, above, c;
-            wave_locate_bin(p.hist1 + ((size_t)t * p.n_cf + j) * REP * NBIN, REP, p.ovfc + ((size_t)t * p.n_cf + j) * 64 * 32,
-                            st->k, b, above, c);
-            const BinPlan q = plan_bin(st->lo, st->s, b, above, c);
-            if (lane == 0) {
-                rp[wib][j][0] = q.mode; rp[wib][j][1] = q.base; rp[wib][j][2] = q.span;
-                if (first) {
-                    store_plan(st, q);
-                    if (q.mode == MODE_FAIL) p.status->error = 1;  // the exact routes cannot fail
-                }
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // rp is read back by the same wavefront
+    // loads that depend on nothing but the tile number come first, so that they are in flight together
+    const int any_fail = p.status->any_fail;
+    const double ssd = lane < SUB ? p.ssd[(size_t)u * SUB + lane] : 0.0;
+    uint32_t on[NCF];
+    double os[NCF];
+#pragma unroll
+    for (int j = 0; j < NCF; ++j) {
+        const bool have = lane < SUB && j < p.n_cf;
+        on[j] = have ? p.ovn[((size_t)u * SUB + lane) * p.n_cf + j] : 0u;
+        os[j] = have ? p.ovs[((size_t)u * SUB + lane) * p.n_cf + j] : 0.0;
     }
-    uint32_t mode[NCF], base[NCF], span[NCF], top[NCF];
+    const TileRef tr = tile_ref(p, u);
+    const uint32_t cnt = tr.tl.total();
+    const int t = tile_seg(p, u);
+    const bool redo = any_fail != 0 && p.seg[t].fail != 0;
+    const bool first = redo && (u == seg_tile0(p, t));
     uint32_t hn[NCF], tin = 0;
     double hs[NCF];
 #pragma unroll
-    for (int j = 0; j < NCF; ++j) {
-        mode[j] = MODE_RESOLVED; base[j] = NONE; span[j] = 0; top[j] = 0; hn[j] = 0; hs[j] = 0.0;
-        if (j < p.n_cf) {
-            const CfState* st = &p.st[(size_t)t * p.n_cf + j];
-            top[j] = st->top;
-            if (redo) { mode[j] = rp[wib][j][0]; base[j] = rp[wib][j][1]; span[j] = rp[wib][j][2]; }
-            else { mode[j] = st->mode; base[j] = st->base; span[j] = st->span; }
-            if (mode[j] == MODE_FAIL) { base[j] = NONE; top[j] = 0; }  // (an error: nothing is counted)
-        }
-    }
-    const uint32_t* bk = p.brk_key + (size_t)u * TW;
-    const float* bv = p.brk_val + (size_t)u * TW;
-    // what one bracket-list entry adds, per CF whose bracket it lies in
-    const auto take = [&](uint32_t key, float val, bool live) {
-        const double dv = p.random ? (double)val : (double)__uint_as_float(key);  // Top-k: the key is |acc|
-#pragma unroll
-        for (int j = 0; j < NCF; ++j) {
-            if (j >= p.n_cf) continue;
-            const bool mine = live && key < top[j] && key >= base[j];
-            const bool in = mine && key - base[j] <= span[j];
-            // Random-k: the entry at the threshold is the last one selected and has no particular magnitude, so a bin
-            // that is one key wide adds its energy here (Top-k adds need * tau^2 in the scan instead)
-            if (mine && (!in || (p.random && mode[j] == MODE_RESOLVED))) { hs[j] += dv * dv; hn[j] += in ? 0u : 1u; }
-            if (j == p.commit && in) ++tin;
-            if (mode[j] == MODE_GATHER) {
-                // one counter update per wavefront: the lanes with a key in the bin take consecutive slots
-                const uint64_t m = __ballot(in);
-                if (m != 0ull) {
-                    const size_t lst = ((size_t)t * p.n_cf + j) * REP + (blockIdx.x & (REP - 1));
-                    const int leader = __ffsll((unsigned long long)m) - 1;
-                    uint32_t at = 0;
-                    if (lane == leader) at = atomicAdd(&p.list_cnt[lst * 32], (uint32_t)__popcll(m));
-                    at = __shfl(at, leader, 64);
-                    const uint32_t pos = at + lanes_below(m);
-                    if (in && pos < LCAP) {
-                        p.list_key[lst * LCAP + pos] = key;
-                        p.list_tile[lst * LCAP + pos] = u;
-                        if (p.random) p.list_val[lst * LCAP + pos] = val;
+    for (int j = 0; j < NCF; ++j) { hn[j] = 0; hs[j] = 0.0; }
+    if (cnt != 0 || first) {
+        // exact route: the plan comes from the rebuilt bracket histogram.  A plain loop whose results go through
+        // LDS, so that the search does not inflate the register count of the common path.
+        __shared__ uint32_t rp[LWAVES][MAXCF][3];
+        const int wib = threadIdx.x >> 6;
+        if (redo) {
+            const uint32_t fail_kind = p.seg[t].fail;
+            if (first && lane == 0 && fail_kind == FAIL_NARROW) atomicAdd(&p.status->n_narrow, 1);
+            for (int j = 0; j < p.n_cf; ++j) {
+                CfState* st = &p.st[(size_t)t * p.n_cf + j];
+                if (fail_kind == FAIL_NARROW && st->redo == 0) {
+                    // this CF was not binned again: its plan stands (nobody writes it during this kernel)
+                    if (lane == 0) { rp[wib][j][0] = st->mode; rp[wib][j][1] = st->base; rp[wib][j][2] = st->span; }
+                    continue;
+                }
+                uint32_t b, above, c;
+                wave_locate_bin(p.hist1 + ((size_t)t * p.n_cf + j) * REP * NBIN, REP, p.ovfc + ((size_t)t * p.n_cf + j) * 64 * 32,
+                                st->k, b, above, c);
+                const BinPlan q = plan_bin(st->lo, st->s, b, above, c);
+                if (lane == 0) {
+                    rp[wib][j][0] = q.mode; rp[wib][j][1] = q.base; rp[wib][j][2] = q.span;
+                    if (first) {
+                        store_plan(st, q);
+                        if (q.mode == MODE_FAIL) p.status->error = 1;  // the exact routes cannot fail
                     }
                 }
-            } else if (mode[j] == MODE_HIST && in) {
-                atomicAdd(&p.hist2[((size_t)t * p.n_cf + j) * NBIN + (key - base[j])], 1u);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // rp is read back by the same wavefront
+        }
+        uint32_t mode[NCF], base[NCF], span[NCF], top[NCF];
+#pragma unroll
+        for (int j = 0; j < NCF; ++j) {
+            mode[j] = MODE_RESOLVED; base[j] = NONE; span[j] = 0; top[j] = 0;
+            if (j < p.n_cf) {
+                const CfState* st = &p.st[(size_t)t * p.n_cf + j];
+                top[j] = st->top;
+                if (redo) { mode[j] = rp[wib][j][0]; base[j] = rp[wib][j][1]; span[j] = rp[wib][j][2]; }
+                else { mode[j] = st->mode; base[j] = st->base; span[j] = st->span; }
+                if (mode[j] == MODE_FAIL) { base[j] = NONE; top[j] = 0; }  // (an error: nothing is counted)
             }
         }
-    };
-    for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
-        // eight loads in flight per lane
-        uint32_t kq[8];
-        float vq[8];
+        // what one entry adds, per CF whose bracket it lies in (below top_j: what lies above was counted by the pass)
+        const auto take = [&](uint32_t key, float val, bool live) {
+            const double dv = p.random ? (double)val : (double)__uint_as_float(key);  // Top-k: the key is |acc|
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const uint32_t i = i0 + q * 64 + lane;
-            const uint32_t sl = (i < cnt) ? tl.slot(i) : 0u;
-            kq[q] = bk[sl];
-            vq[q] = p.random ? bv[sl] : 0.0f;
+            for (int j = 0; j < NCF; ++j) {
+                if (j >= p.n_cf) continue;
+                const bool mine = live && key < top[j] && key >= base[j];
+                const bool in = mine && key - base[j] <= span[j];
+                // Random-k: the entry at the threshold is the last one selected and has no particular magnitude, so a
+                // bin that is one key wide adds its energy here (Top-k adds need * tau^2 in the scan instead)
+                if (mine && (!in || (p.random && mode[j] == MODE_RESOLVED))) { hs[j] += dv * dv; hn[j] += in ? 0u : 1u; }
+                if (j == p.commit && in) ++tin;
+                if (mode[j] == MODE_GATHER) {
+                    // one counter update per wavefront: the lanes with a key in the bin take consecutive slots
+                    const uint64_t m = __ballot(in);
+                    if (m != 0ull) {
+                        const size_t lst = ((size_t)t * p.n_cf + j) * REP + (blockIdx.x & (REP - 1));
+                        const int leader = __ffsll((unsigned long long)m) - 1;
+                        uint32_t at = 0;
+                        if (lane == leader) at = atomicAdd(&p.list_cnt[lst * 32], (uint32_t)__popcll(m));
+                        at = __shfl(at, leader, 64);
+                        const uint32_t pos = at + lanes_below(m);
+                        if (in && pos < LCAP) {
+                            p.list_key[lst * LCAP + pos] = key;
+                            p.list_tile[lst * LCAP + pos] = u;
+                            if (p.random) p.list_val[lst * LCAP + pos] = val;
+                        }
+                    }
+                } else if (mode[j] == MODE_HIST && in) {
+                    atomicAdd(&p.hist2[((size_t)t * p.n_cf + j) * NBIN + (key - base[j])], 1u);
+                }
+            }
+        };
+        for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
+            // eight loads in flight per lane
+            uint32_t kq[8];
+            float vq[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const uint32_t i = i0 + q * 64 + lane;
+                ref_entry(p, u, tr, i < cnt ? i : 0u, kq[q], vq[q]);
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) take(kq[q], vq[q], i0 + q * 64 + lane < cnt);
         }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) take(kq[q], vq[q], i0 + q * 64 + lane < cnt);
     }
     // the tile's sums: what the pass over the gradient counted above the brackets, plus the above
     {
-        const double x = wave_sum(lane < SUB ? p.ssd[(size_t)u * SUB + lane] : 0.0);
+        const double x = wave_sum(ssd);
         if (lane == 0) p.ssd_t[u] = x;
     }
     tin = wave_sum(tin);
 #pragma unroll
     for (int j = 0; j < NCF; ++j) {
         if (j < p.n_cf) {
-            const uint32_t on = wave_sum(hn[j] + (lane < SUB ? p.ovn[((size_t)u * SUB + lane) * p.n_cf + j] : 0u));
+            const uint32_t n = wave_sum(hn[j] + on[j]);
             // (the counted energy first, in sub-tile order, then the listed entries': a fixed order)
-            const double os = wave_sum(lane < SUB ? p.ovs[((size_t)u * SUB + lane) * p.n_cf + j] : 0.0) + wave_sum(hs[j]);
+            const double e = wave_sum(os[j]) + wave_sum(hs[j]);
             if (lane == 0) {
-                p.sss[(size_t)u * p.n_cf + j] = os;
-                if (j == p.commit) { p.tg0[u] = on; p.tin[u] = tin; }
+                p.sss[(size_t)u * p.n_cf + j] = e;
+                if (j == p.commit) { p.tg0[u] = n; p.tin[u] = tin; }
             }
         }
     }
@@ -1498,8 +1774,10 @@ constexpr int SCAN_T = 1024;                 // threads
 constexpr int SCAN_W = SCAN_T / 64;
 constexpr int SCAN_PER = 4;                  // tiles per thread
 constexpr int SCAN_SLICE = SCAN_T * SCAN_PER;
-constexpr int LPER = LCAP / SCAN_T;          // gathered entries per thread
-static_assert(LCAP % SCAN_T == 0, "the gathered entries are dealt evenly");
+constexpr int RW = 8;                        // gathered entries per lane where one wavefront holds them all ...
+constexpr uint32_t WAVE_CAP = 64 * RW;       // ... which it does up to this many (no barrier in its search)
+constexpr int LPER = LCAP / SCAN_T;          // gathered entries per thread otherwise
+static_assert(LCAP % SCAN_T == 0 && LPER <= RW, "the gathered entries are dealt evenly");
 
 __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
 {
@@ -1516,21 +1794,60 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
     const uint32_t id = (uint32_t)t * p.n_cf + j;
     const uint32_t u0 = seg_tile0(p, t), u1 = seg_tile1(p, t);
     const uint32_t slice0 = scan_role ? u0 + blockIdx.y * SCAN_SLICE : 0u;
-    if (scan_role && slice0 >= u1) return;
+    if ((scan_role && slice0 >= u1) || seg_small(p, t)) return;
     CfState* st = &p.st[id];
 
-    // ---- resolve (segment t, CF j)
-    // the fill counts of the gather lists are fetched together with the plan, not after it (they do not depend on it)
+    // ---- loads that do not depend on the threshold come first, so that they overlap with its resolution
+    // the fill counts of the gather lists and the plan
     uint32_t fill[REP];
 #pragma unroll
     for (int r = 0; r < REP; ++r) fill[r] = p.list_cnt[((size_t)id * REP + r) * 32];
-    const uint32_t mode = st->mode, k = st->k, above = st->above, base = st->base, span = st->span;
+    const uint32_t mode = st->mode, k = st->k, above = st->above, base = st->base, span = st->span, c = st->c;
     uint32_t tau = st->tau, need = st->need, cnt_gt = st->cnt_gt;   // valid if the located bin was one key wide
-    uint32_t d[LPER], rt[LPER];   // this thread's gathered entries: key - base (0 for a slot past the last entry) and tile
-    float rv[LPER];
-    bool rl[LPER];
+    // scan: this slice, coalesced (entries above the located bin, entries inside it), and the totals of the
+    // earlier slices of this segment; statistics: the tiles' sums, sixteen tiles per thread and round, fixed order
+    uint32_t og[SCAN_PER], oi[SCAN_PER], pg = 0, pi = 0;
+    double sd = 0.0, sj = 0.0;
+    if (scan_role) {
 #pragma unroll
-    for (int q = 0; q < LPER; ++q) { d[q] = 0; rt[q] = 0; rv[q] = 0.0f; rl[q] = false; }
+        for (int q = 0; q < SCAN_PER; ++q) {
+            const uint32_t u = slice0 + q * SCAN_T + tid;
+            og[q] = (u < u1) ? p.tg0[u] : 0u;
+            oi[q] = (u < u1) ? p.tin[u] : 0u;
+        }
+        for (uint32_t v0 = u0 + tid; v0 < slice0; v0 += 32 * SCAN_T) {
+            uint32_t xg[32], xe[32];
+#pragma unroll
+            for (int q = 0; q < 32; ++q) {
+                const uint32_t v = v0 + q * SCAN_T;
+                xg[q] = (v < slice0) ? p.tg0[v] : 0u;
+                xe[q] = (v < slice0) ? p.tin[v] : 0u;
+            }
+#pragma unroll
+            for (int q = 0; q < 32; ++q) { pg += xg[q]; pi += xe[q]; }
+        }
+    } else {
+        for (uint32_t v0 = u0 + tid; v0 < u1; v0 += 16 * SCAN_T) {
+            double xd[16], xj[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const uint32_t u = v0 + q * SCAN_T;
+                xd[q] = (u < u1) ? p.ssd_t[u] : 0.0;
+                xj[q] = (u < u1) ? p.sss[(size_t)u * p.n_cf + j] : 0.0;
+            }
+#pragma unroll
+            for (int q = 0; q < 16; ++q) { sd += xd[q]; sj += xj[q]; }
+        }
+    }
+
+    // ---- resolve (segment t, CF j)
+    // This thread's gathered entries: key - base, tile, value, and which of the slots hold one.  Up to WAVE_CAP
+    // entries sit in the block's first wavefront, RW per lane (its search needs no barrier); more are dealt over
+    // the block, LPER per thread.
+    uint32_t d[RW], rt[RW], live = 0;
+    float rv[RW];
+#pragma unroll
+    for (int q = 0; q < RW; ++q) { d[q] = 0; rt[q] = 0; rv[q] = 0.0f; }
     if (mode == MODE_FAIL) {
         if (tid == 0) p.status->error = 1;
         tau = 0; need = 0; cnt_gt = 0;
@@ -1548,7 +1865,7 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
     } else if (mode == MODE_GATHER) {
         // the want-th largest of the listed keys, by a bitwise search on d = key - base.
         // The keys sit in REP lists; list r holds positions [off_r, off_r + n_r) of the concatenation.
-        const uint32_t c = st->c, want = k - above;
+        const uint32_t want = k - above;
         uint32_t off[REP + 1];
         off[0] = 0;
 #pragma unroll
@@ -1557,11 +1874,15 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
             if (tid == 0) p.status->error = 1;
             tau = base; need = 0; cnt_gt = above;
         } else {
+            const bool small = c <= WAVE_CAP;
+            const int nq = small ? (wib == 0 ? RW : 0) : LPER;
             // all loads first, without branches around them (a position past the last key reads key 0 of the lists
             // instead; c >= 1 here), so that they are in flight together
 #pragma unroll
-            for (int q = 0; q < LPER; ++q) {
-                const uint32_t i = (uint32_t)(q * SCAN_T + tid) < c ? (uint32_t)(q * SCAN_T + tid) : 0u;
+            for (int q = 0; q < RW; ++q) {
+                if (q >= nq) continue;
+                const uint32_t pos = small ? (uint32_t)(q * 64 + lane) : (uint32_t)(q * SCAN_T + tid);
+                const uint32_t i = pos < c ? pos : 0u;
                 int r = 0;
 #pragma unroll
                 for (int x = 1; x < REP; ++x) r += (i >= off[x]);
@@ -1572,40 +1893,56 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
                 d[q] = p.list_key[at];
                 rt[q] = p.list_tile[at];
                 rv[q] = p.random ? p.list_val[at] : 0.0f;
+                if (pos < c) live |= 1u << q;
             }
 #pragma unroll
-            for (int q = 0; q < LPER; ++q) {
-                rl[q] = (uint32_t)(q * SCAN_T + tid) < c;
-                d[q] = rl[q] ? d[q] - base : 0u;  // padding never counts: trial values are >= 1
-            }
+            for (int q = 0; q < RW; ++q) d[q] = ((live >> q) & 1u) ? d[q] - base : 0u;  // padding never counts: trial values are >= 1
             int nbits = 0;
             while (nbits < 32 && (span >> nbits) != 0u) ++nbits;
-            uint32_t prefix = 0;
-            int buf = 0;
-            for (int bit = nbits - 1; bit >= 0; --bit) {
-                const uint32_t trial = prefix | (1u << bit);
-                uint32_t cn = 0;
+            uint32_t prefix = 0, gsum = 0;
+            if (small) {
+                if (wib == 0) {
+                    for (int bit = nbits - 1; bit >= 0; --bit) {
+                        const uint32_t trial = prefix | (1u << bit);
+                        uint32_t cn = 0;
 #pragma unroll
-                for (int q = 0; q < LPER; ++q) cn += (d[q] >= trial);
-                cn = wave_sum(cn);
-                if (lane == 0) wsum[buf][wib] = cn;
+                        for (int q = 0; q < RW; ++q) cn += (d[q] >= trial);
+                        if (wave_sum(cn) >= want) prefix = trial;
+                    }
+                    uint32_t gt = 0;
+#pragma unroll
+                    for (int q = 0; q < RW; ++q) gt += ((live >> q) & 1u) && (d[q] > prefix);
+                    gt = wave_sum(gt);
+                    if (lane == 0) { res3[0] = prefix; res3[1] = gt; }
+                }
                 __syncthreads();
-                uint32_t total = 0;
+                prefix = res3[0]; gsum = res3[1];
+            } else {
+                int buf = 0;
+                for (int bit = nbits - 1; bit >= 0; --bit) {
+                    const uint32_t trial = prefix | (1u << bit);
+                    uint32_t cn = 0;
 #pragma unroll
-                for (int w = 0; w < SCAN_W; ++w) total += wsum[buf][w];
-                buf ^= 1;
-                if (total >= want) prefix = trial;
+                    for (int q = 0; q < LPER; ++q) cn += (d[q] >= trial);
+                    cn = wave_sum(cn);
+                    if (lane == 0) wsum[buf][wib] = cn;
+                    __syncthreads();
+                    uint32_t total = 0;
+#pragma unroll
+                    for (int w = 0; w < SCAN_W; ++w) total += wsum[buf][w];
+                    buf ^= 1;
+                    if (total >= want) prefix = trial;
+                }
+                uint32_t gt = 0;
+#pragma unroll
+                for (int q = 0; q < LPER; ++q) gt += ((live >> q) & 1u) && (d[q] > prefix);
+                gt = wave_sum(gt);
+                __syncthreads();
+                if (lane == 0) wsum[0][wib] = gt;
+                __syncthreads();
+#pragma unroll
+                for (int w = 0; w < SCAN_W; ++w) gsum += wsum[0][w];
             }
-            uint32_t gt = 0;
-#pragma unroll
-            for (int q = 0; q < LPER; ++q) gt += rl[q] && (d[q] > prefix);
-            gt = wave_sum(gt);
-            __syncthreads();
-            if (lane == 0) wsum[0][wib] = gt;
-            __syncthreads();
-            uint32_t gsum = 0;
-#pragma unroll
-            for (int w = 0; w < SCAN_W; ++w) gsum += wsum[0][w];
             tau = base + prefix; cnt_gt = above + gsum; need = k - cnt_gt;
             __syncthreads();
         }
@@ -1615,35 +1952,19 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
     if (scan_role) {
         // (the plan itself stays as it is: the segment's other blocks are reading it)
         if (blockIdx.y == 0 && tid == 0) { st->tau = tau; st->need = need; st->cnt_gt = cnt_gt; }
-        // this slice, coalesced: entries above the located bin; entries equal to tau if that bin is one key wide
-        uint32_t og[SCAN_PER], oe[SCAN_PER];
+        // entries equal to tau: those inside a located bin that is one key wide
+        uint32_t pe = (mode == MODE_RESOLVED) ? pi : 0u;
 #pragma unroll
         for (int q = 0; q < SCAN_PER; ++q) {
-            const uint32_t u = slice0 + q * SCAN_T + tid;
-            og[q] = (u < u1) ? p.tg0[u] : 0u;
-            oe[q] = (u < u1 && mode == MODE_RESOLVED) ? p.tin[u] : 0u;
+            sg[q * SCAN_T + tid] = og[q];
+            se[q * SCAN_T + tid] = (mode == MODE_RESOLVED) ? oi[q] : 0u;
         }
-        // totals of the earlier slices of this segment
-        uint32_t pg = 0, pe = 0;
-        for (uint32_t v0 = u0 + tid; v0 < slice0; v0 += 32 * SCAN_T) {
-            uint32_t xg[32], xe[32];
-#pragma unroll
-            for (int q = 0; q < 32; ++q) {
-                const uint32_t v = v0 + q * SCAN_T;
-                xg[q] = (v < slice0) ? p.tg0[v] : 0u;
-                xe[q] = (v < slice0 && mode == MODE_RESOLVED) ? p.tin[v] : 0u;
-            }
-#pragma unroll
-            for (int q = 0; q < 32; ++q) { pg += xg[q]; pe += xe[q]; }
-        }
-#pragma unroll
-        for (int q = 0; q < SCAN_PER; ++q) { sg[q * SCAN_T + tid] = og[q]; se[q * SCAN_T + tid] = oe[q]; }
         __syncthreads();
         if (mode == MODE_GATHER) {
             // the gathered entries above and at the threshold, by tile
 #pragma unroll
-            for (int q = 0; q < LPER; ++q) {
-                if (!rl[q] || d[q] < dtau) continue;
+            for (int q = 0; q < RW; ++q) {
+                if (!((live >> q) & 1u) || d[q] < dtau) continue;
                 const bool gt = d[q] > dtau;
                 if (rt[q] < slice0) { if (gt) ++pg; else ++pe; }
                 else if (rt[q] - slice0 < (uint32_t)SCAN_SLICE) atomicAdd(gt ? &sg[rt[q] - slice0] : &se[rt[q] - slice0], 1u);
@@ -1652,15 +1973,16 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
             // more keys in the located bin than a gather list holds (a mass of equal values): the tiles that have
             // entries in the bin are walked again, up to the end of this slice, one wavefront per tile at a time
             const uint32_t uend = slice0 + SCAN_SLICE < u1 ? slice0 + SCAN_SLICE : u1;
+            const uint32_t top = st->top;
             for (uint32_t u = u0 + wib; u < uend; u += SCAN_W) {
                 if (p.tin[u] == 0) continue;
-                const TileLists tl = tile_lists(p.brk_cnt, u);
-                const uint32_t cnt = tl.total();
-                const uint32_t* bk = p.brk_key + (size_t)u * TW;
-                const uint32_t top = st->top;
+                const TileRef tr = tile_ref(p, u);
+                const uint32_t cnt = tr.tl.total();
                 uint32_t g = 0, e = 0;
                 for (uint32_t i = lane; i < cnt; i += 64) {
-                    const uint32_t key = bk[tl.slot(i)];
+                    uint32_t key;
+                    float unused;
+                    ref_entry(p, u, tr, i, key, unused);
                     if (key < top && key >= base && key - base <= span) { g += key > tau; e += key == tau; }
                 }
                 g = wave_sum(g); e = wave_sum(e);
@@ -1701,17 +2023,16 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
             run_g += g[i];
             run_e += e[i];
         }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < SCAN_PER; ++i) {
-            sg[tid * SCAN_PER + i] = off[i];
-            se[tid * SCAN_PER + i] = tk[i];
-        }
         // the number of pairs a tile emits is written by the thread that holds its counts
 #pragma unroll
         for (int i = 0; i < SCAN_PER; ++i) {
             const uint32_t u = slice0 + tid * SCAN_PER + i;
             if (u < u1) p.tsel[u] = g[i] + tk[i];
+        }
+#pragma unroll
+        for (int i = 0; i < SCAN_PER; ++i) {
+            sg[tid * SCAN_PER + i] = off[i];
+            se[tid * SCAN_PER + i] = tk[i];
         }
         __syncthreads();
 #pragma unroll
@@ -1723,57 +2044,44 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
     }
 
     // ---- statistics of (segment t, CF j)
-    // sixteen tiles per thread and round, all loads of a round in flight together; fixed summation order
-    double sd = 0.0, sj = 0.0;
-    for (uint32_t v0 = u0 + tid; v0 < u1; v0 += 16 * SCAN_T) {
-        double xd[16], xj[16];
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const uint32_t u = v0 + q * SCAN_T;
-            xd[q] = (u < u1) ? p.ssd_t[u] : 0.0;
-            xj[q] = (u < u1) ? p.sss[(size_t)u * p.n_cf + j] : 0.0;
-        }
-#pragma unroll
-        for (int q = 0; q < 16; ++q) { sd += xd[q]; sj += xj[q]; }
-    }
     // the entries of the located bin above the threshold (Random-k: and the one at it).  Their order in the gather
     // lists varies from run to run, so their energies are added as integers: every square, exact in binary64, is
     // scaled by a power of two that puts the largest of them below 2^50 and truncated, the sum of up to LCAP of them
     // fits 64 bits and does not depend on the order, and it is off by less than 2^-38 of itself.
     double ebin = 0.0;
     if (mode == MODE_GATHER) {
-        double sq[LPER], mx = 0.0;
-#pragma unroll
-        for (int q = 0; q < LPER; ++q) {
-            const bool in = rl[q] && (d[q] > dtau || (p.random && d[q] == dtau));
+        const auto square = [&](int q) {
+            const bool in = ((live >> q) & 1u) && (d[q] > dtau || (p.random && d[q] == dtau));
             const double dv = p.random ? (double)rv[q] : (double)__uint_as_float(base + d[q]);
-            sq[q] = in ? dv * dv : 0.0;
-            mx = fmax(mx, sq[q]);   // (a NaN square is skipped here and shows in the plain sum below)
+            return in ? dv * dv : 0.0;
+        };
+        double mx = 0.0, plain = 0.0;
+        bool finite = true;
+#pragma unroll
+        for (int q = 0; q < RW; ++q) {
+            const double x = square(q);
+            mx = fmax(mx, x);   // (a NaN square is skipped here and shows in the plain sum)
+            plain += x;
+            finite = finite && (x <= 1.0e300);
         }
         mx = wave_max(mx);
         if (lane == 0) dred[2][wib] = mx;
-        __syncthreads();
+        const bool all_finite = __syncthreads_and(finite ? 1 : 0) != 0;
         mx = 0.0;
 #pragma unroll
         for (int w = 0; w < SCAN_W; ++w) mx = fmax(mx, dred[2][w]);
-        bool finite = true;
-#pragma unroll
-        for (int q = 0; q < LPER; ++q) finite = finite && (sq[q] <= 1.0e300);
-        const bool all_finite = __syncthreads_and(finite ? 1 : 0) != 0;
+        __syncthreads();
         if (!all_finite) {
             // an infinite or NaN square: the sum is infinite or NaN in any order
-            double s = 0.0;
-#pragma unroll
-            for (int q = 0; q < LPER; ++q) s += sq[q];
-            s = wave_sum(s);
-            if (lane == 0) dred[2][wib] = s;
+            plain = wave_sum(plain);
+            if (lane == 0) dred[2][wib] = plain;
             __syncthreads();
             for (int w = 0; w < SCAN_W; ++w) ebin += dred[2][w];
         } else if (mx > 0.0) {
             const int ex = ilogb(mx);                      // 2^ex <= mx < 2^(ex + 1)
             uint64_t acc = 0;
 #pragma unroll
-            for (int q = 0; q < LPER; ++q) acc += (uint64_t)scalbn(sq[q], 49 - ex);   // < 2^50 each
+            for (int q = 0; q < RW; ++q) acc += (uint64_t)scalbn(square(q), 49 - ex);   // < 2^50 each
             acc = wave_sum(acc);
             if (lane == 0) ured[wib] = acc;
             __syncthreads();
@@ -1798,7 +2106,6 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
     // every wavefront's sum, then the SCAN_W of them in order: the same order in every run
     {
         const double wd = wave_sum(sd), wj = wave_sum(sj);
-        __syncthreads();
         if (lane == 0) { dred[0][wib] = wd; dred[1][wib] = wj; }
     }
     __syncthreads();
@@ -1814,7 +2121,6 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
         o[1] = ss_dense;
         o[2] = (ss_dense == 0.0) ? 1.0 : ss_sel / ss_dense;
         o[3] = tauv;
-        if (id == 0 && p.out_count) *p.out_count = p.total_out;
         if (j != p.commit) { st->tau = tau; st->need = need; st->cnt_gt = cnt_gt; }
     }
 }
@@ -2435,8 +2741,8 @@ Layout make_layout(int64_t n, int n_cf, int n_seg)
     const uint64_t nt = max_tiles(n, n_seg), nsb = max_sample_blocks(n, n_seg);
     const size_t sc = (size_t)n_seg * n_cf;
     L.status = take(sizeof(Status));
-    // host-built tables, one piece: SegInfo[n_seg], ktab[n_seg][n_cf], sblock_seg[sample blocks]
-    L.tables_bytes = sizeof(SegInfo) * n_seg + sizeof(uint32_t) * sc + sizeof(uint32_t) * nsb;
+    // host-built tables, one piece: SegInfo[n_seg], ktab[n_seg][n_cf], sblock_seg[sample blocks], small_list[n_seg]
+    L.tables_bytes = sizeof(SegInfo) * n_seg + sizeof(uint32_t) * sc + sizeof(uint32_t) * nsb + sizeof(uint32_t) * n_seg;
     L.tables = take(L.tables_bytes);
     L.tseg = take(sizeof(uint32_t) * nt);
     L.st = take(sizeof(CfState) * sc);
@@ -2517,9 +2823,17 @@ StagingSlot* staging_acquire(size_t bytes)
     StagingSlot* s = nullptr;
     {
         std::lock_guard<std::mutex> lock(g_staging_mutex);
-        for (int i = 0; i < STAGING_SLOTS && !s; ++i) {
-            StagingSlot* c = &g_staging[(g_staging_next + i) % STAGING_SLOTS];
-            if (!c->busy) { s = c; g_staging_next = (g_staging_next + i + 1) % STAGING_SLOTS; }
+        // a slot that is large enough and whose last copy has run, else one that has no memory yet, else any free one
+        for (int pass = 0; pass < 3 && !s; ++pass) {
+            for (int i = 0; i < STAGING_SLOTS && !s; ++i) {
+                StagingSlot* c = &g_staging[(g_staging_next + i) % STAGING_SLOTS];
+                if (c->busy) continue;
+                const bool ready = c->cap >= bytes && (!c->pending || hipEventQuery(c->done) == hipSuccess);
+                if ((pass == 0 && ready) || (pass == 1 && c->cap == 0) || pass == 2) {
+                    s = c;
+                    g_staging_next = (g_staging_next + i + 1) % STAGING_SLOTS;
+                }
+            }
         }
         if (!s) return nullptr;  // more concurrent callers than slots
         s->busy = true;
@@ -2660,6 +2974,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     p.map_idx = map_idx; p.restore = restore; p.n_restore = restore ? n_restore : 0; p.single = single ? 1 : 0;
     // 16-byte accesses need 16-byte aligned buffers; anything else is read and written element by element
     p.vec_ok = (((uintptr_t)grad & 15) == 0 && ((uintptr_t)residual & 15) == 0 && ((uintptr_t)map_idx & 15) == 0) ? 1 : 0;
+    p.split = (cf_list[commit] > cf_min) ? 1 : 0;
     p.bounds_from = (flags & GRAVAC_FLAG_FORCE_FALLBACK) ? BOUNDS_FORCED : (random ? BOUNDS_RANDOM : BOUNDS_SAMPLED);
     if (random) {
         // the seed goes through SplitMix64 (its first output for that seed) and gives the two 31-bit keys
@@ -2712,6 +3027,9 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     int64_t total_out = 0;
     uint32_t max_seg_tiles = 1;  // tiles of the largest segment
     int sample_rounds = 1;       // groups per thread of the sampling kernel
+    uint32_t n_small = 0;        // layerwise: tensors of at most SMALL_MAX elements, one workgroup each (not under the
+                                 // testing flag, which sends every tensor through the histogram route)
+    const bool small_ok = ns > 1 && !(flags & GRAVAC_FLAG_FORCE_FALLBACK);
     StagingSlot* slot = nullptr;
     size_t table_bytes = 0;
     if (ns == 1) {
@@ -2736,6 +3054,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         for (int t = 0; t < ns; ++t) {
             const int64_t nt = seg_offsets[t + 1] - seg_offsets[t];
             total_out += gravac_topk_count(nt, cf_list[commit]);
+            if (small_ok && nt <= SMALL_MAX) { ++n_small; continue; }  // one workgroup does it all: no tiles, no samples
             const uint64_t tt = (uint64_t)((nt + TW - 1) / TW);
             tiles += tt;
             if (tt > max_seg_tiles) max_seg_tiles = (uint32_t)tt;
@@ -2751,24 +3070,34 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         if (const int rc = refuse_capture(stream)) return rc;
     (void)hipGetLastError();  // an error left behind by earlier work of the process is not this call's
     if (ns > 1) {
-        table_bytes = sizeof(SegInfo) * ns + sizeof(uint32_t) * (size_t)ns * n_cf + sizeof(uint32_t) * p.n_sample_blocks;
+        table_bytes = sizeof(SegInfo) * ns + sizeof(uint32_t) * (size_t)ns * n_cf + sizeof(uint32_t) * p.n_sample_blocks +
+                      sizeof(uint32_t) * n_small;
         slot = staging_acquire(table_bytes);
         if (!slot) return GRAVAC_ERR_HIP;
         SegInfo* segs = (SegInfo*)slot->mem;
         uint32_t* ktab = (uint32_t*)(slot->mem + sizeof(SegInfo) * ns);
         uint32_t* sblock_seg = ktab + (size_t)ns * n_cf;
+        uint32_t* small_list = sblock_seg + p.n_sample_blocks;
+        p.small_list = p.sblock_seg + p.n_sample_blocks;
+        p.n_small = n_small;
         int64_t koff = 0;
-        uint32_t tile_at = 0, sb_at = 0;
+        uint32_t tile_at = 0, sb_at = 0, small_at_ = 0;
         for (int t = 0; t < ns; ++t) {
             const int64_t nt = seg_offsets[t + 1] - seg_offsets[t];
             SegInfo& g = segs[t];
             std::memset(&g, 0, sizeof(g));
             g.begin = seg_offsets[t]; g.end = seg_offsets[t + 1]; g.koff = koff;
-            g.tile0 = tile_at; tile_at += (uint32_t)((nt + TW - 1) / TW); g.tile1 = tile_at;
-            g.samp0 = sb_at; g.samp_cnt = sample_count((uint64_t)nt, cf_min, cf_max, false);
-            const uint32_t nb = (g.samp_cnt + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
-            for (uint32_t b = 0; b < nb; ++b) sblock_seg[sb_at + b] = (uint32_t)t;
-            sb_at += nb;
+            g.tile0 = g.tile1 = tile_at; g.samp0 = sb_at;
+            if (small_ok && nt <= SMALL_MAX) {
+                g.small = 1;
+                small_list[small_at_++] = (uint32_t)t;
+            } else {
+                tile_at += (uint32_t)((nt + TW - 1) / TW); g.tile1 = tile_at;
+                g.samp_cnt = sample_count((uint64_t)nt, cf_min, cf_max, false);
+                const uint32_t nb = (g.samp_cnt + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK;
+                for (uint32_t b = 0; b < nb; ++b) sblock_seg[sb_at + b] = (uint32_t)t;
+                sb_at += nb;
+            }
             for (int j = 0; j < n_cf; ++j) ktab[(size_t)t * n_cf + j] = (uint32_t)gravac_topk_count(nt, cf_list[j]);
             koff += ktab[(size_t)t * n_cf + commit];
         }
@@ -2793,37 +3122,52 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     const uint32_t light_grid = (p.n_tiles + LWAVES - 1) / LWAVES;
     const uint32_t scan_slices = (max_seg_tiles + SCAN_SLICE - 1) / SCAN_SLICE;
 
+    const int ncf_form = n_cf <= 1 ? 0 : n_cf <= 2 ? 1 : n_cf <= 4 ? 2 : 3;
+    static_assert(MAXCF >= 4, "forms for 1, 2, 4 and MAXCF CFs");
     static_assert(DENSE_ROUNDS == 4, "forms of the sampling kernel for 1, 2 and 4 groups per thread");
-    hipLaunchKernelGGL(sample_rounds == 1 ? sample_kernel<1> : sample_rounds == 2 ? sample_kernel<2> : sample_kernel<4>,
-                       dim3(p.n_sample_blocks), dim3(256), 0, stream, p);
-    // few segments: their sample histograms are added up by SGRP workgroups each; many: by one each
-    if (ns <= 32 && p.bounds_from == BOUNDS_SAMPLED)
-        hipLaunchKernelGGL(threshold_kernel<SGRP>, dim3(ns, SGRP), dim3(1024 / SGRP), 0, stream, p);
+    // (a layerwise call takes SAMPLE_BLOCK samples per block; its small tensors are extra workgroups of this launch)
+    const bool have_tiles = p.n_tiles != 0;  // (not if every tensor of a layerwise call is small)
+    if (have_tiles) {
+        void (*const sample_forms[3])(Params) = {sample_kernel<1>, sample_kernel<2>, sample_kernel<4>};
+        hipLaunchKernelGGL(sample_forms[sample_rounds == 1 ? 0 : sample_rounds == 2 ? 1 : 2], dim3(p.n_sample_blocks), dim3(256),
+                           0, stream, p);
+    }
+    // a layerwise call's small tensors are done by their workgroups of this launch; few segments (none of them small):
+    // their sample histograms are added up by SGRP workgroups each; many: by one each
+    if (n_small)
+        hipLaunchKernelGGL((threshold_kernel<1, true>), dim3(ns, 1), dim3(1024), 0, stream, p);
+    else if (ns <= 32 && p.bounds_from == BOUNDS_SAMPLED)
+        hipLaunchKernelGGL((threshold_kernel<SGRP, false>), dim3(ns, SGRP), dim3(1024 / SGRP), 0, stream, p);
     else
-        hipLaunchKernelGGL(threshold_kernel<1>, dim3(ns, 1), dim3(1024), 0, stream, p);
+        hipLaunchKernelGGL((threshold_kernel<1, false>), dim3(ns, 1), dim3(1024), 0, stream, p);
     {
-        void (*kern)(Params) = single ? stream_kernel<SM_SINGLE, false>
-                                      : (random ? stream_kernel<SM_EF, true> : stream_kernel<SM_EF, false>);
-        if (ev)  // the kernel's own begin and end time stamps
+        // the Top-k pass exists in forms for 1, 2, 4 and MAXCF CFs (its loops over the CFs are unrolled)
+        void (*const ef_forms[4])(Params) = {stream_kernel<SM_EF, false, 1>, stream_kernel<SM_EF, false, 2>,
+                                             stream_kernel<SM_EF, false, 4>, stream_kernel<SM_EF, false, MAXCF>};
+        void (*kern)(Params) = single ? stream_kernel<SM_SINGLE, false, 1>   // (a second-level call has one CF)
+                                      : (random ? stream_kernel<SM_EF, true, MAXCF> : ef_forms[ncf_form]);
+        if (!have_tiles) {
+            if (ev) { (void)hipEventRecord((hipEvent_t)ev->pass_begin, stream); (void)hipEventRecord((hipEvent_t)ev->pass_end, stream); }
+        } else if (ev)  // the kernel's own begin and end time stamps
             hipExtLaunchKernelGGL(kern, dim3(sub_grid), dim3(WG), 0, stream, (hipEvent_t)ev->pass_begin,
                                   (hipEvent_t)ev->pass_end, 0, p);
         else
             hipLaunchKernelGGL(kern, dim3(sub_grid), dim3(WG), 0, stream, p);
     }
+    if (have_tiles) {
     hipLaunchKernelGGL(locate_kernel, dim3((uint32_t)(ns * n_cf)), dim3(256), 0, stream, p);
     // exact routes, taken only by segments whose bracket failed (the kernels return at once otherwise)
     hipLaunchKernelGGL(coarse_kernel, dim3(tile_grid < XGRID ? tile_grid : XGRID), dim3(WG), 0, stream, p);
     if (random)
-        hipLaunchKernelGGL((stream_kernel<SM_EXACT, true>), dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
+        hipLaunchKernelGGL((stream_kernel<SM_EXACT, true, MAXCF>), dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
     else
-        hipLaunchKernelGGL((stream_kernel<SM_EXACT, false>), dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
+        hipLaunchKernelGGL((stream_kernel<SM_EXACT, false, MAXCF>), dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
     // the refine kernel loops over the CFs: forms for 1, 2, 4 and MAXCF CFs
-    const int ncf_form = n_cf <= 1 ? 0 : n_cf <= 2 ? 1 : n_cf <= 4 ? 2 : 3;
-    static_assert(MAXCF >= 4, "forms for 1, 2, 4 and MAXCF CFs");
     void (*const refine_forms[4])(Params) = {refine_kernel<1>, refine_kernel<2>, refine_kernel<4>, refine_kernel<MAXCF>};
     hipLaunchKernelGGL(refine_forms[ncf_form], dim3(light_grid), dim3(LWG), 0, stream, p);
     hipLaunchKernelGGL(scan_kernel, dim3(ns, scan_slices + n_cf), dim3(SCAN_T), 0, stream, p, scan_slices);
     hipLaunchKernelGGL(emit_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
+    }
     if (ev) (void)hipEventRecord((hipEvent_t)ev->call_end, stream);
     if (hipGetLastError() != hipSuccess) return GRAVAC_ERR_HIP;
     return GRAVAC_OK;

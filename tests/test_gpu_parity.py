@@ -234,6 +234,24 @@ def test_segmented_ragged(flags):
     check(g, r, [10.0, 100.0, 1000.0], commit=0, seg=off, flags=flags, what="segmented 3 CFs")
 
 
+def test_layerwise_small_tensors_only_and_at_the_size_limit():
+    """Tensors of at most 8192 elements are selected by one workgroup each, out of LDS: a call that has only such
+    tensors (no tile at all), tensors just below, at and above the limit, ties, several CFs, every commit."""
+    rng = np.random.default_rng(5)
+    for sizes in ([64, 1, 100, 8192, 5, 2048, 4097], [8192, 8193, 8191, 16_384, 3, 70_001, 8192]):
+        off = workloads.offsets_of(sizes)
+        n = int(off[-1])
+        g = workloads.resnet_like_gradient(n, seed=n)
+        r = workloads.normal_gradient(n, 1e-5, seed=n + 1)
+        check(g, r, [100.0], seg=off, what=f"small tensors {sizes}")
+        for commit in range(3):
+            check(g, r, [1.0, 7.0, 100.0], commit=commit, seg=off, what=f"small tensors {sizes} commit {commit}")
+        ties = (rng.integers(-4, 5, n) * 0.5).astype(np.float32)
+        ties[rng.random(n) < 0.2] = -0.0
+        check(ties, np.zeros(n, np.float32), [3.0, 20.0], commit=0, seg=off, what=f"small tensors, ties {sizes}")
+        check(ties, np.zeros(n, np.float32), [3.0, 20.0], commit=1, seg=off, what=f"small tensors, ties {sizes}")
+
+
 def test_config5_reduced_resnet_tensor_list():
     sizes = workloads.scaled_sizes(workloads.resnet101_tensor_sizes(), 16)
     off = workloads.offsets_of(sizes)

@@ -295,44 +295,83 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t m)
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
 
-__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
+// Cross-lane sums with DPP (data-parallel primitives of the vector ALU) instead of LDS permutes: a step costs an
+// instruction, not a round trip through the LDS crossbar, which matters where a wavefront's reductions sit on the
+// critical path of a short kernel.  A row is 16 lanes; a lane whose source does not exist reads 0.
+constexpr int DPP_QUAD_1032 = 0xB1, DPP_QUAD_2301 = 0x4E;       // quad_perm:[1,0,3,2], quad_perm:[2,3,0,1]
+constexpr int DPP_ROW_SHR = 0x110, DPP_ROW_ROR = 0x120;         // + n: row_shr:n, row_ror:n
+constexpr int DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143; // lane 15 of a row to the next row; lane 31 to rows 2 and 3
+
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, true);
 }
 
-__device__ __forceinline__ double wave_sum(double v)
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ double dpp_move(double v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    const uint64_t b = (uint64_t)__double_as_longlong(v);
+    const uint32_t lo = dpp_move<CTRL, ROW_MASK>((uint32_t)b), hi = dpp_move<CTRL, ROW_MASK>((uint32_t)(b >> 32));
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));   // a missing source gives +0.0
 }
 
-__device__ __forceinline__ uint64_t wave_sum(uint64_t v)
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ uint64_t dpp_move(uint64_t v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += (uint64_t)__shfl_xor((unsigned long long)v, o, 64);
-    return v;
+    const uint32_t lo = dpp_move<CTRL, ROW_MASK>((uint32_t)v), hi = dpp_move<CTRL, ROW_MASK>((uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
 }
+
+__device__ __forceinline__ uint32_t last_lane(uint32_t v) { return (uint32_t)__builtin_amdgcn_readlane((int)v, 63); }
+__device__ __forceinline__ uint64_t last_lane(uint64_t v)
+{
+    return ((uint64_t)last_lane((uint32_t)(v >> 32)) << 32) | last_lane((uint32_t)v);
+}
+__device__ __forceinline__ double last_lane(double v)
+{
+    return __longlong_as_double((long long)last_lane((uint64_t)__double_as_longlong(v)));
+}
+
+// Sum over the 64 lanes, the same value (and for floating point the same order of additions) in every lane:
+// pairs, quads, the row's four quads, then rows 0+1 and 2+3, then all in lane 63, which is broadcast.
+template <typename T>
+__device__ __forceinline__ T wave_sum_t(T v)
+{
+    v += dpp_move<DPP_QUAD_1032>(v);
+    v += dpp_move<DPP_QUAD_2301>(v);
+    v += dpp_move<DPP_ROW_ROR + 4>(v);
+    v += dpp_move<DPP_ROW_ROR + 8>(v);
+    v += dpp_move<DPP_ROW_BCAST15, 0xA>(v);
+    v += dpp_move<DPP_ROW_BCAST31, 0xC>(v);
+    return last_lane(v);
+}
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) { return wave_sum_t(v); }
+__device__ __forceinline__ double wave_sum(double v) { return wave_sum_t(v); }
+__device__ __forceinline__ uint64_t wave_sum(uint64_t v) { return wave_sum_t(v); }
 
 __device__ __forceinline__ double wave_max(double v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
-    return v;
+    v = fmax(v, dpp_move<DPP_QUAD_1032>(v));   // (the values are not negative: a missing source's +0.0 changes nothing)
+    v = fmax(v, dpp_move<DPP_QUAD_2301>(v));
+    v = fmax(v, dpp_move<DPP_ROW_ROR + 4>(v));
+    v = fmax(v, dpp_move<DPP_ROW_ROR + 8>(v));
+    v = fmax(v, dpp_move<DPP_ROW_BCAST15, 0xA>(v));
+    v = fmax(v, dpp_move<DPP_ROW_BCAST31, 0xC>(v));
+    return last_lane(v);
 }
 
-// inclusive prefix sum over the lanes of a wavefront
+// inclusive prefix sum over the lanes of a wavefront: within the rows first, then the earlier rows' totals
 __device__ __forceinline__ uint32_t wave_scan(uint32_t v)
 {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t x = __shfl_up(v, o, 64);
-        if (lane >= o) v += x;
-    }
-    return v;
+    uint32_t s = v + dpp_move<DPP_ROW_SHR + 1>(v);
+    s += dpp_move<DPP_ROW_SHR + 2>(v);
+    s += dpp_move<DPP_ROW_SHR + 3>(v);
+    s += dpp_move<DPP_ROW_SHR + 4>(s);
+    s += dpp_move<DPP_ROW_SHR + 8>(s);
+    s += dpp_move<DPP_ROW_BCAST15, 0xA>(s);
+    s += dpp_move<DPP_ROW_BCAST31, 0xC>(s);
+    return s;
 }
 
 __device__ __forceinline__ uint32_t hash32(uint32_t x)
@@ -1727,8 +1766,11 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
                 }
             }
         };
-        for (uint32_t i0 = 0; i0 < cnt; i0 += 64 * 8) {
-            // eight loads in flight per lane
+        // 64 entries per load and lane-row; eight loads in flight per lane where there are that many entries left, two
+        // otherwise (most tiles hold a hundred entries or so, and a round that no lane has an entry for costs as many
+        // instructions as a full one)
+        uint32_t i0 = 0;
+        for (; i0 + 64 * 2 < cnt; i0 += 64 * 8) {
             uint32_t kq[8];
             float vq[8];
 #pragma unroll
@@ -1738,6 +1780,17 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
             }
 #pragma unroll
             for (int q = 0; q < 8; ++q) take(kq[q], vq[q], i0 + q * 64 + lane < cnt);
+        }
+        if (i0 < cnt) {
+            uint32_t kq[2];
+            float vq[2];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const uint32_t i = i0 + q * 64 + lane;
+                ref_entry(p, u, tr, i < cnt ? i : 0u, kq[q], vq[q]);
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q) take(kq[q], vq[q], i0 + q * 64 + lane < cnt);
         }
     }
     // the tile's sums: what the pass over the gradient counted above the brackets, plus the above
@@ -2173,9 +2226,10 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
     const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * LWAVES + (threadIdx.x >> 6));
     if (u >= p.n_tiles) return;
     uint32_t cc[SUB];
-    bool any_dense = false;
+    uint32_t dmask = 0;  // bit j: sub-tile j keeps no candidate list
 #pragma unroll
-    for (int j = 0; j < SUB; ++j) { cc[j] = p.cand_cnt[(size_t)u * SUB + j]; any_dense |= (cc[j] & DENSE_BIT) != 0u; }
+    for (int j = 0; j < SUB; ++j) { cc[j] = p.cand_cnt[(size_t)u * SUB + j]; dmask |= (cc[j] & DENSE_BIT) ? 1u << j : 0u; }
+    const bool any_dense = dmask != 0u;
     const int t = tile_seg(p, u);
     EmitCtx x;
     x.take = p.ttake[u];
@@ -2225,15 +2279,28 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
                 }
             }
 #pragma unroll
-            for (int r = 0; r < 4; ++r) emit_listed(p, x, iq[r], vq[r], b0 + r * 64 + lane < cnt);
+            for (int r = 0; r < 4; ++r) {
+                if (b0 + r * 64 >= cnt) break;  // (a round that no lane has a candidate for costs as much as a full one)
+                emit_listed(p, x, iq[r], vq[r], b0 + r * 64 + lane < cnt);
+            }
         }
         return;
     }
     // sub-tile by sub-tile
+    __shared__ int32_t stage_idx[LWAVES][TS];   // a sub-tile's part of the message, per wavefront
+    __shared__ float stage_val[LWAVES][TS];
+    int32_t* sidx = stage_idx[threadIdx.x >> 6];
+    float* sval = stage_val[threadIdx.x >> 6];
     const int64_t tile0 = seg_begin(p, t) + (int64_t)(u - seg_tile0(p, t)) * TW;
+    v4f nxt[ROWS];  // the rows of the next sub-tile without a list
+    {
+        const int64_t sn = tile0 + (int64_t)(__ffs((int)dmask) - 1) * TS;
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) nxt[q] = *(const v4f*)(p.acc + sn + q * ROW + 4 * lane);
+    }
     for (int j = 0; j < SUB; ++j) {
-        const uint32_t c = p.cand_cnt[(size_t)u * SUB + j];
-        if (!(c & DENSE_BIT)) {
+        if (!((dmask >> j) & 1u)) {
+            const uint32_t c = p.cand_cnt[(size_t)u * SUB + j];
             for (uint32_t b0 = 0; b0 < c; b0 += 64 * 4) {
                 float vq[4];
                 int32_t iq[4];
@@ -2244,16 +2311,29 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
                     iq[r] = ci[j * TS + (q < c ? q : 0u)];
                 }
 #pragma unroll
-                for (int r = 0; r < 4; ++r) emit_listed(p, x, iq[r], vq[r], b0 + r * 64 + lane < c);
+                for (int r = 0; r < 4; ++r) {
+                    if (b0 + r * 64 >= c) break;
+                    emit_listed(p, x, iq[r], vq[r], b0 + r * 64 + lane < c);
+                }
             }
             continue;
         }
         // a whole, aligned sub-tile that kept acc in the residual (or is the message itself, single-source mode):
-        // four rows of 256 elements, a lane's four consecutive elements at a time
+        // four rows of 256 elements, a lane's four consecutive elements at a time.  Its rows were loaded while the
+        // sub-tile before it was worked on; now the next such sub-tile's loads are issued.
         const int64_t s0 = tile0 + (int64_t)j * TS;
+        uint32_t staged = 0;  // pairs of this sub-tile in LDS so far
         v4f av[ROWS];
 #pragma unroll
-        for (int q = 0; q < ROWS; ++q) av[q] = *(const v4f*)(p.acc + s0 + q * ROW + 4 * lane);
+        for (int q = 0; q < ROWS; ++q) av[q] = nxt[q];
+        {
+            const uint32_t later = dmask & ~((2u << j) - 1u);
+            if (later != 0u) {
+                const int64_t sn = tile0 + (int64_t)(__ffs((int)later) - 1) * TS;
+#pragma unroll
+                for (int q = 0; q < ROWS; ++q) nxt[q] = *(const v4f*)(p.acc + sn + q * ROW + 4 * lane);
+            }
+        }
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) {
             const int64_t g = s0 + q * ROW + 4 * lane;
@@ -2286,22 +2366,18 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
                 pre += lanes_below(m);
                 tot += (uint32_t)__popcll(m);
             }
-            int64_t o = x.pos + pre;
+            // the selected pairs go to their place in the sub-tile's part of the message, in LDS first
+            uint32_t o = staged + pre;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 if (!sel[e]) continue;
-                if (o < x.lim) {
-                    p.out_val[o] = a[e];
-                    if (!p.single) {
-                        p.out_idx[o] = (int32_t)(g + e);
-                    } else {
-                        const int mi = p.map_idx[g + e];
-                        p.out_idx[o] = mi;
-                        if (p.restore && (uint64_t)(int64_t)mi < (uint64_t)p.n_restore) p.restore[mi] = 0.0f;
-                    }
-                } else {
-                    p.status->error = 1;
+                int32_t gi = (int32_t)(g + e);
+                if (p.single) {
+                    gi = p.map_idx[g + e];
+                    if (p.restore && (uint64_t)(int64_t)gi < (uint64_t)p.n_restore) p.restore[gi] = 0.0f;
                 }
+                sidx[o] = gi;
+                sval[o] = a[e];
                 ++o;
             }
             if (!p.single) {
@@ -2310,9 +2386,20 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
                 r.z = sel[2] ? 0.0f : a[2]; r.w = sel[3] ? 0.0f : a[3];
                 *(v4f*)(p.res + g) = r;
             }
-            x.pos += tot;
+            staged += tot;
             x.erun += ties_row;
         }
+        // ... and from there into the message, 64 consecutive pairs per store
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // the wavefront's own LDS writes, read back by other lanes
+        if (x.pos + (int64_t)staged > x.lim) p.status->error = 1;  // cannot happen if the counts are consistent
+        for (uint32_t i = lane; i < staged; i += 64) {
+            if (x.pos + i < x.lim) {   // never write out of range
+                p.out_idx[x.pos + i] = sidx[i];
+                p.out_val[x.pos + i] = sval[i];
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // read before the next sub-tile overwrites them
+        x.pos += staged;
     }
 }
 

@@ -1,5 +1,6 @@
 """GPU parity at the full sizes of the five benchmark configurations, through the C ABI, in the launch
-configuration bench.py times (flat call, caller-owned workspace, default flags).
+configuration bench.py times (flat call, caller-owned workspace, default flags, every call samples its
+thresholds; the step of bench.py is this compress call followed by the W = 8 decompression checked below).
 
 Where the full-sort oracle finishes in well under a minute it is run on the same inputs and compared
 element by element.  Further iterations are checked with properties that hold at any size and that,
@@ -100,12 +101,38 @@ def test_config3_vgg16_cf1000_five_iterations():
             check_properties(res_host + g, idx, val, stats[0, 0], new_res, 138_358, f"config3 it{it}")
         assert st["any_fallback"] == 0
         res_host = new_res
+    # the second half of a bench step: the last message and seven peers' messages (their own gradients, residual
+    # zero) summed into one dense buffer, with the workspace and with the library's static scratch, against the
+    # oracle's double loop
+    from oracle import oracle
+    k = comp.k_total
+    msgs_i, msgs_v = [idx], [val]
+    for w in range(1, 8):
+        scratch = torch.zeros(n, dtype=torch.float32, device="cuda")
+        gi, gv, _, _ = run_gpu(comp, workloads.config3_grad(100 + w, n_conv, n_fc), scratch)
+        msgs_i.append(gi)
+        msgs_v.append(gv)
+        del scratch
+    all_i, all_v = np.concatenate(msgs_i), np.concatenate(msgs_v)
+    want = np.zeros(n, np.float32)
+    oracle.decompress_accumulate(all_i, all_v, [k] * 8, want)
+    di, dv = torch.from_numpy(all_i).cuda(), torch.from_numpy(all_v).cuda()
+    ws = torch.empty(binding.gravac_decompress_workspace_bytes(8, n), dtype=torch.uint8, device="cuda")
+    for how in ("workspace", "static"):
+        dense = torch.zeros(n, dtype=torch.float32, device="cuda")
+        if how == "workspace":
+            binding.gravac_decompress_accumulate(di, dv, [k] * 8, dense, workspace=ws)
+        else:
+            binding.gravac_decompress_accumulate_static(di, dv, [k] * 8, dense)
+        torch.cuda.synchronize()
+        assert np.array_equal(dense.cpu().numpy().view(np.uint32), want.view(np.uint32)), how
+        del dense
 
 
 def test_vgg16_shape_dense_selection_with_the_larger_sample():
     """CF 10 on the VGG16-shaped gradient: k n is large enough for the flat sampling pass to take its larger
-    sample (eight groups per thread).  Two iterations without threshold reuse, so both run that sampling pass;
-    a second CF rides along and is committed in the second iteration."""
+    sample (four groups per thread), and the conv part's sub-tiles are mostly candidates (no candidate list: the
+    emit step reads them again).  Two iterations; a second CF rides along and is committed in the second."""
     n = workloads.VGG16_N_CONV + workloads.VGG16_N_FC
     cfs = [10.0, 1000.0]
     res_t = torch.zeros(n, device="cuda")

@@ -87,7 +87,8 @@ constexpr uint32_t SKEY0 = 79u << 23;
 static_assert((uint64_t)SKEY0 + ((uint64_t)SBIN << SSHIFT) <= 0x7F800000ull, "the window lies inside the finite keys");
 constexpr int SGRP = 8;             // the sample bins in SGRP groups: one workgroup of the threshold kernel each
 constexpr int SAMPLE_BLOCK = 1024;  // samples per workgroup of the sampling kernel
-constexpr int SAMPLE_MAX = 65536;   // samples per segment at most (unless the segment is read whole)
+constexpr int SAMPLE_MAX = 65536;   // samples of a flat tensor at most (unless k n is large, see SAMPLE_MAX_FLAT)
+constexpr int SAMPLE_MAX_SEG = 32768;  // layerwise: samples per tensor at most (a tensor of up to twice that is read whole)
 constexpr int SAMPLE_MAX_FLAT = 524288;  // flat mode, a large k: see sample_count
 constexpr int DENSE_ROUNDS = 4;          // ... whose sample blocks are up to DENSE_ROUNDS * SAMPLE_BLOCK samples each
 constexpr int DENSE_BLOCKS = 128;        // ... so that there are at most this many of them
@@ -154,7 +155,9 @@ struct SegInfo {
     uint32_t samp0;          // first sample block
     uint32_t samp_cnt;       // samples taken
     uint32_t small;          // 1: at most SMALL_MAX elements, handled by one workgroup out of LDS: no tiles, no samples
-    uint32_t pad[5];
+    uint32_t rep;            // copies of the segment's bracket histograms and gather lists: REP for a large tensor, else 1
+    uint32_t pool0;          // its first copy block in hist1 / list_* / list_cnt (n_cf * rep consecutive blocks, CF-major)
+    uint32_t pad[3];
 };
 static_assert(sizeof(SegInfo) == 64, "SegInfo layout");
 
@@ -195,15 +198,15 @@ struct Params {
     SegState* seg;       // [n_seg]
     uint32_t* bnd_lo;    // [n_seg][n_cf] the bracket of every CF as the threshold kernel found it: first key ...
     uint32_t* bnd_hi;    // [n_seg][n_cf] ... and one past its last key (at most KEY_END)
-    uint32_t* hist1;     // [n_seg][n_cf][REP][NBIN] bracket histogram, REP copies
+    uint32_t* hist1;     // [copy blocks][NBIN] bracket histograms: REP copies per CF of a large tensor, one otherwise
     uint32_t* ovfc;      // [n_seg][n_cf][64][32] counts above the bracket (the histogram's last bin), spread over
                          // 64 cache lines; word 0 of each line is used
     uint32_t* hist2;     // [n_seg][n_cf][NBIN] refine histogram
     uint32_t* coarse;    // [n_seg][NBIN] histogram of key >> 20 (exact route)
-    uint32_t* list_key;  // [n_seg][n_cf][REP][LCAP] gather lists, REP copies: key ...
+    uint32_t* list_key;  // [copy blocks][LCAP] gather lists: key ...
     uint32_t* list_tile; //                          ... tile ...
     float* list_val;     //                          ... and value (written for Random-k only) of the listed entries
-    uint32_t* list_cnt;  // [n_seg][n_cf][REP][32] fill counts of the gather lists, one cache line each
+    uint32_t* list_cnt;  // [copy blocks][32] fill counts of the gather lists, one cache line each
     uint32_t* samp_hist; // [n_sample_blocks][SBIN / 2] sample histograms, two 16-bit counts per word
     uint32_t* samp_grp;  // [n_sample_blocks][SGRP] samples per group of SBIN / SGRP bins
     uint32_t* cand_cnt;  // [n_tiles][SUB] listed candidates of every sub-tile (| DENSE_BIT: none listed, the sub-tile is read again)
@@ -242,6 +245,13 @@ __device__ __forceinline__ uint32_t seg_k(const Params& p, int t, int j) { retur
 __device__ __forceinline__ int64_t seg_koff(const Params& p, int t) { return is_flat(p) ? 0 : p.segs[t].koff; }
 __device__ __forceinline__ int tile_seg(const Params& p, uint32_t u) { return is_flat(p) ? 0 : (int)p.tseg[u]; }
 __device__ __forceinline__ bool seg_small(const Params& p, int t) { return !is_flat(p) && p.segs[t].small != 0u; }
+// Copy blocks: one holds a copy of a (segment, CF)'s bracket histogram (NBIN words of hist1), a gather list (LCAP
+// slots of list_*) and its fill count (a cache line of list_cnt).  Copy r of (t, j) is block seg_block(p, t, j) + r.
+__device__ __forceinline__ uint32_t seg_rep(const Params& p, int t) { return is_flat(p) ? (uint32_t)REP : p.segs[t].rep; }
+__device__ __forceinline__ size_t seg_block(const Params& p, int t, int j)
+{
+    return is_flat(p) ? (size_t)j * REP : (size_t)p.segs[t].pool0 + (size_t)j * p.segs[t].rep;
+}
 
 __device__ __forceinline__ uint32_t key_of(float a) { return __float_as_uint(a) & 0x7FFFFFFFu; }
 
@@ -783,12 +793,13 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
         const uint32_t per = SAMPLE_BLOCK * R;
         const uint32_t nbk = is_flat(p) ? p.n_sample_blocks : (S + per - 1) / per;
         const uint4 z = make_uint4(0u, 0u, 0u, 0u);
-        uint4* h1 = (uint4*)(p.hist1 + (size_t)t * p.n_cf * REP * NBIN);
-        for (uint32_t i = lb * 256 + tid; i < (uint32_t)p.n_cf * REP * NBIN / 4; i += nbk * 256) h1[i] = z;
+        const uint32_t blocks = (uint32_t)p.n_cf * seg_rep(p, t);  // the segment's copy blocks
+        uint4* h1 = (uint4*)(p.hist1 + seg_block(p, t, 0) * NBIN);
+        for (uint32_t i = lb * 256 + tid; i < blocks * NBIN / 4; i += nbk * 256) h1[i] = z;
         uint4* cs = (uint4*)(p.coarse + (size_t)t * NBIN);
         for (uint32_t i = lb * 256 + tid; i < NBIN / 4; i += nbk * 256) cs[i] = z;
         for (uint32_t i = lb * 256 + tid; i < (uint32_t)p.n_cf * 64; i += nbk * 256) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
-        for (uint32_t i = lb * 256 + tid; i < (uint32_t)p.n_cf * REP; i += nbk * 256) p.list_cnt[((size_t)t * p.n_cf * REP + i) * 32] = 0;
+        for (uint32_t i = lb * 256 + tid; i < blocks; i += nbk * 256) p.list_cnt[(seg_block(p, t, 0) + i) * 32] = 0;
     }
     if (p.bounds_from != BOUNDS_SAMPLED) return;
     const int64_t s0 = seg_begin(p, t);
@@ -1020,7 +1031,8 @@ struct SubCtx {
     uint32_t ovn[NCF];     // entries above CF j's bracket ...
     double ovs[NCF];       // ... and their sum of acc^2
     bool split;            // the entries inside the brackets get a list of their own in every sub-tile
-    uint32_t* h1;   // this wavefront's copy of the bracket histograms of the tile's segment (CF stride REP*NBIN)
+    uint32_t* h1;   // this wavefront's copy of the bracket histograms of the tile's segment ...
+    uint32_t hstride;  // ... whose CFs are this many words apart
     int32_t* cidx;  // candidate-list slots of this sub-tile
     float* cval;
     uint32_t run;   // candidates listed so far
@@ -1046,7 +1058,7 @@ __device__ __forceinline__ bool bracket_count(SubCtx<NCF>& c, uint32_t key, floa
                 c.ovn[j]++;
                 c.ovs[j] += d * d;
             } else {
-                atomicAdd(&c.h1[j * REP * NBIN + ((key - c.lo[j]) >> c.sh[j])], 1u);
+                atomicAdd(&c.h1[j * c.hstride + ((key - c.lo[j]) >> c.sh[j])], 1u);
                 inside = true;
             }
         }
@@ -1297,7 +1309,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                         if (!narrow) st->top = xb->end[j];
                     }
                     for (int i = lane; i < NBIN; i += 64) p.hist2[((size_t)t * p.n_cf + j) * NBIN + i] = 0;
-                    if (lane < REP) p.list_cnt[(((size_t)t * p.n_cf + j) * REP + lane) * 32] = 0;
+                    if (lane < (int)seg_rep(p, t)) p.list_cnt[(seg_block(p, t, j) + lane) * 32] = 0;
                 }
             }
         }
@@ -1306,7 +1318,8 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
     }
     // the copy of the histogram this wavefront adds to: spread by the sub-tile number, and by the tile number too,
     // because the narrow route's re-binning calls arrive with v = 8 u only
-    c.h1 = p.hist1 + ((size_t)t * p.n_cf * REP + ((v ^ (v / SUB)) & (REP - 1))) * NBIN;
+    c.hstride = seg_rep(p, t) * NBIN;
+    c.h1 = p.hist1 + (seg_block(p, t, 0) + ((v ^ (v / SUB)) & (seg_rep(p, t) - 1u))) * NBIN;
     c.cidx = p.cand_idx + (size_t)v * TS;
     c.cval = p.cand_val + (size_t)v * TS;
     c.bkey = p.brk_key + (size_t)v * TS;
@@ -1339,7 +1352,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                 for (int j = 0; j < NCF; ++j) {
                     if (j < c.ncf && kq[q] >= c.lo[j] && kq[q] < xb->top[j]) {
                         if (kq[q] >= c.top[j]) c.ovn[j]++;
-                        else atomicAdd(&c.h1[j * REP * NBIN + ((kq[q] - c.lo[j]) >> c.sh[j])], 1u);
+                        else atomicAdd(&c.h1[j * c.hstride + ((kq[q] - c.lo[j]) >> c.sh[j])], 1u);
                     }
                 }
             }
@@ -1530,7 +1543,7 @@ __global__ __launch_bounds__(WG) void coarse_kernel(Params p)
                     const int64_t s0 = sb + (int64_t)(u - seg_tile0(p, t)) * TW;
                     const int64_t e0 = (s0 + TW < se) ? s0 + TW : se;
                     if (u == seg_tile0(p, t)) {
-                        for (int i = lane; i < p.n_cf * REP * NBIN; i += 64) p.hist1[(size_t)t * p.n_cf * REP * NBIN + i] = 0;
+                        for (uint32_t i = lane; i < (uint32_t)p.n_cf * seg_rep(p, t) * NBIN; i += 64) p.hist1[seg_block(p, t, 0) * NBIN + i] = 0;
                         for (int i = lane; i < p.n_cf * 64; i += 64) p.ovfc[((size_t)t * p.n_cf * 64 + i) * 32] = 0;
                     }
                     const uint32_t pz = p.single ? NONE : p.seg[t].pz;
@@ -1614,7 +1627,8 @@ __global__ __launch_bounds__(256) void locate_kernel(Params p)
     uint32_t s, top;
     bracket_bins(lo, p.bnd_hi[id], s, top);
     uint32_t b, above, c;
-    team_locate_bin(p.hist1 + (size_t)id * REP * NBIN, REP, p.ovfc + (size_t)id * 64 * 32, k, tid, scratch,
+    const uint32_t copies = seg_rep(p, t);
+    team_locate_bin(p.hist1 + seg_block(p, t, j) * NBIN, (int)copies, p.ovfc + (size_t)id * 64 * 32, k, tid, scratch,
                     [] { __syncthreads(); }, b, above, c);
     const BinPlan q = plan_bin(lo, s, b, above, c);
     if (q.mode == MODE_HIST)
@@ -1624,7 +1638,7 @@ __global__ __launch_bounds__(256) void locate_kernel(Params p)
         // a bin 2^s keys wide (s > 11) with more than LCAP keys: XBINS bins of 2^(s - 10) keys cover it, and a
         // bin at most 2^10 keys wide can always be resolved (gathered or histogrammed key by key); this CF's
         // histogram is rebuilt by the exact route, the count above the bracket stays
-        for (int i = tid; i < REP * NBIN; i += 256) p.hist1[(size_t)id * REP * NBIN + i] = 0;
+        for (uint32_t i = tid; i < copies * NBIN; i += 256) p.hist1[seg_block(p, t, j) * NBIN + i] = 0;
     }
     if (tid == 0) {
         st->k = k; st->lo = lo; st->s = s; st->top = top;
@@ -1708,7 +1722,7 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
                     continue;
                 }
                 uint32_t b, above, c;
-                wave_locate_bin(p.hist1 + ((size_t)t * p.n_cf + j) * REP * NBIN, REP, p.ovfc + ((size_t)t * p.n_cf + j) * 64 * 32,
+                wave_locate_bin(p.hist1 + seg_block(p, t, j) * NBIN, (int)seg_rep(p, t), p.ovfc + ((size_t)t * p.n_cf + j) * 64 * 32,
                                 st->k, b, above, c);
                 const BinPlan q = plan_bin(st->lo, st->s, b, above, c);
                 if (lane == 0) {
@@ -1749,7 +1763,7 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
                     // one counter update per wavefront: the lanes with a key in the bin take consecutive slots
                     const uint64_t m = __ballot(in);
                     if (m != 0ull) {
-                        const size_t lst = ((size_t)t * p.n_cf + j) * REP + (blockIdx.x & (REP - 1));
+                        const size_t lst = seg_block(p, t, j) + (blockIdx.x & (seg_rep(p, t) - 1u));
                         const int leader = __ffsll((unsigned long long)m) - 1;
                         uint32_t at = 0;
                         if (lane == leader) at = atomicAdd(&p.list_cnt[lst * 32], (uint32_t)__popcll(m));
@@ -1852,9 +1866,11 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
 
     // ---- loads that do not depend on the threshold come first, so that they overlap with its resolution
     // the fill counts of the gather lists and the plan
+    const uint32_t copies = seg_rep(p, t);
+    const size_t block0 = seg_block(p, t, j);
     uint32_t fill[REP];
 #pragma unroll
-    for (int r = 0; r < REP; ++r) fill[r] = p.list_cnt[((size_t)id * REP + r) * 32];
+    for (int r = 0; r < REP; ++r) fill[r] = (uint32_t)r < copies ? p.list_cnt[(block0 + r) * 32] : 0u;
     const uint32_t mode = st->mode, k = st->k, above = st->above, base = st->base, span = st->span, c = st->c;
     uint32_t tau = st->tau, need = st->need, cnt_gt = st->cnt_gt;   // valid if the located bin was one key wide
     // scan: this slice, coalesced (entries above the located bin, entries inside it), and the totals of the
@@ -1942,7 +1958,7 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
                 uint32_t o = 0;
 #pragma unroll
                 for (int x = 0; x < REP; ++x) if (x == r) o = off[x];
-                const size_t at = ((size_t)id * REP + r) * LCAP + (i - o);
+                const size_t at = (block0 + r) * LCAP + (i - o);
                 d[q] = p.list_key[at];
                 rt[q] = p.list_tile[at];
                 rv[q] = p.random ? p.list_val[at] : 0.0f;
@@ -2815,9 +2831,27 @@ uint64_t max_sample_blocks(int64_t n, int n_seg)
 {
     static_assert(DENSE_BLOCKS * SAMPLE_BLOCK <= 2 * SAMPLE_MAX && SAMPLE_MAX_FLAT <= DENSE_BLOCKS * SAMPLE_BLOCK * DENSE_ROUNDS,
                   "the blocks of a dense sample fit as well");
-    const uint64_t a = (uint64_t)n_seg * (2 * SAMPLE_MAX / SAMPLE_BLOCK);
+    const uint64_t a = (uint64_t)n_seg * (2 * (n_seg > 1 ? SAMPLE_MAX_SEG : SAMPLE_MAX) / SAMPLE_BLOCK);
     const uint64_t b = (uint64_t)((n + SAMPLE_BLOCK - 1) / SAMPLE_BLOCK) + (uint64_t)n_seg;
     return a < b ? a : b;
+}
+
+// Copy blocks of the bracket histograms and gather lists.  Global atomics on one cache line queue up, so a large
+// tensor spreads them over REP copies (with one copy the streaming pass of the 314-tensor ResNet list takes 120
+// instead of 97 us); a small tensor puts so few entries into its brackets that fewer do: 1 below 2^17 elements, then
+// 2, 4 and from 2^19 elements on REP.  A flat call always takes REP.  A tensor's copies number at most
+// 1 + nt / 2^16, which bounds a layerwise call's total by n_seg + n / 2^16.
+uint32_t seg_copies(int64_t nt, bool flat)
+{
+    static_assert(REP == 8, "1, 2, 4, 8 copies");
+    if (flat || nt >= (1 << 19)) return REP;
+    return nt >= (1 << 18) ? 4u : nt >= (1 << 17) ? 2u : 1u;
+}
+size_t pool_blocks(int64_t n, int n_cf, int n_seg)
+{
+    if (n_seg <= 1) return (size_t)n_cf * REP;
+    const size_t graded = (size_t)n_seg + (size_t)(n >> 16), all = (size_t)n_seg * REP;
+    return (size_t)n_cf * (graded < all ? graded : all);
 }
 
 Layout make_layout(int64_t n, int n_cf, int n_seg)
@@ -2836,14 +2870,15 @@ Layout make_layout(int64_t n, int n_cf, int n_seg)
     L.seg = take(sizeof(SegState) * n_seg);
     L.bnd_lo = take(sizeof(uint32_t) * sc);
     L.bnd_hi = take(sizeof(uint32_t) * sc);
-    L.hist1 = take(sizeof(uint32_t) * sc * REP * NBIN);
+    const size_t blocks = pool_blocks(n, n_cf, n_seg);
+    L.hist1 = take(sizeof(uint32_t) * blocks * NBIN);
     L.ovfc = take(sizeof(uint32_t) * sc * 64 * 32);
     L.hist2 = take(sizeof(uint32_t) * sc * NBIN);
     L.coarse = take(sizeof(uint32_t) * (size_t)n_seg * NBIN);
-    L.list_key = take(sizeof(uint32_t) * sc * REP * LCAP);
-    L.list_tile = take(sizeof(uint32_t) * sc * REP * LCAP);
-    L.list_val = take(sizeof(float) * sc * REP * LCAP);
-    L.list_cnt = take(sizeof(uint32_t) * sc * REP * 32);
+    L.list_key = take(sizeof(uint32_t) * blocks * LCAP);
+    L.list_tile = take(sizeof(uint32_t) * blocks * LCAP);
+    L.list_val = take(sizeof(float) * blocks * LCAP);
+    L.list_cnt = take(sizeof(uint32_t) * blocks * 32);
     L.samp_hist = take(sizeof(uint32_t) * nsb * (SBIN / 2));
     L.samp_grp = take(sizeof(uint32_t) * nsb * SGRP);
     L.cand_cnt = take(sizeof(uint32_t) * nt * SUB);
@@ -2875,7 +2910,8 @@ uint32_t sample_count(uint64_t nt, double cf_min, double cf_max, bool flat)
     uint64_t target = flat ? (uint64_t)SAMPLE_MAX : (uint64_t)(32.0 * std::ceil(cf_max));
     if (!flat && target < nt / 64) target = nt / 64;
     if (target < 4096) target = 4096;
-    if (target > (uint64_t)SAMPLE_MAX) target = SAMPLE_MAX;
+    const uint64_t cap = flat ? SAMPLE_MAX : SAMPLE_MAX_SEG;
+    if (target > cap) target = cap;
     if (flat) {
         // The bracket spans about 10 standard deviations of a sampled rank, which is 10 sqrt(k nt / m) of the tensor's
         // entries for m samples, and every entry inside it costs the streaming pass a device-wide atomic (about
@@ -3168,13 +3204,14 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         p.small_list = p.sblock_seg + p.n_sample_blocks;
         p.n_small = n_small;
         int64_t koff = 0;
-        uint32_t tile_at = 0, sb_at = 0, small_at_ = 0;
+        uint32_t tile_at = 0, sb_at = 0, small_at_ = 0, block_at = 0;
         for (int t = 0; t < ns; ++t) {
             const int64_t nt = seg_offsets[t + 1] - seg_offsets[t];
             SegInfo& g = segs[t];
             std::memset(&g, 0, sizeof(g));
             g.begin = seg_offsets[t]; g.end = seg_offsets[t + 1]; g.koff = koff;
             g.tile0 = g.tile1 = tile_at; g.samp0 = sb_at;
+            g.rep = seg_copies(nt, false); g.pool0 = block_at; block_at += (uint32_t)n_cf * g.rep;
             if (small_ok && nt <= SMALL_MAX) {
                 g.small = 1;
                 small_list[small_at_++] = (uint32_t)t;

@@ -452,3 +452,55 @@ int oracle_randomk_compress(const float* grad, float* residual, int64_t n,
     if (out_count) *out_count = written;
     return ORACLE_OK;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Threshold sparsifier with error feedback.  Sec. II-C describes DGC's selection rule in one clause:
+ * entries below a threshold are discarded; its momentum correction and gradient clipping are named
+ * there but not defined, and are not part of this.  Steps:
+ *   acc = residual + grad                      (Sec. III-B error feedback, as for every compressor)
+ *   keep entry i  <=>  |acc[i]| >= tau         (Sec. II-C, DGC: what lies below the threshold is dropped)
+ *   message = the kept (index, acc) pairs in ascending index order; residual = acc with the kept slots
+ *   set to +0.0f (Alg. 1 residual update); gain = ||message||^2 / ||acc||^2 (Sec. III-B), 1 if 0 / 0.
+ * Readings: "below" is strict, so an entry equal to tau is kept; magnitudes are compared as bit
+ * patterns with the sign cleared, as everywhere in this file (a NaN pattern ranks above every finite
+ * tau and is kept); tau is a positive, finite binary32 number.  The number of kept entries is data
+ * dependent: *out_count always gets it; if it exceeds out_capacity nothing is emitted or removed
+ * (the residual holds acc), the statistics are still those of the full selection, and the function
+ * returns ORACLE_CAPACITY.  out_stats = { ||g_c||^2, ||g_ef||^2, gain, tau }.
+ * ------------------------------------------------------------------------------------------------ */
+int oracle_threshold_compress(const float* grad, float* residual, int64_t n, float tau,
+                              int32_t* out_idx, float* out_val, int64_t out_capacity,
+                              int64_t* out_count, double* out_stats)
+{
+    if (!grad || !residual || !out_count || !out_stats || n <= 0 || n > 2147483647LL) return ORACLE_BAD_ARG;
+    if (!(tau > 0.0f) || isinf(tau)) return ORACLE_BAD_ARG;
+    if (out_capacity > 0 && (!out_idx || !out_val)) return ORACLE_BAD_ARG;
+    const uint32_t tau_bits = f32_bits(tau);
+    double ss_dense = 0.0, ss_sel = 0.0;
+    int64_t kept = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float a = residual[i] + grad[i];
+        residual[i] = a;
+        ss_dense += (double)a * (double)a;
+        if ((f32_bits(a) & 0x7FFFFFFFu) >= tau_bits) {
+            ss_sel += (double)a * (double)a;
+            ++kept;
+        }
+    }
+    out_stats[0] = ss_sel;
+    out_stats[1] = ss_dense;
+    out_stats[2] = (ss_dense == 0.0) ? 1.0 : ss_sel / ss_dense;
+    out_stats[3] = (double)tau;
+    *out_count = kept;
+    if (kept > out_capacity) return ORACLE_CAPACITY;
+    int64_t w = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if ((f32_bits(residual[i]) & 0x7FFFFFFFu) >= tau_bits) {
+            out_idx[w] = (int32_t)i;
+            out_val[w] = residual[i];
+            residual[i] = 0.0f;
+            ++w;
+        }
+    }
+    return ORACLE_OK;
+}

@@ -55,6 +55,8 @@ def _load():
         lib.oracle_randomk_priority.argtypes = [ctypes.c_uint64, ctypes.c_uint32]
         lib.oracle_randomk_compress.restype = i32
         lib.oracle_randomk_compress.argtypes = [p, p, i64, p, i32, i32, ctypes.c_uint64, p, i32, p, p, i64, p, p]
+        lib.oracle_threshold_compress.restype = i32
+        lib.oracle_threshold_compress.argtypes = [p, p, i64, ctypes.c_float, p, p, i64, p, p]
         lib.oracle_recompress.restype = i32
         lib.oracle_recompress.argtypes = [p, p, i64, dbl, p, i64, p, i32, p, p, i64, p, p]
         _lib = lib
@@ -199,3 +201,28 @@ def randomk_compress(grad: np.ndarray, residual: np.ndarray, cf_list, seed: int,
         raise RuntimeError(f"oracle_randomk_compress failed with code {rc}")
     assert count.value == cap
     return idx, val, stats
+
+
+def threshold_compress(grad: np.ndarray, residual: np.ndarray, tau: float, capacity=None):
+    """Threshold sparsifier with error feedback (Sec. II-C, the selection rule given for DGC): keep |acc| >= tau.
+
+    ``residual`` is updated IN PLACE.  Returns ``(idx, val, stats float64[4], count)``; a stats row is
+    ``(||g_c||^2, ||g_ef||^2, gain, tau)``.  With ``capacity`` smaller than the number of kept entries the message
+    is empty (``idx.size == 0``), the residual holds acc and ``count`` still says how many would have been kept.
+    """
+    lib = _load()
+    assert grad.dtype == np.float32 and residual.dtype == np.float32
+    assert grad.flags.c_contiguous and residual.flags.c_contiguous and residual.size == grad.size
+    n = grad.size
+    cap = n if capacity is None else int(capacity)
+    idx = np.empty(cap, dtype=np.int32)
+    val = np.empty(cap, dtype=np.float32)
+    stats = np.zeros(4, dtype=np.float64)
+    count = ctypes.c_int64(0)
+    rc = lib.oracle_threshold_compress(_ptr(grad), _ptr(residual), n, ctypes.c_float(tau), _ptr(idx), _ptr(val), cap,
+                                       ctypes.byref(count), _ptr(stats))
+    if rc == -2:                              # capacity: nothing emitted
+        return idx[:0], val[:0], stats, int(count.value)
+    if rc != 0:
+        raise RuntimeError(f"oracle_threshold_compress failed with code {rc}")
+    return idx[:count.value].copy(), val[:count.value].copy(), stats, int(count.value)

@@ -142,6 +142,30 @@ int gravac_randomk_compress(const float* grad, float* residual, int64_t n,
                             unsigned flags, void* stream);
 
 /*
+ * Threshold sparsifier with error feedback: what Sec. II-C says of DGC's selection, entries below a threshold are
+ * discarded (DGC's momentum correction and gradient clipping are named there but not defined, and are not part of
+ * this).  acc = residual + grad (Sec. III-B); entry i is kept iff |acc[i]| >= tau, magnitudes compared as bit
+ * patterns with the sign cleared, so an entry equal to tau is kept and a NaN ranks above every tau; the message is
+ * the kept (index, acc) pairs in ascending index order, the residual acc with the kept slots set to +0.0f (Alg. 1),
+ * the gain ||message||^2 / ||acc||^2 (1 if 0 / 0).  One flat tensor.
+ *
+ *   grad, residual, n   as for gravac_compress.
+ *   tau            positive and finite.
+ *   out_idx, out_val   device, int32 / float [out_capacity] (may be NULL if out_capacity is 0).
+ *   out_capacity   >= 0.  The number of kept entries depends on the data: if it exceeds out_capacity NOTHING is
+ *                  emitted and nothing is removed (the residual holds acc), while out_count and out_stats still
+ *                  describe the full selection; the caller sees out_count > out_capacity and calls again with
+ *                  larger buffers (on the residual as it is, with a zero gradient) or a higher tau.
+ *   out_count      device, int64 scalar, required: the number of entries at or above tau.
+ *   out_stats      device, double[4]: { ||g_c||^2, ||g_ef||^2, gain, tau }.
+ *   workspace      device, 256-byte aligned, at least gravac_workspace_bytes(n, 1, 0) bytes.
+ */
+int gravac_threshold_compress(const float* grad, float* residual, int64_t n, float tau,
+                              int32_t* out_idx, float* out_val, int64_t out_capacity,
+                              int64_t* out_count, double* out_stats,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Multi-level compression (Sec. IV-C): the second-level Top-k.  Given the level-1 message
  * (idx1, val1) that gravac_compress emitted at CF theta1, select the k2 = ceil(k1 / cf_rel) entries of
  * largest |val1| (ties to the lower index, i.e. the earlier position), which is the message a direct

@@ -27,7 +27,7 @@ MAX_CF = 8
 FLAG_FORCE_FALLBACK = 1
 
 EXPORTS = (
-    "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_compress_profiled", "gravac_randomk_compress", "gravac_recompress", "gravac_commit",
+    "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_compress_profiled", "gravac_randomk_compress", "gravac_threshold_compress", "gravac_recompress", "gravac_commit",
     "gravac_decompress_workspace_bytes", "gravac_decompress_accumulate", "gravac_decompress_accumulate_static",
     "gravac_read_status", "gravac_strerror",
     "gravac_controller_create", "gravac_controller_destroy", "gravac_controller_candidates",
@@ -91,6 +91,8 @@ def lib() -> ctypes.CDLL:
         L.gravac_randomk_compress.restype = i32
         L.gravac_randomk_compress.argtypes = [vp, vp, i64, vp, i32, i32, ctypes.c_uint64, vp, i32, vp, vp, i64, vp, vp, vp,
                                               ctypes.c_size_t, u32, vp]
+        L.gravac_threshold_compress.restype = i32
+        L.gravac_threshold_compress.argtypes = [vp, vp, i64, ctypes.c_float, vp, vp, i64, vp, vp, vp, ctypes.c_size_t, vp]
         L.gravac_recompress.restype = i32
         L.gravac_recompress.argtypes = [vp, vp, i64, dbl, vp, i32, vp, i64, vp, vp, i64, vp, vp, vp,
                                         ctypes.c_size_t, u32, vp]
@@ -214,6 +216,17 @@ def gravac_randomk_compress(grad, residual, cf_list, seed, commit=0, seg_offsets
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), int(flags), _stream_handle(stream))
     if rc != OK:
         raise GravacError(rc, "gravac_randomk_compress")
+
+
+def gravac_threshold_compress(grad, residual, tau, *, out_idx, out_val, out_count, out_stats, workspace, stream=None) -> None:
+    """``gravac_threshold_compress`` of the C ABI on torch device tensors (asynchronous on ``stream``)."""
+    rc = lib().gravac_threshold_compress(
+        _dev_ptr(grad, torch.float32), _dev_ptr(residual, torch.float32), grad.numel(), ctypes.c_float(tau),
+        _dev_ptr(out_idx, torch.int32), _dev_ptr(out_val, torch.float32), out_idx.numel(),
+        _dev_ptr(out_count, torch.int64), _dev_ptr(out_stats, torch.float64),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if rc != OK:
+        raise GravacError(rc, "gravac_threshold_compress")
 
 
 def gravac_recompress(idx1, val1, cf_rel, seg_counts=None, residual=None, *, out_idx, out_val, out_count=None,

@@ -105,7 +105,8 @@ enum : uint32_t { MODE_RESOLVED = 0, MODE_GATHER = 1, MODE_HIST = 2, MODE_FAIL =
 //   FAIL_FULL    the k-th largest lies outside the bracket (or there was none): acc is read again.
 enum : uint32_t { FAIL_NONE = 0, FAIL_NARROW = 1, FAIL_FULL = 3 };
 // where a call's brackets come from
-enum : uint32_t { BOUNDS_SAMPLED = 0, BOUNDS_RANDOM = 1, BOUNDS_FORCED = 2 };
+enum : uint32_t { BOUNDS_SAMPLED = 0, BOUNDS_RANDOM = 1, BOUNDS_FORCED = 2,
+                  BOUNDS_FIXED = 3 };  // the threshold sparsifier: the caller gives the threshold, nothing is searched for
 
 // Selection state of one (segment, CF).
 struct CfState {
@@ -141,7 +142,8 @@ struct Status {
     int error;
     int n_seg;
     int n_narrow;             // segments of n_fail that were only binned again from their bracket lists
-    int pad[3];
+    int count;                // threshold sparsifier: entries at or above the threshold (written by the scan)
+    int pad[2];
 };
 
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -174,6 +176,7 @@ struct Params {
     int split;               // 1 if the committed CF is not the lowest of the list: the entries inside the brackets then get a
                              // list of their own everywhere; 0: a sub-tile's candidate list, where it has one, holds them all
     uint32_t bounds_from;    // BOUNDS_*
+    uint32_t fixed_key;      // BOUNDS_FIXED: the key of the caller's threshold; entries with key >= fixed_key are kept
     uint32_t rk_s0, rk_s1;   // Random-k: the two 31-bit keys (from the seed)
     int64_t n;
     int n_seg;  // >= 1
@@ -274,6 +277,7 @@ __device__ __forceinline__ void bracket_bins(uint32_t lo, uint32_t hi, uint32_t&
 {
     const uint32_t span = hi > lo ? hi - lo : 0u;
     s = 0;
+    if (span == 0u) { top = lo; return; }  // an empty bracket: every key from lo on counts as above it
     while ((span >> s) > OVF - 1u) ++s;
     const uint64_t t = (uint64_t)lo + ((uint64_t)OVF << s);
     top = t >= (uint64_t)KEY_END ? KEY_END : (uint32_t)t;
@@ -894,8 +898,8 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
     const int t = blockIdx.x, y = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
     if (t == 0 && y == 0 && tid == 0) {
         p.status->any_fail = 0; p.status->n_fail = 0; p.status->error = 0; p.status->n_seg = p.n_seg;
-        p.status->n_narrow = 0;
-        if (p.out_count) *p.out_count = p.total_out;
+        p.status->n_narrow = 0; p.status->count = 0;
+        if (p.out_count && p.bounds_from != BOUNDS_FIXED) *p.out_count = p.total_out;  // (else the scan knows it)
     }
     if constexpr (SMALL) {
         static_assert(G == 1 && SM_T == 1024, "the small tensors' workgroups are this kernel's");
@@ -929,6 +933,23 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
             r_hi = (b < 1.0) ? 1u : (uint32_t)b;
         }
         rank_lo[tid] = r_lo; rank_hi[tid] = r_hi;
+    }
+    if (p.bounds_from == BOUNDS_FIXED) {
+        // the threshold sparsifier (one flat tensor, one "CF"): an empty bracket at the caller's threshold, so that the
+        // pass over the gradient counts and lists what lies at or above it; the later steps find everything resolved:
+        // selected <=> key > tau with tau one key below the threshold, no ties to take
+        if (tid == 0) {
+            p.bnd_lo[0] = p.fixed_key; p.bnd_hi[0] = p.fixed_key;
+            CfState st;
+            st.k = 0; st.lo = p.fixed_key; st.s = 0; st.mode = MODE_RESOLVED; st.base = p.fixed_key; st.span = 0;
+            st.above = 0; st.c = 0; st.tau = p.fixed_key - 1u; st.need = 0; st.cnt_gt = 0; st.redo = 0; st.lo2 = 0; st.s2 = 0;
+            st.top = p.fixed_key; st.pad = 0;
+            p.st[0] = st;
+            SegState sg;
+            sg.lo_min = p.fixed_key; sg.fail = FAIL_NONE; sg.pz = p.single ? NONE : p.fixed_key; sg.lo_c = p.fixed_key;
+            p.seg[0] = sg;
+        }
+        return;
     }
     if (!sampled) {
         // no sample: the brackets follow from k alone (Random-k) or are left empty (every segment takes the exact route)
@@ -2098,6 +2119,12 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
             const uint32_t u = slice0 + tid * SCAN_PER + i;
             if (u < u1) p.tsel[u] = g[i] + tk[i];
         }
+        // threshold sparsifier: how many entries are kept is only known here (the last thread of the last slice has
+        // counted them all); the emit step emits them if they fit the caller's buffers
+        if (p.bounds_from == BOUNDS_FIXED && tid == SCAN_T - 1 && slice0 + SCAN_SLICE >= u1) {
+            p.status->count = (int)run_g;
+            if (p.out_count) *p.out_count = (int64_t)run_g;
+        }
 #pragma unroll
         for (int i = 0; i < SCAN_PER; ++i) {
             sg[tid * SCAN_PER + i] = off[i];
@@ -2189,7 +2216,7 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
         o[0] = ss_sel;
         o[1] = ss_dense;
         o[2] = (ss_dense == 0.0) ? 1.0 : ss_sel / ss_dense;
-        o[3] = tauv;
+        o[3] = p.bounds_from == BOUNDS_FIXED ? (double)__uint_as_float(p.fixed_key) : tauv;
         if (j != p.commit) { st->tau = tau; st->need = need; st->cnt_gt = cnt_gt; }
     }
 }
@@ -2255,6 +2282,12 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
     // not, which can only be when the threshold turned out to lie at or above pz.
     x.pz = (p.single || p.seg[t].fail == FAIL_FULL) ? NONE : p.seg[t].pz;
     x.put_back = x.pz != NONE && x.tau >= x.pz;
+    if (p.bounds_from == BOUNDS_FIXED && (int64_t)p.status->count > p.total_out) {
+        // threshold sparsifier, more entries kept than the caller's buffers hold: nothing is emitted and nothing removed.
+        // The listed sub-tiles get back the values the pass replaced by +0; the others kept acc.
+        for (int j = 0; j < SUB; ++j) put_back_subtile(p, u * SUB + j, x.pz, lane);
+        return;
+    }
     if (p.tsel[u] == 0 && !x.put_back) return;
     const int64_t seg_out = seg_koff(p, t);
     x.lim = seg_out + (int64_t)seg_k(p, t, p.commit);  // end of this segment's message
@@ -3064,11 +3097,15 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
                          const int64_t* seg_offsets, int n_seg, int32_t* out_idx, float* out_val, int64_t out_capacity,
                          int64_t* out_count, double* out_stats, void* workspace, size_t workspace_bytes, unsigned flags,
                          hipStream_t stream, const int32_t* map_idx, float* restore, int64_t n_restore,
-                         const uint64_t* seed, const gravac_profile_events* ev)
+                         const uint64_t* seed, const gravac_profile_events* ev, const float* tau = nullptr)
 {
     const bool single = map_idx != nullptr;
     const bool random = seed != nullptr;
-    if (!grad || (!single && !residual) || !cf_list || !out_idx || !out_val || !out_stats) return GRAVAC_ERR_INVALID_ARG;
+    const bool fixed = tau != nullptr;  // the threshold sparsifier: one flat tensor, cf_list = {1}, out_capacity as given
+    if (fixed && (single || random || n_seg != 0 || n_cf != 1 || !out_count || out_capacity < 0)) return GRAVAC_ERR_INVALID_ARG;
+    if (fixed && (!(*tau > 0.0f) || std::isinf(*tau))) return GRAVAC_ERR_INVALID_ARG;
+    if (!grad || (!single && !residual) || !cf_list || !out_stats) return GRAVAC_ERR_INVALID_ARG;
+    if ((!out_idx || !out_val) && !(fixed && out_capacity == 0)) return GRAVAC_ERR_INVALID_ARG;
     if (n <= 0 || n > 2147483647LL || n_cf < 1 || n_cf > MAXCF || commit < 0 || commit >= n_cf) return GRAVAC_ERR_INVALID_ARG;
     if (((uintptr_t)grad & 3) || ((uintptr_t)residual & 3) || ((uintptr_t)map_idx & 3)) return GRAVAC_ERR_INVALID_ARG;
     if (flags & ~(unsigned)GRAVAC_FLAG_FORCE_FALLBACK) return GRAVAC_ERR_INVALID_ARG;
@@ -3099,6 +3136,10 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     p.vec_ok = (((uintptr_t)grad & 15) == 0 && ((uintptr_t)residual & 15) == 0 && ((uintptr_t)map_idx & 15) == 0) ? 1 : 0;
     p.split = (cf_list[commit] > cf_min) ? 1 : 0;
     p.bounds_from = (flags & GRAVAC_FLAG_FORCE_FALLBACK) ? BOUNDS_FORCED : (random ? BOUNDS_RANDOM : BOUNDS_SAMPLED);
+    if (fixed) {
+        p.bounds_from = BOUNDS_FIXED;
+        std::memcpy(&p.fixed_key, tau, sizeof(uint32_t));   // positive and finite: the bit pattern is the key
+    }
     if (random) {
         // the seed goes through SplitMix64 (its first output for that seed) and gives the two 31-bit keys
         uint64_t z = *seed + 0x9E3779B97F4A7C15ull;
@@ -3169,6 +3210,11 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         const uint32_t per_block = SAMPLE_BLOCK * sample_rounds;
         p.n_sample_blocks = (p.flat_samples + per_block - 1) / per_block;
         total_out = p.flat_k[commit];
+        if (fixed) {
+            // the number of pairs is only known on the device: the emit step writes up to the caller's capacity
+            total_out = out_capacity < n ? out_capacity : n;
+            p.flat_k[0] = (uint32_t)total_out;
+        }
         if (total_out > out_capacity) return GRAVAC_ERR_CAPACITY;
     } else {
         // layerwise tables: sized first, then built straight into a pinned staging slot and copied into the
@@ -3251,7 +3297,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     static_assert(DENSE_ROUNDS == 4, "forms of the sampling kernel for 1, 2 and 4 groups per thread");
     // (a layerwise call takes SAMPLE_BLOCK samples per block; its small tensors are extra workgroups of this launch)
     const bool have_tiles = p.n_tiles != 0;  // (not if every tensor of a layerwise call is small)
-    if (have_tiles) {
+    if (have_tiles && !fixed) {              // (the threshold sparsifier uses nothing of what this kernel samples or clears)
         void (*const sample_forms[3])(Params) = {sample_kernel<1>, sample_kernel<2>, sample_kernel<4>};
         hipLaunchKernelGGL(sample_forms[sample_rounds == 1 ? 0 : sample_rounds == 2 ? 1 : 2], dim3(p.n_sample_blocks), dim3(256),
                            0, stream, p);
@@ -3278,7 +3324,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         else
             hipLaunchKernelGGL(kern, dim3(sub_grid), dim3(WG), 0, stream, p);
     }
-    if (have_tiles) {
+    if (have_tiles && !fixed) {
     hipLaunchKernelGGL(locate_kernel, dim3((uint32_t)(ns * n_cf)), dim3(256), 0, stream, p);
     // exact routes, taken only by segments whose bracket failed (the kernels return at once otherwise)
     hipLaunchKernelGGL(coarse_kernel, dim3(tile_grid < XGRID ? tile_grid : XGRID), dim3(WG), 0, stream, p);
@@ -3286,6 +3332,8 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         hipLaunchKernelGGL((stream_kernel<SM_EXACT, true, MAXCF>), dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
     else
         hipLaunchKernelGGL((stream_kernel<SM_EXACT, false, MAXCF>), dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
+    }
+    if (have_tiles) {
     // the refine kernel loops over the CFs: forms for 1, 2, 4 and MAXCF CFs
     void (*const refine_forms[4])(Params) = {refine_kernel<1>, refine_kernel<2>, refine_kernel<4>, refine_kernel<MAXCF>};
     hipLaunchKernelGGL(refine_forms[ncf_form], dim3(light_grid), dim3(LWG), 0, stream, p);
@@ -3328,6 +3376,16 @@ int gravac_randomk_compress(const float* grad, float* residual, int64_t n, const
     return compress_impl(grad, residual, n, cf_list, n_cf, commit, seg_offsets, n_seg, out_idx, out_val, out_capacity,
                          out_count, out_stats, workspace, workspace_bytes, flags, (hipStream_t)stream_v, nullptr, nullptr, 0,
                          &seed, nullptr);
+}
+
+int gravac_threshold_compress(const float* grad, float* residual, int64_t n, float tau, int32_t* out_idx, float* out_val,
+                              int64_t out_capacity, int64_t* out_count, double* out_stats, void* workspace,
+                              size_t workspace_bytes, void* stream_v)
+{
+    if (!residual) return GRAVAC_ERR_INVALID_ARG;
+    const double one = 1.0;
+    return compress_impl(grad, residual, n, &one, 1, 0, nullptr, 0, out_idx, out_val, out_capacity, out_count, out_stats,
+                         workspace, workspace_bytes, 0, (hipStream_t)stream_v, nullptr, nullptr, 0, nullptr, nullptr, &tau);
 }
 
 int gravac_recompress(const int32_t* idx1, const float* val1, int64_t k1, double cf_rel, const int64_t* seg_counts,

@@ -82,7 +82,7 @@ class ConfigTimer:
         self.flush = torch.empty(512 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")
         self.timer = binding.CallTimer()
 
-    def row(self, name, g, cfs, commit, seg=None, res0=None, iters=3, reps=6, modes=("cold",)):
+    def row(self, name, g, cfs, commit, seg=None, res0=None, iters=3, reps=7, modes=("cold",)):
         torch, binding = self.torch, self.binding
         n = g.numel()
         comp = binding.Compressor(n, cfs, commit, seg)
@@ -96,7 +96,7 @@ class ConfigTimer:
                     if mode == "cold":
                         self.flush.fill_(1.0)
                     comp(g, r, timer=self.timer)
-                    if it == iters - 1 and rep >= 1:
+                    if it == iters - 1 and rep >= 2:   # (the first calls of a layerwise shape allocate staging buffers)
                         tot.append(self.timer.call_ms())
                         strm.append(self.timer.pass_ms())
                 st = comp.status()
@@ -112,38 +112,62 @@ class ConfigTimer:
         return rec
 
 
-def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None):
+def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None, only=None):
     """One compress call of every configuration and the W = 8 decompression of configuration 5.  With full_table
-    also warm numbers, the 66 M-element LSTM variant and the direct / second-level comparison of Table III."""
+    also warm numbers, the 66 M-element LSTM variant and the direct / second-level comparison of Table III.
+    `only`: a substring that selects the configurations to run (for a profiler run of one of them)."""
     ct = ConfigTimer(torch, binding)
     modes = ("warm", "cold") if full_table else ("cold",)
     rows = []
-    g = torch.from_numpy(workloads.config1(0)).cuda()
-    rows.append(ct.row("1: N = 2^20, Normal(0, 1e-3)", g, [100.0], 0, modes=modes))
-    g = torch.from_numpy(workloads.config2_grad(0)).cuda()
-    r0 = torch.from_numpy(workloads.config2_residual0()).cuda()
-    for c in range(3):
-        rows.append(ct.row("2: ResNet101-shaped, three CFs in one call", g, [10.0, 100.0, 1000.0], c, res0=r0, modes=modes))
-    rows.append(ct.row("2: ResNet101-shaped, CF 100 alone", g, [100.0], 0, res0=r0, modes=modes))
+
+    def want(name):
+        return only is None or only in name
+
+    def add(name, make, cfs, commits, seg=None, res0=None):
+        if not want(name):
+            return
+        g = make()
+        r0 = res0() if res0 is not None else None
+        for c in commits:
+            rows.append(ct.row(name, g, cfs, c, seg=seg, res0=r0, modes=modes))
+
+    cache = {}
+
+    def resnet():
+        if "g2" not in cache:
+            cache["g2"] = torch.from_numpy(workloads.config2_grad(0)).cuda()
+        return cache["g2"]
+
+    def resnet_r0():
+        if "r2" not in cache:
+            cache["r2"] = torch.from_numpy(workloads.config2_residual0()).cuda()
+        return cache["r2"]
+
+    def vgg():
+        if "g3" not in cache:
+            cache["g3"] = vgg_grad if vgg_grad is not None else torch.from_numpy(workloads.config3_grad(0)).cuda()
+        return cache["g3"]
+
+    add("1: N = 2^20, Normal(0, 1e-3)", lambda: torch.from_numpy(workloads.config1(0)).cuda(), [100.0], [0])
+    add("2: ResNet101-shaped, three CFs in one call", resnet, [10.0, 100.0, 1000.0], [0, 1, 2], res0=resnet_r0)
+    add("2: ResNet101-shaped, CF 100 alone", resnet, [100.0], [0], res0=resnet_r0)
     if full_table:
-        rows.append(ct.row("2: ResNet101-shaped, CF 10 alone", g, [10.0], 0, res0=r0, modes=modes))
-    del g, r0
-    g = vgg_grad if vgg_grad is not None else torch.from_numpy(workloads.config3_grad(0)).cuda()
-    rows.append(ct.row("3: VGG16-shaped, CF 1000", g, [1000.0], 0, modes=modes))
-    rows.append(ct.row("3: VGG16-shaped, CF 100", g, [100.0], 0, modes=modes))
-    rows.append(ct.row("3: VGG16-shaped, CF 10", g, [10.0], 0, modes=modes))
-    del g
-    g = torch.from_numpy(workloads.config4_grad(0)).cuda()
-    for c in range(2):
-        rows.append(ct.row("4: LSTM, listed shapes", g, [100.0, 1000.0], c, modes=modes))
-    del g
+        add("2: ResNet101-shaped, CF 10 alone", resnet, [10.0], [0], res0=resnet_r0)
+    cache.pop("g2", None); cache.pop("r2", None)
+    add("3: VGG16-shaped, CF 1000", vgg, [1000.0], [0])
+    add("3: VGG16-shaped, CF 100", vgg, [100.0], [0])
+    add("3: VGG16-shaped, CF 10", vgg, [10.0], [0])
+    cache.pop("g3", None)
+    add("4: LSTM, listed shapes", lambda: torch.from_numpy(workloads.config4_grad(0)).cuda(), [100.0, 1000.0], [0, 1])
     if full_table:
-        g = torch.from_numpy(workloads.config4_grad(0, 10000, 1500)).cuda()
-        rows.append(ct.row("4: LSTM, 66,034,000-element variant", g, [100.0, 1000.0], 0, modes=modes))
-        del g
-    g = torch.from_numpy(workloads.config5_worker_grad(0)).cuda()
+        add("4: LSTM, 66,034,000-element variant", lambda: torch.from_numpy(workloads.config4_grad(0, 10000, 1500)).cuda(),
+            [100.0, 1000.0], [0])
     seg = workloads.offsets_of(workloads.resnet101_tensor_sizes())
-    rows.append(ct.row("5: ResNet101-shaped, 314 tensors, layerwise", g, [100.0], 0, seg=seg, modes=modes))
+    add("5: ResNet101-shaped, 314 tensors, layerwise", lambda: torch.from_numpy(workloads.config5_worker_grad(0)).cuda(),
+        [100.0], [0], seg=seg)
+    if not want("5: decompress_accumulate, W = 8"):
+        return rows
+    g = torch.from_numpy(workloads.config5_worker_grad(0)).cuda()
     # decompression of the eight workers' messages of configuration 5
     n = g.numel()
     comp = binding.Compressor(n, [100.0], 0, seg)
@@ -179,7 +203,7 @@ def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None):
             rec[mode + "_algorithmic_GBps"] = round((8.0 * n + 8.0 * N_WORKERS * k) / t / 1e6, 1)
         log(json.dumps(rec))
         rows.append(rec)
-    if not full_table:
+    if not full_table or only is not None:
         return rows
     # direct compression at each CF against the second-level Top-k on a level-1 message (the comparison of the
     # paper's Table III, on the synthetic gradients)
@@ -254,6 +278,8 @@ def main():
     ap.add_argument("--configs", action="store_true",
                     help="instead of the headline step, time one compress call of every configuration (1-5), warm and "
                          "cold, and the decompression of configuration 5, print one JSON line {\"configs\": [...]} and exit")
+    ap.add_argument("--filter", default=None,
+                    help="with --configs: only the configurations whose name contains this text")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 10 plain device copies of the gradient's size (known traffic: 4N read + 4N "
                          "written per copy) so that profiler byte counters can be scaled, then exit")
@@ -273,7 +299,7 @@ def main():
     torch.cuda.set_device(dev)
 
     if args.configs:
-        print(json.dumps({"configs": time_all_configs(torch, binding, workloads, True), "data": "synthetic",
+        print(json.dumps({"configs": time_all_configs(torch, binding, workloads, True, only=args.filter), "data": "synthetic",
                           "note": "times from the caller's HIP events around one gravac_compress call, third "
                                   "error-feedback iteration; call fraction = (12 N + 8 k) / t / 8 TB/s"}), flush=True)
         return

@@ -970,21 +970,18 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
         return;
     }
     // samples in the groups of bins above this workgroup's, and in all
+    // (the group counts of up to two blocks per thread are fetched first and added up after the histograms, so that
+    // both sets of loads are in flight together)
     uint32_t g_above = 0, g_total = 0;
+    uint4 ga[2][2];
+    static_assert(G == 1 || 2 * (1024 / G) >= 2 * DENSE_BLOCKS, "two blocks' group counts per thread cover a flat sample");
     if (G > 1) {
-        for (uint32_t b = tid; b < nb; b += T) {
-            const uint4* gp = (const uint4*)(p.samp_grp + (size_t)(sb0 + b) * SGRP);
-            const uint4 a = gp[0], c = gp[1];
-            const uint32_t v[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
 #pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                g_total += v[g];
-                if (g > y) g_above += v[g];
-            }
+        for (int x = 0; x < 2; ++x) {
+            const uint32_t b = tid + x * T;
+            const uint4* gp = (const uint4*)(p.samp_grp + (size_t)(sb0 + (b < nb ? b : 0u)) * SGRP);
+            ga[x][0] = gp[0]; ga[x][1] = gp[1];
         }
-        g_above = wave_sum(g_above);
-        g_total = wave_sum(g_total);
-        if (lane == 0) { gab[wib] = g_above; gto[wib] = g_total; }
     }
     uint32_t h0 = 0, h1 = 0, h2 = 0, h3 = 0;
     {
@@ -999,6 +996,21 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
                 h2 += w[q].y & 0xFFFFu; h3 += w[q].y >> 16;
             }
         }
+    }
+    if (G > 1) {
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+            if (tid + x * T >= nb) continue;
+            const uint32_t v[8] = {ga[x][0].x, ga[x][0].y, ga[x][0].z, ga[x][0].w, ga[x][1].x, ga[x][1].y, ga[x][1].z, ga[x][1].w};
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                g_total += v[g];
+                if (g > y) g_above += v[g];
+            }
+        }
+        g_above = wave_sum(g_above);
+        g_total = wave_sum(g_total);
+        if (lane == 0) { gab[wib] = g_above; gto[wib] = g_total; }
     }
     const uint32_t mine = h0 + h1 + h2 + h3;
     const uint32_t incl = wave_scan(mine);
@@ -1718,9 +1730,19 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
         on[j] = have ? p.ovn[((size_t)u * SUB + lane) * p.n_cf + j] : 0u;
         os[j] = have ? p.ovs[((size_t)u * SUB + lane) * p.n_cf + j] : 0.0;
     }
+    const int t = tile_seg(p, u);
+    // (the plan as the locate step left it: fetched with the counts, not after them)
+    uint32_t mode[NCF], base[NCF], span[NCF], top[NCF];
+#pragma unroll
+    for (int j = 0; j < NCF; ++j) {
+        mode[j] = MODE_RESOLVED; base[j] = NONE; span[j] = 0; top[j] = 0;
+        if (j < p.n_cf) {
+            const CfState* st = &p.st[(size_t)t * p.n_cf + j];
+            mode[j] = st->mode; base[j] = st->base; span[j] = st->span; top[j] = st->top;
+        }
+    }
     const TileRef tr = tile_ref(p, u);
     const uint32_t cnt = tr.tl.total();
-    const int t = tile_seg(p, u);
     const bool redo = any_fail != 0 && p.seg[t].fail != 0;
     const bool first = redo && (u == seg_tile0(p, t));
     uint32_t hn[NCF], tin = 0;
@@ -1756,15 +1778,13 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
             }
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // rp is read back by the same wavefront
         }
-        uint32_t mode[NCF], base[NCF], span[NCF], top[NCF];
 #pragma unroll
         for (int j = 0; j < NCF; ++j) {
-            mode[j] = MODE_RESOLVED; base[j] = NONE; span[j] = 0; top[j] = 0;
             if (j < p.n_cf) {
-                const CfState* st = &p.st[(size_t)t * p.n_cf + j];
-                top[j] = st->top;
-                if (redo) { mode[j] = rp[wib][j][0]; base[j] = rp[wib][j][1]; span[j] = rp[wib][j][2]; }
-                else { mode[j] = st->mode; base[j] = st->base; span[j] = st->span; }
+                if (redo) {  // (an exact route may have moved the bracket's end too)
+                    mode[j] = rp[wib][j][0]; base[j] = rp[wib][j][1]; span[j] = rp[wib][j][2];
+                    top[j] = p.st[(size_t)t * p.n_cf + j].top;
+                }
                 if (mode[j] == MODE_FAIL) { base[j] = NONE; top[j] = 0; }  // (an error: nothing is counted)
             }
         }

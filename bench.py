@@ -16,6 +16,7 @@ in HBM before the timed region.  The same run then times one compress call of ev
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -102,9 +103,10 @@ class ConfigTimer:
                 st = comp.status()
                 fb |= st["any_fallback"]
                 assert st["internal_error"] == 0, (name, st)
-            t = float(np.mean(tot))
+            t = float(np.median(tot))   # (median of five: one host hiccup does not move the row)
             rec[mode + "_us"] = round(t * 1e3, 1)
-            rec[mode + "_stream_kernel_us"] = round(float(np.mean(strm)) * 1e3, 1)
+            rec[mode + "_max_us"] = round(float(np.max(tot)) * 1e3, 1)
+            rec[mode + "_stream_kernel_us"] = round(float(np.median(strm)) * 1e3, 1)
             rec[mode + "_dense_GBps"] = round(4.0 * n / t / 1e6, 1)
             rec[mode + "_call_frac_of_hbm_peak"] = round((ALGO_BYTES_PER_ELEMENT * n + 8.0 * comp.k_total) / t / 1e6 / HBM_PEAK_GBS, 4)
             rec[mode + "_fallback"] = bool(fb)
@@ -115,13 +117,13 @@ class ConfigTimer:
 def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None, only=None):
     """One compress call of every configuration and the W = 8 decompression of configuration 5.  With full_table
     also warm numbers, the 66 M-element LSTM variant and the direct / second-level comparison of Table III.
-    `only`: a substring that selects the configurations to run (for a profiler run of one of them)."""
+    `only`: a regular expression that selects the configurations to run (for a profiler run of one of them)."""
     ct = ConfigTimer(torch, binding)
     modes = ("warm", "cold") if full_table else ("cold",)
     rows = []
 
     def want(name):
-        return only is None or only in name
+        return only is None or re.search(only, name) is not None
 
     def add(name, make, cfs, commits, seg=None, res0=None):
         if not want(name):
@@ -198,7 +200,7 @@ def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None, only=
                 torch.cuda.synchronize()
                 if rep >= 2:
                     ts.append(e0.elapsed_time(e1))
-            t = float(np.mean(ts))
+            t = float(np.median(ts))
             rec[mode + "_us"] = round(t * 1e3, 1)
             rec[mode + "_algorithmic_GBps"] = round((8.0 * n + 8.0 * N_WORKERS * k) / t / 1e6, 1)
         log(json.dumps(rec))
@@ -259,7 +261,7 @@ def compact(rows):
                         "algorithmic_GBps": r["cold_algorithmic_GBps"]})
         elif "cold_us" in r:
             out.append({"config": r["config"], "n": r["n"], "cfs": r["cfs"], "commit_cf": r["commit_cf"], "k": r["k"],
-                        "cold_us": r["cold_us"], "stream_kernel_us": r["cold_stream_kernel_us"],
+                        "cold_us": r["cold_us"], "cold_max_us": r["cold_max_us"], "stream_kernel_us": r["cold_stream_kernel_us"],
                         "call_frac": r["cold_call_frac_of_hbm_peak"], "fallback": r["cold_fallback"]})
     return out
 
@@ -279,7 +281,8 @@ def main():
                     help="instead of the headline step, time one compress call of every configuration (1-5), warm and "
                          "cold, and the decompression of configuration 5, print one JSON line {\"configs\": [...]} and exit")
     ap.add_argument("--filter", default=None,
-                    help="with --configs: only the configurations whose name contains this text")
+                    help="with --configs: only the configurations whose name matches this regular expression "
+                         "(re.search), e.g. 'VGG16-shaped, CF 10$'")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 10 plain device copies of the gradient's size (known traffic: 4N read + 4N "
                          "written per copy) so that profiler byte counters can be scaled, then exit")

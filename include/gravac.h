@@ -72,9 +72,11 @@ int64_t gravac_topk_count(int64_t n, double cf);
 /*
  * Workspace size in bytes for a gravac_compress call on n elements with n_cf candidate CFs
  * and n_seg segments (0 or 1 = one flat tensor).  The size depends only on these three
- * numbers (it covers any segment table with n_seg entries).  About 17 bytes per element (two index / value lists
- * with a slot per element, so that no list can overflow), plus 0.4 MB per (segment, CF) for histograms and gather
- * lists (layerwise mode: 314 tensors with one CF take 130 MB more than the flat call), plus 2 KB per sample block.
+ * numbers (it covers any segment table with n_seg entries).  About 16 bytes per element (two index / value lists
+ * with a slot per element, so that no list can overflow), plus 56 KB per (segment, CF) and per 65,536 elements for
+ * histograms and gather lists, plus 8 KB per sample block (the size allows 64 of them per tensor in layerwise mode,
+ * 128 for a flat call).  Examples: 44,549,160 elements flat, one CF: 716 MB; the same as 314 tensors: 986 MB;
+ * 138,357,544 elements flat: 2.22 GB.
  */
 int gravac_workspace_bytes(int64_t n, int n_cf, int n_seg, size_t* bytes_out);
 

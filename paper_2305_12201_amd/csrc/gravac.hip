@@ -70,6 +70,7 @@ constexpr uint32_t DENSE_SUB = GV_DENSE;  // a full sub-tile with at least this 
                                           // the emit step reads its 1024 elements again (4 KB read + 4 KB written, what
                                           // about 400 listed candidates cost in list traffic and scattered stores)
 constexpr uint32_t DENSE_BIT = 0x80000000u;  // flag of such a sub-tile in cand_cnt
+constexpr uint32_t LONG_WALK = 256;   // a tile with at least this many listed entries is walked sub-tile by sub-tile
 #ifndef GV_NT
 #define GV_NT 1                     // non-temporal hints on the streaming loads and stores
 #endif
@@ -201,6 +202,7 @@ struct Params {
     SegState* seg;       // [n_seg]
     uint32_t* bnd_lo;    // [n_seg][n_cf] the bracket of every CF as the threshold kernel found it: first key ...
     uint32_t* bnd_hi;    // [n_seg][n_cf] ... and one past its last key (at most KEY_END)
+    uint32_t* bnd_mid;   // [n_seg][n_cf] the key the sample puts the k-th largest at (NONE: no estimate)
     uint32_t* hist1;     // [copy blocks][NBIN] bracket histograms: REP copies per CF of a large tensor, one otherwise
     uint32_t* ovfc;      // [n_seg][n_cf][64][32] counts above the bracket (the histogram's last bin), spread over
                          // 64 cache lines; word 0 of each line is used
@@ -455,6 +457,23 @@ __device__ __forceinline__ void ref_entry(const Params& p, uint32_t u, const Til
     const size_t at = (size_t)u * TW + sl;
     if (!p.random) {
         // the bits of |acc| either way: a candidate's value with its sign, or the key itself
+        const uint32_t* src = from_main ? (const uint32_t*)p.cand_val : p.brk_key;
+        key = src[at] & 0x7FFFFFFFu;
+        val = 0.0f;
+    } else if (from_main) {
+        key = priority_of(p.rk_s0, p.rk_s1, (uint32_t)p.cand_idx[at]);
+        val = p.cand_val[at];
+    } else {
+        key = p.brk_key[at];
+        val = p.brk_val[at];
+    }
+}
+
+// The same for slot sl of sub-tile j of tile u, from its candidate list (from_main) or its bracket list.
+__device__ __forceinline__ void sub_entry(const Params& p, uint32_t u, int j, bool from_main, uint32_t sl, uint32_t& key, float& val)
+{
+    const size_t at = (size_t)u * TW + (size_t)j * TS + sl;
+    if (!p.random) {
         const uint32_t* src = from_main ? (const uint32_t*)p.cand_val : p.brk_key;
         key = src[at] & 0x7FFFFFFFu;
         val = 0.0f;
@@ -894,7 +913,7 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
     constexpr int NW = T / 64;
     static_assert(G == 1 || G == SGRP, "one workgroup per group of bins, or one for all");
     __shared__ uint32_t wtot[NW], gab[NW], gto[NW];
-    __shared__ uint32_t rank_lo[MAXCF], rank_hi[MAXCF];
+    __shared__ uint32_t rank_lo[MAXCF], rank_hi[MAXCF], rank_mid[MAXCF];
     const int t = blockIdx.x, y = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
     if (t == 0 && y == 0 && tid == 0) {
         p.status->any_fail = 0; p.status->n_fail = 0; p.status->error = 0; p.status->n_seg = p.n_seg;
@@ -922,24 +941,25 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
     }
     if (tid < p.n_cf) {
         const uint32_t k = seg_k(p, t, tid);
-        uint32_t r_lo, r_hi;
+        uint32_t r_lo, r_hi, r_mid;
         if (whole) {
-            r_lo = r_hi = k;
+            r_lo = r_hi = r_mid = k;
         } else {
             // expected number of sampled keys among the k largest, widened by ZMARGIN standard deviations
             const double m = (double)k * (double)S / (double)nt, sd = sqrt(m);
             const double a = ceil(m + ZMARGIN * sd + 2.0), b = floor(m - ZMARGIN * sd - 2.0);
             r_lo = (a >= 4.0e9) ? NONE : (uint32_t)a;
             r_hi = (b < 1.0) ? 1u : (uint32_t)b;
+            r_mid = (m < 1.0) ? 1u : (m >= 4.0e9 ? NONE : (uint32_t)(m + 0.5));
         }
-        rank_lo[tid] = r_lo; rank_hi[tid] = r_hi;
+        rank_lo[tid] = r_lo; rank_hi[tid] = r_hi; rank_mid[tid] = r_mid;
     }
     if (p.bounds_from == BOUNDS_FIXED) {
         // the threshold sparsifier (one flat tensor, one "CF"): an empty bracket at the caller's threshold, so that the
         // pass over the gradient counts and lists what lies at or above it; the later steps find everything resolved:
         // selected <=> key > tau with tau one key below the threshold, no ties to take
         if (tid == 0) {
-            p.bnd_lo[0] = p.fixed_key; p.bnd_hi[0] = p.fixed_key;
+            p.bnd_lo[0] = p.fixed_key; p.bnd_hi[0] = p.fixed_key; p.bnd_mid[0] = NONE;
             CfState st;
             st.k = 0; st.lo = p.fixed_key; st.s = 0; st.mode = MODE_RESOLVED; st.base = p.fixed_key; st.span = 0;
             st.above = 0; st.c = 0; st.tau = p.fixed_key - 1u; st.need = 0; st.cnt_gt = 0; st.redo = 0; st.lo2 = 0; st.s2 = 0;
@@ -954,7 +974,7 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
     if (!sampled) {
         // no sample: the brackets follow from k alone (Random-k) or are left empty (every segment takes the exact route)
         if (y == 0 && tid < p.n_cf) {
-            uint32_t lo = NONE, hi = NONE;
+            uint32_t lo = NONE, hi = NONE, mid = NONE;
             if (p.bounds_from == BOUNDS_RANDOM) {
                 // priorities are a keyed permutation of the 31-bit integers: the number of a tensor's nt indices
                 // with priority >= x is as good as binomial (nt, 1 - x / 2^31), so the bounds follow from k alone:
@@ -963,9 +983,11 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
                 const double q_lo = (k + w) / (double)nt, q_hi = (k - w) / (double)nt;
                 lo = q_lo >= 1.0 ? 0u : (uint32_t)floor(2147483648.0 * (1.0 - q_lo));
                 hi = q_hi <= 0.0 ? KEY_END : (uint32_t)ceil(2147483648.0 * (1.0 - q_hi));
+                mid = (uint32_t)floor(2147483648.0 * (1.0 - (k >= (double)nt ? 1.0 : k / (double)nt)));
             }
             p.bnd_lo[(size_t)t * p.n_cf + tid] = lo;
             p.bnd_hi[(size_t)t * p.n_cf + tid] = hi;
+            p.bnd_mid[(size_t)t * p.n_cf + tid] = mid;
         }
         return;
     }
@@ -1029,7 +1051,7 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
     const uint32_t above0 = g_above + local - (before + incl);  // samples in bins above this thread's four
     const uint32_t hh[4] = {h0, h1, h2, h3};
     for (int j = 0; j < p.n_cf; ++j) {
-        const uint32_t r_lo = rank_lo[j], r_hi = rank_hi[j];
+        const uint32_t r_lo = rank_lo[j], r_hi = rank_hi[j], r_mid = rank_mid[j];
         const size_t id = (size_t)t * p.n_cf + j;
         uint32_t above = above0;
 #pragma unroll
@@ -1039,12 +1061,21 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
             // lower edge of the bin of the r_lo-th sample from the top, upper edge of the bin of the r_hi-th
             if (above < r_lo && above + c >= r_lo) p.bnd_lo[id] = sample_bin_first(bin);
             if (above < r_hi && above + c >= r_hi) p.bnd_hi[id] = sample_bin_end(bin);
+            if (above < r_mid && above + c >= r_mid) {
+                // the r_mid-th sample from the top is the (r_mid - above)-th of the c in this bin: that far down from
+                // the bin's upper edge, as if the bin's samples were spread evenly over its keys
+                const uint32_t first = sample_bin_first(bin), end = sample_bin_end(bin);
+                // (an estimate: single precision will do, and keeps a 64-bit division out of this kernel)
+                const uint32_t down = (uint32_t)((float)(end - first) * ((float)(r_mid - above) / (float)c));
+                p.bnd_mid[id] = down >= end - first ? first : end - down;
+            }
             above += c;
         }
         // fewer samples than a rank: the bracket is open on that side
         if (y == 0 && tid == 0) {
             if (g_total < r_lo) p.bnd_lo[id] = 0u;
             if (g_total < r_hi) p.bnd_hi[id] = KEY_END;
+            if (g_total < r_mid) p.bnd_mid[id] = NONE;
         }
     }
 }
@@ -1055,6 +1086,20 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
 //     SM_EXACT (exact route, failed segments only): read acc from residual; the brackets come from the
 //     coarse histogram.  Both collect the lists of the sub-tile in index order.
 // ---------------------------------------------------------------------------------------------
+// From which key on the pass over the gradient stores +0 instead of acc in a sub-tile that lists its candidates
+// (NONE: nowhere): the key the sample puts the committed CF's k-th largest at, kept inside that CF's bracket
+// [lo, top).  Entries from there on are in the candidate list, and most of them are selected: the emit step then has
+// a scattered store only for the entries between this key and the threshold, selected ones below it (+0) or
+// unselected ones at or above it (acc put back), instead of one for every selected entry of the bracket; a
+// scattered 4-byte store costs the memory a read and a write of its 64 bytes, 34 us per million of them.
+__device__ __forceinline__ uint32_t zero_from(const Params& p, int t, uint32_t lo, uint32_t top)
+{
+    if (p.single || top == KEY_END) return NONE;
+    const uint32_t mid = p.bnd_mid[(size_t)t * p.n_cf + p.commit];
+    if (mid == NONE) return top;
+    return mid < lo ? lo : (mid > top ? top : mid);
+}
+
 template <int NCF>  // compiled for calls with up to NCF CFs: the loops over the CFs are unrolled
 struct SubCtx {
     uint32_t lo_min, lo_c, pz;
@@ -1289,7 +1334,7 @@ __device__ __forceinline__ void stream_subtile(const Params& p, uint32_t v, int 
                 c.lo_min = c.lo[j] < c.lo_min ? c.lo[j] : c.lo_min;
                 if (j == p.commit) {
                     c.lo_c = c.lo[j];
-                    if (M == SM_EF && c.top[j] != KEY_END) c.pz = c.top[j];
+                    if (M == SM_EF) c.pz = zero_from(p, t, c.lo[j], c.top[j]);
                 }
             }
         }
@@ -1697,7 +1742,7 @@ __global__ __launch_bounds__(256) void locate_kernel(Params p)
                     uint32_t sx, tx;
                     bracket_bins(lx, p.bnd_hi[(size_t)t * p.n_cf + x], sx, tx);
                     lo_c = lx;
-                    if (!p.single && tx != KEY_END) pz = tx;
+                    pz = zero_from(p, t, lx, tx);
                 }
             }
             p.seg[t].lo_min = lo_min; p.seg[t].lo_c = lo_c; p.seg[t].pz = pz;
@@ -1713,8 +1758,10 @@ __global__ __launch_bounds__(256) void locate_kernel(Params p)
 // segment that took an exact route the plan is derived here, by every wavefront for itself, from the
 // rebuilt bracket histogram (its first tile's wavefront records it).
 // ---------------------------------------------------------------------------------------------
+// (the form for four CFs is held to 80 registers, a dozen values spilled: six wavefronts per SIMD instead of four
+// take the ResNet101 shape's tiles in one round instead of two)
 template <int NCF>  // compiled for calls with up to NCF CFs: the loops over the CFs are unrolled
-__global__ __launch_bounds__(LWG) void refine_kernel(Params p)
+__global__ __launch_bounds__(LWG) __attribute__((amdgpu_waves_per_eu(NCF == 4 ? 6 : 1, 8))) void refine_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
     const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * LWAVES + (threadIdx.x >> 6));
@@ -1795,6 +1842,7 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
             for (int j = 0; j < NCF; ++j) {
                 if (j >= p.n_cf) continue;
                 const bool mine = live && key < top[j] && key >= base[j];
+                if (__ballot(mine) == 0ull) continue;  // (most rounds hold nothing for the CFs with few entries)
                 const bool in = mine && key - base[j] <= span[j];
                 // Random-k: the entry at the threshold is the last one selected and has no particular magnitude, so a
                 // bin that is one key wide adds its energy here (Top-k adds need * tau^2 in the scan instead)
@@ -1825,6 +1873,45 @@ __global__ __launch_bounds__(LWG) void refine_kernel(Params p)
         // otherwise (most tiles hold a hundred entries or so, and a round that no lane has an entry for costs as many
         // instructions as a full one)
         uint32_t i0 = 0;
+        if (cnt >= LONG_WALK) {
+            // long lists (a low CF): sub-tile by sub-tile, so that no lane has to search for its entry's slot; two
+            // rounds per sub-tile are loaded while the sub-tile before it is worked on, whatever it holds
+            const auto counts = [&](int j, uint32_t& c, bool& from_main) {
+                const uint32_t cc = p.cand_cnt[(size_t)u * SUB + j], bc = p.brk_cnt[(size_t)u * SUB + j];
+                from_main = !p.split && !(cc & DENSE_BIT);
+                c = from_main ? cc : bc;
+            };
+            uint32_t c, kn[2];
+            bool fm;
+            float vn[2];
+            counts(0, c, fm);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) sub_entry(p, u, 0, fm, q * 64 + lane, kn[q], vn[q]);
+            for (int j = 0; j < SUB; ++j) {
+                uint32_t kq[2], cnx = 0;
+                float vq[2];
+                bool fnx = false;
+#pragma unroll
+                for (int q = 0; q < 2; ++q) { kq[q] = kn[q]; vq[q] = vn[q]; }
+                if (j + 1 < SUB) {
+                    counts(j + 1, cnx, fnx);
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) sub_entry(p, u, j + 1, fnx, q * 64 + lane, kn[q], vn[q]);
+                }
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+                    if ((uint32_t)q * 64 < c) take(kq[q], vq[q], q * 64 + lane < c);
+                for (uint32_t b0 = 128; b0 < c; b0 += 128) {   // (a sub-tile with more than 128 such entries: rare)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) sub_entry(p, u, j, fm, (b0 + q * 64 + lane) & (TS - 1), kq[q], vq[q]);
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+                        if (b0 + q * 64 < c) take(kq[q], vq[q], b0 + q * 64 + lane < c);
+                }
+                c = cnx; fm = fnx;
+            }
+            i0 = cnt;
+        }
         for (; i0 + 64 * 2 < cnt; i0 += 64 * 8) {
             uint32_t kq[8];
             float vq[8];
@@ -2254,23 +2341,31 @@ struct EmitCtx {
 };
 
 // One round of up to 64 listed candidates (idx, val), one per lane.
+template <bool GEN>
 __device__ __forceinline__ void emit_listed(const Params& p, EmitCtx& x, int32_t idx, float val, bool live)
 {
-    const uint32_t key = cand_key(p, idx, val);
+    const bool rnd = GEN && p.random, single = GEN && p.single;
+    const uint32_t key = rnd ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)idx) : key_of(val);
     const bool gt = live && key > x.tau, eq = live && key == x.tau;
     const uint64_t me = __ballot(eq);
-    const bool sel = gt || (eq && (x.erun + lanes_below(me)) < x.take);
+    bool sel = gt;
+    if (me != 0ull) sel = gt || (eq && (x.erun + lanes_below(me)) < x.take);  // (few rounds hold a tie)
     const uint64_t ms = __ballot(sel);
+    // the wavefront's pairs go to consecutive places from pos on: a uniform base and a small offset per lane
+    const int64_t left = x.lim - x.pos;
+    const uint32_t room = left >= 64 ? 64u : (left > 0 ? (uint32_t)left : 0u);
+    float* ov = p.out_val + x.pos;
+    int32_t* oi = p.out_idx + x.pos;
     if (sel) {
-        const int64_t o = x.pos + lanes_below(ms);
-        if (o < x.lim) {
-            p.out_val[o] = val;
-            if (!p.single) {
-                p.out_idx[o] = idx;
+        const uint32_t o = lanes_below(ms);
+        if (o < room) {
+            ov[o] = val;
+            if (!single) {
+                oi[o] = idx;
                 if (key < x.pz) p.res[idx] = 0.0f;
             } else {
                 const int mi = p.map_idx[idx];  // position in the message -> index in the gradient
-                p.out_idx[o] = mi;
+                oi[o] = mi;
                 if (p.restore && (uint64_t)(int64_t)mi < (uint64_t)p.n_restore) p.restore[mi] = 0.0f;
             }
         } else {
@@ -2283,8 +2378,10 @@ __device__ __forceinline__ void emit_listed(const Params& p, EmitCtx& x, int32_t
     x.erun += (uint32_t)__popcll(me);
 }
 
+template <bool GEN>  // false: compiled for the plain call (Top-k or threshold keys, gradient + residual)
 __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
 {
+    const bool rnd = GEN && p.random, single = GEN && p.single;  // (known to be off in the plain form)
     const int lane = threadIdx.x & 63;
     const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * LWAVES + (threadIdx.x >> 6));
     if (u >= p.n_tiles) return;
@@ -2300,7 +2397,7 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
     // The first pass has left +0 in the residual of its listed sub-tiles for keys >= pz (not on the full exact route,
     // which has put acc back).  Those entries need no store here if they are selected, and get acc back if they are
     // not, which can only be when the threshold turned out to lie at or above pz.
-    x.pz = (p.single || p.seg[t].fail == FAIL_FULL) ? NONE : p.seg[t].pz;
+    x.pz = (single || p.seg[t].fail == FAIL_FULL) ? NONE : p.seg[t].pz;
     x.put_back = x.pz != NONE && x.tau >= x.pz;
     if (p.bounds_from == BOUNDS_FIXED && (int64_t)p.status->count > p.total_out) {
         // threshold sparsifier, more entries kept than the caller's buffers hold: nothing is emitted and nothing removed.
@@ -2315,14 +2412,14 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
     x.erun = 0;
     const float* cv = p.cand_val + (size_t)u * TW;
     const int32_t* ci = p.cand_idx + (size_t)u * TW;
-    if (!any_dense) {
-        // all sub-tiles listed: their lists are walked as one, 64 candidates per round.  The loads of the next
-        // rounds are issued before this round is worked on (an absent candidate reads slot 0 and is not used), so
-        // that a wavefront with a long list does not wait a full round trip per round
-        TileLists tl;
-        tl.start[0] = 0;
+    TileLists tl;
+    tl.start[0] = 0;
 #pragma unroll
-        for (int j = 0; j < SUB; ++j) tl.start[j + 1] = tl.start[j] + cc[j];
+    for (int j = 0; j < SUB; ++j) tl.start[j + 1] = tl.start[j] + (cc[j] & ~DENSE_BIT);
+    if (!any_dense && tl.total() < LONG_WALK) {
+        // all sub-tiles listed, and shortly: their lists are walked as one, 64 candidates per round.  The loads of
+        // the next rounds are issued before this round is worked on (an absent candidate reads slot 0 and is not
+        // used), so that a wavefront does not wait a full round trip per round
         const uint32_t cnt = tl.total();
         float vn[4];
         int32_t in[4];
@@ -2350,14 +2447,49 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 if (b0 + r * 64 >= cnt) break;  // (a round that no lane has a candidate for costs as much as a full one)
-                emit_listed(p, x, iq[r], vq[r], b0 + r * 64 + lane < cnt);
+                emit_listed<GEN>(p, x, iq[r], vq[r], b0 + r * 64 + lane < cnt);
             }
         }
         return;
     }
-    // sub-tile by sub-tile
-    __shared__ int32_t stage_idx[LWAVES][TS];   // a sub-tile's part of the message, per wavefront
-    __shared__ float stage_val[LWAVES][TS];
+    if (!any_dense) {
+        // all sub-tiles listed, at length (a low CF): sub-tile by sub-tile, so that no lane has to search for its
+        // candidate's slot, and the first two rounds of every sub-tile are loaded before any is worked on: the
+        // wavefront pays one round trip to memory, not one per sub-tile
+        float va[SUB][2];
+        int32_t ia[SUB][2];
+#pragma unroll
+        for (int j = 0; j < SUB; ++j) {
+#pragma unroll
+            for (int r = 0; r < 2; ++r) { va[j][r] = cv[j * TS + r * 64 + lane]; ia[j][r] = ci[j * TS + r * 64 + lane]; }
+        }
+#pragma unroll
+        for (int j = 0; j < SUB; ++j) {
+            const uint32_t c = cc[j];
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+                if ((uint32_t)r * 64 < c) emit_listed<GEN>(p, x, ia[j][r], va[j][r], r * 64 + lane < c);
+            for (uint32_t b0 = 128; b0 < c; b0 += 128) {   // (more than 128 candidates and still listed)
+                float vq[2];
+                int32_t iq[2];
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    const uint32_t q = (b0 + r * 64 + lane) & (TS - 1);
+                    vq[r] = cv[j * TS + q];
+                    iq[r] = ci[j * TS + q];
+                }
+#pragma unroll
+                for (int r = 0; r < 2; ++r)
+                    if (b0 + r * 64 < c) emit_listed<GEN>(p, x, iq[r], vq[r], b0 + r * 64 + lane < c);
+            }
+        }
+        return;
+    }
+    // sub-tile by sub-tile: a tile with sub-tiles that keep no list
+    // (two rows of a sub-tile at a time: with room for a whole sub-tile the LDS of a workgroup would limit the
+    // kernel to five wavefronts per SIMD, and the listed tiles of the same launch need the occupancy)
+    __shared__ int32_t stage_idx[LWAVES][TS / 2];   // half a sub-tile's part of the message, per wavefront
+    __shared__ float stage_val[LWAVES][TS / 2];
     int32_t* sidx = stage_idx[threadIdx.x >> 6];
     float* sval = stage_val[threadIdx.x >> 6];
     const int64_t tile0 = seg_begin(p, t) + (int64_t)(u - seg_tile0(p, t)) * TW;
@@ -2367,23 +2499,35 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) nxt[q] = *(const v4f*)(p.acc + sn + q * ROW + 4 * lane);
     }
+    // the first two rounds of the next sub-tile's list, loaded while this one is worked on, whatever they hold
+    float vnx[2];
+    int32_t inx[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) { vnx[r] = cv[r * 64 + lane]; inx[r] = ci[r * 64 + lane]; }
     for (int j = 0; j < SUB; ++j) {
+        float vq[2];
+        int32_t iq[2];
+#pragma unroll
+        for (int r = 0; r < 2; ++r) { vq[r] = vnx[r]; iq[r] = inx[r]; }
+        if (j + 1 < SUB) {
+#pragma unroll
+            for (int r = 0; r < 2; ++r) { vnx[r] = cv[(j + 1) * TS + r * 64 + lane]; inx[r] = ci[(j + 1) * TS + r * 64 + lane]; }
+        }
         if (!((dmask >> j) & 1u)) {
             const uint32_t c = p.cand_cnt[(size_t)u * SUB + j];
-            for (uint32_t b0 = 0; b0 < c; b0 += 64 * 4) {
-                float vq[4];
-                int32_t iq[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const uint32_t q = b0 + r * 64 + lane;
-                    vq[r] = cv[j * TS + (q < c ? q : 0u)];
-                    iq[r] = ci[j * TS + (q < c ? q : 0u)];
+            for (int r = 0; r < 2; ++r)
+                if ((uint32_t)r * 64 < c) emit_listed<GEN>(p, x, iq[r], vq[r], r * 64 + lane < c);
+            for (uint32_t b0 = 128; b0 < c; b0 += 128) {   // (more than 128 candidates and still listed)
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    const uint32_t q = (b0 + r * 64 + lane) & (TS - 1);
+                    vq[r] = cv[j * TS + q];
+                    iq[r] = ci[j * TS + q];
                 }
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if (b0 + r * 64 >= c) break;
-                    emit_listed(p, x, iq[r], vq[r], b0 + r * 64 + lane < c);
-                }
+                for (int r = 0; r < 2; ++r)
+                    if (b0 + r * 64 < c) emit_listed<GEN>(p, x, iq[r], vq[r], b0 + r * 64 + lane < c);
             }
             continue;
         }
@@ -2391,7 +2535,7 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
         // four rows of 256 elements, a lane's four consecutive elements at a time.  Its rows were loaded while the
         // sub-tile before it was worked on; now the next such sub-tile's loads are issued.
         const int64_t s0 = tile0 + (int64_t)j * TS;
-        uint32_t staged = 0;  // pairs of this sub-tile in LDS so far
+        uint32_t staged = 0;  // pairs in LDS so far
         v4f av[ROWS];
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) av[q] = nxt[q];
@@ -2411,7 +2555,7 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
             uint32_t ties_below = 0;   // ties in lower lanes of this row
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t key = p.random ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)(g + e)) : key_of(a[e]);
+                const uint32_t key = rnd ? priority_of(p.rk_s0, p.rk_s1, (uint32_t)(g + e)) : key_of(a[e]);
                 gt[e] = key > x.tau;
                 eq[e] = key == x.tau;
             }
@@ -2441,7 +2585,7 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
             for (int e = 0; e < 4; ++e) {
                 if (!sel[e]) continue;
                 int32_t gi = (int32_t)(g + e);
-                if (p.single) {
+                if (single) {
                     gi = p.map_idx[g + e];
                     if (p.restore && (uint64_t)(int64_t)gi < (uint64_t)p.n_restore) p.restore[gi] = 0.0f;
                 }
@@ -2449,7 +2593,7 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
                 sval[o] = a[e];
                 ++o;
             }
-            if (!p.single) {
+            if (!single) {
                 v4f r;
                 r.x = sel[0] ? 0.0f : a[0]; r.y = sel[1] ? 0.0f : a[1];
                 r.z = sel[2] ? 0.0f : a[2]; r.w = sel[3] ? 0.0f : a[3];
@@ -2457,18 +2601,21 @@ __global__ __launch_bounds__(LWG) void emit_kernel(Params p)
             }
             staged += tot;
             x.erun += ties_row;
-        }
-        // ... and from there into the message, 64 consecutive pairs per store
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // the wavefront's own LDS writes, read back by other lanes
-        if (x.pos + (int64_t)staged > x.lim) p.status->error = 1;  // cannot happen if the counts are consistent
-        for (uint32_t i = lane; i < staged; i += 64) {
-            if (x.pos + i < x.lim) {   // never write out of range
-                p.out_idx[x.pos + i] = sidx[i];
-                p.out_val[x.pos + i] = sval[i];
+            if (q & 1) {
+                // ... and from there into the message, 64 consecutive pairs per store
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // the wavefront's own LDS writes, read back by other lanes
+                if (x.pos + (int64_t)staged > x.lim) p.status->error = 1;  // cannot happen if the counts are consistent
+                for (uint32_t i = lane; i < staged; i += 64) {
+                    if (x.pos + i < x.lim) {   // never write out of range
+                        p.out_idx[x.pos + i] = sidx[i];
+                        p.out_val[x.pos + i] = sval[i];
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // read before the next rows overwrite them
+                x.pos += staged;
+                staged = 0;
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // read before the next sub-tile overwrites them
-        x.pos += staged;
     }
 }
 
@@ -2872,7 +3019,7 @@ __global__ __launch_bounds__(256) void commit_kernel(const int32_t* __restrict__
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-    size_t status, tables, tables_bytes, tseg, st, seg, bnd_lo, bnd_hi, hist1, ovfc, hist2, coarse, list_key, list_tile,
+    size_t status, tables, tables_bytes, tseg, st, seg, bnd_lo, bnd_hi, bnd_mid, hist1, ovfc, hist2, coarse, list_key, list_tile,
         list_val, list_cnt, samp_hist, samp_grp, cand_cnt, brk_cnt, ovn, ovs, tg0, tin, toff, ttake, tsel, ssd, ssd_t, sss,
         cand_idx, cand_val, brk_key, brk_val, total;
 };
@@ -2923,6 +3070,7 @@ Layout make_layout(int64_t n, int n_cf, int n_seg)
     L.seg = take(sizeof(SegState) * n_seg);
     L.bnd_lo = take(sizeof(uint32_t) * sc);
     L.bnd_hi = take(sizeof(uint32_t) * sc);
+    L.bnd_mid = take(sizeof(uint32_t) * sc);
     const size_t blocks = pool_blocks(n, n_cf, n_seg);
     L.hist1 = take(sizeof(uint32_t) * blocks * NBIN);
     L.ovfc = take(sizeof(uint32_t) * sc * 64 * 32);
@@ -3180,6 +3328,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     p.seg = (SegState*)(ws + L.seg);
     p.bnd_lo = (uint32_t*)(ws + L.bnd_lo);
     p.bnd_hi = (uint32_t*)(ws + L.bnd_hi);
+    p.bnd_mid = (uint32_t*)(ws + L.bnd_mid);
     p.hist1 = (uint32_t*)(ws + L.hist1);
     p.ovfc = (uint32_t*)(ws + L.ovfc);
     p.hist2 = (uint32_t*)(ws + L.hist2);
@@ -3358,7 +3507,10 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     void (*const refine_forms[4])(Params) = {refine_kernel<1>, refine_kernel<2>, refine_kernel<4>, refine_kernel<MAXCF>};
     hipLaunchKernelGGL(refine_forms[ncf_form], dim3(light_grid), dim3(LWG), 0, stream, p);
     hipLaunchKernelGGL(scan_kernel, dim3(ns, scan_slices + n_cf), dim3(SCAN_T), 0, stream, p, scan_slices);
-    hipLaunchKernelGGL(emit_kernel, dim3(light_grid), dim3(LWG), 0, stream, p);
+    {
+        void (*emit)(Params) = (p.random || p.single) ? emit_kernel<true> : emit_kernel<false>;
+        hipLaunchKernelGGL(emit, dim3(light_grid), dim3(LWG), 0, stream, p);
+    }
     }
     if (ev) (void)hipEventRecord((hipEvent_t)ev->call_end, stream);
     if (hipGetLastError() != hipSuccess) return GRAVAC_ERR_HIP;

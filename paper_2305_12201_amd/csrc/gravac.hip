@@ -1969,10 +1969,11 @@ constexpr int SCAN_T = 1024;                 // threads
 constexpr int SCAN_W = SCAN_T / 64;
 constexpr int SCAN_PER = 4;                  // tiles per thread
 constexpr int SCAN_SLICE = SCAN_T * SCAN_PER;
-constexpr int RW = 8;                        // gathered entries per lane where one wavefront holds them all ...
-constexpr uint32_t WAVE_CAP = 64 * RW;       // ... which it does up to this many (no barrier in its search)
-constexpr int LPER = LCAP / SCAN_T;          // gathered entries per thread otherwise
-static_assert(LCAP % SCAN_T == 0 && LPER <= RW, "the gathered entries are dealt evenly");
+constexpr int LPER = LCAP / SCAN_T;          // gathered entries per thread
+constexpr int RW = LPER;
+constexpr int SPEC = SCAN_T / REP;           // threads that fetch the head of one gather list before its length is known
+static_assert(LCAP % SCAN_T == 0 && SCAN_T % REP == 0 && SPEC * LPER <= LCAP && 2 * SCAN_T == NBIN,
+              "the gathered entries are dealt evenly; a thread owns two bins of the search's histogram");
 
 __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
 {
@@ -2001,6 +2002,19 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
     for (int r = 0; r < REP; ++r) fill[r] = (uint32_t)r < copies ? p.list_cnt[(block0 + r) * 32] : 0u;
     const uint32_t mode = st->mode, k = st->k, above = st->above, base = st->base, span = st->span, c = st->c;
     uint32_t tau = st->tau, need = st->need, cnt_gt = st->cnt_gt;   // valid if the located bin was one key wide
+    // ... and the head of every gather list, SPEC * LPER entries of it, before the fill counts are known: a list is
+    // rarely longer than that (the located bin's entries spread over the copies), and a load that waits for the
+    // counts would cost this kernel another round trip to memory
+    const uint32_t spec_r = (uint32_t)tid / SPEC;
+    uint32_t sk[LPER], stl[LPER];
+    float sv[LPER];
+#pragma unroll
+    for (int q = 0; q < LPER; ++q) {
+        const size_t at = (block0 + (spec_r < copies ? spec_r : 0u)) * LCAP + (uint32_t)(tid % SPEC) + (uint32_t)q * SPEC;
+        sk[q] = p.list_key[at];
+        stl[q] = p.list_tile[at];
+        sv[q] = p.random ? p.list_val[at] : 0.0f;
+    }
     // scan: this slice, coalesced (entries above the located bin, entries inside it), and the totals of the
     // earlier slices of this segment; statistics: the tiles' sums, sixteen tiles per thread and round, fixed order
     uint32_t og[SCAN_PER], oi[SCAN_PER], pg = 0, pi = 0;
@@ -2038,9 +2052,7 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
     }
 
     // ---- resolve (segment t, CF j)
-    // This thread's gathered entries: key - base, tile, value, and which of the slots hold one.  Up to WAVE_CAP
-    // entries sit in the block's first wavefront, RW per lane (its search needs no barrier); more are dealt over
-    // the block, LPER per thread.
+    // This thread's gathered entries: key - base, tile, value, and which of the slots hold one (LPER per thread).
     uint32_t d[RW], rt[RW], live = 0;
     float rv[RW];
 #pragma unroll
@@ -2060,7 +2072,7 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
         __syncthreads();
         tau = res3[0]; cnt_gt = res3[1]; need = k - cnt_gt;
     } else if (mode == MODE_GATHER) {
-        // the want-th largest of the listed keys, by a bitwise search on d = key - base.
+        // the want-th largest of the listed keys d = key - base.
         // The keys sit in REP lists; list r holds positions [off_r, off_r + n_r) of the concatenation.
         const uint32_t want = k - above;
         uint32_t off[REP + 1];
@@ -2071,74 +2083,75 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
             if (tid == 0) p.status->error = 1;
             tau = base; need = 0; cnt_gt = above;
         } else {
-            const bool small = c <= WAVE_CAP;
-            const int nq = small ? (wib == 0 ? RW : 0) : LPER;
-            // all loads first, without branches around them (a position past the last key reads key 0 of the lists
-            // instead; c >= 1 here), so that they are in flight together
+            bool spec_ok = true;
 #pragma unroll
-            for (int q = 0; q < RW; ++q) {
-                if (q >= nq) continue;
-                const uint32_t pos = small ? (uint32_t)(q * 64 + lane) : (uint32_t)(q * SCAN_T + tid);
-                const uint32_t i = pos < c ? pos : 0u;
-                int r = 0;
+            for (int r = 0; r < REP; ++r) spec_ok = spec_ok && fill[r] <= (uint32_t)(SPEC * LPER);
+            if (spec_ok) {
+                // the entries are the ones fetched ahead: list spec_r, slots tid % SPEC + q SPEC
+                uint32_t my_fill = 0;
 #pragma unroll
-                for (int x = 1; x < REP; ++x) r += (i >= off[x]);
-                uint32_t o = 0;
+                for (int r = 0; r < REP; ++r) if ((uint32_t)r == spec_r) my_fill = fill[r];   // (0 beyond the segment's copies)
 #pragma unroll
-                for (int x = 0; x < REP; ++x) if (x == r) o = off[x];
-                const size_t at = (block0 + r) * LCAP + (i - o);
-                d[q] = p.list_key[at];
-                rt[q] = p.list_tile[at];
-                rv[q] = p.random ? p.list_val[at] : 0.0f;
-                if (pos < c) live |= 1u << q;
+                for (int q = 0; q < LPER; ++q) {
+                    const uint32_t slot = (uint32_t)(tid % SPEC) + (uint32_t)q * SPEC;
+                    d[q] = sk[q]; rt[q] = stl[q]; rv[q] = sv[q];
+                    if (slot < my_fill) live |= 1u << q;
+                }
+            } else {
+                // a long list: the entries are dealt over the block by their position in the concatenation; all loads
+                // first, without branches around them (a position past the last key reads key 0 of the lists instead;
+                // c >= 1 here), so that they are in flight together
+#pragma unroll
+                for (int q = 0; q < LPER; ++q) {
+                    const uint32_t pos = (uint32_t)(q * SCAN_T + tid);
+                    const uint32_t i = pos < c ? pos : 0u;
+                    int r = 0;
+#pragma unroll
+                    for (int x = 1; x < REP; ++x) r += (i >= off[x]);
+                    uint32_t o = 0;
+#pragma unroll
+                    for (int x = 0; x < REP; ++x) if (x == r) o = off[x];
+                    const size_t at = (block0 + r) * LCAP + (i - o);
+                    d[q] = p.list_key[at];
+                    rt[q] = p.list_tile[at];
+                    rv[q] = p.random ? p.list_val[at] : 0.0f;
+                    if (pos < c) live |= 1u << q;
+                }
             }
 #pragma unroll
-            for (int q = 0; q < RW; ++q) d[q] = ((live >> q) & 1u) ? d[q] - base : 0u;  // padding never counts: trial values are >= 1
+            for (int q = 0; q < LPER; ++q) d[q] = ((live >> q) & 1u) ? d[q] - base : 0u;
+            // The want-th largest d: a histogram of 11 bits of d at a time, from the top bits down (one round unless
+            // the located bin is more than 2048 keys wide), among the entries that agree with the bits found so far.
+            // Thread tid owns bins 2047 - 2 tid and 2046 - 2 tid, so that a scan over the threads runs from the top bin.
             int nbits = 0;
             while (nbits < 32 && (span >> nbits) != 0u) ++nbits;
-            uint32_t prefix = 0, gsum = 0;
-            if (small) {
-                if (wib == 0) {
-                    for (int bit = nbits - 1; bit >= 0; --bit) {
-                        const uint32_t trial = prefix | (1u << bit);
-                        uint32_t cn = 0;
-#pragma unroll
-                        for (int q = 0; q < RW; ++q) cn += (d[q] >= trial);
-                        if (wave_sum(cn) >= want) prefix = trial;
-                    }
-                    uint32_t gt = 0;
-#pragma unroll
-                    for (int q = 0; q < RW; ++q) gt += ((live >> q) & 1u) && (d[q] > prefix);
-                    gt = wave_sum(gt);
-                    if (lane == 0) { res3[0] = prefix; res3[1] = gt; }
-                }
-                __syncthreads();
-                prefix = res3[0]; gsum = res3[1];
-            } else {
-                int buf = 0;
-                for (int bit = nbits - 1; bit >= 0; --bit) {
-                    const uint32_t trial = prefix | (1u << bit);
-                    uint32_t cn = 0;
-#pragma unroll
-                    for (int q = 0; q < LPER; ++q) cn += (d[q] >= trial);
-                    cn = wave_sum(cn);
-                    if (lane == 0) wsum[buf][wib] = cn;
-                    __syncthreads();
-                    uint32_t total = 0;
-#pragma unroll
-                    for (int w = 0; w < SCAN_W; ++w) total += wsum[buf][w];
-                    buf ^= 1;
-                    if (total >= want) prefix = trial;
-                }
-                uint32_t gt = 0;
-#pragma unroll
-                for (int q = 0; q < LPER; ++q) gt += ((live >> q) & 1u) && (d[q] > prefix);
-                gt = wave_sum(gt);
-                __syncthreads();
-                if (lane == 0) wsum[0][wib] = gt;
+            uint32_t prefix = 0, pmask = 0, gsum = 0, left = want;
+            int shift = nbits > 11 ? nbits - 11 : 0;
+            for (;;) {
+                sg[2 * tid] = 0; sg[2 * tid + 1] = 0;
                 __syncthreads();
 #pragma unroll
-                for (int w = 0; w < SCAN_W; ++w) gsum += wsum[0][w];
+                for (int q = 0; q < LPER; ++q)
+                    if (((live >> q) & 1u) && (d[q] & pmask) == prefix) atomicAdd(&sg[(d[q] >> shift) & (NBIN - 1)], 1u);
+                __syncthreads();
+                const uint32_t bA = (uint32_t)(NBIN - 1 - 2 * tid), bB = bA - 1u;
+                const uint32_t hA = sg[bA], hB = sg[bB], mine = hA + hB;
+                const uint32_t incl = wave_scan(mine);
+                if (lane == 63) wsum[0][wib] = incl;
+                __syncthreads();
+                uint32_t higher = incl - mine;   // entries in the bins above this thread's two
+#pragma unroll
+                for (int w = 0; w < SCAN_W; ++w) if (w < wib) higher += wsum[0][w];
+                if (higher < left && higher + hA >= left) { res3[0] = bA; res3[1] = higher; }
+                else if (higher + hA < left && higher + mine >= left) { res3[0] = bB; res3[1] = higher + hA; }
+                __syncthreads();
+                prefix |= res3[0] << shift;
+                pmask |= (uint32_t)(NBIN - 1) << shift;
+                gsum += res3[1];
+                left -= res3[1];
+                if (shift == 0) break;
+                shift = shift > 11 ? shift - 11 : 0;
+                __syncthreads();   // (res3 and the histogram are rewritten in the next round)
             }
             tau = base + prefix; cnt_gt = above + gsum; need = k - cnt_gt;
             __syncthreads();

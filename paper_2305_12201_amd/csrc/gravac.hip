@@ -906,8 +906,10 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
 // bracket ends that fall into its bins, so that no workgroup waits for another.  The kernels that
 // use the brackets derive the histogram shift and the rest from them (bracket_bins).
 // ---------------------------------------------------------------------------------------------
+// (the form with the small tensors is held to 64 registers, so that two of its 1024-thread workgroups fit a CU: a
+// layerwise call has more such workgroups than the chip has CUs)
 template <int G, bool SMALL>  // SMALL: the workgroups of tensors of at most SMALL_MAX elements do the whole step for them
-__global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
+__global__ __launch_bounds__(1024 / G) __attribute__((amdgpu_waves_per_eu(SMALL ? 8 : 1, 8))) void threshold_kernel(Params p)
 {
     constexpr int T = 1024 / G;          // thread i owns the bins 4 (y T + i) .. + 3: two words of every block's histogram
     constexpr int NW = T / 64;
@@ -1008,12 +1010,13 @@ __global__ __launch_bounds__(1024 / G) void threshold_kernel(Params p)
     uint32_t h0 = 0, h1 = 0, h2 = 0, h3 = 0;
     {
         const uint2* src = (const uint2*)(p.samp_hist + (size_t)sb0 * (SBIN / 2)) + (y * T + tid);
-        for (uint32_t b0 = 0; b0 < nb; b0 += 32) {
-            uint2 w[32];
+        constexpr int NB = SMALL ? 16 : 32;   // loads in flight per thread
+        for (uint32_t b0 = 0; b0 < nb; b0 += NB) {
+            uint2 w[NB];
 #pragma unroll
-            for (int q = 0; q < 32; ++q) w[q] = (b0 + q < nb) ? src[(size_t)(b0 + q) * (SBIN / 4)] : make_uint2(0u, 0u);
+            for (int q = 0; q < NB; ++q) w[q] = (b0 + q < nb) ? src[(size_t)(b0 + q) * (SBIN / 4)] : make_uint2(0u, 0u);
 #pragma unroll
-            for (int q = 0; q < 32; ++q) {
+            for (int q = 0; q < NB; ++q) {
                 h0 += w[q].x & 0xFFFFu; h1 += w[q].x >> 16;
                 h2 += w[q].y & 0xFFFFu; h3 += w[q].y >> 16;
             }

@@ -22,9 +22,12 @@
  *   - The library never allocates device memory: scratch space comes from the caller's
  *     `workspace`.  Calls that overlap in time must use different workspaces.
  *   - The library keeps no state between calls, with one exception: layerwise calls pass their segment tables
- *     through a ring of eight pinned host staging buffers that the library allocates on first use (hipHostMalloc,
- *     grown when a larger table arrives, kept until the process ends) and that are shared by all callers of the
- *     process.  Flat-mode calls touch no such state.
+ *     through a ring of up to eight pinned host staging buffers that the library allocates on first use
+ *     (hipHostMalloc, grown when a larger table arrives, kept until the process ends) and that are shared by all
+ *     callers of the process.  A caller that issues layerwise calls faster than the GPU runs them is held, once two
+ *     buffers exist, until the table copy of an earlier layerwise call (on whatever stream it was queued) has run:
+ *     the host then stays at most a call or two ahead.  More buffers are only allocated while others are in the
+ *     hands of concurrent callers.  Flat-mode calls touch no such state.
  *   - HIP graphs: a flat-mode compression (gravac_compress, gravac_randomk_compress, gravac_recompress with
  *     n_seg == 0), gravac_commit and gravac_decompress_accumulate consist of kernel launches only (no copies, no
  *     memsets, no host synchronisation), so they can be recorded into a graph and replayed; the host tables

@@ -3163,13 +3163,20 @@ StagingSlot* staging_acquire(size_t bytes)
     StagingSlot* s = nullptr;
     {
         std::lock_guard<std::mutex> lock(g_staging_mutex);
-        // a slot that is large enough and whose last copy has run, else one that has no memory yet, else any free one
-        for (int pass = 0; pass < 3 && !s; ++pass) {
+        // A slot that is large enough and whose last copy has run; else, while fewer than two slots have memory, one
+        // without (it is allocated below); else one whose copy is still queued (its event is waited for below: the host
+        // then runs at most a call or two ahead of the GPU); else, all of those being held by other callers, one
+        // without memory.  Pinning fresh host memory takes milliseconds and slows the first copy out of it, so a caller
+        // that runs ahead of the GPU does not get a new slot for every call it is ahead.
+        int with_mem = 0;
+        for (int i = 0; i < STAGING_SLOTS; ++i) with_mem += g_staging[i].cap > 0 ? 1 : 0;
+        for (int pass = 0; pass < 4 && !s; ++pass) {
+            if (pass == 1 && with_mem >= 2) continue;
             for (int i = 0; i < STAGING_SLOTS && !s; ++i) {
                 StagingSlot* c = &g_staging[(g_staging_next + i) % STAGING_SLOTS];
                 if (c->busy) continue;
                 const bool ready = c->cap >= bytes && (!c->pending || hipEventQuery(c->done) == hipSuccess);
-                if ((pass == 0 && ready) || (pass == 1 && c->cap == 0) || pass == 2) {
+                if ((pass == 0 && ready) || ((pass == 1 || pass == 3) && c->cap == 0) || (pass == 2 && c->cap > 0)) {
                     s = c;
                     g_staging_next = (g_staging_next + i + 1) % STAGING_SLOTS;
                 }

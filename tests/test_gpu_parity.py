@@ -533,3 +533,28 @@ def test_mass_of_equal_values_at_the_threshold_over_several_scan_slices():
     r = np.zeros(n, np.float32)
     for cf in (3.0, 20.0):
         check(g, r, [cf], what=f"ties over slices cf={cf}")
+
+
+def test_values_on_a_coarse_grid_and_the_repairs_of_the_zeroed_entries():
+    """Gradients whose values sit on a grid of 8 mantissa bits (what a bfloat16 backward pass hands over): a sample
+    bin then holds one or two distinct keys, so the key from which the pass zeroes listed entries lands on either
+    side of the threshold, with ties at it.  Both repairs of the emit step (a selected entry below that key gets
+    +0, an unselected one at or above it gets acc back) are exercised over iterations, flat and layerwise."""
+    n = 2_500_003
+    rng = np.random.default_rng(77)
+
+    def on_grid(x):
+        b = x.astype(np.float32).view(np.uint32)
+        return ((b + 0x8000) & 0xFFFF0000).astype(np.uint32).view(np.float32)
+
+    grads = [on_grid(rng.laplace(0.0, 1e-4, n)) for _ in range(3)]
+    for cfs, commit in (([10.0], 0), ([100.0], 0), ([7.0, 300.0], 0), ([7.0, 300.0], 1)):
+        _iterate(n, cfs, commit, grads, [0, 0, 0])
+    seg = workloads.offsets_of([100_000, 9_000, 1_200_003, 191_000, 1_000_000])
+    res_gpu = np.zeros(n, np.float32)
+    res_ref = np.zeros(n, np.float32)
+    for it in range(3):
+        gpu = gpu_compress(grads[it], res_gpu, [20.0], seg=seg)
+        ref = oracle_compress(grads[it], res_ref, [20.0], seg=seg)
+        assert_same(gpu, ref, f"grid values, layerwise, it{it}")
+        res_gpu, res_ref = gpu[3], ref[3]

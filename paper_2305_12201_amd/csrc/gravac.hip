@@ -1764,7 +1764,7 @@ __global__ __launch_bounds__(256) void locate_kernel(Params p)
 // (the form for four CFs is held to 80 registers, a dozen values spilled: six wavefronts per SIMD instead of four
 // take the ResNet101 shape's tiles in one round instead of two)
 template <int NCF>  // compiled for calls with up to NCF CFs: the loops over the CFs are unrolled
-__global__ __launch_bounds__(LWG) __attribute__((amdgpu_waves_per_eu(NCF == 4 ? 6 : 1, 8))) void refine_kernel(Params p)
+__global__ __launch_bounds__(LWG) __attribute__((amdgpu_waves_per_eu((NCF == 3 || NCF == 4) ? 6 : 1, 8))) void refine_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
     const uint32_t u = __builtin_amdgcn_readfirstlane(blockIdx.x * LWAVES + (threadIdx.x >> 6));
@@ -3484,8 +3484,8 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     const uint32_t light_grid = (p.n_tiles + LWAVES - 1) / LWAVES;
     const uint32_t scan_slices = (max_seg_tiles + SCAN_SLICE - 1) / SCAN_SLICE;
 
-    const int ncf_form = n_cf <= 1 ? 0 : n_cf <= 2 ? 1 : n_cf <= 4 ? 2 : 3;
-    static_assert(MAXCF >= 4, "forms for 1, 2, 4 and MAXCF CFs");
+    const int ncf_form = n_cf <= 1 ? 0 : n_cf <= 2 ? 1 : n_cf <= 3 ? 2 : n_cf <= 4 ? 3 : 4;
+    static_assert(MAXCF >= 4, "forms for 1, 2, 3, 4 and MAXCF CFs");
     static_assert(DENSE_ROUNDS == 4, "forms of the sampling kernel for 1, 2 and 4 groups per thread");
     // (a layerwise call takes SAMPLE_BLOCK samples per block; its small tensors are extra workgroups of this launch)
     const bool have_tiles = p.n_tiles != 0;  // (not if every tensor of a layerwise call is small)
@@ -3503,9 +3503,10 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     else
         hipLaunchKernelGGL((threshold_kernel<1, false>), dim3(ns, 1), dim3(1024), 0, stream, p);
     {
-        // the Top-k pass exists in forms for 1, 2, 4 and MAXCF CFs (its loops over the CFs are unrolled)
-        void (*const ef_forms[4])(Params) = {stream_kernel<SM_EF, false, 1>, stream_kernel<SM_EF, false, 2>,
-                                             stream_kernel<SM_EF, false, 4>, stream_kernel<SM_EF, false, MAXCF>};
+        // the Top-k pass exists in forms for 1, 2, 3, 4 and MAXCF CFs (its loops over the CFs are unrolled)
+        void (*const ef_forms[5])(Params) = {stream_kernel<SM_EF, false, 1>, stream_kernel<SM_EF, false, 2>,
+                                             stream_kernel<SM_EF, false, 3>, stream_kernel<SM_EF, false, 4>,
+                                             stream_kernel<SM_EF, false, MAXCF>};
         void (*kern)(Params) = single ? stream_kernel<SM_SINGLE, false, 1>   // (a second-level call has one CF)
                                       : (random ? stream_kernel<SM_EF, true, MAXCF> : ef_forms[ncf_form]);
         if (!have_tiles) {
@@ -3526,8 +3527,8 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         hipLaunchKernelGGL((stream_kernel<SM_EXACT, false, MAXCF>), dim3(sub_grid < XGRID ? sub_grid : XGRID), dim3(WG), 0, stream, p);
     }
     if (have_tiles) {
-    // the refine kernel loops over the CFs: forms for 1, 2, 4 and MAXCF CFs
-    void (*const refine_forms[4])(Params) = {refine_kernel<1>, refine_kernel<2>, refine_kernel<4>, refine_kernel<MAXCF>};
+    // the refine kernel loops over the CFs: forms for 1, 2, 3, 4 and MAXCF CFs
+    void (*const refine_forms[5])(Params) = {refine_kernel<1>, refine_kernel<2>, refine_kernel<3>, refine_kernel<4>, refine_kernel<MAXCF>};
     hipLaunchKernelGGL(refine_forms[ncf_form], dim3(light_grid), dim3(LWG), 0, stream, p);
     hipLaunchKernelGGL(scan_kernel, dim3(ns, scan_slices + n_cf), dim3(SCAN_T), 0, stream, p, scan_slices);
     {

@@ -908,15 +908,20 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
 // ---------------------------------------------------------------------------------------------
 // (the form with the small tensors is held to 64 registers, so that two of its 1024-thread workgroups fit a CU: a
 // layerwise call has more such workgroups than the chip has CUs)
-template <int G, bool SMALL>  // SMALL: the workgroups of tensors of at most SMALL_MAX elements do the whole step for them
-__global__ __launch_bounds__(1024 / G) __attribute__((amdgpu_waves_per_eu(SMALL ? 8 : 1, 8))) void threshold_kernel(Params p)
+template <int G, bool SMALL, int P = 1>  // SMALL: the workgroups of tensors of at most SMALL_MAX elements do the whole step for them
+__global__ __launch_bounds__(P * 1024 / G) __attribute__((amdgpu_waves_per_eu(SMALL ? 8 : 1, 8))) void threshold_kernel(Params p)
 {
-    constexpr int T = 1024 / G;          // thread i owns the bins 4 (y T + i) .. + 3: two words of every block's histogram
+    constexpr int T = 1024 / G;          // thread i < T owns the bins 4 (y T + i) .. + 3: two words of every block's histogram
+    // P threads per such set of bins: thread i + x T adds up the blocks x, x + P, ... (the 64 to 128 blocks of a flat
+    // sample are then one round of loads per thread, not two to four; two threads are best up to 64 blocks, four beyond)
+    static_assert(P * 1024 / G <= 1024 && (G > 1 || P == 1), "threads of a workgroup");
     constexpr int NW = T / 64;
     static_assert(G == 1 || G == SGRP, "one workgroup per group of bins, or one for all");
     __shared__ uint32_t wtot[NW], gab[NW], gto[NW];
     __shared__ uint32_t rank_lo[MAXCF], rank_hi[MAXCF], rank_mid[MAXCF];
+    __shared__ uint32_t hx[P > 1 ? P - 1 : 1][P > 1 ? T : 1][4];
     const int t = blockIdx.x, y = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+    const int part = tid / T, ot = tid - part * T;
     if (t == 0 && y == 0 && tid == 0) {
         p.status->any_fail = 0; p.status->n_fail = 0; p.status->error = 0; p.status->n_seg = p.n_seg;
         p.status->n_narrow = 0; p.status->count = 0;
@@ -938,7 +943,7 @@ __global__ __launch_bounds__(1024 / G) __attribute__((amdgpu_waves_per_eu(SMALL 
     const bool sampled = p.bounds_from == BOUNDS_SAMPLED;
     if (y == 0) {
         if (!is_flat(p))
-            for (uint32_t u = seg_tile0(p, t) + tid; u < seg_tile1(p, t); u += T) p.tseg[u] = (uint32_t)t;
+            for (uint32_t u = seg_tile0(p, t) + tid; u < seg_tile1(p, t); u += T * P) p.tseg[u] = (uint32_t)t;
         if (tid == 0) p.seg[t].fail = FAIL_NONE;  // the locate step raises it
     }
     if (tid < p.n_cf) {
@@ -999,22 +1004,22 @@ __global__ __launch_bounds__(1024 / G) __attribute__((amdgpu_waves_per_eu(SMALL 
     uint32_t g_above = 0, g_total = 0;
     uint4 ga[2][2];
     static_assert(G == 1 || 2 * (1024 / G) >= 2 * DENSE_BLOCKS, "two blocks' group counts per thread cover a flat sample");
-    if (G > 1) {
+    if (G > 1 && part == 0) {
 #pragma unroll
         for (int x = 0; x < 2; ++x) {
-            const uint32_t b = tid + x * T;
+            const uint32_t b = ot + x * T;
             const uint4* gp = (const uint4*)(p.samp_grp + (size_t)(sb0 + (b < nb ? b : 0u)) * SGRP);
             ga[x][0] = gp[0]; ga[x][1] = gp[1];
         }
     }
     uint32_t h0 = 0, h1 = 0, h2 = 0, h3 = 0;
     {
-        const uint2* src = (const uint2*)(p.samp_hist + (size_t)sb0 * (SBIN / 2)) + (y * T + tid);
+        const uint2* src = (const uint2*)(p.samp_hist + (size_t)sb0 * (SBIN / 2)) + (y * T + ot);
         constexpr int NB = SMALL ? 16 : 32;   // loads in flight per thread
-        for (uint32_t b0 = 0; b0 < nb; b0 += NB) {
+        for (uint32_t b0 = (uint32_t)part; b0 < nb; b0 += NB * P) {
             uint2 w[NB];
 #pragma unroll
-            for (int q = 0; q < NB; ++q) w[q] = (b0 + q < nb) ? src[(size_t)(b0 + q) * (SBIN / 4)] : make_uint2(0u, 0u);
+            for (int q = 0; q < NB; ++q) w[q] = (b0 + q * P < nb) ? src[(size_t)(b0 + q * P) * (SBIN / 4)] : make_uint2(0u, 0u);
 #pragma unroll
             for (int q = 0; q < NB; ++q) {
                 h0 += w[q].x & 0xFFFFu; h1 += w[q].x >> 16;
@@ -1022,10 +1027,22 @@ __global__ __launch_bounds__(1024 / G) __attribute__((amdgpu_waves_per_eu(SMALL 
             }
         }
     }
-    if (G > 1) {
+    if (P > 1) {
+        if (part != 0) {
+            uint32_t* d = hx[part - 1][ot];
+            d[0] = h0; d[1] = h1; d[2] = h2; d[3] = h3;
+            h0 = h1 = h2 = h3 = 0;
+        }
+        __syncthreads();
+        if (part == 0) {
+#pragma unroll
+            for (int x = 0; x < P - 1; ++x) { h0 += hx[x][ot][0]; h1 += hx[x][ot][1]; h2 += hx[x][ot][2]; h3 += hx[x][ot][3]; }
+        }
+    }
+    if (G > 1 && part == 0) {
 #pragma unroll
         for (int x = 0; x < 2; ++x) {
-            if (tid + x * T >= nb) continue;
+            if (ot + x * T >= nb) continue;
             const uint32_t v[8] = {ga[x][0].x, ga[x][0].y, ga[x][0].z, ga[x][0].w, ga[x][1].x, ga[x][1].y, ga[x][1].z, ga[x][1].w};
 #pragma unroll
             for (int g = 0; g < 8; ++g) {
@@ -1039,8 +1056,9 @@ __global__ __launch_bounds__(1024 / G) __attribute__((amdgpu_waves_per_eu(SMALL 
     }
     const uint32_t mine = h0 + h1 + h2 + h3;
     const uint32_t incl = wave_scan(mine);
-    if (lane == 63) wtot[wib] = incl;
+    if (lane == 63 && part == 0) wtot[wib] = incl;
     __syncthreads();
+    if (part != 0) return;   // (no barrier follows)
     uint32_t local = 0, before = 0;
     g_above = 0; g_total = 0;
 #pragma unroll
@@ -1060,7 +1078,7 @@ __global__ __launch_bounds__(1024 / G) __attribute__((amdgpu_waves_per_eu(SMALL 
 #pragma unroll
         for (int q = 3; q >= 0; --q) {
             const uint32_t c = hh[q];
-            const uint32_t bin = 4u * (uint32_t)(y * T + tid) + (uint32_t)q;
+            const uint32_t bin = 4u * (uint32_t)(y * T + ot) + (uint32_t)q;
             // lower edge of the bin of the r_lo-th sample from the top, upper edge of the bin of the r_hi-th
             if (above < r_lo && above + c >= r_lo) p.bnd_lo[id] = sample_bin_first(bin);
             if (above < r_hi && above + c >= r_hi) p.bnd_hi[id] = sample_bin_end(bin);
@@ -3499,7 +3517,12 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     if (n_small)
         hipLaunchKernelGGL((threshold_kernel<1, true>), dim3(ns, 1), dim3(1024), 0, stream, p);
     else if (ns <= 32 && p.bounds_from == BOUNDS_SAMPLED)
-        hipLaunchKernelGGL((threshold_kernel<SGRP, false>), dim3(ns, SGRP), dim3(1024 / SGRP), 0, stream, p);
+    {
+        if (p.n_sample_blocks > 64u * (uint32_t)ns)
+            hipLaunchKernelGGL((threshold_kernel<SGRP, false, 4>), dim3(ns, SGRP), dim3(4096 / SGRP), 0, stream, p);
+        else
+            hipLaunchKernelGGL((threshold_kernel<SGRP, false, 2>), dim3(ns, SGRP), dim3(2048 / SGRP), 0, stream, p);
+    }
     else
         hipLaunchKernelGGL((threshold_kernel<1, false>), dim3(ns, 1), dim3(1024), 0, stream, p);
     {

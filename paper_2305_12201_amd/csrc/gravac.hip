@@ -839,6 +839,11 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
     constexpr int Q = 4 * R;
     uint64_t gpos[R];
     bool live[Q];
+    // stratum g16 of G = S / 16 spans [g16 nt / G, (g16 + 1) nt / G): with nt = G qd + rm that is g16 qd + g16 rm / G, one
+    // 64-bit division per thread and 32-bit ones per stratum (g16 rm < G^2 <= 2^30) instead of 64-bit ones throughout
+    const uint32_t G = S / 16 ? S / 16 : 1u;
+    const uint64_t qd = nt / G;
+    const uint32_t rm = (uint32_t)(nt - qd * G);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const uint32_t g = (lb * R + r) * (SAMPLE_BLOCK / 4) + tid;  // group
@@ -847,7 +852,7 @@ __global__ __launch_bounds__(256) void sample_kernel(Params p)
             // four neighbouring threads share one stratum and one run of 16 elements in it that starts at a multiple
             // of 16 in the flat buffer (a 64-byte line if the buffer is aligned to that)
             const uint32_t g16 = g >> 2;
-            const uint64_t G = S / 16, a = ((uint64_t)g16 * nt) / G, e = ((uint64_t)(g16 + 1) * nt) / G;  // e - a >= 32
+            const uint64_t a = (uint64_t)g16 * qd + (g16 * rm) / G, e = (uint64_t)(g16 + 1) * qd + ((g16 + 1) * rm) / G;  // e - a >= 32
             const uint64_t first = ((uint64_t)s0 + a + 15) & ~15ull;                 // first such run inside the stratum
             const uint32_t runs = (uint32_t)(((uint64_t)s0 + e - first) / 16);        // >= 1
             const uint64_t at = first + 16ull * (hash32(g16 * 0x9E3779B9u + 0x85EBCA6Bu) % runs);

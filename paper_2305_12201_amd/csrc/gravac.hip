@@ -1786,7 +1786,11 @@ __global__ __launch_bounds__(256) void locate_kernel(Params p)
 // ---------------------------------------------------------------------------------------------
 // (the form for four CFs is held to 80 registers, a dozen values spilled: six wavefronts per SIMD instead of four
 // take the ResNet101 shape's tiles in one round instead of two)
-template <int NCF>  // compiled for calls with up to NCF CFs: the loops over the CFs are unrolled
+// HEADS: the heads of the tile's lists are fetched before their lengths are known.  That pays where all tiles'
+// wavefronts are resident at once and the kernel's time is one wavefront's chain of round trips to memory (the
+// ResNet101 shape: 10.1 -> 7.9 us); with more tiles than that the chip is busy either way, and the extra loads and
+// registers cost (the VGG16 shape: 10 -> 14 us), so the host picks the form by the number of tiles.
+template <int NCF, bool HEADS>  // compiled for calls with up to NCF CFs: the loops over the CFs are unrolled
 __global__ __launch_bounds__(LWG) __attribute__((amdgpu_waves_per_eu((NCF == 3 || NCF == 4) ? 6 : 1, 8))) void refine_kernel(Params p)
 {
     const int lane = threadIdx.x & 63;
@@ -1795,6 +1799,16 @@ __global__ __launch_bounds__(LWG) __attribute__((amdgpu_waves_per_eu((NCF == 3 |
     // loads that depend on nothing but the tile number come first, so that they are in flight together
     const int any_fail = p.status->any_fail;
     const double ssd = lane < SUB ? p.ssd[(size_t)u * SUB + lane] : 0.0;
+    // ... among them the heads of the tile's eight lists, before their lengths are known: lane l takes entries
+    // l % 8 + 8 r (r < SPEC_R) of sub-tile l / 8.  A tile whose lists are no longer than that (most tiles of a call
+    // with a CF of 100 or more) is done with one round trip to memory less.  Top-k keys only.
+    constexpr int SPEC_R = HEADS ? 4 : 1;
+    uint32_t spec[SPEC_R];
+    if constexpr (HEADS) {
+        const uint32_t* src = (p.split ? p.brk_key : (const uint32_t*)p.cand_val) + (size_t)u * TW + (size_t)(lane >> 3) * TS + (lane & 7);
+#pragma unroll
+        for (int r = 0; r < SPEC_R; ++r) spec[r] = src[8 * r];
+    }
     uint32_t on[NCF];
     double os[NCF];
 #pragma unroll
@@ -1899,7 +1913,25 @@ __global__ __launch_bounds__(LWG) __attribute__((amdgpu_waves_per_eu((NCF == 3 |
         // otherwise (most tiles hold a hundred entries or so, and a round that no lane has an entry for costs as many
         // instructions as a full one)
         uint32_t i0 = 0;
-        if (cnt >= LONG_WALK) {
+        if constexpr (HEADS) {
+            // the lists' heads cover the tile if every list is its sub-tile's expected one and short enough
+            bool heads = !p.random;
+            const uint32_t expect = p.split ? 0u : 0xFFu;
+#pragma unroll
+            for (int j = 0; j < SUB; ++j) heads = heads && tr.tl.start[j + 1] - tr.tl.start[j] <= 8u * SPEC_R;
+            if (heads && tr.main_mask == expect) {
+                uint32_t mine_cnt = 0;
+#pragma unroll
+                for (int j = 0; j < SUB; ++j) if ((lane >> 3) == j) mine_cnt = tr.tl.start[j + 1] - tr.tl.start[j];
+#pragma unroll
+                for (int r = 0; r < SPEC_R; ++r) {
+                    if (__ballot((uint32_t)(lane & 7) + 8u * r < mine_cnt) == 0ull) break;
+                    take(spec[r] & 0x7FFFFFFFu, 0.0f, (uint32_t)(lane & 7) + 8u * r < mine_cnt);
+                }
+                i0 = cnt;
+            }
+        }
+        if (i0 < cnt && cnt >= LONG_WALK) {
             // long lists (a low CF): sub-tile by sub-tile, so that no lane has to search for its entry's slot; two
             // rounds per sub-tile are loaded while the sub-tile before it is worked on, whatever it holds
             const auto counts = [&](int j, uint32_t& c, bool& from_main) {
@@ -3556,8 +3588,13 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     }
     if (have_tiles) {
     // the refine kernel loops over the CFs: forms for 1, 2, 3, 4 and MAXCF CFs
-    void (*const refine_forms[5])(Params) = {refine_kernel<1>, refine_kernel<2>, refine_kernel<3>, refine_kernel<4>, refine_kernel<MAXCF>};
-    hipLaunchKernelGGL(refine_forms[ncf_form], dim3(light_grid), dim3(LWG), 0, stream, p);
+    // (... and with or without the early loads of the lists' heads: with them if the tiles' wavefronts are all resident
+    // at once, six per SIMD on 1024 SIMDs)
+    void (*const refine_forms[2][5])(Params) = {
+        {refine_kernel<1, false>, refine_kernel<2, false>, refine_kernel<3, false>, refine_kernel<4, false>, refine_kernel<MAXCF, false>},
+        {refine_kernel<1, true>, refine_kernel<2, true>, refine_kernel<3, true>, refine_kernel<4, true>, refine_kernel<MAXCF, true>}};
+    const int heads = (!random && p.n_tiles <= 6144u) ? 1 : 0;
+    hipLaunchKernelGGL(refine_forms[heads][ncf_form], dim3(light_grid), dim3(LWG), 0, stream, p);
     hipLaunchKernelGGL(scan_kernel, dim3(ns, scan_slices + n_cf), dim3(SCAN_T), 0, stream, p, scan_slices);
     {
         void (*emit)(Params) = (p.random || p.single) ? emit_kernel<true> : emit_kernel<false>;

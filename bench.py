@@ -246,6 +246,32 @@ def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None, only=
         i2, v2, rec["level2_10_to_100_us"] = level2(i1, v1, 10.0)
         _, _, rec["level2_100_to_1000_us"] = level2(i2, v2, 10.0)
         _, _, rec["level2_10_to_1000_us"] = level2(i1, v1, 100.0)
+
+        # One iteration of Alg. 1 that evaluates CF 10 and CF 100 and sends the CF 100 message, two ways: the level-1
+        # call commits and the level-2 call puts the unselected values back into the residual; or the level-1 call
+        # does not commit (GRAVAC_FLAG_NO_COMMIT), the level-2 call leaves the residual alone, and the message that
+        # is sent is committed afterwards.  Both leave the same residual.
+        kk = binding.gravac_topk_count(i1.numel(), 10.0)
+        ws2 = torch.empty(binding.gravac_workspace_bytes(i1.numel(), 1, 0), dtype=torch.uint8, device="cuda")
+        oi = torch.empty(kk, dtype=torch.int32, device="cuda")
+        ov = torch.empty(kk, dtype=torch.float32, device="cuda")
+        st = torch.zeros(1, 4, dtype=torch.float64, device="cuda")
+        for key, no_commit in (("iteration_10_and_100_restore_us", False), ("iteration_10_and_100_no_commit_us", True)):
+            ts = []
+            for rep in range(8):
+                r.zero_()
+                ct.flush.fill_(1.0)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                a_i, a_v, _ = comp(g, r, flags=binding.FLAG_NO_COMMIT if no_commit else 0)
+                binding.gravac_recompress(a_i, a_v, 10.0, None, None if no_commit else r, out_idx=oi, out_val=ov,
+                                          out_stats=st, workspace=ws2)
+                if no_commit:
+                    binding.gravac_commit(oi, r)
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            rec[key] = round(float(np.median(ts[2:])) * 1e3, 1)
         log(json.dumps(rec))
         rows.append(rec)
         del g, r, comp, i1, v1, i2, v2

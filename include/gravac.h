@@ -64,6 +64,12 @@ extern "C" {
 /* flags of the compression calls (0 = none; any other bit is refused) */
 #define GRAVAC_FLAG_FORCE_FALLBACK 1u /* a testing aid: skip the sampled threshold estimate, so that every segment takes
                                          the exact-histogram route (same results, more passes over memory) */
+#define GRAVAC_FLAG_NO_COMMIT 2u      /* gravac_compress, gravac_randomk_compress: nothing is removed from the residual, which
+                                         receives acc = residual + grad as it is; message and statistics are the same.  For
+                                         a caller that evaluates two CFs and decides afterwards which message to send
+                                         (Alg. 1): compress at theta_min with this flag, derive the candidate CF's message
+                                         from that message (gravac_recompress with residual == NULL), then remove the
+                                         message that is sent with gravac_commit.  Not accepted by the other calls. */
 
 /*
  * Number of pairs a call will emit for a tensor of n elements at compression factor cf:
@@ -88,7 +94,7 @@ int gravac_workspace_bytes(int64_t n, int n_cf, int n_seg, size_t* bytes_out);
  *
  *   grad        device, float[n], read only.
  *   residual    device, float[n].  In: the leftover of earlier iterations.
- *               Out: acc with the committed selection's slots set to +0.0f.
+ *               Out: acc with the committed selection's slots set to +0.0f (with GRAVAC_FLAG_NO_COMMIT: acc).
  *               (Both may start at any float boundary; the fast path, 16-byte accesses, is taken when both are
  *               16-byte aligned, as every allocator's buffers are.)
  *   n           1 <= n <= 2^31 - 1 (indices are int32).
@@ -108,7 +114,7 @@ int gravac_workspace_bytes(int64_t n, int n_cf, int n_seg, size_t* bytes_out);
  *                 |acc| of the smallest selected entry }.
  *   workspace   device, 256-byte aligned, at least gravac_workspace_bytes(n, n_cf, n_seg) bytes.
  *               Contents on entry are irrelevant; contents on exit are unspecified.
- *   flags       0, or GRAVAC_FLAG_FORCE_FALLBACK.
+ *   flags       0, or GRAVAC_FLAG_FORCE_FALLBACK and / or GRAVAC_FLAG_NO_COMMIT.
  */
 int gravac_compress(const float* grad, float* residual, int64_t n,
                     const double* cf_list, int n_cf, int commit,

@@ -25,6 +25,7 @@ ERR_STATIC_LIMIT = -6
 STATIC_SCRATCH_BYTES = 4 << 20
 MAX_CF = 8
 FLAG_FORCE_FALLBACK = 1
+FLAG_NO_COMMIT = 2
 
 EXPORTS = (
     "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_compress_profiled", "gravac_randomk_compress", "gravac_threshold_compress", "gravac_recompress", "gravac_commit",

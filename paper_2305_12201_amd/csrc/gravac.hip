@@ -173,6 +173,7 @@ struct Params {
     int64_t n_restore;       // its length
     int single;              // 1 = single-source mode (second-level compression of a message)
     int random;              // 1 = Random-k: the order is that of a keyed priority of the index, not of |acc|
+    int no_commit;           // 1: nothing is removed from the residual (it keeps acc); the caller commits a message later
     int vec_ok;              // 1 if every buffer the kernels read or write with 16-byte accesses is aligned to 16 bytes
     int split;               // 1 if the committed CF is not the lowest of the list: the entries inside the brackets then get a
                              // list of their own everywhere; 0: a sub-tile's candidate list, where it has one, holds them all
@@ -761,7 +762,7 @@ __device__ __forceinline__ void small_segment(const Params& p, int t, SmallShare
                 p.out_idx[o] = p.single ? p.map_idx[s0 + first + e] : (int32_t)(s0 + first + e);
             }
             ++o;
-            sh.a[small_at(first + e)] = 0.0f;
+            if (!p.no_commit) sh.a[small_at(first + e)] = 0.0f;
         }
     }
     if (tid == 0) {
@@ -1120,7 +1121,7 @@ __global__ __launch_bounds__(P * 1024 / G) __attribute__((amdgpu_waves_per_eu(SM
 // scattered 4-byte store costs the memory a read and a write of its 64 bytes, 34 us per million of them.
 __device__ __forceinline__ uint32_t zero_from(const Params& p, int t, uint32_t lo, uint32_t top)
 {
-    if (p.single || top == KEY_END) return NONE;
+    if (p.single || p.no_commit || top == KEY_END) return NONE;
     const uint32_t mid = p.bnd_mid[(size_t)t * p.n_cf + p.commit];
     if (mid == NONE) return top;
     return mid < lo ? lo : (mid > top ? top : mid);
@@ -2407,6 +2408,7 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
 struct EmitCtx {
     uint32_t tau, take, pz;
     bool put_back;
+    bool zero;   // selected entries are removed from the residual (not in a call without commit)
     int64_t pos, lim;
     uint32_t erun;
 };
@@ -2433,7 +2435,7 @@ __device__ __forceinline__ void emit_listed(const Params& p, EmitCtx& x, int32_t
             ov[o] = val;
             if (!single) {
                 oi[o] = idx;
-                if (key < x.pz) p.res[idx] = 0.0f;
+                if (x.zero && key < x.pz) p.res[idx] = 0.0f;
             } else {
                 const int mi = p.map_idx[idx];  // position in the message -> index in the gradient
                 oi[o] = mi;
@@ -2484,6 +2486,7 @@ __global__ __launch_bounds__(LWG) __attribute__((amdgpu_waves_per_eu(HEADS ? 6 :
     // not, which can only be when the threshold turned out to lie at or above pz.
     x.pz = (single || p.seg[t].fail == FAIL_FULL) ? NONE : p.seg[t].pz;
     x.put_back = x.pz != NONE && x.tau >= x.pz;
+    x.zero = !p.no_commit;
     if (p.bounds_from == BOUNDS_FIXED && (int64_t)p.status->count > p.total_out) {
         // threshold sparsifier, more entries kept than the caller's buffers hold: nothing is emitted and nothing removed.
         // The listed sub-tiles get back the values the pass replaced by +0; the others kept acc.
@@ -2538,7 +2541,7 @@ __global__ __launch_bounds__(LWG) __attribute__((amdgpu_waves_per_eu(HEADS ? 6 :
                     if (o < room) {
                         ov[o] = va[e];
                         oi[o] = ia[e];
-                        if (key[e] < x.pz) p.res[ia[e]] = 0.0f;
+                        if (x.zero && key[e] < x.pz) p.res[ia[e]] = 0.0f;
                     } else {
                         p.status->error = 1;  // cannot happen if the counts are consistent; never write out of range
                     }
@@ -2731,7 +2734,7 @@ __global__ __launch_bounds__(LWG) __attribute__((amdgpu_waves_per_eu(HEADS ? 6 :
                 sval[o] = a[e];
                 ++o;
             }
-            if (!single) {
+            if (!single && x.zero) {
                 v4f r;
                 r.x = sel[0] ? 0.0f : a[0]; r.y = sel[1] ? 0.0f : a[1];
                 r.z = sel[2] ? 0.0f : a[2]; r.w = sel[3] ? 0.0f : a[3];
@@ -3421,7 +3424,8 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     if ((!out_idx || !out_val) && !(fixed && out_capacity == 0)) return GRAVAC_ERR_INVALID_ARG;
     if (n <= 0 || n > 2147483647LL || n_cf < 1 || n_cf > MAXCF || commit < 0 || commit >= n_cf) return GRAVAC_ERR_INVALID_ARG;
     if (((uintptr_t)grad & 3) || ((uintptr_t)residual & 3) || ((uintptr_t)map_idx & 3)) return GRAVAC_ERR_INVALID_ARG;
-    if (flags & ~(unsigned)GRAVAC_FLAG_FORCE_FALLBACK) return GRAVAC_ERR_INVALID_ARG;
+    if (flags & ~(unsigned)(GRAVAC_FLAG_FORCE_FALLBACK | GRAVAC_FLAG_NO_COMMIT)) return GRAVAC_ERR_INVALID_ARG;
+    if ((flags & GRAVAC_FLAG_NO_COMMIT) && (single || fixed)) return GRAVAC_ERR_INVALID_ARG;
     if (n_seg < 0 || (n_seg > 0 && !seg_offsets) || (int64_t)n_seg > n) return GRAVAC_ERR_INVALID_ARG;
     if (ev && (!ev->call_begin || !ev->pass_begin || !ev->pass_end || !ev->call_end)) return GRAVAC_ERR_INVALID_ARG;
     double cf_max = 1.0, cf_min = cf_list[0];
@@ -3448,6 +3452,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     // 16-byte accesses need 16-byte aligned buffers; anything else is read and written element by element
     p.vec_ok = (((uintptr_t)grad & 15) == 0 && ((uintptr_t)residual & 15) == 0 && ((uintptr_t)map_idx & 15) == 0) ? 1 : 0;
     p.split = (cf_list[commit] > cf_min) ? 1 : 0;
+    p.no_commit = (flags & GRAVAC_FLAG_NO_COMMIT) ? 1 : 0;
     p.bounds_from = (flags & GRAVAC_FLAG_FORCE_FALLBACK) ? BOUNDS_FORCED : (random ? BOUNDS_RANDOM : BOUNDS_SAMPLED);
     if (fixed) {
         p.bounds_from = BOUNDS_FIXED;

@@ -200,7 +200,11 @@ int gravac_threshold_compress(const float* grad, float* residual, int64_t n, flo
  *               ratio (1 if the denominator is 0), |val| of the smallest selected entry }.  The ratio
  *               times the level-1 gain is the gain at theta2 (Sec. IV-C).
  *   workspace   device, 256-byte aligned, at least gravac_workspace_bytes(k1, 1, n_seg) bytes.
- *   flags       as for gravac_compress.
+ *   flags       0, or GRAVAC_FLAG_FORCE_FALLBACK.
+ * Putting the unselected values back costs a scattered store per level-1 entry (most of the call's time for a
+ * level-1 message that holds a tenth of the gradient).  A caller that has not committed the level-1 message
+ * (gravac_compress with GRAVAC_FLAG_NO_COMMIT) passes residual == NULL here and commits the message it sends with
+ * gravac_commit.
  */
 int gravac_recompress(const int32_t* idx1, const float* val1, int64_t k1, double cf_rel,
                       const int64_t* seg_counts, int n_seg,
@@ -212,7 +216,8 @@ int gravac_recompress(const int32_t* idx1, const float* val1, int64_t k1, double
 
 /*
  * Commit of a message into the residual (Alg. 1, residual update of the branch taken): residual[idx[i]] =
- * +0.0f for i < count.  With it the controller can take back the deferred commit of gravac_recompress:
+ * +0.0f for i < count.  After a level-1 call with GRAVAC_FLAG_NO_COMMIT it removes the message that is sent, level 1
+ * or level 2, from a residual that still holds acc.  With it the controller can also take back the deferred commit of gravac_recompress:
  * after gravac_compress at theta_min and gravac_recompress on its message the residual is the one of the
  * candidate CF; committing the level-1 message's indices makes it the residual of theta_min again.
  * (For the dense branch, gravac_decompress_accumulate of the level-2 message into the residual gives back

@@ -27,8 +27,12 @@ def _t_iter(choice, cf):
     return 0.05 + (0.0 if choice == co.SEND_DENSE else 0.01) + 0.4 / cf
 
 
+@pytest.mark.parametrize("protocol", ["restore", "no_commit"])
 @pytest.mark.parametrize("epsilon,policy", [(0.55, "geometric"), (0.8, "exponential"), (0.97, "geometric")])
-def test_adaptive_loop_matches_the_oracle_loop(epsilon, policy):
+def test_adaptive_loop_matches_the_oracle_loop(epsilon, policy, protocol):
+    # protocol "restore": the level-1 call commits and the level-2 call puts the unselected values back;
+    # "no_commit": the level-1 call removes nothing, the level-2 call gets no residual, the message sent is committed
+    nc = protocol == "no_commit"
     n, iters, window = 300_007, 36, 4
     theta_min, theta_max, omega, alpha = 4.0, 512.0, 0.02, 0.32
     st = co.State(theta_min, theta_max, epsilon, omega, window, policy, alpha=alpha, N_b=256.0)
@@ -44,25 +48,29 @@ def test_adaptive_loop_matches_the_oracle_loop(epsilon, policy):
         # ---- GPU side
         tmin, tc, rel = ctl.candidates()
         comp = binding.Compressor(n, [tmin], 0)
-        i1, v1, s1 = comp(torch.from_numpy(g).cuda(), res_gpu)
+        i1, v1, s1 = comp(torch.from_numpy(g).cuda(), res_gpu, flags=binding.FLAG_NO_COMMIT if nc else 0)
         k1 = i1.numel()
         k2 = binding.gravac_topk_count(k1, rel)
         ws2 = torch.empty(binding.gravac_workspace_bytes(k1, 1, 0), dtype=torch.uint8, device="cuda")
         i2 = torch.empty(k2, dtype=torch.int32, device="cuda")
         v2 = torch.empty(k2, dtype=torch.float32, device="cuda")
         s2 = torch.zeros(1, 4, dtype=torch.float64, device="cuda")
-        binding.gravac_recompress(i1, v1, rel, None, res_gpu, out_idx=i2, out_val=v2, out_stats=s2, workspace=ws2)
+        binding.gravac_recompress(i1, v1, rel, None, None if nc else res_gpu, out_idx=i2, out_val=v2, out_stats=s2,
+                                  workspace=ws2)
         gain_min = float(s1[0, 0, 2].item())
         gain_c = float(s2[0, 0].item() / s1[0, 0, 1].item()) if s1[0, 0, 1].item() > 0 else 1.0
         choice, dmin, dc = ctl.decide(gain_min, gain_c)
         if choice == binding.SEND_CANDIDATE:
+            if nc:
+                binding.gravac_commit(i2, res_gpu)
             sent_i, sent_v = i2, v2
         elif choice == binding.SEND_MIN:
             binding.gravac_commit(i1, res_gpu)
             sent_i, sent_v = i1, v1
         else:
-            binding.gravac_decompress_accumulate(i2, v2, [k2], res_gpu)     # residual + message = acc
-            dense_sent = res_gpu.clone()
+            if not nc:
+                binding.gravac_decompress_accumulate(i2, v2, [k2], res_gpu)     # residual + message = acc
+            dense_sent = res_gpu.clone()                                        # (no_commit: the residual holds acc)
             res_gpu.zero_()
         torch.cuda.synchronize()
         assert binding.gravac_read_status(comp.workspace)["internal_error"] == 0

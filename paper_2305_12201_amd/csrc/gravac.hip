@@ -2810,7 +2810,7 @@ __device__ __forceinline__ void lower_bounds_32(const int32_t* idx, int64_t a, i
 }
 
 __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restrict__ idx, const float* __restrict__ val,
-                                                         WorkerOffsets wo, int W, int64_t n, float* dense)
+                                                         WorkerOffsets wo, int W, int64_t n, float* dense, float alpha)
 {
     __shared__ __attribute__((aligned(16))) float acc[DTILE];
     __shared__ int64_t lo[DGROUP], hi[DGROUP];
@@ -2913,7 +2913,7 @@ __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restri
                 for (int w = wmin; w <= wmax; ++w) {
 #pragma unroll
                     for (int q = 0; q < DBATCH; ++q)
-                        if (pw[q] == w) acc[pj[q]] += pv[q];
+                        if (pw[q] == w) acc[pj[q]] = __fadd_rn(acc[pj[q]], __fmul_rn(alpha, pv[q]));
                     __syncthreads();
                 }
             }
@@ -2991,16 +2991,23 @@ __global__ __launch_bounds__(256) void bounds_kernel(const int32_t* __restrict__
 
 constexpr int DCHUNK = 32;  // tiles whose boundaries a workgroup fetches in one round of loads
 constexpr int DENT = 768;   // (tile, worker) entries of such a chunk
+#ifndef GRAVAC_DSPARSE
+#define GRAVAC_DSPARSE 512
+#endif
+constexpr uint32_t DSPARSE = GRAVAC_DSPARSE;   // a tile with at most this many pairs is updated entry by entry
+constexpr int DSLOTS = (DSPARSE + 255) / 256;  // pairs per thread of such a tile
 
 // A workgroup takes the tiles blockIdx.x, blockIdx.x + gridDim.x, ...  It first fetches, for a chunk of its
 // tiles at once, every worker's boundaries (one round of independent loads instead of one dependent round per
 // tile) and then walks over the chunk's tiles; a tile no message has a pair in costs no further memory access.
 __global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __restrict__ idx, const float* __restrict__ val,
                                                             WorkerOffsets wo, int W, int64_t n, float* dense,
-                                                            const uint32_t* __restrict__ bounds)
+                                                            const uint32_t* __restrict__ bounds, float alpha)
 {
     __shared__ __attribute__((aligned(16))) float acc[DTILE];
     __shared__ uint32_t blo[DENT], bcnt[DENT];      // first pair and number of pairs, per (tile of the chunk, worker)
+    __shared__ uint32_t btot[DCHUNK];               // pairs of all workers, per tile of the chunk
+    __shared__ uint32_t spre[DMAXW + 1];            // a sparse tile's pairs before worker w, in worker-major order
     __shared__ int64_t wat[DMAXW + 1];              // start of every worker's message
     __shared__ int32_t first[DMAXW], last[DMAXW];   // smallest and largest index of every worker's message
     const int tid = threadIdx.x;
@@ -3016,6 +3023,8 @@ __global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __res
     const int tc = DENT / Wp < DCHUNK ? DENT / Wp : DCHUNK;       // tiles per chunk (>= 12: Wp <= 64)
     for (int64_t c0 = blockIdx.x; c0 < ntile; c0 += (int64_t)tc * gridDim.x) {
         __syncthreads();  // first / last / wat are written; the previous chunk's entries are no longer read
+        if (tid < DCHUNK) btot[tid] = 0;
+        __syncthreads();
         for (int e = tid; e < tc * Wp; e += 256) {
             const int i = e / Wp, w = e - i * Wp;
             const int64_t tile = c0 + (int64_t)i * gridDim.x;
@@ -3036,6 +3045,7 @@ __global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __res
             }
             blo[e] = l;
             bcnt[e] = c;
+            if (c) atomicAdd(&btot[i], c);
         }
         __syncthreads();
         for (int i = 0; i < tc; ++i) {
@@ -3043,6 +3053,64 @@ __global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __res
             if (tile >= ntile) break;
             const int64_t base = tile * DTILE;
             const int len = (int)((n - base < DTILE) ? n - base : DTILE);
+            const uint32_t tot = btot[i];
+            if (tot == 0) continue;  // no message touches the tile
+            if (tot <= DSPARSE) {
+                // Few pairs: only the entries they name are read and written back, not the whole tile (a scattered
+                // access moves 64 bytes, so this pays up to about one pair per 16 entries).  The entries go through
+                // the tile buffer all the same, so that pairs of different workers with the same index are added in
+                // worker order.
+                if (tid < 64) {
+                    const uint32_t inc = wave_scan(tid < Wp ? bcnt[i * Wp + tid] : 0u);
+                    spre[tid + 1] = inc;
+                    if (tid == 0) spre[0] = 0;
+                }
+                __syncthreads();
+                int pj[DSLOTS], pw[DSLOTS];
+                float pv[DSLOTS], dv[DSLOTS];
+                int64_t at[DSLOTS];
+                // the tile's pairs in worker-major order, DSLOTS per thread (a slot past the last pair takes the last
+                // pair's place and is not applied)
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q) {
+                    const uint32_t slot = q * 256 + tid;
+                    const uint32_t sc = slot < tot ? slot : tot - 1;
+                    int w = 0;
+#pragma unroll
+                    for (int step = 32; step >= 1; step >>= 1)
+                        if (spre[w + step] <= sc) w += step;   // spre[64] = tot > sc: w stays below 64
+                    at[q] = wat[w] + (int64_t)blo[i * Wp + w] + (int64_t)(sc - spre[w]);
+                    pw[q] = slot < tot ? w : -1;
+                }
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q) pj[q] = idx[at[q]];
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q) pv[q] = val[at[q]];
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q) {
+                    const int64_t j = (int64_t)pj[q] - base;
+                    if (j < 0 || j >= len) pw[q] = -1;   // an index outside the tile (malformed message) is ignored
+                    pj[q] = (int)(j < 0 || j >= len ? 0 : j);
+                }
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q) dv[q] = pw[q] >= 0 ? dense[base + pj[q]] : 0.0f;
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q)
+                    if (pw[q] >= 0) acc[pj[q]] = dv[q];  // the same value from every pair of that entry
+                __syncthreads();
+                for (int w = 0; w < W; ++w) {
+                    if (bcnt[i * Wp + w] == 0) continue;
+#pragma unroll
+                    for (int q = 0; q < DSLOTS; ++q)
+                        if (pw[q] == w) acc[pj[q]] = __fadd_rn(acc[pj[q]], __fmul_rn(alpha, pv[q]));
+                    __syncthreads();
+                }
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q)
+                    if (pw[q] >= 0) dense[base + pj[q]] = acc[pj[q]];
+                __syncthreads();  // the tile buffer and spre are free again
+                continue;
+            }
             bool loaded = false;
             for (int w0 = 0; w0 < W; w0 += DGROUP) {
                 const uint32_t* cg = bcnt + i * Wp + w0;
@@ -3112,7 +3180,7 @@ __global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __res
                     for (int w = wmin; w <= wmax; ++w) {
 #pragma unroll
                         for (int q = 0; q < DBATCH; ++q)
-                            if (pw[q] == w) acc[pj[q]] += pv[q];
+                            if (pw[q] == w) acc[pj[q]] = __fadd_rn(acc[pj[q]], __fmul_rn(alpha, pv[q]));
                         __syncthreads();
                     }
                 }
@@ -3768,7 +3836,7 @@ int gravac_decompress_workspace_bytes(int W, int64_t n, size_t* bytes_out)
 // bounds: device memory for the tile boundaries of up to DMAXW messages (the caller's workspace or the library's static
 // scratch, already checked for size), or null for the search path.
 static int decompress_impl(const int32_t* idx, const float* val, const int64_t* counts, int W, int64_t n, float* dense_out,
-                           uint32_t* bounds, void* stream_v)
+                           float alpha, uint32_t* bounds, void* stream_v)
 {
     hipStream_t stream = (hipStream_t)stream_v;
     if (!counts || !dense_out || W < 1 || n <= 0 || n > 2147483647LL) return GRAVAC_ERR_INVALID_ARG;
@@ -3800,9 +3868,9 @@ static int decompress_impl(const int32_t* idx, const float* val, const int64_t* 
             hipLaunchKernelGGL(bounds_kernel, dim3(pair_blocks, (uint32_t)wn), dim3(256), 0, stream, idx, wo, ntile,
                                bounds);
             hipLaunchKernelGGL(decompress_ws_kernel, dim3(grid), dim3(256), 0, stream, idx, val, wo, wn, n, dense_out,
-                               (const uint32_t*)bounds);
+                               (const uint32_t*)bounds, alpha);
         } else {
-            hipLaunchKernelGGL(decompress_kernel, dim3(grid), dim3(256), 0, stream, idx, val, wo, wn, n, dense_out);
+            hipLaunchKernelGGL(decompress_kernel, dim3(grid), dim3(256), 0, stream, idx, val, wo, wn, n, dense_out, alpha);
         }
     }
     if (hipGetLastError() != hipSuccess) return GRAVAC_ERR_HIP;
@@ -3819,7 +3887,7 @@ int gravac_decompress_accumulate(const int32_t* idx, const float* val, const int
         if (gravac_decompress_workspace_bytes(W, n, &need) != GRAVAC_OK) return GRAVAC_ERR_INVALID_ARG;
         if (((uintptr_t)workspace & 255) || workspace_bytes < need) return GRAVAC_ERR_WORKSPACE;
     }
-    return decompress_impl(idx, val, counts, W, n, dense_out, (uint32_t*)workspace, stream_v);
+    return decompress_impl(idx, val, counts, W, n, dense_out, 1.0f, (uint32_t*)workspace, stream_v);
 }
 
 int gravac_decompress_accumulate_static(const int32_t* idx, const float* val, const int64_t* counts, int W, int64_t n,
@@ -3831,7 +3899,7 @@ int gravac_decompress_accumulate_static(const int32_t* idx, const float* val, co
     if (need > (size_t)GRAVAC_STATIC_SCRATCH_BYTES) return GRAVAC_ERR_STATIC_LIMIT;
     uint32_t* bounds = nullptr;
     if (const int rc = static_scratch(&bounds)) return rc;
-    return decompress_impl(idx, val, counts, W, n, dense_out, bounds, stream_v);
+    return decompress_impl(idx, val, counts, W, n, dense_out, 1.0f, bounds, stream_v);
 }
 
 int gravac_read_status(const void* workspace, void* stream_v, int32_t* out8)

@@ -291,13 +291,17 @@ def test_repeat_runs_are_bit_identical_and_grad_is_untouched():
 # decompression
 # --------------------------------------------------------------------------
 
-def _decompress_case(n, ks, seed, offset_elems=0):
+def _decompress_case(n, ks, seed, offset_elems=0, common=0):
     from oracle import oracle
     rng = np.random.default_rng(seed)
     idxs, vals = [], []
+    shared = rng.choice(n, size=common, replace=False)     # indices every worker's message holds
     for k in ks:
-        idxs.append(np.sort(rng.choice(n, size=k, replace=False)).astype(np.int32))
-        vals.append(rng.standard_normal(k).astype(np.float32))
+        own = rng.choice(n, size=k, replace=False)
+        own = np.setdiff1d(own, shared)[:max(k - common, 0)]
+        idxs.append(np.sort(np.concatenate([shared[:min(common, k)], own])).astype(np.int32))
+        vals.append(rng.standard_normal(idxs[-1].size).astype(np.float32))
+    ks = [i.size for i in idxs]
     idx = np.concatenate(idxs) if ks else np.zeros(0, np.int32)
     val = np.concatenate(vals) if ks else np.zeros(0, np.float32)
     dense = rng.standard_normal(n).astype(np.float32)
@@ -326,6 +330,19 @@ def test_decompress_accumulate_small_and_ragged():
     _decompress_case(100_003, [5000] * 8, seed=4)
     _decompress_case(100_003, [5000] * 8, seed=5, offset_elems=1)     # dense buffer not 16-byte aligned
     _decompress_case(50_000, [100] * 70, seed=6)                       # more than 64 workers: two launches
+
+
+def test_decompress_tiles_with_few_pairs():
+    # tiles of 8192 entries with a handful of pairs each take another route through the kernel (only the named
+    # entries are read and written) than tiles with many; the same entry named by several workers must still be
+    # added to in worker order
+    _decompress_case(1_000_003, [300] * 8, seed=11, common=120)
+    _decompress_case(1_000_003, [300] * 8, seed=12, common=120, offset_elems=3)
+    _decompress_case(200_000, [40] * 64, seed=13, common=25)           # 64 workers, about 100 pairs per tile
+    _decompress_case(300_000, [30] * 70, seed=14, common=10)           # two launches
+    _decompress_case(81_920, [640] * 8, seed=15, common=300)           # about 512 pairs per tile: both routes in one call
+    _decompress_case(81_920 + 77, [64, 0, 1, 640, 0, 3, 512, 9], seed=16, common=0)
+    _decompress_case(5, [5, 5, 5], seed=17, common=5)
 
 
 def test_decompress_gaps_clusters_and_out_of_range_indices():

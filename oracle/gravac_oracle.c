@@ -14,7 +14,8 @@
  *                                                         Alg. 1 gain lines) for every candidate CF
  *   5. the same per tensor ("layerwise", Sec. III-A)     with global indices
  *   6. decompression: rebuild to the dense dimension     (Sec. III-A, t_decompress) and sum the
- *      workers' contributions
+ *      workers' contributions; the same applied to the parameters as the step -eta * aggregate
+ *      (Alg. 1, update of w)
  *
  * The selection is the plain definition: a full sort of all entries by
  * (|acc| descending, index ascending) and a cut after k entries.  No histogram,
@@ -218,6 +219,32 @@ int oracle_decompress_accumulate(const int32_t* idx, const float* val,
             if (i < 0 || i >= n) return ORACLE_BAD_ARG;
             volatile float s = dense_out[i] + val[at + r];
             dense_out[i] = s;
+        }
+        at += counts[w];
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * Parameter update from the W workers' messages without a dense gradient in between (Alg. 1, the update
+ * w_{i+1} = w_i - eta * g~ with g~ the aggregate of the compressed gradients; Eq. (1) for the 1/N of the mean):
+ * with alpha = -eta / W every pair is one step  w[idx] = w[idx] + alpha * val,  the product rounded to binary32,
+ * then the sum rounded to binary32, workers in order, pairs in stored order.  In exact arithmetic this is
+ * w - eta * (1/W) * sum of the decompressed messages; alpha = 1 is oracle_decompress_accumulate.
+ */
+int oracle_decompress_update(const int32_t* idx, const float* val,
+                             const int64_t* counts, int W, int64_t n, float alpha, float* w_inout)
+{
+    if (!counts || !w_inout || W < 1 || n <= 0) return ORACLE_BAD_ARG;
+    int64_t at = 0;
+    for (int w = 0; w < W; ++w) {
+        if (counts[w] < 0) return ORACLE_BAD_ARG;
+        for (int64_t r = 0; r < counts[w]; ++r) {
+            int64_t i = idx[at + r];
+            if (i < 0 || i >= n) return ORACLE_BAD_ARG;
+            volatile float step = alpha * val[at + r];
+            volatile float s = w_inout[i] + step;
+            w_inout[i] = s;
         }
         at += counts[w];
     }

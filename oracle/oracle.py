@@ -47,6 +47,8 @@ def _load():
         lib.oracle_compress.argtypes = [p, p, i64, p, i32, i32, p, i32, p, p, i64, p, p]
         lib.oracle_decompress_accumulate.restype = i32
         lib.oracle_decompress_accumulate.argtypes = [p, p, p, i32, i64, p]
+        lib.oracle_decompress_update.restype = i32
+        lib.oracle_decompress_update.argtypes = [p, p, p, i32, i64, ctypes.c_float, p]
         lib.oracle_commit.restype = i32
         lib.oracle_commit.argtypes = [p, i64, p, i64]
         lib.oracle_splitmix64_first.restype = ctypes.c_uint64
@@ -118,6 +120,18 @@ def decompress_accumulate(idx: np.ndarray, val: np.ndarray, counts, dense_out: n
                                           _ptr(cnt), cnt.size, dense_out.size, _ptr(dense_out))
     if rc != 0:
         raise RuntimeError(f"oracle_decompress_accumulate failed with code {rc}")
+
+
+def decompress_update(idx: np.ndarray, val: np.ndarray, counts, alpha: float, w: np.ndarray) -> None:
+    """w[idx] += alpha * val pair by pair (product, then sum, each rounded to binary32), workers in order, in
+    place: with alpha = -eta / W the update step of Alg. 1 applied straight from the W messages."""
+    lib = _load()
+    assert idx.dtype == np.int32 and val.dtype == np.float32 and w.dtype == np.float32
+    cnt = np.ascontiguousarray(np.asarray(counts, dtype=np.int64))
+    rc = lib.oracle_decompress_update(_ptr(np.ascontiguousarray(idx)), _ptr(np.ascontiguousarray(val)),
+                                      _ptr(cnt), cnt.size, w.size, ctypes.c_float(alpha), _ptr(w))
+    if rc != 0:
+        raise RuntimeError(f"oracle_decompress_update failed with code {rc}")
 
 
 def commit(idx: np.ndarray, residual: np.ndarray) -> None:

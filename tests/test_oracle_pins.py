@@ -459,6 +459,74 @@ def test_decompress_inverts_compress():
     assert np.array_equal(dense + res, g)             # message + residual = acc
 
 
+def test_decompress_update_hand_values():
+    """Alg. 1's update w - eta * aggregate, taken pair by pair: values worked out by hand."""
+    # exact binary fractions: w = [1, 2, 3, 4], two workers, alpha = -1/4 (eta = 0.5, W = 2)
+    w = np.array([1.0, 2.0, 3.0, 4.0], np.float32)
+    oracle.decompress_update(np.array([0, 2, 2, 3], np.int32), np.array([4.0, 8.0, -2.0, 1.0], np.float32), [2, 2], -0.25, w)
+    assert w.tolist() == [0.0, 2.0, 1.5, 3.75]
+    # the product is rounded before the sum: (1 + 2^-12)^2 = 1 + 2^-11 + 2^-24 rounds to 1 + 2^-11 (a tie, to the even
+    # mantissa), and w = -(1 + 2^-11) then gives exactly 0; a fused multiply-add would leave 2^-24
+    a = np.float32(1.0 + 2.0 ** -12)
+    w = np.array([-(1.0 + 2.0 ** -11)], np.float32)
+    oracle.decompress_update(np.array([0], np.int32), np.array([a], np.float32), [1], float(a), w)
+    assert w[0] == 0.0
+    # workers in order: (2^24 + 1) + 1 = 2^24 + 2 needs two adds of 1 to be taken one by one ... and both are lost
+    # (2^24 + 1 is not a binary32 number, ties to even), while one add of 2 is not
+    w = np.array([2.0 ** 24, 2.0 ** 24], np.float32)
+    oracle.decompress_update(np.array([0, 1, 0], np.int32), np.array([1.0, 2.0, 1.0], np.float32), [2, 1], 1.0, w)
+    assert w.tolist() == [2.0 ** 24, 2.0 ** 24 + 2.0]
+    # order matters: big, then -big, then small keeps the small one; small first loses it
+    w = np.zeros(2, np.float32)
+    oracle.decompress_update(np.array([0, 1, 0, 1, 0, 1], np.int32),
+                             np.array([1e8, 1.0, -1e8, 1e8, 1.0, -1e8], np.float32), [2, 2, 2], 1.0, w)
+    assert w.tolist() == [1.0, 0.0]
+
+
+def test_decompress_update_against_library_arithmetic():
+    rng = np.random.default_rng(19)
+    n, W = 3000, 6
+    w0 = rng.standard_normal(n).astype(np.float32)
+    idxs, vals, counts = [], [], []
+    for _ in range(W):
+        k = int(rng.integers(0, 900))
+        idxs.append(np.sort(rng.choice(n, size=k, replace=False)).astype(np.int32))
+        vals.append((rng.standard_normal(k) * 1e-2).astype(np.float32))
+        counts.append(k)
+    idx, val = np.concatenate(idxs), np.concatenate(vals)
+    alpha = np.float32(-0.1 / W)
+    # numpy's float32 arithmetic, one worker at a time (indices within a worker are distinct, so fancy indexing is safe)
+    want = w0.copy()
+    for i, v in zip(idxs, vals):
+        want[i] = want[i] + alpha * v
+    got = w0.copy()
+    oracle.decompress_update(idx, val, counts, float(alpha), got)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    # against the definition in exact arithmetic: w - eta * mean of the decompressed messages, within W + 1 roundings
+    dense = np.zeros(n, np.float64)
+    for i, v in zip(idxs, vals):
+        dense[i] += v.astype(np.float64)
+    exact = w0.astype(np.float64) - 0.1 * dense / W
+    tol = (2 * W + 2) * 2.0 ** -24 * (np.abs(w0.astype(np.float64)) + 0.1 * np.abs(dense) + 1e-3)
+    assert np.all(np.abs(got.astype(np.float64) - exact) <= tol)
+    # alpha = 1 is the plain accumulation
+    a, b = w0.copy(), w0.copy()
+    oracle.decompress_update(idx, val, counts, 1.0, a)
+    oracle.decompress_accumulate(idx, val, counts, b)
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    # entries no pair names stay as they are, bit for bit
+    untouched = np.setdiff1d(np.arange(n), idx)
+    assert np.array_equal(got[untouched].view(np.uint32), w0[untouched].view(np.uint32))
+
+
+def test_decompress_update_rejects_bad_arguments():
+    w = np.zeros(4, np.float32)
+    with pytest.raises(RuntimeError):
+        oracle.decompress_update(np.array([4], np.int32), np.array([1.0], np.float32), [1], 1.0, w)
+    with pytest.raises(RuntimeError):
+        oracle.decompress_update(np.array([0], np.int32), np.array([1.0], np.float32), [-1], 1.0, w)
+
+
 # --------------------------------------------------------------------------
 # workload shapes
 # --------------------------------------------------------------------------

@@ -185,8 +185,10 @@ def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None, only=
     del g
     dense = torch.zeros(n, dtype=torch.float32, device="cuda")
     dws = torch.empty(binding.gravac_decompress_workspace_bytes(N_WORKERS, n), dtype=torch.uint8, device="cuda")
-    for ws in ((None, dws) if full_table else (dws,)):
-        rec = {"config": "5: decompress_accumulate, W = 8", "n": n, "pairs": N_WORKERS * k, "workspace": ws is not None}
+
+    def time_decompress(label, mi, mv, k, ws, alpha=None):
+        """alpha None: gravac_decompress_accumulate into a zeroed buffer; else gravac_decompress_update of `dense`"""
+        rec = {"config": label, "n": n, "pairs": N_WORKERS * k, "workspace": ws is not None}
         for mode in modes:
             ts = []
             for rep in range(10):
@@ -195,7 +197,10 @@ def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None, only=
                     ct.flush.fill_(1.0)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
-                binding.gravac_decompress_accumulate(mi, mv, [k] * N_WORKERS, dense, workspace=ws)
+                if alpha is None:
+                    binding.gravac_decompress_accumulate(mi, mv, [k] * N_WORKERS, dense, workspace=ws)
+                else:
+                    binding.gravac_decompress_update(mi, mv, [k] * N_WORKERS, alpha, dense, workspace=ws)
                 e1.record()
                 torch.cuda.synchronize()
                 if rep >= 2:
@@ -205,6 +210,25 @@ def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None, only=
             rec[mode + "_algorithmic_GBps"] = round((8.0 * n + 8.0 * N_WORKERS * k) / t / 1e6, 1)
         log(json.dumps(rec))
         rows.append(rec)
+
+    for ws in ((None, dws) if full_table else (dws,)):
+        time_decompress("5: decompress_accumulate, W = 8", mi, mv, k, ws)
+    if full_table and only is None:
+        # the update step of Alg. 1 straight from the same messages (eta = 0.1)
+        time_decompress("5: decompress_update, W = 8", mi, mv, k, dws, alpha=-0.1 / N_WORKERS)
+        # messages of CF 1000 (flat calls on the eight workers' gradients): few pairs per stretch of dense_out
+        comp = binding.Compressor(n, [1000.0], 0)
+        k = comp.k_total
+        mi = torch.empty(N_WORKERS * k, dtype=torch.int32, device="cuda")
+        mv = torch.empty(N_WORKERS * k, dtype=torch.float32, device="cuda")
+        for w in range(N_WORKERS):
+            gw = torch.from_numpy(workloads.config5_worker_grad(w)).cuda()
+            r = torch.zeros(n, dtype=torch.float32, device="cuda")
+            i, v, _ = comp(gw, r)
+            mi[w * k:(w + 1) * k] = i
+            mv[w * k:(w + 1) * k] = v
+        time_decompress("2: decompress_accumulate, W = 8, flat CF 1000 messages", mi, mv, k, dws)
+        time_decompress("2: decompress_update, W = 8, flat CF 1000 messages", mi, mv, k, dws, alpha=-0.1 / N_WORKERS)
     if not full_table or only is not None:
         return rows
     # direct compression at each CF against the second-level Top-k on a level-1 message (the comparison of the

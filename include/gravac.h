@@ -254,6 +254,27 @@ int gravac_decompress_accumulate(const int32_t* idx, const float* val,
                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The update step of Alg. 1 (w_{i+1} = w_i - eta * g~, g~ the aggregate of the workers' compressed gradients;
+ * Eq. (1) for the 1/N of the mean) applied straight from the W messages, without a dense gradient in between:
+ * for workers w = 0 .. W-1 in that order and every pair of the message
+ *     params[idx] = params[idx] + alpha * val
+ * with the product rounded to binary32 first and the sum rounded to binary32 after it (no fused multiply-add).
+ * With alpha = -eta / W this is the plain SGD step on the mean of the decompressed messages; what momentum,
+ * weight decay or another optimizer needs is gravac_decompress_accumulate into a zeroed buffer instead.
+ * alpha = 1 gives gravac_decompress_accumulate bit for bit.  Only entries that a pair names are written, and
+ * with a workspace a stretch of 8192 entries that few pairs name is not read whole either.
+ *
+ *   alpha       any finite or non-finite binary32 value; it is applied as given.
+ *   params      device, float[n]; updated in place.
+ * All other arguments, the order of the adds and the error behaviour as for gravac_decompress_accumulate
+ * (same workspace size).
+ */
+int gravac_decompress_update(const int32_t* idx, const float* val,
+                             const int64_t* counts, int W,
+                             int64_t n, float alpha, float* params,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * gravac_decompress_accumulate for callers that cannot allocate device memory or carry a workspace around: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result
  * (bit for bit) and same kernels as gravac_decompress_accumulate with a workspace, but the tile boundaries of the

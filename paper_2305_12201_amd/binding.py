@@ -30,6 +30,7 @@ FLAG_NO_COMMIT = 2
 EXPORTS = (
     "gravac_topk_count", "gravac_workspace_bytes", "gravac_compress", "gravac_compress_profiled", "gravac_randomk_compress", "gravac_threshold_compress", "gravac_recompress", "gravac_commit",
     "gravac_decompress_workspace_bytes", "gravac_decompress_accumulate", "gravac_decompress_accumulate_static",
+    "gravac_decompress_update",
     "gravac_read_status", "gravac_strerror",
     "gravac_controller_create", "gravac_controller_destroy", "gravac_controller_candidates",
     "gravac_controller_decide", "gravac_controller_finish_iteration", "gravac_controller_throughput",
@@ -101,6 +102,8 @@ def lib() -> ctypes.CDLL:
         L.gravac_commit.argtypes = [vp, i64, vp, i64, vp]
         L.gravac_decompress_accumulate.restype = i32
         L.gravac_decompress_accumulate.argtypes = [vp, vp, vp, i32, i64, vp, vp, ctypes.c_size_t, vp]
+        L.gravac_decompress_update.restype = i32
+        L.gravac_decompress_update.argtypes = [vp, vp, vp, i32, i64, ctypes.c_float, vp, vp, ctypes.c_size_t, vp]
         L.gravac_decompress_accumulate_static.restype = i32
         L.gravac_decompress_accumulate_static.argtypes = [vp, vp, vp, i32, i64, vp, vp]
         L.gravac_decompress_workspace_bytes.restype = i32
@@ -275,6 +278,19 @@ def gravac_decompress_accumulate(idx, val, counts, dense_out, *, workspace=None,
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc != OK:
         raise GravacError(rc, "gravac_decompress_accumulate")
+
+
+def gravac_decompress_update(idx, val, counts, alpha, params, *, workspace=None, stream=None) -> None:
+    """``gravac_decompress_update`` of the C ABI on torch device tensors: ``params[idx] += alpha * val`` pair by
+    pair, workers in order (``workspace`` as for ``gravac_decompress_accumulate``)."""
+    cnt = np.ascontiguousarray(np.asarray(counts, dtype=np.int64))
+    rc = lib().gravac_decompress_update(
+        _dev_ptr(idx, torch.int32), _dev_ptr(val, torch.float32), cnt.ctypes.data_as(ctypes.c_void_p),
+        cnt.size, params.numel(), ctypes.c_float(alpha), _dev_ptr(params, torch.float32),
+        0 if workspace is None else workspace.data_ptr(),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if rc != OK:
+        raise GravacError(rc, "gravac_decompress_update")
 
 
 def gravac_decompress_accumulate_static(idx, val, counts, dense_out, *, stream=None) -> None:

@@ -3890,6 +3890,18 @@ int gravac_decompress_accumulate(const int32_t* idx, const float* val, const int
     return decompress_impl(idx, val, counts, W, n, dense_out, 1.0f, (uint32_t*)workspace, stream_v);
 }
 
+int gravac_decompress_update(const int32_t* idx, const float* val, const int64_t* counts, int W, int64_t n, float alpha,
+                             float* params, void* workspace, size_t workspace_bytes, void* stream_v)
+{
+    if (!counts || !params || W < 1 || n <= 0 || n > 2147483647LL) return GRAVAC_ERR_INVALID_ARG;
+    if (workspace) {
+        size_t need = 0;
+        if (gravac_decompress_workspace_bytes(W, n, &need) != GRAVAC_OK) return GRAVAC_ERR_INVALID_ARG;
+        if (((uintptr_t)workspace & 255) || workspace_bytes < need) return GRAVAC_ERR_WORKSPACE;
+    }
+    return decompress_impl(idx, val, counts, W, n, params, alpha, (uint32_t*)workspace, stream_v);
+}
+
 int gravac_decompress_accumulate_static(const int32_t* idx, const float* val, const int64_t* counts, int W, int64_t n,
                                         float* dense_out, void* stream_v)
 {

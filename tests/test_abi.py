@@ -108,6 +108,14 @@ def test_decompress_rejects_bad_arguments():
     assert L.gravac_decompress_accumulate(0x1000, 0x2000, p, 2, 100, 0, None, 0, None) == binding.ERR_INVALID_ARG
     assert L.gravac_decompress_accumulate(0, 0x2000, p, 2, 100, 0x3000, None, 0, None) == binding.ERR_INVALID_ARG
     assert L.gravac_decompress_accumulate(0x1000, 0x2000, None, 2, 100, 0x3000, None, 0, None) == binding.ERR_INVALID_ARG
+    a = ctypes.c_float(-0.1)
+    assert L.gravac_decompress_update(0x1000, 0x2000, p, 2, 100, a, 0, None, 0, None) == binding.ERR_INVALID_ARG
+    assert L.gravac_decompress_update(0x1000, 0x2000, p, 0, 100, a, 0x3000, None, 0, None) == binding.ERR_INVALID_ARG
+    assert L.gravac_decompress_update(0x1000, 0x2000, p, 2, 0, a, 0x3000, None, 0, None) == binding.ERR_INVALID_ARG
+    assert L.gravac_decompress_update(0, 0x2000, p, 2, 100, a, 0x3000, None, 0, None) == binding.ERR_INVALID_ARG
+    assert L.gravac_decompress_update(0x1000, 0x2000, None, 2, 100, a, 0x3000, None, 0, None) == binding.ERR_INVALID_ARG
+    assert L.gravac_decompress_update(0x1000, 0x2000, p, 2, 100, a, 0x3000, 0x4001, 1 << 20, None) == binding.ERR_WORKSPACE
+    assert L.gravac_decompress_update(0x1000, 0x2000, p, 2, 100, a, 0x3000, 0x4000, 8, None) == binding.ERR_WORKSPACE
 
 
 def test_strerror():

@@ -127,6 +127,14 @@ def test_config3_vgg16_cf1000_five_iterations():
         torch.cuda.synchronize()
         assert np.array_equal(dense.cpu().numpy().view(np.uint32), want.view(np.uint32)), how
         del dense
+    # the update step of Alg. 1 straight from the same messages (eta = 0.05, W = 8) on parameters of the same size
+    params = np.random.default_rng(5).standard_normal(n).astype(np.float32)
+    alpha = -0.05 / 8
+    dp = torch.from_numpy(params).cuda()
+    binding.gravac_decompress_update(di, dv, [k] * 8, alpha, dp, workspace=ws)
+    torch.cuda.synchronize()
+    oracle.decompress_update(all_i, all_v, [k] * 8, alpha, params)
+    assert np.array_equal(dp.cpu().numpy().view(np.uint32), params.view(np.uint32))
 
 
 def test_vgg16_shape_dense_selection_with_the_larger_sample():

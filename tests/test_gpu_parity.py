@@ -291,7 +291,7 @@ def test_repeat_runs_are_bit_identical_and_grad_is_untouched():
 # decompression
 # --------------------------------------------------------------------------
 
-def _decompress_case(n, ks, seed, offset_elems=0, common=0):
+def _decompress_case(n, ks, seed, offset_elems=0, common=0, alpha=None):
     from oracle import oracle
     rng = np.random.default_rng(seed)
     idxs, vals = [], []
@@ -306,7 +306,10 @@ def _decompress_case(n, ks, seed, offset_elems=0, common=0):
     val = np.concatenate(vals) if ks else np.zeros(0, np.float32)
     dense = rng.standard_normal(n).astype(np.float32)
     want = dense.copy()
-    oracle.decompress_accumulate(idx, val, ks, want)
+    if alpha is None:
+        oracle.decompress_accumulate(idx, val, ks, want)
+    else:
+        oracle.decompress_update(idx, val, ks, alpha, want)
     # without a workspace (tile boundaries by search) and with one (boundaries computed once)
     for ws in (None, torch.empty(binding.gravac_decompress_workspace_bytes(len(ks), n), dtype=torch.uint8, device="cuda")):
         if ws is not None:
@@ -314,8 +317,11 @@ def _decompress_case(n, ks, seed, offset_elems=0, common=0):
         buf = torch.zeros(n + offset_elems, dtype=torch.float32, device="cuda")
         d = buf[offset_elems:]
         d.copy_(torch.from_numpy(dense))
-        binding.gravac_decompress_accumulate(torch.from_numpy(idx).cuda(), torch.from_numpy(val).cuda(), ks, d,
-                                             workspace=ws)
+        di, dv = torch.from_numpy(idx).cuda(), torch.from_numpy(val).cuda()
+        if alpha is None:
+            binding.gravac_decompress_accumulate(di, dv, ks, d, workspace=ws)
+        else:
+            binding.gravac_decompress_update(di, dv, ks, alpha, d, workspace=ws)
         torch.cuda.synchronize()
         got = d.cpu().numpy()
         assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), "workspace" if ws is not None else "search"
@@ -343,6 +349,18 @@ def test_decompress_tiles_with_few_pairs():
     _decompress_case(81_920, [640] * 8, seed=15, common=300)           # about 512 pairs per tile: both routes in one call
     _decompress_case(81_920 + 77, [64, 0, 1, 640, 0, 3, 512, 9], seed=16, common=0)
     _decompress_case(5, [5, 5, 5], seed=17, common=5)
+
+
+def test_decompress_update_is_the_sgd_step_from_the_messages():
+    # Alg. 1's update w - eta * aggregate applied pair by pair (alpha = -eta / W): dense and sparse tiles, entries named
+    # by several workers, ragged sizes, an unaligned buffer, more than 64 workers, and multipliers whose products round
+    for alpha in (-0.1 / 8, 1.0 + 2.0 ** -12, -3.0):
+        _decompress_case(100_003, [5000] * 8, seed=21, common=2000, alpha=alpha)
+        _decompress_case(1_000_003, [300] * 8, seed=22, common=120, alpha=alpha)
+    _decompress_case(81_920 + 77, [64, 0, 1, 640, 0, 3, 512, 9], seed=23, alpha=-0.0125, offset_elems=1)
+    _decompress_case(300_000, [30] * 70, seed=24, common=10, alpha=0.5)
+    _decompress_case(8192, [8192, 8192], seed=25, common=8192, alpha=-1e-3)
+    _decompress_case(1000, [100, 0, 250, 1000, 7], seed=26, alpha=0.0)       # x + (+-0) = x
 
 
 def test_decompress_gaps_clusters_and_out_of_range_indices():

@@ -86,22 +86,30 @@ def test_random_case(case):
     np.testing.assert_allclose(stats.cpu().numpy()[..., :3], rs[..., :3], rtol=STAT_RTOL, atol=0, equal_nan=True, err_msg=what)
 
 
-@pytest.mark.parametrize("case", range(N_CASES or 30))
+@pytest.mark.parametrize("case", range(N_CASES or 40))
 def test_random_decompress(case):
-    """W index-sorted messages of random lengths (some empty, some dense, some in one cluster) into a dense buffer
-    that already holds values, with and without the workspace."""
+    """W index-sorted messages of random lengths (some empty, some dense, some thin, some in one cluster) into a
+    dense buffer that already holds values, with and without the workspace; every third case as the parameter
+    update with a multiplier.  In half of the cases every message is thin, so that whole stretches of the buffer
+    are named by a few pairs only."""
     rng = np.random.Generator(np.random.PCG64(5000 + case))
-    n = int(rng.choice([rng.integers(1, 9000), rng.integers(9000, 600_000)]))
+    n = int(rng.choice([rng.integers(1, 9000), rng.integers(9000, 600_000), rng.integers(600_000, 3_000_000)]))
     W = int(rng.choice([1, 2, 8, 8, 17, 64, 70]))
+    thin_only = rng.random() < 0.5
+    alpha = None if case % 3 else float(rng.choice([-0.0125, 0.3, -2.5, 1.0]))
     idx, val, ks = [], [], []
     for w in range(W):
-        mode = rng.integers(0, 4)
+        mode = int(rng.choice([0, 3, 4, 4])) if thin_only else int(rng.integers(0, 5))
         if mode == 0:
             k = 0
         elif mode == 1:
-            k = int(rng.integers(1, n + 1))
+            k = int(rng.integers(1, n + 1)) if n < 600_000 else int(rng.integers(1, n // 8))
+        elif mode == 4:
+            k = int(rng.integers(1, max(2, n // (250 * W) + 1)))      # about 30 pairs of all workers per 8192 entries
         else:
             k = int(rng.integers(1, max(2, n // 50 + 1)))
+        if thin_only and mode == 3:
+            k = min(k, 200)
         if mode == 3 and n > 10:                       # all pairs inside one short range
             lo = int(rng.integers(0, n - min(n, 4 * k) + 1))
             pos = lo + np.sort(rng.choice(min(n - lo, 4 * k), min(k, min(n - lo, 4 * k)), replace=False))
@@ -110,20 +118,32 @@ def test_random_decompress(case):
         idx.append(pos.astype(np.int32))
         val.append((rng.standard_normal(pos.size) * 1e-2).astype(np.float32))
         ks.append(int(pos.size))
+    if W > 1 and ks[0] and ks[1]:                      # some entries named by the first two workers alike
+        m = min(ks[0], ks[1], 50)
+        take = np.sort(rng.choice(ks[0], m, replace=False))
+        idx[1] = np.union1d(idx[1], idx[0][take]).astype(np.int32)
+        val[1] = (rng.standard_normal(idx[1].size) * 1e-2).astype(np.float32)
+        ks[1] = int(idx[1].size)
     idx = np.concatenate(idx) if sum(ks) else np.zeros(0, np.int32)
     val = np.concatenate(val) if sum(ks) else np.zeros(0, np.float32)
     base = (rng.standard_normal(n) * 1e-3).astype(np.float32)
     want = base.copy()
-    oracle.decompress_accumulate(idx, val, ks, want)
+    if alpha is None:
+        oracle.decompress_accumulate(idx, val, ks, want)
+    else:
+        oracle.decompress_update(idx, val, ks, alpha, want)
     ti = torch.from_numpy(idx).cuda() if idx.size else torch.zeros(1, dtype=torch.int32, device="cuda")
     tv = torch.from_numpy(val).cuda() if val.size else torch.zeros(1, dtype=torch.float32, device="cuda")
     for ws in (None, torch.empty(binding.gravac_decompress_workspace_bytes(W, n), dtype=torch.uint8, device="cuda")):
         d = torch.from_numpy(base.copy()).cuda()
-        binding.gravac_decompress_accumulate(ti, tv, ks, d, workspace=ws)
+        if alpha is None:
+            binding.gravac_decompress_accumulate(ti, tv, ks, d, workspace=ws)
+        else:
+            binding.gravac_decompress_update(ti, tv, ks, alpha, d, workspace=ws)
         torch.cuda.synchronize()
         got = d.cpu().numpy()
         assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), \
-            f"case {case}: n={n} W={W} workspace={ws is not None}: differs at {np.nonzero(got != want)[0][:5]}"
+            f"case {case}: n={n} W={W} alpha={alpha} workspace={ws is not None}: differs at {np.nonzero(got != want)[0][:5]}"
 
 
 @pytest.mark.parametrize("case", range(N_CASES or 30))

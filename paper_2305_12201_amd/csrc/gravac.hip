@@ -470,22 +470,6 @@ __device__ __forceinline__ void ref_entry(const Params& p, uint32_t u, const Til
     }
 }
 
-// The same for slot sl of sub-tile j of tile u, from its candidate list (from_main) or its bracket list.
-__device__ __forceinline__ void sub_entry(const Params& p, uint32_t u, int j, bool from_main, uint32_t sl, uint32_t& key, float& val)
-{
-    const size_t at = (size_t)u * TW + (size_t)j * TS + sl;
-    if (!p.random) {
-        const uint32_t* src = from_main ? (const uint32_t*)p.cand_val : p.brk_key;
-        key = src[at] & 0x7FFFFFFFu;
-        val = 0.0f;
-    } else if (from_main) {
-        key = priority_of(p.rk_s0, p.rk_s1, (uint32_t)p.cand_idx[at]);
-        val = p.cand_val[at];
-    } else {
-        key = p.brk_key[at];
-        val = p.brk_val[at];
-    }
-}
 
 // One wavefront finds the bin of a 2048-bin histogram (given as `copies` arrays of NBIN counts that
 // are added up) that holds the k-th largest entry: scanning from the top bin down,
@@ -1932,42 +1916,49 @@ __global__ __launch_bounds__(LWG) __attribute__((amdgpu_waves_per_eu((NCF == 3 |
                 i0 = cnt;
             }
         }
-        if (i0 < cnt && cnt >= LONG_WALK) {
-            // long lists (a low CF): sub-tile by sub-tile, so that no lane has to search for its entry's slot; two
-            // rounds per sub-tile are loaded while the sub-tile before it is worked on, whatever it holds
+        if (i0 < cnt && cnt >= LONG_WALK && !p.random) {
+            // long lists (a low CF, Top-k keys): sub-tile by sub-tile, so that no lane has to search for its entry's
+            // slot.  A step's work is a fraction of a round trip to memory, and every wavefront of the launch is in
+            // the same place, so the first two rounds of the next AHEAD sub-tiles are on their way while one is
+            // worked on, whatever they hold; the words are carried as loaded and decoded where they are used
+            // (decoded at once, the loads would be waited for at once).  The counts are the ones fetched with the
+            // tile's first loads.
+            constexpr int AHEAD = 4;
             const auto counts = [&](int j, uint32_t& c, bool& from_main) {
-                const uint32_t cc = p.cand_cnt[(size_t)u * SUB + j], bc = p.brk_cnt[(size_t)u * SUB + j];
-                from_main = !p.split && !(cc & DENSE_BIT);
-                c = from_main ? cc : bc;
+                c = 0;
+#pragma unroll
+                for (int x = 0; x < SUB; ++x) c = (x == j) ? tr.tl.start[x + 1] - tr.tl.start[x] : c;
+                from_main = (tr.main_mask >> j) & 1u;
             };
-            uint32_t c, kn[2];
-            bool fm;
-            float vn[2];
-            counts(0, c, fm);
+            const auto fetch = [&](int j, uint32_t (&w)[2]) {
+                const uint32_t* src = (((tr.main_mask >> j) & 1u) ? (const uint32_t*)p.cand_val : p.brk_key) + (size_t)u * TW + (size_t)j * TS;
 #pragma unroll
-            for (int q = 0; q < 2; ++q) sub_entry(p, u, 0, fm, q * 64 + lane, kn[q], vn[q]);
+                for (int q = 0; q < 2; ++q) w[q] = src[q * 64 + lane];
+            };
+            uint32_t wq[AHEAD][2];
+#pragma unroll
+            for (int a = 0; a < AHEAD; ++a) fetch(a, wq[a]);
             for (int j = 0; j < SUB; ++j) {
-                uint32_t kq[2], cnx = 0;
-                float vq[2];
-                bool fnx = false;
+                uint32_t w0[2], c;
+                bool fm;
 #pragma unroll
-                for (int q = 0; q < 2; ++q) { kq[q] = kn[q]; vq[q] = vn[q]; }
-                if (j + 1 < SUB) {
-                    counts(j + 1, cnx, fnx);
+                for (int q = 0; q < 2; ++q) w0[q] = wq[0][q];
 #pragma unroll
-                    for (int q = 0; q < 2; ++q) sub_entry(p, u, j + 1, fnx, q * 64 + lane, kn[q], vn[q]);
-                }
+                for (int a = 0; a + 1 < AHEAD; ++a) { wq[a][0] = wq[a + 1][0]; wq[a][1] = wq[a + 1][1]; }
+                if (j + AHEAD < SUB) fetch(j + AHEAD, wq[AHEAD - 1]);
+                counts(j, c, fm);
 #pragma unroll
                 for (int q = 0; q < 2; ++q)
-                    if ((uint32_t)q * 64 < c) take(kq[q], vq[q], q * 64 + lane < c);
+                    if ((uint32_t)q * 64 < c) take(w0[q] & 0x7FFFFFFFu, 0.0f, q * 64 + lane < c);
                 for (uint32_t b0 = 128; b0 < c; b0 += 128) {   // (a sub-tile with more than 128 such entries: rare)
+                    const uint32_t* src = (fm ? (const uint32_t*)p.cand_val : p.brk_key) + (size_t)u * TW + (size_t)j * TS;
+                    uint32_t kq[2];
 #pragma unroll
-                    for (int q = 0; q < 2; ++q) sub_entry(p, u, j, fm, (b0 + q * 64 + lane) & (TS - 1), kq[q], vq[q]);
+                    for (int q = 0; q < 2; ++q) kq[q] = src[(b0 + q * 64 + lane) & (TS - 1)] & 0x7FFFFFFFu;
 #pragma unroll
                     for (int q = 0; q < 2; ++q)
-                        if (b0 + q * 64 < c) take(kq[q], vq[q], b0 + q * 64 + lane < c);
+                        if (b0 + q * 64 < c) take(kq[q], 0.0f, b0 + q * 64 + lane < c);
                 }
-                c = cnx; fm = fnx;
             }
             i0 = cnt;
         }

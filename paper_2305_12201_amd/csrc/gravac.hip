@@ -2321,6 +2321,26 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
             const double dv = p.random ? (double)rv[q] : (double)__uint_as_float(base + d[q]);
             return in ? dv * dv : 0.0;
         };
+        const uint32_t kmax = base + span;   // the located bin's largest key
+        if (!p.random && kmax < 0x7F800000u) {
+            // Top-k keys are magnitudes, and the bin's own bounds say how large a square can get: no look at the
+            // entries for the scale, and nothing can be infinite or NaN
+            if (kmax != 0u) {
+                const double m = (double)__uint_as_float(kmax);
+                const int ex = ilogb(m * m);                  // every square is below 2^(ex + 1)
+                const double sc = scalbn(1.0, 49 - ex);       // (a power of two: the product is exact)
+                uint64_t acc = 0;
+#pragma unroll
+                for (int q = 0; q < RW; ++q) acc += (uint64_t)(square(q) * sc);   // < 2^50 each
+                acc = wave_sum(acc);
+                if (lane == 0) ured[wib] = acc;
+                __syncthreads();
+                uint64_t all = 0;
+#pragma unroll
+                for (int w = 0; w < SCAN_W; ++w) all += ured[w];
+                ebin = scalbn((double)all, ex - 49);
+            }
+        } else {
         double mx = 0.0, plain = 0.0;
         bool finite = true;
 #pragma unroll
@@ -2355,6 +2375,7 @@ __global__ __launch_bounds__(SCAN_T) void scan_kernel(Params p, uint32_t slices)
 #pragma unroll
             for (int w = 0; w < SCAN_W; ++w) all += ured[w];
             ebin = scalbn((double)all, ex - 49);
+        }
         }
     } else if (mode == MODE_HIST) {
         // Top-k only (priorities are distinct): the key-by-key histogram's bins above the threshold, in bin order

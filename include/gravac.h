@@ -24,7 +24,8 @@
  *   - The library keeps no state between calls, with one exception: layerwise calls pass their segment tables
  *     through a ring of up to eight pinned host staging buffers that the library allocates on first use
  *     (hipHostMalloc, grown when a larger table arrives, kept until the process ends) and that are shared by all
- *     callers of the process.  A caller that issues layerwise calls faster than the GPU runs them is held, once two
+ *     callers of the process; the call's first kernel reads the buffer and copies the tables into the workspace.
+ *     A caller that issues layerwise calls faster than the GPU runs them is held, once two
  *     buffers exist, until the table copy of an earlier layerwise call (on whatever stream it was queued) has run:
  *     the host then stays at most a call or two ahead.  More buffers are only allocated while others are in the
  *     hands of concurrent callers.  Flat-mode calls touch no such state.

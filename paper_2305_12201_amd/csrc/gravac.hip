@@ -3221,6 +3221,17 @@ __global__ __launch_bounds__(256) void decompress_ws_kernel(const int32_t* __res
 }
 
 // ---------------------------------------------------------------------------------------------
+// A layerwise call's tables, from the pinned host buffer they were built in into the workspace.  A kernel that
+// reads the host buffer is queued like every other kernel of the call; a copy by the DMA engine starts 10 to 20 us
+// later and the call's first kernel waits for it.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void table_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, uint32_t n16)
+{
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
+}
+
+// ---------------------------------------------------------------------------------------------
 // Commit of a message: residual[idx[i]] = +0.0f.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void commit_kernel(const int32_t* __restrict__ idx, int64_t count,
@@ -3353,6 +3364,7 @@ uint32_t sample_count(uint64_t nt, double cf_min, double cf_max, bool flat)
 // This ring is the only state the library keeps between calls.
 struct StagingSlot {
     char* mem = nullptr;
+    char* dev = nullptr;   // the same memory as a kernel addresses it (null: only copies can read it)
     size_t cap = 0;
     hipEvent_t done = nullptr;
     bool pending = false;  // `done` was recorded and not yet waited for
@@ -3399,10 +3411,14 @@ StagingSlot* staging_acquire(size_t bytes)
     }
     if (ok && s->cap < bytes) {
         if (s->mem) (void)hipHostFree(s->mem);
-        s->mem = nullptr; s->cap = 0;
+        s->mem = nullptr; s->dev = nullptr; s->cap = 0;
         const size_t want = bytes < 65536 ? 65536 : bytes + bytes / 2;
+        s->dev = nullptr;
         if (hipHostMalloc((void**)&s->mem, want, hipHostMallocDefault) != hipSuccess) { s->mem = nullptr; ok = false; }
-        else s->cap = want;
+        else {
+            s->cap = want;
+            if (hipHostGetDevicePointer((void**)&s->dev, s->mem, 0) != hipSuccess) { s->dev = nullptr; (void)hipGetLastError(); }
+        }
     }
     if (!ok) {
         std::lock_guard<std::mutex> lock(g_staging_mutex);
@@ -3640,6 +3656,7 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     if (ns > 1) {
         table_bytes = sizeof(SegInfo) * ns + sizeof(uint32_t) * (size_t)ns * n_cf + sizeof(uint32_t) * p.n_sample_blocks +
                       sizeof(uint32_t) * n_small;
+        table_bytes = (table_bytes + 15) & ~(size_t)15;   // (moved 16 bytes at a time; the workspace's part is that long)
         slot = staging_acquire(table_bytes);
         if (!slot) return GRAVAC_ERR_HIP;
         SegInfo* segs = (SegInfo*)slot->mem;
@@ -3677,7 +3694,15 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
         return GRAVAC_ERR_HIP;
     }
     if (slot) {
-        const bool copied = hipMemcpyAsync(ws + L.tables, slot->mem, table_bytes, hipMemcpyHostToDevice, stream) == hipSuccess;
+        bool copied;
+        if (slot->dev) {
+            const uint32_t n16 = (uint32_t)(table_bytes / 16);
+            hipLaunchKernelGGL(table_copy_kernel, dim3((n16 + 255) / 256), dim3(256), 0, stream, (const uint4*)slot->dev,
+                               (uint4*)(ws + L.tables), n16);
+            copied = hipGetLastError() == hipSuccess;
+        } else {
+            copied = hipMemcpyAsync(ws + L.tables, slot->mem, table_bytes, hipMemcpyHostToDevice, stream) == hipSuccess;
+        }
         bool recorded = copied && hipEventRecord(slot->done, stream) == hipSuccess;
         // a copy that is queued but not followed by the slot's event: wait for it here, so that the slot is not
         // rewritten under it

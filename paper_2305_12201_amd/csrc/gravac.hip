@@ -3364,7 +3364,6 @@ uint32_t sample_count(uint64_t nt, double cf_min, double cf_max, bool flat)
 // This ring is the only state the library keeps between calls.
 struct StagingSlot {
     char* mem = nullptr;
-    char* dev = nullptr;   // the same memory as a kernel addresses it (null: only copies can read it)
     size_t cap = 0;
     hipEvent_t done = nullptr;
     bool pending = false;  // `done` was recorded and not yet waited for
@@ -3411,14 +3410,10 @@ StagingSlot* staging_acquire(size_t bytes)
     }
     if (ok && s->cap < bytes) {
         if (s->mem) (void)hipHostFree(s->mem);
-        s->mem = nullptr; s->dev = nullptr; s->cap = 0;
+        s->mem = nullptr; s->cap = 0;
         const size_t want = bytes < 65536 ? 65536 : bytes + bytes / 2;
-        s->dev = nullptr;
         if (hipHostMalloc((void**)&s->mem, want, hipHostMallocDefault) != hipSuccess) { s->mem = nullptr; ok = false; }
-        else {
-            s->cap = want;
-            if (hipHostGetDevicePointer((void**)&s->dev, s->mem, 0) != hipSuccess) { s->dev = nullptr; (void)hipGetLastError(); }
-        }
+        else s->cap = want;
     }
     if (!ok) {
         std::lock_guard<std::mutex> lock(g_staging_mutex);
@@ -3695,9 +3690,12 @@ static int compress_impl(const float* grad, float* residual, int64_t n, const do
     }
     if (slot) {
         bool copied;
-        if (slot->dev) {
+        // the buffer as a kernel of the current device addresses it (none: only a copy can read it)
+        void* dev = nullptr;
+        if (hipHostGetDevicePointer(&dev, slot->mem, 0) != hipSuccess) { dev = nullptr; (void)hipGetLastError(); }
+        if (dev) {
             const uint32_t n16 = (uint32_t)(table_bytes / 16);
-            hipLaunchKernelGGL(table_copy_kernel, dim3((n16 + 255) / 256), dim3(256), 0, stream, (const uint4*)slot->dev,
+            hipLaunchKernelGGL(table_copy_kernel, dim3((n16 + 255) / 256), dim3(256), 0, stream, (const uint4*)dev,
                                (uint4*)(ws + L.tables), n16);
             copied = hipGetLastError() == hipSuccess;
         } else {

@@ -1,7 +1,8 @@
 """GPU end-to-end: the adaptive loop of Alg. 1 (compress at theta_min, second-level compression to the
-candidate CF, the controller's epsilon switch, the residual update of the branch taken) run through the C
-ABI, against the same loop built from the CPU oracle.  Every iteration's message and residual bit-exact,
-the same decisions and the same CF schedule."""
+candidate CF, the controller's epsilon switch, the residual update of the branch taken, the parameter update
+w - eta * g~ from the message that was sent) run through the C ABI, against the same loop built from the CPU
+oracle.  Every iteration's message, residual and parameters bit-exact, the same decisions and the same CF
+schedule."""
 import numpy as np
 import pytest
 import torch
@@ -41,6 +42,9 @@ def test_adaptive_loop_matches_the_oracle_loop(epsilon, policy, protocol):
                              alpha=alpha, samples_per_iteration=256.0)
     res_gpu = torch.zeros(n, dtype=torch.float32, device="cuda")
     res_cpu = np.zeros(n, np.float32)
+    eta = 0.05
+    w_cpu = np.random.default_rng(3).standard_normal(n).astype(np.float32)     # the parameters (one worker: g~ is its message)
+    w_gpu = torch.from_numpy(w_cpu.copy()).cuda()
     choices = []
     for it in range(iters):
         g = _gradient(n, it)
@@ -72,6 +76,11 @@ def test_adaptive_loop_matches_the_oracle_loop(epsilon, policy, protocol):
                 binding.gravac_decompress_accumulate(i2, v2, [k2], res_gpu)     # residual + message = acc
             dense_sent = res_gpu.clone()                                        # (no_commit: the residual holds acc)
             res_gpu.zero_()
+        # the update step from what was sent: the message's pairs, or the dense gradient (product, then sum)
+        if choice == binding.SEND_DENSE:
+            w_gpu += dense_sent * (-eta)
+        else:
+            binding.gravac_decompress_update(sent_i, sent_v, [sent_i.numel()], -eta, w_gpu)
         torch.cuda.synchronize()
         assert binding.gravac_read_status(comp.workspace)["internal_error"] == 0
         cf_used = {binding.SEND_CANDIDATE: tc, binding.SEND_MIN: tmin, binding.SEND_DENSE: 1.0}[choice]
@@ -86,8 +95,12 @@ def test_adaptive_loop_matches_the_oracle_loop(epsilon, policy, protocol):
         r = co.iteration(st, lambda cf: gains[cf], _t_iter)
         if r["choice"] == co.SEND_MIN:
             oracle.commit(oi1, res_cpu)
+            oracle.decompress_update(oi1, ov1, [oi1.size], -eta, w_cpu)
         elif r["choice"] == co.SEND_DENSE:
             res_cpu[:] = 0.0
+            w_cpu += acc * np.float32(-eta)
+        else:
+            oracle.decompress_update(oi2, ov2, [oi2.size], -eta, w_cpu)
 
         # ---- compare
         assert choice == r["choice"], (it, gain_min, gain_c, gains)
@@ -102,6 +115,7 @@ def test_adaptive_loop_matches_the_oracle_loop(epsilon, policy, protocol):
             d = dense_sent.cpu().numpy()
             assert np.array_equal(d, acc) and np.array_equal(d.view(np.uint32)[acc != 0], acc.view(np.uint32)[acc != 0])
         assert np.array_equal(res_gpu.cpu().numpy().view(np.uint32), res_cpu.view(np.uint32)), it
+        assert np.array_equal(w_gpu.cpu().numpy().view(np.uint32), w_cpu.view(np.uint32)), it
         choices.append(choice)
     assert len(set(choices)) >= 2, choices          # the run exercises more than one branch
     assert st.theta_s != 2.0 or st.theta_min != theta_min

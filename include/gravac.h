@@ -243,10 +243,10 @@ int gravac_commit(const int32_t* idx, int64_t count, float* residual, int64_t n,
  * scheduling.
  *   workspace   device, 256-byte aligned, at least gravac_decompress_workspace_bytes(W, n) bytes, or NULL.
  *               With a workspace the tile boundaries of every message are computed once (one thread per
- *               pair) instead of being searched for tile by tile, and a stretch of 8192 entries that few pairs
- *               name is updated entry by entry instead of being rewritten whole: up to twice as fast for
- *               dense messages, three times for messages spread thinly over dense_out; the result is the
- *               same.  Contents on entry are irrelevant.
+ *               pair) instead of being searched for tile by tile: up to twice as fast, for messages spread
+ *               thinly over dense_out as for dense ones (either way a stretch of 8192 entries that few pairs
+ *               name is updated entry by entry, not rewritten whole; without a workspace only for W <= 8); the
+ *               result is the same.  Contents on entry are irrelevant.
  */
 int gravac_decompress_workspace_bytes(int W, int64_t n, size_t* bytes_out);
 int gravac_decompress_accumulate(const int32_t* idx, const float* val,

@@ -2785,6 +2785,11 @@ constexpr int DTILE = 8192;  // floats of dense_out per tile (32 KiB of LDS)
 constexpr int DMAXW = 64;    // workers per launch
 constexpr int DGROUP = 8;    // workers searched at a time
 constexpr int DBATCH = 4;    // pairs per thread and batch
+#ifndef GRAVAC_DSPARSE
+#define GRAVAC_DSPARSE 512
+#endif
+constexpr uint32_t DSPARSE = GRAVAC_DSPARSE;   // a tile with at most this many pairs is updated entry by entry
+constexpr int DSLOTS = (DSPARSE + 255) / 256;  // pairs per thread of such a tile
 
 struct WorkerOffsets {
     int64_t at[DMAXW + 1];
@@ -2869,6 +2874,50 @@ __global__ __launch_bounds__(256) void decompress_kernel(const int32_t* __restri
             __syncthreads();
             const uint32_t total = pre[DGROUP];
             if (total == 0) continue;  // no message of this group touches the tile
+            if (W <= DGROUP && total <= DSPARSE) {
+                // few pairs, and this group is all there is: only the entries they name are read and written back (as in
+                // the kernel that works from tile boundaries; they still go through the tile buffer, worker by worker)
+                int pj[DSLOTS], pw[DSLOTS];
+                float pv[DSLOTS], dv[DSLOTS];
+                int64_t at[DSLOTS];
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q) {
+                    const uint32_t slot = q * 256 + tid;
+                    const uint32_t sc = slot < total ? slot : total - 1;
+                    int w = 0;
+#pragma unroll
+                    for (int x = 1; x < DGROUP; ++x) w += (sc >= pre[x]);
+                    at[q] = lo[w] + (int64_t)(sc - pre[w]);
+                    pw[q] = slot < total ? w : -1;
+                }
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q) pj[q] = idx[at[q]];
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q) pv[q] = val[at[q]];
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q) {
+                    const int64_t j = (int64_t)pj[q] - base;
+                    if (j < 0 || j >= len) pw[q] = -1;   // an index outside the tile (malformed message) is ignored
+                    pj[q] = (int)(j < 0 || j >= len ? 0 : j);
+                }
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q) dv[q] = pw[q] >= 0 ? dense[base + pj[q]] : 0.0f;
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q)
+                    if (pw[q] >= 0) acc[pj[q]] = dv[q];  // the same value from every pair of that entry
+                __syncthreads();
+                for (int w = 0; w < wn; ++w) {
+                    if (pre[w + 1] == pre[w]) continue;
+#pragma unroll
+                    for (int q = 0; q < DSLOTS; ++q)
+                        if (pw[q] == w) acc[pj[q]] = __fadd_rn(acc[pj[q]], __fmul_rn(alpha, pv[q]));
+                    __syncthreads();
+                }
+#pragma unroll
+                for (int q = 0; q < DSLOTS; ++q)
+                    if (pw[q] >= 0) dense[base + pj[q]] = acc[pj[q]];
+                continue;   // (nothing was loaded whole: nothing is written back; the next tile starts with a barrier)
+            }
             if (!loaded) {
                 if (vec && len == DTILE) {
                     // a whole tile: all eight loads of a thread in flight together
@@ -3003,11 +3052,6 @@ __global__ __launch_bounds__(256) void bounds_kernel(const int32_t* __restrict__
 
 constexpr int DCHUNK = 32;  // tiles whose boundaries a workgroup fetches in one round of loads
 constexpr int DENT = 768;   // (tile, worker) entries of such a chunk
-#ifndef GRAVAC_DSPARSE
-#define GRAVAC_DSPARSE 512
-#endif
-constexpr uint32_t DSPARSE = GRAVAC_DSPARSE;   // a tile with at most this many pairs is updated entry by entry
-constexpr int DSLOTS = (DSPARSE + 255) / 256;  // pairs per thread of such a tile
 
 // A workgroup takes the tiles blockIdx.x, blockIdx.x + gridDim.x, ...  It first fetches, for a chunk of its
 // tiles at once, every worker's boundaries (one round of independent loads instead of one dependent round per

@@ -167,7 +167,10 @@ def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None, only=
     seg = workloads.offsets_of(workloads.resnet101_tensor_sizes())
     add("5: ResNet101-shaped, 314 tensors, layerwise", lambda: torch.from_numpy(workloads.config5_worker_grad(0)).cuda(),
         [100.0], [0], seg=seg)
-    if not want("5: decompress_accumulate, W = 8"):
+    D5, U5 = "5: decompress_accumulate, W = 8", "5: decompress_update, W = 8"
+    D2, U2 = "2: decompress_accumulate, W = 8, flat CF 1000 messages", "2: decompress_update, W = 8, flat CF 1000 messages"
+    extra = full_table and (only is None or any(re.search(only, x) for x in (U5, D2, U2)))
+    if not (want(D5) or extra):
         return rows
     g = torch.from_numpy(workloads.config5_worker_grad(0)).cuda()
     # decompression of the eight workers' messages of configuration 5
@@ -211,11 +214,13 @@ def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None, only=
         log(json.dumps(rec))
         rows.append(rec)
 
-    for ws in ((None, dws) if full_table else (dws,)):
-        time_decompress("5: decompress_accumulate, W = 8", mi, mv, k, ws)
-    if full_table and only is None:
+    if want(D5):
+        for ws in ((None, dws) if full_table else (dws,)):
+            time_decompress(D5, mi, mv, k, ws)
+    if extra:
         # the update step of Alg. 1 straight from the same messages (eta = 0.1)
-        time_decompress("5: decompress_update, W = 8", mi, mv, k, dws, alpha=-0.1 / N_WORKERS)
+        if want(U5):
+            time_decompress(U5, mi, mv, k, dws, alpha=-0.1 / N_WORKERS)
         # messages of CF 1000 (flat calls on the eight workers' gradients): few pairs per stretch of dense_out
         comp = binding.Compressor(n, [1000.0], 0)
         k = comp.k_total
@@ -227,8 +232,11 @@ def time_all_configs(torch, binding, workloads, full_table, vgg_grad=None, only=
             i, v, _ = comp(gw, r)
             mi[w * k:(w + 1) * k] = i
             mv[w * k:(w + 1) * k] = v
-        time_decompress("2: decompress_accumulate, W = 8, flat CF 1000 messages", mi, mv, k, dws)
-        time_decompress("2: decompress_update, W = 8, flat CF 1000 messages", mi, mv, k, dws, alpha=-0.1 / N_WORKERS)
+        if want(D2):
+            time_decompress(D2, mi, mv, k, None)
+            time_decompress(D2, mi, mv, k, dws)
+        if want(U2):
+            time_decompress(U2, mi, mv, k, dws, alpha=-0.1 / N_WORKERS)
     if not full_table or only is not None:
         return rows
     # direct compression at each CF against the second-level Top-k on a level-1 message (the comparison of the
